@@ -1,0 +1,223 @@
+"""ctypes front end of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this module.  It loads (and, if needed, compiles with gcc) oracle/sentry_oracle.c
+and marshals numpy arrays; it contains no arithmetic of its own.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sentry_oracle.c")
+_LIB = os.path.join(_HERE, "libsentry_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over independent rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(
+            os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "sentry_oracle.h"))):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+class _Layer(C.Structure):
+    _fields_ = ([("nH", C.c_int32), ("nG", C.c_int32), ("dh", C.c_int32), ("d", C.c_int32),
+                 ("F", C.c_int32)]
+                + [(n, C.c_void_p) for n in ("Wq", "bq", "Wk", "bk", "Wv", "bv", "Wo", "bo",
+                                             "W1", "b1", "W2", "b2",
+                                             "ln1_g", "ln1_b", "ln2_g", "ln2_b",
+                                             "head_group", "head_mask", "ffn_mask")])
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.orc_num_active.restype = C.c_int32
+        _lib.orc_round_bf16.restype = C.c_double
+        _lib.orc_round_bf16.argtypes = [C.c_double]
+        _lib.orc_max_threads.restype = C.c_int32
+        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward"):
+            getattr(_lib, f).restype = C.c_int32
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f64(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def max_threads() -> int:
+    return int(lib().orc_max_threads())
+
+
+def num_active(T: int, c: int) -> int:
+    return int(lib().orc_num_active(C.c_int32(T), C.c_int32(c)))
+
+
+def round_bf16(a) -> np.ndarray:
+    a = np.asarray(a, dtype=np.float64)
+    out = np.empty_like(a)
+    f = lib().orc_round_bf16
+    flat_in, flat_out = a.reshape(-1), out.reshape(-1)
+    for i in range(flat_in.size):
+        flat_out[i] = f(float(flat_in[i]))
+    return out
+
+
+def gate_scores_to_masks(g_head, g_ffn, k_head, k_ffn, Hk: int) -> Dict[str, np.ndarray]:
+    g_head = np.ascontiguousarray(g_head, dtype=np.float32)
+    g_ffn = np.ascontiguousarray(g_ffn, dtype=np.float32)
+    nl, P, Hq = g_head.shape
+    F = g_ffn.shape[2]
+    k_head = np.ascontiguousarray(k_head, dtype=np.int32)
+    k_ffn = np.ascontiguousarray(k_ffn, dtype=np.int32)
+    out = {
+        "head_mask": np.zeros((nl, P, Hq), np.uint8), "ffn_mask": np.zeros((nl, P, F), np.uint8),
+        "head_idx": np.zeros((nl, P, Hq), np.int32), "ffn_idx": np.zeros((nl, P, F), np.int32),
+        "group_idx": np.zeros((nl, P, Hk), np.int32), "n_groups": np.zeros((nl, P), np.int32),
+        "head_group": np.zeros((nl, P, Hq), np.int32),
+    }
+    rc = lib().orc_gate_scores_to_masks(
+        C.c_int32(nl), C.c_int32(P), C.c_int32(Hq), C.c_int32(Hk), C.c_int32(F),
+        _p(g_head), _p(g_ffn), _p(k_head), _p(k_ffn),
+        _p(out["head_mask"]), _p(out["ffn_mask"]), _p(out["head_idx"]), _p(out["ffn_idx"]),
+        _p(out["group_idx"]), _p(out["n_groups"]), _p(out["head_group"]))
+    if rc != 0:
+        raise ValueError("orc_gate_scores_to_masks: bad arguments")
+    return out
+
+
+def gather_rows(src, idx, block: int = 1) -> np.ndarray:
+    src = _f64(src)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    row_len = int(np.prod(src.shape[1:])) if src.ndim > 1 else 1
+    dst = np.zeros((idx.size * block,) + src.shape[1:], np.float64)
+    lib().orc_gather_rows(_p(src), _p(idx), C.c_int32(idx.size), C.c_int32(block),
+                          C.c_int64(row_len), _p(dst))
+    return dst
+
+
+def layernorm(x, gamma, beta, eps: float = 1e-5, bf16: bool = False) -> np.ndarray:
+    x = _f64(x)
+    d = x.shape[-1]
+    y = np.empty_like(x)
+    g, b = _f64(gamma), _f64(beta)
+    lib().orc_layernorm(_p(x), C.c_int64(x.size // d), C.c_int32(d), _p(g), _p(b),
+                        C.c_double(eps), C.c_int32(int(bf16)), _p(y))
+    return y
+
+
+def sparse_gqa(Q, K, V, head_group, U: int, key_valid=None, forced_sel=None, bf16: bool = False,
+               head_group_b=None, want_score: bool = True):
+    """Returns (O [B,L,nH*dh], score [B,nH,L], sel [B,nH,U], prob_check [2])."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    B, nH, L, dh = Q.shape
+    nG = K.shape[1]
+    assert K.shape == (B, nG, L, dh) and V.shape == K.shape
+    hg = np.ascontiguousarray(head_group, dtype=np.int32)
+    hgb = None if head_group_b is None else np.ascontiguousarray(head_group_b, dtype=np.int32)
+    kv = None if key_valid is None else np.ascontiguousarray(key_valid, dtype=np.uint8)
+    fs = None if forced_sel is None else np.ascontiguousarray(forced_sel, dtype=np.int32)
+    O = np.zeros((B, L, nH * dh), np.float64)
+    score = np.zeros((B, nH, L), np.float64) if want_score else None
+    sel = np.full((B, nH, max(U, 1)), -1, np.int32)
+    chk = np.zeros(2, np.float64)
+    rc = lib().orc_sparse_gqa(C.c_int32(B), C.c_int32(nH), C.c_int32(nG), C.c_int32(L),
+                              C.c_int32(dh), _p(Q), _p(K), _p(V), _p(hg), _p(hgb), _p(kv),
+                              C.c_int32(U), _p(fs), C.c_int32(int(bf16)), _p(O), _p(score),
+                              _p(sel), _p(chk))
+    if rc != 0:
+        raise ValueError("orc_sparse_gqa: bad arguments")
+    return O, score, sel[:, :, :U], chk
+
+
+class LayerPack:
+    """Keeps the float64 copies alive for as long as the C struct is used."""
+
+    def __init__(self, w: Dict[str, np.ndarray], nH: int, nG: int, dh: int, head_group,
+                 head_mask=None, ffn_mask=None):
+        self.keep = {}
+        s = _Layer()
+        d = int(np.asarray(w["Wq"]).shape[1])
+        F = int(np.asarray(w["W1"]).shape[0])
+        s.nH, s.nG, s.dh, s.d, s.F = nH, nG, dh, d, F
+        assert np.asarray(w["Wq"]).shape == (nH * dh, d), (np.asarray(w["Wq"]).shape, nH, dh, d)
+        assert np.asarray(w["Wk"]).shape == (nG * dh, d)
+        assert np.asarray(w["Wo"]).shape == (nH * dh, d)
+        assert np.asarray(w["W2"]).shape == (F, d)
+        for n in ("Wq", "bq", "Wk", "bk", "Wv", "bv", "Wo", "bo", "W1", "b1", "W2", "b2",
+                  "ln1_g", "ln1_b", "ln2_g", "ln2_b"):
+            a = _f64(w.get(n))
+            self.keep[n] = a
+            setattr(s, n, None if a is None else a.ctypes.data)
+        hg = np.ascontiguousarray(head_group, dtype=np.int32)
+        assert hg.shape == (nH,)
+        hm = None if head_mask is None else np.ascontiguousarray(head_mask, dtype=np.uint8)
+        fm = None if ffn_mask is None else np.ascontiguousarray(ffn_mask, dtype=np.uint8)
+        self.keep.update(hg=hg, hm=hm, fm=fm)
+        s.head_group = hg.ctypes.data
+        s.head_mask = None if hm is None else hm.ctypes.data
+        s.ffn_mask = None if fm is None else fm.ctypes.data
+        self.struct = s
+
+
+def pruned_ffn(pack: LayerPack, x, act: int = 0, eps: float = 1e-5, pre_ln: bool = True,
+               add_residual: bool = True, bf16: bool = False) -> np.ndarray:
+    x = _f64(x)
+    d = x.shape[-1]
+    y = np.empty_like(x)
+    lib().orc_pruned_ffn(C.byref(pack.struct), _p(x), C.c_int64(x.size // d), C.c_int32(act),
+                         C.c_double(eps), C.c_int32(int(pre_ln)), C.c_int32(int(add_residual)),
+                         C.c_int32(int(bf16)), _p(y))
+    return y
+
+
+def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,
+                    key_valid=None, act: int = 0, eps: float = 1e-5, forced_sel=None,
+                    final_ln: Optional[Dict[str, np.ndarray]] = None, bf16: bool = False,
+                    want_sel: bool = True, want_score: bool = False):
+    """packs[l][p] = LayerPack of layer l, pattern p.
+    Returns (y [B,L,d], sel [nl,B,nHmax,U] or None, score [nl,B,nHmax,L] or None)."""
+    x = _f64(x)
+    B, L, d = x.shape
+    nl, P = len(packs), len(packs[0])
+    arr = (_Layer * (nl * P))()
+    nHmax = 0
+    for l in range(nl):
+        for p in range(P):
+            arr[l * P + p] = packs[l][p].struct
+            nHmax = max(nHmax, packs[l][p].struct.nH)
+    pid = None if pattern_id is None else np.ascontiguousarray(pattern_id, dtype=np.int32)
+    kv = None if key_valid is None else np.ascontiguousarray(key_valid, dtype=np.uint8)
+    fs = None
+    if forced_sel is not None:
+        fs = np.ascontiguousarray(forced_sel, dtype=np.int32)
+        assert fs.shape == (nl, B, nHmax, U), (fs.shape, (nl, B, nHmax, U))
+    fg = None if final_ln is None else _f64(final_ln["g"])
+    fb = None if final_ln is None else _f64(final_ln["b"])
+    y = np.empty_like(x)
+    sel = np.full((nl, B, nHmax, max(U, 1)), -1, np.int32) if want_sel else None
+    score = np.full((nl, B, nHmax, L), -np.inf, np.float64) if want_score else None
+    rc = lib().orc_encoder_forward(
+        C.c_int32(B), C.c_int32(L), C.c_int32(nl), C.c_int32(P), arr, _p(pid), _p(kv),
+        C.c_int32(U), C.c_int32(act), C.c_double(eps), _p(fs), C.c_int32(nHmax), _p(fg), _p(fb),
+        C.c_int32(int(bf16)), _p(x), _p(y), _p(sel), _p(score))
+    if rc != 0:
+        raise ValueError("orc_encoder_forward: bad arguments")
+    if sel is not None:
+        sel = sel[..., :U]
+    return y, sel, score

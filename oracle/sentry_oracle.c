@@ -1,0 +1,471 @@
+/*
+ * CPU oracle (TEST INFRASTRUCTURE ONLY) -- see sentry_oracle.h.
+ *
+ * Plain C, fp64 everywhere, single accumulator per output in index order,
+ * no blocking and no fusion: each function is the definition written out.
+ * OpenMP only splits independent output rows between threads.
+ */
+#include "sentry_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int32_t orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- Sec. 4.4: U = c * ceil(ln T) -------------------------------------- */
+int32_t orc_num_active(int32_t T, int32_t c)
+{
+    if (T <= 0 || c <= 0) return 0;
+    double u = (double)c * ceil(log((double)T));
+    if (u > (double)T) return T;
+    return (int32_t)u;
+}
+
+/* ---- bf16: 8 significant bits, exponent range of binary32 -------------- */
+double orc_round_bf16(double x)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(x, &e);               /* |x| = m * 2^e, m in [0.5, 1) */
+    int q = e - 8;                    /* spacing of bf16 values near x is 2^q */
+    if (q < -133) q = -133;           /* subnormal range: fixed spacing 2^-133 */
+    double r = ldexp(nearbyint(ldexp(x, -q)), q);   /* nearbyint: ties to even */
+    if (fabs(r) >= ldexp(1.0, 128)) r = (x > 0) ? INFINITY : -INFINITY;
+    return r;
+}
+
+static inline double rnd(double x, int32_t bf16) { return bf16 ? orc_round_bf16(x) : x; }
+
+/* ---- Sec. 4.5: gate scores -> keep sets -------------------------------- */
+typedef struct { float g; int32_t i; } scored;
+
+static int by_score_desc_index_asc(const void *a, const void *b)
+{
+    const scored *x = (const scored *)a, *y = (const scored *)b;
+    if (x->g > y->g) return -1;
+    if (x->g < y->g) return 1;
+    return (x->i > y->i) - (x->i < y->i);
+}
+
+/* mark the k best of n scores; write mask[n] and ascending idx (padded -1) */
+static void keep_top_k(const float *g, int32_t n, int32_t k, uint8_t *mask, int32_t *idx)
+{
+    scored *s = (scored *)malloc(sizeof(scored) * (size_t)n);
+    for (int32_t i = 0; i < n; ++i) { s[i].g = g[i]; s[i].i = i; }
+    qsort(s, (size_t)n, sizeof(scored), by_score_desc_index_asc);
+    memset(mask, 0, (size_t)n);
+    for (int32_t r = 0; r < k; ++r) mask[s[r].i] = 1;
+    int32_t w = 0;
+    for (int32_t i = 0; i < n; ++i) if (mask[i]) idx[w++] = i;
+    for (; w < n; ++w) idx[w] = -1;
+    free(s);
+}
+
+int32_t orc_gate_scores_to_masks(int32_t nl, int32_t P, int32_t Hq, int32_t Hk, int32_t F,
+                                 const float *g_head, const float *g_ffn,
+                                 const int32_t *k_head, const int32_t *k_ffn,
+                                 uint8_t *head_mask, uint8_t *ffn_mask,
+                                 int32_t *head_idx, int32_t *ffn_idx,
+                                 int32_t *group_idx, int32_t *n_groups, int32_t *head_group)
+{
+    if (nl < 1 || P < 1 || Hq < 1 || Hk < 1 || F < 1 || Hq % Hk != 0) return -1;
+    const int32_t per_group = Hq / Hk;      /* heads sharing one K/V projection */
+    for (int32_t l = 0; l < nl; ++l) {
+        if (k_head[l] < 1 || k_head[l] > Hq || k_ffn[l] < 1 || k_ffn[l] > F) return -1;
+        for (int32_t p = 0; p < P; ++p) {
+            const int64_t lp = (int64_t)l * P + p;
+            uint8_t *hm = head_mask + lp * Hq;
+            int32_t *hi = head_idx + lp * Hq;
+            keep_top_k(g_head + lp * Hq, Hq, k_head[l], hm, hi);
+            keep_top_k(g_ffn + lp * F, F, k_ffn[l], ffn_mask + lp * F, ffn_idx + lp * F);
+
+            /* K_keep = floor(H_keep / (Hq/Hk)); an unreferenced group is removed */
+            int32_t *gi = group_idx + lp * Hk;
+            int32_t ng = 0;
+            for (int32_t g = 0; g < Hk; ++g) {
+                int referenced = 0;
+                for (int32_t h = 0; h < Hq; ++h)
+                    if (hm[h] && h / per_group == g) referenced = 1;
+                if (referenced) gi[ng++] = g;
+            }
+            n_groups[lp] = ng;
+            for (int32_t g = ng; g < Hk; ++g) gi[g] = -1;
+
+            int32_t *hg = head_group + lp * Hq;
+            for (int32_t i = 0; i < Hq; ++i) {
+                hg[i] = -1;
+                if (hi[i] < 0) continue;
+                for (int32_t r = 0; r < ng; ++r)
+                    if (gi[r] == hi[i] / per_group) hg[i] = r;
+            }
+        }
+    }
+    return 0;
+}
+
+void orc_gather_rows(const double *src, const int32_t *idx, int32_t n_keep,
+                     int32_t block, int64_t row_len, double *dst)
+{
+    for (int32_t i = 0; i < n_keep; ++i)
+        for (int32_t r = 0; r < block; ++r)
+            memcpy(dst + ((int64_t)i * block + r) * row_len,
+                   src + ((int64_t)idx[i] * block + r) * row_len,
+                   sizeof(double) * (size_t)row_len);
+}
+
+/* ---- LayerNorm ---------------------------------------------------------- */
+void orc_layernorm(const double *x, int64_t rows, int32_t d, const double *gamma,
+                   const double *beta, double eps, int32_t bf16, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *xr = x + r * d;
+        double *yr = y + r * d;
+        double mean = 0.0;
+        for (int32_t k = 0; k < d; ++k) mean += xr[k];
+        mean /= d;
+        double var = 0.0;
+        for (int32_t k = 0; k < d; ++k) var += (xr[k] - mean) * (xr[k] - mean);
+        var /= d;                                    /* biased variance */
+        const double inv = 1.0 / sqrt(var + eps);
+        for (int32_t k = 0; k < d; ++k) {
+            double v = (xr[k] - mean) * inv;
+            if (gamma) v *= gamma[k];
+            if (beta) v += beta[k];
+            yr[k] = rnd(v, bf16);
+        }
+    }
+}
+
+/* y[r, n] = sum_k x[r, k] * W[n, k] + b[n]  for the listed output units.
+ * W is unit-major (one output unit per row).  out_stride = row length of y. */
+static void project_units(const double *x, int64_t rows, int32_t d, const double *W,
+                          const double *b, int32_t unit0, int32_t n_units, int32_t bf16,
+                          double *y, int64_t out_stride, int32_t out0)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *xr = x + r * d;
+        for (int32_t n = 0; n < n_units; ++n) {
+            const double *wn = W + (int64_t)(unit0 + n) * d;
+            double acc = 0.0;
+            for (int32_t k = 0; k < d; ++k) acc += xr[k] * wn[k];
+            if (b) acc += b[unit0 + n];
+            y[r * out_stride + out0 + n] = rnd(acc, bf16);
+        }
+    }
+}
+
+/* ---- SentryAttend for one (sample, head) -------------------------------- */
+typedef struct { float m; int32_t i; } qscore;
+
+static int by_m_desc_index_asc(const void *a, const void *b)
+{
+    const qscore *x = (const qscore *)a, *y = (const qscore *)b;
+    if (x->m > y->m) return -1;
+    if (x->m < y->m) return 1;
+    return (x->i > y->i) - (x->i < y->i);
+}
+
+static int int_asc(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * q [L,dh] one head's queries, k,v [L,dh] its group's keys/values,
+ * valid [L] or NULL.  Writes o rows at o[i*o_stride + 0..dh).
+ * score_out [L] or NULL, sel_out [U] or NULL, forced [U] or NULL.
+ */
+static void sgqa_one_head(int32_t L, int32_t dh, const double *q, const double *k,
+                          const double *v, const uint8_t *valid, int32_t U,
+                          const int32_t *forced, int32_t bf16, double *o, int64_t o_stride,
+                          double *score_out, int32_t *sel_out, double *prob_check)
+{
+    const double scale = 1.0 / sqrt((double)dh);
+    int32_t n_allowed = 0;
+    for (int32_t j = 0; j < L; ++j) if (!valid || valid[j]) ++n_allowed;
+
+    /* sparsity score of every query: max_j s_ij - mean_j s_ij over allowed keys */
+    double *M = (double *)malloc(sizeof(double) * (size_t)L);
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < L; ++i) {
+        if (valid && !valid[i]) { M[i] = -INFINITY; continue; }
+        double mx = -INFINITY, sum = 0.0;
+        for (int32_t j = 0; j < L; ++j) {
+            if (valid && !valid[j]) continue;
+            double s = 0.0;
+            for (int32_t e = 0; e < dh; ++e) s += q[(int64_t)i * dh + e] * k[(int64_t)j * dh + e];
+            s *= scale;
+            if (s > mx) mx = s;
+            sum += s;
+        }
+        M[i] = mx - sum / n_allowed;
+    }
+    if (score_out) memcpy(score_out, M, sizeof(double) * (size_t)L);
+
+    /* active set: the U queries with the highest score (ties: lower index) */
+    uint8_t *active = (uint8_t *)calloc((size_t)L, 1);
+    int32_t *chosen = (int32_t *)malloc(sizeof(int32_t) * (size_t)(U > 0 ? U : 1));
+    int32_t n_chosen = 0;
+    if (forced) {
+        for (int32_t r = 0; r < U; ++r)
+            if (forced[r] >= 0 && forced[r] < L && !active[forced[r]]) {
+                active[forced[r]] = 1;
+                chosen[n_chosen++] = forced[r];
+            }
+    } else {
+        qscore *qs = (qscore *)malloc(sizeof(qscore) * (size_t)L);
+        int32_t nq = 0;
+        for (int32_t i = 0; i < L; ++i)
+            if (!valid || valid[i]) { qs[nq].m = (float)M[i]; qs[nq].i = i; ++nq; }
+        qsort(qs, (size_t)nq, sizeof(qscore), by_m_desc_index_asc);
+        for (int32_t r = 0; r < nq && r < U; ++r) {
+            active[qs[r].i] = 1;
+            chosen[n_chosen++] = qs[r].i;
+        }
+        free(qs);
+    }
+    qsort(chosen, (size_t)n_chosen, sizeof(int32_t), int_asc);
+    if (sel_out) {
+        for (int32_t r = 0; r < U; ++r) sel_out[r] = r < n_chosen ? chosen[r] : -1;
+    }
+
+    /* context vector: mean of V_g over allowed keys */
+    double *ctx = (double *)calloc((size_t)dh, sizeof(double));
+    for (int32_t j = 0; j < L; ++j) {
+        if (valid && !valid[j]) continue;
+        for (int32_t e = 0; e < dh; ++e) ctx[e] += v[(int64_t)j * dh + e];
+    }
+    for (int32_t e = 0; e < dh; ++e) ctx[e] /= n_allowed;
+
+    double worst_sum = 0.0, worst_leak = 0.0;
+#pragma omp parallel for schedule(static) reduction(max : worst_sum, worst_leak)
+    for (int32_t i = 0; i < L; ++i) {
+        double *oi = o + (int64_t)i * o_stride;
+        if (!active[i]) {                       /* lazy row */
+            for (int32_t e = 0; e < dh; ++e) oi[e] = rnd(ctx[e], bf16);
+            continue;
+        }
+        /* active row, Eq. (6): softmax(q_i K_g^T / sqrt(d_k)) V_g */
+        double *p = (double *)malloc(sizeof(double) * (size_t)L);
+        double mx = -INFINITY;
+        for (int32_t j = 0; j < L; ++j) {
+            if (valid && !valid[j]) { p[j] = -INFINITY; continue; }
+            double s = 0.0;
+            for (int32_t e = 0; e < dh; ++e) s += q[(int64_t)i * dh + e] * k[(int64_t)j * dh + e];
+            p[j] = s * scale;
+            if (p[j] > mx) mx = p[j];
+        }
+        double den = 0.0;
+        for (int32_t j = 0; j < L; ++j) {
+            p[j] = (valid && !valid[j]) ? 0.0 : exp(p[j] - mx);
+            den += p[j];
+        }
+        double rowsum = 0.0, leak = 0.0;
+        for (int32_t j = 0; j < L; ++j) {
+            p[j] /= den;
+            rowsum += p[j];
+            if (valid && !valid[j] && p[j] > leak) leak = p[j];
+        }
+        if (fabs(rowsum - 1.0) > worst_sum) worst_sum = fabs(rowsum - 1.0);
+        if (leak > worst_leak) worst_leak = leak;
+        for (int32_t e = 0; e < dh; ++e) {
+            double acc = 0.0;
+            for (int32_t j = 0; j < L; ++j) acc += p[j] * v[(int64_t)j * dh + e];
+            oi[e] = rnd(acc, bf16);
+        }
+        free(p);
+    }
+    if (prob_check) {
+        if (worst_sum > prob_check[0]) prob_check[0] = worst_sum;
+        if (worst_leak > prob_check[1]) prob_check[1] = worst_leak;
+    }
+    free(ctx); free(chosen); free(active); free(M);
+}
+
+int32_t orc_sparse_gqa(int32_t B, int32_t nH, int32_t nG, int32_t L, int32_t dh,
+                       const double *Q, const double *K, const double *V,
+                       const int32_t *head_group, const int32_t *head_group_b,
+                       const uint8_t *key_valid, int32_t U, const int32_t *forced_sel,
+                       int32_t bf16, double *O, double *score, int32_t *sel,
+                       double *prob_check)
+{
+    if (B < 0 || nH < 1 || nG < 1 || L < 1 || dh < 1 || U < 0) return -1;
+    if (prob_check) { prob_check[0] = 0.0; prob_check[1] = 0.0; }
+    double *o_tmp = O ? NULL : (double *)malloc(sizeof(double) * (size_t)L * dh);
+    for (int32_t b = 0; b < B; ++b) {
+        const uint8_t *valid = key_valid ? key_valid + (int64_t)b * L : NULL;
+        if (valid) {
+            int32_t n = 0;
+            for (int32_t j = 0; j < L; ++j) n += valid[j] != 0;
+            if (n == 0) { free(o_tmp); return -1; }
+        }
+        for (int32_t h = 0; h < nH; ++h) {
+            const int32_t g = head_group_b ? head_group_b[(int64_t)b * nH + h] : head_group[h];
+            if (g < 0 || g >= nG) { free(o_tmp); return -1; }
+            const int64_t bh = (int64_t)b * nH + h;
+            sgqa_one_head(L, dh, Q + bh * L * dh, K + ((int64_t)b * nG + g) * L * dh,
+                          V + ((int64_t)b * nG + g) * L * dh, valid, U,
+                          forced_sel ? forced_sel + bh * U : NULL, bf16,
+                          O ? O + (int64_t)b * L * nH * dh + (int64_t)h * dh : o_tmp,
+                          O ? (int64_t)nH * dh : dh,
+                          score ? score + bh * L : NULL, sel ? sel + bh * U : NULL,
+                          prob_check);
+        }
+    }
+    free(o_tmp);
+    return 0;
+}
+
+/* ---- FFN ----------------------------------------------------------------- */
+static double activation(double z, int32_t act)
+{
+    if (act == 1) return 0.5 * z * (1.0 + erf(z / sqrt(2.0)));   /* erf-GELU */
+    return z > 0.0 ? z : 0.0;                                      /* ReLU */
+}
+
+void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t act,
+                    double eps, int32_t pre_ln, int32_t add_residual, int32_t bf16,
+                    double *y)
+{
+    const int32_t d = w->d, F = w->F;
+    double *xn = (double *)malloc(sizeof(double) * (size_t)rows * d);
+    double *hid = (double *)malloc(sizeof(double) * (size_t)rows * F);
+    if (pre_ln) orc_layernorm(x, rows, d, w->ln2_g, w->ln2_b, eps, bf16, xn);
+    else memcpy(xn, x, sizeof(double) * (size_t)rows * d);
+
+    /* hidden = act(xn W1^T + b1), removed channels are exactly zero */
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int32_t f = 0; f < F; ++f) {
+            if (w->ffn_mask && !w->ffn_mask[f]) { hid[r * F + f] = 0.0; continue; }
+            double acc = 0.0;
+            for (int32_t k = 0; k < d; ++k) acc += xn[r * d + k] * w->W1[(int64_t)f * d + k];
+            if (w->b1) acc += w->b1[f];
+            hid[r * F + f] = rnd(activation(acc, act), bf16);
+        }
+    }
+    /* y = x + hidden W2 + b2 */
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int32_t n = 0; n < d; ++n) {
+            double acc = 0.0;
+            for (int32_t f = 0; f < F; ++f) {
+                if (w->ffn_mask && !w->ffn_mask[f]) continue;
+                acc += hid[r * F + f] * w->W2[(int64_t)f * d + n];
+            }
+            if (w->b2) acc += w->b2[n];
+            if (add_residual) acc += x[r * d + n];
+            y[r * d + n] = rnd(acc, bf16);
+        }
+    }
+    free(hid); free(xn);
+}
+
+/* ---- encoder stack ------------------------------------------------------- */
+int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
+                            const orc_layer *layers, const int32_t *pattern_id,
+                            const uint8_t *key_valid, int32_t U, int32_t act, double eps,
+                            const int32_t *forced_sel, int32_t nHmax,
+                            const double *final_g, const double *final_b, int32_t bf16,
+                            const double *x, double *y, int32_t *sel_out, double *score_out)
+{
+    if (B < 0 || L < 1 || nl < 1 || P < 1 || U < 0) return -1;
+    const int32_t d = layers[0].d;
+    const int64_t Ld = (int64_t)L * d;
+    double *cur = (double *)malloc(sizeof(double) * (size_t)Ld);
+    double *xn = (double *)malloc(sizeof(double) * (size_t)Ld);
+    int32_t rc = 0;
+
+    for (int32_t b = 0; b < B && rc == 0; ++b) {
+        const uint8_t *valid = key_valid ? key_valid + (int64_t)b * L : NULL;
+        if (valid) {
+            int32_t n = 0;
+            for (int32_t j = 0; j < L; ++j) n += valid[j] != 0;
+            if (n == 0) { rc = -1; break; }
+        }
+        const int32_t p = pattern_id ? pattern_id[b] : 0;
+        if (p < 0 || p >= P) { rc = -1; break; }
+        memcpy(cur, x + b * Ld, sizeof(double) * (size_t)Ld);
+
+        for (int32_t l = 0; l < nl; ++l) {
+            const orc_layer *w = &layers[(int64_t)l * P + p];
+            const int32_t nH = w->nH, nG = w->nG, dh = w->dh;
+            if (w->d != d || nH > nHmax) { rc = -1; break; }
+            double *Q = (double *)calloc((size_t)nH * L * dh, sizeof(double));
+            double *Kg = (double *)calloc((size_t)nG * L * dh, sizeof(double));
+            double *Vg = (double *)calloc((size_t)nG * L * dh, sizeof(double));
+            double *O = (double *)calloc((size_t)L * nH * dh, sizeof(double));
+
+            orc_layernorm(cur, L, d, w->ln1_g, w->ln1_b, eps, bf16, xn);
+
+            /* per-head Q, per-group K/V (only for units that survive) */
+            for (int32_t h = 0; h < nH; ++h) {
+                if (w->head_mask && !w->head_mask[h]) continue;
+                project_units(xn, L, d, w->Wq, w->bq, h * dh, dh, bf16, Q + (int64_t)h * L * dh, dh, 0);
+            }
+            for (int32_t g = 0; g < nG; ++g) {
+                int used = 0;
+                for (int32_t h = 0; h < nH; ++h)
+                    if ((!w->head_mask || w->head_mask[h]) && w->head_group[h] == g) used = 1;
+                if (!used) continue;
+                project_units(xn, L, d, w->Wk, w->bk, g * dh, dh, bf16, Kg + (int64_t)g * L * dh, dh, 0);
+                project_units(xn, L, d, w->Wv, w->bv, g * dh, dh, bf16, Vg + (int64_t)g * L * dh, dh, 0);
+            }
+
+            /* SentryAttend per surviving head; a removed head's output is 0 */
+            for (int32_t h = 0; h < nH; ++h) {
+                if (w->head_mask && !w->head_mask[h]) continue;
+                const int32_t g = w->head_group[h];
+                const int64_t slot = (((int64_t)l * B + b) * nHmax + h);
+                sgqa_one_head(L, dh, Q + (int64_t)h * L * dh, Kg + (int64_t)g * L * dh,
+                              Vg + (int64_t)g * L * dh, valid, U,
+                              forced_sel ? forced_sel + slot * U : NULL, bf16,
+                              O + (int64_t)h * dh, (int64_t)nH * dh,
+                              score_out ? score_out + slot * L : NULL,
+                              sel_out ? sel_out + slot * U : NULL, NULL);
+            }
+
+            /* x <- x + O Wo + bo  (rows of Wo belonging to removed heads never enter) */
+#pragma omp parallel for schedule(static)
+            for (int32_t i = 0; i < L; ++i) {
+                for (int32_t n = 0; n < d; ++n) {
+                    double acc = 0.0;
+                    for (int32_t h = 0; h < nH; ++h) {
+                        if (w->head_mask && !w->head_mask[h]) continue;
+                        for (int32_t e = 0; e < dh; ++e)
+                            acc += O[(int64_t)i * nH * dh + h * dh + e] *
+                                   w->Wo[((int64_t)h * dh + e) * d + n];
+                    }
+                    if (w->bo) acc += w->bo[n];
+                    xn[(int64_t)i * d + n] = rnd(cur[(int64_t)i * d + n] + acc, bf16);
+                }
+            }
+            memcpy(cur, xn, sizeof(double) * (size_t)Ld);
+
+            /* x <- x + FFN(LN2(x)) */
+            orc_pruned_ffn(w, cur, L, act, eps, 1, 1, bf16, xn);
+            memcpy(cur, xn, sizeof(double) * (size_t)Ld);
+
+            free(O); free(Vg); free(Kg); free(Q);
+        }
+        if (rc) break;
+        if (final_g || final_b) orc_layernorm(cur, L, d, final_g, final_b, eps, bf16, y + b * Ld);
+        else memcpy(y + b * Ld, cur, sizeof(double) * (size_t)Ld);
+    }
+    free(xn); free(cur);
+    return rc;
+}

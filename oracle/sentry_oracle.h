@@ -1,0 +1,150 @@
+/*
+ * CPU oracle for the pruned multimodal encoder forward of SentryFuse
+ * (SentryGate keep-masks + SentryAttend sparse grouped-query attention +
+ * pruned FFN).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, fp64 implementation that
+ * exists only so that tests, the smoke check and the benchmark's CPU-baseline
+ * leg have something independent to compare the GPU library with.  It shares
+ * no code, header, table or helper with the GPU library and must never be
+ * called from the product path.
+ *
+ * Every function below takes HOST pointers.  All floating-point tensors are
+ * double; "bf16 mode" (bf16 != 0) means: inputs already hold bf16-representable
+ * values and every *stored* intermediate tensor is rounded to the nearest bf16
+ * value (ties to even) at the points listed at orc_encoder_forward.
+ *
+ * Readings of the paper that the paper itself does not pin ("parity
+ * unpinned"): the query sparsity score is max-minus-mean of the scaled dot
+ * products (Sec. 4.4 only cites the measure), the lazy-row context vector is
+ * the arithmetic mean of V_g (Sec. 4.4 says "aggregated"), the FFN activation
+ * is ReLU or erf-GELU, and the layer is pre-norm.  The pins in tests/ only
+ * check those readings for self-consistency; everything else is pinned.
+ */
+#ifndef SENTRY_ORACLE_H
+#define SENTRY_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Number of active queries per head, Sec. 4.4: U = c * ceil(ln T), clipped to
+ * T.  The worked example (n=8, T=128, c=5 -> U ~ 25) fixes the natural log. */
+int32_t orc_num_active(int32_t T, int32_t c);
+
+/* Round a double to the nearest bf16-representable value, ties to even. */
+double orc_round_bf16(double x);
+
+/*
+ * Sec. 4.5 "Head pruning with GQA consistency" / "FFN pruning", with integer
+ * keep counts per layer: for each (layer l, presence pattern p) keep the
+ * k_head[l] heads and k_ffn[l] channels with the highest gate score (ties: the
+ * lower index wins).  K/V groups kept = { floor(h / (Hq/Hk)) : h kept }.
+ *
+ *   g_head [nl,P,Hq], g_ffn [nl,P,F]         gate scores
+ *   head_mask [nl,P,Hq], ffn_mask [nl,P,F]   1 = kept
+ *   head_idx [nl,P,Hq] (first k_head[l] valid, ascending, rest -1)
+ *   ffn_idx  [nl,P,F]  (first k_ffn[l] valid, ascending, rest -1)
+ *   group_idx [nl,P,Hk] kept groups ascending, rest -1;  n_groups [nl,P]
+ *   head_group [nl,P,Hq]: for kept head i (i-th entry of head_idx) the rank of
+ *                         its group inside group_idx; rest -1
+ * returns 0, or -1 on bad arguments.
+ */
+int32_t orc_gate_scores_to_masks(int32_t nl, int32_t P, int32_t Hq, int32_t Hk, int32_t F,
+                                 const float *g_head, const float *g_ffn,
+                                 const int32_t *k_head, const int32_t *k_ffn,
+                                 uint8_t *head_mask, uint8_t *ffn_mask,
+                                 int32_t *head_idx, int32_t *ffn_idx,
+                                 int32_t *group_idx, int32_t *n_groups, int32_t *head_group);
+
+/* Row gather: dst[i, :] = src[idx[i], :] for i < n_keep (Sec. 4.5:
+ * W1' = W1[:, N_keep], W2' = W2[N_keep, :], and the head blocks of W_Q).
+ * rows are `row_len` doubles; `block` consecutive rows move per index. */
+void orc_gather_rows(const double *src, const int32_t *idx, int32_t n_keep,
+                     int32_t block, int64_t row_len, double *dst);
+
+/* One encoder layer's parameters as the oracle sees them.  Unit-major: every
+ * head dimension / FFN channel is one contiguous row of length d.
+ *   Wq [nH*dh, d]  (column blocks of the paper's W_Q in R^{d x Hq*dh})
+ *   Wk, Wv [nG*dh, d]
+ *   Wo [nH*dh, d]  (row blocks of the output projection)
+ *   W1 [F, d]      (columns of the paper's W_1 in R^{d x F})
+ *   W2 [F, d]      (rows of the paper's W_2 in R^{F x d})
+ * biases may be NULL.  head_group[h] = K/V group (0..nG-1) used by head h.
+ * head_mask[h] / ffn_mask[f] = 0 removes the unit (NULL = keep all). */
+typedef struct {
+    int32_t nH, nG, dh, d, F;
+    const double *Wq, *bq, *Wk, *bk, *Wv, *bv, *Wo, *bo;
+    const double *W1, *b1, *W2, *b2;
+    const double *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+    const int32_t *head_group;
+    const uint8_t *head_mask;
+    const uint8_t *ffn_mask;
+} orc_layer;
+
+/* LayerNorm over the last dimension (biased variance). y may alias x. */
+void orc_layernorm(const double *x, int64_t rows, int32_t d, const double *gamma,
+                   const double *beta, double eps, int32_t bf16, double *y);
+
+/*
+ * SentryAttend, Sec. 4.4 Eq. (6), for B samples.
+ *   Q [B,nH,L,dh], K,V [B,nG,L,dh], head_group [nH] (shared by all samples)
+ *   head_group_b: if not NULL, [B,nH] per-sample head->group map (overrides)
+ *   key_valid [B,L] or NULL (all keys allowed)
+ *   U         number of active queries per head (U >= L: every row active)
+ *   forced_sel [B,nH,U] or NULL: use these query indices (entries < 0 skipped)
+ *              instead of the oracle's own top-U choice
+ * outputs (any may be NULL):
+ *   O     [B,L,nH*dh]  heads concatenated in index order
+ *   score [B,nH,L]     sparsity score M_i (-inf for disallowed queries)
+ *   sel   [B,nH,U]     chosen queries ascending, padded with -1
+ *   prob_check [2]     max |rowsum-1| over active rows, max prob on a
+ *                      disallowed key (softmax invariants)
+ * returns 0, or -1 on bad arguments (a sample with no allowed key).
+ */
+int32_t orc_sparse_gqa(int32_t B, int32_t nH, int32_t nG, int32_t L, int32_t dh,
+                       const double *Q, const double *K, const double *V,
+                       const int32_t *head_group, const int32_t *head_group_b,
+                       const uint8_t *key_valid, int32_t U, const int32_t *forced_sel,
+                       int32_t bf16, double *O, double *score, int32_t *sel,
+                       double *prob_check);
+
+/* Pruned FFN with residual, Sec. 4.5: y = x + act(LN2(x) W1'^T + b1') W2' + b2
+ * for `rows` tokens of one pattern.  act: 0 ReLU, 1 erf-GELU.
+ * add_residual = 0 drops the "x +".  pre_ln = 0 skips the LayerNorm. */
+void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t act,
+                    double eps, int32_t pre_ln, int32_t add_residual, int32_t bf16,
+                    double *y);
+
+/*
+ * The whole pruned encoder forward: for l = 0..nl-1
+ *     x <- x + Wo-proj( SentryAttend( QKV-proj( LN1(x) ) ) )
+ *     x <- x + FFN( LN2(x) )
+ * and an optional final LayerNorm.
+ *   x [B,L,d] in, y [B,L,d] out
+ *   layers [nl*P]      layer l of pattern p at layers[l*P + p]
+ *   pattern_id [B]     (NULL = all 0)
+ *   key_valid [B,L] or NULL
+ *   forced_sel [nl,B,nHmax,U] or NULL (nHmax = max nH over all layers)
+ *   sel_out    [nl,B,nHmax,U] or NULL, score_out [nl,B,nHmax,L] or NULL
+ *   final_g/final_b [d] or NULL (no final LN)
+ * bf16 rounding points (bf16 != 0): LN outputs, Q, K, V, the attention output
+ * O, the FFN hidden after the activation, and x after each residual add.
+ * returns 0 or -1.
+ */
+int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
+                            const orc_layer *layers, const int32_t *pattern_id,
+                            const uint8_t *key_valid, int32_t U, int32_t act, double eps,
+                            const int32_t *forced_sel, int32_t nHmax,
+                            const double *final_g, const double *final_b, int32_t bf16,
+                            const double *x, double *y, int32_t *sel_out, double *score_out);
+
+/* Threads the OpenMP runtime will use (for the benchmark's report). */
+int32_t orc_max_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
