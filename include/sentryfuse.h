@@ -1,0 +1,238 @@
+/*
+ * sentryfuse.h -- C ABI of the MI355X (gfx950) library for the pruned
+ * multimodal encoder forward of SentryFuse: SentryGate keep-masks (Sec. 4.2,
+ * Sec. 4.5 of the paper), their compaction into dense weight slices
+ * (Sec. 4.5), SentryAttend sparse grouped-query attention (Sec. 4.4, Eq. (6)),
+ * the pruned FFN (Sec. 4.5) and the pre-norm encoder stack around them.
+ *
+ * Conventions shared by every entry point
+ *  - Every pointer is a DEVICE pointer unless its name ends in `_host`.
+ *  - Every buffer is allocated and freed by the caller.  The library keeps no
+ *    pointer after a call returns and allocates no device memory; scratch
+ *    comes from the (workspace, workspace_bytes) pair, sized by the matching
+ *    sf_*_workspace_bytes query.  Workspace must be 256-byte aligned.
+ *  - `stream` is a hipStream_t.  Calls only enqueue work; outputs are valid
+ *    once the caller has synchronised the stream.  Two calls that share a
+ *    workspace must be ordered on one stream.
+ *  - Return value: SF_OK or a negative sf_status.  On any error other than
+ *    SF_ERR_HIP nothing has been enqueued and no output was touched.
+ *    sf_last_error() returns a thread-local message for the last failure.
+ *  - Results are deterministic: no floating-point atomics; the same inputs
+ *    give the same bits.
+ *  - dtype SF_F32: all floating tensors are fp32, fp32 arithmetic.
+ *    dtype SF_BF16: all floating tensors (activations, weights, biases,
+ *    LayerNorm parameters) are bf16; contractions run on bf16 MFMA with fp32
+ *    accumulation; stored tensors are rounded to bf16 (nearest even) at: the
+ *    LayerNorm output, Q, K, V, the attention output, the FFN hidden after
+ *    the activation, and the residual stream after each add.
+ *  - Gate scores, sparsity scores and all index tensors are fp32 / int32 /
+ *    uint8 regardless of dtype.
+ */
+#ifndef SENTRYFUSE_H
+#define SENTRYFUSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sf_status {
+    SF_OK = 0,
+    SF_ERR_INVALID_ARG = -1,   /* NULL where data is required, counts out of range */
+    SF_ERR_SHAPE = -2,         /* sizes the kernels cannot take (see each call) */
+    SF_ERR_UNSUPPORTED = -3,   /* dtype / flag combination not built */
+    SF_ERR_WORKSPACE = -4,     /* workspace missing, misaligned or too small */
+    SF_ERR_HIP = -5            /* a HIP launch failed; see sf_last_error() */
+} sf_status;
+
+enum { SF_F32 = 0, SF_BF16 = 1 };
+enum { SF_RELU = 0, SF_GELU_ERF = 1 };
+enum { SF_FLAG_FINAL_LN = 1u };
+
+/* Problem descriptor (plain data).  Set struct_size = sizeof(sf_desc). */
+typedef struct sf_desc {
+    uint32_t struct_size;
+    int32_t B;          /* samples */
+    int32_t L;          /* tokens per sample (all modalities concatenated), the paper's T */
+    int32_t d_model;    /* multiple of 8 (bf16) */
+    int32_t Hq;         /* query heads of the dense model */
+    int32_t Hk;         /* K/V groups of the dense model, Hq % Hk == 0 */
+    int32_t dh;         /* head dim; bf16: 32, 64 or 128 */
+    int32_t d_ff;       /* FFN hidden width of the dense model */
+    int32_t n_layers;
+    int32_t P;          /* number of modality-presence patterns in use */
+    int32_t dtype;      /* SF_F32 | SF_BF16 */
+    int32_t act;        /* SF_RELU | SF_GELU_ERF */
+    int32_t c_factor;   /* c of U = c*ceil(ln L) (Sec. 4.4); 5 if <= 0 */
+    int32_t U_override; /* < 0: use c_factor; >= 0: this many active queries (clipped to L) */
+    uint32_t flags;     /* SF_FLAG_* */
+    float ln_eps;       /* 1e-5 if <= 0 */
+    int32_t ffn_pad;    /* kept FFN width is padded with zero channels to a multiple of
+                           this; must be a multiple of 64; 64 if <= 0 */
+} sf_desc;
+
+const char *sf_last_error(void);
+
+/* U = min(L, c*ceil(ln L)) of Sec. 4.4 (natural log: the worked example
+ * T=128, c=5 gives 25), or the override.  Negative status on a bad desc. */
+int32_t sf_num_active(const sf_desc *desc);
+
+/* round_up(k_ffn, ffn_pad) */
+int32_t sf_ffn_padded(const sf_desc *desc, int32_t k_ffn);
+
+/* ------------------------------------------------------------------------
+ * gate_scores_to_masks -- Sec. 4.5, "Head pruning with GQA consistency" and
+ * "FFN pruning".  For every (layer l, pattern p) the k_head_host[l] heads and
+ * k_ffn_host[l] channels with the highest gate score g (Eq. (1)) are kept;
+ * ties go to the lower index.  K/V groups kept = { floor(h/(Hq/Hk)) : h kept }.
+ *
+ *   g_head [n_layers,P,Hq] fp32, g_ffn [n_layers,P,d_ff] fp32 (no NaNs)
+ *   k_head_host, k_ffn_host [n_layers] int32 HOST arrays, 1 <= k <= n
+ * outputs (all required):
+ *   head_mask [n_layers,P,Hq] u8, ffn_mask [n_layers,P,d_ff] u8   1 = kept
+ *   head_idx  [n_layers,P,Hq]   kept heads ascending, then -1
+ *   ffn_idx   [n_layers,P,d_ff] kept channels ascending, then -1
+ *   group_idx [n_layers,P,Hk]   kept groups ascending, then -1
+ *   n_groups  [n_layers,P]
+ *   head_group[n_layers,P,Hq]   for the i-th kept head: rank of its group in
+ *                               group_idx; then -1
+ * Limits: Hq <= 64, d_ff <= 16384.  No workspace.
+ */
+int32_t sf_gate_scores_to_masks(const sf_desc *desc, const float *g_head, const float *g_ffn,
+                                const int32_t *k_head_host, const int32_t *k_ffn_host,
+                                uint8_t *head_mask, uint8_t *ffn_mask, int32_t *head_idx,
+                                int32_t *ffn_idx, int32_t *group_idx, int32_t *n_groups,
+                                int32_t *head_group, void *stream);
+
+/* Dense parameters of one encoder layer, unit-major: every head dimension and
+ * every FFN channel is one contiguous row of d_model elements.
+ *   Wq [Hq*dh, d]   column blocks of the paper's W_Q in R^{d x Hq*dh}
+ *   Wk, Wv [Hk*dh, d]
+ *   Wo [Hq*dh, d]   row blocks of the output projection
+ *   W1 [d_ff, d]    columns of the paper's W_1 in R^{d x d_ff}
+ *   W2 [d_ff, d]    rows of the paper's W_2 in R^{d_ff x d}
+ *   bq [Hq*dh], bk, bv [Hk*dh], bo [d], b1 [d_ff], b2 [d]; any bias may be NULL
+ *   ln1_g, ln1_b, ln2_g, ln2_b [d] (required by sf_encoder_forward) */
+typedef struct sf_dense_layer {
+    const void *Wq, *bq, *Wk, *bk, *Wv, *bv, *Wo, *bo;
+    const void *W1, *b1, *W2, *b2;
+    const void *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+} sf_dense_layer;
+
+/* Compacted parameters of one layer for all P patterns (leading dimension P).
+ * With Hq' = k_head, F' = k_ffn, Fp = sf_ffn_padded(F'), Nqkv = (Hq'+2*Hk)*dh:
+ *   Wqkv [P, Nqkv, d]  rows: the Hq' kept query heads (ascending), then Hk
+ *                      K-group slots, then Hk V-group slots; slot r holds kept
+ *                      group r for r < n_groups and zeros otherwise
+ *   bqkv [P, Nqkv]     (NULL iff bq, bk and bv are all NULL)
+ *   WoT  [P, d, Hq'*dh] WoT[n, i*dh+e] = Wo[head_idx[i]*dh+e, n]
+ *   W1   [P, Fp, d]    kept channels ascending, zero rows above F'
+ *   b1   [P, Fp]       (NULL iff dense b1 is NULL)
+ *   W2T  [P, d, Fp]    W2T[n, j] = W2[ffn_idx[j], n], zeros above F'
+ * bo, b2 and the LayerNorm vectors are not pruned: they point at the dense
+ * arrays.  head_group [P,Hq] and n_groups [P] are this layer's slices of the
+ * sf_gate_scores_to_masks outputs. */
+typedef struct sf_compact_layer {
+    int32_t k_head;            /* Hq' */
+    int32_t k_ffn;             /* F'  */
+    void *Wqkv, *bqkv, *WoT, *W1, *b1, *W2T;
+    const void *bo, *b2, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+    const int32_t *head_group;
+    const int32_t *n_groups;
+} sf_compact_layer;
+
+/* ------------------------------------------------------------------------
+ * compact_heads_channels -- Sec. 4.5: keep the column blocks of W_Q for
+ * H_keep, the blocks of W_K / W_V of the referenced groups, the matching row
+ * blocks of the output projection, and W1' = W1[:, N_keep], W2' = W2[N_keep, :].
+ * Pure data movement (bit-exact).  `layer` selects the slices of the index
+ * tensors; dense_host / compact_host are HOST structs of DEVICE pointers.
+ * compact_host->k_head / k_ffn must equal the counts used for the masks; the
+ * caller has allocated Wqkv, bqkv, WoT, W1, b1, W2T at the sizes above and
+ * copied bo, b2, ln*, head_group, n_groups pointers itself.  No workspace.
+ */
+int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
+                                  const sf_dense_layer *dense_host,
+                                  const int32_t *head_idx, const int32_t *group_idx,
+                                  const int32_t *n_groups, const int32_t *ffn_idx,
+                                  const sf_compact_layer *compact_host, void *stream);
+
+/* Element strides of a [B, heads, L, dh] tensor whose last dimension is
+ * contiguous (for V with v_transposed: a [B, groups, dh, L] tensor whose L
+ * dimension is contiguous and `l` is the stride between dh rows). */
+typedef struct sf_strides { int64_t b, h, l; } sf_strides;
+
+/* ------------------------------------------------------------------------
+ * sparse_gqa_forward -- SentryAttend, Sec. 4.4.  For every sample b and head
+ * h (using K/V group head_group[h]):
+ *   1. sparsity score of query i over the allowed keys A_b:
+ *        M_i = max_j s_ij - mean_j s_ij,  s_ij = q_i.k_j / sqrt(dh)
+ *      (max-minus-mean is this library's reading of the measure the paper
+ *      cites; disallowed queries score -inf);
+ *   2. the U queries with the highest M_i are active (ties: lower index; at
+ *      most |A_b| queries);
+ *   3. active rows, Eq. (6): o_i = softmax_j(s_ij) V_g over A_b;
+ *   4. every other row is the context vector mean_{j in A_b} v_j of its group.
+ * uses desc->B, L, dh, dtype and the U of sf_num_active(desc).
+ *   nH, nG        heads in Q, groups in K/V of THIS call (e.g. Hq', Hk)
+ *   Q, K, V       strided tensors, see sf_strides; bf16: strides multiples of 8
+ *   v_transposed  0: V is [B,nG,L,dh]; 1: V is [B,nG,dh,L]
+ *   head_group    [n_maps, nH] int32, head -> group slot (0..nG-1)
+ *   pattern_id    [B] int32 row of head_group used by sample b, or NULL (row 0)
+ *   key_valid     [B,L] u8, 1 = key/query allowed, or NULL (all allowed);
+ *                 a sample with no allowed key gives undefined rows for that
+ *                 sample (callers validate presence on the host)
+ *   forced_sel    [B,nH,U] int32 or NULL: active queries given by the caller
+ *                 (ascending, distinct, -1 padded at the end); skips 1-2
+ *   O             [B,L,nH*dh], row stride ldo elements
+ *   sel_out       [B,nH,U] int32 or NULL: the active queries, ascending, -1 padded
+ *   score_out     [B,nH,L] fp32 or NULL: M_i (not written when U >= L or forced_sel)
+ */
+size_t sf_sparse_gqa_workspace_bytes(const sf_desc *desc, int32_t nH, int32_t nG);
+int32_t sf_sparse_gqa_forward(const sf_desc *desc, int32_t nH, int32_t nG,
+                              const void *Q, sf_strides sq, const void *K, sf_strides sk,
+                              const void *V, sf_strides sv, int32_t v_transposed,
+                              const int32_t *head_group, const int32_t *pattern_id,
+                              const uint8_t *key_valid, const int32_t *forced_sel,
+                              void *O, int64_t ldo, int32_t *sel_out, float *score_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * pruned_ffn_forward -- Sec. 4.5: Y = [X +] act(X' W1'^T + b1') W2' + b2 with
+ * X' = LayerNorm(X) when pre_ln != 0, else X.  X, Y [B*L, d]; sample b uses
+ * pattern pattern_id[b] (NULL: 0).  Uses k_ffn, W1, b1, W2T, b2, ln2_g, ln2_b
+ * of `layer_host` (a HOST struct of device pointers).  Y may not alias X.
+ */
+size_t sf_pruned_ffn_workspace_bytes(const sf_desc *desc, int32_t k_ffn);
+int32_t sf_pruned_ffn_forward(const sf_desc *desc, const sf_compact_layer *layer_host,
+                              const void *X, const int32_t *pattern_id, int32_t pre_ln,
+                              int32_t add_residual, void *Y, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * encoder_forward -- the pruned encoder: for l = 0..n_layers-1
+ *     x <- x + OutProj( SentryAttend( QKV( LN1(x) ) ) )
+ *     x <- x + FFN( LN2(x) )                       (pre-norm)
+ * and a final LayerNorm when SF_FLAG_FINAL_LN is set.
+ *   X [B,L,d] in, Y [B,L,d] out (Y may not alias X)
+ *   layers_host [n_layers]  HOST array of sf_compact_layer
+ *   pattern_id  [B] or NULL;  key_valid [B,L] or NULL
+ *   final_g, final_b [d]    (required with SF_FLAG_FINAL_LN)
+ *   forced_sel  [n_layers,B,Hq'max,U] or NULL  (Hq'max = max k_head over layers)
+ *   sel_out     [n_layers,B,Hq'max,U] or NULL  active queries per layer
+ *   score_out   [n_layers,B,Hq'max,L] fp32 or NULL
+ */
+size_t sf_encoder_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers_host);
+int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers_host,
+                           const void *X, const int32_t *pattern_id, const uint8_t *key_valid,
+                           const void *final_g, const void *final_b,
+                           const int32_t *forced_sel, void *Y, int32_t *sel_out,
+                           float *score_out, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SENTRYFUSE_H */

@@ -1,0 +1,309 @@
+"""Thin ctypes binding of libsentryfuse.so (the gfx950 HIP library).
+
+Argument marshalling only: every step of the path runs in the library's
+kernels.  PyTorch is used for device memory and the current HIP stream.
+There is no CPU fallback: if the shared library has not been built, loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsentryfuse.so")
+_lib = None
+
+SF_F32, SF_BF16 = 0, 1
+SF_RELU, SF_GELU_ERF = 0, 1
+SF_FLAG_FINAL_LN = 1
+
+EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks",
+           "sf_compact_heads_channels", "sf_sparse_gqa_workspace_bytes", "sf_sparse_gqa_forward",
+           "sf_pruned_ffn_workspace_bytes", "sf_pruned_ffn_forward", "sf_encoder_workspace_bytes",
+           "sf_encoder_forward"]
+
+
+class SfDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("L", C.c_int32), ("d_model", C.c_int32),
+                ("Hq", C.c_int32), ("Hk", C.c_int32), ("dh", C.c_int32), ("d_ff", C.c_int32),
+                ("n_layers", C.c_int32), ("P", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
+                ("c_factor", C.c_int32), ("U_override", C.c_int32), ("flags", C.c_uint32),
+                ("ln_eps", C.c_float), ("ffn_pad", C.c_int32)]
+
+
+class SfStrides(C.Structure):
+    _fields_ = [("b", C.c_int64), ("h", C.c_int64), ("l", C.c_int64)]
+
+
+_DENSE_FIELDS = ("Wq", "bq", "Wk", "bk", "Wv", "bv", "Wo", "bo", "W1", "b1", "W2", "b2",
+                 "ln1_g", "ln1_b", "ln2_g", "ln2_b")
+
+
+class SfDenseLayer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _DENSE_FIELDS]
+
+
+class SfCompactLayer(C.Structure):
+    _fields_ = ([("k_head", C.c_int32), ("k_ffn", C.c_int32)]
+                + [(n, C.c_void_p) for n in ("Wqkv", "bqkv", "WoT", "W1", "b1", "W2T", "bo", "b2",
+                                             "ln1_g", "ln1_b", "ln2_g", "ln2_b", "head_group", "n_groups")])
+
+
+class SentryFuseError(RuntimeError):
+    pass
+
+
+def lib():
+    """Load the HIP library; never falls back to anything else."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SentryFuseError(f"{LIB_PATH} is missing: run `python -m paper_2604_08971_amd.build` first")
+        L = C.CDLL(LIB_PATH)
+        L.sf_last_error.restype = C.c_char_p
+        for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes"):
+            getattr(L, n).restype = C.c_size_t
+        for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
+                  "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward"):
+            getattr(L, n).restype = C.c_int32
+        L.sf_sparse_gqa_forward.argtypes = [
+            C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
+            SfStrides, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sf_gate_scores_to_masks.argtypes = [C.POINTER(SfDesc)] + [C.c_void_p] * 12
+        L.sf_compact_heads_channels.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayer),
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.POINTER(SfCompactLayer), C.c_void_p]
+        L.sf_pruned_ffn_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.c_void_p, C.c_void_p,
+                                            C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sf_encoder_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sf_encoder_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)]
+        L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
+        L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        L.sf_num_active.argtypes = [C.POINTER(SfDesc)]
+        L.sf_ffn_padded.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise SentryFuseError(f"{what} failed with status {rc}: {lib().sf_last_error().decode()}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def torch_dtype(dtype: int):
+    return torch.bfloat16 if dtype == SF_BF16 else torch.float32
+
+
+def make_desc(B, L, d_model, Hq, Hk, dh, d_ff, n_layers=1, P=1, dtype=SF_BF16, act=SF_RELU, c_factor=5,
+              U_override=-1, final_ln=False, ln_eps=1e-5, ffn_pad=64) -> SfDesc:
+    return SfDesc(C.sizeof(SfDesc), B, L, d_model, Hq, Hk, dh, d_ff, n_layers, P, dtype, act, c_factor,
+                  U_override, SF_FLAG_FINAL_LN if final_ln else 0, ln_eps, ffn_pad)
+
+
+def num_active(desc: SfDesc) -> int:
+    u = lib().sf_num_active(C.byref(desc))
+    if u < 0:
+        _check(u, "sf_num_active")
+    return int(u)
+
+
+def ffn_padded(desc: SfDesc, k_ffn: int) -> int:
+    r = lib().sf_ffn_padded(C.byref(desc), int(k_ffn))
+    if r < 0:
+        _check(r, "sf_ffn_padded")
+    return int(r)
+
+
+def workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# --------------------------------------------------------------------------- a1
+def gate_scores_to_masks(desc: SfDesc, g_head: torch.Tensor, g_ffn: torch.Tensor, k_head: Sequence[int],
+                         k_ffn: Sequence[int]) -> Dict[str, torch.Tensor]:
+    nl, P, Hq, Hk, F = desc.n_layers, desc.P, desc.Hq, desc.Hk, desc.d_ff
+    dev = g_head.device
+    assert g_head.dtype == torch.float32 and g_ffn.dtype == torch.float32
+    assert tuple(g_head.shape) == (nl, P, Hq) and tuple(g_ffn.shape) == (nl, P, F)
+    assert g_head.is_contiguous() and g_ffn.is_contiguous()
+    out = {
+        "head_mask": torch.empty((nl, P, Hq), dtype=torch.uint8, device=dev),
+        "ffn_mask": torch.empty((nl, P, F), dtype=torch.uint8, device=dev),
+        "head_idx": torch.empty((nl, P, Hq), dtype=torch.int32, device=dev),
+        "ffn_idx": torch.empty((nl, P, F), dtype=torch.int32, device=dev),
+        "group_idx": torch.empty((nl, P, Hk), dtype=torch.int32, device=dev),
+        "n_groups": torch.empty((nl, P), dtype=torch.int32, device=dev),
+        "head_group": torch.empty((nl, P, Hq), dtype=torch.int32, device=dev),
+    }
+    kh = (C.c_int32 * nl)(*[int(k) for k in k_head])
+    kf = (C.c_int32 * nl)(*[int(k) for k in k_ffn])
+    rc = lib().sf_gate_scores_to_masks(
+        C.byref(desc), _ptr(g_head), _ptr(g_ffn), C.cast(kh, C.c_void_p), C.cast(kf, C.c_void_p),
+        _ptr(out["head_mask"]), _ptr(out["ffn_mask"]), _ptr(out["head_idx"]), _ptr(out["ffn_idx"]),
+        _ptr(out["group_idx"]), _ptr(out["n_groups"]), _ptr(out["head_group"]), _stream())
+    _check(rc, "sf_gate_scores_to_masks")
+    return out
+
+
+# --------------------------------------------------------------------------- a2
+class CompactLayer:
+    """Device buffers of one compacted layer (all P patterns) plus the C struct."""
+
+    def __init__(self, desc: SfDesc, dense: Dict[str, torch.Tensor], k_head: int, k_ffn: int,
+                 head_group: torch.Tensor, n_groups: torch.Tensor):
+        P, dh, d, Hk = desc.P, desc.dh, desc.d_model, desc.Hk
+        dt, dev = torch_dtype(desc.dtype), dense["Wq"].device
+        self.k_head, self.k_ffn = int(k_head), int(k_ffn)
+        self.Fp = ffn_padded(desc, k_ffn)
+        self.Nqkv = (self.k_head + 2 * Hk) * dh
+        e = lambda *s: torch.empty(s, dtype=dt, device=dev)
+        self.Wqkv = e(P, self.Nqkv, d)
+        self.bqkv = e(P, self.Nqkv) if dense.get("bq") is not None else None
+        self.WoT = e(P, d, self.k_head * dh)
+        self.W1 = e(P, self.Fp, d)
+        self.b1 = e(P, self.Fp) if dense.get("b1") is not None else None
+        self.W2T = e(P, d, self.Fp)
+        self.dense = dense                     # keeps bo, b2, ln* alive
+        self.head_group, self.n_groups = head_group, n_groups
+        s = SfCompactLayer()
+        s.k_head, s.k_ffn = self.k_head, self.k_ffn
+        for n in ("Wqkv", "bqkv", "WoT", "W1", "b1", "W2T"):
+            t = getattr(self, n)
+            setattr(s, n, None if t is None else t.data_ptr())
+        for n in ("bo", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b"):
+            t = dense.get(n)
+            setattr(s, n, None if t is None else t.data_ptr())
+        s.head_group = head_group.data_ptr()
+        s.n_groups = n_groups.data_ptr()
+        self.struct = s
+
+
+def dense_struct(dense: Dict[str, torch.Tensor]) -> SfDenseLayer:
+    s = SfDenseLayer()
+    for n in _DENSE_FIELDS:
+        t = dense.get(n)
+        if t is not None:
+            assert t.is_contiguous()
+        setattr(s, n, None if t is None else t.data_ptr())
+    return s
+
+
+def compact_heads_channels(desc: SfDesc, layer: int, dense: Dict[str, torch.Tensor],
+                           masks: Dict[str, torch.Tensor], k_head: int, k_ffn: int) -> CompactLayer:
+    """Allocates the compact buffers of `layer` and fills them on the GPU."""
+    hg = masks["head_group"][layer]
+    ng = masks["n_groups"][layer]
+    cl = CompactLayer(desc, dense, k_head, k_ffn, hg, ng)
+    ds = dense_struct(dense)
+    rc = lib().sf_compact_heads_channels(C.byref(desc), int(layer), C.byref(ds), _ptr(masks["head_idx"]),
+                                         _ptr(masks["group_idx"]), _ptr(masks["n_groups"]),
+                                         _ptr(masks["ffn_idx"]), C.byref(cl.struct), _stream())
+    _check(rc, "sf_compact_heads_channels")
+    return cl
+
+
+# ------------------------------------------------------------------------ a4-a7
+def _strides4(t: torch.Tensor) -> SfStrides:
+    assert t.dim() == 4 and t.stride(3) == 1
+    return SfStrides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def sparse_gqa_workspace_bytes(desc: SfDesc, nH: int, nG: int) -> int:
+    return int(lib().sf_sparse_gqa_workspace_bytes(C.byref(desc), nH, nG))
+
+
+def sparse_gqa_forward(desc: SfDesc, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                       head_group: torch.Tensor, pattern_id: Optional[torch.Tensor] = None,
+                       key_valid: Optional[torch.Tensor] = None, forced_sel: Optional[torch.Tensor] = None,
+                       v_transposed: bool = False, want_sel: bool = True, want_score: bool = False,
+                       ws: Optional[torch.Tensor] = None):
+    """Q [B,nH,L,dh], K [B,nG,L,dh], V [B,nG,L,dh] (or [B,nG,dh,L] with v_transposed);
+    last dimension contiguous.  Returns (O [B,L,nH*dh], sel [B,nH,U] | None, score [B,nH,L] | None)."""
+    B, nH, L, dh = Q.shape
+    nG = K.shape[1]
+    U = num_active(desc)
+    dev = Q.device
+    O = torch.empty((B, L, nH * dh), dtype=Q.dtype, device=dev)
+    sel = torch.empty((B, nH, max(U, 1)), dtype=torch.int32, device=dev) if want_sel else None
+    score = torch.full((B, nH, L), float("nan"), dtype=torch.float32, device=dev) if want_score else None
+    if ws is None:
+        ws = workspace(sparse_gqa_workspace_bytes(desc, nH, nG), dev)
+    rc = lib().sf_sparse_gqa_forward(
+        C.byref(desc), nH, nG, _ptr(Q), _strides4(Q), _ptr(K), _strides4(K), _ptr(V), _strides4(V),
+        int(v_transposed), _ptr(head_group), _ptr(pattern_id), _ptr(key_valid), _ptr(forced_sel), _ptr(O),
+        nH * dh, _ptr(sel), _ptr(score), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "sf_sparse_gqa_forward")
+    if sel is not None:
+        sel = sel[:, :, :U]
+    return O, sel, score
+
+
+# --------------------------------------------------------------------------- a9
+def pruned_ffn_forward(desc: SfDesc, layer: CompactLayer, X: torch.Tensor,
+                       pattern_id: Optional[torch.Tensor] = None, pre_ln: bool = True,
+                       add_residual: bool = True, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    assert X.is_contiguous()
+    Y = torch.empty_like(X)
+    if ws is None:
+        ws = workspace(lib().sf_pruned_ffn_workspace_bytes(C.byref(desc), layer.k_ffn), X.device)
+    rc = lib().sf_pruned_ffn_forward(C.byref(desc), C.byref(layer.struct), _ptr(X), _ptr(pattern_id),
+                                     int(pre_ln), int(add_residual), _ptr(Y), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "sf_pruned_ffn_forward")
+    return Y
+
+
+# -------------------------------------------------------------------------- a10
+def layer_array(layers: List[CompactLayer]):
+    arr = (SfCompactLayer * len(layers))()
+    for i, l in enumerate(layers):
+        arr[i] = l.struct
+    return arr
+
+
+def encoder_workspace_bytes(desc: SfDesc, layers: List[CompactLayer]) -> int:
+    return int(lib().sf_encoder_workspace_bytes(C.byref(desc), layer_array(layers)))
+
+
+def encoder_forward(desc: SfDesc, layers: List[CompactLayer], X: torch.Tensor,
+                    pattern_id: Optional[torch.Tensor] = None, key_valid: Optional[torch.Tensor] = None,
+                    final_ln: Optional[Dict[str, torch.Tensor]] = None,
+                    forced_sel: Optional[torch.Tensor] = None, want_sel: bool = False,
+                    want_score: bool = False, out: Optional[torch.Tensor] = None,
+                    ws: Optional[torch.Tensor] = None):
+    """Returns (Y [B,L,d], sel [nl,B,Hq'max,U] | None, score [nl,B,Hq'max,L] | None)."""
+    assert X.is_contiguous()
+    B, L, _ = X.shape
+    nl = desc.n_layers
+    U = num_active(desc)
+    khmax = max(l.k_head for l in layers)
+    dev = X.device
+    Y = torch.empty_like(X) if out is None else out
+    sel = torch.full((nl, B, khmax, max(U, 1)), -1, dtype=torch.int32, device=dev) if want_sel else None
+    score = torch.full((nl, B, khmax, L), float("-inf"), dtype=torch.float32, device=dev) if want_score else None
+    if sel is not None and U == 0:
+        sel = sel[..., :0].contiguous()
+    arr = layer_array(layers)
+    if ws is None:
+        ws = workspace(lib().sf_encoder_workspace_bytes(C.byref(desc), arr), dev)
+    fg = None if final_ln is None else final_ln["g"]
+    fb = None if final_ln is None else final_ln["b"]
+    rc = lib().sf_encoder_forward(C.byref(desc), arr, _ptr(X), _ptr(pattern_id), _ptr(key_valid), _ptr(fg),
+                                  _ptr(fb), _ptr(forced_sel), _ptr(Y), _ptr(sel if U > 0 else None),
+                                  _ptr(score), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "sf_encoder_forward")
+    return Y, sel, score

@@ -1,0 +1,300 @@
+// Descriptor handling, error reporting, pruned_ffn_forward and encoder_forward
+// (the pre-norm layer stack around SentryAttend and the pruned FFN; Sec. 4.4
+// and Sec. 4.5 of the paper).
+#include <math.h>
+#include <string.h>
+
+#include "attention.hpp"
+#include "gemm.hpp"
+
+namespace sf {
+
+char *err_buf()
+{
+    static thread_local char buf[512] = "";
+    return buf;
+}
+
+int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(err_buf(), 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int32_t check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return SF_OK;
+}
+
+int32_t read_desc(const sf_desc *desc, Dims &D)
+{
+    if (!desc) return fail(SF_ERR_INVALID_ARG, "descriptor is NULL");
+    if (desc->struct_size != sizeof(sf_desc))
+        return fail(SF_ERR_INVALID_ARG, "descriptor struct_size %u, expected %zu", desc->struct_size, sizeof(sf_desc));
+    D.B = desc->B; D.L = desc->L; D.d = desc->d_model; D.Hq = desc->Hq; D.Hk = desc->Hk; D.dh = desc->dh;
+    D.F = desc->d_ff; D.nl = desc->n_layers; D.P = desc->P; D.dtype = desc->dtype; D.act = desc->act;
+    D.flags = desc->flags;
+    D.eps = desc->ln_eps > 0.f ? desc->ln_eps : 1e-5f;
+    D.ffn_pad = desc->ffn_pad > 0 ? desc->ffn_pad : 64;
+    if (D.B < 1 || D.L < 1 || D.d < 1 || D.Hq < 1 || D.Hk < 1 || D.dh < 1 || D.F < 1 || D.nl < 1 || D.P < 1)
+        return fail(SF_ERR_INVALID_ARG, "descriptor: sizes must be positive");
+    if (D.Hq % D.Hk) return fail(SF_ERR_INVALID_ARG, "descriptor: Hq %% Hk != 0");
+    if (D.dtype != SF_F32 && D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "descriptor: unknown dtype");
+    if (D.act != SF_RELU && D.act != SF_GELU_ERF) return fail(SF_ERR_UNSUPPORTED, "descriptor: unknown activation");
+    if (D.ffn_pad % 64) return fail(SF_ERR_SHAPE, "descriptor: ffn_pad must be a multiple of 64");
+    if (D.dtype == SF_BF16 && (D.d % 8 || D.dh % 8))
+        return fail(SF_ERR_SHAPE, "descriptor: bf16 needs d_model and dh to be multiples of 8");
+    if ((int64_t)D.B * D.L > (int64_t)1 << 30) return fail(SF_ERR_SHAPE, "descriptor: B*L too large");
+    const int c = desc->c_factor > 0 ? desc->c_factor : 5;
+    if (desc->U_override >= 0) {
+        D.U = desc->U_override < D.L ? desc->U_override : D.L;
+    } else {
+        const double u = (double)c * ceil(log((double)D.L));      // natural log, Sec. 4.4 worked example
+        D.U = u < (double)D.L ? (int)u : D.L;
+    }
+    return SF_OK;
+}
+
+static int gemm_act(int act) { return act == SF_GELU_ERF ? ACT_GELU : ACT_RELU; }
+
+// ---- FFN ------------------------------------------------------------------------
+struct FfnWs { void *xn, *hid; size_t bytes; };
+static FfnWs ffn_ws(const Dims &D, int Fp, bool pre_ln, void *ws)
+{
+    Carver c(ws);
+    FfnWs w{};
+    const size_t es = elem_size(D.dtype), rows = (size_t)D.B * D.L;
+    w.xn = pre_ln ? c.take<char>(rows * D.d * es) : nullptr;
+    w.hid = c.take<char>(rows * Fp * es);
+    w.bytes = c.off;
+    return w;
+}
+
+static int32_t ffn_forward(const Dims &D, const sf_compact_layer &ly, const void *X, const int32_t *pattern_id,
+                           bool pre_ln, bool add_residual, void *Y, void *xn, void *hid, hipStream_t st)
+{
+    const int Fp = (int)align_up(ly.k_ffn, D.ffn_pad);
+    const void *in = X;
+    if (pre_ln) {
+        layernorm(D.dtype, X, ly.ln2_g, ly.ln2_b, D.eps, (int64_t)D.B * D.L, D.d, xn, st);
+        in = xn;
+    }
+    GemmArgs g{};
+    g.A = in; g.lda = D.d; g.W = ly.W1; g.ldw = D.d; g.w_pstride = (int64_t)Fp * D.d;
+    g.bias = ly.b1; g.bias_pstride = Fp; g.pattern_id = pattern_id;
+    g.B = D.B; g.L = D.L; g.N = Fp; g.K = D.d; g.epi = EPI_ROWMAJOR; g.act = gemm_act(D.act);
+    g.C = hid; g.ldc = Fp;
+    if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+
+    GemmArgs h{};
+    h.A = hid; h.lda = Fp; h.W = ly.W2T; h.ldw = Fp; h.w_pstride = (int64_t)D.d * Fp;
+    h.bias = ly.b2; h.bias_pstride = 0; h.pattern_id = pattern_id;
+    h.B = D.B; h.L = D.L; h.N = D.d; h.K = Fp; h.epi = EPI_ROWMAJOR; h.act = ACT_NONE;
+    h.R = add_residual ? X : nullptr; h.ldr = D.d;
+    h.C = Y; h.ldc = D.d;
+    return gemm(D.dtype, h, st);
+}
+
+// ---- encoder ----------------------------------------------------------------------
+struct EncWs {
+    void *xn, *qkv, *vt, *att, *x1, *hid, *attn_ws;
+    size_t attn_ws_bytes, bytes;
+    int kh_max, Fp_max, Lp;
+};
+
+static AttnArgs enc_attn_args(const Dims &D, int kh)
+{
+    AttnArgs a{};
+    a.B = D.B; a.nH = kh; a.nG = D.Hk; a.L = D.L; a.dh = D.dh; a.U = D.U;
+    a.v_transposed = D.dtype == SF_BF16;
+    return a;
+}
+
+static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, EncWs &w)
+{
+    w = EncWs{};
+    int kh_max = 0, kf_max = 0;
+    for (int l = 0; l < D.nl; ++l) {
+        if (layers[l].k_head < 1 || layers[l].k_head > D.Hq || layers[l].k_ffn < 1 || layers[l].k_ffn > D.F)
+            return fail(SF_ERR_INVALID_ARG, "encoder: keep counts of layer %d out of range", l);
+        if (layers[l].k_head > kh_max) kh_max = layers[l].k_head;
+        if (layers[l].k_ffn > kf_max) kf_max = layers[l].k_ffn;
+    }
+    w.kh_max = kh_max;
+    w.Fp_max = (int)align_up(kf_max, D.ffn_pad);
+    w.Lp = (int)align_up(D.L, 8);
+    const size_t es = elem_size(D.dtype), rows = (size_t)D.B * D.L;
+    const bool bf = D.dtype == SF_BF16;
+    Carver c(ws);
+    w.xn = c.take<char>(rows * D.d * es);
+    // bf16: Q and K token-major, V transposed [B,Hk,dh,Lp]; fp32: Q, K, V token-major
+    w.qkv = c.take<char>(rows * (size_t)(kh_max + (bf ? 1 : 2) * D.Hk) * D.dh * es);
+    w.vt = bf ? c.take<char>((size_t)D.B * D.Hk * D.dh * w.Lp * es) : nullptr;
+    w.att = c.take<char>(rows * (size_t)kh_max * D.dh * es);
+    w.x1 = c.take<char>(rows * D.d * es);
+    w.hid = c.take<char>(rows * (size_t)w.Fp_max * es);
+    size_t amax = 0;
+    for (int l = 0; l < D.nl; ++l) {
+        const size_t b = attn_plan(D.dtype, enc_attn_args(D, layers[l].k_head), nullptr).bytes;
+        if (b > amax) amax = b;
+    }
+    w.attn_ws_bytes = amax;
+    w.attn_ws = c.take<char>(amax);
+    w.bytes = c.off;
+    return SF_OK;
+}
+
+}  // namespace sf
+
+using namespace sf;
+
+extern "C" const char *sf_last_error(void) { return err_buf(); }
+
+extern "C" int32_t sf_num_active(const sf_desc *desc)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    return D.U;
+}
+
+extern "C" int32_t sf_ffn_padded(const sf_desc *desc, int32_t k_ffn)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (k_ffn < 1 || k_ffn > D.F) return fail(SF_ERR_INVALID_ARG, "ffn_padded: k_ffn out of range");
+    return (int32_t)align_up(k_ffn, D.ffn_pad);
+}
+
+extern "C" size_t sf_pruned_ffn_workspace_bytes(const sf_desc *desc, int32_t k_ffn)
+{
+    Dims D;
+    if (read_desc(desc, D) || k_ffn < 1 || k_ffn > D.F) return 0;
+    return ffn_ws(D, (int)align_up(k_ffn, D.ffn_pad), true, nullptr).bytes;
+}
+
+extern "C" int32_t sf_pruned_ffn_forward(const sf_desc *desc, const sf_compact_layer *ly, const void *X,
+                                         const int32_t *pattern_id, int32_t pre_ln, int32_t add_residual,
+                                         void *Y, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!ly || !X || !Y) return fail(SF_ERR_INVALID_ARG, "pruned_ffn: NULL argument");
+    if (X == Y) return fail(SF_ERR_INVALID_ARG, "pruned_ffn: Y may not alias X");
+    if (ly->k_ffn < 1 || ly->k_ffn > D.F) return fail(SF_ERR_INVALID_ARG, "pruned_ffn: k_ffn out of range");
+    if (!ly->W1 || !ly->W2T) return fail(SF_ERR_INVALID_ARG, "pruned_ffn: NULL weight pointer");
+    if (D.P > 1 && !pattern_id) return fail(SF_ERR_INVALID_ARG, "pruned_ffn: pattern_id required when P > 1");
+    const int Fp = (int)align_up(ly->k_ffn, D.ffn_pad);
+    FfnWs w = ffn_ws(D, Fp, pre_ln != 0, workspace);
+    if (!workspace || workspace_bytes < w.bytes || ((uintptr_t)workspace & 255))
+        return fail(SF_ERR_WORKSPACE, "pruned_ffn: workspace of %zu bytes (256-byte aligned) required, got %zu",
+                    w.bytes, workspace_bytes);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (int32_t rc = ffn_forward(D, *ly, X, pattern_id, pre_ln != 0, add_residual != 0, Y, w.xn, w.hid, st))
+        return rc;
+    return check_launch("pruned_ffn_forward");
+}
+
+extern "C" size_t sf_encoder_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers)
+{
+    Dims D;
+    EncWs w;
+    if (read_desc(desc, D) || !layers || enc_ws(D, layers, nullptr, w)) return 0;
+    return w.bytes;
+}
+
+extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers, const void *X,
+                                      const int32_t *pattern_id, const uint8_t *key_valid,
+                                      const void *final_g, const void *final_b, const int32_t *forced_sel,
+                                      void *Y, int32_t *sel_out, float *score_out, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!layers || !X || !Y) return fail(SF_ERR_INVALID_ARG, "encoder: NULL argument");
+    if (X == Y) return fail(SF_ERR_INVALID_ARG, "encoder: Y may not alias X");
+    if (D.P > 1 && !pattern_id) return fail(SF_ERR_INVALID_ARG, "encoder: pattern_id required when P > 1");
+    if ((D.flags & SF_FLAG_FINAL_LN) && (!final_g || !final_b))
+        return fail(SF_ERR_INVALID_ARG, "encoder: final LayerNorm parameters missing");
+    for (int l = 0; l < D.nl; ++l) {
+        const sf_compact_layer &ly = layers[l];
+        if (!ly.Wqkv || !ly.WoT || !ly.W1 || !ly.W2T || !ly.ln1_g || !ly.ln1_b || !ly.ln2_g || !ly.ln2_b ||
+            !ly.head_group)
+            return fail(SF_ERR_INVALID_ARG, "encoder: NULL pointer in layer %d", l);
+    }
+    // shape limits of the attention kernels, checked before anything is enqueued
+    if (D.L > 16384) return fail(SF_ERR_SHAPE, "encoder: L <= 16384 required");
+    if (D.dtype == SF_BF16 && D.dh != 32 && D.dh != 64 && D.dh != 128)
+        return fail(SF_ERR_SHAPE, "encoder(bf16): dh must be 32, 64 or 128");
+    if (D.dtype == SF_F32 && (D.dh % 4 || D.dh > 256))
+        return fail(SF_ERR_SHAPE, "encoder(f32): dh must be a multiple of 4, at most 256");
+    if (D.Hq > 64) return fail(SF_ERR_SHAPE, "encoder: Hq <= 64 required");
+    EncWs w;
+    if (int32_t rc = enc_ws(D, layers, workspace, w)) return rc;
+    if (!workspace || workspace_bytes < w.bytes || ((uintptr_t)workspace & 255))
+        return fail(SF_ERR_WORKSPACE, "encoder: workspace of %zu bytes (256-byte aligned) required, got %zu",
+                    w.bytes, workspace_bytes);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf = D.dtype == SF_BF16;
+    const size_t es = elem_size(D.dtype);
+    const int64_t rows = (int64_t)D.B * D.L;
+    const void *in = X;
+    for (int l = 0; l < D.nl; ++l) {
+        const sf_compact_layer &ly = layers[l];
+        const int kh = ly.k_head, dh = D.dh, Hk = D.Hk;
+        const int Nqk = (kh + Hk) * dh, Nqkv = (kh + 2 * Hk) * dh;
+        const int ldq = bf ? Nqk : Nqkv;                    // row length of the token-major buffer
+
+        // x' = LN1(x);  Q, K (token-major) and V (bf16: transposed) = x' Wqkv'^T + b
+        layernorm(D.dtype, in, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, w.xn, st);
+        GemmArgs g{};
+        g.A = w.xn; g.lda = D.d; g.W = ly.Wqkv; g.ldw = D.d; g.w_pstride = (int64_t)Nqkv * D.d;
+        g.bias = ly.bqkv; g.bias_pstride = Nqkv; g.pattern_id = pattern_id;
+        g.B = D.B; g.L = D.L; g.K = D.d; g.act = ACT_NONE; g.epi = EPI_ROWMAJOR;
+        g.C = w.qkv; g.ldc = ldq; g.n0 = 0; g.N = bf ? Nqk : Nqkv;
+        if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+        if (bf) {
+            g.n0 = Nqk; g.N = Hk * dh; g.epi = EPI_VT; g.C = w.vt;
+            g.vt_b = (int64_t)Hk * dh * w.Lp; g.vt_n = w.Lp;
+            if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+        }
+
+        // SentryAttend over the kept heads
+        AttnArgs a = enc_attn_args(D, kh);
+        a.Q = w.qkv; a.sq = sf_strides{(int64_t)D.L * ldq, dh, ldq};
+        a.K = (const char *)w.qkv + (size_t)kh * dh * es; a.sk = a.sq;
+        if (bf) {
+            a.V = w.vt; a.sv = sf_strides{(int64_t)Hk * dh * w.Lp, (int64_t)dh * w.Lp, w.Lp};
+        } else {
+            a.V = (const char *)w.qkv + (size_t)(kh + Hk) * dh * es; a.sv = a.sq;
+        }
+        a.head_group = ly.head_group; a.hg_stride = D.Hq; a.pattern_id = pattern_id; a.key_valid = key_valid;
+        a.selH = w.kh_max;
+        const size_t sel_layer = (size_t)D.B * w.kh_max * D.U, score_layer = (size_t)D.B * w.kh_max * D.L;
+        a.forced_sel = forced_sel ? forced_sel + l * sel_layer : nullptr;
+        a.sel_out = sel_out ? sel_out + l * sel_layer : nullptr;
+        a.score_out = score_out ? score_out + l * score_layer : nullptr;
+        a.O = w.att; a.ldo = (int64_t)kh * dh;
+        a.ws = w.attn_ws; a.ws_bytes = w.attn_ws_bytes;
+        if (int32_t rc = attention_forward(D.dtype, a, st)) return rc;
+
+        // x1 = x + att Wo' + bo   (only the kept heads' rows of Wo exist)
+        GemmArgs o{};
+        o.A = w.att; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
+        o.w_pstride = (int64_t)D.d * kh * dh; o.bias = ly.bo; o.bias_pstride = 0; o.pattern_id = pattern_id;
+        o.B = D.B; o.L = D.L; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
+        o.R = in; o.ldr = D.d; o.C = w.x1; o.ldc = D.d;
+        if (int32_t rc = gemm(D.dtype, o, st)) return rc;
+
+        // y = x1 + FFN(LN2(x1))
+        if (int32_t rc = ffn_forward(D, ly, w.x1, pattern_id, true, true, Y, w.xn, w.hid, st)) return rc;
+        in = Y;
+    }
+    if (D.flags & SF_FLAG_FINAL_LN) layernorm(D.dtype, Y, final_g, final_b, D.eps, rows, D.d, Y, st);
+    return check_launch("encoder_forward");
+}

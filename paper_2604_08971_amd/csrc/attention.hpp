@@ -1,0 +1,50 @@
+// Internal interface of SentryAttend (sparse grouped-query attention,
+// Sec. 4.4 of the paper, Eq. (6)).
+#pragma once
+
+#include "common.hpp"
+
+namespace sf {
+
+struct AttnArgs {
+    int B, nH, nG, L, dh, U;                 // U active queries per head, 0..L
+    const void *Q, *K, *V;
+    sf_strides sq, sk, sv;
+    int v_transposed;                        // V is [B,nG,dh,L] (sv.l = stride between dh rows)
+    const int32_t *head_group; int hg_stride;   // head_group[pattern(b)*hg_stride + h]
+    const int32_t *pattern_id;               // [B] or NULL
+    const uint8_t *key_valid;                // [B,L] or NULL
+    const int32_t *forced_sel;               // [B,selH,U] or NULL
+    void *O; int64_t ldo;                    // [B,L,nH*dh]
+    int32_t *sel_out;                        // [B,selH,U] or NULL
+    float *score_out;                        // [B,selH,L] or NULL
+    int selH;                                // heads per sample in forced_sel / sel_out / score_out (0 = nH)
+    void *ws; size_t ws_bytes;
+};
+
+// Pieces of the workspace (all sizes derive from the same few integers, so the
+// size query and the forward agree by construction).
+struct AttnPlan {
+    int splits;            // key splits of the active pass (1 = write O directly)
+    int keys_per_split;    // multiple of 64
+    int stat_chunks;       // partial-sum chunks of the K/V statistics
+    int Upad;              // U rounded up to 32
+    int Lp;                // L rounded up to 8 (row length of the transposed V copy)
+    size_t bytes;
+    // carved pointers (NULL when planning only)
+    void *vt; float *stat_part; float *stats; int32_t *n_valid; float *score;
+    int32_t *sel; int32_t *slot; float *part_o; float *part_ml;
+};
+AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws);
+
+int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st);
+
+// bf16 MFMA kernels (attention_bf16.hip)
+// score [B,scoreH,L]; sel [B,selH,U]
+int32_t score_bf16(const AttnArgs &a, const AttnPlan &pl, float *score, int scoreH, hipStream_t st);
+int32_t attend_bf16(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_strides svt,
+                    const int32_t *sel, int selH, hipStream_t st);
+
+constexpr int STAT_CHUNK = 512;     // keys per partial-sum block of the K/V statistics
+
+}  // namespace sf

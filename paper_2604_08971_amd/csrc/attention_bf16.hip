@@ -1,0 +1,413 @@
+// SentryAttend on bf16 MFMA (Sec. 4.4 of the paper, Eq. (6)).
+//
+// Both kernels compute the TRANSPOSED score tile S^T = K_tile . Q^T with
+// 32x32x16 MFMAs, so that one accumulator lane owns ONE query (column
+// lane % 32) and 16 of the tile's 32 keys.  Everything the softmax needs per
+// query (running max, running sum, rescaling of the output accumulator) then
+// lives in that lane; only one exchange with lane ^ 32 (the other 16 keys of
+// the same query) is needed per tile.  The output is accumulated transposed
+// as well, O^T = V^T . P^T, so P goes from accumulator registers straight
+// into the MFMA "B" operand without leaving the lane; V is read from a
+// [dh, L] (key-contiguous) layout so that its fragments are plain vector
+// loads too.  K and V^T tiles are staged in LDS once per workgroup and shared
+// by all waves, i.e. by all heads of the K/V group.
+#include "attention.hpp"
+
+namespace sf {
+
+constexpr int NWAVE = 4;
+constexpr int BKEY = 64;          // keys per LDS tile (two 32-key MFMA blocks)
+constexpr int PAD = 8;            // bf16 elements of row padding (16 bytes) against bank conflicts
+constexpr float LOG2E = 1.4426950408889634f;
+
+// Bit j%32 of word j/32 = key j of sample b is allowed (0 beyond L).
+__device__ __forceinline__ void build_mask_words(const uint8_t *kv, int L, uint32_t *words, int nwords)
+{
+    for (int w = threadIdx.x; w < nwords; w += blockDim.x) {
+        uint32_t m = 0;
+        const int j0 = w * 32;
+        for (int t = 0; t < 32; ++t) {
+            const int j = j0 + t;
+            if (j < L && (!kv || kv[j])) m |= 1u << t;
+        }
+        words[w] = m;
+    }
+}
+
+// K tile [BKEY keys][DH] -> LDS rows of DH+PAD; rows at or beyond L are zero.
+template <int DH>
+__device__ __forceinline__ void stage_k_tile(const __bf16 *Kb, int64_t sl, int j0, int L, __bf16 *Ks)
+{
+    constexpr int CH = DH / 8;                         // 16-byte chunks per row
+    for (int c = threadIdx.x; c < BKEY * CH; c += NWAVE * 64) {
+        const int r = c / CH, cc = c % CH;
+        const int j = j0 + r;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (j < L) v = *reinterpret_cast<const uint4 *>(Kb + (int64_t)j * sl + cc * 8);
+        *reinterpret_cast<uint4 *>(Ks + r * (DH + PAD) + cc * 8) = v;
+    }
+}
+
+// ------------------------------------------------------------- sparsity score
+// M_i = max_j s_ij - mean_j s_ij over allowed keys.  The max comes from the
+// streamed S^T tiles; the mean is q_i . mean_key (computed once per group),
+// which is the same number up to fp32 rounding.
+// grid (query blocks, B*nH); each wave owns QBS blocks of 32 queries.
+template <int DH, int QBS>
+__global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
+    const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
+    const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
+    const uint8_t *__restrict__ key_valid, const float *__restrict__ stats, int nH, int nG, int L,
+    float *__restrict__ score, int scoreH)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                              // [BKEY][DH+PAD]
+    float *kbar = reinterpret_cast<float *>(Ks + BKEY * (DH + PAD));            // [DH]
+    uint32_t *words = reinterpret_cast<uint32_t *>(kbar + DH);                  // [ceil(L/32)]
+
+    const int bh = blockIdx.y, b = bh / nH, h = bh % nH;
+    const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    const int nwords = (L + 31) / 32;
+    build_mask_words(kv, L, words, nwords);
+    if (threadIdx.x < DH) kbar[threadIdx.x] = stats[((int64_t)b * nG + g) * 2 * DH + threadIdx.x];
+
+    const __bf16 *Qb = Q + (int64_t)b * sq.b + (int64_t)h * sq.h;
+    const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const int q0 = (blockIdx.x * NWAVE + wave) * QBS * 32;
+
+    bf16x8 qf[QBS][DH / 16];
+    float rmax[QBS];
+#pragma unroll
+    for (int qq = 0; qq < QBS; ++qq) {
+        const int i = min(q0 + qq * 32 + l32, L - 1);
+#pragma unroll
+        for (int kk = 0; kk < DH / 16; ++kk)
+            qf[qq][kk] = *reinterpret_cast<const bf16x8 *>(Qb + (int64_t)i * sq.l + kk * 16 + lhi * 8);
+        rmax[qq] = -INFINITY;
+    }
+    __syncthreads();
+
+    for (int j0 = 0; j0 < L; j0 += BKEY) {
+        const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
+        if ((w0 | w1) == 0u) continue;                     // uniform: the whole tile is disallowed
+        stage_k_tile<DH>(Kb, sk.l, j0, L, Ks);
+        __syncthreads();
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const uint32_t w = kb ? w1 : w0;
+            if (w == 0u) continue;
+            bf16x8 kf[DH / 16];
+#pragma unroll
+            for (int kk = 0; kk < DH / 16; ++kk)
+                kf[kk] = *reinterpret_cast<const bf16x8 *>(Ks + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+            const uint32_t wl = w >> (lhi * 4);
+#pragma unroll
+            for (int qq = 0; qq < QBS; ++qq) {
+                f32x16 s;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < DH / 16; ++kk)
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s, 0, 0, 0);
+                float m = rmax[qq];
+                if (w == 0xffffffffu) {
+#pragma unroll
+                    for (int e = 0; e < 16; e += 2) m = fmaxf(fmaxf(m, s[e]), s[e + 1]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)       // key row of s[e]: (e/4)*8 + lhi*4 + e%4
+                        if ((wl >> ((e / 4) * 8 + (e % 4))) & 1u) m = fmaxf(m, s[e]);
+                }
+                rmax[qq] = m;
+            }
+        }
+        __syncthreads();
+    }
+
+    const float scale = 1.0f / sqrtf((float)DH);
+#pragma unroll
+    for (int qq = 0; qq < QBS; ++qq) {
+        float m = fmaxf(rmax[qq], __shfl_xor(rmax[qq], 32));
+        float dot = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < DH / 16; ++kk)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf((float)qf[qq][kk][e], kbar[kk * 16 + lhi * 8 + e], dot);
+        dot += __shfl_xor(dot, 32);
+        const int i = q0 + qq * 32 + l32;
+        if (lhi == 0 && i < L) {
+            const bool ok = !kv || kv[i];
+            score[((int64_t)b * scoreH + h) * L + i] = ok ? (m - dot) * scale : -INFINITY;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- active pass
+// grid (pair chunks, B*nG, key splits).  A "pair" is (head of the group,
+// block of 32 active queries); each wave owns QB pairs, all waves share the
+// K / V^T tiles of the group.
+template <int DH, int QB>
+__global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
+    const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
+    const __bf16 *__restrict__ VT, sf_strides svt, const int32_t *__restrict__ head_group, int hg_stride,
+    const int32_t *__restrict__ pattern_id, const uint8_t *__restrict__ key_valid,
+    const int32_t *__restrict__ sel, int selH, int nH, int nG, int L, int Lp, int U, int Upad, int splits,
+    int keys_per_split, __bf16 *__restrict__ O, int64_t ldo, float *__restrict__ part_o,
+    float *__restrict__ part_ml)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                         // [BKEY][DH+PAD]
+    __bf16 *Vs = Ks + BKEY * (DH + PAD);                                   // [DH][BKEY+PAD]
+    uint32_t *words = reinterpret_cast<uint32_t *>(Vs + DH * (BKEY + PAD));   // [ceil(L/32)]
+    __shared__ int heads[64];
+    __shared__ int n_heads;
+
+    const int bg = blockIdx.y, b = bg / nG, g = bg % nG, sp = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    const int32_t *hg = head_group + (int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride;
+
+    if (wave == 0) {                      // ordered list of the group's heads (nH <= 64)
+        const bool mine = lane < nH && hg[lane] == g;
+        const unsigned long long bal = __ballot(mine);
+        if (mine) heads[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
+        if (lane == 0) n_heads = __popcll(bal);
+    }
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    const int nwords = (L + 31) / 32;
+    build_mask_words(kv, L, words, nwords);
+    __syncthreads();
+
+    const int nqb = Upad / 32;
+    const int npairs = n_heads * nqb;
+    const int pair0 = blockIdx.x * (NWAVE * QB);
+    if (pair0 >= npairs) return;          // uniform
+
+    int head[QB], qidx[QB], slot[QB];
+    bf16x8 qf[QB][DH / 16];
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq) {
+        const int pi = pair0 + wave * QB + qq;
+        head[qq] = -1; qidx[qq] = -1; slot[qq] = 0;
+        if (pi < npairs) {
+            head[qq] = heads[pi / nqb];
+            slot[qq] = (pi % nqb) * 32 + l32;
+            if (slot[qq] < U) qidx[qq] = sel[((int64_t)b * selH + head[qq]) * U + slot[qq]];
+        }
+        const __bf16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
+                             (int64_t)max(qidx[qq], 0) * sq.l;
+#pragma unroll
+        for (int kk = 0; kk < DH / 16; ++kk)
+            qf[qq][kk] = *reinterpret_cast<const bf16x8 *>(qrow + kk * 16 + lhi * 8);
+    }
+
+    f32x16 oacc[QB][DH / 32];
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq) {
+        m_run[qq] = -INFINITY; l_run[qq] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[qq][db][e] = 0.f;
+    }
+
+    const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const __bf16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const float sc = LOG2E / sqrtf((float)DH);
+    const int jbeg = sp * keys_per_split, jend = min(L, jbeg + keys_per_split);
+
+    for (int j0 = jbeg; j0 < jend; j0 += BKEY) {
+        const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
+        if ((w0 | w1) == 0u) continue;                    // uniform
+        stage_k_tile<DH>(Kb, sk.l, j0, L, Ks);
+        // V^T tile [DH][BKEY]: key-contiguous rows; keys at or beyond L are zeroed
+        for (int c = threadIdx.x; c < DH * (BKEY / 8); c += NWAVE * 64) {
+            const int e = c / (BKEY / 8), cc = c % (BKEY / 8);
+            const int j = j0 + cc * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (j < Lp) {
+                v = *reinterpret_cast<const uint4 *>(Vb + (int64_t)e * svt.l + j);
+                if (j + 8 > L) {
+                    uint16_t *hv = reinterpret_cast<uint16_t *>(&v);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t)
+                        if (j + t >= L) hv[t] = 0;
+                }
+            }
+            *reinterpret_cast<uint4 *>(Vs + e * (BKEY + PAD) + cc * 8) = v;
+        }
+        __syncthreads();
+
+        // S^T blocks for the two 32-key halves
+        f32x16 s[QB][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            bf16x8 kf[DH / 16];
+#pragma unroll
+            for (int kk = 0; kk < DH / 16; ++kk)
+                kf[kk] = *reinterpret_cast<const bf16x8 *>(Ks + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+#pragma unroll
+            for (int qq = 0; qq < QB; ++qq) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[qq][kb][e] = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < DH / 16; ++kk)
+                    s[qq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s[qq][kb], 0, 0, 0);
+            }
+        }
+
+        // online softmax per query (per lane), log2 domain
+        bf16x8 pf[QB][4];
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+            float mt = -INFINITY;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const uint32_t w = kb ? w1 : w0;
+                const uint32_t wl = w >> (lhi * 4);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float v = s[qq][kb][e] * sc;
+                    if (w != 0xffffffffu && !((wl >> ((e / 4) * 8 + (e % 4))) & 1u)) v = -INFINITY;
+                    s[qq][kb][e] = v;
+                    mt = fmaxf(mt, v);
+                }
+            }
+            mt = fmaxf(mt, __shfl_xor(mt, 32));
+            const float m_new = fmaxf(m_run[qq], mt);
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run[qq] - m_safe);
+            m_run[qq] = m_new;
+            float rs = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(s[qq][kb][e] - m_safe);
+                    s[qq][kb][e] = p;
+                    rs += p;
+                }
+            l_run[qq] = l_run[qq] * alpha + rs;
+#pragma unroll
+            for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[qq][db][e] *= alpha;
+            // k-step t covers keys 16t..16t+15; this lane supplies keys
+            // {16t + lhi*4 + 0..3, 16t + 8 + lhi*4 + 0..3} = accumulator entries (t%2)*8 + 0..7
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[qq][t][e] = (__bf16)s[qq][t / 2][(t % 2) * 8 + e];
+        }
+
+        // O^T += V^T . P^T
+#pragma unroll
+        for (int db = 0; db < DH / 32; ++db) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const __bf16 *vrow = Vs + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 4;
+                const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vrow);
+                const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vrow + 8);
+                bf16x8 vf;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
+#pragma unroll
+                for (int qq = 0; qq < QB; ++qq)
+                    oacc[qq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qq][t], oacc[qq][db], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+
+    // lane owns query l32 and output dims db*32 + ig*8 + lhi*4 + {0..3}
+#pragma unroll
+    for (int qq = 0; qq < QB; ++qq) {
+        const float l_tot = l_run[qq] + __shfl_xor(l_run[qq], 32);
+        if (qidx[qq] < 0) continue;
+        if (splits <= 1) {
+            const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+            __bf16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
+#pragma unroll
+            for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                for (int ig = 0; ig < 4; ++ig) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[qq][db][ig * 4 + e] * inv);
+                    *reinterpret_cast<bf16x4 *>(orow + db * 32 + ig * 8 + lhi * 4) = o;
+                }
+        } else {
+            const int64_t base = (((int64_t)b * nH + head[qq]) * Upad + slot[qq]) * splits + sp;
+            float *po = part_o + base * DH;
+#pragma unroll
+            for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                for (int ig = 0; ig < 4; ++ig) {
+                    f32x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = oacc[qq][db][ig * 4 + e];
+                    *reinterpret_cast<f32x4 *>(po + db * 32 + ig * 8 + lhi * 4) = o;
+                }
+            if (lhi == 0) {
+                part_ml[base * 2] = m_run[qq];
+                part_ml[base * 2 + 1] = l_tot;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- host side
+template <int DH, int QBS>
+static int32_t launch_score(const AttnArgs &a, const AttnPlan &pl, float *score, int scoreH, hipStream_t st)
+{
+    const size_t lds = (size_t)BKEY * (DH + PAD) * 2 + DH * 4 + (size_t)ceil_div(a.L, 32) * 4;
+    dim3 grid(ceil_div(a.L, NWAVE * QBS * 32), a.B * a.nH);
+    hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
+                       a.sq, (const __bf16 *)a.K, a.sk, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
+                       pl.stats, a.nH, a.nG, a.L, score, scoreH);
+    return SF_OK;
+}
+
+int32_t score_bf16(const AttnArgs &a, const AttnPlan &pl, float *score, int scoreH, hipStream_t st)
+{
+    const bool wide = a.L >= 1024;
+    switch (a.dh) {
+    case 32:  return wide ? launch_score<32, 4>(a, pl, score, scoreH, st) : launch_score<32, 2>(a, pl, score, scoreH, st);
+    case 64:  return wide ? launch_score<64, 4>(a, pl, score, scoreH, st) : launch_score<64, 2>(a, pl, score, scoreH, st);
+    case 128: return wide ? launch_score<128, 2>(a, pl, score, scoreH, st) : launch_score<128, 1>(a, pl, score, scoreH, st);
+    }
+    return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): dh must be 32, 64 or 128");
+}
+
+template <int DH, int QB>
+static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_strides svt,
+                             const int32_t *sel, int selH, hipStream_t st)
+{
+    const size_t lds = (size_t)BKEY * (DH + PAD) * 2 + (size_t)DH * (BKEY + PAD) * 2 +
+                       (size_t)ceil_div(a.L, 32) * 4;
+    const int nqb = pl.Upad / 32;
+    // upper bound on pairs of one group: every head in the same group
+    dim3 grid(ceil_div(a.nH * nqb, NWAVE * QB), a.B * a.nG, pl.splits);
+    hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
+                       a.sq, (const __bf16 *)a.K, a.sk, (const __bf16 *)vt, svt, a.head_group, a.hg_stride,
+                       a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, a.L, pl.Lp, a.U, pl.Upad, pl.splits,
+                       pl.keys_per_split, (__bf16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
+    return SF_OK;
+}
+
+int32_t attend_bf16(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_strides svt,
+                    const int32_t *sel, int selH, hipStream_t st)
+{
+    if (a.nH > 64) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): at most 64 heads");
+    const bool many = a.U >= 256;       // dense-like: two query blocks per wave
+    switch (a.dh) {
+    case 32:  return many ? launch_attend<32, 2>(a, pl, vt, svt, sel, selH, st) : launch_attend<32, 1>(a, pl, vt, svt, sel, selH, st);
+    case 64:  return many ? launch_attend<64, 2>(a, pl, vt, svt, sel, selH, st) : launch_attend<64, 1>(a, pl, vt, svt, sel, selH, st);
+    case 128: return launch_attend<128, 1>(a, pl, vt, svt, sel, selH, st);
+    }
+    return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): dh must be 32, 64 or 128");
+}
+
+}  // namespace sf

@@ -1,0 +1,457 @@
+// SentryAttend (Sec. 4.4 of the paper): the steps that are not contractions --
+// K/V statistics (mean key for the sparsity score, mean value = context
+// vector), the top-U query choice, the lazy-row fill -- plus the plain fp32
+// kernels and the dispatch.  The bf16 MFMA kernels are in attention_bf16.hip.
+#include "attention.hpp"
+#include "topk.hpp"
+
+namespace sf {
+
+// ---------------------------------------------------------------- statistics
+// Partial column sums of K and V over one chunk of allowed keys.
+// grid (chunks, B*nG), 256 threads; thread t owns column e = t % DHP.
+template <class T>
+__global__ __launch_bounds__(256) void kv_stats_partial_kernel(
+    const T *__restrict__ K, sf_strides sk, const T *__restrict__ V, sf_strides sv, int64_t v_sj,
+    int64_t v_se, const uint8_t *__restrict__ key_valid, int nG, int L, int dh, int DHP,
+    float *__restrict__ part)
+{
+    __shared__ float red[2][256];
+    const int bg = blockIdx.y, b = bg / nG, g = bg % nG;
+    const int e = threadIdx.x % DHP, rg = threadIdx.x / DHP, nrg = 256 / DHP;
+    const int j0 = blockIdx.x * STAT_CHUNK, j1 = min(L, j0 + STAT_CHUNK);
+    const T *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const T *Vb = V + (int64_t)b * sv.b + (int64_t)g * sv.h;
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    float sk_ = 0.f, sv_ = 0.f;
+    if (e < dh)
+        for (int j = j0 + rg; j < j1; j += nrg) {
+            if (kv && !kv[j]) continue;
+            sk_ += to_f32(Kb[(int64_t)j * sk.l + e]);
+            sv_ += to_f32(Vb[(int64_t)j * v_sj + (int64_t)e * v_se]);
+        }
+    red[0][threadIdx.x] = sk_;
+    red[1][threadIdx.x] = sv_;
+    __syncthreads();
+    if (threadIdx.x < DHP && e < dh) {
+        float a = 0.f, c = 0.f;
+        for (int r = 0; r < nrg; ++r) { a += red[0][r * DHP + e]; c += red[1][r * DHP + e]; }
+        float *o = part + (((int64_t)bg * gridDim.x + blockIdx.x) * 2) * dh;
+        o[e] = a;
+        o[dh + e] = c;
+    }
+}
+
+// stats[bg][0][:] = mean allowed key, stats[bg][1][:] = mean allowed value.
+__global__ __launch_bounds__(256) void kv_stats_final_kernel(
+    const float *__restrict__ part, int chunks, const uint8_t *__restrict__ key_valid, int nG, int L,
+    int dh, float *__restrict__ stats, int32_t *__restrict__ n_valid)
+{
+    __shared__ int red[4];
+    const int bg = blockIdx.x, b = bg / nG;
+    int c = 0;
+    if (key_valid) {
+        for (int j = threadIdx.x; j < L; j += 256) c += key_valid[(int64_t)b * L + j] != 0;
+        c = block_sum<256>(c, red);
+    } else {
+        c = L;
+    }
+    if (threadIdx.x == 0 && bg % nG == 0) n_valid[b] = c;
+    const float inv = c > 0 ? 1.0f / (float)c : 0.f;
+    for (int t = threadIdx.x; t < 2 * dh; t += 256) {
+        float s = 0.f;
+        for (int ch = 0; ch < chunks; ++ch) s += part[(((int64_t)bg * chunks + ch) * 2) * dh + t];
+        stats[(int64_t)bg * 2 * dh + t] = s * inv;
+    }
+}
+
+// ------------------------------------------------------------------- selection
+// One block per (b, head): the U_eff = min(U, #allowed) queries with the
+// highest score, ties to the lower index; emitted ascending.  score == NULL
+// means "every allowed query" (used when U >= L).
+__global__ __launch_bounds__(256) void select_kernel(
+    const float *__restrict__ score, int scoreH, const uint8_t *__restrict__ key_valid, int nH, int L,
+    int U, int32_t *__restrict__ sel, int selH, int32_t *__restrict__ slot)
+{
+    extern __shared__ uint32_t keys[];
+    __shared__ int red[4];
+    const int bh = blockIdx.x, b = bh / nH, h = bh % nH;
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    const float *M = score ? score + ((int64_t)b * scoreH + h) * L : nullptr;
+    int32_t *sl = slot + (int64_t)bh * L;
+    int32_t *se = sel + ((int64_t)b * selH + h) * U;
+    int c = 0;
+    for (int i = threadIdx.x; i < L; i += 256) {
+        const bool ok = !kv || kv[i];
+        // allowed queries get a key >= 1 (sortable_key(-inf) > 0), others key 0
+        keys[i] = ok ? (M ? sortable_key(M[i]) : 1u) : 0u;
+        c += ok;
+    }
+    const int n_ok = block_sum<256>(c, red);        // also orders the LDS writes
+    const int k = min(U, n_ok);
+    if (k == 0) {
+        for (int i = threadIdx.x; i < L; i += 256) sl[i] = -1;
+    } else {
+        block_topk<256>(keys, L, k, red, [&](int i, bool kept, int pos) {
+            sl[i] = kept ? pos : -1;
+            if (kept) se[pos] = i;
+        });
+    }
+    for (int r = k + threadIdx.x; r < U; r += 256) se[r] = -1;
+}
+
+// Caller-supplied active set: build the row -> slot map and copy the list.
+__global__ __launch_bounds__(256) void forced_slot_kernel(const int32_t *__restrict__ forced, int forcedH,
+                                                          int nH, int L, int U, int32_t *__restrict__ sel,
+                                                          int selH, int32_t *__restrict__ slot)
+{
+    const int bh = blockIdx.x, b = bh / nH, h = bh % nH;
+    int32_t *sl = slot + (int64_t)bh * L;
+    for (int i = threadIdx.x; i < L; i += 256) sl[i] = -1;
+    __syncthreads();
+    for (int r = threadIdx.x; r < U; r += 256) {
+        int q = forced[((int64_t)b * forcedH + h) * U + r];
+        if (q < 0 || q >= L) q = -1;
+        sel[((int64_t)b * selH + h) * U + r] = q;
+        if (q >= 0) sl[q] = r;
+    }
+}
+
+// ------------------------------------------------------------------------ fill
+// Every row that is not active takes its group's context vector; when the
+// active pass ran split over the keys, the partial results are merged here.
+// One thread per 4 consecutive output elements.
+template <class T>
+__global__ __launch_bounds__(256) void fill_kernel(
+    int nH, int nG, int L, int dh, int Upad, int splits, const int32_t *__restrict__ slot,
+    const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
+    const float *__restrict__ stats, const float *__restrict__ part_o, const float *__restrict__ part_ml,
+    T *__restrict__ O, int64_t ldo)
+{
+    const int b = blockIdx.y;
+    const int q4 = dh / 4;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)L * nH * q4) return;
+    const int e = (int)(idx % q4) * 4;
+    const int h = (int)((idx / q4) % nH);
+    const int i = (int)(idx / ((int64_t)q4 * nH));
+    const int s = slot[((int64_t)b * nH + h) * L + i];
+    float v[4];
+    if (s < 0) {
+        const int p = pattern_id ? pattern_id[b] : 0;
+        const int g = head_group[(int64_t)p * hg_stride + h];
+        const float *ctx = stats + (((int64_t)b * nG + g) * 2 + 1) * dh + e;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = ctx[t];
+    } else {
+        if (splits <= 1) return;                       // written by the active pass
+        const int64_t base = (((int64_t)b * nH + h) * Upad + s) * splits;
+        float m = -INFINITY;
+        for (int sp = 0; sp < splits; ++sp) m = fmaxf(m, part_ml[(base + sp) * 2]);
+        float den = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = 0.f;
+        for (int sp = 0; sp < splits; ++sp) {
+            const float ms = part_ml[(base + sp) * 2];
+            const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
+            den += w * part_ml[(base + sp) * 2 + 1];
+            const float *po = part_o + (base + sp) * dh + e;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] += w * po[t];
+        }
+        const float inv = den > 0.f ? 1.0f / den : 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] *= inv;
+    }
+    T *o = O + ((int64_t)b * L + i) * ldo + (int64_t)h * dh + e;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) o[t] = from_f32<T>(v[t]);
+}
+
+// V [B,nG,L,dh] -> VT [B,nG,dh,Lp] (bf16), 32x32 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__restrict__ V, sf_strides sv, int nG,
+                                                          int L, int dh, int Lp, uint16_t *__restrict__ VT)
+{
+    __shared__ uint16_t tile[32][33];
+    const int bg = blockIdx.z, b = bg / nG, g = bg % nG;
+    const int j0 = blockIdx.x * 32, e0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const uint16_t *Vb = V + (int64_t)b * sv.b + (int64_t)g * sv.h;
+    for (int jj = ty; jj < 32; jj += 8) {
+        const int j = j0 + jj, e = e0 + tx;
+        tile[jj][tx] = (j < L && e < dh) ? Vb[(int64_t)j * sv.l + e] : (uint16_t)0;
+    }
+    __syncthreads();
+    uint16_t *o = VT + (int64_t)bg * dh * Lp;
+    for (int ee = ty; ee < 32; ee += 8) {
+        const int e = e0 + ee, j = j0 + tx;
+        if (e < dh && j < Lp) o[(int64_t)e * Lp + j] = tile[tx][ee];
+    }
+}
+
+// ------------------------------------------------------------ plain fp32 path
+// Sparsity score, one thread per query.
+__global__ __launch_bounds__(256) void score_f32_kernel(
+    const float *__restrict__ Q, sf_strides sq, const float *__restrict__ K, sf_strides sk,
+    const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
+    const uint8_t *__restrict__ key_valid, const int32_t *__restrict__ n_valid, int nH, int L, int dh,
+    float *__restrict__ score, int scoreH)
+{
+    const int bh = blockIdx.y, b = bh / nH, h = bh % nH;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= L) return;
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    float *out = score + ((int64_t)b * scoreH + h) * L + i;
+    if (kv && !kv[i]) { *out = -INFINITY; return; }
+    const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
+    const float *q = Q + (int64_t)b * sq.b + (int64_t)h * sq.h + (int64_t)i * sq.l;
+    const float *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const float scale = 1.0f / sqrtf((float)dh);
+    float mx = -INFINITY, sum = 0.f;
+    for (int j = 0; j < L; ++j) {
+        if (kv && !kv[j]) continue;
+        const float *k = Kb + (int64_t)j * sk.l;
+        float s = 0.f;
+        for (int e = 0; e < dh; ++e) s = fmaf(q[e], k[e], s);
+        s *= scale;
+        mx = fmaxf(mx, s);
+        sum += s;
+    }
+    *out = mx - sum / (float)n_valid[b];
+}
+
+// Active rows, Eq. (6): one 64-lane wave per (b, head, slot).
+__global__ __launch_bounds__(64) void attend_f32_kernel(
+    const float *__restrict__ Q, sf_strides sq, const float *__restrict__ K, sf_strides sk,
+    const float *__restrict__ V, sf_strides sv, int64_t v_sj, int64_t v_se,
+    const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
+    const uint8_t *__restrict__ key_valid, const int32_t *__restrict__ sel, int selH, int nH, int L, int dh,
+    int U, float *__restrict__ O, int64_t ldo)
+{
+    extern __shared__ float prob[];
+    const int bh = blockIdx.y, b = bh / nH, h = bh % nH, lane = threadIdx.x;
+    const int qi = sel[((int64_t)b * selH + h) * U + blockIdx.x];
+    if (qi < 0) return;
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
+    const float *q = Q + (int64_t)b * sq.b + (int64_t)h * sq.h + (int64_t)qi * sq.l;
+    const float *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const float *Vb = V + (int64_t)b * sv.b + (int64_t)g * sv.h;
+    const float scale = 1.0f / sqrtf((float)dh);
+    float mx = -INFINITY;
+    for (int j = lane; j < L; j += 64) {
+        float s = -INFINITY;
+        if (!kv || kv[j]) {
+            const float *k = Kb + (int64_t)j * sk.l;
+            s = 0.f;
+            for (int e = 0; e < dh; ++e) s = fmaf(q[e], k[e], s);
+            s *= scale;
+        }
+        prob[j] = s;
+        mx = fmaxf(mx, s);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float den = 0.f;
+    for (int j = lane; j < L; j += 64) {
+        const float pj = prob[j] == -INFINITY ? 0.f : expf(prob[j] - mx);
+        prob[j] = pj;
+        den += pj;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o);
+    __syncthreads();
+    const float inv = 1.0f / den;
+    for (int e = lane; e < dh; e += 64) {
+        float acc = 0.f;
+        for (int j = 0; j < L; ++j) acc = fmaf(prob[j], Vb[(int64_t)j * v_sj + (int64_t)e * v_se], acc);
+        O[((int64_t)b * L + qi) * ldo + (int64_t)h * dh + e] = acc * inv;
+    }
+}
+
+// ------------------------------------------------------------------- planning
+AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws)
+{
+    AttnPlan pl{};
+    const bool sparse = a.U < a.L;
+    pl.Upad = (int)align_up(a.U > 0 ? a.U : 1, 32);
+    pl.Lp = (int)align_up(a.L, 8);
+    pl.stat_chunks = ceil_div(a.L, STAT_CHUNK);
+    pl.splits = 1;
+    pl.keys_per_split = (int)align_up(a.L, 64);
+    if (dtype == SF_BF16 && sparse && a.U > 0) {
+        // the active pass has only B*nG independent (sample, group) problems:
+        // split the keys until roughly 768 workgroups exist
+        const int64_t bg = (int64_t)a.B * a.nG;
+        int want = (int)((768 + bg - 1) / bg);
+        const int max_splits = a.L / 128 > 0 ? a.L / 128 : 1;
+        if (want > max_splits) want = max_splits;
+        if (want > 1) {
+            pl.keys_per_split = (int)align_up(ceil_div(a.L, want), 64);
+            pl.splits = ceil_div(a.L, pl.keys_per_split);
+        }
+    }
+    Carver c(ws);
+    const size_t BH = (size_t)a.B * a.nH, BG = (size_t)a.B * a.nG;
+    pl.vt = (dtype == SF_BF16 && !a.v_transposed) ? c.take<uint16_t>(BG * a.dh * pl.Lp) : nullptr;
+    pl.stat_part = c.take<float>(BG * pl.stat_chunks * 2 * a.dh);
+    pl.stats = c.take<float>(BG * 2 * a.dh);
+    pl.n_valid = c.take<int32_t>(a.B);
+    pl.score = c.take<float>(BH * a.L);
+    pl.sel = c.take<int32_t>(BH * (a.U > 0 ? a.U : 1));
+    pl.slot = c.take<int32_t>(BH * a.L);
+    if (pl.splits > 1) {
+        pl.part_o = c.take<float>(BH * pl.Upad * pl.splits * a.dh);
+        pl.part_ml = c.take<float>(BH * pl.Upad * pl.splits * 2);
+    }
+    pl.bytes = c.off;
+    return pl;
+}
+
+int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
+{
+    if (a.B <= 0) return SF_OK;
+    if (a.L > 16384) return fail(SF_ERR_SHAPE, "sparse_gqa: L <= 16384 required");
+    if (a.dh % 4 || a.ldo % 4) return fail(SF_ERR_SHAPE, "sparse_gqa: dh and ldo must be multiples of 4");
+    if (dtype == SF_BF16) {
+        if (a.dh != 32 && a.dh != 64 && a.dh != 128)
+            return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): dh must be 32, 64 or 128");
+        if ((a.sq.b | a.sq.h | a.sq.l | a.sk.b | a.sk.h | a.sk.l | a.sv.b | a.sv.h | a.sv.l) % 8)
+            return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): strides must be multiples of 8 elements");
+    } else if (a.dh > 256) {
+        return fail(SF_ERR_SHAPE, "sparse_gqa(f32): dh <= 256 required");
+    }
+    AttnPlan pl = attn_plan(dtype, a, a.ws);
+    if (pl.bytes > 0 && (!a.ws || a.ws_bytes < pl.bytes || ((uintptr_t)a.ws & 255)))
+        return fail(SF_ERR_WORKSPACE, "sparse_gqa: workspace of %zu bytes (256-byte aligned) required, got %zu",
+                    pl.bytes, a.ws_bytes);
+
+    const int BH = a.B * a.nH, BG = a.B * a.nG;
+    // V as the kernels will read it
+    const void *Vuse = a.V;
+    sf_strides svu = a.sv;
+    int vT = a.v_transposed;
+    if (dtype == SF_BF16 && !a.v_transposed) {
+        dim3 grid(ceil_div(pl.Lp, 32), ceil_div(a.dh, 32), BG);
+        hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, st, (const uint16_t *)a.V, a.sv, a.nG,
+                           a.L, a.dh, pl.Lp, (uint16_t *)pl.vt);
+        Vuse = pl.vt;
+        svu.b = (int64_t)a.nG * a.dh * pl.Lp;
+        svu.h = (int64_t)a.dh * pl.Lp;
+        svu.l = pl.Lp;
+        vT = 1;
+    }
+    const int64_t v_sj = vT ? 1 : svu.l, v_se = vT ? svu.l : 1;
+
+    // 1. statistics: mean key (for the score's mean term) and context vector
+    {
+        int DHP = 4;
+        while (DHP < a.dh) DHP *= 2;
+        dim3 grid(pl.stat_chunks, BG);
+        if (dtype == SF_BF16)
+            hipLaunchKernelGGL(kv_stats_partial_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)a.K,
+                               a.sk, (const __bf16 *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
+                               DHP, pl.stat_part);
+        else
+            hipLaunchKernelGGL(kv_stats_partial_kernel<float>, grid, dim3(256), 0, st, (const float *)a.K,
+                               a.sk, (const float *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
+                               DHP, pl.stat_part);
+        hipLaunchKernelGGL(kv_stats_final_kernel, dim3(BG), dim3(256), 0, st, pl.stat_part, pl.stat_chunks,
+                           a.key_valid, a.nG, a.L, a.dh, pl.stats, pl.n_valid);
+    }
+
+    // 2. active set
+    const int userH = a.selH > 0 ? a.selH : a.nH;
+    int32_t *sel = a.sel_out ? a.sel_out : pl.sel;
+    const int selH = a.sel_out ? userH : a.nH;
+    if (a.forced_sel && a.U > 0) {
+        hipLaunchKernelGGL(forced_slot_kernel, dim3(BH), dim3(256), 0, st, a.forced_sel, userH, a.nH, a.L, a.U,
+                           sel, selH, pl.slot);
+    } else {
+        const float *M = nullptr;
+        int scoreH = a.nH;
+        if (a.U > 0 && a.U < a.L) {
+            float *score = a.score_out ? a.score_out : pl.score;
+            scoreH = a.score_out ? userH : a.nH;
+            if (dtype == SF_BF16) {
+                if (int32_t rc = score_bf16(a, pl, score, scoreH, st)) return rc;
+            } else {
+                dim3 grid(ceil_div(a.L, 256), BH);
+                hipLaunchKernelGGL(score_f32_kernel, grid, dim3(256), 0, st, (const float *)a.Q, a.sq,
+                                   (const float *)a.K, a.sk, a.head_group, a.hg_stride, a.pattern_id,
+                                   a.key_valid, pl.n_valid, a.nH, a.L, a.dh, score, scoreH);
+            }
+            M = score;
+        }
+        hipLaunchKernelGGL(select_kernel, dim3(BH), dim3(256), a.L * sizeof(uint32_t), st, M, scoreH,
+                           a.key_valid, a.nH, a.L, a.U, sel, selH, pl.slot);
+    }
+
+    // 3. active rows
+    if (a.U > 0) {
+        if (dtype == SF_BF16) {
+            if (int32_t rc = attend_bf16(a, pl, Vuse, svu, sel, selH, st)) return rc;
+        } else {
+            dim3 grid(a.U, BH);
+            hipLaunchKernelGGL(attend_f32_kernel, grid, dim3(64), a.L * sizeof(float), st, (const float *)a.Q,
+                               a.sq, (const float *)a.K, a.sk, (const float *)Vuse, svu, v_sj, v_se,
+                               a.head_group, a.hg_stride, a.pattern_id, a.key_valid, sel, selH, a.nH, a.L,
+                               a.dh, a.U, (float *)a.O, a.ldo);
+        }
+    }
+
+    // 4. lazy rows (+ merge of the key splits)
+    {
+        const int64_t n = (int64_t)a.L * a.nH * (a.dh / 4);
+        dim3 grid((unsigned)((n + 255) / 256), a.B);
+        if (dtype == SF_BF16)
+            hipLaunchKernelGGL(fill_kernel<__bf16>, grid, dim3(256), 0, st, a.nH, a.nG, a.L, a.dh, pl.Upad,
+                               pl.splits, pl.slot, a.head_group, a.hg_stride, a.pattern_id, pl.stats,
+                               pl.part_o, pl.part_ml, (__bf16 *)a.O, a.ldo);
+        else
+            hipLaunchKernelGGL(fill_kernel<float>, grid, dim3(256), 0, st, a.nH, a.nG, a.L, a.dh, pl.Upad,
+                               pl.splits, pl.slot, a.head_group, a.hg_stride, a.pattern_id, pl.stats,
+                               pl.part_o, pl.part_ml, (float *)a.O, a.ldo);
+    }
+    return check_launch("sparse_gqa_forward");
+}
+
+}  // namespace sf
+
+using namespace sf;
+
+static int32_t make_attn_args(const sf_desc *desc, int32_t nH, int32_t nG, Dims &D, AttnArgs &a)
+{
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (nH < 1 || nG < 1) return fail(SF_ERR_INVALID_ARG, "sparse_gqa: nH and nG must be positive");
+    a = AttnArgs{};
+    a.B = D.B; a.nH = nH; a.nG = nG; a.L = D.L; a.dh = D.dh; a.U = D.U;
+    return SF_OK;
+}
+
+extern "C" size_t sf_sparse_gqa_workspace_bytes(const sf_desc *desc, int32_t nH, int32_t nG)
+{
+    Dims D; AttnArgs a;
+    if (make_attn_args(desc, nH, nG, D, a)) return 0;
+    a.v_transposed = 0;       // the larger of the two cases
+    return attn_plan(D.dtype, a, nullptr).bytes;
+}
+
+extern "C" int32_t sf_sparse_gqa_forward(const sf_desc *desc, int32_t nH, int32_t nG, const void *Q,
+                                         sf_strides sq, const void *K, sf_strides sk, const void *V,
+                                         sf_strides sv, int32_t v_transposed, const int32_t *head_group,
+                                         const int32_t *pattern_id, const uint8_t *key_valid,
+                                         const int32_t *forced_sel, void *O, int64_t ldo, int32_t *sel_out,
+                                         float *score_out, void *workspace, size_t workspace_bytes,
+                                         void *stream)
+{
+    Dims D; AttnArgs a;
+    if (int32_t rc = make_attn_args(desc, nH, nG, D, a)) return rc;
+    if (!Q || !K || !V || !head_group || !O) return fail(SF_ERR_INVALID_ARG, "sparse_gqa: NULL argument");
+    if (ldo < (int64_t)nH * D.dh) return fail(SF_ERR_SHAPE, "sparse_gqa: ldo smaller than nH*dh");
+    a.Q = Q; a.K = K; a.V = V; a.sq = sq; a.sk = sk; a.sv = sv; a.v_transposed = v_transposed != 0;
+    a.head_group = head_group; a.hg_stride = nH; a.pattern_id = pattern_id; a.key_valid = key_valid;
+    a.forced_sel = forced_sel; a.O = O; a.ldo = ldo; a.sel_out = sel_out; a.score_out = score_out;
+    a.ws = workspace; a.ws_bytes = workspace_bytes;
+    return attention_forward(D.dtype, a, static_cast<hipStream_t>(stream));
+}

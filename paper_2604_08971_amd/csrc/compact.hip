@@ -1,0 +1,160 @@
+// compact_heads_channels: gather the kept head blocks / FFN channels of the
+// dense weights into padded dense buffers (Sec. 4.5: column blocks of W_Q for
+// H_keep, the matching K/V group blocks, W1' = W1[:, N_keep],
+// W2' = W2[N_keep, :]).  Pure data movement; HBM-bound.
+#include "common.hpp"
+
+namespace sf {
+
+// dst[p, R, :] = src[idx[p, R / block] * block + R % block, :]  (zeros when the
+// slot is unused).  One block per output row; VEC-typed copies.  Pattern p's
+// rows start dst_p_stride VECs after pattern p-1's (so a region of a larger
+// per-pattern buffer can be the target).
+template <class VEC>
+__global__ __launch_bounds__(256) void gather_rows_kernel(
+    const VEC *__restrict__ src, VEC *__restrict__ dst, const int32_t *__restrict__ idx,
+    int idx_stride, int block, int n_static, const int32_t *__restrict__ n_dev,
+    size_t dst_p_stride, int row_vecs)
+{
+    const int p = blockIdx.y, R = blockIdx.x;
+    const int slot = R / block, r = R % block;
+    const int n_valid = n_dev ? n_dev[p] : n_static;
+    int src_unit = -1;
+    if (slot < n_valid) src_unit = idx[(size_t)p * idx_stride + slot];
+    VEC *d = dst + (size_t)p * dst_p_stride + (size_t)R * row_vecs;
+    if (src_unit < 0) {
+        VEC z{};
+        for (int i = threadIdx.x; i < row_vecs; i += blockDim.x) d[i] = z;
+    } else {
+        const VEC *s = src + ((size_t)src_unit * block + r) * row_vecs;
+        for (int i = threadIdx.x; i < row_vecs; i += blockDim.x) d[i] = s[i];
+    }
+}
+
+// dstT[p, n, J] = src[idx[p, J / block] * block + J % block, n]  for n < d,
+// J < cols_out (zeros when the slot is unused).  32x32 tiles through LDS so
+// both the reads (along n) and the writes (along J) are contiguous.
+template <class T>
+__global__ __launch_bounds__(256) void gather_transpose_kernel(
+    const T *__restrict__ src, T *__restrict__ dstT, const int32_t *__restrict__ idx,
+    int idx_stride, int block, int n_valid, int cols_out, int d)
+{
+    __shared__ T tile[32][33];
+    const int p = blockIdx.z;
+    const int J0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    for (int jj = ty; jj < 32; jj += 8) {
+        const int J = J0 + jj, n = n0 + tx;
+        T v = T(0);
+        if (J < cols_out && n < d) {
+            const int slot = J / block;
+            const int unit = slot < n_valid ? idx[(size_t)p * idx_stride + slot] : -1;
+            if (unit >= 0) v = src[((size_t)unit * block + J % block) * d + n];
+        }
+        tile[jj][tx] = v;
+    }
+    __syncthreads();
+    for (int nn = ty; nn < 32; nn += 8) {
+        const int n = n0 + nn, J = J0 + tx;
+        if (n < d && J < cols_out) dstT[((size_t)p * d + n) * cols_out + J] = tile[tx][nn];
+    }
+}
+
+static void gather_rows(hipStream_t st, const void *src, void *dst, const int32_t *idx,
+                        int idx_stride, int block, int n_static, const int32_t *n_dev,
+                        int rows_out, size_t rows_per_pattern, size_t row_bytes, int P)
+{
+    const size_t pstride = rows_per_pattern * row_bytes;
+    dim3 grid(rows_out, P);
+    const bool v16 = row_bytes % 16 == 0 && ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0);
+    if (v16) {
+        const int rv = (int)(row_bytes / 16);
+        const int nt = rv >= 256 ? 256 : (rv >= 128 ? 128 : 64);
+        hipLaunchKernelGGL(gather_rows_kernel<uint4>, grid, dim3(nt), 0, st, (const uint4 *)src,
+                           (uint4 *)dst, idx, idx_stride, block, n_static, n_dev, pstride / 16, rv);
+    } else if (row_bytes % 4 == 0) {
+        hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, grid, dim3(64), 0, st, (const uint32_t *)src,
+                           (uint32_t *)dst, idx, idx_stride, block, n_static, n_dev, pstride / 4,
+                           (int)(row_bytes / 4));
+    } else {
+        hipLaunchKernelGGL(gather_rows_kernel<uint16_t>, grid, dim3(64), 0, st, (const uint16_t *)src,
+                           (uint16_t *)dst, idx, idx_stride, block, n_static, n_dev, pstride / 2,
+                           (int)(row_bytes / 2));
+    }
+}
+
+static void gather_transpose(hipStream_t st, int dtype, const void *src, void *dst,
+                             const int32_t *idx, int idx_stride, int block, int n_valid,
+                             int cols_out, int d, int P)
+{
+    dim3 grid(ceil_div(cols_out, 32), ceil_div(d, 32), P);
+    if (dtype == SF_BF16)
+        hipLaunchKernelGGL(gather_transpose_kernel<uint16_t>, grid, dim3(256), 0, st,
+                           (const uint16_t *)src, (uint16_t *)dst, idx, idx_stride, block, n_valid,
+                           cols_out, d);
+    else
+        hipLaunchKernelGGL(gather_transpose_kernel<uint32_t>, grid, dim3(256), 0, st,
+                           (const uint32_t *)src, (uint32_t *)dst, idx, idx_stride, block, n_valid,
+                           cols_out, d);
+}
+
+}  // namespace sf
+
+using namespace sf;
+
+extern "C" int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
+                                             const sf_dense_layer *dense,
+                                             const int32_t *head_idx, const int32_t *group_idx,
+                                             const int32_t *n_groups, const int32_t *ffn_idx,
+                                             const sf_compact_layer *c, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!dense || !c || !head_idx || !group_idx || !n_groups || !ffn_idx)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels: NULL argument");
+    if (layer < 0 || layer >= D.nl)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels: layer %d out of range", layer);
+    if (c->k_head < 1 || c->k_head > D.Hq || c->k_ffn < 1 || c->k_ffn > D.F)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels: keep counts out of range");
+    if (!dense->Wq || !dense->Wk || !dense->Wv || !dense->Wo || !dense->W1 || !dense->W2 ||
+        !c->Wqkv || !c->WoT || !c->W1 || !c->W2T)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels: NULL weight pointer");
+    const bool qkv_bias = dense->bq || dense->bk || dense->bv;
+    if (qkv_bias && !(dense->bq && dense->bk && dense->bv))
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels: bq, bk, bv must be all set or all NULL");
+    if ((qkv_bias && !c->bqkv) || (dense->b1 && !c->b1))
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels: compact bias buffer missing");
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t es = elem_size(D.dtype);
+    const int P = D.P, dh = D.dh, d = D.d, kh = c->k_head, kf = c->k_ffn;
+    const int Fp = (int)align_up(kf, D.ffn_pad);
+    const int Nqkv = (kh + 2 * D.Hk) * dh;
+    const int32_t *hi = head_idx + (size_t)layer * P * D.Hq;
+    const int32_t *gi = group_idx + (size_t)layer * P * D.Hk;
+    const int32_t *ng = n_groups + (size_t)layer * P;
+    const int32_t *fi = ffn_idx + (size_t)layer * P * D.F;
+
+    // Wqkv [P, Nqkv, d] has three row regions: kept Q heads, K group slots, V group slots.
+    struct Region { const void *W, *b; const int32_t *idx; int stride, n_static; const int32_t *n_dev; int row0, rows; };
+    const Region regs[3] = {
+        {dense->Wq, dense->bq, hi, D.Hq, kh, nullptr, 0, kh * dh},
+        {dense->Wk, dense->bk, gi, D.Hk, 0, ng, kh * dh, D.Hk * dh},
+        {dense->Wv, dense->bv, gi, D.Hk, 0, ng, (kh + D.Hk) * dh, D.Hk * dh},
+    };
+    for (const Region &r : regs) {
+        char *dW = (char *)c->Wqkv + (size_t)r.row0 * d * es;
+        gather_rows(st, r.W, dW, r.idx, r.stride, dh, r.n_static, r.n_dev, r.rows, Nqkv, (size_t)d * es, P);
+        if (qkv_bias) {
+            char *db = (char *)c->bqkv + (size_t)r.row0 * es;
+            gather_rows(st, r.b, db, r.idx, r.stride, dh, r.n_static, r.n_dev, r.rows, Nqkv, es, P);
+        }
+    }
+    // W1' rows (+ zero pad rows), b1'
+    gather_rows(st, dense->W1, c->W1, fi, D.F, 1, kf, nullptr, Fp, Fp, (size_t)d * es, P);
+    if (dense->b1) gather_rows(st, dense->b1, c->b1, fi, D.F, 1, kf, nullptr, Fp, Fp, es, P);
+    // W2'^T and Wo'^T: unit rows become columns so the GEMMs read K-contiguous operands
+    gather_transpose(st, D.dtype, dense->W2, c->W2T, fi, D.F, 1, kf, Fp, d, P);
+    gather_transpose(st, D.dtype, dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, d, P);
+    return check_launch("compact_heads_channels");
+}

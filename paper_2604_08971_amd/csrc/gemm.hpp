@@ -1,0 +1,36 @@
+// Interface of the GEMM used for every projection of the encoder layer:
+//   C[b*L+i, n0+n] = act( sum_k A[b*L+i, k] * W[p(b)][n0+n, k] + bias[p(b)][n0+n] ) (+ R[b*L+i, n0+n])
+// A is token-major, W is unit-major (one output feature per row), p(b) is the
+// presence pattern of sample b, so tiles never straddle two samples.
+#pragma once
+
+#include "common.hpp"
+
+namespace sf {
+
+enum { EPI_ROWMAJOR = 0, EPI_VT = 1 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+
+struct GemmArgs {
+    const void *A; int64_t lda;
+    const void *W; int64_t ldw; int64_t w_pstride;       // elements between patterns
+    const void *bias; int64_t bias_pstride;              // may be NULL; 0 stride = shared
+    const int32_t *pattern_id;                           // [B] or NULL (pattern 0)
+    int B, L, N, K;                                      // N = number of output features of this launch
+    int n0;                                              // first feature (row of W, entry of bias)
+    int epi;                                             // EPI_ROWMAJOR: C[row, c0 + n], EPI_VT: C[b, n, i]
+    int act;
+    const void *R; int64_t ldr; int r0;                  // residual (NULL = none), first column r0
+    void *C; int64_t ldc; int c0;                        // EPI_ROWMAJOR: row stride, first column
+    int64_t vt_b, vt_n;                                  // EPI_VT: strides of b and n (i contiguous)
+};
+
+// dtype SF_BF16: bf16 MFMA, fp32 accumulate (K % 8 == 0, lda/ldw/ldr % 8 == 0,
+// ldc % 4 == 0, 16-byte aligned bases).  dtype SF_F32: fp32 FMA.
+int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st);
+
+// LayerNorm over rows of d elements (biased variance), y may alias x.
+void layernorm(int dtype, const void *x, const void *gamma, const void *beta, float eps,
+               int64_t rows, int d, void *y, hipStream_t st);
+
+}  // namespace sf

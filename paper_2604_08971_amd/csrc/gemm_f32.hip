@@ -1,0 +1,121 @@
+// fp32 GEMM (plain FMA, LDS-tiled) and LayerNorm for both dtypes.
+// The fp32 path exists for the 1e-5 parity bar of the fp32 workload; it is
+// not the throughput path.
+#include "gemm.hpp"
+
+namespace sf {
+
+int32_t gemm_bf16(const GemmArgs &a, hipStream_t st);
+
+constexpr int FT = 32;      // output tile edge
+constexpr int FK = 16;      // K step
+
+__device__ __forceinline__ float act_f32(float z, int act)
+{
+    if (act == ACT_RELU) return z > 0.f ? z : 0.f;
+    if (act == ACT_GELU) return 0.5f * z * (1.f + erff(z * 0.70710678118654752f));
+    return z;
+}
+
+// 256 threads; thread (tx,ty) of a 16x16 grid owns a 2x2 patch of the 32x32 tile.
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a)
+{
+    __shared__ float Xs[FT][FK + 1], Ws[FT][FK + 1];
+    const int tiles_m = (a.L + FT - 1) / FT;
+    const int b = blockIdx.x / tiles_m;
+    const int m0 = (blockIdx.x % tiles_m) * FT;
+    const int nt0 = blockIdx.y * FT;
+    const int p = a.pattern_id ? a.pattern_id[b] : 0;
+    const float *A = static_cast<const float *>(a.A) + ((int64_t)b * a.L) * a.lda;
+    const float *W = static_cast<const float *>(a.W) + (int64_t)p * a.w_pstride + (int64_t)a.n0 * a.ldw;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+
+    for (int k0 = 0; k0 < a.K; k0 += FK) {
+        for (int e = threadIdx.x; e < FT * FK; e += 256) {
+            const int r = e / FK, k = e % FK;
+            const int i = m0 + r, n = nt0 + r;
+            Xs[r][k] = (i < a.L && k0 + k < a.K) ? A[(int64_t)i * a.lda + k0 + k] : 0.f;
+            Ws[r][k] = (n < a.N && k0 + k < a.K) ? W[(int64_t)n * a.ldw + k0 + k] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < FK; ++k) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int v = 0; v < 2; ++v)
+                    acc[u][v] = fmaf(Xs[ty * 2 + u][k], Ws[tx * 2 + v][k], acc[u][v]);
+        }
+        __syncthreads();
+    }
+    const float *bias = a.bias ? static_cast<const float *>(a.bias) + (int64_t)p * a.bias_pstride + a.n0 : nullptr;
+    const float *R = static_cast<const float *>(a.R);
+    float *C = static_cast<float *>(a.C);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            const int i = m0 + ty * 2 + u, n = nt0 + tx * 2 + v;
+            if (i >= a.L || n >= a.N) continue;
+            const int64_t row = (int64_t)b * a.L + i;
+            float z = acc[u][v] + (bias ? bias[n] : 0.f);
+            z = act_f32(z, a.act);
+            if (R) z += R[row * a.ldr + a.r0 + n];
+            if (a.epi == EPI_VT) C[(int64_t)b * a.vt_b + (int64_t)n * a.vt_n + i] = z;
+            else C[row * a.ldc + a.c0 + n] = z;
+        }
+}
+
+int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st)
+{
+    if (dtype == SF_BF16) return gemm_bf16(a, st);
+    if (a.B <= 0 || a.N <= 0) return SF_OK;
+    dim3 grid(ceil_div(a.L, FT) * a.B, ceil_div(a.N, FT));
+    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, a);
+    return SF_OK;
+}
+
+// One 64-lane wave per row; statistics in fp32; biased variance.
+template <class T>
+__global__ __launch_bounds__(256) void layernorm_kernel(const T *x, const T *__restrict__ gamma,
+                                                        const T *__restrict__ beta, float eps, int64_t rows,
+                                                        int d, T *y)      // y may alias x (row-wise in place)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const T *xr = x + row * d;
+    T *yr = y + row * d;
+    float s = 0.f;
+    for (int k = lane; k < d; k += 64) s += to_f32(xr[k]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mean = s / d;
+    float v = 0.f;
+    for (int k = lane; k < d; k += 64) { const float c = to_f32(xr[k]) - mean; v += c * c; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    const float inv = 1.0f / sqrtf(v / d + eps);
+    for (int k = lane; k < d; k += 64) {
+        float z = (to_f32(xr[k]) - mean) * inv;
+        if (gamma) z *= to_f32(gamma[k]);
+        if (beta) z += to_f32(beta[k]);
+        yr[k] = from_f32<T>(z);
+    }
+}
+
+void layernorm(int dtype, const void *x, const void *gamma, const void *beta, float eps,
+               int64_t rows, int d, void *y, hipStream_t st)
+{
+    if (rows <= 0) return;
+    dim3 grid((unsigned)((rows + 3) / 4));
+    if (dtype == SF_BF16)
+        hipLaunchKernelGGL(layernorm_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)x,
+                           (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, (__bf16 *)y);
+    else
+        hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, st, (const float *)x,
+                           (const float *)gamma, (const float *)beta, eps, rows, d, (float *)y);
+}
+
+}  // namespace sf

@@ -1,0 +1,91 @@
+// gate_scores_to_masks: SentryGate scores -> keep masks, kept-index lists and
+// the GQA-consistent K/V group keep set (Sec. 4.5 of the paper).
+// Integer / fp32-compare work only: results are exact.
+#include "common.hpp"
+#include "topk.hpp"
+
+namespace sf {
+
+constexpr int MASK_NT = 256;
+constexpr int MAX_LAYERS = 128;
+struct KeepCounts { int k[MAX_LAYERS]; };
+
+// One block per (layer, pattern): top-k of n scores.
+// GROUPS: additionally derive the kept K/V groups of the kept heads.
+template <bool GROUPS>
+__global__ __launch_bounds__(MASK_NT) void keep_topk_kernel(
+    const float *__restrict__ g, int n, int P, KeepCounts kc, uint8_t *__restrict__ mask,
+    int32_t *__restrict__ idx, int Hk, int32_t *__restrict__ group_idx,
+    int32_t *__restrict__ n_groups, int32_t *__restrict__ head_group)
+{
+    extern __shared__ uint32_t keys[];
+    __shared__ int red[MASK_NT / 64];
+    const int lp = blockIdx.x;
+    const int k = kc.k[lp / P];
+    const float *gs = g + (size_t)lp * n;
+    uint8_t *m = mask + (size_t)lp * n;
+    int32_t *ix = idx + (size_t)lp * n;
+
+    for (int i = threadIdx.x; i < n; i += MASK_NT) keys[i] = sortable_key(gs[i]);
+    __syncthreads();
+    block_topk<MASK_NT>(keys, n, k, red, [&](int i, bool kept, int pos) {
+        m[i] = kept ? 1 : 0;
+        if (kept) ix[pos] = i;
+    });
+    for (int i = k + threadIdx.x; i < n; i += MASK_NT) ix[i] = -1;
+
+    if (GROUPS) {
+        // K_keep = floor(H_keep / (Hq/Hk)); groups no kept head refers to are dropped.
+        __syncthreads();                     // ix[] written by other threads (global, same block)
+        __threadfence_block();
+        if (threadIdx.x == 0) {
+            const int per = n / Hk;
+            int32_t *gi = group_idx + (size_t)lp * Hk;
+            int32_t *hg = head_group + (size_t)lp * n;
+            int ng = 0;
+            for (int i = 0; i < k; ++i) {    // ix ascending => groups ascending
+                const int grp = ix[i] / per;
+                if (ng == 0 || gi[ng - 1] != grp) gi[ng++] = grp;
+                hg[i] = ng - 1;
+            }
+            for (int i = k; i < n; ++i) hg[i] = -1;
+            for (int r = ng; r < Hk; ++r) gi[r] = -1;
+            n_groups[lp] = ng;
+        }
+    }
+}
+
+}  // namespace sf
+
+using namespace sf;
+
+extern "C" int32_t sf_gate_scores_to_masks(const sf_desc *desc, const float *g_head,
+                                           const float *g_ffn, const int32_t *k_head_host,
+                                           const int32_t *k_ffn_host, uint8_t *head_mask,
+                                           uint8_t *ffn_mask, int32_t *head_idx, int32_t *ffn_idx,
+                                           int32_t *group_idx, int32_t *n_groups,
+                                           int32_t *head_group, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!g_head || !g_ffn || !k_head_host || !k_ffn_host || !head_mask || !ffn_mask || !head_idx ||
+        !ffn_idx || !group_idx || !n_groups || !head_group)
+        return fail(SF_ERR_INVALID_ARG, "gate_scores_to_masks: NULL argument");
+    if (D.Hq > 64 || D.F > 16384 || D.nl > MAX_LAYERS)
+        return fail(SF_ERR_SHAPE, "gate_scores_to_masks: needs Hq <= 64, d_ff <= 16384, n_layers <= %d",
+                    MAX_LAYERS);
+    KeepCounts kh{}, kf{};
+    for (int l = 0; l < D.nl; ++l) {
+        if (k_head_host[l] < 1 || k_head_host[l] > D.Hq || k_ffn_host[l] < 1 || k_ffn_host[l] > D.F)
+            return fail(SF_ERR_INVALID_ARG, "gate_scores_to_masks: keep count out of range at layer %d", l);
+        kh.k[l] = k_head_host[l];
+        kf.k[l] = k_ffn_host[l];
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int blocks = D.nl * D.P;
+    hipLaunchKernelGGL(keep_topk_kernel<true>, dim3(blocks), dim3(MASK_NT), D.Hq * sizeof(uint32_t), st,
+                       g_head, D.Hq, D.P, kh, head_mask, head_idx, D.Hk, group_idx, n_groups, head_group);
+    hipLaunchKernelGGL(keep_topk_kernel<false>, dim3(blocks), dim3(MASK_NT), D.F * sizeof(uint32_t), st,
+                       g_ffn, D.F, D.P, kf, ffn_mask, ffn_idx, 0, nullptr, nullptr, nullptr);
+    return check_launch("gate_scores_to_masks");
+}

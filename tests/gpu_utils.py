@@ -1,0 +1,102 @@
+"""Plumbing shared by the GPU parity tests, the smoke check and the benchmark:
+uploads a synthetic workload, runs plan construction (masks + compaction) and
+the encoder through the C-ABI binding.  No arithmetic of the method lives here.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from paper_2604_08971_amd import binding as sf
+from paper_2604_08971_amd import workloads as W
+
+
+def to_dev(a: Optional[np.ndarray], dtype: str, device="cuda") -> Optional[torch.Tensor]:
+    """fp32 host array (bf16-valued when dtype == 'bf16') -> device tensor of the path's dtype."""
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if t.dtype == torch.float32 and dtype == "bf16":
+        t = t.to(torch.bfloat16)          # exact: the values are bf16 numbers already
+    return t.to(device).contiguous()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    t = t.detach()
+    if t.dtype == torch.bfloat16:
+        t = t.to(torch.float32)
+    return t.cpu().numpy()
+
+
+def desc_for(wl: W.Workload, B: Optional[int] = None, U_override: int = -1, c: Optional[int] = None):
+    s = wl.spec
+    return sf.make_desc(B=wl.x.shape[0] if B is None else B, L=s.L, d_model=s.d, Hq=s.Hq, Hk=s.Hk, dh=s.dh,
+                        d_ff=s.F, n_layers=s.n_layers, P=wl.P,
+                        dtype=sf.SF_BF16 if s.dtype == "bf16" else sf.SF_F32, act=s.act,
+                        c_factor=s.c if c is None else c, U_override=U_override,
+                        final_ln=wl.final_ln is not None)
+
+
+class DeviceModel:
+    """A workload resident on the GPU: dense weights, plan (masks, compact layers), inputs."""
+
+    def __init__(self, wl: W.Workload, U_override: int = -1, device="cuda"):
+        s = wl.spec
+        self.wl, self.device = wl, device
+        self.desc = desc_for(wl, U_override=U_override)
+        dt = s.dtype
+        self.x = to_dev(wl.x, dt, device)
+        self.pattern_id = to_dev(wl.pattern_id, dt, device)
+        self.key_valid = to_dev(wl.key_valid, dt, device)
+        self.g_head = to_dev(wl.g_head, "f32", device)
+        self.g_ffn = to_dev(wl.g_ffn, "f32", device)
+        self.dense = [{k: to_dev(v, dt, device) for k, v in lw.items()} for lw in wl.layers]
+        self.final_ln = None if wl.final_ln is None else {k: to_dev(v, dt, device) for k, v in wl.final_ln.items()}
+        self.masks: Dict[str, torch.Tensor] = {}
+        self.layers: List[sf.CompactLayer] = []
+        self.ws: Optional[torch.Tensor] = None
+
+    def build_plan(self):
+        """a1 + a2: gate scores -> masks -> compacted weights, all on the GPU."""
+        wl = self.wl
+        self.masks = sf.gate_scores_to_masks(self.desc, self.g_head, self.g_ffn, wl.k_head, wl.k_ffn)
+        self.layers = [sf.compact_heads_channels(self.desc, l, self.dense[l], self.masks,
+                                                 int(wl.k_head[l]), int(wl.k_ffn[l]))
+                       for l in range(wl.spec.n_layers)]
+        return self
+
+    def forward(self, forced_sel=None, want_sel=False, want_score=False, out=None):
+        if self.ws is None:
+            self.ws = sf.workspace(sf.encoder_workspace_bytes(self.desc, self.layers), self.device)
+        return sf.encoder_forward(self.desc, self.layers, self.x, self.pattern_id, self.key_valid,
+                                  self.final_ln, forced_sel=forced_sel, want_sel=want_sel,
+                                  want_score=want_score, out=out, ws=self.ws)
+
+
+def selection_report(score_oracle: np.ndarray, sel_gpu: np.ndarray, sel_oracle: np.ndarray,
+                     valid: Optional[np.ndarray], eps_rel: float):
+    """Margin check of one (sample, head): the GPU's active set is acceptable iff
+    every chosen query scores >= tau - eps and every allowed query left out
+    scores <= tau + eps, tau being the oracle's U-th largest score.
+    Returns (ok, differs)."""
+    L = score_oracle.shape[0]
+    chosen = sel_gpu[sel_gpu >= 0]
+    ref = sel_oracle[sel_oracle >= 0]
+    if len(chosen) != len(ref) or len(np.unique(chosen)) != len(chosen):
+        return False, True
+    if len(ref) == 0:
+        return True, False
+    if not np.all(np.diff(chosen) > 0):
+        return False, True
+    allowed = np.ones(L, bool) if valid is None else valid.astype(bool)
+    if not allowed[chosen].all():
+        return False, True
+    tau = np.min(score_oracle[ref])
+    eps = eps_rel * max(1.0, abs(tau))
+    mask = np.zeros(L, bool)
+    mask[chosen] = True
+    ok = bool(np.all(score_oracle[chosen] >= tau - eps) and
+              np.all(score_oracle[allowed & ~mask] <= tau + eps))
+    return ok, not np.array_equal(chosen, ref)

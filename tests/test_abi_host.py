@@ -1,0 +1,85 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the
+public header declares, computes U like the paper's worked example, and turns
+bad arguments into error codes before touching the GPU."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_08971_amd import binding as sf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "sentryfuse.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(sf_[a-z_0-9]+)\s*\(", hdr)))
+    assert "sf_encoder_forward" in declared and "sf_sparse_gqa_forward" in declared
+    L = sf.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(sf.EXPORTS) == declared
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(sf.SfDesc) == 17 * 4
+    assert C.sizeof(sf.SfStrides) == 24
+    assert C.sizeof(sf.SfDenseLayer) == 16 * 8
+    assert C.sizeof(sf.SfCompactLayer) == 8 + 14 * 8
+
+
+def test_num_active_matches_paper_example():
+    # Sec. 4.4: T = 128, c = 5 gives U of about 25 (natural log)
+    assert sf.num_active(sf.make_desc(1, 128, 64, 8, 2, 8, 64)) == 25
+    for L, U in ((48, 20), (384, 30), (480, 35), (512, 35), (4096, 45), (1, 0), (3, 3)):
+        assert sf.num_active(sf.make_desc(1, L, 64, 8, 2, 8, 64)) == U
+    assert sf.num_active(sf.make_desc(1, 128, 64, 8, 2, 8, 64, U_override=500)) == 128
+    assert sf.num_active(sf.make_desc(1, 128, 64, 8, 2, 8, 64, U_override=0)) == 0
+    assert sf.num_active(sf.make_desc(1, 128, 64, 8, 2, 8, 64, c_factor=2)) == 10
+    assert sf.ffn_padded(sf.make_desc(1, 128, 64, 8, 2, 8, 3072), 2150) == 2176
+    assert sf.ffn_padded(sf.make_desc(1, 128, 64, 8, 2, 8, 3072, ffn_pad=128), 2150) == 2176
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(Hq=8, Hk=3), -1), (dict(B=0), -1), (dict(L=0), -1), (dict(dtype=7), -3), (dict(act=9), -3),
+    (dict(ffn_pad=48), -2), (dict(d_model=60, dtype=sf.SF_BF16), -2), (dict(dh=12, dtype=sf.SF_BF16), -2),
+])
+def test_bad_descriptor_is_rejected(kw, code):
+    base = dict(B=1, L=16, d_model=64, Hq=8, Hk=2, dh=8, d_ff=64, dtype=sf.SF_F32)
+    base.update(kw)
+    d = sf.make_desc(**base)
+    assert sf.lib().sf_num_active(C.byref(d)) == code
+    assert len(sf.lib().sf_last_error()) > 0
+    d2 = sf.make_desc(1, 16, 64, 8, 2, 8, 64)
+    d2.struct_size = 12
+    assert sf.lib().sf_num_active(C.byref(d2)) == -1
+
+
+def test_null_and_range_errors_before_any_launch():
+    L = sf.lib()
+    d = sf.make_desc(2, 16, 64, 8, 2, 8, 64, dtype=sf.SF_F32)
+    assert L.sf_gate_scores_to_masks(C.byref(d), *([None] * 12)) == -1
+    assert L.sf_encoder_forward(C.byref(d), None, None, None, None, None, None, None, None, None, None,
+                                None, 0, None) == -1
+    z = sf.SfStrides(0, 0, 0)
+    assert L.sf_sparse_gqa_forward(C.byref(d), 4, 2, None, z, None, z, None, z, 0, None, None, None, None,
+                                   None, 32, None, None, None, 0, None) == -1
+    assert L.sf_sparse_gqa_forward(C.byref(d), 0, 2, None, z, None, z, None, z, 0, None, None, None, None,
+                                   None, 32, None, None, None, 0, None) == -1
+    assert L.sf_pruned_ffn_forward(C.byref(d), None, None, None, 1, 1, None, None, 0, None) == -1
+    assert L.sf_sparse_gqa_workspace_bytes(C.byref(d), 4, 2) > 0
+    assert L.sf_pruned_ffn_workspace_bytes(C.byref(d), 0) == 0
+    cl = sf.SfCompactLayer()
+    cl.k_head, cl.k_ffn = 9, 10          # more heads than the model has
+    assert L.sf_encoder_workspace_bytes(C.byref(d), C.byref(cl)) == 0
+    cl.k_head = 4
+    assert L.sf_encoder_workspace_bytes(C.byref(d), C.byref(cl)) > 0
+    # host-side keep counts out of range
+    kh, kf = (C.c_int32 * 1)(9), (C.c_int32 * 1)(3)
+    one = C.c_void_p(256)                 # never dereferenced: the count check comes first
+    assert L.sf_gate_scores_to_masks(C.byref(d), one, one, C.cast(kh, C.c_void_p), C.cast(kf, C.c_void_p),
+                                     one, one, one, one, one, one, one, None) == -1

@@ -1,0 +1,407 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Bar: masks, kept-index lists and compacted weights bit-exact; outputs within
+max |a-b| / max(1,|b|) <= 1e-5 (fp32) or 2e-2 (bf16 inputs, fp32 accumulate).
+The active-query choice is a floating-point decision: the GPU's choice must be
+within a margin of the oracle's threshold score, and outputs are compared with
+the oracle re-run on the GPU's choice.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cpu_oracle as orc
+from paper_2604_08971_amd import binding as sf
+from paper_2604_08971_amd import workloads as W
+from gpu_utils import DeviceModel, selection_report, to_dev, to_host
+from helpers import compact_packs, compact_weights, err_metric, oracle_masks
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+EPS_SEL_OP = {"f32": 1e-5, "bf16": 1e-4}       # sparse_gqa_forward on identical inputs
+EPS_SEL_ENC = {"f32": 1e-5, "bf16": 2e-2}      # inside the encoder (inputs differ by bf16 rounding)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ a1: masks
+MASK_KEYS = ("head_mask", "ffn_mask", "head_idx", "ffn_idx", "group_idx", "n_groups", "head_group")
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_masks_bit_exact_on_configs(name):
+    _say(f"masks {name}")
+    wl = W.make_workload(W.CONFIGS[name], with_x=False)
+    ref = oracle_masks(wl)
+    desc = sf.make_desc(1, wl.spec.L, wl.spec.d, wl.spec.Hq, wl.spec.Hk, wl.spec.dh, wl.spec.F,
+                        wl.spec.n_layers, wl.P, sf.SF_F32)
+    got = sf.gate_scores_to_masks(desc, to_dev(wl.g_head, "f32"), to_dev(wl.g_ffn, "f32"), wl.k_head, wl.k_ffn)
+    torch.cuda.synchronize()
+    for k in MASK_KEYS:
+        assert np.array_equal(to_host(got[k]), ref[k]), k
+
+
+@pytest.mark.parametrize("Hq,Hk,F,kh,kf", [(8, 2, 257, 3, 100), (64, 8, 16384, 17, 9000), (1, 1, 1, 1, 1),
+                                           (12, 4, 3000, 12, 3000), (6, 3, 33, 1, 1)])
+def test_masks_ties_and_edges(Hq, Hk, F, kh, kf):
+    _say(f"masks ties Hq={Hq} F={F}")
+    rng = np.random.default_rng(Hq * 1000 + F)
+    nl, P = 2, 3
+    g_head = (rng.integers(0, 3, (nl, P, Hq)) / 2).astype(np.float32)            # heavy ties
+    g_ffn = (rng.integers(0, 7, (nl, P, F)) / 8 - 0.25).astype(np.float32)       # ties, negatives, +-0
+    g_ffn[0, 0, : F // 2] = -0.0
+    ref = orc.gate_scores_to_masks(g_head, g_ffn, [kh, Hq], [kf, F], Hk)
+    desc = sf.make_desc(1, 8, 8, Hq, Hk, 8, F, nl, P, sf.SF_F32)
+    got = sf.gate_scores_to_masks(desc, to_dev(g_head, "f32"), to_dev(g_ffn, "f32"), [kh, Hq], [kf, F])
+    torch.cuda.synchronize()
+    for k in MASK_KEYS:
+        assert np.array_equal(to_host(got[k]), ref[k]), k
+
+
+# ------------------------------------------------------------- a2: compaction
+def _check_compaction(wl, dm, ref_masks):
+    s = wl.spec
+    for l in range(s.n_layers):
+        cl = dm.layers[l]
+        kh, kf, Fp = int(wl.k_head[l]), int(wl.k_ffn[l]), cl.Fp
+        assert Fp % 64 == 0 and Fp >= kf and Fp - kf < 64
+        for p in range(wl.P):
+            c, _, ng, _ = compact_weights(wl, ref_masks, l, p)
+            dh, Hk, d = s.dh, s.Hk, s.d
+            Wqkv = to_host(cl.Wqkv[p]); bqkv = to_host(cl.bqkv[p])
+            nq = kh * dh
+            assert np.array_equal(Wqkv[:nq], c["Wq"]) and np.array_equal(bqkv[:nq], c["bq"])
+            assert np.array_equal(Wqkv[nq:nq + ng * dh], c["Wk"]) and np.array_equal(bqkv[nq:nq + ng * dh], c["bk"])
+            assert not Wqkv[nq + ng * dh: nq + Hk * dh].any() and not bqkv[nq + ng * dh: nq + Hk * dh].any()
+            v0 = nq + Hk * dh
+            assert np.array_equal(Wqkv[v0:v0 + ng * dh], c["Wv"]) and np.array_equal(bqkv[v0:v0 + ng * dh], c["bv"])
+            assert not Wqkv[v0 + ng * dh:].any() and not bqkv[v0 + ng * dh:].any()
+            assert np.array_equal(to_host(cl.WoT[p]), c["Wo"].T)
+            W1 = to_host(cl.W1[p]); b1 = to_host(cl.b1[p]); W2T = to_host(cl.W2T[p])
+            assert np.array_equal(W1[:kf], c["W1"]) and not W1[kf:].any()
+            assert np.array_equal(b1[:kf], c["b1"]) and not b1[kf:].any()
+            assert np.array_equal(W2T[:, :kf], c["W2"].T) and not W2T[:, kf:].any()
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_compaction_bit_exact_on_configs(name):
+    _say(f"compaction {name}")
+    wl = W.make_workload(W.CONFIGS[name], with_x=False)
+    ref = oracle_masks(wl)
+    # the numpy slicing used as reference agrees with the oracle's own row gather
+    c, kh, ng, _ = compact_weights(wl, ref, 0, 0)
+    assert np.array_equal(orc.gather_rows(wl.layers[0]["W1"], ref["ffn_idx"][0, 0, :wl.k_ffn[0]]), c["W1"])
+    assert np.array_equal(orc.gather_rows(wl.layers[0]["Wq"], ref["head_idx"][0, 0, :kh], block=wl.spec.dh), c["Wq"])
+    wl.x = np.zeros((1, wl.spec.L, wl.spec.d), np.float32)
+    wl.pattern_id = wl.pattern_id[:1]
+    if wl.key_valid is not None:
+        wl.key_valid = wl.key_valid[:1]
+    dm = DeviceModel(wl).build_plan()
+    torch.cuda.synchronize()
+    _check_compaction(wl, dm, ref)
+
+
+def test_compaction_keep_all_is_identity():
+    spec = W.small_spec(dtype="bf16", d=64, dh=32, Hq=4, Hk=2, F=128, head_keep=1.0, ffn_keep=1.0, nl=1)
+    wl = W.make_workload(spec)
+    dm = DeviceModel(wl).build_plan()
+    torch.cuda.synchronize()
+    cl = dm.layers[0]
+    for p in range(wl.P):
+        w = wl.layers[0]
+        assert np.array_equal(to_host(cl.Wqkv[p]), np.concatenate([w["Wq"], w["Wk"], w["Wv"]]))
+        assert np.array_equal(to_host(cl.W1[p]), w["W1"]) and np.array_equal(to_host(cl.W2T[p]), w["W2"].T)
+        assert np.array_equal(to_host(cl.WoT[p]), w["Wo"].T)
+
+
+# -------------------------------------------------- a4-a7: sparse_gqa_forward
+def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=False, forced=False,
+              v_transposed=False, strided=False):
+    rng = np.random.default_rng(seed)
+    q = W.to_bf16_values if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    Q = q(rng.standard_normal((B, nH, L, dh)).astype(np.float32))
+    K = q(rng.standard_normal((B, nG, L, dh)).astype(np.float32))
+    V = q(rng.standard_normal((B, nG, L, dh)).astype(np.float32))
+    n_maps = 3 if per_sample_map else 1
+    hg = rng.integers(0, nG, (n_maps, nH)).astype(np.int32)
+    hg[:, 0] = 0
+    pid = rng.integers(0, n_maps, B).astype(np.int32) if per_sample_map else None
+    kv = None
+    if mask:
+        kv = (rng.random((B, L)) < 0.7).astype(np.uint8)
+        kv[:, L // 3: L // 3 + 40] = 0          # a whole disallowed stretch (a dropped modality)
+        kv[:, 0] = 1
+        if B > 1:
+            kv[1] = 0
+            kv[1, [1, L // 2, L - 1]] = 1        # fewer allowed queries than U
+    desc = sf.make_desc(B, L, 64, nH, nG, dh, 64, dtype=sf.SF_BF16 if dtype == "bf16" else sf.SF_F32,
+                        U_override=U_override)
+    U = sf.num_active(desc)
+    hgb = hg[pid] if pid is not None else None
+    fs = None
+    if forced:
+        fs = np.full((B, nH, U), -1, np.int32)
+        for b in range(B):
+            for h in range(nH):
+                n = int(rng.integers(0, U + 1))
+                fs[b, h, :n] = np.sort(rng.choice(L, n, replace=False))
+    # device tensors (optionally as strided views of a token-major buffer, V transposed)
+    if strided:
+        buf = torch.zeros((B, L, (nH + 2 * nG) * dh), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32,
+                          device="cuda")
+        buf[:, :, :nH * dh] = to_dev(Q, dtype).permute(0, 2, 1, 3).reshape(B, L, nH * dh)
+        buf[:, :, nH * dh:(nH + nG) * dh] = to_dev(K, dtype).permute(0, 2, 1, 3).reshape(B, L, nG * dh)
+        buf[:, :, (nH + nG) * dh:] = to_dev(V, dtype).permute(0, 2, 1, 3).reshape(B, L, nG * dh)
+        Qd = buf[:, :, :nH * dh].view(B, L, nH, dh).permute(0, 2, 1, 3)
+        Kd = buf[:, :, nH * dh:(nH + nG) * dh].view(B, L, nG, dh).permute(0, 2, 1, 3)
+        Vd = buf[:, :, (nH + nG) * dh:].view(B, L, nG, dh).permute(0, 2, 1, 3)
+    else:
+        Qd, Kd, Vd = to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype)
+    if v_transposed:
+        Lp = (L + 7) // 8 * 8
+        vt = torch.full((B, nG, dh, Lp), float("nan"), dtype=Vd.dtype, device="cuda")   # padding must not leak
+        vt[..., :L] = to_dev(V, dtype).permute(0, 1, 3, 2)
+        Vd = vt
+    O, sel, score = sf.sparse_gqa_forward(desc, Qd, Kd, Vd, to_dev(hg, dtype), to_dev(pid, dtype),
+                                          to_dev(kv, dtype), to_dev(fs, dtype), v_transposed=v_transposed,
+                                          want_sel=True, want_score=True)
+    torch.cuda.synchronize()
+    O, sel, score = to_host(O), to_host(sel), to_host(score)
+
+    bf = dtype == "bf16"
+    _, M_ref, sel_ref, _ = orc.sparse_gqa(Q, K, V, hg[0], U, kv, fs, bf, hgb)
+    n_diff = 0
+    if not forced:
+        for b in range(B):
+            for h in range(nH):
+                ok, diff = selection_report(M_ref[b, h], sel[b, h], sel_ref[b, h],
+                                            None if kv is None else kv[b], EPS_SEL_OP[dtype])
+                assert ok, (b, h, sel[b, h], sel_ref[b, h])
+                n_diff += diff
+        if U < L and U > 0:
+            fin = np.isfinite(M_ref)
+            assert np.array_equal(np.isneginf(score), np.isneginf(M_ref))
+            assert np.max(np.abs(score[fin] - M_ref[fin]) / np.maximum(1, np.abs(M_ref[fin]))) < \
+                (1e-5 if dtype == "f32" else 1e-4)
+    else:
+        assert np.array_equal(sel, sel_ref)
+    O_ref, _, _, _ = orc.sparse_gqa(Q, K, V, hg[0], U, kv, sel, bf, hgb)
+    e = err_metric(O, O_ref)
+    assert np.isfinite(O).all()
+    assert e <= TOL[dtype], e
+    assert n_diff <= max(1, (B * nH) // 50), n_diff
+    return e
+
+
+@pytest.mark.parametrize("dtype,B,nH,nG,L,dh,Uo,mask", [
+    ("f32", 2, 4, 2, 48, 16, -1, True),            # C1-shaped
+    ("f32", 3, 3, 3, 77, 8, -1, False),            # ragged, groups = heads
+    ("f32", 2, 2, 1, 130, 20, 0, True),            # U = 0: every row is the context vector
+    ("f32", 2, 4, 2, 65, 12, 65, True),            # dense pattern with a key mask
+    ("bf16", 2, 6, 2, 384, 32, -1, True),          # C2-shaped (dh 32)
+    ("bf16", 3, 4, 4, 480, 64, -1, True),          # C3-shaped
+    ("bf16", 2, 7, 2, 512, 64, -1, False),         # C4-shaped, 3+4 heads per group
+    ("bf16", 1, 8, 4, 4096, 64, -1, False),        # C5-shaped: key splits
+    ("bf16", 2, 3, 1, 203, 64, -1, True),          # ragged L, one group
+    ("bf16", 2, 4, 2, 333, 128, -1, True),         # dh 128
+    ("bf16", 2, 4, 2, 200, 64, 200, False),        # dense pattern (U = L): flash GQA
+    ("bf16", 2, 4, 2, 300, 32, 300, True),         # dense pattern with a key mask
+    ("bf16", 2, 2, 2, 96, 64, 0, True),            # U = 0
+    ("bf16", 1, 2, 1, 40, 64, 7, False),           # fewer rows than one MFMA block
+])
+def test_sparse_gqa_parity(dtype, B, nH, nG, L, dh, Uo, mask):
+    _say(f"sgqa {dtype} B={B} nH={nH} nG={nG} L={L} dh={dh} U={Uo} mask={mask}")
+    _gqa_case(dtype, B, nH, nG, L, dh, Uo, mask, seed=L * 7 + dh)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sparse_gqa_variants(dtype):
+    dh = 16 if dtype == "f32" else 64
+    _say(f"sgqa variants {dtype}")
+    _gqa_case(dtype, 4, 5, 3, 150, dh, -1, True, seed=1, per_sample_map=True)
+    _gqa_case(dtype, 2, 4, 2, 150, dh, -1, True, seed=2, forced=True)
+    _gqa_case(dtype, 2, 4, 2, 150, dh, -1, True, seed=3, strided=True)
+    _gqa_case(dtype, 2, 4, 2, 150, dh, -1, False, seed=4, v_transposed=True)
+    _gqa_case(dtype, 2, 4, 2, 1150, dh, -1, True, seed=5, v_transposed=True, strided=True)
+
+
+def test_sparse_gqa_dense_equals_library_attention():
+    """groups = heads, every row active: the kernel is plain multi-head attention."""
+    torch.manual_seed(0)
+    B, H, L, dh = 2, 4, 256, 64
+    Q, K, V = (torch.randn(B, H, L, dh, device="cuda").to(torch.bfloat16) for _ in range(3))
+    desc = sf.make_desc(B, L, 64, H, H, dh, 64, dtype=sf.SF_BF16, U_override=L)
+    O, _, _ = sf.sparse_gqa_forward(desc, Q, K, V, torch.arange(H, dtype=torch.int32, device="cuda"))
+    ref = torch.nn.functional.scaled_dot_product_attention(Q.cpu().double(), K.cpu().double(), V.cpu().double())
+    ref = ref.permute(0, 2, 1, 3).reshape(B, L, H * dh).numpy()
+    assert err_metric(to_host(O), ref) <= 2e-2
+
+
+def test_sparse_gqa_is_deterministic():
+    rng = np.random.default_rng(0)
+    B, nH, nG, L, dh = 2, 6, 2, 1024, 64
+    Q, K, V = (to_dev(W.to_bf16_values(rng.standard_normal(s).astype(np.float32)), "bf16")
+               for s in ((B, nH, L, dh), (B, nG, L, dh), (B, nG, L, dh)))
+    hg = torch.tensor([[0, 0, 0, 1, 1, 1]], dtype=torch.int32, device="cuda")
+    desc = sf.make_desc(B, L, 64, nH, nG, dh, 64, dtype=sf.SF_BF16)
+    a = sf.sparse_gqa_forward(desc, Q, K, V, hg, want_score=True)
+    b = sf.sparse_gqa_forward(desc, Q, K, V, hg, want_score=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+# ------------------------------------------------------------------- a9: FFN
+@pytest.mark.parametrize("dtype,act,B,L,d,F,keep", [
+    ("f32", 0, 2, 48, 64, 256, 0.5), ("f32", 1, 3, 37, 40, 100, 0.33),
+    ("bf16", 0, 4, 384, 256, 1024, 0.6), ("bf16", 1, 3, 203, 128, 520, 0.71), ("bf16", 0, 2, 4096, 768, 3072, 0.7),
+])
+def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
+    _say(f"ffn {dtype} act={act} B={B} L={L} d={d} F={F}")
+    spec = W.small_spec(dtype=dtype, B=B, seg=(L - 1,), extra=1, d=d, Hq=2, Hk=1, dh=32, F=F, nl=1,
+                        head_keep=1.0, ffn_keep=keep, dropout="none", final_ln=False, act=act, seed=L + F)
+    wl = W.make_workload(spec)
+    # three patterns with different channel sets
+    rng = np.random.default_rng(5)
+    wl.pattern_bits = np.arange(3)
+    wl.pattern_id = rng.integers(0, 3, B).astype(np.int32)
+    wl.g_head = np.repeat(wl.g_head, 3, axis=1)
+    wl.g_ffn = rng.random((1, 3, F), dtype=np.float32)
+    masks = oracle_masks(wl)
+    dm = DeviceModel(wl).build_plan()
+    for pre_ln, res in ((True, True), (False, False)):
+        Y = sf.pruned_ffn_forward(dm.desc, dm.layers[0], dm.x.view(B * L, d), dm.pattern_id, pre_ln, res)
+        torch.cuda.synchronize()
+        Y = to_host(Y).reshape(B, L, d)
+        packs = compact_packs(wl, masks)
+        for b in range(B):
+            ref = orc.pruned_ffn(packs[0][wl.pattern_id[b]], wl.x[b], act=act, pre_ln=pre_ln,
+                                 add_residual=res, bf16=dtype == "bf16")
+            e = err_metric(Y[b], ref)
+            assert e <= TOL[dtype], (b, pre_ln, e)
+
+
+# ------------------------------------------------------------ a10: encoder
+def _encoder_parity(wl, samples=None, U_override=-1, max_diff_frac=0.02):
+    s = wl.spec
+    bf = s.dtype == "bf16"
+    dm = DeviceModel(wl, U_override=U_override).build_plan()
+    U = sf.num_active(dm.desc)
+    ref_masks = oracle_masks(wl)
+    for k in MASK_KEYS:
+        assert np.array_equal(to_host(dm.masks[k]), ref_masks[k]), k
+    Y, sel, score = dm.forward(want_sel=True, want_score=False)
+    torch.cuda.synchronize()
+    Y, sel = to_host(Y), to_host(sel)
+    assert np.isfinite(Y).all()
+    B = wl.x.shape[0]
+    samples = list(range(B)) if samples is None else samples
+    packs = compact_packs(wl, ref_masks)
+    kv = None if wl.key_valid is None else wl.key_valid[samples]
+    # oracle with its own choice: gives the reference scores / choices for the margin check
+    y_own, sel_own, score_own = orc.encoder_forward(wl.x[samples], packs, U, wl.pattern_id[samples], kv,
+                                                    act=s.act, final_ln=wl.final_ln, bf16=bf, want_score=True)
+    # oracle forced to the GPU's choice, layer by layer: the output reference
+    y_ref, sel_chk, score_f = orc.encoder_forward(wl.x[samples], packs, U, wl.pattern_id[samples], kv, act=s.act,
+                                                  forced_sel=sel[:, samples], final_ln=wl.final_ln, bf16=bf,
+                                                  want_score=True)
+    n_diff = n_tot = 0
+    if 0 < U < s.L:
+        for l in range(s.n_layers):
+            for bi, b in enumerate(samples):
+                for h in range(int(wl.k_head[l])):
+                    # scores of the forced run are the ones this layer's GPU input corresponds to
+                    m = score_f[l, bi, h]
+                    ref_sel = np.sort(np.lexsort((np.arange(s.L), -m.astype(np.float32)))[:np.sum(sel[l, b, h] >= 0)])
+                    ok, diff = selection_report(m, sel[l, b, h], ref_sel, None if kv is None else kv[bi],
+                                                EPS_SEL_ENC[s.dtype])
+                    assert ok, (l, b, h)
+                    n_diff += diff
+                    n_tot += 1
+    e = err_metric(Y[samples], y_ref)
+    _say(f"   encoder {s.name}: err {e:.3e}, selections differing {n_diff}/{n_tot}, "
+         f"err vs oracle's own choice {err_metric(Y[samples], y_own):.3e}")
+    assert e <= TOL[s.dtype], e
+    assert n_diff <= max(1, int(max_diff_frac * n_tot)), (n_diff, n_tot)
+    if s.dtype == "f32":
+        assert n_diff == 0
+    return e
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32"),
+    dict(dtype="f32", act=1, dropout="upto:2", B=5, c=1),
+    dict(dtype="f32", dropout="none", Hq=6, Hk=3, head_keep=0.34, nl=3),
+    dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=4),
+    dict(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=300, seg=(100, 33, 64), extra=3, B=3, nl=3,
+         head_keep=(0.4, 0.9), act=1, c=3),
+])
+def test_encoder_parity_small(kw):
+    _say(f"encoder small {kw}")
+    _encoder_parity(W.make_workload(W.small_spec(**kw)))
+
+
+def test_encoder_parity_C1_full():
+    _say("encoder C1")
+    wl = W.make_workload(W.CONFIGS["C1"])
+    _encoder_parity(wl)
+    for kh in (1, 2, 3, 4):                      # the config names no head keep ratio: sweep it
+        wl2 = W.make_workload(W.CONFIGS["C1"])
+        wl2.k_head[:] = kh
+        _encoder_parity(wl2)
+
+
+def test_encoder_parity_C2_full():
+    _say("encoder C2")
+    _encoder_parity(W.make_workload(W.CONFIGS["C2"]))
+
+
+@pytest.mark.parametrize("name,n_samples", [("C3", 6), ("C4", 3), ("C5", 1)])
+def test_encoder_parity_full_size_sampled(name, n_samples):
+    """Full-size launch (the configuration the benchmark times); the oracle
+    recomputes a few whole samples, which are independent of the others."""
+    _say(f"encoder {name} (full batch on the GPU, {n_samples} samples through the oracle)")
+    wl = W.make_workload(W.CONFIGS[name])
+    B = wl.x.shape[0]
+    rng = np.random.default_rng(1)
+    samples = sorted(rng.choice(B, n_samples, replace=False).tolist())
+    if wl.P > 1:                                 # make sure more than one pattern is checked
+        pats = np.unique(wl.pattern_id)
+        samples = sorted(set(samples[: max(1, n_samples - 2)]) |
+                         {int(np.flatnonzero(wl.pattern_id == pats[0])[0]), int(np.flatnonzero(wl.pattern_id == pats[-1])[0])})
+    _encoder_parity(wl, samples=samples)
+
+
+def test_encoder_dense_pattern_and_U0():
+    _say("encoder dense pattern / U=0")
+    wl = W.make_workload(W.small_spec(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=3))
+    _encoder_parity(wl, U_override=wl.spec.L)
+    _encoder_parity(wl, U_override=0)
+    wl = W.make_workload(W.small_spec(dtype="f32", B=2))
+    _encoder_parity(wl, U_override=wl.spec.L)
+    _encoder_parity(wl, U_override=0)
+
+
+def test_encoder_is_deterministic_and_reusable():
+    wl = W.make_workload(W.small_spec(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=4))
+    dm = DeviceModel(wl).build_plan()
+    y1, s1, _ = dm.forward(want_sel=True)
+    y2, s2, _ = dm.forward(want_sel=True)          # same workspace, second call
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2) and torch.equal(s1, s2)
+
+
+def test_encoder_rejects_small_workspace():
+    wl = W.make_workload(W.small_spec(dtype="f32", B=2))
+    dm = DeviceModel(wl).build_plan()
+    with pytest.raises(sf.SentryFuseError, match="workspace"):
+        sf.encoder_forward(dm.desc, dm.layers, dm.x, dm.pattern_id, dm.key_valid, dm.final_ln,
+                           ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
