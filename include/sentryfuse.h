@@ -24,7 +24,9 @@
  *    LayerNorm parameters) are bf16; contractions run on bf16 MFMA with fp32
  *    accumulation; stored tensors are rounded to bf16 (nearest even) at: the
  *    LayerNorm output, Q, K, V, the attention output, the FFN hidden after
- *    the activation, and the residual stream after each add.
+ *    the activation, and the output Y of each entry point.  Inside
+ *    sf_encoder_forward the residual stream between layers is an fp32
+ *    accumulation and is not rounded.
  *  - Gate scores, sparsity scores and all index tensors are fp32 / int32 /
  *    uint8 regardless of dtype.
  */

@@ -337,9 +337,11 @@ static double activation(double z, int32_t act)
     return z > 0.0 ? z : 0.0;                                      /* ReLU */
 }
 
-void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t act,
-                    double eps, int32_t pre_ln, int32_t add_residual, int32_t bf16,
-                    double *y)
+/* bf16: rounding of the stored intermediates (LN output, hidden);
+ * out_bf16: rounding of y itself */
+static void ffn_core(const orc_layer *w, const double *x, int64_t rows, int32_t act,
+                     double eps, int32_t pre_ln, int32_t add_residual, int32_t bf16,
+                     int32_t out_bf16, double *y)
 {
     const int32_t d = w->d, F = w->F;
     double *xn = (double *)malloc(sizeof(double) * (size_t)rows * d);
@@ -369,10 +371,17 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
             }
             if (w->b2) acc += w->b2[n];
             if (add_residual) acc += x[r * d + n];
-            y[r * d + n] = rnd(acc, bf16);
+            y[r * d + n] = rnd(acc, out_bf16);
         }
     }
     free(hid); free(xn);
+}
+
+void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t act,
+                    double eps, int32_t pre_ln, int32_t add_residual, int32_t bf16,
+                    double *y)
+{
+    ffn_core(w, x, rows, act, eps, pre_ln, add_residual, bf16, bf16, y);
 }
 
 /* ---- encoder stack ------------------------------------------------------- */
@@ -451,20 +460,23 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                                    w->Wo[((int64_t)h * dh + e) * d + n];
                     }
                     if (w->bo) acc += w->bo[n];
-                    xn[(int64_t)i * d + n] = rnd(cur[(int64_t)i * d + n] + acc, bf16);
+                    xn[(int64_t)i * d + n] = cur[(int64_t)i * d + n] + acc;   /* stream stays unrounded */
                 }
             }
             memcpy(cur, xn, sizeof(double) * (size_t)Ld);
 
             /* x <- x + FFN(LN2(x)) */
-            orc_pruned_ffn(w, cur, L, act, eps, 1, 1, bf16, xn);
+            ffn_core(w, cur, L, act, eps, 1, 1, bf16, 0, xn);
             memcpy(cur, xn, sizeof(double) * (size_t)Ld);
 
             free(O); free(Vg); free(Kg); free(Q);
         }
         if (rc) break;
-        if (final_g || final_b) orc_layernorm(cur, L, d, final_g, final_b, eps, bf16, y + b * Ld);
-        else memcpy(y + b * Ld, cur, sizeof(double) * (size_t)Ld);
+        if (final_g || final_b) {
+            orc_layernorm(cur, L, d, final_g, final_b, eps, bf16, y + b * Ld);
+        } else {
+            for (int64_t t = 0; t < Ld; ++t) y[b * Ld + t] = rnd(cur[t], bf16);   /* the output is a stored tensor */
+        }
     }
     free(xn); free(cur);
     return rc;

@@ -131,7 +131,11 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
  *   sel_out    [nl,B,nHmax,U] or NULL, score_out [nl,B,nHmax,L] or NULL
  *   final_g/final_b [d] or NULL (no final LN)
  * bf16 rounding points (bf16 != 0): LN outputs, Q, K, V, the attention output
- * O, the FFN hidden after the activation, and x after each residual add.
+ * O, the FFN hidden after the activation, and the final output y.  The
+ * residual stream x itself is an accumulation and is NOT rounded between
+ * layers ("bf16 inputs, fp32 accumulate"): with a bf16-stored stream two
+ * equally valid implementations drift apart by several bf16 ulps over a few
+ * layers, more than the 2e-2 parity bar.
  * returns 0 or -1.
  */
 int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,

@@ -75,13 +75,16 @@ static FfnWs ffn_ws(const Dims &D, int Fp, bool pre_ln, void *ws)
     return w;
 }
 
-static int32_t ffn_forward(const Dims &D, const sf_compact_layer &ly, const void *X, const int32_t *pattern_id,
-                           bool pre_ln, bool add_residual, void *Y, void *xn, void *hid, hipStream_t st)
+// x_f32 / y_f32: X / Y hold fp32 although the model dtype is bf16 (the
+// encoder's residual stream).  With x_f32, pre_ln is required (the GEMM reads bf16).
+static int32_t ffn_forward(const Dims &D, const sf_compact_layer &ly, const void *X, bool x_f32,
+                           const int32_t *pattern_id, bool pre_ln, bool add_residual, void *Y, bool y_f32,
+                           void *xn, void *hid, hipStream_t st)
 {
     const int Fp = (int)align_up(ly.k_ffn, D.ffn_pad);
     const void *in = X;
     if (pre_ln) {
-        layernorm(D.dtype, X, ly.ln2_g, ly.ln2_b, D.eps, (int64_t)D.B * D.L, D.d, xn, st);
+        layernorm(D.dtype, x_f32, X, ly.ln2_g, ly.ln2_b, D.eps, (int64_t)D.B * D.L, D.d, xn, st);
         in = xn;
     }
     GemmArgs g{};
@@ -95,14 +98,14 @@ static int32_t ffn_forward(const Dims &D, const sf_compact_layer &ly, const void
     h.A = hid; h.lda = Fp; h.W = ly.W2T; h.ldw = Fp; h.w_pstride = (int64_t)D.d * Fp;
     h.bias = ly.b2; h.bias_pstride = 0; h.pattern_id = pattern_id;
     h.B = D.B; h.L = D.L; h.N = D.d; h.K = Fp; h.epi = EPI_ROWMAJOR; h.act = ACT_NONE;
-    h.R = add_residual ? X : nullptr; h.ldr = D.d;
-    h.C = Y; h.ldc = D.d;
+    h.R = add_residual ? X : nullptr; h.ldr = D.d; h.r_f32 = x_f32;
+    h.C = Y; h.ldc = D.d; h.c_f32 = y_f32;
     return gemm(D.dtype, h, st);
 }
 
 // ---- encoder ----------------------------------------------------------------------
 struct EncWs {
-    void *xn, *qkv, *vt, *att, *x1, *hid, *attn_ws;
+    void *xn, *qkv, *vt, *att, *x1, *x2, *hid, *attn_ws;     // x1, x2: the fp32 residual stream
     size_t attn_ws_bytes, bytes;
     int kh_max, Fp_max, Lp;
 };
@@ -136,7 +139,8 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     w.qkv = c.take<char>(rows * (size_t)(kh_max + (bf ? 1 : 2) * D.Hk) * D.dh * es);
     w.vt = bf ? c.take<char>((size_t)D.B * D.Hk * D.dh * w.Lp * es) : nullptr;
     w.att = c.take<char>(rows * (size_t)kh_max * D.dh * es);
-    w.x1 = c.take<char>(rows * D.d * es);
+    w.x1 = c.take<float>(rows * D.d);
+    w.x2 = D.nl > 1 || (D.flags & SF_FLAG_FINAL_LN) ? c.take<float>(rows * D.d) : nullptr;
     w.hid = c.take<char>(rows * (size_t)w.Fp_max * es);
     size_t amax = 0;
     for (int l = 0; l < D.nl; ++l) {
@@ -194,7 +198,8 @@ extern "C" int32_t sf_pruned_ffn_forward(const sf_desc *desc, const sf_compact_l
         return fail(SF_ERR_WORKSPACE, "pruned_ffn: workspace of %zu bytes (256-byte aligned) required, got %zu",
                     w.bytes, workspace_bytes);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (int32_t rc = ffn_forward(D, *ly, X, pattern_id, pre_ln != 0, add_residual != 0, Y, w.xn, w.hid, st))
+    if (int32_t rc = ffn_forward(D, *ly, X, false, pattern_id, pre_ln != 0, add_residual != 0, Y, false, w.xn,
+                                 w.hid, st))
         return rc;
     return check_launch("pruned_ffn_forward");
 }
@@ -243,7 +248,12 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
     const bool bf = D.dtype == SF_BF16;
     const size_t es = elem_size(D.dtype);
     const int64_t rows = (int64_t)D.B * D.L;
+    // The residual stream is kept in fp32 between layers (x1 after the attention
+    // block, x2 after the FFN); only the tensors feeding a contraction and the
+    // final output are stored in the model dtype.
     const void *in = X;
+    bool in_f32 = !bf;
+    const bool final_ln = (D.flags & SF_FLAG_FINAL_LN) != 0;
     for (int l = 0; l < D.nl; ++l) {
         const sf_compact_layer &ly = layers[l];
         const int kh = ly.k_head, dh = D.dh, Hk = D.Hk;
@@ -251,7 +261,7 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
         const int ldq = bf ? Nqk : Nqkv;                    // row length of the token-major buffer
 
         // x' = LN1(x);  Q, K (token-major) and V (bf16: transposed) = x' Wqkv'^T + b
-        layernorm(D.dtype, in, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, w.xn, st);
+        layernorm(D.dtype, in_f32, in, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, w.xn, st);
         GemmArgs g{};
         g.A = w.xn; g.lda = D.d; g.W = ly.Wqkv; g.ldw = D.d; g.w_pstride = (int64_t)Nqkv * D.d;
         g.bias = ly.bqkv; g.bias_pstride = Nqkv; g.pattern_id = pattern_id;
@@ -288,13 +298,17 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
         o.A = w.att; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
         o.w_pstride = (int64_t)D.d * kh * dh; o.bias = ly.bo; o.bias_pstride = 0; o.pattern_id = pattern_id;
         o.B = D.B; o.L = D.L; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
-        o.R = in; o.ldr = D.d; o.C = w.x1; o.ldc = D.d;
+        o.R = in; o.ldr = D.d; o.r_f32 = in_f32; o.C = w.x1; o.ldc = D.d; o.c_f32 = 1;
         if (int32_t rc = gemm(D.dtype, o, st)) return rc;
 
-        // y = x1 + FFN(LN2(x1))
-        if (int32_t rc = ffn_forward(D, ly, w.x1, pattern_id, true, true, Y, w.xn, w.hid, st)) return rc;
-        in = Y;
+        // x2 = x1 + FFN(LN2(x1)); the last layer without a final LN writes Y directly
+        const bool to_y = l == D.nl - 1 && !final_ln;
+        if (int32_t rc = ffn_forward(D, ly, w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y, w.xn,
+                                     w.hid, st))
+            return rc;
+        in = w.x2;
+        in_f32 = true;
     }
-    if (D.flags & SF_FLAG_FINAL_LN) layernorm(D.dtype, Y, final_g, final_b, D.eps, rows, D.d, Y, st);
+    if (final_ln) layernorm(D.dtype, 1, w.x2, final_g, final_b, D.eps, rows, D.d, Y, st);
     return check_launch("encoder_forward");
 }

@@ -22,6 +22,7 @@ struct GemmArgs {
     int act;
     const void *R; int64_t ldr; int r0;                  // residual (NULL = none), first column r0
     void *C; int64_t ldc; int c0;                        // EPI_ROWMAJOR: row stride, first column
+    int r_f32, c_f32;                                    // bf16 GEMM only: R / C hold fp32 (the residual stream)
     int64_t vt_b, vt_n;                                  // EPI_VT: strides of b and n (i contiguous)
 };
 
@@ -29,8 +30,9 @@ struct GemmArgs {
 // ldc % 4 == 0, 16-byte aligned bases).  dtype SF_F32: fp32 FMA.
 int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st);
 
-// LayerNorm over rows of d elements (biased variance), y may alias x.
-void layernorm(int dtype, const void *x, const void *gamma, const void *beta, float eps,
+// LayerNorm over rows of d elements (biased variance).  gamma/beta are in the
+// model dtype; x is fp32 when x_f32 (or dtype is SF_F32), y is in the model dtype.
+void layernorm(int dtype, int x_f32, const void *x, const void *gamma, const void *beta, float eps,
                int64_t rows, int d, void *y, hipStream_t st);
 
 }  // namespace sf

@@ -135,8 +135,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
     const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)p * a.bias_pstride + a.n0 : nullptr;
     if (!SWAP) {
         // lane: token i = m0 + wm*WTM + tm*32 + l32 ; features n = wn*WTN + tn*32 + q*8 + lhi*4 + {0..3}
-        __bf16 *C = static_cast<__bf16 *>(a.C);
-        const __bf16 *R = static_cast<const __bf16 *>(a.R);
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             const int i = m0 + wm * WTM + tm * 32 + l32;
@@ -158,15 +156,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
                     }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], a.act);
-                    if (R) {
-                        const bf16x4 rv = *reinterpret_cast<const bf16x4 *>(R + row * a.ldr + a.r0 + n);
+                    if (a.R) {
+                        const int64_t ro = row * a.ldr + a.r0 + n;
+                        if (a.r_f32) {
+                            const f32x4 rv = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(a.R) + ro);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
+                            for (int e = 0; e < 4; ++e) v[e] += rv[e];
+                        } else {
+                            const bf16x4 rv = *reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + ro);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
+                        }
                     }
-                    bf16x4 o;
+                    const int64_t co = row * a.ldc + a.c0 + n;
+                    if (a.c_f32) {
+                        f32x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
-                    *reinterpret_cast<bf16x4 *>(C + row * a.ldc + a.c0 + n) = o;
+                        for (int e = 0; e < 4; ++e) o[e] = v[e];
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co) = o;
+                    } else {
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
+                        *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co) = o;
+                    }
                 }
             }
         }
@@ -226,7 +239,7 @@ int32_t gemm_bf16(const GemmArgs &a, hipStream_t st)
         (a.epi == EPI_ROWMAJOR && (a.ldc % 4 || a.c0 % 4)))
         return fail(SF_ERR_SHAPE, "gemm(bf16): K, leading dimensions and column origins must be multiples of 8/4");
     const bool swap = a.epi == EPI_VT;
-    if (swap && a.R) return fail(SF_ERR_UNSUPPORTED, "gemm(bf16): residual with transposed store");
+    if (swap && (a.R || a.c_f32)) return fail(SF_ERR_UNSUPPORTED, "gemm(bf16): residual / fp32 output with transposed store");
     const int64_t rows = (int64_t)a.B * a.L;
     const bool big = a.L >= 192 && a.N >= 192 && rows * a.N >= (int64_t)256 * 256 * 256;
     if (swap) {

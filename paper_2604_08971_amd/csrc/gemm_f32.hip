@@ -77,16 +77,18 @@ int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st)
 }
 
 // One 64-lane wave per row; statistics in fp32; biased variance.
-template <class T>
-__global__ __launch_bounds__(256) void layernorm_kernel(const T *x, const T *__restrict__ gamma,
-                                                        const T *__restrict__ beta, float eps, int64_t rows,
-                                                        int d, T *y)      // y may alias x (row-wise in place)
+// TI: stored type of x, TP: type of gamma/beta, TO: type of y.  y may alias x
+// when TI == TO (each row is read completely before it is written).
+template <class TI, class TP, class TO>
+__global__ __launch_bounds__(256) void layernorm_kernel(const TI *x, const TP *__restrict__ gamma,
+                                                        const TP *__restrict__ beta, float eps, int64_t rows,
+                                                        int d, TO *y)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const T *xr = x + row * d;
-    T *yr = y + row * d;
+    const TI *xr = x + row * d;
+    TO *yr = y + row * d;
     float s = 0.f;
     for (int k = lane; k < d; k += 64) s += to_f32(xr[k]);
 #pragma unroll
@@ -101,20 +103,23 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const T *x, const T *__r
         float z = (to_f32(xr[k]) - mean) * inv;
         if (gamma) z *= to_f32(gamma[k]);
         if (beta) z += to_f32(beta[k]);
-        yr[k] = from_f32<T>(z);
+        yr[k] = from_f32<TO>(z);
     }
 }
 
-void layernorm(int dtype, const void *x, const void *gamma, const void *beta, float eps,
+void layernorm(int dtype, int x_f32, const void *x, const void *gamma, const void *beta, float eps,
                int64_t rows, int d, void *y, hipStream_t st)
 {
     if (rows <= 0) return;
     dim3 grid((unsigned)((rows + 3) / 4));
-    if (dtype == SF_BF16)
-        hipLaunchKernelGGL(layernorm_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)x,
+    if (dtype == SF_BF16 && !x_f32)
+        hipLaunchKernelGGL((layernorm_kernel<__bf16, __bf16, __bf16>), grid, dim3(256), 0, st, (const __bf16 *)x,
+                           (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, (__bf16 *)y);
+    else if (dtype == SF_BF16)
+        hipLaunchKernelGGL((layernorm_kernel<float, __bf16, __bf16>), grid, dim3(256), 0, st, (const float *)x,
                            (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, (__bf16 *)y);
     else
-        hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, st, (const float *)x,
+        hipLaunchKernelGGL((layernorm_kernel<float, float, float>), grid, dim3(256), 0, st, (const float *)x,
                            (const float *)gamma, (const float *)beta, eps, rows, d, (float *)y);
 }
 
