@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruned multimodal encoder forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--no-cpu] [--no-extras]
+
+One "step" is one pass of the whole hot path over one batch of seeded synthetic
+input already resident in HBM: gate scores -> keep masks, compaction of the
+weights, and the encoder forward (LayerNorm, Q/K/V projection, sparse GQA,
+output projection, pruned FFN) of every layer.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+METRIC = "encoder tokens/sec + sparse-GQA TFLOP/s (% of bf16 MFMA peak), 1 MI355X"
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_flops(wl, masks_host, U):
+    """Flops credited per step: kept heads / kept groups / kept channels only, no padding."""
+    import numpy as np
+    s = wl.spec
+    B, L, d, dh = wl.x.shape[0], s.L, s.d, s.dh
+    n_allowed = np.full(B, L) if wl.key_valid is None else wl.key_valid.sum(axis=1).astype(np.int64)
+    gemm = score = active = 0
+    for l in range(s.n_layers):
+        kh, kf = int(wl.k_head[l]), int(wl.k_ffn[l])
+        ng = masks_host["n_groups"][l][wl.pattern_id].astype(np.int64)          # per sample
+        gemm += int((2 * L * d * dh * (kh + 2 * ng)).sum())                     # Q, K, V projections
+        gemm += B * 2 * L * kh * dh * d                                         # output projection
+        gemm += B * 4 * L * d * kf                                              # both FFN GEMMs
+        if 0 < U < L:
+            score += int((kh * 2 * n_allowed * n_allowed * dh).sum())           # QK^T stream of the sparsity score
+        active += int((kh * 4 * np.minimum(U, n_allowed) * n_allowed * dh).sum())   # QK^T + PV of the active rows
+    return {"gemm": gemm, "score": score, "active": active, "total": gemm + score + active}
+
+
+def time_steps(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return ev0.elapsed_time(ev1) / steps, wall
+
+
+def bench_config(name, steps, warmup, extras, cpu):
+    import numpy as np
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from paper_2604_08971_amd import workloads as W
+    from gpu_utils import DeviceModel, to_host
+
+    spec = W.CONFIGS[name]
+    t0 = time.perf_counter()
+    wl = W.make_workload(spec)
+    dm = DeviceModel(wl).build_plan()
+    torch.cuda.synchronize()
+    log(f"[{name}] inputs generated and uploaded in {time.perf_counter() - t0:.1f} s")
+    s = spec
+    B, L = wl.x.shape[0], s.L
+    U = sf.num_active(dm.desc)
+    y = torch.empty_like(dm.x)
+    masks_host = {k: to_host(v) for k, v in dm.masks.items()}
+    flops = algorithmic_flops(wl, masks_host, U)
+
+    def step():                       # the whole hot path
+        dm.build_plan()
+        dm.forward(out=y)
+
+    ms, wall_ms = time_steps(step, steps, warmup)
+    res = {"workload": name, "ms_per_step": ms, "host_ms_per_step": wall_ms, "tokens_per_s": B * L / (ms * 1e-3),
+           "B": B, "L": L, "U": U, "algorithmic_tflop_per_step": flops["total"] / 1e12,
+           "tflops_total": flops["total"] / (ms * 1e-3) / 1e12}
+    if not extras:
+        return res, dm, wl, flops
+
+    ms_fwd, _ = time_steps(lambda: dm.forward(out=y), steps, 2)
+    ms_plan, _ = time_steps(lambda: dm.build_plan(), steps, 2)
+    res.update({"ms_encoder_only": ms_fwd, "ms_plan_only": ms_plan,
+                "tokens_per_s_encoder_only": B * L / (ms_fwd * 1e-3)})
+
+    # per-kernel-class timing with HIP events on the launch stream (second pass of the same steps)
+    prof = {}
+    if s.dtype == "bf16":
+        for cls, key in ((sf.SF_KERNEL_GEMM, "gemm"), (sf.SF_KERNEL_SCORE, "score"), (sf.SF_KERNEL_ATTEND, "active")):
+            sf.profile_begin(cls, steps * 64 * s.n_layers)
+            for _ in range(steps):
+                step()
+            n, tot_ms = sf.profile_end()
+            if n:
+                prof[key] = {"launches_per_step": n / steps, "avg_launch_us": tot_ms * 1e3 / n,
+                             "ms_per_step": tot_ms / steps,
+                             "tflops": flops[key] * steps / (tot_ms * 1e-3) / 1e12 if tot_ms > 0 else None}
+                prof[key]["frac_of_bf16_peak"] = prof[key]["tflops"] / PEAK_BF16_TFLOPS if prof[key]["tflops"] else None
+    res["kernels"] = prof
+    return res, dm, wl, flops
+
+
+def bench_sparse_gqa(dm, wl, steps):
+    """sparse_gqa_forward alone, at the workload's kept shapes, c-sparse and dense pattern."""
+    import numpy as np
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    s = wl.spec
+    if s.dtype != "bf16":
+        return None
+    B, L, dh, kh = wl.x.shape[0], s.L, s.dh, int(wl.k_head[0])
+    g = torch.Generator(device="cuda").manual_seed(1)
+    Q = torch.randn((B, kh, L, dh), generator=g, device="cuda").to(torch.bfloat16)
+    K = torch.randn((B, s.Hk, L, dh), generator=g, device="cuda").to(torch.bfloat16)
+    V = torch.randn((B, s.Hk, L, dh), generator=g, device="cuda").to(torch.bfloat16)
+    hg = dm.masks["head_group"][0][:, :kh].contiguous()
+    n_allowed = np.full(B, L) if wl.key_valid is None else wl.key_valid.sum(axis=1).astype(np.int64)
+    out = {}
+    for tag, Uo in (("c5", -1), ("dense", L)):
+        desc = sf.make_desc(B, L, s.d, s.Hq, s.Hk, dh, s.F, dtype=sf.SF_BF16, c_factor=s.c, U_override=Uo)
+        U = sf.num_active(desc)
+        ws = sf.workspace(sf.sparse_gqa_workspace_bytes(desc, kh, s.Hk))
+        fn = lambda: sf.sparse_gqa_forward(desc, Q, K, V, hg, dm.pattern_id, dm.key_valid, want_sel=False, ws=ws)
+        ms, _ = time_steps(fn, steps, 2)
+        fl = int((kh * 4 * np.minimum(U, n_allowed) * n_allowed * dh).sum())
+        if U < L:
+            fl += int((kh * 2 * n_allowed * n_allowed * dh).sum())
+        out[tag] = {"U": U, "ms": ms, "tflops": fl / (ms * 1e-3) / 1e12,
+                    "frac_of_bf16_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    return out
+
+
+def cpu_baseline(wl, flops_total):
+    """The CPU oracle, as it stands, on a bounded number of whole samples of the same workload."""
+    import numpy as np
+    from oracle import cpu_oracle as orc
+    from helpers import compact_packs, oracle_masks
+    s = wl.spec
+    B, L = wl.x.shape[0], s.L
+    threads = orc.max_threads()
+    per_sample = flops_total / B
+    n = int(max(1, min(B, round(15.0 * threads * 0.7e9 / per_sample))))    # aim at roughly 15 s
+    masks = oracle_masks(wl)
+    packs = compact_packs(wl, masks)
+    U = orc.num_active(L, s.c)
+    kv = None if wl.key_valid is None else wl.key_valid[:n]
+    t0 = time.perf_counter()
+    orc.encoder_forward(wl.x[:n], packs, U, wl.pattern_id[:n], kv, act=s.act, final_ln=wl.final_ln,
+                        bf16=s.dtype == "bf16", want_sel=False)
+    dt = time.perf_counter() - t0
+    return {"value": n * L / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {B} samples of {s.name} (whole encoder forward, fp64 C oracle, OpenMP over rows), {dt:.1f} s",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C5", help="workload timed for `value` (C1..C5)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline number")
+    ap.add_argument("--other-configs", default="C2,C3,C4", help="also time these (reported under `other_workloads`)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (one MI355X holds every workload and no step of the path "
+                 "crosses samples); run with --gpus 1")
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    from paper_2604_08971_amd import binding as sf
+    from paper_2604_08971_amd import workloads as W
+    sf.lib()
+
+    extras = not args.no_extras
+    res, dm, wl, flops = bench_config(args.config, args.steps, args.warmup, extras, not args.no_cpu)
+    spec = wl.spec
+    out = {
+        "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if spec.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: B={res['B']} L={res['L']} d={spec.d} Hq/Hk/dh={spec.Hq}/{spec.Hk}/{spec.dh} "
+                               f"F={spec.F} layers={spec.n_layers} kept heads={list(map(int, wl.k_head))} "
+                               f"kept channels={int(wl.k_ffn[0])} U={res['U']} patterns={wl.P}",
+                   "step": "gate_scores_to_masks + compact_heads_channels + encoder_forward"},
+        "algorithmic_tflop_per_step": res["algorithmic_tflop_per_step"],
+        "tflops": res["tflops_total"], "frac_of_bf16_peak": res["tflops_total"] / PEAK_BF16_TFLOPS,
+    }
+    if extras:
+        out["detail"] = {k: res[k] for k in ("ms_encoder_only", "ms_plan_only", "tokens_per_s_encoder_only",
+                                             "host_ms_per_step") if k in res}
+        k = res.get("kernels", {})
+        if "gemm" in k:
+            g = k["gemm"]
+            out["roofline"] = {"bound": "mfma", "kernel": "gemm_bf16_kernel (all projections + FFN)",
+                               "achieved": g["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                               "frac": g["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+                               "avg_launch_us": g["avg_launch_us"], "launches_per_step": g["launches_per_step"]}
+        out["kernels"] = k
+        out["sparse_gqa"] = bench_sparse_gqa(dm, wl, args.steps)
+    if not args.no_cpu:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(wl, flops["total"])
+    del dm
+    torch.cuda.empty_cache()
+    if extras and args.other_configs:
+        others = {}
+        for name in args.other_configs.split(","):
+            name = name.strip()
+            if not name or name == args.config:
+                continue
+            r, dm2, _, _ = bench_config(name, args.steps, args.warmup, True, False)
+            others[name] = {k: r[k] for k in ("ms_per_step", "tokens_per_s", "tflops_total", "ms_encoder_only",
+                                              "ms_plan_only", "host_ms_per_step") if k in r}
+            others[name]["kernels"] = r.get("kernels")
+            del dm2
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

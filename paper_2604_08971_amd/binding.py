@@ -24,7 +24,8 @@ SF_FLAG_FINAL_LN = 1
 EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks",
            "sf_compact_heads_channels", "sf_sparse_gqa_workspace_bytes", "sf_sparse_gqa_forward",
            "sf_pruned_ffn_workspace_bytes", "sf_pruned_ffn_forward", "sf_encoder_workspace_bytes",
-           "sf_encoder_forward"]
+           "sf_encoder_forward", "sf_profile_begin", "sf_profile_end"]
+SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
 
 class SfDesc(C.Structure):
@@ -68,7 +69,8 @@ def lib():
         for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
-                  "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward"):
+                  "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
+                  "sf_profile_end"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -86,6 +88,8 @@ def lib():
         L.sf_encoder_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)]
         L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
         L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        L.sf_profile_begin.argtypes = [C.c_int32, C.c_int32]
+        L.sf_profile_end.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_float)]
         L.sf_num_active.argtypes = [C.POINTER(SfDesc)]
         L.sf_ffn_padded.argtypes = [C.POINTER(SfDesc), C.c_int32]
         _lib = L
@@ -133,15 +137,26 @@ def workspace(nbytes: int, device="cuda") -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def profile_begin(kernel_class: int, max_launches: int):
+    _check(lib().sf_profile_begin(kernel_class, max_launches), "sf_profile_begin")
+
+
+def profile_end():
+    """Returns (number of launches timed, sum of their durations in ms)."""
+    n, ms = C.c_int32(0), C.c_float(0.0)
+    _check(lib().sf_profile_end(C.byref(n), C.byref(ms)), "sf_profile_end")
+    return int(n.value), float(ms.value)
+
+
 # --------------------------------------------------------------------------- a1
 def gate_scores_to_masks(desc: SfDesc, g_head: torch.Tensor, g_ffn: torch.Tensor, k_head: Sequence[int],
-                         k_ffn: Sequence[int]) -> Dict[str, torch.Tensor]:
+                         k_ffn: Sequence[int], out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
     nl, P, Hq, Hk, F = desc.n_layers, desc.P, desc.Hq, desc.Hk, desc.d_ff
     dev = g_head.device
     assert g_head.dtype == torch.float32 and g_ffn.dtype == torch.float32
     assert tuple(g_head.shape) == (nl, P, Hq) and tuple(g_ffn.shape) == (nl, P, F)
     assert g_head.is_contiguous() and g_ffn.is_contiguous()
-    out = {
+    out = out if out is not None else {
         "head_mask": torch.empty((nl, P, Hq), dtype=torch.uint8, device=dev),
         "ffn_mask": torch.empty((nl, P, F), dtype=torch.uint8, device=dev),
         "head_idx": torch.empty((nl, P, Hq), dtype=torch.int32, device=dev),
@@ -204,11 +219,18 @@ def dense_struct(dense: Dict[str, torch.Tensor]) -> SfDenseLayer:
 
 
 def compact_heads_channels(desc: SfDesc, layer: int, dense: Dict[str, torch.Tensor],
-                           masks: Dict[str, torch.Tensor], k_head: int, k_ffn: int) -> CompactLayer:
-    """Allocates the compact buffers of `layer` and fills them on the GPU."""
-    hg = masks["head_group"][layer]
-    ng = masks["n_groups"][layer]
-    cl = CompactLayer(desc, dense, k_head, k_ffn, hg, ng)
+                           masks: Dict[str, torch.Tensor], k_head: int, k_ffn: int,
+                           out: Optional[CompactLayer] = None) -> CompactLayer:
+    """Fills the compact buffers of `layer` on the GPU (allocating them unless `out`,
+    built for the same masks tensors and counts, is given)."""
+    if out is None:
+        hg = masks["head_group"][layer]
+        ng = masks["n_groups"][layer]
+        cl = CompactLayer(desc, dense, k_head, k_ffn, hg, ng)
+    else:
+        cl = out
+        assert cl.k_head == int(k_head) and cl.k_ffn == int(k_ffn)
+        assert cl.head_group.data_ptr() == masks["head_group"][layer].data_ptr()
     ds = dense_struct(dense)
     rc = lib().sf_compact_heads_channels(C.byref(desc), int(layer), C.byref(ds), _ptr(masks["head_idx"]),
                                          _ptr(masks["group_idx"]), _ptr(masks["n_groups"]),

@@ -31,6 +31,26 @@ int32_t check_launch(const char *what)
     return SF_OK;
 }
 
+// ---- per-kernel event timing ----------------------------------------------------
+static struct {
+    int kernel_class = -1;
+    int cap = 0, n = 0;
+    hipEvent_t *start = nullptr, *stop = nullptr;
+} g_prof;
+
+ProfScope::ProfScope(int kernel_class, hipStream_t s) : slot(-1), st(s)
+{
+    if (g_prof.kernel_class == kernel_class && g_prof.n < g_prof.cap) {
+        slot = g_prof.n++;
+        hipEventRecord(g_prof.start[slot], st);
+    }
+}
+
+ProfScope::~ProfScope()
+{
+    if (slot >= 0) hipEventRecord(g_prof.stop[slot], st);
+}
+
 int32_t read_desc(const sf_desc *desc, Dims &D)
 {
     if (!desc) return fail(SF_ERR_INVALID_ARG, "descriptor is NULL");
@@ -158,6 +178,46 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
 using namespace sf;
 
 extern "C" const char *sf_last_error(void) { return err_buf(); }
+
+extern "C" int32_t sf_profile_begin(int32_t kernel_class, int32_t max_launches)
+{
+    if (g_prof.kernel_class >= 0) return fail(SF_ERR_INVALID_ARG, "profile: already profiling");
+    if (kernel_class < 0 || kernel_class > SF_KERNEL_ATTEND || max_launches < 1 || max_launches > (1 << 20))
+        return fail(SF_ERR_INVALID_ARG, "profile: bad kernel class or launch count");
+    g_prof.start = new hipEvent_t[max_launches];
+    g_prof.stop = new hipEvent_t[max_launches];
+    for (int i = 0; i < max_launches; ++i) {
+        if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess)
+            return fail(SF_ERR_HIP, "profile: hipEventCreate failed");
+    }
+    g_prof.cap = max_launches;
+    g_prof.n = 0;
+    g_prof.kernel_class = kernel_class;
+    return SF_OK;
+}
+
+extern "C" int32_t sf_profile_end(int32_t *n_launches, float *total_ms)
+{
+    if (g_prof.kernel_class < 0) return fail(SF_ERR_INVALID_ARG, "profile: not profiling");
+    g_prof.kernel_class = -1;
+    float sum = 0.f;
+    int32_t rc = SF_OK;
+    for (int i = 0; i < g_prof.n; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess)
+            rc = fail(SF_ERR_HIP, "profile: reading event %d failed", i);
+        sum += ms;
+    }
+    for (int i = 0; i < g_prof.cap; ++i) { hipEventDestroy(g_prof.start[i]); hipEventDestroy(g_prof.stop[i]); }
+    delete[] g_prof.start;
+    delete[] g_prof.stop;
+    if (n_launches) *n_launches = g_prof.n;
+    if (total_ms) *total_ms = sum;
+    g_prof.start = g_prof.stop = nullptr;
+    g_prof.cap = g_prof.n = 0;
+    return rc;
+}
 
 extern "C" int32_t sf_num_active(const sf_desc *desc)
 {

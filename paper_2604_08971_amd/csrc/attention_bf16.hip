@@ -364,6 +364,7 @@ static int32_t launch_score(const AttnArgs &a, const AttnPlan &pl, float *score,
 {
     const size_t lds = (size_t)BKEY * (DH + PAD) * 2 + DH * 4 + (size_t)ceil_div(a.L, 32) * 4;
     dim3 grid(ceil_div(a.L, NWAVE * QBS * 32), a.B * a.nH);
+    ProfScope prof(SF_KERNEL_SCORE, st);
     hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
                        a.sq, (const __bf16 *)a.K, a.sk, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
                        pl.stats, a.nH, a.nG, a.L, score, scoreH);
@@ -390,6 +391,7 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
     const int nqb = pl.Upad / 32;
     // upper bound on pairs of one group: every head in the same group
     dim3 grid(ceil_div(a.nH * nqb, NWAVE * QB), a.B * a.nG, pl.splits);
+    ProfScope prof(SF_KERNEL_ATTEND, st);
     hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
                        a.sq, (const __bf16 *)a.K, a.sk, (const __bf16 *)vt, svt, a.head_group, a.hg_stride,
                        a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, a.L, pl.Lp, a.U, pl.Upad, pl.splits,

@@ -15,6 +15,16 @@ char *err_buf();                       // thread-local, 512 bytes
 int32_t fail(int32_t code, const char *fmt, ...);
 int32_t check_launch(const char *what);   // wraps hipGetLastError()
 
+// ---- optional per-kernel timing (measurement aid, off by default) -----------
+// While a kernel class is being profiled, every launch of that class is
+// bracketed by a pair of HIP events on the launch stream.
+struct ProfScope {
+    ProfScope(int kernel_class, hipStream_t st);
+    ~ProfScope();
+    int slot;
+    hipStream_t st;
+};
+
 // ---- descriptor ------------------------------------------------------------
 struct Dims {
     int B, L, d, Hq, Hk, dh, F, nl, P, dtype, act, U, ffn_pad;

@@ -228,6 +228,7 @@ static int32_t launch_cfg(const GemmArgs &a, hipStream_t st)
         attr_set = true;
     }
     dim3 grid(ceil_div(a.L, BM) * a.B, ceil_div(a.N, BN));
+    ProfScope prof(SF_KERNEL_GEMM, st);
     hipLaunchKernelGGL(kern, grid, dim3(64 * WAVES_M * WAVES_N), lds, st, a);
     return SF_OK;
 }

@@ -61,9 +61,12 @@ class DeviceModel:
     def build_plan(self):
         """a1 + a2: gate scores -> masks -> compacted weights, all on the GPU."""
         wl = self.wl
-        self.masks = sf.gate_scores_to_masks(self.desc, self.g_head, self.g_ffn, wl.k_head, wl.k_ffn)
+        first = not self.layers
+        self.masks = sf.gate_scores_to_masks(self.desc, self.g_head, self.g_ffn, wl.k_head, wl.k_ffn,
+                                             out=None if first else self.masks)
         self.layers = [sf.compact_heads_channels(self.desc, l, self.dense[l], self.masks,
-                                                 int(wl.k_head[l]), int(wl.k_ffn[l]))
+                                                 int(wl.k_head[l]), int(wl.k_ffn[l]),
+                                                 out=None if first else self.layers[l])
                        for l in range(wl.spec.n_layers)]
         return self
 
