@@ -233,9 +233,16 @@ static int32_t launch_cfg(const GemmArgs &a, hipStream_t st)
     return SF_OK;
 }
 
+int32_t gemm_bf16_fast(const GemmArgs &a, hipStream_t st, bool &done);
+
 int32_t gemm_bf16(const GemmArgs &a, hipStream_t st)
 {
     if (a.B <= 0 || a.N <= 0) return SF_OK;
+    {
+        bool done = false;
+        if (int32_t rc = gemm_bf16_fast(a, st, done)) return rc;
+        if (done) return SF_OK;
+    }
     if (a.K % 8 || a.lda % 8 || a.ldw % 8 || a.N % 4 || a.n0 % 4 || (a.R && (a.ldr % 4 || a.r0 % 4)) ||
         (a.epi == EPI_ROWMAJOR && (a.ldc % 4 || a.c0 % 4)))
         return fail(SF_ERR_SHAPE, "gemm(bf16): K, leading dimensions and column origins must be multiples of 8/4");
