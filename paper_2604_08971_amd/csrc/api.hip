@@ -42,13 +42,13 @@ ProfScope::ProfScope(int kernel_class, hipStream_t s) : slot(-1), st(s)
 {
     if (g_prof.kernel_class == kernel_class && g_prof.n < g_prof.cap) {
         slot = g_prof.n++;
-        hipEventRecord(g_prof.start[slot], st);
+        (void)hipEventRecord(g_prof.start[slot], st);
     }
 }
 
 ProfScope::~ProfScope()
 {
-    if (slot >= 0) hipEventRecord(g_prof.stop[slot], st);
+    if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], st);
 }
 
 int32_t read_desc(const sf_desc *desc, Dims &D)
@@ -209,7 +209,7 @@ extern "C" int32_t sf_profile_end(int32_t *n_launches, float *total_ms)
             rc = fail(SF_ERR_HIP, "profile: reading event %d failed", i);
         sum += ms;
     }
-    for (int i = 0; i < g_prof.cap; ++i) { hipEventDestroy(g_prof.start[i]); hipEventDestroy(g_prof.stop[i]); }
+    for (int i = 0; i < g_prof.cap; ++i) { (void)hipEventDestroy(g_prof.start[i]); (void)hipEventDestroy(g_prof.stop[i]); }
     delete[] g_prof.start;
     delete[] g_prof.stop;
     if (n_launches) *n_launches = g_prof.n;

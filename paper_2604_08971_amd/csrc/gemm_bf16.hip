@@ -234,12 +234,15 @@ static int32_t launch_cfg(const GemmArgs &a, hipStream_t st)
 }
 
 int32_t gemm_bf16_fast(const GemmArgs &a, hipStream_t st, bool &done);
+int32_t gemm_bf16_ws(const GemmArgs &a, hipStream_t st, bool &done);
 
 int32_t gemm_bf16(const GemmArgs &a, hipStream_t st)
 {
     if (a.B <= 0 || a.N <= 0) return SF_OK;
     {
         bool done = false;
+        if (int32_t rc = gemm_bf16_ws(a, st, done)) return rc;
+        if (done) return SF_OK;
         if (int32_t rc = gemm_bf16_fast(a, st, done)) return rc;
         if (done) return SF_OK;
     }

@@ -16,14 +16,14 @@
 //    the weight matrix stays resident in that L2;
 //  * the epilogue pairs lane l with lane l+32 (v_permlane32_swap) so that each
 //    lane owns 8 consecutive features of a token: 16-byte stores.
+#include <type_traits>
+
 #include "gemm.hpp"
 
 namespace sf {
 
 constexpr int FBK = 64;
 constexpr int N_XCD = 8;
-
-__device__ __forceinline__ int fswz(int row, int chunk) { return row * FBK + ((chunk ^ (row & 7)) << 3); }
 
 template <int ACT>
 __device__ __forceinline__ float fact(float z)
@@ -36,18 +36,46 @@ __device__ __forceinline__ float fact(float z)
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void glb_void;
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool SWAP, int ACT>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n,
-                                                                                 int total_tiles, int per_xcd)
+// LDS layout of a [rows][BKT] bf16 tile.  The LDS serves 16 lanes of a
+// ds_read_b128 per cycle (256 bytes), so 16 consecutive rows of one logical
+// 16-byte chunk must fall into 16 different 16-byte slots modulo 256 bytes:
+// rows are packed into 256-byte super-rows and the slot is XOR-ed with the
+// super-row number.
+template <int BKT>
+struct Lay {
+    static constexpr int CH = BKT / 8;          // 16-byte chunks per row
+    static constexpr int RPS = 16 / CH;         // rows per super-row
+    __device__ __forceinline__ static int off(int row, int chunk)      // element offset
+    {
+        const int sr = row / RPS;
+        const int pos = ((row % RPS) * CH + chunk) ^ (sr % CH);
+        return sr * 128 + pos * 8;
+    }
+};
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// One workgroup per CU (its LDS tiles take most of the 160 KB), so a wave may use
+// 512 / (waves per SIMD) registers: say so, or the accumulators spill.
+template <int WAVES_M, int WAVES_N, int TM, int TN, int BKT, int NSTAGE, bool SWAP, int ACT>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N)
+__attribute__((amdgpu_waves_per_eu(WAVES_M * WAVES_N / 4,
+                                   (WAVES_M * WAVES_N * TM * TN >= 64) ? WAVES_M * WAVES_N / 4 : 2)))
+void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd)
 {
+    using L = Lay<BKT>;
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    constexpr int RG = (BM + BN) / 8;               // 8-row groups per K tile (one load instruction each)
-    constexpr int LPW = RG / NW;                    // load instructions per wave per K tile
-    static_assert(RG % NW == 0, "row groups must divide among the waves");
+    constexpr int ROWS_PER_LOAD = 4 * L::RPS;             // one load instruction fills 4 super-rows (1 KB)
+    constexpr int LX = BM / ROWS_PER_LOAD / NW;           // load instructions per wave per K tile: X rows
+    constexpr int LW = BN / ROWS_PER_LOAD / NW;           //                                          W rows
+    constexpr int LPW = LX + LW;
+    constexpr int STAGE = (BM + BN) * BKT;                // elements per stage
+    static_assert(BM % (ROWS_PER_LOAD * NW) == 0 && BN % (ROWS_PER_LOAD * NW) == 0, "loads must divide among the waves");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4 && (NSTAGE - 2) * LPW <= 63, "pipeline depth");
 
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [2][(BM+BN)*FBK]: X rows then W rows
+    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NSTAGE][X rows | W rows][BKT]
 
     // XCD-aware tile order
     const int wid = blockIdx.x;
@@ -59,35 +87,47 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_fast_kernel(
     const int nt0 = tn_i * BN;
     const int p = a.pattern_id ? a.pattern_id[b] : 0;
 
-    const __bf16 *A = static_cast<const __bf16 *>(a.A) + ((int64_t)b * a.L) * a.lda;
-    const __bf16 *W = static_cast<const __bf16 *>(a.W) + (int64_t)p * a.w_pstride + (int64_t)a.n0 * a.ldw;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: keeps LDS bases in SGPRs
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int l32 = lane & 31, lhi = lane >> 5;
 
-    // per-lane source pointers of this wave's load instructions (advanced by FBK per K tile)
-    const __bf16 *src[LPW];
+    // Sources of this wave's load instructions: a uniform base that advances by BKT per K
+    // tile plus a fixed per-lane byte offset.  Lane -> LDS slot is fixed (lane*16 bytes), so
+    // the slot's (row, chunk) is decoded here; rows beyond the edge are clamped.
+    const char *Ab = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.A) + ((int64_t)b * a.L + m0) * a.lda);
+    const char *Wb = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.W) + (int64_t)p * a.w_pstride +
+                                                    (int64_t)(a.n0 + nt0) * a.ldw);
+    uint32_t xoff[LX], woff[LW];
+    {
+        const int srl = lane >> 4;                            // super-row within the instruction
+        const int rows_x = min(BM, a.L - m0), rows_w = min(BN, a.N - nt0);
 #pragma unroll
-    for (int j = 0; j < LPW; ++j) {
-        const int rg = wave + j * NW;
-        const int r = rg * 8 + (lane >> 3);          // row within [X rows | W rows]
-        const int c = (lane & 7) ^ (r & 7);          // logical chunk that must land in physical chunk lane&7
-        if (rg < BM / 8) {
-            const int i = min(m0 + r, a.L - 1);
-            src[j] = A + (int64_t)i * a.lda + c * 8;
-        } else {
-            const int n = min(nt0 + r - BM, a.N - 1);
-            src[j] = W + (int64_t)n * a.ldw + c * 8;
+        for (int j = 0; j < LX; ++j) {
+            const int sr = (wave + j * NW) * 4 + srl;
+            const int t = (lane & 15) ^ (sr % L::CH);
+            const int r = min(sr * L::RPS + t / L::CH, rows_x - 1);
+            xoff[j] = (uint32_t)(r * (int)a.lda + (t % L::CH) * 8) * 2u;
+        }
+#pragma unroll
+        for (int j = 0; j < LW; ++j) {
+            const int sr = (wave + j * NW) * 4 + srl;
+            const int t = (lane & 15) ^ (sr % L::CH);
+            const int r = min(sr * L::RPS + t / L::CH, rows_w - 1);
+            woff[j] = (uint32_t)(r * (int)a.ldw + (t % L::CH) * 8) * 2u;
         }
     }
-    auto issue_loads = [&](int buf) {
-        __bf16 *base = smem + buf * (BM + BN) * FBK;
-#pragma unroll
-        for (int j = 0; j < LPW; ++j) {
-            const int rg = wave + j * NW;
-            __builtin_amdgcn_global_load_lds((glb_void *)src[j], (lds_void *)(base + rg * 8 * FBK), 16, 0, 0);
-            src[j] += FBK;
+    // load instruction j (0..LPW-1) of K tile `tile` into ring slot `stage`
+    auto issue_load = [&](int j, int tile, int stage) {
+        __bf16 *base = smem + stage * STAGE;
+        const int64_t koff = (int64_t)tile * BKT * 2;
+        if (j < LX) {
+            __builtin_amdgcn_global_load_lds((glb_void *)(Ab + koff + xoff[j]),
+                                             (lds_void *)(base + (wave + j * NW) * 512), 16, 0, 0);
+        } else {
+            const int jw = j - LX;
+            __builtin_amdgcn_global_load_lds((glb_void *)(Wb + koff + woff[jw]),
+                                             (lds_void *)(base + BM * BKT + (wave + jw * NW) * 512), 16, 0, 0);
         }
     };
 
@@ -100,29 +140,36 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_fast_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int nk = a.K / FBK;
-    issue_loads(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    constexpr int KS = BKT / 16;                  // MFMA k-steps per K tile
+    constexpr int LPS = LPW / KS;                 // load instructions issued per k-step
+    static_assert(LPW % KS == 0, "loads must divide among the k-steps");
 
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) issue_loads((kt + 1) & 1);
-        const __bf16 *xs = smem + (kt & 1) * (BM + BN) * FBK;
-        const __bf16 *ws = xs + BM * FBK;
+    // One K tile: the fragments of k-step s+1 are read while the MFMAs of k-step s issue, and
+    // the direct-to-LDS loads of a younger tile are spread over the k-steps (a burst of loads at
+    // the top of the iteration stalls instruction issue until the address unit has taken them).
+    auto k_tile = [&](int kt, auto with_loads) {
+        constexpr bool LOADS = decltype(with_loads)::value;
+        const __bf16 *xs = smem + (kt % NSTAGE) * STAGE;
+        const __bf16 *ws = xs + BM * BKT;
+        const int load_tile = kt + NSTAGE - 1, load_stage = load_tile % NSTAGE;
         bf16x8 xf[2][TM], wf[2][TN];
         auto load_frags = [&](int s, int slot) {
             const int chunk = s * 2 + lhi;
 #pragma unroll
             for (int t = 0; t < TM; ++t)
-                xf[slot][t] = *reinterpret_cast<const bf16x8 *>(xs + fswz((wm * TM + t) * 32 + l32, chunk));
+                xf[slot][t] = *reinterpret_cast<const bf16x8 *>(xs + L::off((wm * TM + t) * 32 + l32, chunk));
 #pragma unroll
             for (int t = 0; t < TN; ++t)
-                wf[slot][t] = *reinterpret_cast<const bf16x8 *>(ws + fswz((wn * TN + t) * 32 + l32, chunk));
+                wf[slot][t] = *reinterpret_cast<const bf16x8 *>(ws + L::off((wn * TN + t) * 32 + l32, chunk));
         };
         load_frags(0, 0);
 #pragma unroll
-        for (int s = 0; s < FBK / 16; ++s) {
-            if (s + 1 < FBK / 16) load_frags(s + 1, (s + 1) & 1);
+        for (int s = 0; s < KS; ++s) {
+            if (s + 1 < KS) load_frags(s + 1, (s + 1) & 1);
+            if (LOADS) {
+#pragma unroll
+                for (int j = 0; j < LPS; ++j) issue_load(s * LPS + j, load_tile, load_stage);
+            }
 #pragma unroll
             for (int i = 0; i < TP; ++i)
 #pragma unroll
@@ -130,9 +177,38 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_fast_kernel(
                     if (SWAP) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[s & 1][i], wf[s & 1][j], acc[i][j], 0, 0, 0);
                     else      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s & 1][i], xf[s & 1][j], acc[i][j], 0, 0, 0);
                 }
+            // pin the interleaving: MFMA, LDS read, MFMA, LDS read, ..., the global loads last
+            constexpr int NMFMA = TP * TQ, NVM = LOADS ? LPS : 0;
+            const int NDS = (s + 1 < KS) ? TM + TN : 0;
+#pragma unroll
+            for (int i = 0; i < NMFMA; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                         // one MFMA
+                if (i < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // one LDS read
+                if (i >= NMFMA - NVM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+            }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+
+    // NSTAGE-deep ring: tile kt+NSTAGE-1 is requested while tile kt is consumed
+    const int nk = a.K / BKT;
+    for (int t = 0; t < NSTAGE - 1 && t < nk; ++t) {
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) issue_load(j, t, t);
+    }
+    const int n_main = nk - (NSTAGE - 1);         // iterations that still have a tile to request
+    int kt = 0;
+    for (; kt < n_main; ++kt) {
+        wait_vmcnt<(NSTAGE - 2) * LPW>();         // tile kt has landed; NSTAGE-2 younger tiles stay in flight
+        __syncthreads();                          // ... for every wave; and everyone is done with tile kt-1
+        k_tile(kt, std::true_type{});
+    }
+    for (; kt < nk; ++kt) {
+        const int younger = nk - 1 - kt;
+        if (NSTAGE >= 4 && younger >= 2) wait_vmcnt<2 * LPW>();
+        else if (NSTAGE >= 3 && younger >= 1) wait_vmcnt<LPW>();
+        else wait_vmcnt<0>();
         __syncthreads();
+        k_tile(kt, std::false_type{});
     }
 
     // ---- epilogue -------------------------------------------------------------
@@ -236,12 +312,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_fast_kernel(
     }
 }
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, bool SWAP, int ACT>
+template <int WAVES_M, int WAVES_N, int TM, int TN, int BKT, int NSTAGE, bool SWAP, int ACT>
 static int32_t launch_fast(const GemmArgs &a, hipStream_t st)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-    auto kern = gemm_bf16_fast_kernel<WAVES_M, WAVES_N, TM, TN, SWAP, ACT>;
-    constexpr size_t lds = (size_t)2 * (BM + BN) * FBK * sizeof(__bf16);
+    auto kern = gemm_bf16_fast_kernel<WAVES_M, WAVES_N, TM, TN, BKT, NSTAGE, SWAP, ACT>;
+    constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * BKT * sizeof(__bf16);
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -256,6 +332,15 @@ static int32_t launch_fast(const GemmArgs &a, hipStream_t st)
     hipLaunchKernelGGL(kern, dim3(per_xcd * N_XCD), dim3(64 * WAVES_M * WAVES_N), lds, st, a, tiles_m, tiles_n,
                        total, per_xcd);
     return SF_OK;
+}
+
+#define SMALLCFG 2, 2, 2, 2, 64, 2
+
+#define BIGCFG 2, 4, 4, 2, 64, 2
+template <bool SWAP, int ACT>
+static int32_t launch_big(const GemmArgs &a, hipStream_t st)
+{
+    return launch_fast<BIGCFG, SWAP, ACT>(a, st);
 }
 
 // Returns SF_OK and sets `done` when the fast kernel took the problem.
@@ -276,16 +361,16 @@ int32_t gemm_bf16_fast(const GemmArgs &a, hipStream_t st, bool &done)
     const bool big = a.L >= 192 && a.N >= 192;
     if (swap) {
         if (a.act != ACT_NONE) { done = false; return SF_OK; }
-        if (big) return launch_fast<2, 4, 4, 2, true, ACT_NONE>(a, st);
-        return launch_fast<2, 2, 2, 2, true, ACT_NONE>(a, st);
+        if (big) return launch_big<true, ACT_NONE>(a, st);
+        return launch_fast<SMALLCFG, true, ACT_NONE>(a, st);
     }
     switch (a.act) {
     case ACT_RELU:
-        return big ? launch_fast<2, 4, 4, 2, false, ACT_RELU>(a, st) : launch_fast<2, 2, 2, 2, false, ACT_RELU>(a, st);
+        return big ? launch_big<false, ACT_RELU>(a, st) : launch_fast<SMALLCFG, false, ACT_RELU>(a, st);
     case ACT_GELU:
-        return big ? launch_fast<2, 4, 4, 2, false, ACT_GELU>(a, st) : launch_fast<2, 2, 2, 2, false, ACT_GELU>(a, st);
+        return big ? launch_big<false, ACT_GELU>(a, st) : launch_fast<SMALLCFG, false, ACT_GELU>(a, st);
     default:
-        return big ? launch_fast<2, 4, 4, 2, false, ACT_NONE>(a, st) : launch_fast<2, 2, 2, 2, false, ACT_NONE>(a, st);
+        return big ? launch_big<false, ACT_NONE>(a, st) : launch_fast<SMALLCFG, false, ACT_NONE>(a, st);
     }
 }
 
