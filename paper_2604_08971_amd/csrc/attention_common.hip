@@ -42,6 +42,55 @@ __global__ __launch_bounds__(256) void kv_stats_partial_kernel(
     }
 }
 
+// bf16 variant with 16-byte loads: K rows are dh-contiguous, V is read from
+// its key-contiguous transposed layout [dh][Lp].  Same outputs as above.
+template <int DH>
+__global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
+    const __bf16 *__restrict__ K, sf_strides sk, const __bf16 *__restrict__ VT, sf_strides svt,
+    const uint8_t *__restrict__ key_valid, int nG, int L, float *__restrict__ part)
+{
+    constexpr int CH = DH / 8, RP = 256 / CH, TPR = 256 / DH;
+    __shared__ float red[RP][DH];
+    const int bg = blockIdx.y, b = bg / nG, g = bg % nG, tid = threadIdx.x;
+    const int j0 = blockIdx.x * STAT_CHUNK, j1 = min(L, j0 + STAT_CHUNK);
+    const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const __bf16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    float *o = part + (((int64_t)bg * gridDim.x + blockIdx.x) * 2) * DH;
+
+    {   // column sums of K over the allowed keys of this chunk
+        const int r = tid / CH, c = tid % CH;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int j = j0 + r; j < j1; j += RP) {
+            if (kv && !kv[j]) continue;
+            const bf16x8 t = *reinterpret_cast<const bf16x8 *>(Kb + (int64_t)j * sk.l + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += (float)t[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[r][c * 8 + e] = acc[e];
+        __syncthreads();
+        if (tid < DH) {
+            float s = 0.f;
+            for (int rr = 0; rr < RP; ++rr) s += red[rr][tid];
+            o[tid] = s;
+        }
+    }
+    {   // row sums of V^T over the allowed keys of this chunk
+        const int e = tid / TPR, q = tid % TPR;
+        float s = 0.f;
+        for (int j = j0 + q * 8; j < j1; j += TPR * 8) {
+            const bf16x8 t = *reinterpret_cast<const bf16x8 *>(Vb + (int64_t)e * svt.l + j);   // j + 8 <= Lp
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (j + u < j1 && (!kv || kv[j + u])) s += (float)t[u];
+        }
+#pragma unroll
+        for (int w = 1; w < TPR; w <<= 1) s += __shfl_xor(s, w);
+        if (q == 0) o[DH + e] = s;
+    }
+}
+
 // stats[bg][0][:] = mean allowed key, stats[bg][1][:] = mean allowed value.
 __global__ __launch_bounds__(256) void kv_stats_final_kernel(
     const float *__restrict__ part, int chunks, const uint8_t *__restrict__ key_valid, int nG, int L,
@@ -74,7 +123,8 @@ __global__ __launch_bounds__(256) void select_kernel(
     int U, int32_t *__restrict__ sel, int selH, int32_t *__restrict__ slot)
 {
     extern __shared__ uint32_t keys[];
-    __shared__ int red[4];
+    __shared__ int scratch[TOPK_SCRATCH];
+    __shared__ int red[4];          // not part of `scratch`: block_topk clears its histogram there right away
     const int bh = blockIdx.x, b = bh / nH, h = bh % nH;
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     const float *M = score ? score + ((int64_t)b * scoreH + h) * L : nullptr;
@@ -92,7 +142,7 @@ __global__ __launch_bounds__(256) void select_kernel(
     if (k == 0) {
         for (int i = threadIdx.x; i < L; i += 256) sl[i] = -1;
     } else {
-        block_topk<256>(keys, L, k, red, [&](int i, bool kept, int pos) {
+        block_topk<256>(keys, L, k, scratch, [&](int i, bool kept, int pos) {
             sl[i] = kept ? pos : -1;
             if (kept) se[pos] = i;
         });
@@ -120,8 +170,8 @@ __global__ __launch_bounds__(256) void forced_slot_kernel(const int32_t *__restr
 // ------------------------------------------------------------------------ fill
 // Every row that is not active takes its group's context vector; when the
 // active pass ran split over the keys, the partial results are merged here.
-// One thread per 4 consecutive output elements.
-template <class T>
+// One thread per VEC consecutive output elements (VEC = 8 when dh % 8 == 0).
+template <class T, int VEC>
 __global__ __launch_bounds__(256) void fill_kernel(
     int nH, int nG, int L, int dh, int Upad, int splits, const int32_t *__restrict__ slot,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
@@ -129,20 +179,20 @@ __global__ __launch_bounds__(256) void fill_kernel(
     T *__restrict__ O, int64_t ldo)
 {
     const int b = blockIdx.y;
-    const int q4 = dh / 4;
+    const int qv = dh / VEC;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)L * nH * q4) return;
-    const int e = (int)(idx % q4) * 4;
-    const int h = (int)((idx / q4) % nH);
-    const int i = (int)(idx / ((int64_t)q4 * nH));
+    if (idx >= (int64_t)L * nH * qv) return;
+    const int e = (int)(idx % qv) * VEC;
+    const int h = (int)((idx / qv) % nH);
+    const int i = (int)(idx / ((int64_t)qv * nH));
     const int s = slot[((int64_t)b * nH + h) * L + i];
-    float v[4];
+    float v[VEC];
     if (s < 0) {
         const int p = pattern_id ? pattern_id[b] : 0;
         const int g = head_group[(int64_t)p * hg_stride + h];
         const float *ctx = stats + (((int64_t)b * nG + g) * 2 + 1) * dh + e;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) v[t] = ctx[t];
+        for (int t = 0; t < VEC; ++t) v[t] = ctx[t];
     } else {
         if (splits <= 1) return;                       // written by the active pass
         const int64_t base = (((int64_t)b * nH + h) * Upad + s) * splits;
@@ -150,22 +200,29 @@ __global__ __launch_bounds__(256) void fill_kernel(
         for (int sp = 0; sp < splits; ++sp) m = fmaxf(m, part_ml[(base + sp) * 2]);
         float den = 0.f;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) v[t] = 0.f;
+        for (int t = 0; t < VEC; ++t) v[t] = 0.f;
         for (int sp = 0; sp < splits; ++sp) {
             const float ms = part_ml[(base + sp) * 2];
             const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
             den += w * part_ml[(base + sp) * 2 + 1];
             const float *po = part_o + (base + sp) * dh + e;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) v[t] += w * po[t];
+            for (int t = 0; t < VEC; ++t) v[t] += w * po[t];
         }
         const float inv = den > 0.f ? 1.0f / den : 0.f;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) v[t] *= inv;
+        for (int t = 0; t < VEC; ++t) v[t] *= inv;
     }
     T *o = O + ((int64_t)b * L + i) * ldo + (int64_t)h * dh + e;
+    if constexpr (sizeof(T) == 2 && VEC == 8) {
+        bf16x8 ov;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) o[t] = from_f32<T>(v[t]);
+        for (int t = 0; t < 8; ++t) ov[t] = (__bf16)v[t];
+        *reinterpret_cast<bf16x8 *>(o) = ov;                 // ldo % 8 == 0 and 16-byte aligned O checked on the host
+    } else {
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) o[t] = from_f32<T>(v[t]);
+    }
 }
 
 // V [B,nG,L,dh] -> VT [B,nG,dh,Lp] (bf16), 32x32 tiles through LDS.
@@ -348,7 +405,16 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         int DHP = 4;
         while (DHP < a.dh) DHP *= 2;
         dim3 grid(pl.stat_chunks, BG);
-        if (dtype == SF_BF16)
+        if (dtype == SF_BF16 && vT && a.dh == 32)
+            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<32>, grid, dim3(256), 0, st, (const __bf16 *)a.K, a.sk,
+                               (const __bf16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+        else if (dtype == SF_BF16 && vT && a.dh == 64)
+            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<64>, grid, dim3(256), 0, st, (const __bf16 *)a.K, a.sk,
+                               (const __bf16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+        else if (dtype == SF_BF16 && vT && a.dh == 128)
+            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<128>, grid, dim3(256), 0, st, (const __bf16 *)a.K, a.sk,
+                               (const __bf16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+        else if (dtype == SF_BF16)
             hipLaunchKernelGGL(kv_stats_partial_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)a.K,
                                a.sk, (const __bf16 *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
                                DHP, pl.stat_part);
@@ -402,16 +468,15 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
 
     // 4. lazy rows (+ merge of the key splits)
     {
-        const int64_t n = (int64_t)a.L * a.nH * (a.dh / 4);
+        const bool v8 = dtype == SF_BF16 && a.dh % 8 == 0 && a.ldo % 8 == 0 && ((uintptr_t)a.O % 16 == 0);
+        const int64_t n = (int64_t)a.L * a.nH * (a.dh / (v8 ? 8 : 4));
         dim3 grid((unsigned)((n + 255) / 256), a.B);
-        if (dtype == SF_BF16)
-            hipLaunchKernelGGL(fill_kernel<__bf16>, grid, dim3(256), 0, st, a.nH, a.nG, a.L, a.dh, pl.Upad,
-                               pl.splits, pl.slot, a.head_group, a.hg_stride, a.pattern_id, pl.stats,
-                               pl.part_o, pl.part_ml, (__bf16 *)a.O, a.ldo);
-        else
-            hipLaunchKernelGGL(fill_kernel<float>, grid, dim3(256), 0, st, a.nH, a.nG, a.L, a.dh, pl.Upad,
-                               pl.splits, pl.slot, a.head_group, a.hg_stride, a.pattern_id, pl.stats,
-                               pl.part_o, pl.part_ml, (float *)a.O, a.ldo);
+#define SF_FILL_ARGS grid, dim3(256), 0, st, a.nH, a.nG, a.L, a.dh, pl.Upad, pl.splits, pl.slot, a.head_group, \
+                     a.hg_stride, a.pattern_id, pl.stats, pl.part_o, pl.part_ml
+        if (dtype == SF_BF16 && v8) hipLaunchKernelGGL((fill_kernel<__bf16, 8>), SF_FILL_ARGS, (__bf16 *)a.O, a.ldo);
+        else if (dtype == SF_BF16) hipLaunchKernelGGL((fill_kernel<__bf16, 4>), SF_FILL_ARGS, (__bf16 *)a.O, a.ldo);
+        else hipLaunchKernelGGL((fill_kernel<float, 4>), SF_FILL_ARGS, (float *)a.O, a.ldo);
+#undef SF_FILL_ARGS
     }
     return check_launch("sparse_gqa_forward");
 }

@@ -107,20 +107,103 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const TI *x, const TP *_
     }
 }
 
+// Vector variant for d % 8 == 0 and d <= 64 * 8 * NCH: the row is read once with
+// 16/32-byte loads, kept in registers for both statistics passes, and written
+// with 16-byte stores.  One wave per row, 4 rows per block.
+template <class TI, class TP, class TO, int NCH>
+__global__ __launch_bounds__(256) void layernorm_vec_kernel(const TI *x, const TP *__restrict__ gamma,
+                                                            const TP *__restrict__ beta, float eps, int64_t rows,
+                                                            int d, TO *y)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const TI *xr = x + row * d;
+    TO *yr = y + row * d;
+    const int nch = d >> 3;                       // chunks of 8 elements
+    float v[NCH][8];
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int ch = lane + c * 64;
+        if (ch < nch) {
+            if constexpr (sizeof(TI) == 2) {
+                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(xr + ch * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[c][e] = (float)t[e];
+            } else {
+                const f32x4 t0 = *reinterpret_cast<const f32x4 *>(xr + ch * 8);
+                const f32x4 t1 = *reinterpret_cast<const f32x4 *>(xr + ch * 8 + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[c][e] = t0[e]; v[c][4 + e] = t1[e]; }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += v[c][e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mean = s / d;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+        if (lane + c * 64 < nch) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float t = v[c][e] - mean; q += t * t; }
+        }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    const float inv = 1.0f / sqrtf(q / d + eps);
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int ch = lane + c * 64;
+        if (ch >= nch) continue;
+        float z[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            z[e] = (v[c][e] - mean) * inv;
+            if (gamma) z[e] *= to_f32(gamma[ch * 8 + e]);
+            if (beta) z[e] += to_f32(beta[ch * 8 + e]);
+        }
+        if constexpr (sizeof(TO) == 2) {
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)z[e];
+            *reinterpret_cast<bf16x8 *>(yr + ch * 8) = o;
+        } else {
+            f32x4 o0, o1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { o0[e] = z[e]; o1[e] = z[4 + e]; }
+            *reinterpret_cast<f32x4 *>(yr + ch * 8) = o0;
+            *reinterpret_cast<f32x4 *>(yr + ch * 8 + 4) = o1;
+        }
+    }
+}
+
+template <class TI, class TP, class TO>
+static void launch_ln(const void *x, const void *gamma, const void *beta, float eps, int64_t rows, int d, void *y,
+                      hipStream_t st)
+{
+    dim3 grid((unsigned)((rows + 3) / 4));
+    const bool vec = d % 8 == 0 && ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 16 == 0);
+#define SF_LN_ARGS grid, dim3(256), 0, st, (const TI *)x, (const TP *)gamma, (const TP *)beta, eps, rows, d, (TO *)y
+    if (vec && d <= 512) hipLaunchKernelGGL((layernorm_vec_kernel<TI, TP, TO, 1>), SF_LN_ARGS);
+    else if (vec && d <= 1024) hipLaunchKernelGGL((layernorm_vec_kernel<TI, TP, TO, 2>), SF_LN_ARGS);
+    else if (vec && d <= 2048) hipLaunchKernelGGL((layernorm_vec_kernel<TI, TP, TO, 4>), SF_LN_ARGS);
+    else hipLaunchKernelGGL((layernorm_kernel<TI, TP, TO>), SF_LN_ARGS);
+#undef SF_LN_ARGS
+}
+
 void layernorm(int dtype, int x_f32, const void *x, const void *gamma, const void *beta, float eps,
                int64_t rows, int d, void *y, hipStream_t st)
 {
     if (rows <= 0) return;
-    dim3 grid((unsigned)((rows + 3) / 4));
-    if (dtype == SF_BF16 && !x_f32)
-        hipLaunchKernelGGL((layernorm_kernel<__bf16, __bf16, __bf16>), grid, dim3(256), 0, st, (const __bf16 *)x,
-                           (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, (__bf16 *)y);
-    else if (dtype == SF_BF16)
-        hipLaunchKernelGGL((layernorm_kernel<float, __bf16, __bf16>), grid, dim3(256), 0, st, (const float *)x,
-                           (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, (__bf16 *)y);
-    else
-        hipLaunchKernelGGL((layernorm_kernel<float, float, float>), grid, dim3(256), 0, st, (const float *)x,
-                           (const float *)gamma, (const float *)beta, eps, rows, d, (float *)y);
+    if (dtype == SF_BF16 && !x_f32) launch_ln<__bf16, __bf16, __bf16>(x, gamma, beta, eps, rows, d, y, st);
+    else if (dtype == SF_BF16) launch_ln<float, __bf16, __bf16>(x, gamma, beta, eps, rows, d, y, st);
+    else launch_ln<float, float, float>(x, gamma, beta, eps, rows, d, y, st);
 }
 
 }  // namespace sf

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(MASK_NT) void keep_topk_kernel(
     int32_t *__restrict__ n_groups, int32_t *__restrict__ head_group)
 {
     extern __shared__ uint32_t keys[];
-    __shared__ int red[MASK_NT / 64];
+    __shared__ int scratch[TOPK_SCRATCH];
     const int lp = blockIdx.x;
     const int k = kc.k[lp / P];
     const float *gs = g + (size_t)lp * n;
@@ -28,7 +28,7 @@ __global__ __launch_bounds__(MASK_NT) void keep_topk_kernel(
 
     for (int i = threadIdx.x; i < n; i += MASK_NT) keys[i] = sortable_key(gs[i]);
     __syncthreads();
-    block_topk<MASK_NT>(keys, n, k, red, [&](int i, bool kept, int pos) {
+    block_topk<MASK_NT>(keys, n, k, scratch, [&](int i, bool kept, int pos) {
         m[i] = kept ? 1 : 0;
         if (kept) ix[pos] = i;
     });

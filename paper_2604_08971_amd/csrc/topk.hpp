@@ -1,11 +1,19 @@
 // Block-wide exact top-k selection over keys held in LDS, with the tie rule
 // "higher key first, then lower index".  Used for the gate-score keep sets
 // (Sec. 4.5) and for the top-U query choice of SentryAttend (Sec. 4.4).
+//
+// The k-th largest key is found by a 4-pass radix select (8 bits per pass, a
+// 256-bin LDS histogram with integer atomics: the counts, hence the result,
+// do not depend on the order of the atomics).  The kept indices are then
+// emitted in ascending order from contiguous per-thread index ranges with two
+// block-wide prefix sums.
 #pragma once
 
 #include "common.hpp"
 
 namespace sf {
+
+constexpr int TOPK_SCRATCH = 256 + 16 + 2;      // ints of LDS scratch block_topk needs
 
 // Sum of one int per thread over the block; every thread gets the total.
 // `red` is LDS scratch of at least NT/64 ints.
@@ -23,16 +31,20 @@ __device__ __forceinline__ int block_sum(int v, int *red)
     return t;
 }
 
-// Exclusive prefix count of a 0/1 flag in thread order; `total` gets the block
-// total.  `red` is LDS scratch of at least NT/64 ints.
+// Exclusive prefix sum of one int per thread in thread order; `total` gets the
+// block total.  `red` is LDS scratch of at least NT/64 ints.
 template <int NT>
-__device__ __forceinline__ int block_excl_count(bool flag, int *red, int &total)
+__device__ __forceinline__ int block_excl_scan(int v, int *red, int &total)
 {
-    const unsigned long long bal = __ballot(flag);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int below = __popcll(bal & ((1ull << lane) - 1ull));
+    int x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(x, o);
+        if (lane >= o) x += t;
+    }
     __syncthreads();
-    if (lane == 0) red[w] = __popcll(bal);
+    if (lane == 63) red[w] = x;
     __syncthreads();
     int off = 0, t = 0;
 #pragma unroll
@@ -42,41 +54,77 @@ __device__ __forceinline__ int block_excl_count(bool flag, int *red, int &total)
         t += c;
     }
     total = t;
-    return off + below;
+    return off + x - v;
 }
 
 // keys[0..n) in LDS (already synchronised).  Selects the k largest
 // (1 <= k <= n).  For every index i, in ascending order within a thread,
 // calls emit(i, kept, pos) where pos is the rank of i among the kept indices
-// (ascending index order) when kept.  Must be called by all NT threads.
+// (ascending index order) when kept.  Must be called by all NT threads;
+// `scratch` is LDS of TOPK_SCRATCH ints.
 template <int NT, class Emit>
-__device__ void block_topk(const uint32_t *keys, int n, int k, int *red, Emit emit)
+__device__ void block_topk(const uint32_t *keys, int n, int k, int *scratch, Emit emit)
 {
-    // k-th largest key: the largest T with #{key >= T} >= k, built bit by bit
-    uint32_t T = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = T | (1u << bit);
-        int c = 0;
-        for (int i = threadIdx.x; i < n; i += NT) c += keys[i] >= cand;
-        if (block_sum<NT>(c, red) >= k) T = cand;
-    }
-    int c = 0;
-    for (int i = threadIdx.x; i < n; i += NT) c += keys[i] > T;
-    const int need = k - block_sum<NT>(c, red);     // how many keys == T are kept (lowest indices)
+    int *hist = scratch, *red = scratch + 256, *res = scratch + 256 + 16;
+    const int tid = threadIdx.x, lane = tid & 63;
+    __syncthreads();        // nobody may still be reading `scratch` (or writing `keys`) from before the call
 
-    int eq_base = 0, kept_base = 0;
-    for (int i0 = 0; i0 < n; i0 += NT) {
-        const int i = i0 + threadIdx.x;
-        const bool in = i < n;
-        const uint32_t key = in ? keys[i] : 0u;
-        const bool eq = in && key == T;
-        int eq_total, kept_total;
-        const int eq_rank = eq_base + block_excl_count<NT>(eq, red, eq_total);
-        const bool kept = in && (key > T || (eq && eq_rank < need));
-        const int pos = kept_base + block_excl_count<NT>(kept, red, kept_total);
-        if (in) emit(i, kept, pos);
-        eq_base += eq_total;
-        kept_base += kept_total;
+    // k-th largest key T, most significant byte first
+    uint32_t prefix = 0, mask = 0;
+    int kk = k;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int j = tid; j < 256; j += NT) hist[j] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += NT) {
+            const uint32_t key = keys[i];
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane owns bins 4*lane .. 4*lane+3; find the bin holding the kk-th largest candidate
+            int h[4], local = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { h[j] = hist[4 * lane + j]; local += h[j]; }
+            int incl = local;                       // becomes the sum over lanes >= lane
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_down(incl, o);
+                if (lane + o < 64) incl += t;
+            }
+            int run = incl - local;                 // candidates in strictly higher bins
+#pragma unroll
+            for (int j = 3; j >= 0; --j) {
+                if (run < kk && run + h[j] >= kk) { res[0] = 4 * lane + j; res[1] = kk - run; }
+                run += h[j];
+            }
+        }
+        __syncthreads();
+        prefix |= (uint32_t)res[0] << shift;
+        mask |= 255u << shift;
+        kk = res[1];
+        __syncthreads();                            // res is rewritten in the next pass
+    }
+    const uint32_t T = prefix;
+    const int need = kk;                            // how many keys == T are kept (lowest indices)
+
+    // emit in ascending index order: thread t owns indices [t*E, (t+1)*E)
+    const int E = (n + NT - 1) / NT;
+    const int i0 = min(n, tid * E), i1 = min(n, i0 + E);
+    int c_gt = 0, c_eq = 0;
+    for (int i = i0; i < i1; ++i) { const uint32_t key = keys[i]; c_gt += key > T; c_eq += key == T; }
+    int tot;
+    const int eq_before = block_excl_scan<NT>(c_eq, red, tot);
+    const int eq_kept = max(0, min(c_eq, need - eq_before));
+    int pos = block_excl_scan<NT>(c_gt + eq_kept, red, tot);
+    int eqr = eq_before;
+    for (int i = i0; i < i1; ++i) {
+        const uint32_t key = keys[i];
+        const bool eq = key == T;
+        const bool kept = key > T || (eq && eqr < need);
+        eqr += eq;
+        emit(i, kept, pos);
+        pos += kept;
     }
 }
 

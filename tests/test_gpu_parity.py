@@ -291,7 +291,7 @@ def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
 
 
 # ------------------------------------------------------------ a10: encoder
-def _encoder_parity(wl, samples=None, U_override=-1, max_diff_frac=0.25):
+def _encoder_parity(wl, samples=None, U_override=-1, max_pick_diff_frac=0.03):
     s = wl.spec
     bf = s.dtype == "bf16"
     dm = DeviceModel(wl, U_override=U_override).build_plan()
@@ -314,7 +314,7 @@ def _encoder_parity(wl, samples=None, U_override=-1, max_diff_frac=0.25):
     y_ref, sel_chk, score_f = orc.encoder_forward(wl.x[samples], packs, U, wl.pattern_id[samples], kv, act=s.act,
                                                   forced_sel=sel[:, samples], final_ln=wl.final_ln, bf16=bf,
                                                   want_score=True)
-    n_diff = n_tot = 0
+    n_diff = n_tot = picks_diff = picks_tot = 0
     if 0 < U < s.L:
         for l in range(s.n_layers):
             for bi, b in enumerate(samples):
@@ -327,14 +327,16 @@ def _encoder_parity(wl, samples=None, U_override=-1, max_diff_frac=0.25):
                     assert ok, (l, b, h)
                     n_diff += diff
                     n_tot += 1
+                    picks_diff += len(np.setdiff1d(sel[l, b, h][sel[l, b, h] >= 0], ref_sel))
+                    picks_tot += len(ref_sel)
     e = err_metric(Y[samples], y_ref)
-    _say(f"   encoder {s.name}: err {e:.3e}, selections differing {n_diff}/{n_tot}, "
-         f"err vs oracle's own choice {err_metric(Y[samples], y_own):.3e}")
+    _say(f"   encoder {s.name}: err {e:.3e}, (sample, head, layer) sets differing {n_diff}/{n_tot}, "
+         f"picks differing {picks_diff}/{picks_tot}, err vs oracle's own choice {err_metric(Y[samples], y_own):.3e}")
     assert e <= TOL[s.dtype], e
     # Inside the bf16 stack Q and K carry 1-ulp rounding differences, so near-ties at the
     # U-th score may resolve differently (each such choice passed the margin check above);
-    # they must stay a minority.  In fp32 the choice must be identical.
-    assert n_diff <= max(1, int(max_diff_frac * n_tot)), (n_diff, n_tot)
+    # only a few of the picked queries may differ.  In fp32 the choice must be identical.
+    assert picks_diff <= max(2, int(max_pick_diff_frac * picks_tot)), (picks_diff, picks_tot)
     if s.dtype == "f32":
         assert n_diff == 0
     return e
