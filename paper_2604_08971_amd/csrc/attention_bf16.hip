@@ -48,11 +48,59 @@ __device__ __forceinline__ void stage_k_tile(const __bf16 *Kb, int64_t sl, int j
     }
 }
 
+// List of the 64-key tiles of [jbeg, jend) that contain at least one allowed key (ascending),
+// built by the first wave; returns the count through *n_tiles.  Needs `words` complete.
+__device__ __forceinline__ void build_tile_list(const uint32_t *words, int nwords, int jbeg, int jend,
+                                                uint16_t *tiles, int *n_tiles)
+{
+    if (threadIdx.x < 64) {
+        int base = 0;
+        for (int t0 = jbeg / BKEY; t0 * BKEY < jend; t0 += 64) {
+            const int t = t0 + (int)threadIdx.x;
+            bool live = false;
+            if (t * BKEY < jend) {
+                const uint32_t w0 = words[2 * t], w1 = (2 * t + 1 < nwords) ? words[2 * t + 1] : 0u;
+                live = (w0 | w1) != 0u;
+            }
+            const unsigned long long bal = __ballot(live);
+            if (live) tiles[base + __popcll(bal & ((1ull << threadIdx.x) - 1ull))] = (uint16_t)t;
+            base += __popcll(bal);
+        }
+        if (threadIdx.x == 0) *n_tiles = base;
+    }
+}
+
+// K tile chunks of this thread -> registers (rows at or beyond L are zero)
+template <int DH>
+__device__ __forceinline__ void fetch_k_tile(const __bf16 *Kb, int64_t sl, int j0, int L, uint4 (&r)[BKEY * (DH / 8) / (NWAVE * 64)])
+{
+    constexpr int CH = DH / 8, N = BKEY * CH / (NWAVE * 64);
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+        const int c = threadIdx.x + u * NWAVE * 64;
+        const int row = c / CH, cc = c % CH;
+        const int j = j0 + row;
+        r[u] = (j < L) ? *reinterpret_cast<const uint4 *>(Kb + (int64_t)j * sl + cc * 8) : make_uint4(0, 0, 0, 0);
+    }
+}
+template <int DH>
+__device__ __forceinline__ void put_k_tile(const uint4 (&r)[BKEY * (DH / 8) / (NWAVE * 64)], __bf16 *Ks)
+{
+    constexpr int CH = DH / 8, N = BKEY * CH / (NWAVE * 64);
+#pragma unroll
+    for (int u = 0; u < N; ++u) {
+        const int c = threadIdx.x + u * NWAVE * 64;
+        *reinterpret_cast<uint4 *>(Ks + (c / CH) * (DH + PAD) + (c % CH) * 8) = r[u];
+    }
+}
+
 // ------------------------------------------------------------- sparsity score
 // M_i = max_j s_ij - mean_j s_ij over allowed keys.  The max comes from the
 // streamed S^T tiles; the mean is q_i . mean_key (computed once per group),
 // which is the same number up to fp32 rounding.
-// grid (query blocks, B*nH); each wave owns QBS blocks of 32 queries.
+// grid (query blocks, B*nH); each wave owns QBS blocks of 32 queries.  K tiles
+// are double-buffered in LDS and the next tile is prefetched into registers
+// while the current one is multiplied, so one barrier per tile suffices.
 template <int DH, int QBS>
 __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
     const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
@@ -61,9 +109,11 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
     float *__restrict__ score, int scoreH)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                              // [BKEY][DH+PAD]
-    float *kbar = reinterpret_cast<float *>(Ks + BKEY * (DH + PAD));            // [DH]
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                              // [2][BKEY][DH+PAD]
+    float *kbar = reinterpret_cast<float *>(Ks + 2 * BKEY * (DH + PAD));        // [DH]
     uint32_t *words = reinterpret_cast<uint32_t *>(kbar + DH);                  // [ceil(L/32)]
+    uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (L + 31) / 32);      // [ceil(L/64)]
+    __shared__ int n_tiles;
 
     const int bh = blockIdx.y, b = bh / nH, h = bh % nH;
     const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
@@ -88,12 +138,19 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
         rmax[qq] = -INFINITY;
     }
     __syncthreads();
+    build_tile_list(words, nwords, 0, L, tiles, &n_tiles);
+    __syncthreads();
+    const int nt = n_tiles;
 
-    for (int j0 = 0; j0 < L; j0 += BKEY) {
+    uint4 kreg[BKEY * (DH / 8) / (NWAVE * 64)];
+    if (nt > 0) fetch_k_tile<DH>(Kb, sk.l, tiles[0] * BKEY, L, kreg);
+    for (int it = 0; it < nt; ++it) {
+        const int j0 = tiles[it] * BKEY;
+        __bf16 *Kt = Ks + (it & 1) * BKEY * (DH + PAD);
+        put_k_tile<DH>(kreg, Kt);
+        __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffer)
+        if (it + 1 < nt) fetch_k_tile<DH>(Kb, sk.l, tiles[it + 1] * BKEY, L, kreg);
         const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
-        if ((w0 | w1) == 0u) continue;                     // uniform: the whole tile is disallowed
-        stage_k_tile<DH>(Kb, sk.l, j0, L, Ks);
-        __syncthreads();
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             const uint32_t w = kb ? w1 : w0;
@@ -101,7 +158,7 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
             bf16x8 kf[DH / 16];
 #pragma unroll
             for (int kk = 0; kk < DH / 16; ++kk)
-                kf[kk] = *reinterpret_cast<const bf16x8 *>(Ks + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+                kf[kk] = *reinterpret_cast<const bf16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
             const uint32_t wl = w >> (lhi * 4);
 #pragma unroll
             for (int qq = 0; qq < QBS; ++qq) {
@@ -123,7 +180,6 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
                 rmax[qq] = m;
             }
         }
-        __syncthreads();
     }
 
     const float scale = 1.0f / sqrtf((float)DH);
@@ -362,7 +418,8 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
 template <int DH, int QBS>
 static int32_t launch_score(const AttnArgs &a, const AttnPlan &pl, float *score, int scoreH, hipStream_t st)
 {
-    const size_t lds = (size_t)BKEY * (DH + PAD) * 2 + DH * 4 + (size_t)ceil_div(a.L, 32) * 4;
+    const size_t lds = (size_t)2 * BKEY * (DH + PAD) * 2 + DH * 4 + (size_t)ceil_div(a.L, 32) * 4 +
+                       (size_t)ceil_div(a.L, BKEY) * 2 + 16;
     dim3 grid(ceil_div(a.L, NWAVE * QBS * 32), a.B * a.nH);
     ProfScope prof(SF_KERNEL_SCORE, st);
     hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
