@@ -214,11 +214,13 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
     float *__restrict__ part_ml)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                         // [BKEY][DH+PAD]
-    __bf16 *Vs = Ks + BKEY * (DH + PAD);                                   // [DH][BKEY+PAD]
-    uint32_t *words = reinterpret_cast<uint32_t *>(Vs + DH * (BKEY + PAD));   // [ceil(L/32)]
+    constexpr int KT = BKEY * (DH + PAD), VT_ = DH * (BKEY + PAD);          // elements of one K / V^T tile
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                         // [2][BKEY][DH+PAD]
+    __bf16 *Vs = Ks + 2 * KT;                                              // [2][DH][BKEY+PAD]
+    uint32_t *words = reinterpret_cast<uint32_t *>(Vs + 2 * VT_);          // [ceil(L/32)]
+    uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (L + 31) / 32); // [ceil(L/64)]
     __shared__ int heads[64];
-    __shared__ int n_heads;
+    __shared__ int n_heads, n_tiles;
 
     const int bg = blockIdx.y, b = bg / nG, g = bg % nG, sp = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
@@ -274,12 +276,12 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
     const float sc = LOG2E / sqrtf((float)DH);
     const int jbeg = sp * keys_per_split, jend = min(L, jbeg + keys_per_split);
 
-    for (int j0 = jbeg; j0 < jend; j0 += BKEY) {
-        const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
-        if ((w0 | w1) == 0u) continue;                    // uniform
-        stage_k_tile<DH>(Kb, sk.l, j0, L, Ks);
-        // V^T tile [DH][BKEY]: key-contiguous rows; keys at or beyond L are zeroed
-        for (int c = threadIdx.x; c < DH * (BKEY / 8); c += NWAVE * 64) {
+    // V^T tile chunks of this thread -> registers; keys at or beyond L are zeroed
+    constexpr int NV = DH * (BKEY / 8) / (NWAVE * 64);
+    auto fetch_v = [&](int j0, uint4 (&r)[NV]) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int c = threadIdx.x + u * NWAVE * 64;
             const int e = c / (BKEY / 8), cc = c % (BKEY / 8);
             const int j = j0 + cc * 8;
             uint4 v = make_uint4(0, 0, 0, 0);
@@ -292,9 +294,31 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
                         if (j + t >= L) hv[t] = 0;
                 }
             }
-            *reinterpret_cast<uint4 *>(Vs + e * (BKEY + PAD) + cc * 8) = v;
+            r[u] = v;
         }
-        __syncthreads();
+    };
+    auto put_v = [&](const uint4 (&r)[NV], __bf16 *Vt) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int c = threadIdx.x + u * NWAVE * 64;
+            *reinterpret_cast<uint4 *>(Vt + (c / (BKEY / 8)) * (BKEY + PAD) + (c % (BKEY / 8)) * 8) = r[u];
+        }
+    };
+
+    build_tile_list(words, nwords, jbeg, jend, tiles, &n_tiles);
+    __syncthreads();
+    const int nt = n_tiles;
+    uint4 kreg[BKEY * (DH / 8) / (NWAVE * 64)], vreg[NV];
+    if (nt > 0) { fetch_k_tile<DH>(Kb, sk.l, tiles[0] * BKEY, L, kreg); fetch_v(tiles[0] * BKEY, vreg); }
+
+    for (int it = 0; it < nt; ++it) {
+        const int j0 = tiles[it] * BKEY;
+        __bf16 *Kt = Ks + (it & 1) * KT, *Vt = Vs + (it & 1) * VT_;
+        put_k_tile<DH>(kreg, Kt);
+        put_v(vreg, Vt);
+        __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffers)
+        if (it + 1 < nt) { fetch_k_tile<DH>(Kb, sk.l, tiles[it + 1] * BKEY, L, kreg); fetch_v(tiles[it + 1] * BKEY, vreg); }
+        const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
 
         // S^T blocks for the two 32-key halves
         f32x16 s[QB][2];
@@ -303,7 +327,7 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
             bf16x8 kf[DH / 16];
 #pragma unroll
             for (int kk = 0; kk < DH / 16; ++kk)
-                kf[kk] = *reinterpret_cast<const bf16x8 *>(Ks + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+                kf[kk] = *reinterpret_cast<const bf16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
 #pragma unroll
             for (int qq = 0; qq < QB; ++qq) {
 #pragma unroll
@@ -363,7 +387,7 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
         for (int db = 0; db < DH / 32; ++db) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const __bf16 *vrow = Vs + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 4;
+                const __bf16 *vrow = Vt + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 4;
                 const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vrow);
                 const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vrow + 8);
                 bf16x8 vf;
@@ -374,7 +398,6 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
                     oacc[qq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qq][t], oacc[qq][db], 0, 0, 0);
             }
         }
-        __syncthreads();
     }
 
     // lane owns query l32 and output dims db*32 + ig*8 + lhi*4 + {0..3}
@@ -443,8 +466,8 @@ template <int DH, int QB>
 static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_strides svt,
                              const int32_t *sel, int selH, hipStream_t st)
 {
-    const size_t lds = (size_t)BKEY * (DH + PAD) * 2 + (size_t)DH * (BKEY + PAD) * 2 +
-                       (size_t)ceil_div(a.L, 32) * 4;
+    const size_t lds = (size_t)2 * BKEY * (DH + PAD) * 2 + (size_t)2 * DH * (BKEY + PAD) * 2 +
+                       (size_t)ceil_div(a.L, 32) * 4 + (size_t)ceil_div(a.L, BKEY) * 2 + 16;
     const int nqb = pl.Upad / 32;
     // upper bound on pairs of one group: every head in the same group
     dim3 grid(ceil_div(a.nH * nqb, NWAVE * QB), a.B * a.nG, pl.splits);

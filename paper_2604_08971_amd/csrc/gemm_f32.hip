@@ -107,6 +107,24 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const TI *x, const TP *_
     }
 }
 
+// 8 consecutive parameters as floats (`fill` when the vector is absent); 16-byte aligned offsets
+template <class TP>
+__device__ __forceinline__ void load8(const TP *p, int off, float fill, float (&out)[8])
+{
+    if (!p) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = fill;
+    } else if constexpr (sizeof(TP) == 2) {
+        const bf16x8 t = *reinterpret_cast<const bf16x8 *>(p + off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = (float)t[e];
+    } else {
+        const f32x4 t0 = *reinterpret_cast<const f32x4 *>(p + off), t1 = *reinterpret_cast<const f32x4 *>(p + off + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { out[e] = t0[e]; out[4 + e] = t1[e]; }
+    }
+}
+
 // Vector variant for d % 8 == 0 and d <= 64 * 8 * NCH: the row is read once with
 // 16/32-byte loads, kept in registers for both statistics passes, and written
 // with 16-byte stores.  One wave per row, 4 rows per block.
@@ -161,13 +179,11 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const TI *x, const T
     for (int c = 0; c < NCH; ++c) {
         const int ch = lane + c * 64;
         if (ch >= nch) continue;
-        float z[8];
+        float z[8], gm[8], bt[8];
+        load8(gamma, ch * 8, 1.f, gm);
+        load8(beta, ch * 8, 0.f, bt);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            z[e] = (v[c][e] - mean) * inv;
-            if (gamma) z[e] *= to_f32(gamma[ch * 8 + e]);
-            if (beta) z[e] += to_f32(beta[ch * 8 + e]);
-        }
+        for (int e = 0; e < 8; ++e) z[e] = (v[c][e] - mean) * inv * gm[e] + bt[e];
         if constexpr (sizeof(TO) == 2) {
             bf16x8 o;
 #pragma unroll
@@ -188,7 +204,8 @@ static void launch_ln(const void *x, const void *gamma, const void *beta, float 
                       hipStream_t st)
 {
     dim3 grid((unsigned)((rows + 3) / 4));
-    const bool vec = d % 8 == 0 && ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 16 == 0);
+    const bool vec = d % 8 == 0 && ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 16 == 0) &&
+                     ((uintptr_t)gamma % 16 == 0) && ((uintptr_t)beta % 16 == 0);
 #define SF_LN_ARGS grid, dim3(256), 0, st, (const TI *)x, (const TP *)gamma, (const TP *)beta, eps, rows, d, (TO *)y
     if (vec && d <= 512) hipLaunchKernelGGL((layernorm_vec_kernel<TI, TP, TO, 1>), SF_LN_ARGS);
     else if (vec && d <= 1024) hipLaunchKernelGGL((layernorm_vec_kernel<TI, TP, TO, 2>), SF_LN_ARGS);
