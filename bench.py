@@ -180,6 +180,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="only the headline number")
     ap.add_argument("--other-configs", default="C2,C3,C4", help="also time these (reported under `other_workloads`)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run one plain device copy of this many MiB (known traffic, for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (one MI355X holds every workload and no step of the path "
@@ -191,6 +194,16 @@ def main():
     from paper_2604_08971_amd import binding as sf
     from paper_2604_08971_amd import workloads as W
     sf.lib()
+
+    if args.copy_calibration > 0:
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"copy calibration: 3 device copies of {args.copy_calibration} MiB (reads and writes that many bytes each)")
+        del src, dst
 
     extras = not args.no_extras
     res, dm, wl, flops = bench_config(args.config, args.steps, args.warmup, extras, not args.no_cpu)

@@ -6,27 +6,33 @@
 
 namespace sf {
 
-// dst[p, R, :] = src[idx[p, R / block] * block + R % block, :]  (zeros when the
-// slot is unused).  One block per output row; VEC-typed copies.  Pattern p's
-// rows start dst_p_stride VECs after pattern p-1's (so a region of a larger
-// per-pattern buffer can be the target).
+// One launch gathers up to 4 "regions".  Region g: dst_g[p, R, :] = src_g[idx_g[p, R / block] * block +
+// R % block, :] for R < rows (zeros when the slot is unused); pattern p's rows start dst_pstride VECs
+// after pattern p-1's (so a region can be part of a larger per-pattern buffer).  All regions of a
+// launch share the row length.  One block per output row; VEC-typed copies.
+struct GatherRegion {
+    const void *src; void *dst; const int32_t *idx; const int32_t *n_dev;
+    int idx_stride, block, n_static, rows; size_t dst_pstride;
+};
+struct GatherRegions { GatherRegion r[4]; int n; };
+
 template <class VEC>
-__global__ __launch_bounds__(256) void gather_rows_kernel(
-    const VEC *__restrict__ src, VEC *__restrict__ dst, const int32_t *__restrict__ idx,
-    int idx_stride, int block, int n_static, const int32_t *__restrict__ n_dev,
-    size_t dst_p_stride, int row_vecs)
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherRegions regs, int row_vecs)
 {
-    const int p = blockIdx.y, R = blockIdx.x;
-    const int slot = R / block, r = R % block;
-    const int n_valid = n_dev ? n_dev[p] : n_static;
+    const int p = blockIdx.y;
+    int R = blockIdx.x, g = 0;
+    while (g + 1 < regs.n && R >= regs.r[g].rows) { R -= regs.r[g].rows; ++g; }
+    const GatherRegion &rg = regs.r[g];
+    const int slot = R / rg.block, r = R % rg.block;
+    const int n_valid = rg.n_dev ? rg.n_dev[p] : rg.n_static;
     int src_unit = -1;
-    if (slot < n_valid) src_unit = idx[(size_t)p * idx_stride + slot];
-    VEC *d = dst + (size_t)p * dst_p_stride + (size_t)R * row_vecs;
+    if (slot < n_valid) src_unit = rg.idx[(size_t)p * rg.idx_stride + slot];
+    VEC *d = static_cast<VEC *>(rg.dst) + (size_t)p * rg.dst_pstride + (size_t)R * row_vecs;
     if (src_unit < 0) {
         VEC z{};
         for (int i = threadIdx.x; i < row_vecs; i += blockDim.x) d[i] = z;
     } else {
-        const VEC *s = src + ((size_t)src_unit * block + r) * row_vecs;
+        const VEC *s = static_cast<const VEC *>(rg.src) + ((size_t)src_unit * rg.block + r) * row_vecs;
         for (int i = threadIdx.x; i < row_vecs; i += blockDim.x) d[i] = s[i];
     }
 }
@@ -60,26 +66,26 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(
     }
 }
 
-static void gather_rows(hipStream_t st, const void *src, void *dst, const int32_t *idx,
-                        int idx_stride, int block, int n_static, const int32_t *n_dev,
-                        int rows_out, size_t rows_per_pattern, size_t row_bytes, int P)
+// regs.r[g].dst_pstride is given in ROWS here and converted to VECs
+static void gather_rows(hipStream_t st, GatherRegions regs, size_t row_bytes, int P)
 {
-    const size_t pstride = rows_per_pattern * row_bytes;
-    dim3 grid(rows_out, P);
-    const bool v16 = row_bytes % 16 == 0 && ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0);
-    if (v16) {
-        const int rv = (int)(row_bytes / 16);
+    int rows = 0;
+    bool a16 = row_bytes % 16 == 0;
+    for (int g = 0; g < regs.n; ++g) {
+        rows += regs.r[g].rows;
+        a16 = a16 && ((uintptr_t)regs.r[g].src % 16 == 0) && ((uintptr_t)regs.r[g].dst % 16 == 0);
+    }
+    dim3 grid(rows, P);
+    const size_t unit = a16 ? 16 : (row_bytes % 4 == 0 ? 4 : 2);
+    for (int g = 0; g < regs.n; ++g) regs.r[g].dst_pstride = regs.r[g].dst_pstride * row_bytes / unit;
+    const int rv = (int)(row_bytes / unit);
+    if (unit == 16) {
         const int nt = rv >= 256 ? 256 : (rv >= 128 ? 128 : 64);
-        hipLaunchKernelGGL(gather_rows_kernel<uint4>, grid, dim3(nt), 0, st, (const uint4 *)src,
-                           (uint4 *)dst, idx, idx_stride, block, n_static, n_dev, pstride / 16, rv);
-    } else if (row_bytes % 4 == 0) {
-        hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, grid, dim3(64), 0, st, (const uint32_t *)src,
-                           (uint32_t *)dst, idx, idx_stride, block, n_static, n_dev, pstride / 4,
-                           (int)(row_bytes / 4));
+        hipLaunchKernelGGL(gather_rows_kernel<uint4>, grid, dim3(nt), 0, st, regs, rv);
+    } else if (unit == 4) {
+        hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, grid, dim3(64), 0, st, regs, rv);
     } else {
-        hipLaunchKernelGGL(gather_rows_kernel<uint16_t>, grid, dim3(64), 0, st, (const uint16_t *)src,
-                           (uint16_t *)dst, idx, idx_stride, block, n_static, n_dev, pstride / 2,
-                           (int)(row_bytes / 2));
+        hipLaunchKernelGGL(gather_rows_kernel<uint16_t>, grid, dim3(64), 0, st, regs, rv);
     }
 }
 
@@ -135,24 +141,32 @@ extern "C" int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
     const int32_t *ng = n_groups + (size_t)layer * P;
     const int32_t *fi = ffn_idx + (size_t)layer * P * D.F;
 
-    // Wqkv [P, Nqkv, d] has three row regions: kept Q heads, K group slots, V group slots.
-    struct Region { const void *W, *b; const int32_t *idx; int stride, n_static; const int32_t *n_dev; int row0, rows; };
-    const Region regs[3] = {
-        {dense->Wq, dense->bq, hi, D.Hq, kh, nullptr, 0, kh * dh},
-        {dense->Wk, dense->bk, gi, D.Hk, 0, ng, kh * dh, D.Hk * dh},
-        {dense->Wv, dense->bv, gi, D.Hk, 0, ng, (kh + D.Hk) * dh, D.Hk * dh},
+    // One launch for all weight rows and one for all bias entries: the three row regions of
+    // Wqkv [P, Nqkv, d] (kept Q heads, K group slots, V group slots) and W1' (+ zero pad rows).
+    auto region = [&](const void *src, void *dst, size_t elem_off, const int32_t *idx, int idx_stride, int block,
+                      int n_static, const int32_t *n_dev, int rows, size_t rows_per_pattern, size_t row_bytes) {
+        GatherRegion r{};
+        r.src = src; r.dst = (char *)dst + elem_off * row_bytes; r.idx = idx; r.n_dev = n_dev;
+        r.idx_stride = idx_stride; r.block = block; r.n_static = n_static; r.rows = rows;
+        r.dst_pstride = rows_per_pattern;
+        return r;
     };
-    for (const Region &r : regs) {
-        char *dW = (char *)c->Wqkv + (size_t)r.row0 * d * es;
-        gather_rows(st, r.W, dW, r.idx, r.stride, dh, r.n_static, r.n_dev, r.rows, Nqkv, (size_t)d * es, P);
-        if (qkv_bias) {
-            char *db = (char *)c->bqkv + (size_t)r.row0 * es;
-            gather_rows(st, r.b, db, r.idx, r.stride, dh, r.n_static, r.n_dev, r.rows, Nqkv, es, P);
-        }
+    const size_t rowW = (size_t)d * es;
+    GatherRegions wr{};
+    wr.r[0] = region(dense->Wq, c->Wqkv, 0, hi, D.Hq, dh, kh, nullptr, kh * dh, Nqkv, rowW);
+    wr.r[1] = region(dense->Wk, c->Wqkv, (size_t)kh * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, rowW);
+    wr.r[2] = region(dense->Wv, c->Wqkv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, rowW);
+    wr.r[3] = region(dense->W1, c->W1, 0, fi, D.F, 1, kf, nullptr, Fp, Fp, rowW);
+    wr.n = 4;
+    gather_rows(st, wr, rowW, P);
+    GatherRegions br{};
+    if (qkv_bias) {
+        br.r[br.n++] = region(dense->bq, c->bqkv, 0, hi, D.Hq, dh, kh, nullptr, kh * dh, Nqkv, es);
+        br.r[br.n++] = region(dense->bk, c->bqkv, (size_t)kh * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, es);
+        br.r[br.n++] = region(dense->bv, c->bqkv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, es);
     }
-    // W1' rows (+ zero pad rows), b1'
-    gather_rows(st, dense->W1, c->W1, fi, D.F, 1, kf, nullptr, Fp, Fp, (size_t)d * es, P);
-    if (dense->b1) gather_rows(st, dense->b1, c->b1, fi, D.F, 1, kf, nullptr, Fp, Fp, es, P);
+    if (dense->b1) br.r[br.n++] = region(dense->b1, c->b1, 0, fi, D.F, 1, kf, nullptr, Fp, Fp, es);
+    if (br.n) gather_rows(st, br, es, P);
     // W2'^T and Wo'^T: unit rows become columns so the GEMMs read K-contiguous operands
     gather_transpose(st, D.dtype, dense->W2, c->W2T, fi, D.F, 1, kf, Fp, d, P);
     gather_transpose(st, D.dtype, dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, d, P);
