@@ -19,6 +19,7 @@ constexpr int NWAVE = 4;
 constexpr int BKEY = 64;          // keys per LDS tile (two 32-key MFMA blocks)
 constexpr int PAD = 8;            // bf16 elements of row padding (16 bytes) against bank conflicts
 constexpr float LOG2E = 1.4426950408889634f;
+#define SF_SCORE_OCC __attribute__((amdgpu_waves_per_eu(4, 4)))
 
 // Bit j%32 of word j/32 = key j of sample b is allowed (0 beyond L).
 __device__ __forceinline__ void build_mask_words(const uint8_t *kv, int L, uint32_t *words, int nwords)
@@ -31,20 +32,6 @@ __device__ __forceinline__ void build_mask_words(const uint8_t *kv, int L, uint3
             if (j < L && (!kv || kv[j])) m |= 1u << t;
         }
         words[w] = m;
-    }
-}
-
-// K tile [BKEY keys][DH] -> LDS rows of DH+PAD; rows at or beyond L are zero.
-template <int DH>
-__device__ __forceinline__ void stage_k_tile(const __bf16 *Kb, int64_t sl, int j0, int L, __bf16 *Ks)
-{
-    constexpr int CH = DH / 8;                         // 16-byte chunks per row
-    for (int c = threadIdx.x; c < BKEY * CH; c += NWAVE * 64) {
-        const int r = c / CH, cc = c % CH;
-        const int j = j0 + r;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (j < L) v = *reinterpret_cast<const uint4 *>(Kb + (int64_t)j * sl + cc * 8);
-        *reinterpret_cast<uint4 *>(Ks + r * (DH + PAD) + cc * 8) = v;
     }
 }
 
@@ -70,43 +57,51 @@ __device__ __forceinline__ void build_tile_list(const uint32_t *words, int nword
     }
 }
 
-// K tile chunks of this thread -> registers (rows at or beyond L are zero)
-template <int DH>
-__device__ __forceinline__ void fetch_k_tile(const __bf16 *Kb, int64_t sl, int j0, int L, uint4 (&r)[BKEY * (DH / 8) / (NWAVE * 64)])
-{
-    constexpr int CH = DH / 8, N = BKEY * CH / (NWAVE * 64);
+// K tile chunks of this thread -> registers (rows at or beyond L are zero); NT
+// threads share a tile.  j0 must be wave-uniform: the tile base stays scalar
+// and each lane adds a 32-bit offset that does not change from tile to tile.
+template <int DH, int NT>
+struct KTile {
+    static constexpr int CH = DH / 8, TOTAL = BKEY * CH, N = (TOTAL + NT - 1) / NT;
+    static __device__ __forceinline__ void fetch(const __bf16 *Kb, int64_t sl, int j0, int L, uint4 (&r)[N])
+    {
+        const char *base = reinterpret_cast<const char *>(Kb + (int64_t)j0 * sl);
 #pragma unroll
-    for (int u = 0; u < N; ++u) {
-        const int c = threadIdx.x + u * NWAVE * 64;
-        const int row = c / CH, cc = c % CH;
-        const int j = j0 + row;
-        r[u] = (j < L) ? *reinterpret_cast<const uint4 *>(Kb + (int64_t)j * sl + cc * 8) : make_uint4(0, 0, 0, 0);
+        for (int u = 0; u < N; ++u) {
+            const int c = threadIdx.x + u * NT;
+            const int row = c / CH, cc = c % CH;
+            const uint32_t off = (uint32_t)row * (uint32_t)sl * 2u + (uint32_t)cc * 16u;   // < 64 rows * row stride bytes
+            r[u] = ((TOTAL % NT == 0 || c < TOTAL) && j0 + row < L)
+                       ? *reinterpret_cast<const uint4 *>(base + off) : make_uint4(0, 0, 0, 0);
+        }
     }
-}
-template <int DH>
-__device__ __forceinline__ void put_k_tile(const uint4 (&r)[BKEY * (DH / 8) / (NWAVE * 64)], __bf16 *Ks)
-{
-    constexpr int CH = DH / 8, N = BKEY * CH / (NWAVE * 64);
+    static __device__ __forceinline__ void put(const uint4 (&r)[N], __bf16 *Ks)
+    {
 #pragma unroll
-    for (int u = 0; u < N; ++u) {
-        const int c = threadIdx.x + u * NWAVE * 64;
-        *reinterpret_cast<uint4 *>(Ks + (c / CH) * (DH + PAD) + (c % CH) * 8) = r[u];
+        for (int u = 0; u < N; ++u) {
+            const int c = threadIdx.x + u * NT;
+            if (TOTAL % NT == 0 || c < TOTAL)
+                *reinterpret_cast<uint4 *>(Ks + (c / CH) * (DH + PAD) + (c % CH) * 8) = r[u];
+        }
     }
-}
+};
 
 // ------------------------------------------------------------- sparsity score
 // M_i = max_j s_ij - mean_j s_ij over allowed keys.  The max comes from the
 // streamed S^T tiles; the mean is q_i . mean_key (computed once per group),
 // which is the same number up to fp32 rounding.
-// grid (query blocks, B*nH); each wave owns QBS blocks of 32 queries.  K tiles
+// 1-D grid over (query block, sample*head) items, query block fastest; each
+// wave owns QBS blocks of 32 queries.  The launch index is folded so that all
+// query blocks of one (sample, head) - and of the neighbouring heads, which
+// mostly share the K/V group - run on one XCD and find K in its L2.  K tiles
 // are double-buffered in LDS and the next tile is prefetched into registers
 // while the current one is multiplied, so one barrier per tile suffices.
 template <int DH, int QBS>
-__global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
+__global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
     const uint8_t *__restrict__ key_valid, const float *__restrict__ stats, int nH, int nG, int L,
-    float *__restrict__ score, int scoreH)
+    float *__restrict__ score, int scoreH, int qblocks, int n_items)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                              // [2][BKEY][DH+PAD]
@@ -115,7 +110,9 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
     uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (L + 31) / 32);      // [ceil(L/64)]
     __shared__ int n_tiles;
 
-    const int bh = blockIdx.y, b = bh / nH, h = bh % nH;
+    const int item = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+    if (item >= n_items) return;                          // uniform
+    const int qblk = item % qblocks, bh = item / qblocks, b = bh / nH, h = bh % nH;
     const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
@@ -125,7 +122,7 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
 
     const __bf16 *Qb = Q + (int64_t)b * sq.b + (int64_t)h * sq.h;
     const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const int q0 = (blockIdx.x * NWAVE + wave) * QBS * 32;
+    const int q0 = (qblk * NWAVE + wave) * QBS * 32;
 
     bf16x8 qf[QBS][DH / 16];
     float rmax[QBS];
@@ -142,15 +139,19 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
     __syncthreads();
     const int nt = n_tiles;
 
-    uint4 kreg[BKEY * (DH / 8) / (NWAVE * 64)];
-    if (nt > 0) fetch_k_tile<DH>(Kb, sk.l, tiles[0] * BKEY, L, kreg);
+    using KT_ = KTile<DH, NWAVE * 64>;
+    uint4 kreg[KT_::N];
+    auto tile_j0 = [&](int it) { return __builtin_amdgcn_readfirstlane((int)tiles[it]) * BKEY; };   // same for every lane
+    if (nt > 0) KT_::fetch(Kb, sk.l, tile_j0(0), L, kreg);
     for (int it = 0; it < nt; ++it) {
-        const int j0 = tiles[it] * BKEY;
+        const int j0 = tile_j0(it);
         __bf16 *Kt = Ks + (it & 1) * BKEY * (DH + PAD);
-        put_k_tile<DH>(kreg, Kt);
+        KT_::put(kreg, Kt);
         __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffer)
-        if (it + 1 < nt) fetch_k_tile<DH>(Kb, sk.l, tiles[it + 1] * BKEY, L, kreg);
-        const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
+        if (it + 1 < nt) KT_::fetch(Kb, sk.l, tile_j0(it + 1), L, kreg);
+        // the mask words are the same for every lane: keep them scalar
+        const uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)words[j0 / 32]);
+        const uint32_t w1 = (j0 / 32 + 1 < nwords) ? (uint32_t)__builtin_amdgcn_readfirstlane((int)words[j0 / 32 + 1]) : 0u;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             const uint32_t w = kb ? w1 : w0;
@@ -159,25 +160,36 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
 #pragma unroll
             for (int kk = 0; kk < DH / 16; ++kk)
                 kf[kk] = *reinterpret_cast<const bf16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
-            const uint32_t wl = w >> (lhi * 4);
+            if (w == 0xffffffffu) {                 // scalar branch: the usual tile, no masking
 #pragma unroll
-            for (int qq = 0; qq < QBS; ++qq) {
-                f32x16 s;
+                for (int qq = 0; qq < QBS; ++qq) {
+                    f32x16 s;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) s[e] = 0.f;
+                    for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-                for (int kk = 0; kk < DH / 16; ++kk)
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s, 0, 0, 0);
-                float m = rmax[qq];
-                if (w == 0xffffffffu) {
+                    for (int kk = 0; kk < DH / 16; ++kk)
+                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s, 0, 0, 0);
+                    float m = rmax[qq];
 #pragma unroll
                     for (int e = 0; e < 16; e += 2) m = fmaxf(fmaxf(m, s[e]), s[e + 1]);
-                } else {
+                    rmax[qq] = m;
+                }
+            } else {
+                const uint32_t wl = w >> (lhi * 4);
+#pragma unroll
+                for (int qq = 0; qq < QBS; ++qq) {
+                    f32x16 s;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+                    for (int kk = 0; kk < DH / 16; ++kk)
+                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s, 0, 0, 0);
+                    float m = rmax[qq];
 #pragma unroll
                     for (int e = 0; e < 16; ++e)       // key row of s[e]: (e/4)*8 + lhi*4 + e%4
-                        if ((wl >> ((e / 4) * 8 + (e % 4))) & 1u) m = fmaxf(m, s[e]);
+                        m = fmaxf(m, ((wl >> ((e / 4) * 8 + (e % 4))) & 1u) ? s[e] : -INFINITY);
+                    rmax[qq] = m;
                 }
-                rmax[qq] = m;
             }
         }
     }
@@ -201,18 +213,25 @@ __global__ __launch_bounds__(NWAVE * 64) void score_bf16_kernel(
 }
 
 // ---------------------------------------------------------------- active pass
-// grid (pair chunks, B*nG, key splits).  A "pair" is (head of the group,
-// block of 32 active queries); each wave owns QB pairs, all waves share the
-// K / V^T tiles of the group.
+// A "pair" is (head of the group, block of 32 active queries).  A workgroup of
+// AWAVE waves serves one (sample, K/V group, key split): each wave owns QB
+// pairs and all waves share the K / V^T tiles staged in LDS; a group with more
+// pairs than AWAVE*QB is served in several passes over the key range.
+// 1-D grid; the launch index is folded so that consecutive work items (the
+// pair chunks of one (sample, group), which read the same K/V) run on the same
+// XCD and share its L2, and the items are spread evenly over the XCDs.
+constexpr int AWAVE = 8;
+
 template <int DH, int QB>
-__global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
+__global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
     const __bf16 *__restrict__ VT, sf_strides svt, const int32_t *__restrict__ head_group, int hg_stride,
     const int32_t *__restrict__ pattern_id, const uint8_t *__restrict__ key_valid,
-    const int32_t *__restrict__ sel, int selH, int nH, int nG, int L, int Lp, int U, int Upad, int splits,
-    int keys_per_split, __bf16 *__restrict__ O, int64_t ldo, float *__restrict__ part_o,
-    float *__restrict__ part_ml)
+    const int32_t *__restrict__ sel, int selH, int nH, int nG, int BG, int chunks, int L, int Lp, int U,
+    int Upad, int splits, int keys_per_split, __bf16 *__restrict__ O, int64_t ldo,
+    float *__restrict__ part_o, float *__restrict__ part_ml)
 {
+    constexpr int NT = AWAVE * 64;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int KT = BKEY * (DH + PAD), VT_ = DH * (BKEY + PAD);          // elements of one K / V^T tile
     __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                         // [2][BKEY][DH+PAD]
@@ -222,7 +241,12 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
     __shared__ int heads[64];
     __shared__ int n_heads, n_tiles;
 
-    const int bg = blockIdx.y, b = bg / nG, g = bg % nG, sp = blockIdx.z;
+    // launch index -> work item: XCD x (launch index % 8) takes the x-th eighth of the items
+    const int per_xcd = gridDim.x / 8;
+    const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (item >= chunks * BG * splits) return;             // uniform
+    const int chunk = item % chunks, bg = (item / chunks) % BG, sp = item / (chunks * BG);
+    const int b = bg / nG, g = bg % nG;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
     const int32_t *hg = head_group + (int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride;
 
@@ -235,58 +259,30 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     const int nwords = (L + 31) / 32;
     build_mask_words(kv, L, words, nwords);
+    const int jbeg = sp * keys_per_split, jend = min(L, jbeg + keys_per_split);
     __syncthreads();
-
+    build_tile_list(words, nwords, jbeg, jend, tiles, &n_tiles);
+    __syncthreads();
+    const int nt = n_tiles;
     const int nqb = Upad / 32;
     const int npairs = n_heads * nqb;
-    const int pair0 = blockIdx.x * (NWAVE * QB);
-    if (pair0 >= npairs) return;          // uniform
-
-    int head[QB], qidx[QB], slot[QB];
-    bf16x8 qf[QB][DH / 16];
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq) {
-        const int pi = pair0 + wave * QB + qq;
-        head[qq] = -1; qidx[qq] = -1; slot[qq] = 0;
-        if (pi < npairs) {
-            head[qq] = heads[pi / nqb];
-            slot[qq] = (pi % nqb) * 32 + l32;
-            if (slot[qq] < U) qidx[qq] = sel[((int64_t)b * selH + head[qq]) * U + slot[qq]];
-        }
-        const __bf16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
-                             (int64_t)max(qidx[qq], 0) * sq.l;
-#pragma unroll
-        for (int kk = 0; kk < DH / 16; ++kk)
-            qf[qq][kk] = *reinterpret_cast<const bf16x8 *>(qrow + kk * 16 + lhi * 8);
-    }
-
-    f32x16 oacc[QB][DH / 32];
-    float m_run[QB], l_run[QB];
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq) {
-        m_run[qq] = -INFINITY; l_run[qq] = 0.f;
-#pragma unroll
-        for (int db = 0; db < DH / 32; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[qq][db][e] = 0.f;
-    }
 
     const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
     const __bf16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
     const float sc = LOG2E / sqrtf((float)DH);
-    const int jbeg = sp * keys_per_split, jend = min(L, jbeg + keys_per_split);
 
     // V^T tile chunks of this thread -> registers; keys at or beyond L are zeroed
-    constexpr int NV = DH * (BKEY / 8) / (NWAVE * 64);
+    constexpr int VTOTAL = DH * (BKEY / 8), NV = (VTOTAL + NT - 1) / NT;
     auto fetch_v = [&](int j0, uint4 (&r)[NV]) {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int c = threadIdx.x + u * NWAVE * 64;
+            const int c = threadIdx.x + u * NT;
             const int e = c / (BKEY / 8), cc = c % (BKEY / 8);
             const int j = j0 + cc * 8;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (j < Lp) {
-                v = *reinterpret_cast<const uint4 *>(Vb + (int64_t)e * svt.l + j);
+            if ((VTOTAL % NT == 0 || c < VTOTAL) && j < Lp) {
+                const uint32_t off = (uint32_t)e * (uint32_t)svt.l * 2u + (uint32_t)cc * 16u;   // < dh rows of Lp keys
+                v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(Vb + j0) + off);
                 if (j + 8 > L) {
                     uint16_t *hv = reinterpret_cast<uint16_t *>(&v);
 #pragma unroll
@@ -300,140 +296,178 @@ __global__ __launch_bounds__(NWAVE * 64) void attend_bf16_kernel(
     auto put_v = [&](const uint4 (&r)[NV], __bf16 *Vt) {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int c = threadIdx.x + u * NWAVE * 64;
-            *reinterpret_cast<uint4 *>(Vt + (c / (BKEY / 8)) * (BKEY + PAD) + (c % (BKEY / 8)) * 8) = r[u];
+            const int c = threadIdx.x + u * NT;
+            if (VTOTAL % NT == 0 || c < VTOTAL)
+                *reinterpret_cast<uint4 *>(Vt + (c / (BKEY / 8)) * (BKEY + PAD) + (c % (BKEY / 8)) * 8) = r[u];
         }
     };
+    using KT_ = KTile<DH, NT>;
+    auto tile_j0 = [&](int it) { return __builtin_amdgcn_readfirstlane((int)tiles[it]) * BKEY; };   // same for every lane
 
-    build_tile_list(words, nwords, jbeg, jend, tiles, &n_tiles);
-    __syncthreads();
-    const int nt = n_tiles;
-    uint4 kreg[BKEY * (DH / 8) / (NWAVE * 64)], vreg[NV];
-    if (nt > 0) { fetch_k_tile<DH>(Kb, sk.l, tiles[0] * BKEY, L, kreg); fetch_v(tiles[0] * BKEY, vreg); }
-
-    for (int it = 0; it < nt; ++it) {
-        const int j0 = tiles[it] * BKEY;
-        __bf16 *Kt = Ks + (it & 1) * KT, *Vt = Vs + (it & 1) * VT_;
-        put_k_tile<DH>(kreg, Kt);
-        put_v(vreg, Vt);
-        __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffers)
-        if (it + 1 < nt) { fetch_k_tile<DH>(Kb, sk.l, tiles[it + 1] * BKEY, L, kreg); fetch_v(tiles[it + 1] * BKEY, vreg); }
-        const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
-
-        // S^T blocks for the two 32-key halves
-        f32x16 s[QB][2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            bf16x8 kf[DH / 16];
-#pragma unroll
-            for (int kk = 0; kk < DH / 16; ++kk)
-                kf[kk] = *reinterpret_cast<const bf16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
-#pragma unroll
-            for (int qq = 0; qq < QB; ++qq) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) s[qq][kb][e] = 0.f;
-#pragma unroll
-                for (int kk = 0; kk < DH / 16; ++kk)
-                    s[qq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s[qq][kb], 0, 0, 0);
-            }
-        }
-
-        // online softmax per query (per lane), log2 domain
-        bf16x8 pf[QB][4];
+    for (int pair0 = chunk * (AWAVE * QB); pair0 < npairs; pair0 += chunks * (AWAVE * QB)) {
+        int head[QB], qidx[QB], slot[QB];
+        bf16x8 qf[QB][DH / 16];
 #pragma unroll
         for (int qq = 0; qq < QB; ++qq) {
-            float mt = -INFINITY;
+            const int pi = pair0 + wave * QB + qq;
+            head[qq] = -1; qidx[qq] = -1; slot[qq] = 0;
+            if (pi < npairs) {
+                head[qq] = heads[pi / nqb];
+                slot[qq] = (pi % nqb) * 32 + l32;
+                if (slot[qq] < U) qidx[qq] = sel[((int64_t)b * selH + head[qq]) * U + slot[qq]];
+            }
+            const __bf16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
+                                 (int64_t)max(qidx[qq], 0) * sq.l;
+#pragma unroll
+            for (int kk = 0; kk < DH / 16; ++kk)
+                qf[qq][kk] = *reinterpret_cast<const bf16x8 *>(qrow + kk * 16 + lhi * 8);
+        }
+        const bool idle = pair0 + wave * QB >= npairs;        // wave-uniform: no pair at all
+
+        f32x16 oacc[QB][DH / 32];
+        float m_run[QB], l_run[QB];
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+            m_run[qq] = -INFINITY; l_run[qq] = 0.f;
+#pragma unroll
+            for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[qq][db][e] = 0.f;
+        }
+
+        uint4 kreg[KT_::N], vreg[NV];
+        if (nt > 0) { KT_::fetch(Kb, sk.l, tile_j0(0), L, kreg); fetch_v(tile_j0(0), vreg); }
+
+        for (int it = 0; it < nt; ++it) {
+            const int j0 = tile_j0(it);
+            __bf16 *Kt = Ks + (it & 1) * KT, *Vt = Vs + (it & 1) * VT_;
+            KT_::put(kreg, Kt);
+            put_v(vreg, Vt);
+            __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffers)
+            if (it + 1 < nt) { const int jn = tile_j0(it + 1); KT_::fetch(Kb, sk.l, jn, L, kreg); fetch_v(jn, vreg); }
+            if (idle) continue;
+            const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
+            // the same for every lane: a tile with all 64 keys allowed skips the masking
+            const bool all_allowed = (uint32_t)__builtin_amdgcn_readfirstlane((int)(w0 & w1)) == 0xffffffffu;
+
+            // S^T blocks for the two 32-key halves
+            f32x16 s[QB][2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const uint32_t w = kb ? w1 : w0;
-                const uint32_t wl = w >> (lhi * 4);
+                bf16x8 kf[DH / 16];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float v = s[qq][kb][e] * sc;
-                    if (w != 0xffffffffu && !((wl >> ((e / 4) * 8 + (e % 4))) & 1u)) v = -INFINITY;
-                    s[qq][kb][e] = v;
-                    mt = fmaxf(mt, v);
+                for (int kk = 0; kk < DH / 16; ++kk)
+                    kf[kk] = *reinterpret_cast<const bf16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+#pragma unroll
+                for (int qq = 0; qq < QB; ++qq) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) s[qq][kb][e] = 0.f;
+#pragma unroll
+                    for (int kk = 0; kk < DH / 16; ++kk)
+                        s[qq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s[qq][kb], 0, 0, 0);
                 }
             }
-            mt = fmaxf(mt, __shfl_xor(mt, 32));
-            const float m_new = fmaxf(m_run[qq], mt);
-            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qq] - m_safe);
-            m_run[qq] = m_new;
-            float rs = 0.f;
+
+            // online softmax per query (per lane), log2 domain
+            bf16x8 pf[QB][4];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int qq = 0; qq < QB; ++qq) {
+                if (!all_allowed) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(s[qq][kb][e] - m_safe);
-                    s[qq][kb][e] = p;
-                    rs += p;
+                    for (int kb = 0; kb < 2; ++kb) {
+                        const uint32_t wl = (kb ? w1 : w0) >> (lhi * 4);
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            if (!((wl >> ((e / 4) * 8 + (e % 4))) & 1u)) s[qq][kb][e] = -INFINITY;
+                    }
                 }
-            l_run[qq] = l_run[qq] * alpha + rs;
+                float mt = -INFINITY;
 #pragma unroll
-            for (int db = 0; db < DH / 32; ++db)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[qq][db][e] *= alpha;
-            // k-step t covers keys 16t..16t+15; this lane supplies keys
-            // {16t + lhi*4 + 0..3, 16t + 8 + lhi*4 + 0..3} = accumulator entries (t%2)*8 + 0..7
+                    for (int e = 0; e < 16; ++e) mt = fmaxf(mt, s[qq][kb][e]);
+                mt *= sc;                                  // sc > 0: max and scaling commute
+                mt = fmaxf(mt, __shfl_xor(mt, 32));
+                const float m_new = fmaxf(m_run[qq], mt);
+                const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f(m_run[qq] - m_safe);
+                m_run[qq] = m_new;
+                float rs = 0.f;
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf[qq][t][e] = (__bf16)s[qq][t / 2][(t % 2) * 8 + e];
+                    for (int e = 0; e < 16; ++e) {
+                        const float p = __builtin_amdgcn_exp2f(fmaf(s[qq][kb][e], sc, -m_safe));
+                        s[qq][kb][e] = p;
+                        rs += p;
+                    }
+                l_run[qq] = l_run[qq] * alpha + rs;
+#pragma unroll
+                for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[qq][db][e] *= alpha;
+                // k-step t covers keys 16t..16t+15; this lane supplies keys
+                // {16t + lhi*4 + 0..3, 16t + 8 + lhi*4 + 0..3} = accumulator entries (t%2)*8 + 0..7
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pf[qq][t][e] = (__bf16)s[qq][t / 2][(t % 2) * 8 + e];
+            }
+
+            // O^T += V^T . P^T
+#pragma unroll
+            for (int db = 0; db < DH / 32; ++db) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const __bf16 *vrow = Vt + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 4;
+                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vrow);
+                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vrow + 8);
+                    bf16x8 vf;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
+#pragma unroll
+                    for (int qq = 0; qq < QB; ++qq)
+                        oacc[qq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qq][t], oacc[qq][db], 0, 0, 0);
+                }
+            }
         }
 
-        // O^T += V^T . P^T
+        // lane owns query l32 and output dims db*32 + ig*8 + lhi*4 + {0..3}
 #pragma unroll
-        for (int db = 0; db < DH / 32; ++db) {
+        for (int qq = 0; qq < QB; ++qq) {
+            const float l_tot = l_run[qq] + __shfl_xor(l_run[qq], 32);
+            if (qidx[qq] < 0) continue;
+            if (splits <= 1) {
+                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+                __bf16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const __bf16 *vrow = Vt + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 4;
-                const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vrow);
-                const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vrow + 8);
-                bf16x8 vf;
+                for (int db = 0; db < DH / 32; ++db)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
+                    for (int ig = 0; ig < 4; ++ig) {
+                        bf16x4 o;
 #pragma unroll
-                for (int qq = 0; qq < QB; ++qq)
-                    oacc[qq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qq][t], oacc[qq][db], 0, 0, 0);
+                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[qq][db][ig * 4 + e] * inv);
+                        *reinterpret_cast<bf16x4 *>(orow + db * 32 + ig * 8 + lhi * 4) = o;
+                    }
+            } else {
+                const int64_t base = (((int64_t)b * nH + head[qq]) * splits + sp) * Upad + slot[qq];   // [b, head, split, slot]
+                float *po = part_o + base * DH;
+#pragma unroll
+                for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                    for (int ig = 0; ig < 4; ++ig) {
+                        f32x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = oacc[qq][db][ig * 4 + e];
+                        *reinterpret_cast<f32x4 *>(po + db * 32 + ig * 8 + lhi * 4) = o;
+                    }
+                if (lhi == 0) {
+                    part_ml[base * 2] = m_run[qq];
+                    part_ml[base * 2 + 1] = l_tot;
+                }
             }
         }
-    }
-
-    // lane owns query l32 and output dims db*32 + ig*8 + lhi*4 + {0..3}
-#pragma unroll
-    for (int qq = 0; qq < QB; ++qq) {
-        const float l_tot = l_run[qq] + __shfl_xor(l_run[qq], 32);
-        if (qidx[qq] < 0) continue;
-        if (splits <= 1) {
-            const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-            __bf16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
-#pragma unroll
-            for (int db = 0; db < DH / 32; ++db)
-#pragma unroll
-                for (int ig = 0; ig < 4; ++ig) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[qq][db][ig * 4 + e] * inv);
-                    *reinterpret_cast<bf16x4 *>(orow + db * 32 + ig * 8 + lhi * 4) = o;
-                }
-        } else {
-            const int64_t base = (((int64_t)b * nH + head[qq]) * Upad + slot[qq]) * splits + sp;
-            float *po = part_o + base * DH;
-#pragma unroll
-            for (int db = 0; db < DH / 32; ++db)
-#pragma unroll
-                for (int ig = 0; ig < 4; ++ig) {
-                    f32x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = oacc[qq][db][ig * 4 + e];
-                    *reinterpret_cast<f32x4 *>(po + db * 32 + ig * 8 + lhi * 4) = o;
-                }
-            if (lhi == 0) {
-                part_ml[base * 2] = m_run[qq];
-                part_ml[base * 2 + 1] = l_tot;
-            }
-        }
+        __syncthreads();            // the next pass restages both tile buffers
     }
 }
 
@@ -443,11 +477,14 @@ static int32_t launch_score(const AttnArgs &a, const AttnPlan &pl, float *score,
 {
     const size_t lds = (size_t)2 * BKEY * (DH + PAD) * 2 + DH * 4 + (size_t)ceil_div(a.L, 32) * 4 +
                        (size_t)ceil_div(a.L, BKEY) * 2 + 16;
-    dim3 grid(ceil_div(a.L, NWAVE * QBS * 32), a.B * a.nH);
+    const int qblocks = ceil_div(a.L, NWAVE * QBS * 32);
+    const int64_t items = (int64_t)qblocks * a.B * a.nH;
+    if (items > (1 << 30)) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): too many work items");
+    dim3 grid((unsigned)align_up(items, 8));
     ProfScope prof(SF_KERNEL_SCORE, st);
     hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
                        a.sq, (const __bf16 *)a.K, a.sk, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
-                       pl.stats, a.nH, a.nG, a.L, score, scoreH);
+                       pl.stats, a.nH, a.nG, a.L, score, scoreH, qblocks, (int)items);
     return SF_OK;
 }
 
@@ -468,14 +505,17 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
 {
     const size_t lds = (size_t)2 * BKEY * (DH + PAD) * 2 + (size_t)2 * DH * (BKEY + PAD) * 2 +
                        (size_t)ceil_div(a.L, 32) * 4 + (size_t)ceil_div(a.L, BKEY) * 2 + 16;
-    const int nqb = pl.Upad / 32;
-    // upper bound on pairs of one group: every head in the same group
-    dim3 grid(ceil_div(a.nH * nqb, NWAVE * QB), a.B * a.nG, pl.splits);
+    const int nqb = pl.Upad / 32, BG = a.B * a.nG;
+    // pair chunks per (sample, group) for evenly spread heads; a group with more heads takes several passes
+    const int chunks = ceil_div(ceil_div(a.nH, a.nG) * nqb, AWAVE * QB);
+    const int64_t items = (int64_t)chunks * BG * pl.splits;
+    if (items > (1 << 30)) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): too many work items");
+    dim3 grid((unsigned)align_up(items, 8));
     ProfScope prof(SF_KERNEL_ATTEND, st);
-    hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
+    hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const __bf16 *)a.Q,
                        a.sq, (const __bf16 *)a.K, a.sk, (const __bf16 *)vt, svt, a.head_group, a.hg_stride,
-                       a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, a.L, pl.Lp, a.U, pl.Upad, pl.splits,
-                       pl.keys_per_split, (__bf16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
+                       a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
+                       pl.splits, pl.keys_per_split, (__bf16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
     return SF_OK;
 }
 

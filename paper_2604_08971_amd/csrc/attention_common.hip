@@ -168,60 +168,94 @@ __global__ __launch_bounds__(256) void forced_slot_kernel(const int32_t *__restr
 }
 
 // ------------------------------------------------------------------------ fill
-// Every row that is not active takes its group's context vector; when the
-// active pass ran split over the keys, the partial results are merged here.
-// One thread per VEC consecutive output elements (VEC = 8 when dh % 8 == 0).
+// Every row that is not active takes its group's context vector.  One block
+// per (sample, 32 rows): the row -> slot map of the 32 rows and the context
+// vectors of all heads are staged in LDS (coalesced along the row index), then
+// every thread writes VEC consecutive output elements at a time, rows of O
+// contiguous.  Active rows are left alone.
 template <class T, int VEC>
 __global__ __launch_bounds__(256) void fill_kernel(
-    int nH, int nG, int L, int dh, int Upad, int splits, const int32_t *__restrict__ slot,
+    int nH, int nG, int L, int dh, const int32_t *__restrict__ slot,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
-    const float *__restrict__ stats, const float *__restrict__ part_o, const float *__restrict__ part_ml,
-    T *__restrict__ O, int64_t ldo)
+    const float *__restrict__ stats, T *__restrict__ O, int64_t ldo)
 {
-    const int b = blockIdx.y;
-    const int qv = dh / VEC;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)L * nH * qv) return;
-    const int e = (int)(idx % qv) * VEC;
-    const int h = (int)((idx / qv) % nH);
-    const int i = (int)(idx / ((int64_t)qv * nH));
-    const int s = slot[((int64_t)b * nH + h) * L + i];
-    float v[VEC];
-    if (s < 0) {
-        const int p = pattern_id ? pattern_id[b] : 0;
+    extern __shared__ __attribute__((aligned(16))) char fsm[];
+    float *ctx = reinterpret_cast<float *>(fsm);                 // [nH][dh]
+    int32_t *sl = reinterpret_cast<int32_t *>(ctx + nH * dh);    // [nH][32]
+    const int b = blockIdx.y, i0 = blockIdx.x * 32;
+    const int p = pattern_id ? pattern_id[b] : 0;
+    for (int t = threadIdx.x; t < nH * dh; t += 256) {
+        const int h = t / dh, e = t % dh;
         const int g = head_group[(int64_t)p * hg_stride + h];
-        const float *ctx = stats + (((int64_t)b * nG + g) * 2 + 1) * dh + e;
-#pragma unroll
-        for (int t = 0; t < VEC; ++t) v[t] = ctx[t];
-    } else {
-        if (splits <= 1) return;                       // written by the active pass
-        const int64_t base = (((int64_t)b * nH + h) * Upad + s) * splits;
-        float m = -INFINITY;
-        for (int sp = 0; sp < splits; ++sp) m = fmaxf(m, part_ml[(base + sp) * 2]);
-        float den = 0.f;
-#pragma unroll
-        for (int t = 0; t < VEC; ++t) v[t] = 0.f;
-        for (int sp = 0; sp < splits; ++sp) {
-            const float ms = part_ml[(base + sp) * 2];
-            const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
-            den += w * part_ml[(base + sp) * 2 + 1];
-            const float *po = part_o + (base + sp) * dh + e;
-#pragma unroll
-            for (int t = 0; t < VEC; ++t) v[t] += w * po[t];
-        }
-        const float inv = den > 0.f ? 1.0f / den : 0.f;
-#pragma unroll
-        for (int t = 0; t < VEC; ++t) v[t] *= inv;
+        ctx[t] = stats[(((int64_t)b * nG + g) * 2 + 1) * dh + e];
     }
-    T *o = O + ((int64_t)b * L + i) * ldo + (int64_t)h * dh + e;
-    if constexpr (sizeof(T) == 2 && VEC == 8) {
-        bf16x8 ov;
+    for (int t = threadIdx.x; t < nH * 32; t += 256) {
+        const int h = t / 32, i = i0 + (t % 32);
+        sl[t] = i < L ? slot[((int64_t)b * nH + h) * L + i] : 0;
+    }
+    __syncthreads();
+    const int qv = dh / VEC, per_row = nH * qv;
+    for (int c = threadIdx.x; c < 32 * per_row; c += 256) {
+        const int r = c / per_row, h = (c % per_row) / qv, e = (c % qv) * VEC;
+        const int i = i0 + r;
+        if (i >= L) break;
+        if (sl[h * 32 + r] >= 0) continue;                 // active row: written by the active pass / the merge
+        float v[VEC];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) ov[t] = (__bf16)v[t];
-        *reinterpret_cast<bf16x8 *>(o) = ov;                 // ldo % 8 == 0 and 16-byte aligned O checked on the host
-    } else {
+        for (int t = 0; t < VEC; ++t) v[t] = ctx[h * dh + e + t];
+        T *o = O + ((int64_t)b * L + i) * ldo + (int64_t)h * dh + e;
+        if constexpr (sizeof(T) == 2 && VEC == 8) {
+            bf16x8 ov;
 #pragma unroll
-        for (int t = 0; t < VEC; ++t) o[t] = from_f32<T>(v[t]);
+            for (int t = 0; t < 8; ++t) ov[t] = (__bf16)v[t];
+            *reinterpret_cast<bf16x8 *>(o) = ov;             // ldo % 8 == 0 and 16-byte aligned O checked on the host
+        } else {
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) o[t] = from_f32<T>(v[t]);
+        }
+    }
+}
+
+// Merge of the key splits of the active pass: one wave per (sample, head,
+// active slot).  Lane sp holds the (max, sum) pair of split sp (splits <= 64),
+// the weights 2^(m_sp - m) are formed once, then lane e accumulates output
+// dimension e over the splits (partials are [b, head, split, slot, dh]).
+template <class T>
+__global__ __launch_bounds__(256) void merge_splits_kernel(
+    int nH, int L, int dh, int U, int Upad, int splits, int64_t n_waves, const int32_t *__restrict__ sel,
+    int selH, const float *__restrict__ part_o, const float *__restrict__ part_ml, T *__restrict__ O,
+    int64_t ldo)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= n_waves) return;
+    const int s = (int)(w % U);
+    const int64_t bh = w / U;
+    const int h = (int)(bh % nH);
+    const int64_t b = bh / nH;
+    const int64_t base = bh * splits;
+    float ms = -INFINITY, ls = 0.f;
+    if (lane < splits) {
+        const int64_t q = (base + lane) * Upad + s;
+        ms = part_ml[q * 2];
+        ls = part_ml[q * 2 + 1];
+    }
+    float m = ms;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    const float wgt = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
+    float den = wgt * ls;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o);
+    const float inv = den > 0.f ? 1.0f / den : 0.f;
+    const int qi = sel[((int64_t)b * selH + h) * U + s];
+    T *orow = O + ((int64_t)b * L + qi) * ldo + (int64_t)h * dh;
+    for (int e = lane; e < dh; e += 64) {
+        float acc = 0.f;
+        const float *po = part_o + (base * Upad + s) * dh + e;
+#pragma unroll 4
+        for (int sp = 0; sp < splits; ++sp) acc += __shfl(wgt, sp) * po[(int64_t)sp * Upad * dh];
+        orow[e] = from_f32<T>(acc * inv);
     }
 }
 
@@ -343,6 +377,7 @@ AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws)
         int want = (int)((768 + bg - 1) / bg);
         const int max_splits = a.L / 128 > 0 ? a.L / 128 : 1;
         if (want > max_splits) want = max_splits;
+        if (want > 64) want = 64;                     // the merge holds one split per lane
         if (want > 1) {
             pl.keys_per_split = (int)align_up(ceil_div(a.L, want), 64);
             pl.splits = ceil_div(a.L, pl.keys_per_split);
@@ -466,13 +501,19 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         }
     }
 
-    // 4. lazy rows (+ merge of the key splits)
-    {
+    // 4. merge of the key splits, then the lazy rows
+    if (pl.splits > 1) {
+        const int64_t n_waves = (int64_t)BH * a.U;
+        hipLaunchKernelGGL(merge_splits_kernel<__bf16>, dim3((unsigned)((n_waves + 3) / 4)), dim3(256), 0, st,
+                           a.nH, a.L, a.dh, a.U, pl.Upad, pl.splits, n_waves, sel, selH, pl.part_o, pl.part_ml,
+                           (__bf16 *)a.O, a.ldo);
+    }
+    {   // with U == L rows can still be lazy (fewer allowed rows than U)
         const bool v8 = dtype == SF_BF16 && a.dh % 8 == 0 && a.ldo % 8 == 0 && ((uintptr_t)a.O % 16 == 0);
-        const int64_t n = (int64_t)a.L * a.nH * (a.dh / (v8 ? 8 : 4));
-        dim3 grid((unsigned)((n + 255) / 256), a.B);
-#define SF_FILL_ARGS grid, dim3(256), 0, st, a.nH, a.nG, a.L, a.dh, pl.Upad, pl.splits, pl.slot, a.head_group, \
-                     a.hg_stride, a.pattern_id, pl.stats, pl.part_o, pl.part_ml
+        dim3 grid(ceil_div(a.L, 32), a.B);
+        const size_t fl = (size_t)a.nH * a.dh * 4 + (size_t)a.nH * 32 * 4;
+#define SF_FILL_ARGS grid, dim3(256), fl, st, a.nH, a.nG, a.L, a.dh, pl.slot, a.head_group, a.hg_stride, \
+                     a.pattern_id, pl.stats
         if (dtype == SF_BF16 && v8) hipLaunchKernelGGL((fill_kernel<__bf16, 8>), SF_FILL_ARGS, (__bf16 *)a.O, a.ldo);
         else if (dtype == SF_BF16) hipLaunchKernelGGL((fill_kernel<__bf16, 4>), SF_FILL_ARGS, (__bf16 *)a.O, a.ldo);
         else hipLaunchKernelGGL((fill_kernel<float, 4>), SF_FILL_ARGS, (float *)a.O, a.ldo);
