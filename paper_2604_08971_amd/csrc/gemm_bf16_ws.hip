@@ -9,6 +9,11 @@
 // waves do nothing but feed the double-buffered LDS ring with
 // global_load_lds_dwordx4 (12 waves = 3 per SIMD, <= 168 registers each).
 //
+//  * The ring is asymmetric: the activation operand X is streamed once from
+//    HBM (a cold miss per line, a few microseconds under load) while the weight
+//    tile is re-read from L2 by every row block.  X therefore gets three 32 KB
+//    slots and is fetched two K tiles ahead, W gets two slots and is fetched
+//    one tile ahead: 160 KB, all of a CU's LDS.
 //  * LDS layout: 256-byte super-rows (two 128-byte K rows) with the 16-byte slot
 //    XOR-ed by the super-row number: the LDS serves 16 lanes of a ds_read_b128
 //    per cycle and this keeps any 16 consecutive rows of one chunk conflict-free.
@@ -33,7 +38,8 @@ constexpr int BM = 256, BN = 256, BKT = 64;
 constexpr int NCW = 8, NLW = 4;                 // compute waves, loader waves
 constexpr int WAVES_N = 4;                      // compute waves: 2 (M) x 4 (N)
 constexpr int TM = 4, TN = 2;                   // 32x32 MFMA tiles per compute wave
-constexpr int STAGE = (BM + BN) * BKT;          // bf16 elements per ring slot (64 KB)
+constexpr int XSLOT = BM * BKT, WSLOT = BN * BKT;  // bf16 elements per X / W ring slot (32 KB each)
+constexpr int NXS = 3, NWS = 2;                 // ring slots: X two tiles ahead, W one tile ahead
 constexpr int N_XCD = 8;
 
 typedef __attribute__((address_space(3))) void lds_void;
@@ -59,7 +65,7 @@ __global__ __launch_bounds__(64 * (NCW + NLW)) __attribute__((amdgpu_waves_per_e
 void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd)
 {
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [2][X rows | W rows][64]
+    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NXS][X rows][64] | [NWS][W rows][64]
 
     const int wid = blockIdx.x;
     const int w = (wid % N_XCD) * per_xcd + wid / N_XCD;
@@ -91,22 +97,35 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
             xoff[j] = (uint32_t)(min(r, rows_x - 1) * (int)a.lda + c * 8) * 2u;
             woff[j] = (uint32_t)(min(r, rows_w - 1) * (int)a.ldw + c * 8) * 2u;
         }
-        auto issue = [&](int tile) {
-            __bf16 *base = smem + (tile & 1) * STAGE;
+        auto issue_x = [&](int tile) {
+            __bf16 *base = smem + (tile % NXS) * XSLOT;
             const int64_t koff = (int64_t)tile * BKT * 2;
 #pragma unroll
-            for (int j = 0; j < LPW; ++j) {
+            for (int j = 0; j < LPW; ++j)
                 __builtin_amdgcn_global_load_lds((glb_void *)(Ab + koff + xoff[j]),
                                                  (lds_void *)(base + (lw * LPW + j) * 512), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((glb_void *)(Wb + koff + woff[j]),
-                                                 (lds_void *)(base + BM * BKT + (lw * LPW + j) * 512), 16, 0, 0);
-            }
         };
-        issue(0);
+        auto issue_w = [&](int tile) {
+            __bf16 *base = smem + NXS * XSLOT + (tile % NWS) * WSLOT;
+            const int64_t koff = (int64_t)tile * BKT * 2;
+#pragma unroll
+            for (int j = 0; j < LPW; ++j)
+                __builtin_amdgcn_global_load_lds((glb_void *)(Wb + koff + woff[j]),
+                                                 (lds_void *)(base + (lw * LPW + j) * 512), 16, 0, 0);
+        };
+        // Loads complete in issue order.  Order kept: X(0) W(0) X(1) | W(1) X(2) | W(2) X(3) | ...
+        // so at barrier kt only the LPW loads of X(kt+1) may still be in flight.
+        issue_x(0);
+        issue_w(0);
+        if (nk > 1) issue_x(1);
         for (int kt = 0; kt < nk; ++kt) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // tile kt has landed
-            __syncthreads();                                      // barrier kt: tile kt visible, slot of tile kt-1 free
-            if (kt + 1 < nk) issue(kt + 1);
+            if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");   // X(kt), W(kt) landed
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // bare barrier: __syncthreads() carries a fence that would wait for the loads still in flight
+            __builtin_amdgcn_s_barrier();     // barrier kt: tile kt visible; slots of X(kt-1), W(kt-1) free
+            asm volatile("" ::: "memory");
+            if (kt + 1 < nk) issue_w(kt + 1);
+            if (kt + 2 < nk) issue_x(kt + 2);
         }
         __syncthreads();                                          // matches the barrier before the epilogue
         return;
@@ -123,35 +142,44 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // Byte address in LDS of this lane's fragment (k-step 0, MFMA tile 0) inside an X / W slot.  In the
+    // layout of lay(), MFMA tile t adds t * 4096 bytes and k-step s flips bits 5..6 (XOR with s << 5).
+    const uint32_t xlane = (uint32_t)lay(wm * TM * 32 + l32, lhi) * 2u;
+    const uint32_t wlane = (uint32_t)(NXS * XSLOT) * 2u + (uint32_t)lay(wn * TN * 32 + l32, lhi) * 2u;
+    static_assert(TN == 2 && TM == 4 && BKT == 64, "the interleaving below is written for 2 x 4 MFMA tiles per wave");
+    uint32_t xslot = 0, wslot = 0;          // byte offsets of the ring slots of tile kt
     for (int kt = 0; kt < nk; ++kt) {
-        __syncthreads();                                          // barrier kt
-        const __bf16 *xs = smem + (kt & 1) * STAGE;
-        const __bf16 *ws = xs + BM * BKT;
-        bf16x8 xf[2][TM], wf[2][TN];
-        auto load_frags = [&](int s, int slot) {
-            const int chunk = s * 2 + lhi;
+        // bare barrier: no global memory traffic of this wave needs ordering here
+        __builtin_amdgcn_s_barrier();                             // barrier kt
+        asm volatile("" ::: "memory");
+        const uint32_t xb = xlane + xslot, wb = wlane + wslot;
+        xslot = (xslot + XSLOT * 2 == NXS * XSLOT * 2) ? 0u : xslot + XSLOT * 2;
+        wslot = (wslot + WSLOT * 2 == NWS * WSLOT * 2) ? 0u : wslot + WSLOT * 2;
+        // Fragment registers are scarce next to 128 accumulators: the W fragments are double-buffered,
+        // the X fragments are single-buffered and X fragment j of the next k-step is read right after
+        // its last use in this k-step, so every read has about six MFMAs of cover.  The order below is
+        // kept as written (sched_barrier), one address register per operand and k-step.
+        bf16x8 xf[TM], wf[2][TN];
+        auto rd = [&](uint32_t addr) { return *reinterpret_cast<const bf16x8 *>(smem_raw + addr); };
+        {
+            wf[0][0] = rd(wb); wf[0][1] = rd(wb + 4096);
 #pragma unroll
-            for (int t = 0; t < TM; ++t)
-                xf[slot][t] = *reinterpret_cast<const bf16x8 *>(xs + lay((wm * TM + t) * 32 + l32, chunk));
-#pragma unroll
-            for (int t = 0; t < TN; ++t)
-                wf[slot][t] = *reinterpret_cast<const bf16x8 *>(ws + lay((wn * TN + t) * 32 + l32, chunk));
-        };
-        load_frags(0, 0);
+            for (int t = 0; t < TM; ++t) xf[t] = rd(xb + t * 4096);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < BKT / 16; ++s) {
-            if (s + 1 < BKT / 16) load_frags(s + 1, (s + 1) & 1);
+            const bool more = s + 1 < BKT / 16;
+            const uint32_t xa = xb ^ ((uint32_t)(s + 1) << 5), wa = wb ^ ((uint32_t)(s + 1) << 5);
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s & 1][i], xf[s & 1][j], acc[i][j], 0, 0, 0);
-            // MFMA, LDS read, MFMA, LDS read, ...: the reads of k-step s+1 ride under the MFMAs of k-step s
-            const int NDS = (s + 1 < BKT / 16) ? TM + TN : 0;
-#pragma unroll
-            for (int i = 0; i < TM * TN; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (i < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int j = 0; j < TM; ++j) {
+                acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s & 1][0], xf[j], acc[0][j], 0, 0, 0);
+                acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s & 1][1], xf[j], acc[1][j], 0, 0, 0);
+                if (more) {
+                    xf[j] = rd(xa + j * 4096);
+                    if (j < TN) wf[(s + 1) & 1][j] = rd(wa + j * 4096);
+                }
+                __builtin_amdgcn_sched_barrier(0);      // keep exactly this order: MFMA MFMA read(s)
             }
         }
     }
@@ -203,7 +231,8 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
             const bf16x8 o = *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const __bf16 *>(stg) + lay(r, c));
             const int i = mrow0 + r, n = ncol0 + c * 8;
             if (i < a.L && n < a.N)
-                *reinterpret_cast<bf16x8 *>(static_cast<__bf16 *>(a.C) + (grow0 + i) * a.ldc + a.c0 + n) = o;
+                // streamed out: the output is far larger than L2 and must not push the weights out of it
+                __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(static_cast<__bf16 *>(a.C) + (grow0 + i) * a.ldc + a.c0 + n));
         }
     } else {
         // residual and/or fp32 output: stage fp32, 32 features (128 bytes per row) at a time
@@ -246,23 +275,23 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                     if (a.R) {
                         const int64_t ro = (grow0 + i) * a.ldr + a.r0 + n;
                         if (a.r_f32) {
-                            const f32x4 rv = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(a.R) + ro);
+                            const f32x4 rv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(a.R) + ro));
 #pragma unroll
                             for (int e = 0; e < 4; ++e) v[e] += rv[e];
                         } else {
-                            const bf16x4 rv = *reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + ro);
+                            const bf16x4 rv = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + ro));
 #pragma unroll
                             for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
                         }
                     }
                     const int64_t co = (grow0 + i) * a.ldc + a.c0 + n;
                     if (a.c_f32) {
-                        *reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co) = v;
+                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co));
                     } else {
                         bf16x4 o;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
-                        *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co) = o;
+                        __builtin_nontemporal_store(o, reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co));
                     }
                 }
             }
@@ -276,7 +305,7 @@ template <int ACT>
 static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
 {
     auto kern = gemm_bf16_ws_kernel<ACT>;
-    constexpr size_t lds = (size_t)2 * STAGE * sizeof(__bf16);
+    constexpr size_t lds = ((size_t)NXS * XSLOT + (size_t)NWS * WSLOT) * sizeof(__bf16);     // 160 KB
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
