@@ -240,15 +240,16 @@ int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers_h
  * pairs; from then on every launch of that kernel class made by this library
  * (from any entry point, on any stream) is bracketed by one pair until
  * sf_profile_end, which synchronises the recorded events, returns the number
- * of launches seen and the sum of their durations in milliseconds, and
- * destroys the events.  Launches beyond max_launches are not timed.  Not
+ * of launches seen, the sum of their durations in milliseconds and (when
+ * each_ms_host is not NULL: a host array of max_launches floats) every
+ * duration in launch order, and destroys the events.  Launches beyond max_launches are not timed.  Not
  * thread-safe; do not use under graph capture.
  */
 enum { SF_KERNEL_GEMM = 0,      /* bf16 MFMA GEMM (all projections and both FFN GEMMs) */
        SF_KERNEL_SCORE = 1,     /* sparsity-score stream (QK^T with running max) */
        SF_KERNEL_ATTEND = 2 };  /* active-row attention (Eq. (6)) */
 int32_t sf_profile_begin(int32_t kernel_class, int32_t max_launches);
-int32_t sf_profile_end(int32_t *n_launches_host, float *total_ms_host);
+int32_t sf_profile_end(int32_t *n_launches_host, float *total_ms_host, float *each_ms_host);
 
 #ifdef __cplusplus
 }

@@ -89,7 +89,7 @@ def lib():
         L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
         L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
         L.sf_profile_begin.argtypes = [C.c_int32, C.c_int32]
-        L.sf_profile_end.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_float)]
+        L.sf_profile_end.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.sf_num_active.argtypes = [C.POINTER(SfDesc)]
         L.sf_ffn_padded.argtypes = [C.POINTER(SfDesc), C.c_int32]
         _lib = L
@@ -137,14 +137,22 @@ def workspace(nbytes: int, device="cuda") -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+_prof_cap = 0
+
+
 def profile_begin(kernel_class: int, max_launches: int):
+    global _prof_cap
     _check(lib().sf_profile_begin(kernel_class, max_launches), "sf_profile_begin")
+    _prof_cap = max_launches
 
 
-def profile_end():
-    """Returns (number of launches timed, sum of their durations in ms)."""
+def profile_end(each: bool = False):
+    """Returns (number of launches timed, sum of their durations in ms[, list of durations in launch order])."""
     n, ms = C.c_int32(0), C.c_float(0.0)
-    _check(lib().sf_profile_end(C.byref(n), C.byref(ms)), "sf_profile_end")
+    buf = (C.c_float * max(_prof_cap, 1))() if each else None
+    _check(lib().sf_profile_end(C.byref(n), C.byref(ms), buf), "sf_profile_end")
+    if each:
+        return int(n.value), float(ms.value), [float(buf[i]) for i in range(int(n.value))]
     return int(n.value), float(ms.value)
 
 

@@ -196,7 +196,7 @@ extern "C" int32_t sf_profile_begin(int32_t kernel_class, int32_t max_launches)
     return SF_OK;
 }
 
-extern "C" int32_t sf_profile_end(int32_t *n_launches, float *total_ms)
+extern "C" int32_t sf_profile_end(int32_t *n_launches, float *total_ms, float *each_ms)
 {
     if (g_prof.kernel_class < 0) return fail(SF_ERR_INVALID_ARG, "profile: not profiling");
     g_prof.kernel_class = -1;
@@ -208,6 +208,7 @@ extern "C" int32_t sf_profile_end(int32_t *n_launches, float *total_ms)
             hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess)
             rc = fail(SF_ERR_HIP, "profile: reading event %d failed", i);
         sum += ms;
+        if (each_ms) each_ms[i] = ms;
     }
     for (int i = 0; i < g_prof.cap; ++i) { (void)hipEventDestroy(g_prof.start[i]); (void)hipEventDestroy(g_prof.stop[i]); }
     delete[] g_prof.start;
