@@ -266,24 +266,14 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                     *reinterpret_cast<f32x4 *>(stf + lay(tm * 32 + l32, f0 / 4) / 2) = o0;
                     *reinterpret_cast<f32x4 *>(stf + lay(tm * 32 + l32, f0 / 4 + 1) / 2) = o1;
                 }
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int r = j * 8 + (lane >> 3), c = lane & 7;
-                f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(r, c) / 2);
-                const int i = mrow0 + r, n = ncol0 + tn * 32 + c * 4;
+            // rows out: 8 lanes x 16 bytes = 128 bytes of one row, 8 rows per instruction.  The residual
+            // reads of the whole pass are issued first (the accumulators just staged have freed the
+            // registers), so their latency is paid once per pass and not once per row group.
+            const int er = lane >> 3, ec = lane & 7;
+            const int n = ncol0 + tn * 32 + ec * 4;
+            auto finish = [&](int j, f32x4 v) {
+                const int i = mrow0 + j * 8 + er;
                 if (i < a.L && n < a.N) {
-                    if (a.R) {
-                        const int64_t ro = (grow0 + i) * a.ldr + a.r0 + n;
-                        if (a.r_f32) {
-                            const f32x4 rv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(a.R) + ro));
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] += rv[e];
-                        } else {
-                            const bf16x4 rv = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + ro));
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
-                        }
-                    }
                     const int64_t co = (grow0 + i) * a.ldc + a.c0 + n;
                     if (a.c_f32) {
                         __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co));
@@ -294,6 +284,41 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                         __builtin_nontemporal_store(o, reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co));
                     }
                 }
+            };
+            if (a.R && a.r_f32) {
+                f32x4 rr[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int i = min(mrow0 + j * 8 + er, a.L - 1);          // clamped: never stored when out of range
+                    const int64_t ro = (grow0 + i) * a.ldr + a.r0 + min(n, a.N - 4);
+                    rr[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(a.R) + ro));
+                }
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += rr[j][e];
+                    finish(j, v);
+                }
+            } else if (a.R) {
+                bf16x4 rr[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int i = min(mrow0 + j * 8 + er, a.L - 1);
+                    const int64_t ro = (grow0 + i) * a.ldr + a.r0 + min(n, a.N - 4);
+                    rr[j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + ro));
+                }
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += (float)rr[j][e];
+                    finish(j, v);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    finish(j, *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2));
             }
         }
     }
