@@ -97,7 +97,7 @@ def time_steps(fn, steps, warmup):
     return ev0.elapsed_time(ev1) / steps, wall
 
 
-def bench_config(name, steps, warmup, extras, cpu):
+def bench_config(name, steps, warmup, extras, cpu, use_graph=False):
     import numpy as np
     import torch
     from paper_2604_08971_amd import binding as sf
@@ -121,10 +121,43 @@ def bench_config(name, steps, warmup, extras, cpu):
         dm.build_plan()
         dm.forward(out=y)
 
-    ms, wall_ms = time_steps(step, steps, warmup)
+    # Optionally the step's launches (about 20 per layer) are recorded once into a HIP graph and replayed: same
+    # kernels, same arguments, same stream order.
+    launch = "eager"
+    run = step
+    if use_graph:
+        try:
+            step()                                        # first call sizes the workspace and sets kernel attributes
+            torch.cuda.synchronize()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            torch.cuda.synchronize()
+            y_ref = y.clone()
+            y.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(y, y_ref):
+                raise RuntimeError("graph replay differs from the eager step")
+            run, launch = graph.replay, "hipGraph"
+        except Exception as e:                            # noqa: BLE001 - any capture problem falls back to eager launches
+            log(f"[{name}] graph capture not used: {e}")
+            torch.cuda.synchronize()
+            run, launch = step, "eager"
+
+    ms, wall_ms = time_steps(run, steps, warmup)
     res = {"workload": name, "ms_per_step": ms, "host_ms_per_step": wall_ms, "tokens_per_s": B * L / (ms * 1e-3),
            "B": B, "L": L, "U": U, "algorithmic_tflop_per_step": flops["total"] / 1e12,
-           "tflops_total": flops["total"] / (ms * 1e-3) / 1e12}
+           "tflops_total": flops["total"] / (ms * 1e-3) / 1e12, "launch": launch}
+    if launch != "eager":
+        ms_eager, _ = time_steps(step, steps, 2)
+        res["ms_per_step_eager"] = ms_eager
     if not extras:
         return res, dm, wl, flops
 
@@ -223,6 +256,8 @@ def main():
     ap.add_argument("--config", default="C5", help="workload timed for `value` (C1..C5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="only the headline number")
+    ap.add_argument("--graph", action="store_true",
+                    help="time a replayed HIP graph of the step instead of eager launches (measured slower on ROCm 7.2: 1.38 vs 1.35 ms)")
     ap.add_argument("--other-configs", default="C2,C3,C4", help="also time these (reported under `other_workloads`)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (known traffic, for scaling the "
@@ -250,7 +285,7 @@ def main():
         del src, dst
 
     extras = not args.no_extras
-    res, dm, wl, flops = bench_config(args.config, args.steps, args.warmup, extras, not args.no_cpu)
+    res, dm, wl, flops = bench_config(args.config, args.steps, args.warmup, extras, not args.no_cpu, args.graph)
     spec = wl.spec
     out = {
         "metric": METRIC, "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
@@ -260,13 +295,14 @@ def main():
         "config": {"workload": f"{spec.name}: B={res['B']} L={res['L']} d={spec.d} Hq/Hk/dh={spec.Hq}/{spec.Hk}/{spec.dh} "
                                f"F={spec.F} layers={spec.n_layers} kept heads={list(map(int, wl.k_head))} "
                                f"kept channels={int(wl.k_ffn[0])} U={res['U']} patterns={wl.P}",
-                   "step": "gate_scores_to_masks + compact_heads_channels + encoder_forward"},
+                   "step": "gate_scores_to_masks + compact_heads_channels + encoder_forward",
+                   "launch": res["launch"]},
         "algorithmic_tflop_per_step": res["algorithmic_tflop_per_step"],
         "tflops": res["tflops_total"], "frac_of_bf16_peak": res["tflops_total"] / PEAK_BF16_TFLOPS,
     }
     if extras:
         out["detail"] = {k: res[k] for k in ("ms_encoder_only", "ms_plan_only", "tokens_per_s_encoder_only",
-                                             "host_ms_per_step") if k in res}
+                                             "host_ms_per_step", "ms_per_step_eager") if k in res}
         k = res.get("kernels", {})
         if "gemm" in k and "by_launch" in k["gemm"]:
             # the dominant kernel: the GEMM launch that takes the most time per step
@@ -300,9 +336,9 @@ def main():
             name = name.strip()
             if not name or name == args.config:
                 continue
-            r, dm2, _, _ = bench_config(name, args.steps, args.warmup, True, False)
+            r, dm2, _, _ = bench_config(name, args.steps, args.warmup, True, False, args.graph)
             others[name] = {k: r[k] for k in ("ms_per_step", "tokens_per_s", "tflops_total", "ms_encoder_only",
-                                              "ms_plan_only", "host_ms_per_step") if k in r}
+                                              "ms_plan_only", "host_ms_per_step", "launch", "ms_per_step_eager") if k in r}
             others[name]["kernels"] = r.get("kernels")
             del dm2
             torch.cuda.empty_cache()

@@ -405,6 +405,51 @@ def test_encoder_is_deterministic_and_reusable():
     assert torch.equal(y1, y2) and torch.equal(s1, s2)
 
 
+@pytest.mark.parametrize("which", ["small-bf16", "small-f32", "C2"])
+def test_step_under_hip_graph_replay(which):
+    """The whole step (masks + compaction + encoder) recorded into a HIP graph: every replay, with eager work
+    and synchronisations in between, must reproduce the eager result bit for bit."""
+    _say(f"graph replay {which}")
+    if which == "C2":
+        wl = W.make_workload(W.CONFIGS["C2"])
+    else:
+        wl = W.make_workload(W.small_spec(dtype=which.split("-")[1], d=64, dh=32, F=192, seg=(70, 50, 90), B=4, nl=2))
+    dm = DeviceModel(wl).build_plan()
+    y = torch.empty_like(dm.x)
+
+    def step():
+        dm.build_plan()
+        dm.forward(out=y)
+
+    step()
+    torch.cuda.synchronize()
+    y_eager = y.clone()
+    masks_eager = {k: v.clone() for k, v in dm.masks.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        y.fill_(float("nan"))
+        for v in dm.masks.values():
+            v.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {rep} differs from the eager step"
+        for k, v in dm.masks.items():
+            assert torch.equal(v, masks_eager[k]), f"replay {rep}: {k} differs"
+        step()                                     # eager work between the replays, same buffers
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager)
+
+
 def test_encoder_rejects_small_workspace():
     wl = W.make_workload(W.small_spec(dtype="f32", B=2))
     dm = DeviceModel(wl).build_plan()
