@@ -121,9 +121,18 @@ def layernorm(x, gamma, beta, eps: float = 1e-5, bf16: bool = False) -> np.ndarr
     return y
 
 
+def _sample(sample_idx, B):
+    if sample_idx is None:
+        return None, 0
+    si = np.ascontiguousarray(sample_idx, dtype=np.int32)
+    assert si.ndim == 2 and si.shape[0] == B, si.shape
+    return si, si.shape[1]
+
+
 def sparse_gqa(Q, K, V, head_group, U: int, key_valid=None, forced_sel=None, bf16: bool = False,
-               head_group_b=None, want_score: bool = True):
-    """Returns (O [B,L,nH*dh], score [B,nH,L], sel [B,nH,U], prob_check [2])."""
+               head_group_b=None, want_score: bool = True, sample_idx=None):
+    """Returns (O [B,L,nH*dh], score [B,nH,L], sel [B,nH,U], prob_check [2]).
+    sample_idx [B,S] (optional): key sample of the sparsity score."""
     Q, K, V = _f64(Q), _f64(K), _f64(V)
     B, nH, L, dh = Q.shape
     nG = K.shape[1]
@@ -136,8 +145,10 @@ def sparse_gqa(Q, K, V, head_group, U: int, key_valid=None, forced_sel=None, bf1
     score = np.zeros((B, nH, L), np.float64) if want_score else None
     sel = np.full((B, nH, max(U, 1)), -1, np.int32)
     chk = np.zeros(2, np.float64)
+    si, ns = _sample(sample_idx, B)
     rc = lib().orc_sparse_gqa(C.c_int32(B), C.c_int32(nH), C.c_int32(nG), C.c_int32(L),
                               C.c_int32(dh), _p(Q), _p(K), _p(V), _p(hg), _p(hgb), _p(kv),
+                              _p(si), C.c_int32(ns),
                               C.c_int32(U), _p(fs), C.c_int32(int(bf16)), _p(O), _p(score),
                               _p(sel), _p(chk))
     if rc != 0:
@@ -189,7 +200,7 @@ def pruned_ffn(pack: LayerPack, x, act: int = 0, eps: float = 1e-5, pre_ln: bool
 def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,
                     key_valid=None, act: int = 0, eps: float = 1e-5, forced_sel=None,
                     final_ln: Optional[Dict[str, np.ndarray]] = None, bf16: bool = False,
-                    want_sel: bool = True, want_score: bool = False):
+                    want_sel: bool = True, want_score: bool = False, sample_idx=None):
     """packs[l][p] = LayerPack of layer l, pattern p.
     Returns (y [B,L,d], sel [nl,B,nHmax,U] or None, score [nl,B,nHmax,L] or None)."""
     x = _f64(x)
@@ -212,9 +223,10 @@ def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=
     y = np.empty_like(x)
     sel = np.full((nl, B, nHmax, max(U, 1)), -1, np.int32) if want_sel else None
     score = np.full((nl, B, nHmax, L), -np.inf, np.float64) if want_score else None
+    si, ns = _sample(sample_idx, B)
     rc = lib().orc_encoder_forward(
         C.c_int32(B), C.c_int32(L), C.c_int32(nl), C.c_int32(P), arr, _p(pid), _p(kv),
-        C.c_int32(U), C.c_int32(act), C.c_double(eps), _p(fs), C.c_int32(nHmax), _p(fg), _p(fb),
+        _p(si), C.c_int32(ns), C.c_int32(U), C.c_int32(act), C.c_double(eps), _p(fs), C.c_int32(nHmax), _p(fg), _p(fb),
         C.c_int32(int(bf16)), _p(x), _p(y), _p(sel), _p(score))
     if rc != 0:
         raise ValueError("orc_encoder_forward: bad arguments")

@@ -188,31 +188,43 @@ static int int_asc(const void *a, const void *b)
  * q [L,dh] one head's queries, k,v [L,dh] its group's keys/values,
  * valid [L] or NULL.  Writes o rows at o[i*o_stride + 0..dh).
  * score_out [L] or NULL, sel_out [U] or NULL, forced [U] or NULL.
+ * score_keys [L] or NULL: when given, the sparsity score only looks at the
+ * allowed keys j with score_keys[j] != 0 (the sampled-key estimate of the
+ * measure); the attention of the active rows and the context vector always
+ * use every allowed key.
  */
 static void sgqa_one_head(int32_t L, int32_t dh, const double *q, const double *k,
-                          const double *v, const uint8_t *valid, int32_t U,
-                          const int32_t *forced, int32_t bf16, double *o, int64_t o_stride,
-                          double *score_out, int32_t *sel_out, double *prob_check)
+                          const double *v, const uint8_t *valid, const uint8_t *score_keys,
+                          int32_t U, const int32_t *forced, int32_t bf16, double *o,
+                          int64_t o_stride, double *score_out, int32_t *sel_out,
+                          double *prob_check)
 {
     const double scale = 1.0 / sqrt((double)dh);
-    int32_t n_allowed = 0;
-    for (int32_t j = 0; j < L; ++j) if (!valid || valid[j]) ++n_allowed;
+    int32_t n_allowed = 0, n_score = 0;
+    for (int32_t j = 0; j < L; ++j) {
+        if (valid && !valid[j]) continue;
+        ++n_allowed;
+        if (!score_keys || score_keys[j]) ++n_score;
+    }
 
-    /* sparsity score of every query: max_j s_ij - mean_j s_ij over allowed keys */
+    /* sparsity score of every query: max_j s_ij - mean_j s_ij over the allowed
+     * (and, if a sample is given, sampled) keys; 0 when that set is empty */
     double *M = (double *)malloc(sizeof(double) * (size_t)L);
 #pragma omp parallel for schedule(static)
     for (int32_t i = 0; i < L; ++i) {
         if (valid && !valid[i]) { M[i] = -INFINITY; continue; }
+        if (n_score == 0) { M[i] = 0.0; continue; }
         double mx = -INFINITY, sum = 0.0;
         for (int32_t j = 0; j < L; ++j) {
             if (valid && !valid[j]) continue;
+            if (score_keys && !score_keys[j]) continue;
             double s = 0.0;
             for (int32_t e = 0; e < dh; ++e) s += q[(int64_t)i * dh + e] * k[(int64_t)j * dh + e];
             s *= scale;
             if (s > mx) mx = s;
             sum += s;
         }
-        M[i] = mx - sum / n_allowed;
+        M[i] = mx - sum / n_score;
     }
     if (score_out) memcpy(score_out, M, sizeof(double) * (size_t)L);
 
@@ -296,10 +308,20 @@ static void sgqa_one_head(int32_t L, int32_t dh, const double *q, const double *
     free(ctx); free(chosen); free(active); free(M);
 }
 
+/* membership mask [L] of one sample's key sample (entries outside [0, L) are ignored) */
+static uint8_t *sample_mask(const int32_t *sample_idx, int32_t n_sample, int32_t L)
+{
+    uint8_t *m = (uint8_t *)calloc((size_t)L, 1);
+    for (int32_t r = 0; r < n_sample; ++r)
+        if (sample_idx[r] >= 0 && sample_idx[r] < L) m[sample_idx[r]] = 1;
+    return m;
+}
+
 int32_t orc_sparse_gqa(int32_t B, int32_t nH, int32_t nG, int32_t L, int32_t dh,
                        const double *Q, const double *K, const double *V,
                        const int32_t *head_group, const int32_t *head_group_b,
-                       const uint8_t *key_valid, int32_t U, const int32_t *forced_sel,
+                       const uint8_t *key_valid, const int32_t *sample_idx, int32_t n_sample,
+                       int32_t U, const int32_t *forced_sel,
                        int32_t bf16, double *O, double *score, int32_t *sel,
                        double *prob_check)
 {
@@ -313,18 +335,20 @@ int32_t orc_sparse_gqa(int32_t B, int32_t nH, int32_t nG, int32_t L, int32_t dh,
             for (int32_t j = 0; j < L; ++j) n += valid[j] != 0;
             if (n == 0) { free(o_tmp); return -1; }
         }
+        uint8_t *skeys = sample_idx ? sample_mask(sample_idx + (int64_t)b * n_sample, n_sample, L) : NULL;
         for (int32_t h = 0; h < nH; ++h) {
             const int32_t g = head_group_b ? head_group_b[(int64_t)b * nH + h] : head_group[h];
-            if (g < 0 || g >= nG) { free(o_tmp); return -1; }
+            if (g < 0 || g >= nG) { free(o_tmp); free(skeys); return -1; }
             const int64_t bh = (int64_t)b * nH + h;
             sgqa_one_head(L, dh, Q + bh * L * dh, K + ((int64_t)b * nG + g) * L * dh,
-                          V + ((int64_t)b * nG + g) * L * dh, valid, U,
+                          V + ((int64_t)b * nG + g) * L * dh, valid, skeys, U,
                           forced_sel ? forced_sel + bh * U : NULL, bf16,
                           O ? O + (int64_t)b * L * nH * dh + (int64_t)h * dh : o_tmp,
                           O ? (int64_t)nH * dh : dh,
                           score ? score + bh * L : NULL, sel ? sel + bh * U : NULL,
                           prob_check);
         }
+        free(skeys);
     }
     free(o_tmp);
     return 0;
@@ -387,7 +411,8 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
 /* ---- encoder stack ------------------------------------------------------- */
 int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                             const orc_layer *layers, const int32_t *pattern_id,
-                            const uint8_t *key_valid, int32_t U, int32_t act, double eps,
+                            const uint8_t *key_valid, const int32_t *sample_idx, int32_t n_sample,
+                            int32_t U, int32_t act, double eps,
                             const int32_t *forced_sel, int32_t nHmax,
                             const double *final_g, const double *final_b, int32_t bf16,
                             const double *x, double *y, int32_t *sel_out, double *score_out)
@@ -409,6 +434,7 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
         const int32_t p = pattern_id ? pattern_id[b] : 0;
         if (p < 0 || p >= P) { rc = -1; break; }
         memcpy(cur, x + b * Ld, sizeof(double) * (size_t)Ld);
+        uint8_t *skeys = sample_idx ? sample_mask(sample_idx + (int64_t)b * n_sample, n_sample, L) : NULL;
 
         for (int32_t l = 0; l < nl; ++l) {
             const orc_layer *w = &layers[(int64_t)l * P + p];
@@ -441,7 +467,7 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                 const int32_t g = w->head_group[h];
                 const int64_t slot = (((int64_t)l * B + b) * nHmax + h);
                 sgqa_one_head(L, dh, Q + (int64_t)h * L * dh, Kg + (int64_t)g * L * dh,
-                              Vg + (int64_t)g * L * dh, valid, U,
+                              Vg + (int64_t)g * L * dh, valid, skeys, U,
                               forced_sel ? forced_sel + slot * U : NULL, bf16,
                               O + (int64_t)h * dh, (int64_t)nH * dh,
                               score_out ? score_out + slot * L : NULL,
@@ -471,6 +497,7 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
 
             free(O); free(Vg); free(Kg); free(Q);
         }
+        free(skeys);
         if (rc) break;
         if (final_g || final_b) {
             orc_layernorm(cur, L, d, final_g, final_b, eps, bf16, y + b * Ld);

@@ -93,6 +93,12 @@ void orc_layernorm(const double *x, int64_t rows, int32_t d, const double *gamma
  *   Q [B,nH,L,dh], K,V [B,nG,L,dh], head_group [nH] (shared by all samples)
  *   head_group_b: if not NULL, [B,nH] per-sample head->group map (overrides)
  *   key_valid [B,L] or NULL (all keys allowed)
+ *   sample_idx [B,n_sample] or NULL: key sample of each sample for the
+ *             sparsity score (the sampled-key estimate behind the O(T log T)
+ *             claim of Sec. 4.4): the score's max and mean run over the allowed
+ *             keys listed here only (a set: duplicates and entries outside
+ *             [0,L) are ignored; an empty set scores every allowed query 0).
+ *             Active-row attention and the context vector are unaffected.
  *   U         number of active queries per head (U >= L: every row active)
  *   forced_sel [B,nH,U] or NULL: use these query indices (entries < 0 skipped)
  *              instead of the oracle's own top-U choice
@@ -107,7 +113,8 @@ void orc_layernorm(const double *x, int64_t rows, int32_t d, const double *gamma
 int32_t orc_sparse_gqa(int32_t B, int32_t nH, int32_t nG, int32_t L, int32_t dh,
                        const double *Q, const double *K, const double *V,
                        const int32_t *head_group, const int32_t *head_group_b,
-                       const uint8_t *key_valid, int32_t U, const int32_t *forced_sel,
+                       const uint8_t *key_valid, const int32_t *sample_idx, int32_t n_sample,
+                       int32_t U, const int32_t *forced_sel,
                        int32_t bf16, double *O, double *score, int32_t *sel,
                        double *prob_check);
 
@@ -127,6 +134,8 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
  *   layers [nl*P]      layer l of pattern p at layers[l*P + p]
  *   pattern_id [B]     (NULL = all 0)
  *   key_valid [B,L] or NULL
+ *   sample_idx [B,n_sample] or NULL: key sample for the sparsity score, as in
+ *              orc_sparse_gqa (the same sample in every layer)
  *   forced_sel [nl,B,nHmax,U] or NULL (nHmax = max nH over all layers)
  *   sel_out    [nl,B,nHmax,U] or NULL, score_out [nl,B,nHmax,L] or NULL
  *   final_g/final_b [d] or NULL (no final LN)
@@ -140,7 +149,8 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
  */
 int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                             const orc_layer *layers, const int32_t *pattern_id,
-                            const uint8_t *key_valid, int32_t U, int32_t act, double eps,
+                            const uint8_t *key_valid, const int32_t *sample_idx, int32_t n_sample,
+                            int32_t U, int32_t act, double eps,
                             const int32_t *forced_sel, int32_t nHmax,
                             const double *final_g, const double *final_b, int32_t bf16,
                             const double *x, double *y, int32_t *sel_out, double *score_out);

@@ -291,6 +291,75 @@ def test_all_ones_mask_equals_no_mask():
         assert np.array_equal(x, y)
 
 
+def test_sampled_score_pins():
+    """Sampled-key estimate of the sparsity score (the reading behind the O(T log T) claim of Sec. 4.4):
+    max and mean run over the caller's key sample only; attention itself still uses every allowed key."""
+    rng = np.random.default_rng(21)
+    B, H, G, L, dh, U = 2, 3, 1, 17, 5, 4
+    Q, K, V = rng.standard_normal((B, H, L, dh)), rng.standard_normal((B, G, L, dh)), rng.standard_normal((B, G, L, dh))
+    valid = (rng.random((B, L)) < 0.7).astype(np.uint8); valid[:, :2] = 1
+    hg = [0, 0, 0]
+    base = orc.sparse_gqa(Q, K, V, hg, U=U, key_valid=valid)
+    # (1) the sample "all keys" (any order, with padding, duplicates and out-of-range entries) is the plain score
+    full = np.stack([np.concatenate([rng.permutation(L), [-1, 3, 3, L, L + 7]]) for _ in range(B)]).astype(np.int32)
+    same = orc.sparse_gqa(Q, K, V, hg, U=U, key_valid=valid, sample_idx=full)
+    for x, y in zip(base[:3], same[:3]):
+        assert np.array_equal(x, y)
+    # (2) definition written out for a random sample: per query, max - mean of q.k/sqrt(dh) over sample & allowed
+    samp = np.stack([rng.choice(L, 6, replace=False) for _ in range(B)]).astype(np.int32)
+    O, M, sel, chk = orc.sparse_gqa(Q, K, V, hg, U=U, key_valid=valid, sample_idx=samp)
+    for b in range(B):
+        keys = sorted(j for j in set(samp[b].tolist()) if valid[b, j])
+        assert keys, "seed gives a non-empty intersection"
+        for h in range(H):
+            s = Q[b, h] @ K[b, 0][keys].T / math.sqrt(dh)                  # [L, |keys|]
+            want = s.max(axis=1) - s.mean(axis=1)
+            ok = valid[b] == 1
+            assert np.allclose(M[b, h][ok], want[ok], atol=1e-13)
+            assert np.isneginf(M[b, h][~ok]).all()
+            order = sorted(np.flatnonzero(ok).tolist(), key=lambda i: (-np.float32(M[b, h, i]), i))[:U]
+            assert [int(i) for i in sel[b, h] if i >= 0] == sorted(order)
+    # (3) the sample only moves the choice of active rows: with that choice forced, the outputs are those of the
+    #     unsampled operator (same softmax over all allowed keys, same context vector)
+    forced = orc.sparse_gqa(Q, K, V, hg, U=U, key_valid=valid, forced_sel=sel)
+    assert np.array_equal(forced[0], O)
+    assert chk[0] < 1e-14 and chk[1] == 0.0
+    # (4) closed form, dh = 1, positive queries, sample {0, 2} of keys (1, -1, 2): M_i = 2 q_i - 1.5 q_i = q_i / 2;
+    #     a one-key sample has max = mean, so M = 0 and the tie rule takes the lowest indices
+    q = np.array([[[[1.0], [2.0], [3.0]]]]); k = np.array([[[[1.0], [-1.0], [2.0]]]]); v = np.zeros((1, 1, 3, 1))
+    _, M4, sel4, _ = orc.sparse_gqa(q, k, v, [0], U=1, sample_idx=np.array([[0, 2]], np.int32))
+    assert np.allclose(M4[0, 0], [0.5, 1.0, 1.5], atol=1e-15) and sel4[0, 0].tolist() == [2]
+    _, M5, sel5, _ = orc.sparse_gqa(q, k, v, [0], U=2, sample_idx=np.array([[1]], np.int32))
+    assert np.array_equal(M5[0, 0], np.zeros(3)) and sel5[0, 0].tolist() == [0, 1]
+    # (5) empty intersection with the allowed keys: every allowed query scores 0
+    vmask = np.array([[1, 0, 1]], np.uint8)
+    _, M6, sel6, _ = orc.sparse_gqa(q, k, v, [0], U=1, key_valid=vmask, sample_idx=np.array([[1, -1]], np.int32))
+    assert M6[0, 0, 0] == 0.0 and M6[0, 0, 2] == 0.0 and np.isneginf(M6[0, 0, 1]) and sel6[0, 0].tolist() == [0]
+
+
+def test_encoder_sampled_score_matches_operator():
+    """The encoder passes the same key sample to SentryAttend in every layer: its active sets are those of the
+    operator run on the encoder's own Q/K (checked through forced selection) and differ from the unsampled ones."""
+    wl = W.make_workload(W.small_spec(dtype="f32", B=3, nl=2, seg=(20, 13, 16)))
+    masks = oracle_masks(wl)
+    packs = compact_packs(wl, masks)
+    L = wl.spec.L
+    U = orc.num_active(L, wl.spec.c)
+    rng = np.random.default_rng(5)
+    samp = np.stack([rng.choice(L, 7, replace=False) for _ in range(wl.x.shape[0])]).astype(np.int32)
+    y0, sel0, _ = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, act=wl.spec.act, final_ln=wl.final_ln)
+    y1, sel1, sc1 = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, act=wl.spec.act,
+                                        final_ln=wl.final_ln, sample_idx=samp, want_score=True)
+    assert not np.array_equal(sel0, sel1)
+    y2, _, _ = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, act=wl.spec.act,
+                                   final_ln=wl.final_ln, forced_sel=sel1)
+    assert np.array_equal(y1, y2)                       # the sample changes nothing but the choice of rows
+    full = np.tile(np.arange(L, dtype=np.int32), (wl.x.shape[0], 1))
+    y3, sel3, _ = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, act=wl.spec.act,
+                                      final_ln=wl.final_ln, sample_idx=full)
+    assert np.array_equal(y3, y0) and np.array_equal(sel3, sel0)
+
+
 def test_identical_keys_closed_form():
     """All key rows equal => every s_ij is constant in j => M_i = 0 for all i,
     the tie rule selects the lowest U indices, and every output row (active:
