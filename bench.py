@@ -225,6 +225,45 @@ def bench_sparse_gqa(dm, wl, steps):
     return out
 
 
+def bench_sampled_score(wl, steps, warmup):
+    """The same step with the sampled-key sparsity score: n_sample = U = c*ceil(ln L) allowed keys per sample
+    (drawn by the caller, seeded), which replaces the 2*L*L*dh score stream by 2*L*U*dh per head."""
+    import numpy as np
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from gpu_utils import DeviceModel, to_host
+    s = wl.spec
+    B, L = wl.x.shape[0], s.L
+    U = sf.num_active(sf.make_desc(B, L, s.d, s.Hq, s.Hk, s.dh, s.F, c_factor=s.c))
+    if not (0 < U < L) or s.dtype != "bf16":
+        return None
+    rng = np.random.default_rng(7)
+    samp = np.full((B, U), -1, np.int32)
+    for b in range(B):
+        allowed = np.arange(L) if wl.key_valid is None else np.flatnonzero(wl.key_valid[b])
+        k = min(U, len(allowed))
+        samp[b, :k] = np.sort(rng.choice(allowed, k, replace=False))
+    dm = DeviceModel(wl, sample_idx=samp).build_plan()
+    y = torch.empty_like(dm.x)
+
+    def step():
+        dm.build_plan()
+        dm.forward(out=y)
+
+    ms, _ = time_steps(step, steps, warmup)
+    masks_host = {k: to_host(v) for k, v in dm.masks.items()}
+    fl = algorithmic_flops(wl, masks_host, U)
+    n_allowed = np.full(B, L) if wl.key_valid is None else wl.key_valid.sum(axis=1).astype(np.int64)
+    score = sum(int((int(wl.k_head[l]) * 2 * n_allowed * np.minimum(U, n_allowed) * s.dh).sum()) for l in range(s.n_layers))
+    total = fl["gemm"] + fl["active"] + score
+    del dm
+    torch.cuda.empty_cache()
+    return {"n_sample": U, "ms_per_step": ms, "tokens_per_s": B * L / (ms * 1e-3),
+            "algorithmic_tflop_per_step": total / 1e12, "tflops": total / (ms * 1e-3) / 1e12,
+            "note": "sparsity score over a caller-supplied sample of U allowed keys per sample (sample_idx); "
+                    "`value` above is the score over all allowed keys"}
+
+
 def cpu_baseline(wl, flops_total):
     """The CPU oracle, as it stands, on a bounded number of whole samples of the same workload."""
     import numpy as np
@@ -325,6 +364,7 @@ def main():
                                "avg_launch_us": g["avg_launch_us"], "launches_per_step": g["launches_per_step"]}
         out["kernels"] = k
         out["sparse_gqa"] = bench_sparse_gqa(dm, wl, args.steps)
+        out["sampled_score"] = bench_sampled_score(wl, args.steps, args.warmup)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(wl, flops["total"])

@@ -73,6 +73,8 @@ typedef struct sf_desc {
     float ln_eps;       /* 1e-5 if <= 0 */
     int32_t ffn_pad;    /* kept FFN width is padded with zero channels to a multiple of
                            this; must be a multiple of 64; 64 if <= 0 */
+    int32_t n_sample;   /* entries per sample of the key sample `sample_idx` of the sparsity
+                           score (0 = the score uses every allowed key); at most 4096 */
 } sf_desc;
 
 const char *sf_last_error(void);
@@ -186,6 +188,13 @@ typedef struct sf_strides { int64_t b, h, l; } sf_strides;
  *   key_valid     [B,L] u8, 1 = key/query allowed, or NULL (all allowed);
  *                 a sample with no allowed key gives undefined rows for that
  *                 sample (callers validate presence on the host)
+ *   sample_idx    [B,desc->n_sample] int32 or NULL: key sample of step 1 (the
+ *                 sampled-key estimate of the measure, which is what makes the
+ *                 score O(L log L) when n_sample ~ c*ceil(ln L)): max and mean
+ *                 of step 1 run over the allowed keys listed here only.  A set:
+ *                 duplicates and entries outside [0,L) are ignored; if no listed
+ *                 key is allowed, every allowed query scores 0.  Steps 3 and 4
+ *                 always use every allowed key.  Ignored when desc->n_sample = 0.
  *   forced_sel    [B,nH,U] int32 or NULL: active queries given by the caller
  *                 (ascending, distinct, -1 padded at the end); skips 1-2
  *   O             [B,L,nH*dh], row stride ldo elements
@@ -197,7 +206,8 @@ int32_t sf_sparse_gqa_forward(const sf_desc *desc, int32_t nH, int32_t nG,
                               const void *Q, sf_strides sq, const void *K, sf_strides sk,
                               const void *V, sf_strides sv, int32_t v_transposed,
                               const int32_t *head_group, const int32_t *pattern_id,
-                              const uint8_t *key_valid, const int32_t *forced_sel,
+                              const uint8_t *key_valid, const int32_t *sample_idx,
+                              const int32_t *forced_sel,
                               void *O, int64_t ldo, int32_t *sel_out, float *score_out,
                               void *workspace, size_t workspace_bytes, void *stream);
 
@@ -221,6 +231,8 @@ int32_t sf_pruned_ffn_forward(const sf_desc *desc, const sf_compact_layer *layer
  *   X [B,L,d] in, Y [B,L,d] out (Y may not alias X)
  *   layers_host [n_layers]  HOST array of sf_compact_layer
  *   pattern_id  [B] or NULL;  key_valid [B,L] or NULL
+ *   sample_idx  [B,desc->n_sample] or NULL: key sample of the sparsity score, the
+ *               same in every layer (see sf_sparse_gqa_forward)
  *   final_g, final_b [d]    (required with SF_FLAG_FINAL_LN)
  *   forced_sel  [n_layers,B,Hq'max,U] or NULL  (Hq'max = max k_head over layers)
  *   sel_out     [n_layers,B,Hq'max,U] or NULL  active queries per layer
@@ -229,7 +241,7 @@ int32_t sf_pruned_ffn_forward(const sf_desc *desc, const sf_compact_layer *layer
 size_t sf_encoder_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers_host);
 int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers_host,
                            const void *X, const int32_t *pattern_id, const uint8_t *key_valid,
-                           const void *final_g, const void *final_b,
+                           const int32_t *sample_idx, const void *final_g, const void *final_b,
                            const int32_t *forced_sel, void *Y, int32_t *sel_out,
                            float *score_out, void *workspace, size_t workspace_bytes,
                            void *stream);

@@ -33,7 +33,7 @@ class SfDesc(C.Structure):
                 ("Hq", C.c_int32), ("Hk", C.c_int32), ("dh", C.c_int32), ("d_ff", C.c_int32),
                 ("n_layers", C.c_int32), ("P", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
                 ("c_factor", C.c_int32), ("U_override", C.c_int32), ("flags", C.c_uint32),
-                ("ln_eps", C.c_float), ("ffn_pad", C.c_int32)]
+                ("ln_eps", C.c_float), ("ffn_pad", C.c_int32), ("n_sample", C.c_int32)]
 
 
 class SfStrides(C.Structure):
@@ -74,7 +74,7 @@ def lib():
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
-            SfStrides, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+            SfStrides, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_gate_scores_to_masks.argtypes = [C.POINTER(SfDesc)] + [C.c_void_p] * 12
         L.sf_compact_heads_channels.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayer),
@@ -84,7 +84,7 @@ def lib():
                                             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_encoder_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_encoder_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)]
         L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
         L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
@@ -114,9 +114,9 @@ def torch_dtype(dtype: int):
 
 
 def make_desc(B, L, d_model, Hq, Hk, dh, d_ff, n_layers=1, P=1, dtype=SF_BF16, act=SF_RELU, c_factor=5,
-              U_override=-1, final_ln=False, ln_eps=1e-5, ffn_pad=64) -> SfDesc:
+              U_override=-1, final_ln=False, ln_eps=1e-5, ffn_pad=64, n_sample=0) -> SfDesc:
     return SfDesc(C.sizeof(SfDesc), B, L, d_model, Hq, Hk, dh, d_ff, n_layers, P, dtype, act, c_factor,
-                  U_override, SF_FLAG_FINAL_LN if final_ln else 0, ln_eps, ffn_pad)
+                  U_override, SF_FLAG_FINAL_LN if final_ln else 0, ln_eps, ffn_pad, n_sample)
 
 
 def num_active(desc: SfDesc) -> int:
@@ -261,9 +261,11 @@ def sparse_gqa_forward(desc: SfDesc, Q: torch.Tensor, K: torch.Tensor, V: torch.
                        head_group: torch.Tensor, pattern_id: Optional[torch.Tensor] = None,
                        key_valid: Optional[torch.Tensor] = None, forced_sel: Optional[torch.Tensor] = None,
                        v_transposed: bool = False, want_sel: bool = True, want_score: bool = False,
-                       ws: Optional[torch.Tensor] = None):
+                       ws: Optional[torch.Tensor] = None, sample_idx: Optional[torch.Tensor] = None):
     """Q [B,nH,L,dh], K [B,nG,L,dh], V [B,nG,L,dh] (or [B,nG,dh,L] with v_transposed);
-    last dimension contiguous.  Returns (O [B,L,nH*dh], sel [B,nH,U] | None, score [B,nH,L] | None)."""
+    last dimension contiguous.  sample_idx [B, desc.n_sample] int32: key sample of the sparsity score.
+    Returns (O [B,L,nH*dh], sel [B,nH,U] | None, score [B,nH,L] | None)."""
+    _check_sample(desc, sample_idx, Q.shape[0])
     B, nH, L, dh = Q.shape
     nG = K.shape[1]
     U = num_active(desc)
@@ -275,12 +277,19 @@ def sparse_gqa_forward(desc: SfDesc, Q: torch.Tensor, K: torch.Tensor, V: torch.
         ws = workspace(sparse_gqa_workspace_bytes(desc, nH, nG), dev)
     rc = lib().sf_sparse_gqa_forward(
         C.byref(desc), nH, nG, _ptr(Q), _strides4(Q), _ptr(K), _strides4(K), _ptr(V), _strides4(V),
-        int(v_transposed), _ptr(head_group), _ptr(pattern_id), _ptr(key_valid), _ptr(forced_sel), _ptr(O),
+        int(v_transposed), _ptr(head_group), _ptr(pattern_id), _ptr(key_valid), _ptr(sample_idx),
+        _ptr(forced_sel), _ptr(O),
         nH * dh, _ptr(sel), _ptr(score), _ptr(ws), ws.numel(), _stream())
     _check(rc, "sf_sparse_gqa_forward")
     if sel is not None:
         sel = sel[:, :, :U]
     return O, sel, score
+
+
+def _check_sample(desc: SfDesc, sample_idx: Optional[torch.Tensor], B: int):
+    if sample_idx is not None:
+        assert sample_idx.dtype == torch.int32 and sample_idx.is_contiguous()
+        assert tuple(sample_idx.shape) == (B, desc.n_sample), (tuple(sample_idx.shape), (B, desc.n_sample))
 
 
 # --------------------------------------------------------------------------- a9
@@ -314,9 +323,11 @@ def encoder_forward(desc: SfDesc, layers: List[CompactLayer], X: torch.Tensor,
                     final_ln: Optional[Dict[str, torch.Tensor]] = None,
                     forced_sel: Optional[torch.Tensor] = None, want_sel: bool = False,
                     want_score: bool = False, out: Optional[torch.Tensor] = None,
-                    ws: Optional[torch.Tensor] = None):
-    """Returns (Y [B,L,d], sel [nl,B,Hq'max,U] | None, score [nl,B,Hq'max,L] | None)."""
+                    ws: Optional[torch.Tensor] = None, sample_idx: Optional[torch.Tensor] = None):
+    """sample_idx [B, desc.n_sample] int32: key sample of the sparsity score (every layer).
+    Returns (Y [B,L,d], sel [nl,B,Hq'max,U] | None, score [nl,B,Hq'max,L] | None)."""
     assert X.is_contiguous()
+    _check_sample(desc, sample_idx, X.shape[0])
     B, L, _ = X.shape
     nl = desc.n_layers
     U = num_active(desc)
@@ -332,8 +343,8 @@ def encoder_forward(desc: SfDesc, layers: List[CompactLayer], X: torch.Tensor,
         ws = workspace(lib().sf_encoder_workspace_bytes(C.byref(desc), arr), dev)
     fg = None if final_ln is None else final_ln["g"]
     fb = None if final_ln is None else final_ln["b"]
-    rc = lib().sf_encoder_forward(C.byref(desc), arr, _ptr(X), _ptr(pattern_id), _ptr(key_valid), _ptr(fg),
-                                  _ptr(fb), _ptr(forced_sel), _ptr(Y), _ptr(sel if U > 0 else None),
+    rc = lib().sf_encoder_forward(C.byref(desc), arr, _ptr(X), _ptr(pattern_id), _ptr(key_valid),
+                                  _ptr(sample_idx), _ptr(fg), _ptr(fb), _ptr(forced_sel), _ptr(Y), _ptr(sel if U > 0 else None),
                                   _ptr(score), _ptr(ws), ws.numel(), _stream())
     _check(rc, "sf_encoder_forward")
     return Y, sel, score

@@ -61,6 +61,8 @@ int32_t read_desc(const sf_desc *desc, Dims &D)
     D.flags = desc->flags;
     D.eps = desc->ln_eps > 0.f ? desc->ln_eps : 1e-5f;
     D.ffn_pad = desc->ffn_pad > 0 ? desc->ffn_pad : 64;
+    D.n_sample = desc->n_sample;
+    if (D.n_sample < 0 || D.n_sample > 4096) return fail(SF_ERR_INVALID_ARG, "descriptor: n_sample must be in [0, 4096]");
     if (D.B < 1 || D.L < 1 || D.d < 1 || D.Hq < 1 || D.Hk < 1 || D.dh < 1 || D.F < 1 || D.nl < 1 || D.P < 1)
         return fail(SF_ERR_INVALID_ARG, "descriptor: sizes must be positive");
     if (D.Hq % D.Hk) return fail(SF_ERR_INVALID_ARG, "descriptor: Hq %% Hk != 0");
@@ -133,7 +135,7 @@ struct EncWs {
 static AttnArgs enc_attn_args(const Dims &D, int kh)
 {
     AttnArgs a{};
-    a.B = D.B; a.nH = kh; a.nG = D.Hk; a.L = D.L; a.dh = D.dh; a.U = D.U;
+    a.B = D.B; a.nH = kh; a.nG = D.Hk; a.L = D.L; a.dh = D.dh; a.U = D.U; a.n_sample = D.n_sample;
     a.v_transposed = D.dtype == SF_BF16;
     return a;
 }
@@ -275,7 +277,8 @@ extern "C" size_t sf_encoder_workspace_bytes(const sf_desc *desc, const sf_compa
 
 extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers, const void *X,
                                       const int32_t *pattern_id, const uint8_t *key_valid,
-                                      const void *final_g, const void *final_b, const int32_t *forced_sel,
+                                      const int32_t *sample_idx, const void *final_g, const void *final_b,
+                                      const int32_t *forced_sel,
                                       void *Y, int32_t *sel_out, float *score_out, void *workspace,
                                       size_t workspace_bytes, void *stream)
 {
@@ -345,6 +348,7 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
             a.V = (const char *)w.qkv + (size_t)(kh + Hk) * dh * es; a.sv = a.sq;
         }
         a.head_group = ly.head_group; a.hg_stride = D.Hq; a.pattern_id = pattern_id; a.key_valid = key_valid;
+        a.sample_idx = D.n_sample > 0 ? sample_idx : nullptr;
         a.selH = w.kh_max;
         const size_t sel_layer = (size_t)D.B * w.kh_max * D.U, score_layer = (size_t)D.B * w.kh_max * D.L;
         a.forced_sel = forced_sel ? forced_sel + l * sel_layer : nullptr;

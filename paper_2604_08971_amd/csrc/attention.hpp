@@ -14,6 +14,7 @@ struct AttnArgs {
     const int32_t *head_group; int hg_stride;   // head_group[pattern(b)*hg_stride + h]
     const int32_t *pattern_id;               // [B] or NULL
     const uint8_t *key_valid;                // [B,L] or NULL
+    const int32_t *sample_idx; int n_sample; // [B,n_sample] key sample of the sparsity score, or NULL / 0
     const int32_t *forced_sel;               // [B,selH,U] or NULL
     void *O; int64_t ldo;                    // [B,L,nH*dh]
     int32_t *sel_out;                        // [B,selH,U] or NULL
@@ -30,18 +31,22 @@ struct AttnPlan {
     int stat_chunks;       // partial-sum chunks of the K/V statistics
     int Upad;              // U rounded up to 32
     int Lp;                // L rounded up to 8 (row length of the transposed V copy)
+    int Sp;                // key-sample size rounded up to 64 (0: no sample)
     size_t bytes;
     // carved pointers (NULL when planning only)
     void *vt; float *stat_part; float *stats; int32_t *n_valid; float *score;
     int32_t *sel; int32_t *slot; float *part_o; float *part_ml;
+    void *ks; uint8_t *ks_valid; float *ks_stats; int32_t *n_keys;   // gathered key sample [B,nG,Sp,dh], its validity [B,Sp]
 };
 AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws);
 
 int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st);
 
 // bf16 MFMA kernels (attention_bf16.hip)
-// score [B,scoreH,L]; sel [B,selH,U]
-int32_t score_bf16(const AttnArgs &a, const AttnPlan &pl, float *score, int scoreH, hipStream_t st);
+// score [B,scoreH,L]; sel [B,selH,U].  The score is taken over the Lk keys `Kx` (strides skx) with
+// validity key_mask [B,Lk] (NULL: all) and mean-key statistics `stats`; queries use a.key_valid.
+int32_t score_bf16(const AttnArgs &a, const void *Kx, sf_strides skx, int Lk, const uint8_t *key_mask,
+                   const float *stats, float *score, int scoreH, hipStream_t st);
 int32_t attend_bf16(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_strides svt,
                     const int32_t *sel, int selH, hipStream_t st);
 

@@ -100,14 +100,15 @@ template <int DH, int QBS>
 __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
-    const uint8_t *__restrict__ key_valid, const float *__restrict__ stats, int nH, int nG, int L,
-    float *__restrict__ score, int scoreH, int qblocks, int n_items)
+    const uint8_t *__restrict__ query_valid, const uint8_t *__restrict__ key_mask,
+    const float *__restrict__ stats, int nH, int nG, int L, int Lk, float *__restrict__ score, int scoreH,
+    int qblocks, int n_items)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                              // [2][BKEY][DH+PAD]
     float *kbar = reinterpret_cast<float *>(Ks + 2 * BKEY * (DH + PAD));        // [DH]
-    uint32_t *words = reinterpret_cast<uint32_t *>(kbar + DH);                  // [ceil(L/32)]
-    uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (L + 31) / 32);      // [ceil(L/64)]
+    uint32_t *words = reinterpret_cast<uint32_t *>(kbar + DH);                  // [ceil(Lk/32)]
+    uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (Lk + 31) / 32);     // [ceil(Lk/64)]
     __shared__ int n_tiles;
 
     const int item = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
@@ -115,9 +116,9 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     const int qblk = item % qblocks, bh = item / qblocks, b = bh / nH, h = bh % nH;
     const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
-    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
-    const int nwords = (L + 31) / 32;
-    build_mask_words(kv, L, words, nwords);
+    const uint8_t *kv = query_valid ? query_valid + (int64_t)b * L : nullptr;
+    const int nwords = (Lk + 31) / 32;
+    build_mask_words(key_mask ? key_mask + (int64_t)b * Lk : nullptr, Lk, words, nwords);
     if (threadIdx.x < DH) kbar[threadIdx.x] = stats[((int64_t)b * nG + g) * 2 * DH + threadIdx.x];
 
     const __bf16 *Qb = Q + (int64_t)b * sq.b + (int64_t)h * sq.h;
@@ -135,20 +136,20 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
         rmax[qq] = -INFINITY;
     }
     __syncthreads();
-    build_tile_list(words, nwords, 0, L, tiles, &n_tiles);
+    build_tile_list(words, nwords, 0, Lk, tiles, &n_tiles);
     __syncthreads();
     const int nt = n_tiles;
 
     using KT_ = KTile<DH, NWAVE * 64>;
     uint4 kreg[KT_::N];
     auto tile_j0 = [&](int it) { return __builtin_amdgcn_readfirstlane((int)tiles[it]) * BKEY; };   // same for every lane
-    if (nt > 0) KT_::fetch(Kb, sk.l, tile_j0(0), L, kreg);
+    if (nt > 0) KT_::fetch(Kb, sk.l, tile_j0(0), Lk, kreg);
     for (int it = 0; it < nt; ++it) {
         const int j0 = tile_j0(it);
         __bf16 *Kt = Ks + (it & 1) * BKEY * (DH + PAD);
         KT_::put(kreg, Kt);
         __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffer)
-        if (it + 1 < nt) KT_::fetch(Kb, sk.l, tile_j0(it + 1), L, kreg);
+        if (it + 1 < nt) KT_::fetch(Kb, sk.l, tile_j0(it + 1), Lk, kreg);
         // the mask words are the same for every lane: keep them scalar
         const uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)words[j0 / 32]);
         const uint32_t w1 = (j0 / 32 + 1 < nwords) ? (uint32_t)__builtin_amdgcn_readfirstlane((int)words[j0 / 32 + 1]) : 0u;
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
         const int i = q0 + qq * 32 + l32;
         if (lhi == 0 && i < L) {
             const bool ok = !kv || kv[i];
-            score[((int64_t)b * scoreH + h) * L + i] = ok ? (m - dot) * scale : -INFINITY;
+            score[((int64_t)b * scoreH + h) * L + i] = !ok ? -INFINITY : nt == 0 ? 0.f : (m - dot) * scale;   // no key: 0
         }
     }
 }
@@ -473,29 +474,33 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
 
 // ---------------------------------------------------------------- host side
 template <int DH, int QBS>
-static int32_t launch_score(const AttnArgs &a, const AttnPlan &pl, float *score, int scoreH, hipStream_t st)
+static int32_t launch_score(const AttnArgs &a, const void *Kx, sf_strides skx, int Lk, const uint8_t *key_mask,
+                            const float *stats, float *score, int scoreH, hipStream_t st)
 {
-    const size_t lds = (size_t)2 * BKEY * (DH + PAD) * 2 + DH * 4 + (size_t)ceil_div(a.L, 32) * 4 +
-                       (size_t)ceil_div(a.L, BKEY) * 2 + 16;
+    const size_t lds = (size_t)2 * BKEY * (DH + PAD) * 2 + DH * 4 + (size_t)ceil_div(Lk, 32) * 4 +
+                       (size_t)ceil_div(Lk, BKEY) * 2 + 16;
     const int qblocks = ceil_div(a.L, NWAVE * QBS * 32);
     const int64_t items = (int64_t)qblocks * a.B * a.nH;
     if (items > (1 << 30)) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): too many work items");
     dim3 grid((unsigned)align_up(items, 8));
     ProfScope prof(SF_KERNEL_SCORE, st);
     hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
-                       a.sq, (const __bf16 *)a.K, a.sk, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
-                       pl.stats, a.nH, a.nG, a.L, score, scoreH, qblocks, (int)items);
+                       a.sq, (const __bf16 *)Kx, skx, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
+                       key_mask, stats, a.nH, a.nG, a.L, Lk, score, scoreH, qblocks, (int)items);
     return SF_OK;
 }
 
-int32_t score_bf16(const AttnArgs &a, const AttnPlan &pl, float *score, int scoreH, hipStream_t st)
+int32_t score_bf16(const AttnArgs &a, const void *Kx, sf_strides skx, int Lk, const uint8_t *key_mask,
+                   const float *stats, float *score, int scoreH, hipStream_t st)
 {
     const bool wide = a.L >= 1024;
+#define SF_SCORE_ARGS a, Kx, skx, Lk, key_mask, stats, score, scoreH, st
     switch (a.dh) {
-    case 32:  return wide ? launch_score<32, 4>(a, pl, score, scoreH, st) : launch_score<32, 2>(a, pl, score, scoreH, st);
-    case 64:  return wide ? launch_score<64, 4>(a, pl, score, scoreH, st) : launch_score<64, 2>(a, pl, score, scoreH, st);
-    case 128: return wide ? launch_score<128, 2>(a, pl, score, scoreH, st) : launch_score<128, 1>(a, pl, score, scoreH, st);
+    case 32:  return wide ? launch_score<32, 4>(SF_SCORE_ARGS) : launch_score<32, 2>(SF_SCORE_ARGS);
+    case 64:  return wide ? launch_score<64, 4>(SF_SCORE_ARGS) : launch_score<64, 2>(SF_SCORE_ARGS);
+    case 128: return wide ? launch_score<128, 2>(SF_SCORE_ARGS) : launch_score<128, 1>(SF_SCORE_ARGS);
     }
+#undef SF_SCORE_ARGS
     return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): dh must be 32, 64 or 128");
 }
 

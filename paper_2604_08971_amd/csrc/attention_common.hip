@@ -281,26 +281,28 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__rest
 }
 
 // ------------------------------------------------------------ plain fp32 path
-// Sparsity score, one thread per query.
+// Sparsity score, one thread per query, over the Lk keys of K (validity key_mask [B,Lk] or NULL,
+// n_keys[b] of them valid): the sample's own keys, or the gathered key sample.
 __global__ __launch_bounds__(256) void score_f32_kernel(
     const float *__restrict__ Q, sf_strides sq, const float *__restrict__ K, sf_strides sk,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
-    const uint8_t *__restrict__ key_valid, const int32_t *__restrict__ n_valid, int nH, int L, int dh,
-    float *__restrict__ score, int scoreH)
+    const uint8_t *__restrict__ query_valid, const uint8_t *__restrict__ key_mask,
+    const int32_t *__restrict__ n_keys, int nH, int L, int Lk, int dh, float *__restrict__ score, int scoreH)
 {
     const int bh = blockIdx.y, b = bh / nH, h = bh % nH;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= L) return;
-    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     float *out = score + ((int64_t)b * scoreH + h) * L + i;
-    if (kv && !kv[i]) { *out = -INFINITY; return; }
+    if (query_valid && !query_valid[(int64_t)b * L + i]) { *out = -INFINITY; return; }
+    if (n_keys[b] == 0) { *out = 0.f; return; }
+    const uint8_t *km = key_mask ? key_mask + (int64_t)b * Lk : nullptr;
     const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
     const float *q = Q + (int64_t)b * sq.b + (int64_t)h * sq.h + (int64_t)i * sq.l;
     const float *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
     const float scale = 1.0f / sqrtf((float)dh);
     float mx = -INFINITY, sum = 0.f;
-    for (int j = 0; j < L; ++j) {
-        if (kv && !kv[j]) continue;
+    for (int j = 0; j < Lk; ++j) {
+        if (km && !km[j]) continue;
         const float *k = Kb + (int64_t)j * sk.l;
         float s = 0.f;
         for (int e = 0; e < dh; ++e) s = fmaf(q[e], k[e], s);
@@ -308,7 +310,73 @@ __global__ __launch_bounds__(256) void score_f32_kernel(
         mx = fmaxf(mx, s);
         sum += s;
     }
-    *out = mx - sum / (float)n_valid[b];
+    *out = mx - sum / (float)n_keys[b];
+}
+
+// Key sample of the sparsity score: one block per (sample, group).  The sample is treated as a set
+// (LDS bit words, integer atomics), intersected with the allowed keys, listed in ascending key order
+// and gathered into Ks [B,nG,Sp,dh] (zero rows beyond the n_keys[b] listed keys), with the row validity
+// ks_valid [B,Sp] and the mean listed key in ks_stats [(b*nG+g)*2*dh + e] (the layout of the K/V
+// statistics; only the mean-key half is used).
+template <class T>
+__global__ __launch_bounds__(256) void gather_key_sample_kernel(
+    const T *__restrict__ K, sf_strides sk, const uint8_t *__restrict__ key_valid,
+    const int32_t *__restrict__ sample_idx, int n_sample, int nG, int L, int dh, int Sp,
+    T *__restrict__ Ks, uint8_t *__restrict__ ks_valid, float *__restrict__ ks_stats,
+    int32_t *__restrict__ n_keys)
+{
+    extern __shared__ uint32_t gsm[];
+    const int nwords = (L + 31) / 32;
+    uint32_t *words = gsm;                                        // [nwords]
+    int32_t *list = reinterpret_cast<int32_t *>(gsm + nwords);    // [Sp]
+    __shared__ int nk_s;
+    const int bg = blockIdx.x, b = bg / nG, g = bg % nG, tid = threadIdx.x;
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    for (int w = tid; w < nwords; w += 256) words[w] = 0u;
+    __syncthreads();
+    for (int r = tid; r < n_sample; r += 256) {
+        const int idx = sample_idx[(int64_t)b * n_sample + r];
+        if (idx >= 0 && idx < L && (!kv || kv[idx])) atomicOr(&words[idx >> 5], 1u << (idx & 31));
+    }
+    __syncthreads();
+    if (tid < 64) {                                               // ascending list of the set bits
+        int base = 0;
+        for (int w0 = 0; w0 < nwords; w0 += 64) {
+            uint32_t w = (w0 + tid < nwords) ? words[w0 + tid] : 0u;
+            const int pc = __popc(w);
+            int incl = pc;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (tid >= o) incl += t;
+            }
+            int pos = base + incl - pc;
+            while (w) {
+                const int bit = __ffs((int)w) - 1;
+                list[pos++] = (w0 + tid) * 32 + bit;
+                w &= w - 1u;
+            }
+            base += __shfl(incl, 63);
+        }
+        if (tid == 0) nk_s = base;
+    }
+    __syncthreads();
+    const int nk = nk_s;                                          // <= n_sample <= Sp
+    const T *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    T *out = Ks + (int64_t)bg * Sp * dh;
+    for (int t = tid; t < Sp * dh; t += 256) {
+        const int r = t / dh, e = t % dh;
+        out[t] = r < nk ? Kb[(int64_t)list[r] * sk.l + e] : from_f32<T>(0.f);
+    }
+    if (g == 0) {
+        for (int r = tid; r < Sp; r += 256) ks_valid[(int64_t)b * Sp + r] = r < nk ? 1 : 0;
+        if (tid == 0) n_keys[b] = nk;
+    }
+    for (int e = tid; e < dh; e += 256) {
+        float acc = 0.f;
+        for (int r = 0; r < nk; ++r) acc += to_f32(Kb[(int64_t)list[r] * sk.l + e]);
+        ks_stats[((int64_t)bg * 2) * dh + e] = nk ? acc / (float)nk : 0.f;
+    }
 }
 
 // Active rows, Eq. (6): one 64-lane wave per (b, head, slot).
@@ -368,6 +436,7 @@ AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws)
     pl.Upad = (int)align_up(a.U > 0 ? a.U : 1, 32);
     pl.Lp = (int)align_up(a.L, 8);
     pl.stat_chunks = ceil_div(a.L, STAT_CHUNK);
+    pl.Sp = a.n_sample > 0 ? (int)align_up(a.n_sample, 64) : 0;
     pl.splits = 1;
     pl.keys_per_split = (int)align_up(a.L, 64);
     if (dtype == SF_BF16 && sparse && a.U > 0) {
@@ -395,6 +464,12 @@ AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws)
     if (pl.splits > 1) {
         pl.part_o = c.take<float>(BH * pl.Upad * pl.splits * a.dh);
         pl.part_ml = c.take<float>(BH * pl.Upad * pl.splits * 2);
+    }
+    if (pl.Sp > 0) {
+        pl.ks = c.take<char>(BG * pl.Sp * a.dh * elem_size(dtype));
+        pl.ks_valid = c.take<uint8_t>((size_t)a.B * pl.Sp);
+        pl.ks_stats = c.take<float>(BG * 2 * a.dh);
+        pl.n_keys = c.take<int32_t>(a.B);
     }
     pl.bytes = c.off;
     return pl;
@@ -474,13 +549,34 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         if (a.U > 0 && a.U < a.L) {
             float *score = a.score_out ? a.score_out : pl.score;
             scoreH = a.score_out ? userH : a.nH;
+            // keys the score looks at: the sample's own keys, or the gathered key sample
+            const void *Kx = a.K;
+            sf_strides skx = a.sk;
+            int Lk = a.L;
+            const uint8_t *key_mask = a.key_valid;
+            const float *kstats = pl.stats;
+            const int32_t *nkeys = pl.n_valid;
+            if (a.sample_idx && pl.Sp > 0) {
+                const size_t gl = (size_t)ceil_div(a.L, 32) * 4 + (size_t)pl.Sp * 4;
+                if (dtype == SF_BF16)
+                    hipLaunchKernelGGL(gather_key_sample_kernel<__bf16>, dim3(BG), dim3(256), gl, st,
+                                       (const __bf16 *)a.K, a.sk, a.key_valid, a.sample_idx, a.n_sample, a.nG, a.L,
+                                       a.dh, pl.Sp, (__bf16 *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys);
+                else
+                    hipLaunchKernelGGL(gather_key_sample_kernel<float>, dim3(BG), dim3(256), gl, st,
+                                       (const float *)a.K, a.sk, a.key_valid, a.sample_idx, a.n_sample, a.nG, a.L,
+                                       a.dh, pl.Sp, (float *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys);
+                Kx = pl.ks;
+                skx.b = (int64_t)a.nG * pl.Sp * a.dh; skx.h = (int64_t)pl.Sp * a.dh; skx.l = a.dh;
+                Lk = pl.Sp; key_mask = pl.ks_valid; kstats = pl.ks_stats; nkeys = pl.n_keys;
+            }
             if (dtype == SF_BF16) {
-                if (int32_t rc = score_bf16(a, pl, score, scoreH, st)) return rc;
+                if (int32_t rc = score_bf16(a, Kx, skx, Lk, key_mask, kstats, score, scoreH, st)) return rc;
             } else {
                 dim3 grid(ceil_div(a.L, 256), BH);
                 hipLaunchKernelGGL(score_f32_kernel, grid, dim3(256), 0, st, (const float *)a.Q, a.sq,
-                                   (const float *)a.K, a.sk, a.head_group, a.hg_stride, a.pattern_id,
-                                   a.key_valid, pl.n_valid, a.nH, a.L, a.dh, score, scoreH);
+                                   (const float *)Kx, skx, a.head_group, a.hg_stride, a.pattern_id,
+                                   a.key_valid, key_mask, nkeys, a.nH, a.L, Lk, a.dh, score, scoreH);
             }
             M = score;
         }
@@ -531,7 +627,7 @@ static int32_t make_attn_args(const sf_desc *desc, int32_t nH, int32_t nG, Dims 
     if (int32_t rc = read_desc(desc, D)) return rc;
     if (nH < 1 || nG < 1) return fail(SF_ERR_INVALID_ARG, "sparse_gqa: nH and nG must be positive");
     a = AttnArgs{};
-    a.B = D.B; a.nH = nH; a.nG = nG; a.L = D.L; a.dh = D.dh; a.U = D.U;
+    a.B = D.B; a.nH = nH; a.nG = nG; a.L = D.L; a.dh = D.dh; a.U = D.U; a.n_sample = D.n_sample;
     return SF_OK;
 }
 
@@ -547,7 +643,8 @@ extern "C" int32_t sf_sparse_gqa_forward(const sf_desc *desc, int32_t nH, int32_
                                          sf_strides sq, const void *K, sf_strides sk, const void *V,
                                          sf_strides sv, int32_t v_transposed, const int32_t *head_group,
                                          const int32_t *pattern_id, const uint8_t *key_valid,
-                                         const int32_t *forced_sel, void *O, int64_t ldo, int32_t *sel_out,
+                                         const int32_t *sample_idx, const int32_t *forced_sel, void *O,
+                                         int64_t ldo, int32_t *sel_out,
                                          float *score_out, void *workspace, size_t workspace_bytes,
                                          void *stream)
 {
@@ -557,6 +654,7 @@ extern "C" int32_t sf_sparse_gqa_forward(const sf_desc *desc, int32_t nH, int32_
     if (ldo < (int64_t)nH * D.dh) return fail(SF_ERR_SHAPE, "sparse_gqa: ldo smaller than nH*dh");
     a.Q = Q; a.K = K; a.V = V; a.sq = sq; a.sk = sk; a.sv = sv; a.v_transposed = v_transposed != 0;
     a.head_group = head_group; a.hg_stride = nH; a.pattern_id = pattern_id; a.key_valid = key_valid;
+    a.sample_idx = D.n_sample > 0 ? sample_idx : nullptr;
     a.forced_sel = forced_sel; a.O = O; a.ldo = ldo; a.sel_out = sel_out; a.score_out = score_out;
     a.ws = workspace; a.ws_bytes = workspace_bytes;
     return attention_forward(D.dtype, a, static_cast<hipStream_t>(stream));

@@ -27,7 +27,7 @@ struct ProfScope {
 
 // ---- descriptor ------------------------------------------------------------
 struct Dims {
-    int B, L, d, Hq, Hk, dh, F, nl, P, dtype, act, U, ffn_pad;
+    int B, L, d, Hq, Hk, dh, F, nl, P, dtype, act, U, ffn_pad, n_sample;
     unsigned flags;
     float eps;
 };

@@ -30,22 +30,25 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy()
 
 
-def desc_for(wl: W.Workload, B: Optional[int] = None, U_override: int = -1, c: Optional[int] = None):
+def desc_for(wl: W.Workload, B: Optional[int] = None, U_override: int = -1, c: Optional[int] = None,
+             n_sample: int = 0):
     s = wl.spec
     return sf.make_desc(B=wl.x.shape[0] if B is None else B, L=s.L, d_model=s.d, Hq=s.Hq, Hk=s.Hk, dh=s.dh,
                         d_ff=s.F, n_layers=s.n_layers, P=wl.P,
                         dtype=sf.SF_BF16 if s.dtype == "bf16" else sf.SF_F32, act=s.act,
                         c_factor=s.c if c is None else c, U_override=U_override,
-                        final_ln=wl.final_ln is not None)
+                        final_ln=wl.final_ln is not None, n_sample=n_sample)
 
 
 class DeviceModel:
     """A workload resident on the GPU: dense weights, plan (masks, compact layers), inputs."""
 
-    def __init__(self, wl: W.Workload, U_override: int = -1, device="cuda"):
+    def __init__(self, wl: W.Workload, U_override: int = -1, device="cuda", sample_idx: Optional[np.ndarray] = None):
         s = wl.spec
         self.wl, self.device = wl, device
-        self.desc = desc_for(wl, U_override=U_override)
+        self.sample_idx = None if sample_idx is None else torch.from_numpy(
+            np.ascontiguousarray(sample_idx, dtype=np.int32)).to(device)
+        self.desc = desc_for(wl, U_override=U_override, n_sample=0 if sample_idx is None else sample_idx.shape[1])
         dt = s.dtype
         self.x = to_dev(wl.x, dt, device)
         self.pattern_id = to_dev(wl.pattern_id, dt, device)
@@ -75,7 +78,7 @@ class DeviceModel:
             self.ws = sf.workspace(sf.encoder_workspace_bytes(self.desc, self.layers), self.device)
         return sf.encoder_forward(self.desc, self.layers, self.x, self.pattern_id, self.key_valid,
                                   self.final_ln, forced_sel=forced_sel, want_sel=want_sel,
-                                  want_score=want_score, out=out, ws=self.ws)
+                                  want_score=want_score, out=out, ws=self.ws, sample_idx=self.sample_idx)
 
 
 def selection_report(score_oracle: np.ndarray, sel_gpu: np.ndarray, sel_oracle: np.ndarray,

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(sf.SfDesc) == 17 * 4
+    assert C.sizeof(sf.SfDesc) == 18 * 4
     assert C.sizeof(sf.SfStrides) == 24
     assert C.sizeof(sf.SfDenseLayer) == 16 * 8
     assert C.sizeof(sf.SfCompactLayer) == 8 + 14 * 8
@@ -63,13 +63,17 @@ def test_null_and_range_errors_before_any_launch():
     L = sf.lib()
     d = sf.make_desc(2, 16, 64, 8, 2, 8, 64, dtype=sf.SF_F32)
     assert L.sf_gate_scores_to_masks(C.byref(d), *([None] * 12)) == -1
-    assert L.sf_encoder_forward(C.byref(d), None, None, None, None, None, None, None, None, None, None,
+    assert L.sf_encoder_forward(C.byref(d), None, None, None, None, None, None, None, None, None, None, None,
                                 None, 0, None) == -1
     z = sf.SfStrides(0, 0, 0)
-    assert L.sf_sparse_gqa_forward(C.byref(d), 4, 2, None, z, None, z, None, z, 0, None, None, None, None,
+    assert L.sf_sparse_gqa_forward(C.byref(d), 4, 2, None, z, None, z, None, z, 0, None, None, None, None, None,
                                    None, 32, None, None, None, 0, None) == -1
-    assert L.sf_sparse_gqa_forward(C.byref(d), 0, 2, None, z, None, z, None, z, 0, None, None, None, None,
+    assert L.sf_sparse_gqa_forward(C.byref(d), 0, 2, None, z, None, z, None, z, 0, None, None, None, None, None,
                                    None, 32, None, None, None, 0, None) == -1
+    d_bad = sf.make_desc(2, 16, 64, 8, 2, 8, 64, dtype=sf.SF_F32, n_sample=5000)
+    assert L.sf_num_active(C.byref(d_bad)) == -1
+    d_s = sf.make_desc(2, 16, 64, 8, 2, 8, 64, dtype=sf.SF_F32, n_sample=7)
+    assert L.sf_sparse_gqa_workspace_bytes(C.byref(d_s), 4, 2) > L.sf_sparse_gqa_workspace_bytes(C.byref(d), 4, 2)
     assert L.sf_pruned_ffn_forward(C.byref(d), None, None, None, 1, 1, None, None, 0, None) == -1
     assert L.sf_sparse_gqa_workspace_bytes(C.byref(d), 4, 2) > 0
     assert L.sf_pruned_ffn_workspace_bytes(C.byref(d), 0) == 0

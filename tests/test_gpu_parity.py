@@ -124,7 +124,7 @@ def test_compaction_keep_all_is_identity():
 
 # -------------------------------------------------- a4-a7: sparse_gqa_forward
 def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=False, forced=False,
-              v_transposed=False, strided=False):
+              v_transposed=False, strided=False, n_sample=0):
     rng = np.random.default_rng(seed)
     q = W.to_bf16_values if dtype == "bf16" else (lambda a: a.astype(np.float32))
     Q = q(rng.standard_normal((B, nH, L, dh)).astype(np.float32))
@@ -144,8 +144,21 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
             kv[1, [1, L // 2, L - 1]] = 1        # fewer allowed queries than U
     # Hq/Hk of the descriptor describe the dense model and are not used by this entry point
     desc = sf.make_desc(B, L, 64, 8, 2, dh, 64, dtype=sf.SF_BF16 if dtype == "bf16" else sf.SF_F32,
-                        U_override=U_override)
+                        U_override=U_override, n_sample=n_sample)
     U = sf.num_active(desc)
+    samp = None
+    if n_sample:
+        # distinct keys, then a few duplicates, padding and out-of-range entries; sample 0 only hits
+        # disallowed keys when a mask is on (empty intersection: every allowed query scores 0)
+        samp = np.full((B, n_sample), -1, np.int32)
+        for b in range(B):
+            n = max(1, n_sample - 4)
+            samp[b, :n] = rng.choice(L, min(n, L), replace=False)[:n]
+            samp[b, n:] = [samp[b, 0], L + 3, -1, samp[b, n - 1]][: n_sample - n]
+        if mask:
+            bad = np.flatnonzero(kv[0] == 0)
+            samp[0] = -1
+            samp[0, :min(n_sample, len(bad))] = bad[:n_sample]
     hgb = hg[pid] if pid is not None else None
     fs = None
     if forced:
@@ -173,12 +186,12 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
         Vd = vt
     O, sel, score = sf.sparse_gqa_forward(desc, Qd, Kd, Vd, to_dev(hg, dtype), to_dev(pid, dtype),
                                           to_dev(kv, dtype), to_dev(fs, dtype), v_transposed=v_transposed,
-                                          want_sel=True, want_score=True)
+                                          want_sel=True, want_score=True, sample_idx=to_dev(samp, dtype))
     torch.cuda.synchronize()
     O, sel, score = to_host(O), to_host(sel), to_host(score)
 
     bf = dtype == "bf16"
-    _, M_ref, sel_ref, _ = orc.sparse_gqa(Q, K, V, hg[0], U, kv, fs, bf, hgb)
+    _, M_ref, sel_ref, _ = orc.sparse_gqa(Q, K, V, hg[0], U, kv, fs, bf, hgb, sample_idx=samp)
     n_diff = 0
     if not forced:
         for b in range(B):
@@ -232,6 +245,44 @@ def test_sparse_gqa_variants(dtype):
     _gqa_case(dtype, 2, 4, 2, 150, dh, -1, True, seed=3, strided=True)
     _gqa_case(dtype, 2, 4, 2, 150, dh, -1, False, seed=4, v_transposed=True)
     _gqa_case(dtype, 2, 4, 2, 1150, dh, -1, True, seed=5, v_transposed=True, strided=True)
+
+
+@pytest.mark.parametrize("dtype,B,nH,nG,L,dh,ns,mask", [
+    ("f32", 2, 4, 2, 65, 12, 9, False), ("f32", 3, 5, 2, 300, 16, 40, True),
+    ("bf16", 2, 4, 2, 300, 32, 30, True), ("bf16", 3, 6, 3, 777, 64, 35, False),
+    ("bf16", 2, 8, 2, 1100, 64, 150, True), ("bf16", 2, 2, 1, 200, 128, 64, True),
+])
+def test_sparse_gqa_sampled_score_parity(dtype, B, nH, nG, L, dh, ns, mask):
+    _say(f"sgqa sampled {dtype} B={B} nH={nH} nG={nG} L={L} dh={dh} n_sample={ns} mask={mask}")
+    _gqa_case(dtype, B, nH, nG, L, dh, -1, mask, seed=L + ns)
+    _gqa_case(dtype, B, nH, nG, L, dh, -1, mask, seed=L + ns, n_sample=ns)
+    _gqa_case(dtype, B, nH, nG, L, dh, -1, mask, seed=L + ns + 1, n_sample=ns, per_sample_map=True, strided=True,
+              v_transposed=dtype == "bf16")
+
+
+def test_sparse_gqa_full_sample_equals_unsampled():
+    """A sample that lists every key reproduces the unsampled operator (same kernels run on a gathered
+    copy of K in the same key order)."""
+    rng = np.random.default_rng(3)
+    B, nH, nG, L, dh = 2, 4, 2, 384, 64
+    Q, K, V = (to_dev(W.to_bf16_values(rng.standard_normal(s).astype(np.float32)), "bf16")
+               for s in ((B, nH, L, dh), (B, nG, L, dh), (B, nG, L, dh)))
+    hg = to_dev(np.array([[0, 0, 1, 1]], np.int32), "bf16")
+    kv = (rng.random((B, L)) < 0.8).astype(np.uint8); kv[:, 0] = 1
+    d0 = sf.make_desc(B, L, 64, 8, 2, dh, 64, dtype=sf.SF_BF16)
+    d1 = sf.make_desc(B, L, 64, 8, 2, dh, 64, dtype=sf.SF_BF16, n_sample=L)
+    full = to_dev(np.tile(np.arange(L, dtype=np.int32)[::-1], (B, 1)).copy(), "bf16")
+    O0, s0, m0 = sf.sparse_gqa_forward(d0, Q, K, V, hg, None, to_dev(kv, "bf16"), want_score=True)
+    O1, s1, m1 = sf.sparse_gqa_forward(d1, Q, K, V, hg, None, to_dev(kv, "bf16"), want_score=True, sample_idx=full)
+    torch.cuda.synchronize()
+    # the max term is identical (same MFMA products); the mean key is summed in another order, so the scores
+    # agree to fp32 rounding and only an exact near-tie at the U-th score could flip a pick
+    fin = torch.isfinite(m0)
+    assert torch.equal(fin, torch.isfinite(m1))
+    assert float((m0[fin] - m1[fin]).abs().max()) < 2e-5
+    assert int((s0 != s1).sum()) <= 2
+    if torch.equal(s0, s1):
+        assert torch.equal(O0, O1)
 
 
 def test_sparse_gqa_dense_equals_library_attention():
@@ -291,10 +342,10 @@ def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
 
 
 # ------------------------------------------------------------ a10: encoder
-def _encoder_parity(wl, samples=None, U_override=-1, max_pick_diff_frac=0.03):
+def _encoder_parity(wl, samples=None, U_override=-1, max_pick_diff_frac=0.03, sample_idx=None):
     s = wl.spec
     bf = s.dtype == "bf16"
-    dm = DeviceModel(wl, U_override=U_override).build_plan()
+    dm = DeviceModel(wl, U_override=U_override, sample_idx=sample_idx).build_plan()
     U = sf.num_active(dm.desc)
     ref_masks = oracle_masks(wl)
     for k in MASK_KEYS:
@@ -308,12 +359,14 @@ def _encoder_parity(wl, samples=None, U_override=-1, max_pick_diff_frac=0.03):
     packs = compact_packs(wl, ref_masks)
     kv = None if wl.key_valid is None else wl.key_valid[samples]
     # oracle with its own choice: gives the reference scores / choices for the margin check
+    si = None if sample_idx is None else sample_idx[samples]
     y_own, sel_own, score_own = orc.encoder_forward(wl.x[samples], packs, U, wl.pattern_id[samples], kv,
-                                                    act=s.act, final_ln=wl.final_ln, bf16=bf, want_score=True)
+                                                    act=s.act, final_ln=wl.final_ln, bf16=bf, want_score=True,
+                                                    sample_idx=si)
     # oracle forced to the GPU's choice, layer by layer: the output reference
     y_ref, sel_chk, score_f = orc.encoder_forward(wl.x[samples], packs, U, wl.pattern_id[samples], kv, act=s.act,
                                                   forced_sel=sel[:, samples], final_ln=wl.final_ln, bf16=bf,
-                                                  want_score=True)
+                                                  want_score=True, sample_idx=si)
     n_diff = n_tot = picks_diff = picks_tot = 0
     if 0 < U < s.L:
         for l in range(s.n_layers):
@@ -384,6 +437,41 @@ def test_encoder_parity_full_size_sampled(name, n_samples):
         samples = sorted(set(samples[: max(1, n_samples - 2)]) |
                          {int(np.flatnonzero(wl.pattern_id == pats[0])[0]), int(np.flatnonzero(wl.pattern_id == pats[-1])[0])})
     _encoder_parity(wl, samples=samples)
+
+
+def _key_sample(wl, n, seed):
+    """n distinct keys per sample, drawn from the allowed ones (the caller's sampler is not part of the method)."""
+    rng = np.random.default_rng(seed)
+    B, L = wl.x.shape[0], wl.spec.L
+    out = np.full((B, n), -1, np.int32)
+    for b in range(B):
+        allowed = np.arange(L) if wl.key_valid is None else np.flatnonzero(wl.key_valid[b])
+        k = min(n, len(allowed))
+        out[b, :k] = np.sort(rng.choice(allowed, k, replace=False))
+    return out
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f32", B=3, nl=2),
+    dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=4, nl=2),
+    dict(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=300, seg=(100, 33, 64), extra=3, B=3, nl=2, act=1),
+])
+def test_encoder_sampled_score_parity_small(kw):
+    _say(f"encoder sampled small {kw}")
+    wl = W.make_workload(W.small_spec(**kw))
+    _encoder_parity(wl, sample_idx=_key_sample(wl, 12, 1))
+
+
+@pytest.mark.parametrize("name,n_samples", [("C2", 3), ("C5", 1)])
+def test_encoder_sampled_score_parity_full_size(name, n_samples):
+    """Full-size launch with a key sample of U = c*ceil(ln L) keys per sample (the size that makes the
+    score O(L log L))."""
+    _say(f"encoder sampled {name}")
+    wl = W.make_workload(W.CONFIGS[name])
+    U = orc.num_active(wl.spec.L, wl.spec.c)
+    rng = np.random.default_rng(2)
+    samples = sorted(rng.choice(wl.x.shape[0], n_samples, replace=False).tolist())
+    _encoder_parity(wl, samples=samples, sample_idx=_key_sample(wl, U, 3))
 
 
 def test_encoder_dense_pattern_and_U0():
