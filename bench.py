@@ -36,8 +36,8 @@ GEMM_KERNEL_NAMES = {
 # HBM-side bytes per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) and scaled by the
 # reading of the same counters for a plain 256 MiB device copy; the runs are summarised under profiles/.
 MEASURED_TRAFFIC = {
-    ("C5", "ffn_up"): 646.8e6,        # 356.7 MB fetched + 290.1 MB written; algorithmic 104.0 MB read + 281.8 MB written
-    ("C5", "ffn_down"): 691.0e6,      # 588.1 MB fetched + 102.9 MB written; algorithmic 486.4 MB read + 100.7 MB written
+    ("C5", "ffn_up"): 646.9e6,        # 356.8 MB fetched + 290.1 MB written; algorithmic 104.0 MB read + 281.8 MB written
+    ("C5", "ffn_down"): 715.3e6,      # 599.2 MB fetched + 116.1 MB written; algorithmic 486.4 MB read + 100.7 MB written
 }
 
 
