@@ -38,6 +38,11 @@ class _Layer(C.Structure):
                                              "head_group", "head_mask", "ffn_mask")])
 
 
+class _Moe(C.Structure):
+    _fields_ = ([("d", C.c_int32), ("F", C.c_int32), ("E", C.c_int32), ("k", C.c_int32)]
+                + [(n, C.c_void_p) for n in ("Wr", "br", "W1", "b1", "W2", "b2", "ffn_mask", "ln_g", "ln_b")])
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -47,7 +52,7 @@ def lib():
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_max_threads.restype = C.c_int32
-        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward"):
+        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_moe_ffn"):
             getattr(_lib, f).restype = C.c_int32
     return _lib
 
@@ -195,6 +200,33 @@ def pruned_ffn(pack: LayerPack, x, act: int = 0, eps: float = 1e-5, pre_ln: bool
                          C.c_double(eps), C.c_int32(int(pre_ln)), C.c_int32(int(add_residual)),
                          C.c_int32(int(bf16)), _p(y))
     return y
+
+
+def moe_ffn(x, moe: Dict[str, np.ndarray], top_k: int, act: int = 0, eps: float = 1e-5, pre_ln: bool = True,
+            add_residual: bool = True, bf16: bool = False, ffn_mask=None, forced_route=None):
+    """Sparse-MoE FFN of one presence pattern.  moe: Wr [E,d], br [E] | None, W1 [E,F,d], b1 [E,F] | None,
+    W2 [E,F,d], b2 [E,d] | None, ln_g, ln_b [d].  ffn_mask [E,F] u8 (1 = kept) or None.
+    Returns (y [rows,d], route [rows,k], weight [rows,k], logit [rows,E])."""
+    x = _f64(x)
+    d = x.shape[-1]
+    rows = x.size // d
+    keep = {k: _f64(moe.get(k)) for k in ("Wr", "br", "W1", "b1", "W2", "b2", "ln_g", "ln_b")}
+    E, F = keep["W1"].shape[0], keep["W1"].shape[1]
+    assert keep["Wr"].shape == (E, d) and keep["W2"].shape == (E, F, d)
+    fm = None if ffn_mask is None else np.ascontiguousarray(ffn_mask, dtype=np.uint8)
+    fr = None if forced_route is None else np.ascontiguousarray(forced_route, dtype=np.int32)
+    st = _Moe(d, F, E, top_k, *[_p(keep[k]) for k in ("Wr", "br", "W1", "b1", "W2", "b2")], _p(fm),
+              _p(keep["ln_g"]), _p(keep["ln_b"]))
+    y = np.empty_like(x)
+    route = np.full((rows, top_k), -1, np.int32)
+    weight = np.zeros((rows, top_k), np.float64)
+    logit = np.zeros((rows, E), np.float64)
+    rc = lib().orc_moe_ffn(C.byref(st), _p(x), C.c_int64(rows), C.c_int32(act), C.c_double(eps),
+                           C.c_int32(int(pre_ln)), C.c_int32(int(add_residual)), C.c_int32(int(bf16)), _p(fr),
+                           _p(y), _p(route), _p(weight), _p(logit))
+    if rc != 0:
+        raise ValueError("orc_moe_ffn: bad arguments")
+    return y, route, weight, logit
 
 
 def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,

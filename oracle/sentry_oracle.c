@@ -408,6 +408,85 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
     ffn_core(w, x, rows, act, eps, pre_ln, add_residual, bf16, bf16, y);
 }
 
+/* ---- Sparse-MoE FFN ------------------------------------------------------- */
+int32_t orc_moe_ffn(const orc_moe *m, const double *x, int64_t rows, int32_t act, double eps,
+                    int32_t pre_ln, int32_t add_residual, int32_t bf16,
+                    const int32_t *forced_route, double *y, int32_t *route_out,
+                    double *weight_out, double *logit_out)
+{
+    const int32_t d = m->d, F = m->F, E = m->E, k = m->k;
+    if (d < 1 || F < 1 || E < 1 || k < 1 || k > E || rows < 0) return -1;
+    double *xn = (double *)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1) * d);
+    if (pre_ln) orc_layernorm(x, rows, d, m->ln_g, m->ln_b, eps, bf16, xn);
+    else memcpy(xn, x, sizeof(double) * (size_t)rows * d);
+    int32_t rc = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const double *xr = xn + r * d;
+        double *logit = (double *)malloc(sizeof(double) * (size_t)E);
+        qscore *qs = (qscore *)malloc(sizeof(qscore) * (size_t)E);
+        int32_t *pick = (int32_t *)malloc(sizeof(int32_t) * (size_t)k);
+        double *hid = (double *)malloc(sizeof(double) * (size_t)F);
+        for (int32_t e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int32_t c = 0; c < d; ++c) acc += xr[c] * m->Wr[(int64_t)e * d + c];
+            if (m->br) acc += m->br[e];
+            logit[e] = acc;
+            if (logit_out) logit_out[r * E + e] = acc;
+            qs[e].m = (float)acc;
+            qs[e].i = e;
+        }
+        int bad = 0;
+        if (forced_route) {
+            for (int32_t s = 0; s < k; ++s) {
+                pick[s] = forced_route[r * k + s];
+                if (pick[s] < 0 || pick[s] >= E) bad = 1;
+                for (int32_t t = 0; t < s; ++t) if (pick[t] == pick[s]) bad = 1;
+            }
+        } else {
+            qsort(qs, (size_t)E, sizeof(qscore), by_m_desc_index_asc);
+            for (int32_t s = 0; s < k; ++s) pick[s] = qs[s].i;
+        }
+        if (bad) {
+#pragma omp atomic write
+            rc = -1;
+        } else {
+            /* softmax over the chosen logits */
+            double mx = -INFINITY, den = 0.0;
+            for (int32_t s = 0; s < k; ++s) if (logit[pick[s]] > mx) mx = logit[pick[s]];
+            for (int32_t s = 0; s < k; ++s) den += exp(logit[pick[s]] - mx);
+            for (int32_t n = 0; n < d; ++n) y[r * d + n] = add_residual ? x[r * d + n] : 0.0;
+            for (int32_t s = 0; s < k; ++s) {
+                const int32_t e = pick[s];
+                const double pe = exp(logit[e] - mx) / den;
+                if (route_out) route_out[r * k + s] = e;
+                if (weight_out) weight_out[r * k + s] = pe;
+                const double *W1 = m->W1 + (int64_t)e * F * d, *W2 = m->W2 + (int64_t)e * F * d;
+                for (int32_t f = 0; f < F; ++f) {
+                    if (m->ffn_mask && !m->ffn_mask[(int64_t)e * F + f]) { hid[f] = 0.0; continue; }
+                    double acc = 0.0;
+                    for (int32_t c = 0; c < d; ++c) acc += xr[c] * W1[(int64_t)f * d + c];
+                    if (m->b1) acc += m->b1[(int64_t)e * F + f];
+                    hid[f] = rnd(activation(acc, act), bf16);
+                }
+                for (int32_t n = 0; n < d; ++n) {
+                    double acc = 0.0;
+                    for (int32_t f = 0; f < F; ++f) {
+                        if (m->ffn_mask && !m->ffn_mask[(int64_t)e * F + f]) continue;
+                        acc += hid[f] * W2[(int64_t)f * d + n];
+                    }
+                    if (m->b2) acc += m->b2[(int64_t)e * d + n];
+                    y[r * d + n] += pe * acc;
+                }
+            }
+            for (int32_t n = 0; n < d; ++n) y[r * d + n] = rnd(y[r * d + n], bf16);
+        }
+        free(hid); free(pick); free(qs); free(logit);
+    }
+    free(xn);
+    return rc;
+}
+
 /* ---- encoder stack ------------------------------------------------------- */
 int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                             const orc_layer *layers, const int32_t *pattern_id,

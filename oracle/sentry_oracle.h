@@ -155,6 +155,40 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                             const double *final_g, const double *final_b, int32_t bf16,
                             const double *x, double *y, int32_t *sel_out, double *score_out);
 
+/*
+ * Sparse-MoE FFN with pruned experts, Sec. 4.5 "Sparse-MoE FFN pruning": the
+ * number of experts E and the Top-k routing stay fixed; every expert e keeps
+ * its own channel set (W1_e' = W1_e[:, N_keep_e], W2_e' = W2_e[N_keep_e, :]),
+ * here given as a mask over its F channels.  One presence pattern per call.
+ *   Wr [E,d], br [E] or NULL   router (not pruned)
+ *   W1 [E,F,d], b1 [E,F] or NULL, W2 [E,F,d], b2 [E,d] or NULL (unit-major, as orc_layer)
+ *   ffn_mask [E,F] or NULL     1 = channel kept
+ *   ln_g, ln_b [d]             pre-norm LayerNorm of the block (used when pre_ln)
+ * The paper fixes neither the router nor the combination; this library's
+ * reading is the common one: with xn = LayerNorm(x) (or x),
+ *   logit_e = xn . Wr_e + br_e;  the k experts with the highest logit are
+ *   chosen (ties: lower expert index; the comparison is made on the logits
+ *   rounded to fp32, the precision the GPU router compares in);
+ *   p_e = softmax over the chosen logits;
+ *   y = [x +] sum_{chosen e} p_e * ( act(xn W1_e'^T + b1_e') W2_e' + b2_e ).
+ * bf16 rounding points: xn, each expert's hidden activations, and y.
+ *   forced_route [rows,k] or NULL: use these experts (distinct, 0..E-1) instead
+ *   route_out [rows,k] (chosen experts, descending logit), weight_out [rows,k],
+ *   logit_out [rows,E]: any may be NULL
+ * returns 0 or -1.
+ */
+typedef struct {
+    int32_t d, F, E, k;
+    const double *Wr, *br;
+    const double *W1, *b1, *W2, *b2;
+    const uint8_t *ffn_mask;
+    const double *ln_g, *ln_b;
+} orc_moe;
+int32_t orc_moe_ffn(const orc_moe *m, const double *x, int64_t rows, int32_t act, double eps,
+                    int32_t pre_ln, int32_t add_residual, int32_t bf16,
+                    const int32_t *forced_route, double *y, int32_t *route_out,
+                    double *weight_out, double *logit_out);
+
 /* Threads the OpenMP runtime will use (for the benchmark's report). */
 int32_t orc_max_threads(void);
 

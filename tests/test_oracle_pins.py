@@ -163,6 +163,96 @@ def test_ffn_against_library_ops(act):
     assert np.array_equal(orc.pruned_ffn(orc.LayerPack(w2, 1, 1, 4, [0], None, mask), x, act=act), got)
 
 
+# ----------------------------------------------- Sparse-MoE FFN (Sec. 4.5, third pruning location)
+def _moe_params(rng, E, F, d):
+    return {"Wr": rng.standard_normal((E, d)), "br": rng.standard_normal(E) * 0.1,
+            "W1": rng.standard_normal((E, F, d)), "b1": rng.standard_normal((E, F)),
+            "W2": rng.standard_normal((E, F, d)), "b2": rng.standard_normal((E, d)),
+            "ln_g": rng.standard_normal(d), "ln_b": rng.standard_normal(d)}
+
+
+@pytest.mark.parametrize("act", [0, 1])
+def test_moe_against_library_ops(act):
+    """Router logits, Top-k, softmax over the chosen logits and the per-expert pruned FFNs written with
+    library ops (torch.topk / softmax / matmul)."""
+    rng = np.random.default_rng(31)
+    rows, d, F, E, k = 11, 10, 14, 5, 2
+    m = _moe_params(rng, E, F, d)
+    mask = (rng.random((E, F)) < 0.6).astype(np.uint8); mask[:, 0] = 1
+    x = rng.standard_normal((rows, d))
+    y, route, weight, logit = orc.moe_ffn(x, m, k, act=act, ffn_mask=mask)
+    t = torch.from_numpy
+    xn = torch.nn.functional.layer_norm(t(x), (d,), t(m["ln_g"]), t(m["ln_b"]), 1e-5)
+    lg = xn @ t(m["Wr"]).T + t(m["br"])
+    assert np.allclose(logit, lg.numpy(), atol=1e-12)
+    top = torch.topk(lg, k, dim=1)
+    assert np.array_equal(route, top.indices.numpy().astype(np.int32))       # no ties in random data
+    pw = torch.softmax(top.values, dim=1)
+    assert np.allclose(weight, pw.numpy(), atol=1e-14) and np.allclose(weight.sum(axis=1), 1.0, atol=1e-14)
+    want = t(x).clone()
+    for r in range(rows):
+        for s_ in range(k):
+            e = int(top.indices[r, s_])
+            keep = np.flatnonzero(mask[e])
+            z = xn[r] @ t(m["W1"][e][keep]).T + t(m["b1"][e][keep])
+            h = torch.relu(z) if act == 0 else torch.nn.functional.gelu(z)
+            want[r] += pw[r, s_] * (h @ t(m["W2"][e][keep]) + t(m["b2"][e]))
+    assert np.allclose(y, want.numpy(), rtol=0, atol=1e-11)
+    # a removed channel's weights never enter, bit for bit
+    m2 = dict(m); m2["W1"] = m["W1"].copy(); m2["W2"] = m["W2"].copy()
+    m2["W1"][mask == 0] = 1e6; m2["W2"][mask == 0] = -1e6
+    assert np.array_equal(orc.moe_ffn(x, m2, k, act=act, ffn_mask=mask)[0], y)
+
+
+def test_moe_special_cases():
+    rng = np.random.default_rng(32)
+    rows, d, F, E = 7, 8, 12, 4
+    m = _moe_params(rng, E, F, d)
+    x = rng.standard_normal((rows, d))
+    mask1 = (rng.random(F) < 0.7).astype(np.uint8); mask1[0] = 1
+    # one expert, k = 1: the block is the plain pruned FFN
+    one = {k_: (v[:1] if k_ in ("Wr", "br", "W1", "b1", "W2", "b2") else v) for k_, v in m.items()}
+    w = {"W1": m["W1"][0], "b1": m["b1"][0], "W2": m["W2"][0], "b2": m["b2"][0], "ln2_g": m["ln_g"], "ln2_b": m["ln_b"],
+         "Wq": np.zeros((4, d)), "Wk": np.zeros((4, d)), "Wv": np.zeros((4, d)), "Wo": np.zeros((4, d))}
+    ffn = orc.pruned_ffn(orc.LayerPack(w, 1, 1, 4, [0], None, mask1), x, act=1)
+    y1, r1, w1, _ = orc.moe_ffn(x, one, 1, act=1, ffn_mask=mask1[None])
+    assert np.allclose(y1, ffn, atol=1e-13) and (r1 == 0).all() and (w1 == 1.0).all()
+    # identical experts, k = E: the weights sum to one, so the block is again that FFN
+    same = dict(m)
+    for k_ in ("W1", "b1", "W2", "b2"):
+        same[k_] = np.repeat(m[k_][:1], E, axis=0)
+    yE, rE, wE, _ = orc.moe_ffn(x, same, E, act=1, ffn_mask=np.repeat(mask1[None], E, axis=0))
+    assert np.allclose(yE, ffn, atol=1e-12)
+    assert all(sorted(r.tolist()) == list(range(E)) for r in rE)
+    # tie rule: identical router rows -> the k lowest expert indices, equal weights
+    tie = dict(m); tie["Wr"] = np.repeat(m["Wr"][:1], E, axis=0); tie["br"] = np.zeros(E)
+    _, rt, wt, _ = orc.moe_ffn(x, tie, 2)
+    assert (rt == np.array([0, 1])).all() and np.allclose(wt, 0.5, atol=1e-15)
+    # forced routing: its own choice reproduces the output; another choice uses those experts
+    y0, r0, w0, lg = orc.moe_ffn(x, m, 2)
+    assert np.array_equal(orc.moe_ffn(x, m, 2, forced_route=r0)[0], y0)
+    other = np.stack([np.array([e for e in range(E) if e not in r][:2]) for r in r0]).astype(np.int32)
+    y2, r2, w2, _ = orc.moe_ffn(x, m, 2, forced_route=other)
+    assert np.array_equal(r2, other) and not np.allclose(y2, y0)
+    sub = np.take_along_axis(lg, other.astype(np.int64), axis=1)
+    pw = np.exp(sub - sub.max(axis=1, keepdims=True)); pw /= pw.sum(axis=1, keepdims=True)
+    assert np.allclose(w2, pw, atol=1e-14)
+    with pytest.raises(ValueError):
+        orc.moe_ffn(x, m, 2, forced_route=np.zeros((rows, 2), np.int32))          # duplicate expert
+    with pytest.raises(ValueError):
+        orc.moe_ffn(x, m, E + 1)
+    # switches and bf16 rounding points: the output is a stored bf16 tensor
+    y3 = orc.moe_ffn(x, m, 2, pre_ln=False, add_residual=False)[0]
+    y4 = orc.moe_ffn(x, m, 2, pre_ln=False, add_residual=True)[0]
+    assert np.allclose(y4 - x, y3, atol=1e-12)
+    xb = W.to_bf16_values(x.astype(np.float32)).astype(np.float64)
+    mb = {k_: W.to_bf16_values(v.astype(np.float32)).astype(np.float64) for k_, v in m.items()}
+    yb = orc.moe_ffn(xb, mb, 2, bf16=True)[0]
+    assert np.array_equal(yb, W.to_bf16_values(yb.astype(np.float32)).astype(np.float64))
+    # and differs from the unrounded evaluation only by rounding of xn, the hidden activations and y
+    assert np.max(np.abs(yb - orc.moe_ffn(xb, mb, 2)[0]) / np.maximum(1, np.abs(yb))) < 0.1
+
+
 # --------------------------------------------------------- SentryAttend (a4-a7)
 def _mha_textbook(Q, K, V):
     """Independent multi-head attention: [B,H,L,dh] -> [B,L,H*dh]."""
