@@ -247,6 +247,58 @@ int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers_h
                            void *stream);
 
 /* ------------------------------------------------------------------------
+ * Sparse-MoE FFN with pruned experts -- Sec. 4.5 "Sparse-MoE FFN pruning":
+ * the number of experts E and the Top-k routing stay fixed; expert e keeps
+ * its own channel set, W1_e' = W1_e[:, N_keep_e], W2_e' = W2_e[N_keep_e, :].
+ * The paper fixes neither the router nor the combination; this library uses
+ *   xn = LayerNorm(x) (pre_ln) or x;   logit_e = xn . Wr_e + br_e (fp32);
+ *   the top_k experts with the highest logit (ties: lower index);
+ *   p_e = softmax over the chosen logits;
+ *   y = [x +] sum_{chosen e} p_e * ( act(xn W1_e'^T + b1_e') W2_e' + b2_e ).
+ *
+ * Dense expert parameters (device pointers in a HOST struct), unit-major:
+ *   Wr [E,d], br [E] (NULL ok), W1 [E,F,d], b1 [E,F] (NULL ok),
+ *   W2 [E,F,d], b2 [E,d] (NULL ok), ln_g, ln_b [d]      (F = desc->d_ff)
+ * Compact form for all P patterns, Fp = sf_ffn_padded(k_ffn_max), k_ffn_max =
+ * the largest per-expert keep count (narrower experts are zero padded):
+ *   W1 [P,E,Fp,d], b1 [P,E,Fp], W2T [P,E,d,Fp], b2x [P,E,d] (b2 repeated per pattern)
+ * sf_compact_moe_experts gathers them (bit-exact data movement):
+ *   ffn_idx [E,P,F] kept channels of expert e for pattern p, ascending (e.g. the
+ *   ffn_idx output of sf_gate_scores_to_masks run with n_layers = E on the
+ *   expert-internal gate scores), k_ffn_host [E] HOST keep counts.
+ * sf_moe_ffn_forward: X, Y [B*L, d] (Y may not alias X); sample b uses pattern
+ *   pattern_id[b] (NULL: 0);
+ *   forced_route [B*L, top_k] int32 or NULL: experts given by the caller
+ *     (distinct, 0..E-1) instead of the Top-k choice; the weights are still the
+ *     softmax of this call's logits of those experts;
+ *   route_out [B*L, top_k] int32, weight_out [B*L, top_k] fp32,
+ *   logit_out [B*L, E] fp32: any may be NULL.  route_out lists the chosen
+ *   experts by descending logit.
+ * bf16 rounding points: xn, each expert's hidden activations, Y.
+ */
+typedef struct sf_moe_dense {
+    const void *Wr, *br, *W1, *b1, *W2, *b2, *ln_g, *ln_b;
+} sf_moe_dense;
+typedef struct sf_moe_compact {
+    int32_t n_experts;         /* E <= 64 */
+    int32_t top_k;             /* <= min(8, E) */
+    int32_t k_ffn_max;         /* max over experts of the kept channel count */
+    int32_t reserved;
+    const void *Wr, *br;
+    void *W1, *b1, *W2T, *b2x;
+    const void *ln_g, *ln_b;
+} sf_moe_compact;
+int32_t sf_compact_moe_experts(const sf_desc *desc, const sf_moe_dense *dense_host,
+                               const int32_t *ffn_idx, const int32_t *k_ffn_host,
+                               const sf_moe_compact *compact_host, void *stream);
+size_t sf_moe_ffn_workspace_bytes(const sf_desc *desc, const sf_moe_compact *moe_host);
+int32_t sf_moe_ffn_forward(const sf_desc *desc, const sf_moe_compact *moe_host, const void *X,
+                           const int32_t *pattern_id, int32_t pre_ln, int32_t add_residual,
+                           const int32_t *forced_route, void *Y, int32_t *route_out,
+                           float *weight_out, float *logit_out, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel HIP-event timing.
  * sf_profile_begin(kernel_class, max_launches) creates max_launches event
  * pairs; from then on every launch of that kernel class made by this library

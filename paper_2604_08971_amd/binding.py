@@ -24,7 +24,8 @@ SF_FLAG_FINAL_LN = 1
 EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks",
            "sf_compact_heads_channels", "sf_sparse_gqa_workspace_bytes", "sf_sparse_gqa_forward",
            "sf_pruned_ffn_workspace_bytes", "sf_pruned_ffn_forward", "sf_encoder_workspace_bytes",
-           "sf_encoder_forward", "sf_profile_begin", "sf_profile_end"]
+           "sf_encoder_forward", "sf_profile_begin", "sf_profile_end", "sf_compact_moe_experts",
+           "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward"]
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
 
@@ -54,6 +55,18 @@ class SfCompactLayer(C.Structure):
                                              "ln1_g", "ln1_b", "ln2_g", "ln2_b", "head_group", "n_groups")])
 
 
+_MOE_DENSE_FIELDS = ("Wr", "br", "W1", "b1", "W2", "b2", "ln_g", "ln_b")
+
+
+class SfMoeDense(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _MOE_DENSE_FIELDS]
+
+
+class SfMoeCompact(C.Structure):
+    _fields_ = ([("n_experts", C.c_int32), ("top_k", C.c_int32), ("k_ffn_max", C.c_int32), ("reserved", C.c_int32)]
+                + [(n, C.c_void_p) for n in ("Wr", "br", "W1", "b1", "W2T", "b2x", "ln_g", "ln_b")])
+
+
 class SentryFuseError(RuntimeError):
     pass
 
@@ -66,11 +79,12 @@ def lib():
             raise SentryFuseError(f"{LIB_PATH} is missing: run `python -m paper_2604_08971_amd.build` first")
         L = C.CDLL(LIB_PATH)
         L.sf_last_error.restype = C.c_char_p
-        for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes"):
+        for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes",
+                  "sf_moe_ffn_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
-                  "sf_profile_end"):
+                  "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -88,6 +102,12 @@ def lib():
         L.sf_encoder_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)]
         L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
         L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        L.sf_compact_moe_experts.argtypes = [C.POINTER(SfDesc), C.POINTER(SfMoeDense), C.c_void_p, C.c_void_p,
+                                             C.POINTER(SfMoeCompact), C.c_void_p]
+        L.sf_moe_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfMoeCompact)]
+        L.sf_moe_ffn_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfMoeCompact), C.c_void_p, C.c_void_p, C.c_int32,
+                                         C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_profile_begin.argtypes = [C.c_int32, C.c_int32]
         L.sf_profile_end.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.sf_num_active.argtypes = [C.POINTER(SfDesc)]
@@ -304,6 +324,66 @@ def pruned_ffn_forward(desc: SfDesc, layer: CompactLayer, X: torch.Tensor,
                                      int(pre_ln), int(add_residual), _ptr(Y), _ptr(ws), ws.numel(), _stream())
     _check(rc, "sf_pruned_ffn_forward")
     return Y
+
+
+# ---------------------------------------------------------- Sparse-MoE FFN with pruned experts
+class CompactMoe:
+    """Compacted experts of one MoE block: owns the padded device buffers."""
+
+    def __init__(self, desc: SfDesc, dense: Dict[str, torch.Tensor], top_k: int, k_ffn: Sequence[int]):
+        E, F, d = dense["W1"].shape
+        assert F == desc.d_ff and d == desc.d_model and len(k_ffn) == E
+        P = desc.P
+        dt, dev = dense["W1"].dtype, dense["W1"].device
+        self.k_ffn = [int(k) for k in k_ffn]
+        self.E, self.top_k = E, int(top_k)
+        self.Fp = ffn_padded(desc, max(self.k_ffn))
+        self.dense = dense
+        self.W1 = torch.empty((P, E, self.Fp, d), dtype=dt, device=dev)
+        self.b1 = torch.empty((P, E, self.Fp), dtype=dt, device=dev) if dense.get("b1") is not None else None
+        self.W2T = torch.empty((P, E, d, self.Fp), dtype=dt, device=dev)
+        self.b2x = torch.empty((P, E, d), dtype=dt, device=dev) if dense.get("b2") is not None else None
+        self.struct = SfMoeCompact(E, self.top_k, max(self.k_ffn), 0, _ptr(dense["Wr"]), _ptr(dense.get("br")),
+                                   _ptr(self.W1), _ptr(self.b1), _ptr(self.W2T), _ptr(self.b2x),
+                                   _ptr(dense.get("ln_g")), _ptr(dense.get("ln_b")))
+
+
+def compact_moe_experts(desc: SfDesc, dense: Dict[str, torch.Tensor], ffn_idx: torch.Tensor, top_k: int,
+                        k_ffn: Sequence[int], out: Optional[CompactMoe] = None) -> CompactMoe:
+    """dense: Wr [E,d], br [E] | None, W1 [E,F,d], b1 [E,F] | None, W2 [E,F,d], b2 [E,d] | None, ln_g, ln_b [d];
+    ffn_idx [E,P,F] int32 kept channels (ascending) of every expert and pattern."""
+    cm = out if out is not None else CompactMoe(desc, dense, top_k, k_ffn)
+    E = cm.E
+    assert ffn_idx.dtype == torch.int32 and ffn_idx.is_contiguous() and tuple(ffn_idx.shape) == (E, desc.P, desc.d_ff)
+    ds = SfMoeDense(*[_ptr(dense.get(n)) for n in _MOE_DENSE_FIELDS])
+    kf = (C.c_int32 * E)(*cm.k_ffn)
+    _check(lib().sf_compact_moe_experts(C.byref(desc), C.byref(ds), _ptr(ffn_idx), C.cast(kf, C.c_void_p),
+                                        C.byref(cm.struct), _stream()), "sf_compact_moe_experts")
+    return cm
+
+
+def moe_ffn_forward(desc: SfDesc, moe: CompactMoe, X: torch.Tensor, pattern_id: Optional[torch.Tensor] = None,
+                    pre_ln: bool = True, add_residual: bool = True, forced_route: Optional[torch.Tensor] = None,
+                    want_route: bool = False, out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """X [B*L, d].  Returns Y, or (Y, route [B*L,k] int32, weight [B*L,k] f32, logit [B*L,E] f32) with want_route."""
+    assert X.is_contiguous()
+    rows = X.shape[0]
+    Y = torch.empty_like(X) if out is None else out
+    route = weight = logit = None
+    if want_route:
+        route = torch.empty((rows, moe.top_k), dtype=torch.int32, device=X.device)
+        weight = torch.empty((rows, moe.top_k), dtype=torch.float32, device=X.device)
+        logit = torch.empty((rows, moe.E), dtype=torch.float32, device=X.device)
+    if forced_route is not None:
+        assert forced_route.dtype == torch.int32 and forced_route.is_contiguous()
+        assert tuple(forced_route.shape) == (rows, moe.top_k)
+    if ws is None:
+        ws = workspace(lib().sf_moe_ffn_workspace_bytes(C.byref(desc), C.byref(moe.struct)), X.device)
+    rc = lib().sf_moe_ffn_forward(C.byref(desc), C.byref(moe.struct), _ptr(X), _ptr(pattern_id), int(pre_ln),
+                                  int(add_residual), _ptr(forced_route), _ptr(Y), _ptr(route), _ptr(weight),
+                                  _ptr(logit), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "sf_moe_ffn_forward")
+    return (Y, route, weight, logit) if want_route else Y
 
 
 # -------------------------------------------------------------------------- a10

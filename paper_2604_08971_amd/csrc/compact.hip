@@ -37,13 +37,13 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherRegions regs, in
     }
 }
 
-// dstT[p, n, J] = src[idx[p, J / block] * block + J % block, n]  for n < d,
+// dstT[p * dst_pstride + n * cols_out + J] = src[idx[p, J / block] * block + J % block, n]  for n < d,
 // J < cols_out (zeros when the slot is unused).  32x32 tiles through LDS so
 // both the reads (along n) and the writes (along J) are contiguous.
 template <class T>
 __global__ __launch_bounds__(256) void gather_transpose_kernel(
     const T *__restrict__ src, T *__restrict__ dstT, const int32_t *__restrict__ idx,
-    int idx_stride, int block, int n_valid, int cols_out, int d)
+    int idx_stride, int block, int n_valid, int cols_out, int d, size_t dst_pstride)
 {
     __shared__ T tile[32][33];
     const int p = blockIdx.z;
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(
     __syncthreads();
     for (int nn = ty; nn < 32; nn += 8) {
         const int n = n0 + nn, J = J0 + tx;
-        if (n < d && J < cols_out) dstT[((size_t)p * d + n) * cols_out + J] = tile[tx][nn];
+        if (n < d && J < cols_out) dstT[(size_t)p * dst_pstride + (size_t)n * cols_out + J] = tile[tx][nn];
     }
 }
 
@@ -91,17 +91,18 @@ static void gather_rows(hipStream_t st, GatherRegions regs, size_t row_bytes, in
 
 static void gather_transpose(hipStream_t st, int dtype, const void *src, void *dst,
                              const int32_t *idx, int idx_stride, int block, int n_valid,
-                             int cols_out, int d, int P)
+                             int cols_out, int d, int P, size_t dst_pstride = 0)
 {
+    if (dst_pstride == 0) dst_pstride = (size_t)d * cols_out;
     dim3 grid(ceil_div(cols_out, 32), ceil_div(d, 32), P);
     if (dtype == SF_BF16)
         hipLaunchKernelGGL(gather_transpose_kernel<uint16_t>, grid, dim3(256), 0, st,
                            (const uint16_t *)src, (uint16_t *)dst, idx, idx_stride, block, n_valid,
-                           cols_out, d);
+                           cols_out, d, dst_pstride);
     else
         hipLaunchKernelGGL(gather_transpose_kernel<uint32_t>, grid, dim3(256), 0, st,
                            (const uint32_t *)src, (uint32_t *)dst, idx, idx_stride, block, n_valid,
-                           cols_out, d);
+                           cols_out, d, dst_pstride);
 }
 
 }  // namespace sf
@@ -171,4 +172,60 @@ extern "C" int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
     gather_transpose(st, D.dtype, dense->W2, c->W2T, fi, D.F, 1, kf, Fp, d, P);
     gather_transpose(st, D.dtype, dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, d, P);
     return check_launch("compact_heads_channels");
+}
+
+// Sparse-MoE FFN pruning (Sec. 4.5): every expert keeps its own channel set; the compact buffers are padded
+// to the widest expert (zero channels contribute exactly zero).
+extern "C" int32_t sf_compact_moe_experts(const sf_desc *desc, const sf_moe_dense *dense,
+                                          const int32_t *ffn_idx, const int32_t *k_ffn_host,
+                                          const sf_moe_compact *c, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!dense || !c || !ffn_idx || !k_ffn_host) return fail(SF_ERR_INVALID_ARG, "compact_moe_experts: NULL argument");
+    const int E = c->n_experts;
+    if (E < 1 || E > 64 || c->top_k < 1 || c->top_k > E || c->top_k > 8)
+        return fail(SF_ERR_INVALID_ARG, "compact_moe_experts: needs 1 <= top_k <= min(8, n_experts), n_experts <= 64");
+    int kmax = 0;
+    for (int e = 0; e < E; ++e) {
+        if (k_ffn_host[e] < 1 || k_ffn_host[e] > D.F)
+            return fail(SF_ERR_INVALID_ARG, "compact_moe_experts: keep count of expert %d out of range", e);
+        if (k_ffn_host[e] > kmax) kmax = k_ffn_host[e];
+    }
+    if (c->k_ffn_max != kmax) return fail(SF_ERR_INVALID_ARG, "compact_moe_experts: k_ffn_max must be %d", kmax);
+    if (!dense->W1 || !dense->W2 || !c->W1 || !c->W2T || (dense->b1 && !c->b1) || (dense->b2 && !c->b2x))
+        return fail(SF_ERR_INVALID_ARG, "compact_moe_experts: NULL weight pointer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t es = elem_size(D.dtype);
+    const int P = D.P, d = D.d, F = D.F;
+    const int Fp = (int)align_up(kmax, D.ffn_pad);
+    const size_t rowW = (size_t)d * es;
+    for (int e0 = 0; e0 < E; e0 += 4) {          // up to four experts per launch
+        GatherRegions wr{}, br{};
+        for (int e = e0; e < E && e < e0 + 4; ++e) {
+            const int32_t *fi = ffn_idx + (size_t)e * P * F;
+            GatherRegion r{};
+            r.src = (const char *)dense->W1 + (size_t)e * F * rowW; r.dst = (char *)c->W1 + (size_t)e * Fp * rowW;
+            r.idx = fi; r.idx_stride = F; r.block = 1; r.n_static = k_ffn_host[e]; r.rows = Fp;
+            r.dst_pstride = (size_t)E * Fp;
+            wr.r[wr.n++] = r;
+            if (dense->b1) {
+                GatherRegion q = r;
+                q.src = (const char *)dense->b1 + (size_t)e * F * es; q.dst = (char *)c->b1 + (size_t)e * Fp * es;
+                br.r[br.n++] = q;
+            }
+        }
+        gather_rows(st, wr, rowW, P);
+        if (br.n) gather_rows(st, br, es, P);
+    }
+    for (int e = 0; e < E; ++e)
+        gather_transpose(st, D.dtype, (const char *)dense->W2 + (size_t)e * F * rowW,
+                         (char *)c->W2T + (size_t)e * d * Fp * es, ffn_idx + (size_t)e * P * F, F, 1, k_ffn_host[e],
+                         Fp, d, P, (size_t)E * d * Fp);
+    if (dense->b2)                                 // b2x[p, e, :] = b2[e, :]
+        for (int p = 0; p < P; ++p)
+            if (hipMemcpyAsync((char *)c->b2x + (size_t)p * E * rowW, dense->b2, (size_t)E * rowW,
+                               hipMemcpyDeviceToDevice, st) != hipSuccess)
+                return fail(SF_ERR_HIP, "compact_moe_experts: copy of b2 failed");
+    return check_launch("compact_moe_experts");
 }

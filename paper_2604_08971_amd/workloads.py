@@ -224,3 +224,39 @@ def small_spec(name: str = "S", dtype: str = "f32", B: int = 3, seg=(7, 5, 9), e
     """A free-form small spec for tests (ragged sizes, several patterns)."""
     return Spec(name, dtype, B, tuple(seg), extra, d, Hq, Hk, dh, F, nl, head_keep, ffn_keep,
                 dropout, final_ln, seed, c, act)
+
+
+@dataclass
+class MoeBlock:
+    """A Sparse-MoE FFN block on top of a workload's tokens: E experts with their own gate scores and
+    keep counts (ragged F'_e), a router, Top-k.  Arrays are fp32 holding values of the workload's dtype."""
+    E: int
+    top_k: int
+    dense: Dict[str, np.ndarray]        # Wr [E,d], br [E], W1 [E,F,d], b1 [E,F], W2 [E,F,d], b2 [E,d], ln_g, ln_b [d]
+    g_ffn: np.ndarray                   # [E, P, F] expert-internal gate scores per pattern in use
+    k_ffn: np.ndarray                   # [E] kept channels per expert
+
+
+def make_moe_block(wl: Workload, E: int, top_k: int, keep=(0.4, 0.8), seed_offset: int = 500) -> MoeBlock:
+    """Seeded MoE block for the tokens of `wl` (same d, F, patterns).  Router rows N(0, 1/d) so that the
+    logits are O(1); expert weights as the FFN of make_workload; keep ratios U(keep) per expert."""
+    spec = wl.spec
+    d, F, M = spec.d, spec.F, spec.M
+    q = to_bf16_values if spec.dtype == "bf16" else (lambda a: np.ascontiguousarray(a, dtype=np.float32))
+    r = _rng(spec.seed, seed_offset)
+    sd, sF = np.float32(1.0 / math.sqrt(d)), np.float32(1.0 / math.sqrt(F))
+    dense = {
+        "Wr": q(r.standard_normal((E, d), dtype=np.float32) * sd),
+        "br": q(np.float32(0.02) * r.standard_normal(E, dtype=np.float32)),
+        "W1": q(r.standard_normal((E, F, d), dtype=np.float32) * sd),
+        "b1": q(np.float32(0.02) * r.standard_normal((E, F), dtype=np.float32)),
+        "W2": q(r.standard_normal((E, F, d), dtype=np.float32) * sF),
+        "b2": q(np.float32(0.02) * r.standard_normal((E, d), dtype=np.float32)),
+        "ln_g": q(np.float32(1.0) + np.float32(0.05) * r.standard_normal(d, dtype=np.float32)),
+        "ln_b": q(np.float32(0.05) * r.standard_normal(d, dtype=np.float32)),
+    }
+    g_all = r.random((E, 2 ** M, F), dtype=np.float32)
+    g_ffn = np.ascontiguousarray(g_all[:, wl.pattern_bits, :])
+    lo, hi = keep
+    k_ffn = np.array([keep_count(float(x), F) for x in r.uniform(lo, hi, size=E)], dtype=np.int32)
+    return MoeBlock(E, top_k, dense, g_ffn, k_ffn)

@@ -122,6 +122,123 @@ def test_compaction_keep_all_is_identity():
         assert np.array_equal(to_host(cl.WoT[p]), w["Wo"].T)
 
 
+# -------------------------------------------------- Sparse-MoE FFN with pruned experts (Sec. 4.5)
+EPS_ROUTE = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _moe_case(wl, E, top_k, forced=False, pre_ln=True, add_residual=True):
+    s = wl.spec
+    dtype, bf = s.dtype, s.dtype == "bf16"
+    mb = W.make_moe_block(wl, E, top_k)
+    B, L, d, F, P = wl.x.shape[0], s.L, s.d, s.F, wl.P
+    # keep sets of the experts: the mask kernel with "layer" = expert
+    dm = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=E, P=P, dtype=sf.SF_BF16 if bf else sf.SF_F32, act=s.act)
+    g_head = np.zeros((E, P, 8), np.float32)
+    masks = sf.gate_scores_to_masks(dm, to_dev(g_head, "f32"), to_dev(mb.g_ffn, "f32"), [1] * E, mb.k_ffn.tolist())
+    ref = orc.gate_scores_to_masks(g_head, mb.g_ffn, np.ones(E, np.int32), mb.k_ffn, 2)
+    assert np.array_equal(to_host(masks["ffn_idx"]), ref["ffn_idx"]) and np.array_equal(to_host(masks["ffn_mask"]), ref["ffn_mask"])
+    desc = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=1, P=P, dtype=sf.SF_BF16 if bf else sf.SF_F32, act=s.act)
+    dense_dev = {k: to_dev(v, dtype) for k, v in mb.dense.items()}
+    cm = sf.compact_moe_experts(desc, dense_dev, masks["ffn_idx"], top_k, mb.k_ffn.tolist())
+    torch.cuda.synchronize()
+    # compaction is pure data movement: bit-exact against a numpy gather
+    W1c, W2Tc, b1c, b2x = to_host(cm.W1), to_host(cm.W2T), to_host(cm.b1), to_host(cm.b2x)
+    for p in range(P):
+        for e in range(E):
+            idx = ref["ffn_idx"][e, p, :mb.k_ffn[e]]
+            k = len(idx)
+            assert np.array_equal(W1c[p, e, :k], mb.dense["W1"][e][idx]) and not W1c[p, e, k:].any()
+            assert np.array_equal(W2Tc[p, e, :, :k], mb.dense["W2"][e][idx].T) and not W2Tc[p, e, :, k:].any()
+            assert np.array_equal(b1c[p, e, :k], mb.dense["b1"][e][idx]) and not b1c[p, e, k:].any()
+            assert np.array_equal(b2x[p, e], mb.dense["b2"][e])
+    X = wl.x.reshape(B * L, d)
+    fr = None
+    if forced:
+        rng = np.random.default_rng(9)
+        fr = np.stack([rng.choice(E, top_k, replace=False) for _ in range(B * L)]).astype(np.int32)
+    Y, route, weight, logit = sf.moe_ffn_forward(desc, cm, to_dev(X, dtype), to_dev(wl.pattern_id, dtype), pre_ln=pre_ln,
+                                                 add_residual=add_residual, forced_route=to_dev(fr, dtype), want_route=True)
+    Y2 = sf.moe_ffn_forward(desc, cm, to_dev(X, dtype), to_dev(wl.pattern_id, dtype), pre_ln=pre_ln,
+                            add_residual=add_residual, forced_route=to_dev(fr, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y2)                                # deterministic although the row order inside a segment is not
+    Y, route, weight, logit = to_host(Y), to_host(route), to_host(weight), to_host(logit)
+    assert np.isfinite(Y).all()
+    worst, n_flip = 0.0, 0
+    for p in range(P):
+        rows = np.flatnonzero(np.repeat(wl.pattern_id, L) == p)
+        if len(rows) == 0:
+            continue
+        mask = ref["ffn_mask"][:, p, :]
+        y_own, r_own, w_own, lg = orc.moe_ffn(X[rows], mb.dense, top_k, act=s.act, pre_ln=pre_ln, add_residual=add_residual,
+                                              bf16=bf, ffn_mask=mask, forced_route=None if fr is None else fr[rows])
+        assert np.max(np.abs(logit[rows] - lg)) < (1e-4 if not bf else 3e-2)
+        if fr is None:
+            # margin check of the GPU's choice against the oracle's k-th largest logit
+            kth = np.sort(lg, axis=1)[:, -top_k][:, None]
+            eps = EPS_ROUTE[dtype] * np.maximum(1.0, np.abs(kth))
+            chosen = np.zeros_like(lg, dtype=bool)
+            np.put_along_axis(chosen, route[rows].astype(np.int64), True, axis=1)
+            assert chosen.sum(axis=1).tolist() == [top_k] * len(rows)
+            assert np.all(np.where(chosen, lg, np.inf) >= kth - eps) and np.all(np.where(~chosen, lg, -np.inf) <= kth + eps)
+            n_flip += int((np.sort(route[rows], axis=1) != np.sort(r_own, axis=1)).any(axis=1).sum())
+            # listed by descending logit
+            lr = np.take_along_axis(logit[rows], route[rows].astype(np.int64), axis=1)
+            assert np.all(np.diff(lr, axis=1) <= 0)
+        else:
+            assert np.array_equal(route[rows], fr[rows])
+        # output reference: the oracle routed like the GPU
+        y_ref, _, w_ref, _ = orc.moe_ffn(X[rows], mb.dense, top_k, act=s.act, pre_ln=pre_ln, add_residual=add_residual,
+                                         bf16=bf, ffn_mask=mask, forced_route=route[rows])
+        assert np.max(np.abs(weight[rows] - w_ref)) < (1e-5 if not bf else 2e-2)
+        worst = max(worst, err_metric(Y[rows], y_ref))
+    _say(f"   moe {s.name} E={E} k={top_k}: err {worst:.3e}, rows routed differently {n_flip}/{B * L}")
+    assert worst <= TOL[dtype], worst
+    assert n_flip <= max(1, (B * L) // 100)
+    return worst
+
+
+@pytest.mark.parametrize("kw,E,k", [
+    (dict(dtype="f32", B=3), 4, 2),
+    (dict(dtype="f32", B=4, act=1, dropout="upto:2", seg=(40, 30, 50), F=96), 5, 1),
+    (dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=4), 4, 2),
+    (dict(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=320, seg=(100, 133, 64), extra=3, B=5, act=1, dropout="upto:2"), 8, 3),
+])
+def test_moe_ffn_parity_small(kw, E, k):
+    _say(f"moe small {kw} E={E} k={k}")
+    wl = W.make_workload(W.small_spec(**kw))
+    _moe_case(wl, E, k)
+    _moe_case(wl, E, k, forced=True)
+    _moe_case(wl, E, k, pre_ln=False, add_residual=False)
+
+
+def test_moe_ffn_parity_C2_full():
+    """Full-size launch: C2's tokens (B=64, L=384, d=256, F=1024, 8 patterns) through 8 experts, Top-2."""
+    _say("moe C2")
+    _moe_case(W.make_workload(W.CONFIGS["C2"]), 8, 2)
+
+
+def test_moe_single_expert_equals_pruned_ffn():
+    """E = 1, k = 1: the block is the pruned FFN of the encoder (same GEMMs, other row order; the residual
+    is added after the fp32 product instead of inside the GEMM, so the last bf16 bit may differ)."""
+    wl = W.make_workload(W.small_spec(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=3))
+    s = wl.spec
+    B, L, d, F, P = wl.x.shape[0], s.L, s.d, s.F, wl.P
+    dmod = DeviceModel(wl).build_plan()
+    ly = dmod.layers[0]
+    lw = wl.layers[0]
+    dense = {"Wr": np.zeros((1, d), np.float32), "br": None, "W1": lw["W1"][None], "b1": lw["b1"][None],
+             "W2": lw["W2"][None], "b2": lw["b2"][None], "ln_g": lw["ln2_g"], "ln_b": lw["ln2_b"]}
+    dense_dev = {k: to_dev(v, "bf16") for k, v in dense.items()}
+    ffn_idx = dmod.masks["ffn_idx"][0:1].contiguous()                     # [1, P, F]
+    cm = sf.compact_moe_experts(dmod.desc, dense_dev, ffn_idx, 1, [int(wl.k_ffn[0])])
+    X = dmod.x.view(B * L, d)
+    y_moe = sf.moe_ffn_forward(dmod.desc, cm, X, dmod.pattern_id)
+    y_ffn = sf.pruned_ffn_forward(dmod.desc, ly, X, dmod.pattern_id)
+    torch.cuda.synchronize()
+    assert err_metric(to_host(y_moe), to_host(y_ffn)) <= 2.0 ** -7
+
+
 # -------------------------------------------------- a4-a7: sparse_gqa_forward
 def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=False, forced=False,
               v_transposed=False, strided=False, n_sample=0):
