@@ -264,6 +264,59 @@ def bench_sampled_score(wl, steps, warmup):
                     "`value` above is the score over all allowed keys"}
 
 
+def bench_moe(wl, steps, warmup, E=8, top_k=2):
+    """The workload's tokens through one Sparse-MoE FFN block with pruned experts (E experts, Top-k routing,
+    every expert keeps its own channel set): masks of the experts -> compaction -> forward."""
+    import numpy as np
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from paper_2604_08971_amd import workloads as W
+    from gpu_utils import to_dev, to_host
+    s = wl.spec
+    if s.dtype != "bf16":
+        return None
+    B, L, d, F, P = wl.x.shape[0], s.L, s.d, s.F, wl.P
+    mb = W.make_moe_block(wl, E, top_k)
+    dt = sf.SF_BF16
+    dmask = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=E, P=P, dtype=dt, act=s.act)
+    desc = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=1, P=P, dtype=dt, act=s.act)
+    g_head = torch.zeros((E, P, 8), dtype=torch.float32, device="cuda")
+    g_ffn = to_dev(mb.g_ffn, "f32")
+    dense = {k: to_dev(v, "bf16") for k, v in mb.dense.items()}
+    X = to_dev(wl.x, "bf16").view(B * L, d)
+    pid = to_dev(wl.pattern_id, "bf16")
+    kf = mb.k_ffn.tolist()
+    masks = sf.gate_scores_to_masks(dmask, g_head, g_ffn, [1] * E, kf)
+    cm = sf.compact_moe_experts(desc, dense, masks["ffn_idx"], top_k, kf)
+    ws = sf.workspace(sf.lib().sf_moe_ffn_workspace_bytes(__import__("ctypes").byref(desc), __import__("ctypes").byref(cm.struct)))
+    Y = torch.empty_like(X)
+
+    def fwd():
+        sf.moe_ffn_forward(desc, cm, X, pid, out=Y, ws=ws)
+
+    def step():
+        sf.gate_scores_to_masks(dmask, g_head, g_ffn, [1] * E, kf, out=masks)
+        sf.compact_moe_experts(desc, dense, masks["ffn_idx"], top_k, kf, out=cm)
+        fwd()
+
+    ms, _ = time_steps(step, steps, warmup)
+    ms_fwd, _ = time_steps(fwd, steps, warmup)
+    _, route, _, _ = sf.moe_ffn_forward(desc, cm, X, pid, want_route=True, ws=ws)
+    load = np.bincount(to_host(route).ravel(), minlength=E).astype(np.int64)
+    flops = int((load * 4 * d * mb.k_ffn.astype(np.int64)).sum()) + B * L * 2 * d * E
+    sf.profile_begin(0, 64)
+    fwd()
+    _, _, each = sf.profile_end(each=True)
+    del cm, ws, dense
+    torch.cuda.empty_cache()
+    return {"experts": E, "top_k": top_k, "kept_channels": kf, "expert_load": load.tolist(),
+            "ms_per_step": ms, "ms_forward_only": ms_fwd, "tokens_per_s": B * L / (ms * 1e-3),
+            "algorithmic_tflop_per_step": flops / 1e12, "tflops": flops / (ms * 1e-3) / 1e12,
+            "tflops_forward_only": flops / (ms_fwd * 1e-3) / 1e12,
+            "gemm_launch_us": [round(x * 1e3, 1) for x in each],
+            "note": "Sparse-MoE FFN block with pruned experts on the same tokens; not part of `value`"}
+
+
 def cpu_baseline(wl, flops_total):
     """The CPU oracle, as it stands, on a bounded number of whole samples of the same workload."""
     import numpy as np
@@ -365,6 +418,7 @@ def main():
         out["kernels"] = k
         out["sparse_gqa"] = bench_sparse_gqa(dm, wl, args.steps)
         out["sampled_score"] = bench_sampled_score(wl, args.steps, args.warmup)
+        out["moe_ffn"] = bench_moe(wl, args.steps, args.warmup)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(wl, flops["total"])

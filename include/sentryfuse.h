@@ -269,8 +269,10 @@ int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers_h
  * sf_moe_ffn_forward: X, Y [B*L, d] (Y may not alias X); sample b uses pattern
  *   pattern_id[b] (NULL: 0);
  *   forced_route [B*L, top_k] int32 or NULL: experts given by the caller
- *     (distinct, 0..E-1) instead of the Top-k choice; the weights are still the
- *     softmax of this call's logits of those experts;
+ *     (distinct, 0..E-1; values outside are clamped, an expert listed twice
+ *     counts once, in its last slot, the other slot gets weight 0) instead of
+ *     the Top-k choice; the weights are still the softmax of this call's
+ *     logits of those experts;
  *   route_out [B*L, top_k] int32, weight_out [B*L, top_k] fp32,
  *   logit_out [B*L, E] fp32: any may be NULL.  route_out lists the chosen
  *   experts by descending logit.
@@ -287,6 +289,7 @@ typedef struct sf_moe_compact {
     const void *Wr, *br;
     void *W1, *b1, *W2T, *b2x;
     const void *ln_g, *ln_b;
+    int32_t *k_ffn;            /* device [E]: keep count of every expert, written by sf_compact_moe_experts */
 } sf_moe_compact;
 int32_t sf_compact_moe_experts(const sf_desc *desc, const sf_moe_dense *dense_host,
                                const int32_t *ffn_idx, const int32_t *k_ffn_host,

@@ -64,7 +64,7 @@ class SfMoeDense(C.Structure):
 
 class SfMoeCompact(C.Structure):
     _fields_ = ([("n_experts", C.c_int32), ("top_k", C.c_int32), ("k_ffn_max", C.c_int32), ("reserved", C.c_int32)]
-                + [(n, C.c_void_p) for n in ("Wr", "br", "W1", "b1", "W2T", "b2x", "ln_g", "ln_b")])
+                + [(n, C.c_void_p) for n in ("Wr", "br", "W1", "b1", "W2T", "b2x", "ln_g", "ln_b", "k_ffn")])
 
 
 class SentryFuseError(RuntimeError):
@@ -343,9 +343,10 @@ class CompactMoe:
         self.b1 = torch.empty((P, E, self.Fp), dtype=dt, device=dev) if dense.get("b1") is not None else None
         self.W2T = torch.empty((P, E, d, self.Fp), dtype=dt, device=dev)
         self.b2x = torch.empty((P, E, d), dtype=dt, device=dev) if dense.get("b2") is not None else None
+        self.k_ffn_dev = torch.zeros(E, dtype=torch.int32, device=dev)
         self.struct = SfMoeCompact(E, self.top_k, max(self.k_ffn), 0, _ptr(dense["Wr"]), _ptr(dense.get("br")),
                                    _ptr(self.W1), _ptr(self.b1), _ptr(self.W2T), _ptr(self.b2x),
-                                   _ptr(dense.get("ln_g")), _ptr(dense.get("ln_b")))
+                                   _ptr(dense.get("ln_g")), _ptr(dense.get("ln_b")), _ptr(self.k_ffn_dev))
 
 
 def compact_moe_experts(desc: SfDesc, dense: Dict[str, torch.Tensor], ffn_idx: torch.Tensor, top_k: int,

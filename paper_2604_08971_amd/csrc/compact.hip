@@ -105,6 +105,12 @@ static void gather_transpose(hipStream_t st, int dtype, const void *src, void *d
                            cols_out, d, dst_pstride);
 }
 
+struct ExpertCounts { int32_t k[64]; };
+__global__ void store_expert_counts_kernel(ExpertCounts ec, int E, int32_t *__restrict__ out)
+{
+    if ((int)threadIdx.x < E) out[threadIdx.x] = ec.k[threadIdx.x];
+}
+
 }  // namespace sf
 
 using namespace sf;
@@ -193,7 +199,7 @@ extern "C" int32_t sf_compact_moe_experts(const sf_desc *desc, const sf_moe_dens
         if (k_ffn_host[e] > kmax) kmax = k_ffn_host[e];
     }
     if (c->k_ffn_max != kmax) return fail(SF_ERR_INVALID_ARG, "compact_moe_experts: k_ffn_max must be %d", kmax);
-    if (!dense->W1 || !dense->W2 || !c->W1 || !c->W2T || (dense->b1 && !c->b1) || (dense->b2 && !c->b2x))
+    if (!dense->W1 || !dense->W2 || !c->W1 || !c->W2T || !c->k_ffn || (dense->b1 && !c->b1) || (dense->b2 && !c->b2x))
         return fail(SF_ERR_INVALID_ARG, "compact_moe_experts: NULL weight pointer");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const size_t es = elem_size(D.dtype);
@@ -222,6 +228,11 @@ extern "C" int32_t sf_compact_moe_experts(const sf_desc *desc, const sf_moe_dens
         gather_transpose(st, D.dtype, (const char *)dense->W2 + (size_t)e * F * rowW,
                          (char *)c->W2T + (size_t)e * d * Fp * es, ffn_idx + (size_t)e * P * F, F, 1, k_ffn_host[e],
                          Fp, d, P, (size_t)E * d * Fp);
+    {                                              // keep counts to the device as kernel arguments (no host copy)
+        ExpertCounts ec{};
+        for (int e = 0; e < E; ++e) ec.k[e] = k_ffn_host[e];
+        hipLaunchKernelGGL(store_expert_counts_kernel, dim3(1), dim3(64), 0, st, ec, E, c->k_ffn);
+    }
     if (dense->b2)                                 // b2x[p, e, :] = b2[e, :]
         for (int p = 0; p < P; ++p)
             if (hipMemcpyAsync((char *)c->b2x + (size_t)p * E * rowW, dense->b2, (size_t)E * rowW,

@@ -15,13 +15,19 @@ struct GemmArgs {
     const void *A; int64_t lda;
     const void *W; int64_t ldw; int64_t w_pstride;       // elements between patterns
     const void *bias; int64_t bias_pstride;              // may be NULL; 0 stride = shared
-    const int32_t *pattern_id;                           // [B] or NULL (pattern 0)
+    const int32_t *pattern_id;                           // [B] or NULL (pattern 0); a negative entry skips the sample
+    const int32_t *n_lim, *k_lim;                        // per pattern, may be NULL: only the first n_lim[p] features
+                                                         // are computed (the others are not written) and only the first
+                                                         // k_lim[p] elements of K are summed (n_lim % 8 == 0,
+                                                         // k_lim % 64 == 0, k_lim >= 64); device memory
     int B, L, N, K;                                      // N = number of output features of this launch
     int n0;                                              // first feature (row of W, entry of bias)
     int epi;                                             // EPI_ROWMAJOR: C[row, c0 + n], EPI_VT: C[b, n, i]
     int act;
     const void *R; int64_t ldr; int r0;                  // residual (NULL = none), first column r0
     void *C; int64_t ldc; int c0;                        // EPI_ROWMAJOR: row stride, first column
+    int xcd_rows;                                        // hint: deal 256-row tiles to the 8 XCDs round-robin instead of in
+                                                         // contiguous ranges (rows of unequal cost, e.g. n_lim / k_lim)
     int r_f32, c_f32;                                    // bf16 GEMM only: R / C hold fp32 (the residual stream)
     int64_t vt_b, vt_n;                                  // EPI_VT: strides of b and n (i contiguous)
 };

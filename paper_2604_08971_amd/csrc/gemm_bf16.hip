@@ -47,6 +47,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
     const int m0 = (blockIdx.x % tiles_m) * BM;
     const int nt0 = blockIdx.y * BN;                               // first feature of this tile (within launch)
     const int p = a.pattern_id ? a.pattern_id[b] : 0;
+    if (p < 0) return;                                             // sample not in use
+    if (a.n_lim) a.N = min(a.N, a.n_lim[p]);
+    if (a.k_lim) a.K = min(a.K, a.k_lim[p]);
+    if (nt0 >= a.N) return;
 
     const __bf16 *A = static_cast<const __bf16 *>(a.A) + ((int64_t)b * a.L) * a.lda;
     const __bf16 *W = static_cast<const __bf16 *>(a.W) + (int64_t)p * a.w_pstride + (int64_t)a.n0 * a.ldw;

@@ -86,6 +86,10 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
     const int m0 = (tm_i % tiles_m) * BM;
     const int nt0 = tn_i * BN;
     const int p = a.pattern_id ? a.pattern_id[b] : 0;
+    if (p < 0) return;                                             // sample not in use
+    if (a.n_lim) a.N = min(a.N, a.n_lim[p]);
+    if (a.k_lim) a.K = min(a.K, a.k_lim[p]);
+    if (nt0 >= a.N) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: keeps LDS bases in SGPRs

@@ -68,13 +68,27 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NXS][X rows][64] | [NWS][W rows][64]
 
     const int wid = blockIdx.x;
-    const int w = (wid % N_XCD) * per_xcd + wid / N_XCD;
-    if (w >= total_tiles) return;
-    const int tn_i = w % tiles_n, tm_i = w / tiles_n;
+    int tn_i, tm_i;
+    if (a.xcd_rows) {
+        // tile row r goes to XCD r % 8: rows of unequal cost spread evenly over the XCDs
+        const int s = wid / N_XCD;
+        tn_i = s % tiles_n;
+        tm_i = (s / tiles_n) * N_XCD + wid % N_XCD;
+        if (tm_i * tiles_n >= total_tiles) return;
+    } else {
+        const int w = (wid % N_XCD) * per_xcd + wid / N_XCD;
+        if (w >= total_tiles) return;
+        tn_i = w % tiles_n;
+        tm_i = w / tiles_n;
+    }
     const int b = tm_i / tiles_m;
     const int m0 = (tm_i % tiles_m) * BM;
     const int nt0 = tn_i * BN;
     const int p = a.pattern_id ? a.pattern_id[b] : 0;
+    if (p < 0) return;                                             // sample not in use
+    if (a.n_lim) a.N = min(a.N, a.n_lim[p]);
+    if (a.k_lim) a.K = min(a.K, a.k_lim[p]);
+    if (nt0 >= a.N) return;
     const int nk = a.K / BKT;
 
     const int lane = threadIdx.x & 63;
@@ -340,7 +354,7 @@ static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
     }
     const int tiles_m = ceil_div(a.L, BM), tiles_n = ceil_div(a.N, BN);
     const int total = a.B * tiles_m * tiles_n;
-    const int per_xcd = ceil_div(total, N_XCD);
+    const int per_xcd = a.xcd_rows ? ceil_div(a.B * tiles_m, N_XCD) * tiles_n : ceil_div(total, N_XCD);
     ProfScope prof(SF_KERNEL_GEMM, st);
     hipLaunchKernelGGL(kern, dim3(per_xcd * N_XCD), dim3(64 * (NCW + NLW)), lds, st, a, tiles_m, tiles_n, total, per_xcd);
     return SF_OK;

@@ -26,6 +26,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a)
     const int m0 = (blockIdx.x % tiles_m) * FT;
     const int nt0 = blockIdx.y * FT;
     const int p = a.pattern_id ? a.pattern_id[b] : 0;
+    if (p < 0) return;                                             // sample not in use
+    if (a.n_lim) a.N = min(a.N, a.n_lim[p]);
+    if (a.k_lim) a.K = min(a.K, a.k_lim[p]);
+    if (nt0 >= a.N) return;
     const float *A = static_cast<const float *>(a.A) + ((int64_t)b * a.L) * a.lda;
     const float *W = static_cast<const float *>(a.W) + (int64_t)p * a.w_pstride + (int64_t)a.n0 * a.ldw;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;

@@ -30,6 +30,8 @@ def test_struct_layout_matches_header():
     assert C.sizeof(sf.SfStrides) == 24
     assert C.sizeof(sf.SfDenseLayer) == 16 * 8
     assert C.sizeof(sf.SfCompactLayer) == 8 + 14 * 8
+    assert C.sizeof(sf.SfMoeDense) == 8 * 8
+    assert C.sizeof(sf.SfMoeCompact) == 16 + 9 * 8
 
 
 def test_num_active_matches_paper_example():
@@ -82,6 +84,20 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_encoder_workspace_bytes(C.byref(d), C.byref(cl)) == 0
     cl.k_head = 4
     assert L.sf_encoder_workspace_bytes(C.byref(d), C.byref(cl)) > 0
+    # Sparse-MoE block: structure checks come before any launch
+    m = sf.SfMoeCompact()
+    m.n_experts, m.top_k, m.k_ffn_max = 4, 5, 32          # top_k > E
+    assert L.sf_moe_ffn_workspace_bytes(C.byref(d), C.byref(m)) == 0
+    m.top_k = 2
+    assert L.sf_moe_ffn_workspace_bytes(C.byref(d), C.byref(m)) == 0      # no device keep counts
+    m.k_ffn = 256
+    assert L.sf_moe_ffn_workspace_bytes(C.byref(d), C.byref(m)) > 0
+    m.k_ffn_max = 65                                      # more channels than the model has
+    assert L.sf_moe_ffn_workspace_bytes(C.byref(d), C.byref(m)) == 0
+    m.k_ffn_max = 32
+    assert L.sf_moe_ffn_forward(C.byref(d), C.byref(m), None, None, 1, 1, None, None, None, None, None, None, 0,
+                                None) == -1
+    assert L.sf_compact_moe_experts(C.byref(d), None, None, None, C.byref(m), None) == -1
     # host-side keep counts out of range
     kh, kf = (C.c_int32 * 1)(9), (C.c_int32 * 1)(3)
     one = C.c_void_p(256)                 # never dereferenced: the count check comes first

@@ -203,6 +203,9 @@ def _moe_case(wl, E, top_k, forced=False, pre_ln=True, add_residual=True):
     (dict(dtype="f32", B=4, act=1, dropout="upto:2", seg=(40, 30, 50), F=96), 5, 1),
     (dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=4), 4, 2),
     (dict(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=320, seg=(100, 133, 64), extra=3, B=5, act=1, dropout="upto:2"), 8, 3),
+    (dict(dtype="f32", B=2, F=64), 3, 3),                                            # every expert chosen
+    (dict(dtype="f32", B=3, d=40, dh=8, F=72, seg=(20, 11, 9)), 16, 8),              # 16-expert router, widest Top-k
+    (dict(dtype="bf16", d=64, dh=32, F=128, seg=(60, 40, 30), B=3), 64, 4),          # 64-expert router
 ])
 def test_moe_ffn_parity_small(kw, E, k):
     _say(f"moe small {kw} E={E} k={k}")
@@ -216,6 +219,33 @@ def test_moe_ffn_parity_C2_full():
     """Full-size launch: C2's tokens (B=64, L=384, d=256, F=1024, 8 patterns) through 8 experts, Top-2."""
     _say("moe C2")
     _moe_case(W.make_workload(W.CONFIGS["C2"]), 8, 2)
+
+
+def test_moe_forced_route_with_a_repeated_expert():
+    """A caller's list that names an expert twice: the expert counts once (in its last slot), the other slot
+    gets weight 0; values outside 0..E-1 are clamped.  Checked against the oracle run on the distinct experts."""
+    wl = W.make_workload(W.small_spec(dtype="f32", B=2, dropout="none"))
+    s = wl.spec
+    E, k = 4, 3
+    mb = W.make_moe_block(wl, E, k)
+    B, L, d, F = wl.x.shape[0], s.L, s.d, s.F
+    assert wl.P == 1
+    desc = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=1, P=1, dtype=sf.SF_F32, act=s.act)
+    ffn_idx = np.tile(np.arange(F, dtype=np.int32), (E, 1, 1))
+    cm = sf.compact_moe_experts(desc, {n: to_dev(v, "f32") for n, v in mb.dense.items()}, to_dev(ffn_idx, "f32"), k, [F] * E)
+    X = wl.x.reshape(B * L, d)
+    fr = np.tile(np.array([[2, 0, 2]], np.int32), (B * L, 1))
+    fr[1] = [7, -3, 1]                                       # clamped to [3, 0, 1]
+    Y, route, weight, _ = sf.moe_ffn_forward(desc, cm, to_dev(X, "f32"), None, forced_route=to_dev(fr, "f32"), want_route=True)
+    torch.cuda.synchronize()
+    Y, route, weight = to_host(Y), to_host(route), to_host(weight)
+    assert np.array_equal(route[0], [2, 0, 2]) and weight[0, 0] == 0.0 and np.array_equal(route[1], [3, 0, 1])
+    assert np.allclose(weight.sum(axis=1), 1.0, atol=1e-6)
+    y2, _, w2, _ = orc.moe_ffn(X[[0] + list(range(2, B * L))], mb.dense, 2, act=s.act, forced_route=np.tile([[0, 2]], (B * L - 1, 1)))
+    assert np.max(np.abs(weight[[0] + list(range(2, B * L))][:, 1:] - w2)) < 1e-5
+    assert err_metric(Y[[0] + list(range(2, B * L))], y2) <= TOL["f32"]
+    y1, _, _, _ = orc.moe_ffn(X[1:2], mb.dense, 3, act=s.act, forced_route=np.array([[3, 0, 1]], np.int32))
+    assert err_metric(Y[1:2], y1) <= TOL["f32"]
 
 
 def test_moe_single_expert_equals_pruned_ffn():
