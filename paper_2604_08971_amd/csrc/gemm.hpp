@@ -26,6 +26,8 @@ struct GemmArgs {
     int act;
     const void *R; int64_t ldr; int r0;                  // residual (NULL = none), first column r0
     void *C; int64_t ldc; int c0;                        // EPI_ROWMAJOR: row stride, first column
+    const int32_t *row_map;                              // large bf16 row-major problems only (gemm_takes_row_map): row i
+                                                         // of sample b reads A row row_map[b*L + i] (all of A within 4 GiB)
     int xcd_rows;                                        // hint: deal 256-row tiles to the 8 XCDs round-robin instead of in
                                                          // contiguous ranges (rows of unequal cost, e.g. n_lim / k_lim)
     int r_f32, c_f32;                                    // bf16 GEMM only: R / C hold fp32 (the residual stream)
@@ -35,6 +37,9 @@ struct GemmArgs {
 // dtype SF_BF16: bf16 MFMA, fp32 accumulate (K % 8 == 0, lda/ldw/ldr % 8 == 0,
 // ldc % 4 == 0, 16-byte aligned bases).  dtype SF_F32: fp32 FMA.
 int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st);
+
+// True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).
+bool gemm_takes_row_map(int dtype, const GemmArgs &a);
 
 // LayerNorm over rows of d elements (biased variance).  gamma/beta are in the
 // model dtype; x is fp32 when x_f32 (or dtype is SF_F32), y is in the model dtype.

@@ -239,10 +239,14 @@ static int32_t launch_cfg(const GemmArgs &a, hipStream_t st)
 
 int32_t gemm_bf16_fast(const GemmArgs &a, hipStream_t st, bool &done);
 int32_t gemm_bf16_ws(const GemmArgs &a, hipStream_t st, bool &done);
+bool gemm_bf16_ws_eligible(const GemmArgs &a);
+
+bool gemm_takes_row_map(int dtype, const GemmArgs &a) { return dtype == SF_BF16 && gemm_bf16_ws_eligible(a); }
 
 int32_t gemm_bf16(const GemmArgs &a, hipStream_t st)
 {
     if (a.B <= 0 || a.N <= 0) return SF_OK;
+    if (a.row_map && !gemm_bf16_ws_eligible(a)) return fail(SF_ERR_UNSUPPORTED, "gemm(bf16): row_map on a problem the large-tile kernel does not take");
     {
         bool done = false;
         if (int32_t rc = gemm_bf16_ws(a, st, done)) return rc;

@@ -98,7 +98,9 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         // ------------------------------------------------------------ loader wave
         const int lw = wave - NCW;
         constexpr int LPW = (BM / 8) / NLW;       // 8 X-instructions and 8 W-instructions per loader wave
-        const char *Ab = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.A) + ((int64_t)b * a.L + m0) * a.lda);
+        const char *Ab = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.A) +
+                                                        (a.row_map ? (int64_t)0 : ((int64_t)b * a.L + m0) * a.lda));
+        const int32_t *rmap = a.row_map ? a.row_map + (int64_t)b * a.L + m0 : nullptr;
         const char *Wb = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.W) + (int64_t)p * a.w_pstride +
                                                         (int64_t)(a.n0 + nt0) * a.ldw);
         const int rows_x = min(BM, a.L - m0), rows_w = min(BN, a.N - nt0);
@@ -108,7 +110,8 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
             const int sr = (lw * LPW + j) * 4 + (lane >> 4);      // super-row of this lane's 16-byte slot
             const int t = (lane & 15) ^ (sr & 7);
             const int r = sr * 2 + (t >> 3), c = t & 7;
-            xoff[j] = (uint32_t)(min(r, rows_x - 1) * (int)a.lda + c * 8) * 2u;
+            const int rx = min(r, rows_x - 1);
+            xoff[j] = ((uint32_t)(rmap ? rmap[rx] : rx) * (uint32_t)a.lda + (uint32_t)(c * 8)) * 2u;
             woff[j] = (uint32_t)(min(r, rows_w - 1) * (int)a.ldw + c * 8) * 2u;
         }
         auto issue_x = [&](int tile) {
@@ -360,15 +363,22 @@ static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
     return SF_OK;
 }
 
-// Takes the problem (sets `done`) when it is large, row-major and K % 64 == 0.
+// Large, row-major, K % 64 == 0.
+bool gemm_bf16_ws_eligible(const GemmArgs &a)
+{
+    if (a.epi != EPI_ROWMAJOR || a.K % BKT || a.K < BKT || a.N % 8 || a.n0 % 8 || a.lda % 8 || a.ldw % 8 ||
+        a.ldc % 8 || a.c0 % 8 || (a.R && (a.ldr % 8 || a.r0 % 8)))
+        return false;
+    if (a.L < 192 || a.N < 192) return false;
+    if ((int64_t)a.L * a.lda * 2 >= ((int64_t)1 << 32) || (int64_t)a.N * a.ldw * 2 >= ((int64_t)1 << 32)) return false;
+    return true;
+}
+
+// Takes the problem (sets `done`) when it is eligible.
 int32_t gemm_bf16_ws(const GemmArgs &a, hipStream_t st, bool &done)
 {
     done = false;
-    if (a.epi != EPI_ROWMAJOR || a.K % BKT || a.K < BKT || a.N % 8 || a.n0 % 8 || a.lda % 8 || a.ldw % 8 ||
-        a.ldc % 8 || a.c0 % 8 || (a.R && (a.ldr % 8 || a.r0 % 8)))
-        return SF_OK;
-    if (a.L < 192 || a.N < 192) return SF_OK;
-    if ((int64_t)a.L * a.lda * 2 >= ((int64_t)1 << 32) || (int64_t)a.N * a.ldw * 2 >= ((int64_t)1 << 32)) return SF_OK;
+    if (!gemm_bf16_ws_eligible(a)) return SF_OK;
     done = true;
     switch (a.act) {
     case ACT_RELU: return launch_ws<ACT_RELU>(a, st);

@@ -46,10 +46,11 @@ template <> struct Vec16<__bf16> {
     }
 };
 
-// One wave per token, TOK_PER_BLOCK tokens per block: lane e ends up holding logit_e (E <= EB <= 64).  The
-// token's row is read once (16 bytes per lane and step, d % Vec16<T>::N == 0); the router rows are staged in
-// LDS once per block when they fit (WLDS), else they come through the cache.
-constexpr int TOK_PER_BLOCK = 32;
+// Router.  Phase 1, one wave per token (TOK_PER_BLOCK tokens per block): the token's row is read once
+// (16 bytes per lane and step, d % Vec16<T>::N == 0) against the router rows, which are staged in LDS once
+// per block when they fit (WLDS) and come through the cache otherwise; the E logits go to LDS.  Phase 2, one
+// lane per token: Top-k and the softmax over the chosen logits.
+constexpr int TOK_PER_BLOCK = 64;
 
 template <class T, int EB, bool WLDS>
 __global__ __launch_bounds__(256) void moe_router_kernel(
@@ -59,41 +60,61 @@ __global__ __launch_bounds__(256) void moe_router_kernel(
 {
     constexpr int VN = Vec16<T>::N;
     extern __shared__ __attribute__((aligned(16))) char router_lds[];
+    float *lg = reinterpret_cast<float *>(router_lds);      // [TOK_PER_BLOCK][E + 1]
+    const int lgs = E + 1;
     const T *Wl = Wr;
     if constexpr (WLDS) {
-        uint4 *dst = reinterpret_cast<uint4 *>(router_lds);
+        char *wbase = router_lds + (((size_t)TOK_PER_BLOCK * lgs * sizeof(float) + 15) & ~(size_t)15);
+        uint4 *dst = reinterpret_cast<uint4 *>(wbase);
         const uint4 *src = reinterpret_cast<const uint4 *>(Wr);
         const int n16 = E * d / VN;
         for (int i = threadIdx.x; i < n16; i += 256) dst[i] = src[i];
         __syncthreads();
-        Wl = reinterpret_cast<const T *>(router_lds);
+        Wl = reinterpret_cast<const T *>(wbase);
     }
     const int lane = threadIdx.x & 63;
     for (int tt = threadIdx.x >> 6; tt < TOK_PER_BLOCK; tt += 4) {
-    const int64_t t = (int64_t)blockIdx.x * TOK_PER_BLOCK + tt;
-    if (t >= rows) break;
-    const T *x = xn + t * d;
-    float acc[EB];
+        const int64_t t = (int64_t)blockIdx.x * TOK_PER_BLOCK + tt;
+        if (t >= rows) break;
+        const T *x = xn + t * d;
+        float acc[EB];
 #pragma unroll
-    for (int e = 0; e < EB; ++e) acc[e] = 0.f;
-    for (int c = lane * VN; c < d; c += 64 * VN) {
-        float xv[VN];
-        Vec16<T>::load(x + c, xv);
+        for (int e = 0; e < EB; ++e) acc[e] = 0.f;
+        for (int c = lane * VN; c < d; c += 64 * VN) {
+            if constexpr (VN == 8) {
+                // bf16: two products per instruction, fp32 accumulate, no unpacking
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const uint4 xq = *reinterpret_cast<const uint4 *>(x + c);
+                const uint32_t xw[4] = {xq.x, xq.y, xq.z, xq.w};
 #pragma unroll
-        for (int e = 0; e < EB; ++e) {
-            if (e < E) {
-                float wv[VN];
-                Vec16<T>::load(Wl + e * d + c, wv);
+                for (int e = 0; e < EB; ++e) {
+                    if (e < E) {
+                        const uint4 wq = *reinterpret_cast<const uint4 *>(Wl + e * d + c);
+                        const uint32_t ww[4] = {wq.x, wq.y, wq.z, wq.w};
 #pragma unroll
-                for (int i = 0; i < VN; ++i) acc[e] = fmaf(xv[i], wv[i], acc[e]);
+                        for (int i = 0; i < 4; ++i)
+                            acc[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xw[i]),
+                                                                     __builtin_bit_cast(bf16x2, ww[i]), acc[e], false);
+                    }
+                }
+            } else {
+                float xv[VN];
+                Vec16<T>::load(x + c, xv);
+#pragma unroll
+                for (int e = 0; e < EB; ++e) {
+                    if (e < E) {
+                        float wv[VN];
+                        Vec16<T>::load(Wl + e * d + c, wv);
+#pragma unroll
+                        for (int i = 0; i < VN; ++i) acc[e] = fmaf(xv[i], wv[i], acc[e]);
+                    }
+                }
             }
         }
-    }
-    // Transposing reduction: every step halves the number of partial sums a lane carries (the lanes whose
-    // bit `o` is set keep the upper half) until one is left, which the remaining steps sum up; lane l then
-    // holds the logit of expert l >> SH.  EB - 1 + log2(64 / EB) exchanges instead of 6 * EB.
-    constexpr int SH = EB == 64 ? 0 : (EB == 16 ? 2 : 3);
-    {
+        // Transposing reduction: every step halves the number of partial sums a lane carries (the lanes whose
+        // bit `o` is set keep the upper half) until one is left, which the remaining steps sum up; lane l then
+        // holds the logit of expert l >> SH.  EB - 1 + log2(64 / EB) exchanges instead of 6 * EB.
+        constexpr int SH = EB == 64 ? 0 : (EB == 16 ? 2 : 3);
         int n = EB;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -112,35 +133,42 @@ __global__ __launch_bounds__(256) void moe_router_kernel(
                 acc[0] += __shfl_xor(acc[0], o);
             }
         }
+        const int e = lane >> SH;
+        if ((lane & ((1 << SH) - 1)) == 0 && e < E) lg[tt * lgs + e] = acc[0] + (br ? to_f32(br[e]) : 0.f);
     }
-    float mine = __shfl(acc[0], (lane << SH) & 63);         // logit of expert `lane`
-    if (lane < E) { if (br) mine += to_f32(br[lane]); }
-    else mine = -INFINITY;
-    if (logit_out && lane < E) logit_out[t * E + lane] = mine;
-    // Top-k by repeated wave argmax over the experts not taken yet (ties: lower expert index; a NaN logit
-    // ranks below every number), or the caller's experts.  Picks and their logits are wave-uniform.
-    const float val = mine == mine ? mine : -INFINITY;
-    bool avail = lane < E;
+    __syncthreads();
+    // Phase 2: lane tt of the first wave owns token tt.  Top-k by repeated scan over the experts not taken yet
+    // (ties: lower expert index; a NaN logit ranks below every number), or the caller's experts.
+    if (threadIdx.x >= TOK_PER_BLOCK) return;
+    const int64_t t = (int64_t)blockIdx.x * TOK_PER_BLOCK + threadIdx.x;
+    if (t >= rows) return;
+    const float *my = lg + threadIdx.x * lgs;
+    if (logit_out)
+        for (int e = 0; e < E; ++e) logit_out[t * E + e] = my[e];
     int pick[8];
     float pv[8];
+    unsigned long long taken = 0;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
         pick[s] = 0;
         pv[s] = -INFINITY;
         if (s < top_k) {
-            int e;
+            int be = -1;
+            float bv = -INFINITY;
             if (forced_route) {
-                e = __builtin_amdgcn_readfirstlane(min(max(forced_route[t * top_k + s], 0), E - 1));
+                be = min(max(forced_route[t * top_k + s], 0), E - 1);
+                bv = my[be];
+                bv = bv == bv ? bv : -INFINITY;
             } else {
-                float v = avail ? val : -INFINITY;
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-                const unsigned long long m = __ballot(avail && val == v);
-                e = __builtin_amdgcn_readfirstlane(__builtin_ctzll(m));     // m != 0: top_k <= E experts available
-                if (lane == e) avail = false;
+                for (int e = 0; e < E; ++e) {
+                    float v = my[e];
+                    v = v == v ? v : -INFINITY;
+                    if (!((taken >> e) & 1) && (be < 0 || v > bv)) { be = e; bv = v; }
+                }
+                taken |= 1ull << be;                        // be >= 0: top_k <= E
             }
-            pick[s] = e;
-            pv[s] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, val), e));
+            pick[s] = be;
+            pv[s] = bv;
         }
     }
     // softmax over the chosen logits (an expert listed twice by the caller counts once, in its last slot)
@@ -150,8 +178,8 @@ __global__ __launch_bounds__(256) void moe_router_kernel(
         bool again = false;
 #pragma unroll
         for (int q = s + 1; q < 8; ++q) again = again || (q < top_k && pick[q] == pick[s]);
-        if (s >= top_k || again) pv[s] = -INFINITY, ex[s] = -1.f;            // not part of the softmax
-        else ex[s] = 0.f;
+        ex[s] = (s >= top_k || again) ? -1.f : 0.f;         // < 0: not part of the softmax
+        if (ex[s] < 0.f) pv[s] = -INFINITY;
         mx = fmaxf(mx, pv[s]);
     }
 #pragma unroll
@@ -159,16 +187,13 @@ __global__ __launch_bounds__(256) void moe_router_kernel(
         ex[s] = ex[s] < 0.f ? 0.f : expf(pv[s] - mx);
         den += ex[s];
     }
-    int my_e = 0;
-    float my_w = 0.f;
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
-        if (lane == s) { my_e = pick[s]; my_w = ex[s] / den; }
-    if (lane < top_k) {
-        route[t * top_k + lane] = my_e;
-        weight[t * top_k + lane] = my_w;
+    for (int s = 0; s < 8; ++s) {
+        if (s < top_k) {
+            route[t * top_k + s] = pick[s];
+            weight[t * top_k + s] = ex[s] / den;
+        }
     }
-    }   // token loop
 }
 
 __global__ void moe_zero_kernel(int32_t *p, int n)
@@ -258,7 +283,7 @@ __global__ __launch_bounds__(256) void moe_layout_kernel(const int32_t *__restri
 __global__ __launch_bounds__(256) void moe_place_kernel(const int32_t *__restrict__ route, const int32_t *__restrict__ pattern_id,
                                                         int64_t pairs, int L, int P, int E, int top_k,
                                                         const int32_t *__restrict__ seg_base, int32_t *__restrict__ cursor,
-                                                        int32_t *__restrict__ pos)
+                                                        int32_t *__restrict__ pos, int32_t *__restrict__ src_row)
 {
     __shared__ int hist[MAX_SEG];
     constexpr int PER = PAIRS_PER_BLOCK / 256;
@@ -285,7 +310,12 @@ __global__ __launch_bounds__(256) void moe_place_kernel(const int32_t *__restric
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < PER; ++q)
-        if (seg[q] >= 0) pos[i0 + q * 256 + threadIdx.x] = hist[seg[q]] + rank[q];
+        if (seg[q] >= 0) {
+            const int64_t i = i0 + q * 256 + threadIdx.x;
+            const int at = hist[seg[q]] + rank[q];
+            pos[i] = at;
+            src_row[at] = (int32_t)(i / top_k);             // the token whose row the GEMM reads for gathered row `at`
+        }
 }
 
 // Xg[pos[token, slot], :] = xn[token, :]; one wave per (token, slot), 16-byte copies when possible
@@ -353,7 +383,7 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const T *__restrict__ 
 }
 
 struct MoeWs {
-    void *xn, *xg, *hg; float *yg, *weight; int32_t *route, *pos, *counts, *seg_base, *cursor, *blk_seg, *seg_width;
+    void *xn, *xg, *hg; float *yg, *weight; int32_t *route, *pos, *counts, *seg_base, *cursor, *blk_seg, *seg_width, *src_row;
     int n_blocks_max, Fp; size_t bytes;
 };
 
@@ -375,6 +405,7 @@ MoeWs moe_ws(const Dims &D, const sf_moe_compact &m, void *ws)
     w.cursor = c.take<int32_t>(n_seg);
     w.blk_seg = c.take<int32_t>(w.n_blocks_max);
     w.seg_width = c.take<int32_t>(n_seg);
+    w.src_row = c.take<int32_t>(grows);
     w.xg = c.take<char>(grows * D.d * es);
     w.hg = c.take<char>(grows * (size_t)w.Fp * es);
     w.yg = c.take<float>(grows * D.d);
@@ -443,15 +474,16 @@ extern "C" int32_t sf_moe_ffn_forward(const sf_desc *desc, const sf_moe_compact 
     {
         dim3 grid((unsigned)((rows + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK));
         const size_t wbytes = (size_t)E * D.d * es;
-        const bool wlds = wbytes <= 64 * 1024;
+        const size_t lgbytes = ((size_t)TOK_PER_BLOCK * (E + 1) * sizeof(float) + 15) & ~(size_t)15;
+        const bool wlds = lgbytes + wbytes <= 64 * 1024;
 #define SF_ROUTER(T, EB)                                                                                              \
     do {                                                                                                              \
         if (wlds)                                                                                                     \
-            hipLaunchKernelGGL((moe_router_kernel<T, EB, true>), grid, dim3(256), wbytes, st, (const T *)xin,         \
+            hipLaunchKernelGGL((moe_router_kernel<T, EB, true>), grid, dim3(256), lgbytes + wbytes, st, (const T *)xin,         \
                                (const T *)m->Wr, (const T *)m->br, rows, D.d, E, k, forced_route, w.route, w.weight,  \
                                logit_out);                                                                            \
         else                                                                                                          \
-            hipLaunchKernelGGL((moe_router_kernel<T, EB, false>), grid, dim3(256), 0, st, (const T *)xin,             \
+            hipLaunchKernelGGL((moe_router_kernel<T, EB, false>), grid, dim3(256), lgbytes, st, (const T *)xin,             \
                                (const T *)m->Wr, (const T *)m->br, rows, D.d, E, k, forced_route, w.route, w.weight,  \
                                logit_out);                                                                            \
     } while (0)
@@ -469,13 +501,25 @@ extern "C" int32_t sf_moe_ffn_forward(const sf_desc *desc, const sf_moe_compact 
     // counting sort of the (token, slot) pairs by (pattern, expert)
     const unsigned sort_blocks = (unsigned)((pairs + PAIRS_PER_BLOCK - 1) / PAIRS_PER_BLOCK);
     hipLaunchKernelGGL(moe_zero_kernel, dim3(ceil_div(n_seg, 256)), dim3(256), 0, st, w.counts, n_seg);
+    // rows of padding read token 0 (their results are never used)
+    hipLaunchKernelGGL(moe_zero_kernel, dim3(ceil_div(w.n_blocks_max * SEG_ROWS, 256)), dim3(256), 0, st, w.src_row,
+                       w.n_blocks_max * SEG_ROWS);
     hipLaunchKernelGGL(moe_count_kernel, dim3(sort_blocks), dim3(256), 0, st, w.route, pattern_id, pairs, D.L, D.P, E, k,
                        w.counts);
     hipLaunchKernelGGL(moe_layout_kernel, dim3(1), dim3(256), 0, st, w.counts, n_seg, w.n_blocks_max, m->k_ffn, E,
                        D.ffn_pad, w.Fp, w.seg_base, w.cursor, w.blk_seg, w.seg_width);
     hipLaunchKernelGGL(moe_place_kernel, dim3(sort_blocks), dim3(256), 0, st, w.route, pattern_id, pairs, D.L, D.P, E, k,
-                       w.seg_base, w.cursor, w.pos);
-    {
+                       w.seg_base, w.cursor, w.pos, w.src_row);
+    // first GEMM over 256-row blocks; the block's segment selects the weights.  Large bf16 problems read the
+    // token rows through the row map, the others from a gathered copy.
+    GemmArgs g{};
+    g.A = xin; g.lda = D.d; g.W = m->W1; g.ldw = D.d; g.w_pstride = (int64_t)w.Fp * D.d;
+    g.bias = m->b1; g.bias_pstride = w.Fp; g.pattern_id = w.blk_seg; g.n_lim = w.seg_width; g.xcd_rows = 1;
+    g.B = w.n_blocks_max; g.L = SEG_ROWS; g.N = w.Fp; g.K = D.d; g.epi = EPI_ROWMAJOR;
+    g.act = D.act == SF_GELU_ERF ? ACT_GELU : ACT_RELU;
+    g.C = w.hg; g.ldc = w.Fp;
+    g.row_map = w.src_row;
+    if (!(rows * D.d * 2 < ((int64_t)1 << 32) && gemm_takes_row_map(D.dtype, g))) {
         const size_t row_bytes = (size_t)D.d * es;
         dim3 grid((unsigned)((pairs + 3) / 4));
         if (row_bytes % 16 == 0 && ((uintptr_t)xin % 16 == 0))
@@ -484,14 +528,9 @@ extern "C" int32_t sf_moe_ffn_forward(const sf_desc *desc, const sf_moe_compact 
         else
             hipLaunchKernelGGL(moe_gather_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)xin, w.pos, pairs,
                                k, (int)(row_bytes / 2), (uint16_t *)w.xg);
+        g.A = w.xg;
+        g.row_map = nullptr;
     }
-    // the two GEMMs over 256-row blocks; the block's segment selects the weights
-    GemmArgs g{};
-    g.A = w.xg; g.lda = D.d; g.W = m->W1; g.ldw = D.d; g.w_pstride = (int64_t)w.Fp * D.d;
-    g.bias = m->b1; g.bias_pstride = w.Fp; g.pattern_id = w.blk_seg; g.n_lim = w.seg_width; g.xcd_rows = 1;
-    g.B = w.n_blocks_max; g.L = SEG_ROWS; g.N = w.Fp; g.K = D.d; g.epi = EPI_ROWMAJOR;
-    g.act = D.act == SF_GELU_ERF ? ACT_GELU : ACT_RELU;
-    g.C = w.hg; g.ldc = w.Fp;
     if (int32_t rc = gemm(D.dtype, g, st)) return rc;
     GemmArgs h{};
     h.A = w.hg; h.lda = w.Fp; h.W = m->W2T; h.ldw = w.Fp; h.w_pstride = (int64_t)D.d * w.Fp;
