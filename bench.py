@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the pruned multimodal encoder forward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--no-cpu] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--no-cpu] [--no-extras] [--moe-only]
 
 One "step" is one pass of the whole hot path over one batch of seeded synthetic
 input already resident in HBM: gate scores -> keep masks, compaction of the
@@ -30,7 +30,7 @@ GEMM_KERNEL_NAMES = {
     "qk_proj": "gemm_bf16_ws_kernel<0> (Q/K projection)",
     "v_proj": "gemm_bf16_fast_kernel<..., true, 0> (V projection, transposed output)",
     "o_proj": "gemm_bf16_ws_kernel<0> (output projection + residual)",
-    "ffn_up": "gemm_bf16_ws_kernel<1> (FFN up-projection + GELU)",
+    "ffn_up": "gemm_bf16_ws_kernel<1> (FFN up-projection + ReLU)",
     "ffn_down": "gemm_bf16_ws_kernel<0> (FFN down-projection + residual)",
 }
 # HBM-side bytes per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) and scaled by the
@@ -288,7 +288,7 @@ def bench_moe(wl, steps, warmup, E=8, top_k=2):
     kf = mb.k_ffn.tolist()
     masks = sf.gate_scores_to_masks(dmask, g_head, g_ffn, [1] * E, kf)
     cm = sf.compact_moe_experts(desc, dense, masks["ffn_idx"], top_k, kf)
-    ws = sf.workspace(sf.lib().sf_moe_ffn_workspace_bytes(__import__("ctypes").byref(desc), __import__("ctypes").byref(cm.struct)))
+    ws = sf.workspace(sf.moe_ffn_workspace_bytes(desc, cm))
     Y = torch.empty_like(X)
 
     def fwd():
@@ -354,6 +354,8 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--moe-only", action="store_true",
+                    help="time only the Sparse-MoE FFN block on the workload's tokens and print its object (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (one MI355X holds every workload and no step of the path "
@@ -365,6 +367,10 @@ def main():
     from paper_2604_08971_amd import binding as sf
     from paper_2604_08971_amd import workloads as W
     sf.lib()
+
+    if args.moe_only:
+        print(json.dumps(bench_moe(W.make_workload(W.CONFIGS[args.config]), args.steps, args.warmup)), flush=True)
+        return
 
     if args.copy_calibration > 0:
         n = args.copy_calibration << 20

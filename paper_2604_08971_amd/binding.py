@@ -363,6 +363,10 @@ def compact_moe_experts(desc: SfDesc, dense: Dict[str, torch.Tensor], ffn_idx: t
     return cm
 
 
+def moe_ffn_workspace_bytes(desc: SfDesc, moe: CompactMoe) -> int:
+    return int(lib().sf_moe_ffn_workspace_bytes(C.byref(desc), C.byref(moe.struct)))
+
+
 def moe_ffn_forward(desc: SfDesc, moe: CompactMoe, X: torch.Tensor, pattern_id: Optional[torch.Tensor] = None,
                     pre_ln: bool = True, add_residual: bool = True, forced_route: Optional[torch.Tensor] = None,
                     want_route: bool = False, out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
@@ -379,7 +383,7 @@ def moe_ffn_forward(desc: SfDesc, moe: CompactMoe, X: torch.Tensor, pattern_id: 
         assert forced_route.dtype == torch.int32 and forced_route.is_contiguous()
         assert tuple(forced_route.shape) == (rows, moe.top_k)
     if ws is None:
-        ws = workspace(lib().sf_moe_ffn_workspace_bytes(C.byref(desc), C.byref(moe.struct)), X.device)
+        ws = workspace(moe_ffn_workspace_bytes(desc, moe), X.device)
     rc = lib().sf_moe_ffn_forward(C.byref(desc), C.byref(moe.struct), _ptr(X), _ptr(pattern_id), int(pre_ln),
                                   int(add_residual), _ptr(forced_route), _ptr(Y), _ptr(route), _ptr(weight),
                                   _ptr(logit), _ptr(ws), ws.numel(), _stream())
