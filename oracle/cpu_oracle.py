@@ -52,7 +52,8 @@ def lib():
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_max_threads.restype = C.c_int32
-        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_moe_ffn"):
+        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_moe_ffn",
+                  "orc_gate_eval", "orc_budget_search"):
             getattr(_lib, f).restype = C.c_int32
     return _lib
 
@@ -227,6 +228,45 @@ def moe_ffn(x, moe: Dict[str, np.ndarray], top_k: int, act: int = 0, eps: float 
     if rc != 0:
         raise ValueError("orc_moe_ffn: bad arguments")
     return y, route, weight, logit
+
+
+def gate_eval(gate: Dict[str, np.ndarray], pattern_bits, Hq: int, nonlin: int = 0):
+    """Eq. (1) for every layer and presence pattern.  gate: Wa [nl,Hd,M], ba [nl,Hd], Wb [nl,Hq+F,Hd],
+    cb [nl,Hq+F], zeta [nl,Hq+F], gamma [nl].  Returns (g_head [nl,P,Hq], g_ffn [nl,P,F]) in fp64."""
+    Wa, ba, Wb, cb, zeta = (_f64(gate[k]) for k in ("Wa", "ba", "Wb", "cb", "zeta"))
+    gamma = _f64(gate["gamma"])
+    nl, Hd, M = Wa.shape
+    n_units = Wb.shape[1]
+    bits = np.asarray(pattern_bits, dtype=np.int64)
+    out = np.empty((nl, len(bits), n_units), np.float64)
+    row = np.empty(n_units, np.float64)
+    for l in range(nl):
+        for p, b in enumerate(bits):
+            rc = lib().orc_gate_eval(C.c_int32(M), C.c_int32(Hd), C.c_int32(n_units), C.c_int32(nonlin),
+                                     _p(Wa[l]), _p(ba[l]), _p(Wb[l]), _p(cb[l]), _p(zeta[l]),
+                                     C.c_double(float(gamma[l])), C.c_uint32(int(b)), _p(row))
+            if rc != 0:
+                raise ValueError("orc_gate_eval: bad arguments")
+            out[l, p] = row
+    return np.ascontiguousarray(out[:, :, :Hq]), np.ascontiguousarray(out[:, :, Hq:])
+
+
+def budget_search(g_head, g_ffn, Hk: int, c_head, c_group, c_ffn, c_fixed: int, budget: int):
+    """g_head [nl,Hq], g_ffn [nl,F] fp32 scores of one pattern.  Returns dict(feasible, tau, k_head, k_ffn, cost)."""
+    g_head = np.ascontiguousarray(g_head, dtype=np.float32)
+    g_ffn = np.ascontiguousarray(g_ffn, dtype=np.float32)
+    nl, Hq = g_head.shape
+    F = g_ffn.shape[1]
+    ch, cg, cf = (np.ascontiguousarray(a, dtype=np.int64) for a in (c_head, c_group, c_ffn))
+    assert ch.shape == (nl,) and cg.shape == (nl,) and cf.shape == (nl,)
+    tau, cost = C.c_float(0.0), C.c_int64(0)
+    k_head, k_ffn = np.zeros(nl, np.int32), np.zeros(nl, np.int32)
+    rc = lib().orc_budget_search(C.c_int32(nl), C.c_int32(Hq), C.c_int32(Hk), C.c_int32(F), _p(g_head), _p(g_ffn),
+                                 _p(ch), _p(cg), _p(cf), C.c_int64(int(c_fixed)), C.c_int64(int(budget)),
+                                 C.byref(tau), _p(k_head), _p(k_ffn), C.byref(cost))
+    if rc < 0:
+        raise ValueError("orc_budget_search: bad arguments")
+    return {"feasible": bool(rc), "tau": np.float32(tau.value), "k_head": k_head, "k_ffn": k_ffn, "cost": int(cost.value)}
 
 
 def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,

@@ -14,6 +14,91 @@
 #include <omp.h>
 #endif
 
+/* ---- SentryGate: Eq. (1) and the global threshold ------------------------ */
+int32_t orc_gate_eval(int32_t M, int32_t Hd, int32_t n_units, int32_t nonlin, const double *Wa,
+                      const double *ba, const double *Wb, const double *cb, const double *zeta,
+                      double gamma, uint32_t pattern_bits, double *g)
+{
+    if (M < 1 || M > 32 || Hd < 1 || n_units < 1 || nonlin < 0 || nonlin > 1 || !Wa || !Wb || !zeta || !g)
+        return -1;
+    double *h = (double *)malloc(sizeof(double) * (size_t)Hd);
+    if (!h) return -1;
+    for (int32_t r = 0; r < Hd; ++r) {
+        double a = ba ? ba[r] : 0.0;
+        for (int32_t j = 0; j < M; ++j) {
+            const double mj = (double)((pattern_bits >> j) & 1u);
+            a += Wa[(int64_t)r * M + j] * mj;
+        }
+        h[r] = nonlin == 0 ? (a > 0.0 ? a : 0.0) : tanh(a);
+    }
+    for (int32_t i = 0; i < n_units; ++i) {
+        double f = cb ? cb[i] : 0.0;
+        for (int32_t r = 0; r < Hd; ++r) f += Wb[(int64_t)i * Hd + r] * h[r];
+        const double z = zeta[i] + gamma * f;
+        g[i] = 1.0 / (1.0 + exp(-z));
+    }
+    free(h);
+    return 0;
+}
+
+/* cost and sizes of the keep set of threshold v (see the header) */
+static int64_t keep_set_cost(int32_t nl, int32_t Hq, int32_t Hk, int32_t F, const float *g_head,
+                             const float *g_ffn, const int64_t *c_head, const int64_t *c_group,
+                             const int64_t *c_ffn, int64_t c_fixed, float v, int32_t *k_head,
+                             int32_t *k_ffn)
+{
+    const int32_t per_group = Hq / Hk;
+    int64_t cost = c_fixed;
+    for (int32_t l = 0; l < nl; ++l) {
+        const float *gh = g_head + (int64_t)l * Hq, *gf = g_ffn + (int64_t)l * F;
+        int32_t kh = 0, kg = 0, kf = 0;
+        for (int32_t grp = 0; grp < Hk; ++grp) {
+            int any = 0;
+            for (int32_t h = grp * per_group; h < (grp + 1) * per_group; ++h)
+                if (gh[h] >= v) { ++kh; any = 1; }
+            kg += any;
+        }
+        if (kh == 0) { kh = 1; kg = 1; }              /* the best head stays, with its group */
+        for (int32_t c = 0; c < F; ++c)
+            if (gf[c] >= v) ++kf;
+        if (kf == 0) kf = 1;                          /* the best channel stays */
+        cost += (int64_t)kh * c_head[l] + (int64_t)kg * c_group[l] + (int64_t)kf * c_ffn[l];
+        if (k_head) k_head[l] = kh;
+        if (k_ffn) k_ffn[l] = kf;
+    }
+    return cost;
+}
+
+int32_t orc_budget_search(int32_t nl, int32_t Hq, int32_t Hk, int32_t F, const float *g_head,
+                          const float *g_ffn, const int64_t *c_head, const int64_t *c_group,
+                          const int64_t *c_ffn, int64_t c_fixed, int64_t budget, float *tau,
+                          int32_t *k_head, int32_t *k_ffn, int64_t *cost)
+{
+    if (nl < 1 || Hq < 1 || Hk < 1 || F < 1 || Hq % Hk != 0 || !g_head || !g_ffn || !c_head ||
+        !c_group || !c_ffn || !tau || !k_head || !k_ffn || !cost)
+        return -1;
+    for (int32_t l = 0; l < nl; ++l)
+        if (c_head[l] < 0 || c_group[l] < 0 || c_ffn[l] < 0) return -1;
+    const int64_t n_head = (int64_t)nl * Hq, n_all = n_head + (int64_t)nl * F;
+    int found = 0;
+    float best = 0.f;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < n_all; ++i) {
+        const float v = i < n_head ? g_head[i] : g_ffn[i - n_head];
+        const int64_t c = keep_set_cost(nl, Hq, Hk, F, g_head, g_ffn, c_head, c_group, c_ffn, c_fixed, v,
+                                        NULL, NULL);
+        if (c <= budget) {
+#pragma omp critical
+            {
+                if (!found || v < best) { best = v; found = 1; }
+            }
+        }
+    }
+    *tau = found ? best : INFINITY;
+    *cost = keep_set_cost(nl, Hq, Hk, F, g_head, g_ffn, c_head, c_group, c_ffn, c_fixed, *tau, k_head, k_ffn);
+    return found;
+}
+
 int32_t orc_max_threads(void)
 {
 #ifdef _OPENMP

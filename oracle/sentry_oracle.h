@@ -190,6 +190,40 @@ int32_t orc_moe_ffn(const orc_moe *m, const double *x, int64_t rows, int32_t act
                     double *weight_out, double *logit_out);
 
 /* Threads the OpenMP runtime will use (for the benchmark's report). */
+/*
+ * SentryGate importance scores, Eq. (1):  g_i(m) = sigmoid( zeta_i + gamma * f_i(m) )  for the units i of one
+ * layer (its heads and its FFN channels) and one modality-availability mask m in {0,1}^M.
+ * f is a two-layer perceptron with a nonlinearity; the paper gives neither its width nor the nonlinearity.
+ * Reading: the first layer is shared by the units of the layer, h = nonlin(Wa m + ba) with Hd hidden units,
+ * and every unit has its own output row, f_i = Wb[i,:] . h + cb[i].  nonlin: 0 = ReLU, 1 = tanh.
+ *   Wa [Hd,M], ba [Hd], Wb [n_units,Hd], cb [n_units], zeta [n_units]; bit j of pattern_bits = m_j
+ *   g [n_units] (fp64)
+ * returns 0, or -1 on bad arguments.
+ */
+int32_t orc_gate_eval(int32_t M, int32_t Hd, int32_t n_units, int32_t nonlin, const double *Wa,
+                      const double *ba, const double *Wb, const double *cb, const double *zeta,
+                      double gamma, uint32_t pattern_bits, double *g);
+
+/*
+ * Global threshold for a cost budget (Sec. 4.5, the paragraph before "Head pruning ...": the gate outputs of
+ * all layers are evaluated for one platform mask and thresholded globally; Sec. 4.2: the threshold is chosen to
+ * meet a FLOPs or energy budget).  Keep set of a threshold v: every head and channel with score >= v; a layer
+ * whose heads (channels) all fall below v keeps its best head (channel), ties to the lower index, so that no
+ * layer disappears (reading; the paper does not say).  K/V groups follow the kept heads as in
+ * orc_gate_scores_to_masks.  Cost of a keep set, in integer units supplied by the caller:
+ *   c_fixed + sum_l ( kept_heads_l * c_head[l] + kept_groups_l * c_group[l] + kept_channels_l * c_ffn[l] ).
+ * Result: the smallest score value v among all units whose keep set costs <= budget (the largest network within
+ * the budget); k_head[l], k_ffn[l] are the sizes of that keep set and *cost its cost.  Every candidate value is
+ * tried (no search order is assumed).  Scores must not be NaN.
+ *   g_head [nl,Hq], g_ffn [nl,F] (fp32, the scores of the platform's pattern)
+ * returns 1 when such a value exists; 0 when even the one-unit-per-layer network exceeds the budget (then
+ * *tau = +inf and the outputs describe that minimal network); -1 on bad arguments.
+ */
+int32_t orc_budget_search(int32_t nl, int32_t Hq, int32_t Hk, int32_t F, const float *g_head,
+                          const float *g_ffn, const int64_t *c_head, const int64_t *c_group,
+                          const int64_t *c_ffn, int64_t c_fixed, int64_t budget, float *tau,
+                          int32_t *k_head, int32_t *k_ffn, int64_t *cost);
+
 int32_t orc_max_threads(void);
 
 #ifdef __cplusplus

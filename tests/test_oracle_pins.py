@@ -666,3 +666,127 @@ def test_encoder_forced_selection_roundtrip():
         tau = np.sort(m)[::-1][U - 1]
         chosen = np.zeros(spec.L, bool); chosen[sel[0, 0, h]] = True
         assert (m[chosen] >= tau).all() and (m[~chosen] <= tau).all()
+
+
+# ------------------------------------------------ SentryGate: Eq. (1) and the global threshold
+def _gate_params(rng, nl, M, Hd, n_units):
+    return {"Wa": rng.standard_normal((nl, Hd, M)), "ba": 0.3 * rng.standard_normal((nl, Hd)),
+            "Wb": rng.standard_normal((nl, n_units, Hd)) / np.sqrt(Hd), "cb": 0.2 * rng.standard_normal((nl, n_units)),
+            "zeta": rng.standard_normal((nl, n_units)), "gamma": rng.uniform(0.5, 2.0, nl)}
+
+
+@pytest.mark.parametrize("nonlin", [0, 1])
+def test_gate_eval_against_library_ops(nonlin):
+    """Eq. (1) with library routines: matmul for both layers, scipy's expit for the sigmoid."""
+    from scipy.special import expit
+    rng = np.random.default_rng(31)
+    nl, M, Hd, Hq, F = 3, 4, 6, 4, 11
+    gp = _gate_params(rng, nl, M, Hd, Hq + F)
+    bits = np.arange(2 ** M)
+    gh, gf = orc.gate_eval(gp, bits, Hq, nonlin)
+    assert gh.shape == (nl, 16, Hq) and gf.shape == (nl, 16, F)
+    m = ((bits[:, None] >> np.arange(M)) & 1).astype(np.float64)             # [P, M], bit j = modality j
+    for l in range(nl):
+        pre = m @ gp["Wa"][l].T + gp["ba"][l]
+        h = np.maximum(pre, 0.0) if nonlin == 0 else np.tanh(pre)
+        ref = expit(gp["zeta"][l] + gp["gamma"][l] * (h @ gp["Wb"][l].T + gp["cb"][l]))
+        assert np.max(np.abs(np.concatenate([gh[l], gf[l]], axis=1) - ref)) < 1e-14
+
+
+def test_gate_eval_special_cases():
+    rng = np.random.default_rng(32)
+    nl, M, Hd, Hq, F = 2, 3, 5, 2, 7
+    gp = _gate_params(rng, nl, M, Hd, Hq + F)
+    bits = np.arange(8)
+    # gamma = 0: the mask has no say, g = sigmoid(zeta), the same for every pattern
+    g0 = dict(gp, gamma=np.zeros(nl))
+    gh, gf = orc.gate_eval(g0, bits, Hq)
+    want = 1.0 / (1.0 + np.exp(-gp["zeta"]))
+    assert np.allclose(gh, want[:, None, :Hq], atol=1e-15) and np.allclose(gf, want[:, None, Hq:], atol=1e-15)
+    # zeta = 0 and a dead perceptron output: g = 1/2 exactly
+    gz = dict(gp, zeta=np.zeros((nl, Hq + F)), Wb=np.zeros((nl, Hq + F, Hd)), cb=np.zeros((nl, Hq + F)))
+    gh, gf = orc.gate_eval(gz, bits, Hq)
+    assert np.all(gh == 0.5) and np.all(gf == 0.5)
+    # sigmoid(-z) = 1 - sigmoid(z): negate zeta and the output layer
+    gh1, gf1 = orc.gate_eval(gp, bits, Hq, 1)
+    gn = dict(gp, zeta=-gp["zeta"], Wb=-gp["Wb"], cb=-gp["cb"])
+    gh2, gf2 = orc.gate_eval(gn, bits, Hq, 1)
+    assert np.max(np.abs(gh1 + gh2 - 1.0)) < 1e-15 and np.max(np.abs(gf1 + gf2 - 1.0)) < 1e-15
+    # no modality present: the first layer sees only its bias; ReLU of a negative bias kills the unit's input
+    gb = dict(gp, ba=-np.abs(gp["ba"]) - 0.1)
+    gh, gf = orc.gate_eval(gb, [0], Hq, 0)
+    want = 1.0 / (1.0 + np.exp(-(gp["zeta"] + gp["gamma"][:, None] * gp["cb"])))
+    assert np.allclose(gh[:, 0], want[:, :Hq], atol=1e-15) and np.allclose(gf[:, 0], want[:, Hq:], atol=1e-15)
+    # one modality, one hidden unit, by hand: h = relu(2*1 - 0.5) = 1.5, f = 3*1.5 + 0.25 = 4.75, z = -1 + 0.5*4.75
+    one = {"Wa": [[[2.0]]], "ba": [[-0.5]], "Wb": [[[3.0]]], "cb": [[0.25]], "zeta": [[-1.0]], "gamma": [0.5]}
+    gh, _ = orc.gate_eval({k: np.array(v) for k, v in one.items()}, [1], 1)
+    assert abs(gh[0, 0, 0] - 1.0 / (1.0 + math.exp(-1.375))) < 1e-15
+    # monotone in zeta
+    gh_a, _ = orc.gate_eval(gp, bits, Hq)
+    gh_b, _ = orc.gate_eval(dict(gp, zeta=gp["zeta"] + 0.1), bits, Hq)
+    assert np.all(gh_b > gh_a)
+
+
+def test_budget_search_worked_example():
+    """One layer, two heads in one group, three channels; costs head 10, group 4, channel 3, fixed 5.
+    Scores sorted: .9(h0) .8(c1) .7(h1) .6(c0) .2(c2).  Keep sets by threshold:
+      .9 -> h0 + best channel c1 (floor): 5 + 10 + 4 + 3 = 22      .8 -> same set: 22
+      .7 -> h0 h1 c1: 32      .6 -> + c0: 35      .2 -> + c2: 38"""
+    gh = np.array([[0.9, 0.7]], np.float32)
+    gf = np.array([[0.6, 0.8, 0.2]], np.float32)
+    args = (gh, gf, 1, [10], [4], [3], 5)
+    for budget, tau, kh, kf, cost in ((38, 0.2, 2, 3, 38), (100, 0.2, 2, 3, 38), (37, 0.6, 2, 2, 35), (35, 0.6, 2, 2, 35),
+                                      (34, 0.7, 2, 1, 32), (31, 0.8, 1, 1, 22), (22, 0.8, 1, 1, 22)):
+        r = orc.budget_search(*args, budget)
+        assert r["feasible"] and r["tau"] == np.float32(tau), (budget, r)
+        assert (int(r["k_head"][0]), int(r["k_ffn"][0]), r["cost"]) == (kh, kf, cost), (budget, r)
+    r = orc.budget_search(*args, 21)
+    assert not r["feasible"] and np.isinf(r["tau"]) and r["cost"] == 22 and r["k_head"][0] == 1 and r["k_ffn"][0] == 1
+
+
+def test_budget_search_properties():
+    rng = np.random.default_rng(33)
+    nl, Hq, Hk, F = 3, 8, 2, 40
+    gh = rng.random((nl, Hq), dtype=np.float32)
+    gf = rng.random((nl, F), dtype=np.float32)
+    gf[1, :10] = gf[1, 10]                                                   # a run of equal scores
+    ch, cg, cf = rng.integers(50, 100, nl), rng.integers(20, 40, nl), rng.integers(1, 9, nl)
+
+    def cost_of(v):                                                          # vectorised, independent of the C code
+        tot = 7
+        for l in range(nl):
+            kept = gh[l] >= v
+            kh = max(int(kept.sum()), 1)
+            kg = max(int(kept.reshape(Hk, -1).any(axis=1).sum()), 1)
+            kf = max(int((gf[l] >= v).sum()), 1)
+            tot += kh * ch[l] + kg * cg[l] + kf * cf[l]
+        return tot, kh
+
+    dense = cost_of(-1.0)[0]
+    floor = cost_of(2.0)[0]
+    values = np.unique(np.concatenate([gh.ravel(), gf.ravel()]))
+    for budget in (dense, dense - 1, (dense + floor) // 2, floor + 3, floor):
+        r = orc.budget_search(gh, gf, Hk, ch, cg, cf, 7, budget)
+        assert r["feasible"] and r["cost"] == cost_of(r["tau"])[0] <= budget
+        below = values[values < r["tau"]]
+        if len(below):
+            assert cost_of(below[-1])[0] > budget                            # one more distinct value breaks the budget
+        else:
+            assert r["cost"] == dense
+        for l in range(nl):
+            assert r["k_head"][l] == max(int((gh[l] >= r["tau"]).sum()), 1)
+            assert r["k_ffn"][l] == max(int((gf[l] >= r["tau"]).sum()), 1)
+    assert not orc.budget_search(gh, gf, Hk, ch, cg, cf, 7, floor - 1)["feasible"]
+    # equal unit costs, one layer, distinct scores: the threshold keeps the floor((B - fixed) / c) best units
+    g1 = rng.permutation(50).astype(np.float32)[None] / 64
+    r = orc.budget_search(g1[:, :10], g1[:, 10:], 10, [5], [0], [5], 3, 3 + 5 * 23 + 4)
+    assert r["k_head"][0] + r["k_ffn"][0] == 23 and r["tau"] == np.sort(g1.ravel())[::-1][22]
+    # thresholding and top-k agree: the keep counts fed to the mask builder give exactly the units >= tau
+    rb = orc.budget_search(gh, gf, Hk, ch, cg, cf, 7, (dense + floor) // 2)
+    m = orc.gate_scores_to_masks(gh[:, None, :], gf[:, None, :], rb["k_head"], rb["k_ffn"], Hk)
+    tau = rb["tau"]
+    for l in range(nl):
+        if (gh[l] >= tau).any():
+            assert np.array_equal(m["head_mask"][l, 0].astype(bool), gh[l] >= tau)
+        if (gf[l] >= tau).any():
+            assert np.array_equal(m["ffn_mask"][l, 0].astype(bool), gf[l] >= tau)
