@@ -317,6 +317,37 @@ def bench_moe(wl, steps, warmup, E=8, top_k=2):
             "note": "Sparse-MoE FFN block with pruned experts on the same tokens; not part of `value`"}
 
 
+def bench_gate_plan(wl, reps=50):
+    """Plan construction from the gating module: Eq. (1) for all layers and patterns in use, then the global
+    threshold for a budget of 60 % of the dense cost (a stand-in budget; the paper names none for these shapes)."""
+    import numpy as np
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from paper_2604_08971_amd import workloads as W
+    from gpu_utils import to_dev, to_host
+    s = wl.spec
+    nl, P, Hq, Hk, F = s.n_layers, wl.P, s.Hq, s.Hk, s.F
+    desc = sf.make_desc(1, s.L, s.d, Hq, Hk, s.dh, F, nl, P, sf.SF_F32)
+    gp = {k: to_dev(v, "f32") for k, v in W.make_gate_params(nl, s.M, Hq, F, 16, s.seed).items()}
+    bits = to_dev(wl.pattern_bits.astype(np.int32), "f32")
+    U = sf.num_active(sf.make_desc(1, s.L, s.d, Hq, Hk, s.dh, F, c_factor=s.c))
+    ch, cg, cf = W.unit_costs(s, U)
+    dense = sum(Hq * ch[l] + Hk * cg[l] + F * cf[l] for l in range(nl))
+    budget = int(0.6 * dense)
+    res = {}
+
+    def plan():
+        gh, gf = sf.gate_eval(desc, gp, bits)
+        res["out"] = sf.budget_search(desc, gh, gf, P - 1, ch, cg, cf, 0, budget)
+
+    ms, _ = time_steps(plan, reps, 5)
+    o = res["out"]
+    return {"us_per_plan": ms * 1e3, "hidden": 16, "budget_frac_of_dense": 0.6, "tau": float(to_host(o["tau"])[0]),
+            "k_head": to_host(o["k_head"]).tolist(), "k_ffn": to_host(o["k_ffn"]).tolist(),
+            "cost_frac_of_dense": int(to_host(o["cost"])[0]) / dense,
+            "note": "sf_gate_eval + sf_budget_search (plan construction from the gating module); not part of `value`"}
+
+
 def cpu_baseline(wl, flops_total):
     """The CPU oracle, as it stands, on a bounded number of whole samples of the same workload."""
     import numpy as np
@@ -425,6 +456,7 @@ def main():
         out["sparse_gqa"] = bench_sparse_gqa(dm, wl, args.steps)
         out["sampled_score"] = bench_sampled_score(wl, args.steps, args.warmup)
         out["moe_ffn"] = bench_moe(wl, args.steps, args.warmup)
+        out["gate_plan"] = bench_gate_plan(wl)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(wl, flops["total"])

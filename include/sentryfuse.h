@@ -302,6 +302,55 @@ int32_t sf_moe_ffn_forward(const sf_desc *desc, const sf_moe_compact *moe_host, 
                            size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
+ * SentryGate on the device (plan construction; fp32 whatever the model dtype).
+ *
+ * sf_gate_eval - the importance scores of Eq. (1) for every layer and every
+ * presence pattern in use:
+ *   g_i(m) = sigmoid( zeta_i + gamma * f_i(m) ),  f = two-layer perceptron.
+ * The paper gives neither the width nor the nonlinearity of f; here the first
+ * layer is shared by the units of a layer, h = nonlin(Wa m + ba) with `hidden`
+ * units (nonlin: ReLU or tanh), and unit i has its own output row,
+ * f_i = Wb[i,:] . h + cb[i].  The units of a layer are its Hq heads followed
+ * by its F channels (n_units = Hq + F).
+ *   parameters (device pointers in a HOST struct, fp32):
+ *     Wa [nl,hidden,M], ba [nl,hidden] (NULL ok), Wb [nl,n_units,hidden]
+ *     (16-byte aligned), cb [nl,n_units] (NULL ok), zeta [nl,n_units], gamma [nl]
+ *   pattern_bits [P] int32 device: bit j set = modality j present
+ *   g_head [nl,P,Hq], g_ffn [nl,P,F] fp32 out: the layouts
+ *   sf_gate_scores_to_masks takes.
+ *
+ * sf_budget_search - the global threshold of Sec. 4.5 for one platform
+ * pattern and a cost budget (Sec. 4.2: FLOPs or energy).  Keep set of a
+ * threshold v: every head and channel of every layer with score >= v; a layer
+ * keeps at least its best head (with its K/V group) and its best channel.
+ * Cost = c_fixed + sum_l (heads_l*c_head[l] + groups_l*c_group[l] +
+ * channels_l*c_ffn[l]) in the caller's integer units (HOST arrays [nl], >= 0).
+ * Finds the smallest score value whose keep set costs <= budget, i.e. the
+ * largest network within the budget, by bisection over the ordered bit
+ * patterns of the scores (exact, no sort).  Outputs (DEVICE memory):
+ *   tau (that score; +inf when nothing fits), k_head [nl], k_ffn [nl] (sizes
+ *   of the keep set: pass them to sf_gate_scores_to_masks, whose top-k with
+ *   these counts selects exactly the units >= tau), cost, feasible (1 / 0;
+ *   0: even the one-unit-per-layer network exceeds the budget; the outputs
+ *   then describe that network).
+ * Scores must not be NaN.  At most 64 layers and 64 K/V groups.
+ */
+enum { SF_GATE_RELU = 0, SF_GATE_TANH = 1 };
+typedef struct sf_gate_params {
+    int32_t n_modalities;      /* M <= 32 */
+    int32_t hidden;            /* <= 1024 */
+    int32_t nonlin;            /* SF_GATE_RELU | SF_GATE_TANH */
+    int32_t reserved;
+    const void *Wa, *ba, *Wb, *cb, *zeta, *gamma;
+} sf_gate_params;
+int32_t sf_gate_eval(const sf_desc *desc, const sf_gate_params *gate_host, const int32_t *pattern_bits,
+                     float *g_head, float *g_ffn, void *stream);
+int32_t sf_budget_search(const sf_desc *desc, const float *g_head, const float *g_ffn, int32_t pattern,
+                         const int64_t *c_head_host, const int64_t *c_group_host,
+                         const int64_t *c_ffn_host, int64_t c_fixed, int64_t budget, float *tau,
+                         int32_t *k_head, int32_t *k_ffn, int64_t *cost, int32_t *feasible, void *stream);
+
+/* ------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel HIP-event timing.
  * sf_profile_begin(kernel_class, max_launches) creates max_launches event
  * pairs; from then on every launch of that kernel class made by this library

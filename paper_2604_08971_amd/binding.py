@@ -25,7 +25,8 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_compact_heads_channels", "sf_sparse_gqa_workspace_bytes", "sf_sparse_gqa_forward",
            "sf_pruned_ffn_workspace_bytes", "sf_pruned_ffn_forward", "sf_encoder_workspace_bytes",
            "sf_encoder_forward", "sf_profile_begin", "sf_profile_end", "sf_compact_moe_experts",
-           "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward"]
+           "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search"]
+SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
 
@@ -67,6 +68,11 @@ class SfMoeCompact(C.Structure):
                 + [(n, C.c_void_p) for n in ("Wr", "br", "W1", "b1", "W2T", "b2x", "ln_g", "ln_b", "k_ffn")])
 
 
+class SfGateParams(C.Structure):
+    _fields_ = ([("n_modalities", C.c_int32), ("hidden", C.c_int32), ("nonlin", C.c_int32), ("reserved", C.c_int32)]
+                + [(n, C.c_void_p) for n in ("Wa", "ba", "Wb", "cb", "zeta", "gamma")])
+
+
 class SentryFuseError(RuntimeError):
     pass
 
@@ -84,7 +90,8 @@ def lib():
             getattr(L, n).restype = C.c_size_t
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
-                  "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward"):
+                  "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward", "sf_gate_eval",
+                  "sf_budget_search"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -108,6 +115,11 @@ def lib():
         L.sf_moe_ffn_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfMoeCompact), C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sf_gate_eval.argtypes = [C.POINTER(SfDesc), C.POINTER(SfGateParams), C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p]
+        L.sf_budget_search.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]
         L.sf_profile_begin.argtypes = [C.c_int32, C.c_int32]
         L.sf_profile_end.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.sf_num_active.argtypes = [C.POINTER(SfDesc)]
@@ -174,6 +186,45 @@ def profile_end(each: bool = False):
     if each:
         return int(n.value), float(ms.value), [float(buf[i]) for i in range(int(n.value))]
     return int(n.value), float(ms.value)
+
+
+# ------------------------------------------------------- SentryGate: Eq. (1) and the global threshold
+def gate_eval(desc: SfDesc, gate: Dict[str, torch.Tensor], pattern_bits: torch.Tensor, nonlin: int = SF_GATE_RELU):
+    """gate: Wa [nl,Hd,M], ba [nl,Hd] | None, Wb [nl,Hq+F,Hd], cb [nl,Hq+F] | None, zeta [nl,Hq+F], gamma [nl] (fp32,
+    contiguous); pattern_bits [P] int32.  Returns (g_head [nl,P,Hq], g_ffn [nl,P,F]) fp32."""
+    nl, P, Hq, F = desc.n_layers, desc.P, desc.Hq, desc.d_ff
+    Wa, Wb = gate["Wa"], gate["Wb"]
+    Hd, M = Wa.shape[1], Wa.shape[2]
+    for k, shape in (("Wa", (nl, Hd, M)), ("ba", (nl, Hd)), ("Wb", (nl, Hq + F, Hd)), ("cb", (nl, Hq + F)),
+                     ("zeta", (nl, Hq + F)), ("gamma", (nl,))):
+        t = gate.get(k)
+        assert t is None or (t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape), k
+    assert pattern_bits.dtype == torch.int32 and tuple(pattern_bits.shape) == (P,)
+    gp = SfGateParams(M, Hd, nonlin, 0, *[_ptr(gate.get(k)) for k in ("Wa", "ba", "Wb", "cb", "zeta", "gamma")])
+    g_head = torch.empty((nl, P, Hq), dtype=torch.float32, device=Wa.device)
+    g_ffn = torch.empty((nl, P, F), dtype=torch.float32, device=Wa.device)
+    _check(lib().sf_gate_eval(C.byref(desc), C.byref(gp), _ptr(pattern_bits), _ptr(g_head), _ptr(g_ffn), _stream()),
+           "sf_gate_eval")
+    return g_head, g_ffn
+
+
+def budget_search(desc: SfDesc, g_head: torch.Tensor, g_ffn: torch.Tensor, pattern: int, c_head: Sequence[int],
+                  c_group: Sequence[int], c_ffn: Sequence[int], c_fixed: int, budget: int):
+    """Returns device tensors: dict(tau [1] f32, k_head [nl] i32, k_ffn [nl] i32, cost [1] i64, feasible [1] i32)."""
+    nl = desc.n_layers
+    assert g_head.dtype == torch.float32 and g_head.is_contiguous() and tuple(g_head.shape) == (nl, desc.P, desc.Hq)
+    assert g_ffn.dtype == torch.float32 and g_ffn.is_contiguous() and tuple(g_ffn.shape) == (nl, desc.P, desc.d_ff)
+    assert len(c_head) == nl and len(c_group) == nl and len(c_ffn) == nl
+    dev = g_head.device
+    out = {"tau": torch.empty(1, dtype=torch.float32, device=dev), "k_head": torch.empty(nl, dtype=torch.int32, device=dev),
+           "k_ffn": torch.empty(nl, dtype=torch.int32, device=dev), "cost": torch.empty(1, dtype=torch.int64, device=dev),
+           "feasible": torch.empty(1, dtype=torch.int32, device=dev)}
+    ch, cg, cf = ((C.c_int64 * nl)(*[int(v) for v in a]) for a in (c_head, c_group, c_ffn))
+    _check(lib().sf_budget_search(C.byref(desc), _ptr(g_head), _ptr(g_ffn), int(pattern), C.cast(ch, C.c_void_p),
+                                  C.cast(cg, C.c_void_p), C.cast(cf, C.c_void_p), int(c_fixed), int(budget),
+                                  _ptr(out["tau"]), _ptr(out["k_head"]), _ptr(out["k_ffn"]), _ptr(out["cost"]),
+                                  _ptr(out["feasible"]), _stream()), "sf_budget_search")
+    return out
 
 
 # --------------------------------------------------------------------------- a1

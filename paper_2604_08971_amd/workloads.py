@@ -260,3 +260,27 @@ def make_moe_block(wl: Workload, E: int, top_k: int, keep=(0.4, 0.8), seed_offse
     lo, hi = keep
     k_ffn = np.array([keep_count(float(x), F) for x in r.uniform(lo, hi, size=E)], dtype=np.int32)
     return MoeBlock(E, top_k, dense, g_ffn, k_ffn)
+
+
+def make_gate_params(nl: int, M: int, Hq: int, F: int, Hd: int = 16, seed: int = 0, seed_offset: int = 900) -> Dict[str, np.ndarray]:
+    """Seeded parameters of the gating module of Eq. (1), fp32: a first layer shared per layer (Wa [nl,Hd,M],
+    ba [nl,Hd]), one output row per unit (Wb [nl,Hq+F,Hd], cb), base importances zeta ~ N(0,1) and a per-layer
+    scale gamma ~ U(0.5, 2).  Stands in for a trained gate by shape only."""
+    r = _rng(seed, seed_offset)
+    n = Hq + F
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    return {"Wa": f32(r.standard_normal((nl, Hd, M))), "ba": f32(0.3 * r.standard_normal((nl, Hd))),
+            "Wb": f32(r.standard_normal((nl, n, Hd)) / math.sqrt(Hd)), "cb": f32(0.2 * r.standard_normal((nl, n))),
+            "zeta": f32(r.standard_normal((nl, n))), "gamma": f32(r.uniform(0.5, 2.0, nl))}
+
+
+def unit_costs(spec: Spec, U: int):
+    """Integer cost table for the budget search: multiply-adds x 2 per sample of one kept head (Q and output
+    projection, score stream, active rows), one kept K/V group (K and V projection) and one kept FFN channel
+    (both FFN matrices), per layer.  Plain shape arithmetic of the dense operators; not part of the method."""
+    L, d, dh = spec.L, spec.d, spec.dh
+    head = 2 * L * d * dh * 2 + (2 * L * L * dh if 0 < U < L else 0) + 4 * min(U, L) * L * dh
+    group = 2 * L * d * dh * 2
+    ffn = 4 * L * d
+    nl = spec.n_layers
+    return [head] * nl, [group] * nl, [ffn] * nl

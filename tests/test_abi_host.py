@@ -32,6 +32,7 @@ def test_struct_layout_matches_header():
     assert C.sizeof(sf.SfCompactLayer) == 8 + 14 * 8
     assert C.sizeof(sf.SfMoeDense) == 8 * 8
     assert C.sizeof(sf.SfMoeCompact) == 16 + 9 * 8
+    assert C.sizeof(sf.SfGateParams) == 16 + 6 * 8
 
 
 def test_num_active_matches_paper_example():
@@ -98,6 +99,22 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_moe_ffn_forward(C.byref(d), C.byref(m), None, None, 1, 1, None, None, None, None, None, None, 0,
                                 None) == -1
     assert L.sf_compact_moe_experts(C.byref(d), None, None, None, C.byref(m), None) == -1
+    # SentryGate entry points
+    gp = sf.SfGateParams()
+    gp.n_modalities, gp.hidden, gp.nonlin = 3, 16, 0
+    assert L.sf_gate_eval(C.byref(d), C.byref(gp), None, None, None, None) == -1
+    one = C.c_void_p(256)
+    gp.Wa = gp.Wb = gp.zeta = gp.gamma = 256
+    gp.hidden = 5000
+    assert L.sf_gate_eval(C.byref(d), C.byref(gp), one, one, one, None) == -1
+    gp.hidden, gp.nonlin = 16, 7
+    assert L.sf_gate_eval(C.byref(d), C.byref(gp), one, one, one, None) == -3
+    c1 = (C.c_int64 * 1)(5)
+    neg = (C.c_int64 * 1)(-5)
+    cp = lambda a: C.cast(a, C.c_void_p)
+    assert L.sf_budget_search(C.byref(d), one, one, 0, cp(c1), cp(c1), cp(c1), 0, 10, None, one, one, one, one, None) == -1
+    assert L.sf_budget_search(C.byref(d), one, one, 3, cp(c1), cp(c1), cp(c1), 0, 10, one, one, one, one, one, None) == -1
+    assert L.sf_budget_search(C.byref(d), one, one, 0, cp(c1), cp(neg), cp(c1), 0, 10, one, one, one, one, one, None) == -1
     # host-side keep counts out of range
     kh, kf = (C.c_int32 * 1)(9), (C.c_int32 * 1)(3)
     one = C.c_void_p(256)                 # never dereferenced: the count check comes first

@@ -122,6 +122,85 @@ def test_compaction_keep_all_is_identity():
         assert np.array_equal(to_host(cl.WoT[p]), w["Wo"].T)
 
 
+# -------------------------------------------------- SentryGate: Eq. (1) and the global threshold
+def _gate_case(nl, M, Hq, Hk, F, Hd, nonlin, seed):
+    gp = W.make_gate_params(nl, M, Hq, F, Hd, seed)
+    bits = np.arange(1, 2 ** M, dtype=np.int32)                   # every pattern with at least one modality
+    P = len(bits)
+    desc = sf.make_desc(1, 8, 8, Hq, Hk, 8, F, nl, P, sf.SF_F32)
+    gh, gf = sf.gate_eval(desc, {k: to_dev(v, "f32") for k, v in gp.items()}, to_dev(bits, "f32"), nonlin)
+    torch.cuda.synchronize()
+    rh, rf = orc.gate_eval(gp, bits, Hq, nonlin)
+    gh_h, gf_h = to_host(gh), to_host(gf)
+    # fp32 dot products of Hd terms and one expf against fp64; d sigmoid / dz <= 1/4.  The rounding of the
+    # dot product grows with Hd (terms of size ~|h|/sqrt(Hd), gamma <= 2): 1e-6 up to 64 terms, 1e-5 beyond
+    tol = 1e-6 if Hd <= 64 else 1e-5
+    assert np.max(np.abs(gh_h - rh)) <= tol and np.max(np.abs(gf_h - rf)) <= tol
+    return desc, gh, gf, gh_h, gf_h, P
+
+
+@pytest.mark.parametrize("nl,M,Hq,Hk,F,Hd,nonlin", [(2, 3, 4, 2, 48, 16, 0), (1, 2, 12, 4, 3072, 64, 1),
+                                                     (6, 3, 8, 2, 2048, 13, 0), (3, 4, 8, 4, 300, 7, 1),
+                                                     (1, 1, 1, 1, 1, 1, 0), (2, 5, 64, 8, 1000, 1024, 0)])
+def test_gate_eval_parity(nl, M, Hq, Hk, F, Hd, nonlin):
+    _say(f"gate_eval nl={nl} M={M} Hq={Hq} F={F} Hd={Hd} nonlin={nonlin}")
+    _gate_case(nl, M, Hq, Hk, F, Hd, nonlin, seed=nl * 100 + Hd)
+
+
+def _budget_check(desc, gh, gf, gh_h, gf_h, p, Hk, costs, fixed, budget):
+    got = sf.budget_search(desc, gh, gf, p, *costs, fixed, budget)
+    torch.cuda.synchronize()
+    ref = orc.budget_search(gh_h[:, p], gf_h[:, p], Hk, *costs, fixed, budget)      # the same fp32 scores on both sides
+    tau = to_host(got["tau"])[0]
+    assert bool(to_host(got["feasible"])[0]) == ref["feasible"], budget
+    assert (np.isinf(tau) and np.isinf(ref["tau"])) or tau == ref["tau"], (budget, tau, ref["tau"])
+    assert np.array_equal(to_host(got["k_head"]), ref["k_head"]) and np.array_equal(to_host(got["k_ffn"]), ref["k_ffn"])
+    assert int(to_host(got["cost"])[0]) == ref["cost"]
+    return got, ref
+
+
+@pytest.mark.parametrize("nl,M,Hq,Hk,F", [(2, 3, 4, 2, 48), (6, 3, 8, 2, 2048), (4, 2, 32, 8, 4096), (1, 2, 12, 4, 3072)])
+def test_budget_search_parity(nl, M, Hq, Hk, F):
+    _say(f"budget_search nl={nl} Hq={Hq} F={F}")
+    desc, gh, gf, gh_h, gf_h, P = _gate_case(nl, M, Hq, Hk, F, 16, 0, seed=nl + F)
+    rng = np.random.default_rng(F)
+    costs = (rng.integers(1000, 5000, nl).tolist(), rng.integers(500, 2000, nl).tolist(), rng.integers(5, 40, nl).tolist())
+    fixed = 12345
+    dense = fixed + sum(Hq * costs[0][l] + Hk * costs[1][l] + F * costs[2][l] for l in range(nl))
+    floor = fixed + sum(costs[0][l] + costs[1][l] + costs[2][l] for l in range(nl))
+    for p in sorted({0, P // 2, P - 1}):
+        for budget in (dense, dense - 1, int(0.7 * dense), int(0.5 * dense), int(0.2 * dense), floor + 1, floor, floor - 1, 0):
+            got, ref = _budget_check(desc, gh, gf, gh_h, gf_h, p, Hk, costs, fixed, budget)
+        # the counts drive the mask builder: its top-k with these counts is the set of units >= tau
+        got, ref = _budget_check(desc, gh, gf, gh_h, gf_h, p, Hk, costs, fixed, int(0.6 * dense))
+        masks = sf.gate_scores_to_masks(desc, gh, gf, ref["k_head"].tolist(), ref["k_ffn"].tolist())
+        torch.cuda.synchronize()
+        hm, fm = to_host(masks["head_mask"])[:, p].astype(bool), to_host(masks["ffn_mask"])[:, p].astype(bool)
+        for l in range(nl):
+            if (gh_h[l, p] >= ref["tau"]).any():
+                assert np.array_equal(hm[l], gh_h[l, p] >= ref["tau"])
+            if (gf_h[l, p] >= ref["tau"]).any():
+                assert np.array_equal(fm[l], gf_h[l, p] >= ref["tau"])
+
+
+def test_budget_search_ties_and_signs():
+    """Scores given directly (not from Eq. (1)): heavy ties, negatives, both zeros, a tie at the maximum."""
+    nl, Hq, Hk, F, P = 3, 6, 3, 257, 2
+    rng = np.random.default_rng(5)
+    gh_h = (rng.integers(-2, 3, (nl, P, Hq)) / 2).astype(np.float32)
+    gf_h = (rng.integers(-4, 5, (nl, P, F)) / 8).astype(np.float32)
+    gf_h[0, 0, : F // 3] = -0.0
+    gf_h[2, 1, :5] = 7.0                                            # several units share the largest score
+    desc = sf.make_desc(1, 8, 8, Hq, Hk, 8, F, nl, P, sf.SF_F32)
+    gh, gf = to_dev(gh_h, "f32"), to_dev(gf_h, "f32")
+    costs = ([100] * nl, [30] * nl, [7] * nl)
+    dense = sum(Hq * 100 + Hk * 30 + F * 7 for _ in range(nl))
+    floor = nl * (100 + 30 + 7)
+    for p in range(P):
+        for budget in (dense, dense // 2, dense // 3, dense // 10, floor + 4 * 7, floor + 3 * 7, floor, floor - 1):
+            _budget_check(desc, gh, gf, gh_h, gf_h, p, Hk, costs, 0, budget)
+
+
 # -------------------------------------------------- Sparse-MoE FFN with pruned experts (Sec. 4.5)
 EPS_ROUTE = {"f32": 1e-5, "bf16": 2e-2}
 
