@@ -26,6 +26,7 @@
 //    sub-tile through its private 16 KB of the (now free) LDS ring so that
 //    every global store instruction writes 8 rows x 128 contiguous bytes (the
 //    residual is read with the same pattern).
+#include <algorithm>
 #include <type_traits>
 
 #include "gemm.hpp"
@@ -55,9 +56,51 @@ __device__ __forceinline__ int lay(int row, int chunk)
 template <int ACT>
 __device__ __forceinline__ float activate(float z)
 {
-    if (ACT == ACT_RELU) return z > 0.f ? z : 0.f;
+    // integer max on the bit pattern: one instruction, -0 and negatives give +0, no canonicalisation pass
+    if (ACT == ACT_RELU) return __int_as_float(max(__float_as_int(z), 0));
     if (ACT == ACT_GELU) return 0.5f * z * (1.f + erff(z * 0.70710678118654752f));
     return z;
+}
+
+// One output tile of the walk below
+struct Tile { int b, m0, nt0, p, N, nk; };
+
+// The tiles of this workgroup, in order.  The launch has the same number of workgroups on every XCD
+// (workgroup w runs on XCD w % 8); an XCD owns `per_xcd` tile slots: a contiguous range of the tile list
+// (N fastest), or with xcd_rows the tile rows r with r % 8 == XCD.  The workgroups of an XCD take its
+// slots round-robin, so at any time they work on neighbouring tiles (shared W tiles and X rows in that
+// XCD's L2).  Slots past the end, samples with a negative pattern and tiles beyond the pattern's own
+// width are skipped.  Every wave of the workgroup calls this with the same arguments, so loader and MFMA
+// waves see the same sequence.
+__device__ __forceinline__ bool next_tile(const GemmArgs &a, int tiles_m, int tiles_n, int total_tiles, int per_xcd,
+                                          int stride, int &s, Tile &t)
+{
+    const int xcd = blockIdx.x % N_XCD;
+    for (; s < per_xcd; s += stride) {
+        int tn_i, tm_i;
+        if (a.xcd_rows) {
+            tn_i = s % tiles_n;
+            tm_i = (s / tiles_n) * N_XCD + xcd;
+            if (tm_i * tiles_n >= total_tiles) continue;
+        } else {
+            const int w = xcd * per_xcd + s;
+            if (w >= total_tiles) continue;
+            tn_i = w % tiles_n;
+            tm_i = w / tiles_n;
+        }
+        t.b = tm_i / tiles_m;
+        t.m0 = (tm_i % tiles_m) * BM;
+        t.nt0 = tn_i * BN;
+        t.p = a.pattern_id ? a.pattern_id[t.b] : 0;
+        if (t.p < 0) continue;                                     // sample not in use
+        t.N = a.n_lim ? min(a.N, a.n_lim[t.p]) : a.N;
+        if (t.nt0 >= t.N) continue;
+        t.nk = (a.k_lim ? min(a.K, a.k_lim[t.p]) : a.K) / BKT;
+        if (t.nk < 1) continue;
+        s += stride;
+        return true;
+    }
+    return false;
 }
 
 template <int ACT>
@@ -67,109 +110,148 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NXS][X rows][64] | [NWS][W rows][64]
 
-    const int wid = blockIdx.x;
-    int tn_i, tm_i;
-    if (a.xcd_rows) {
-        // tile row r goes to XCD r % 8: rows of unequal cost spread evenly over the XCDs
-        const int s = wid / N_XCD;
-        tn_i = s % tiles_n;
-        tm_i = (s / tiles_n) * N_XCD + wid % N_XCD;
-        if (tm_i * tiles_n >= total_tiles) return;
-    } else {
-        const int w = (wid % N_XCD) * per_xcd + wid / N_XCD;
-        if (w >= total_tiles) return;
-        tn_i = w % tiles_n;
-        tm_i = w / tiles_n;
-    }
-    const int b = tm_i / tiles_m;
-    const int m0 = (tm_i % tiles_m) * BM;
-    const int nt0 = tn_i * BN;
-    const int p = a.pattern_id ? a.pattern_id[b] : 0;
-    if (p < 0) return;                                             // sample not in use
-    if (a.n_lim) a.N = min(a.N, a.n_lim[p]);
-    if (a.k_lim) a.K = min(a.K, a.k_lim[p]);
-    if (nt0 >= a.N) return;
-    const int nk = a.K / BKT;
-
+    const int stride = gridDim.x / N_XCD;                     // workgroups per XCD
+    const int s0 = blockIdx.x / N_XCD;                        // this workgroup's first slot
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     if (wave >= NCW) {
         // ------------------------------------------------------------ loader wave
+        // Three walks over the same tile sequence: the K tiles of X being requested (two steps ahead of
+        // the MFMA waves), those of W (one step ahead) and the step being consumed.  A "step" is one K
+        // tile of one output tile; the ring and the barrier protocol run on across output tiles, so the
+        // first K tiles of the next output tile arrive while the MFMA waves are still in their epilogue.
         const int lw = wave - NCW;
         constexpr int LPW = (BM / 8) / NLW;       // 8 X-instructions and 8 W-instructions per loader wave
-        const char *Ab = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.A) +
-                                                        (a.row_map ? (int64_t)0 : ((int64_t)b * a.L + m0) * a.lda));
-        const int32_t *rmap = a.row_map ? a.row_map + (int64_t)b * a.L + m0 : nullptr;
-        const char *Wb = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.W) + (int64_t)p * a.w_pstride +
-                                                        (int64_t)(a.n0 + nt0) * a.ldw);
-        const int rows_x = min(BM, a.L - m0), rows_w = min(BN, a.N - nt0);
+        int sx = s0, sw = s0, sc = s0;
+        Tile tx, tw, tc;
+        bool vx, vw;
+        const char *xbase = nullptr, *wbase = nullptr;
         uint32_t xoff[LPW], woff[LPW];
+        int ktx = 0, ktw = 0, xs = 0, wsl = 0;
+        auto open_x = [&]() {
+            vx = next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sx, tx);
+            ktx = 0;
+            if (!vx) return;
+            xbase = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.A) +
+                                                   (a.row_map ? (int64_t)0 : ((int64_t)tx.b * a.L + tx.m0) * a.lda));
+            const int32_t *rmap = a.row_map ? a.row_map + (int64_t)tx.b * a.L + tx.m0 : nullptr;
+            const int rows_x = min(BM, a.L - tx.m0);
 #pragma unroll
-        for (int j = 0; j < LPW; ++j) {
-            const int sr = (lw * LPW + j) * 4 + (lane >> 4);      // super-row of this lane's 16-byte slot
-            const int t = (lane & 15) ^ (sr & 7);
-            const int r = sr * 2 + (t >> 3), c = t & 7;
-            const int rx = min(r, rows_x - 1);
-            xoff[j] = ((uint32_t)(rmap ? rmap[rx] : rx) * (uint32_t)a.lda + (uint32_t)(c * 8)) * 2u;
-            woff[j] = (uint32_t)(min(r, rows_w - 1) * (int)a.ldw + c * 8) * 2u;
-        }
-        auto issue_x = [&](int tile) {
-            __bf16 *base = smem + (tile % NXS) * XSLOT;
-            const int64_t koff = (int64_t)tile * BKT * 2;
+            for (int j = 0; j < LPW; ++j) {
+                const int sr = (lw * LPW + j) * 4 + (lane >> 4);      // super-row of this lane's 16-byte slot
+                const int t = (lane & 15) ^ (sr & 7);
+                const int r = sr * 2 + (t >> 3), c = t & 7;
+                const int rx = min(r, rows_x - 1);
+                xoff[j] = ((uint32_t)(rmap ? rmap[rx] : rx) * (uint32_t)a.lda + (uint32_t)(c * 8)) * 2u;
+            }
+        };
+        auto open_w = [&]() {
+            vw = next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sw, tw);
+            ktw = 0;
+            if (!vw) return;
+            wbase = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.W) + (int64_t)tw.p * a.w_pstride +
+                                                   (int64_t)(a.n0 + tw.nt0) * a.ldw);
+            const int rows_w = min(BN, tw.N - tw.nt0);
+#pragma unroll
+            for (int j = 0; j < LPW; ++j) {
+                const int sr = (lw * LPW + j) * 4 + (lane >> 4);
+                const int t = (lane & 15) ^ (sr & 7);
+                const int r = sr * 2 + (t >> 3), c = t & 7;
+                woff[j] = (uint32_t)(min(r, rows_w - 1) * (int)a.ldw + c * 8) * 2u;
+            }
+        };
+        auto issue_x = [&]() {
+            __bf16 *base = smem + xs * XSLOT;
+            const int64_t koff = (int64_t)ktx * BKT * 2;
 #pragma unroll
             for (int j = 0; j < LPW; ++j)
-                __builtin_amdgcn_global_load_lds((glb_void *)(Ab + koff + xoff[j]),
+                __builtin_amdgcn_global_load_lds((glb_void *)(xbase + koff + xoff[j]),
                                                  (lds_void *)(base + (lw * LPW + j) * 512), 16, 0, 0);
+            xs = xs + 1 == NXS ? 0 : xs + 1;
+            if (++ktx == tx.nk) open_x();
         };
-        auto issue_w = [&](int tile) {
-            __bf16 *base = smem + NXS * XSLOT + (tile % NWS) * WSLOT;
-            const int64_t koff = (int64_t)tile * BKT * 2;
+        auto issue_w = [&]() {
+            __bf16 *base = smem + NXS * XSLOT + wsl * WSLOT;
+            const int64_t koff = (int64_t)ktw * BKT * 2;
 #pragma unroll
             for (int j = 0; j < LPW; ++j)
-                __builtin_amdgcn_global_load_lds((glb_void *)(Wb + koff + woff[j]),
+                __builtin_amdgcn_global_load_lds((glb_void *)(wbase + koff + woff[j]),
                                                  (lds_void *)(base + (lw * LPW + j) * 512), 16, 0, 0);
+            wsl = wsl + 1 == NWS ? 0 : wsl + 1;
+            if (++ktw == tw.nk) open_w();
         };
+        open_x();
+        open_w();
         // Loads complete in issue order.  Order kept: X(0) W(0) X(1) | W(1) X(2) | W(2) X(3) | ...
-        // so at barrier kt only the LPW loads of X(kt+1) may still be in flight.
-        issue_x(0);
-        issue_w(0);
-        if (nk > 1) issue_x(1);
-        for (int kt = 0; kt < nk; ++kt) {
-            if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");   // X(kt), W(kt) landed
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            // bare barrier: __syncthreads() carries a fence that would wait for the loads still in flight
-            __builtin_amdgcn_s_barrier();     // barrier kt: tile kt visible; slots of X(kt-1), W(kt-1) free
+        // so at barrier g only the LPW loads of X(g+1) may still be in flight.
+        bool x_ahead = false;
+        if (vx) issue_x();
+        if (vw) issue_w();
+        if (vx) { issue_x(); x_ahead = true; }
+        while (next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sc, tc)) {
+            for (int kt = 0; kt < tc.nk; ++kt) {
+                if (x_ahead) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");   // X(g), W(g) landed
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                // bare barrier: __syncthreads() carries a fence that would wait for the loads still in flight
+                __builtin_amdgcn_s_barrier();     // barrier g: step g visible; slots of X(g-1), W(g-1) free
+                asm volatile("" ::: "memory");
+                if (vw) issue_w();
+                x_ahead = vx;
+                if (vx) issue_x();
+            }
+            __builtin_amdgcn_s_barrier();         // matches the barrier before the epilogue
             asm volatile("" ::: "memory");
-            if (kt + 1 < nk) issue_w(kt + 1);
-            if (kt + 2 < nk) issue_x(kt + 2);
         }
-        __syncthreads();                                          // matches the barrier before the epilogue
         return;
     }
 
     // ---------------------------------------------------------------- MFMA wave
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int l32 = lane & 31, lhi = lane >> 5;
-    f32x16 acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
     // Byte address in LDS of this lane's fragment (k-step 0, MFMA tile 0) inside an X / W slot.  In the
     // layout of lay(), MFMA tile t adds t * 4096 bytes and k-step s flips bits 5..6 (XOR with s << 5).
     const uint32_t xlane = (uint32_t)lay(wm * TM * 32 + l32, lhi) * 2u;
     const uint32_t wlane = (uint32_t)(NXS * XSLOT) * 2u + (uint32_t)lay(wn * TN * 32 + l32, lhi) * 2u;
     static_assert(TN == 2 && TM == 4 && BKT == 64, "the interleaving below is written for 2 x 4 MFMA tiles per wave");
-    uint32_t xslot = 0, wslot = 0;          // byte offsets of the ring slots of tile kt
-    for (int kt = 0; kt < nk; ++kt) {
+    uint32_t xslot = 0, wslot = 0;          // byte offsets of the ring slots of the next step
+    int sm = s0;
+    Tile tl;
+    while (next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sm, tl)) {
+    // The accumulators start at the bias (fp32), so the epilogue has no bias pass.  Entry q*4+e of lane
+    // (l32, lhi) of MFMA tile (tn, tm) is feature tn*32 + q*8 + lhi*4 + e.  The lane number goes through an
+    // opaque copy so that these per-tile values are not hoisted out of the tile loop into long-lived registers.
+    f32x16 acc[TN][TM];
+    {
+        int lb = lane;
+        asm volatile("" : "+v"(lb));
+        const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)tl.p * a.bias_pstride + a.n0 : nullptr;
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4 bv = {};
+                if (bias) {
+                    const int n = min(tl.nt0 + wn * 64 + i * 32 + q * 8 + (lb >> 5) * 4, tl.N - 4);   // clamped: never stored
+                    bv = *reinterpret_cast<const bf16x4 *>(bias + n);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float f = (float)bv[e];
+#pragma unroll
+                    for (int j = 0; j < TM; ++j) acc[i][j][q * 4 + e] = f;
+                }
+            }
+    }
+    uint32_t xdone = 0, wdone = 0;          // slots of the step consumed last: free during the epilogue
+    int kt = 0;
+    do {                                    // next_tile() hands out tiles with nk >= 1 only
         // bare barrier: no global memory traffic of this wave needs ordering here
-        __builtin_amdgcn_s_barrier();                             // barrier kt
+        __builtin_amdgcn_s_barrier();                             // barrier of this step
         asm volatile("" ::: "memory");
         const uint32_t xb = xlane + xslot, wb = wlane + wslot;
+        xdone = xslot;
+        wdone = wslot;
         xslot = (xslot + XSLOT * 2 == NXS * XSLOT * 2) ? 0u : xslot + XSLOT * 2;
         wslot = (wslot + WSLOT * 2 == NWS * WSLOT * 2) ? 0u : wslot + WSLOT * 2;
         // Fragment registers are scarce next to 128 accumulators: the W fragments are double-buffered,
@@ -199,146 +281,155 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                 __builtin_amdgcn_sched_barrier(0);      // keep exactly this order: MFMA MFMA read(s)
             }
         }
-    }
-    __syncthreads();          // every MFMA wave is done reading the ring: its LDS can be reused
+    } while (++kt < tl.nk);
+    // Every MFMA wave is done reading the step consumed last (its fragments went into MFMAs that have
+    // issued): the two slots of that step are free until the loaders are let past the next step's
+    // barrier, and hold the staging areas of the epilogue; the other slots already hold the next tile.
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 
     // ------------------------------------------------------------------ epilogue
     // Accumulator entry q*4+e of lane (l32, lhi) of tile (tn, tm): token tm*32 + l32, feature
     // tn*32 + q*8 + lhi*4 + e.  v_permlane32_swap pairs lane l with l+32 so that lanes < 32 own
     // features [q0*8, q0*8+8) and lanes >= 32 own [q1*8, q1*8+8), (q0, q1) = (0,1), (2,3).
-    const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)p * a.bias_pstride + a.n0 : nullptr;
-    char *stg = smem_raw + wave * 16384;                           // this wave's private staging area
-    const int ncol0 = nt0 + wn * 64;                               // first feature of the wave's sub-tile
-    const int mrow0 = m0 + wm * 128;                               // first token of the wave's sub-tile
-    const int64_t grow0 = (int64_t)b * a.L;
+    // The lane-dependent indices are recomputed per tile from an opaque copy of the lane number: hoisted
+    // out of the tile loop they would have to live across the K loop, i.e. in scratch.  The epilogue is
+    // bound by its instruction count (two MFMA waves share a SIMD), so addresses advance by uniform strides.
+    int le = lane;
+    asm volatile("" : "+v"(le));
+    const int l32e = le & 31, lhie = le >> 5, er = le >> 3, ec = le & 7;
+    const int Np = tl.N;
+    // this wave's private 8 KB staging area: 64 rows of 128 bytes
+    char *stg = smem_raw + (wave < 4 ? xdone + (uint32_t)wave * 8192u
+                                     : (uint32_t)(NXS * XSLOT) * 2u + wdone + (uint32_t)(wave - 4) * 8192u);
+    const int ncol0 = tl.nt0 + wn * 64;                            // first feature of the wave's sub-tile
+    const int mrow0 = tl.m0 + wm * 128;                            // first token of the wave's sub-tile
+    const int64_t grow0 = (int64_t)tl.b * a.L;
+    const int rows_left = a.L - mrow0 - er;                        // row r of the sub-tile (r = er mod 8) exists iff r - er < rows_left
 
     if (!a.c_f32 && !a.R) {
-        // bf16 output, no residual: stage the whole 128 x 64 sub-tile as bf16 rows of 128 bytes
+        // bf16 output, no residual: stage 64 x 64 of the 128 x 64 sub-tile at a time as bf16 rows of 128 bytes
+        __bf16 *cp = static_cast<__bf16 *>(a.C) + (grow0 + mrow0 + er) * a.ldc + a.c0 + ncol0 + ec * 8;
+        const bool col_ok = ncol0 + ec * 8 < Np;
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
+            for (int th = 0; th < 2; ++th)
 #pragma unroll
-                for (int qp = 0; qp < 2; ++qp) {
-                    float v[8];
+                for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[tn][tm][(2 * qp) * 4 + e]),
-                                                                        __float_as_uint(acc[tn][tm][(2 * qp + 1) * 4 + e]),
-                                                                        false, false);
-                        v[e] = __uint_as_float(r[0]);
-                        v[4 + e] = __uint_as_float(r[1]);
+                    for (int qp = 0; qp < 2; ++qp) {
+                        const int tm = half * 2 + th;
+                        float v[8];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[tn][tm][(2 * qp) * 4 + e]),
+                                                                            __float_as_uint(acc[tn][tm][(2 * qp + 1) * 4 + e]),
+                                                                            false, false);
+                            v[e] = __uint_as_float(r[0]);
+                            v[4 + e] = __uint_as_float(r[1]);
+                        }
+                        const int c = tn * 4 + qp * 2 + lhie;               // 16-byte chunk = 8 features
+                        bf16x8 o;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = (__bf16)activate<ACT>(v[e]);
+                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(stg) + lay(th * 32 + l32e, c)) = o;
                     }
-                    const int c = tn * 4 + qp * 2 + lhi;               // 16-byte chunk = 8 features
-                    if (bias) {
-                        const int n = min(ncol0 + c * 8, a.N - 8);     // clamped: out-of-range chunks are not stored
-                        const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(bias + n);
+            // rows out: 8 lanes x 16 bytes = one 128-byte row, 8 rows per instruction
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] += (float)bv[e];
-                    }
-                    bf16x8 o;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] = (__bf16)activate<ACT>(v[e]);
-                    *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(stg) + lay(tm * 32 + l32, c)) = o;
-                }
-        // rows out: 8 lanes x 16 bytes = one 128-byte row, 8 rows per instruction
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int r = j * 8 + (lane >> 3), c = lane & 7;
-            const bf16x8 o = *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const __bf16 *>(stg) + lay(r, c));
-            const int i = mrow0 + r, n = ncol0 + c * 8;
-            if (i < a.L && n < a.N)
-                // streamed out: the output is far larger than L2 and must not push the weights out of it
-                __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(static_cast<__bf16 *>(a.C) + (grow0 + i) * a.ldc + a.c0 + n));
+            for (int j = 0; j < 8; ++j) {
+                const int r = half * 64 + j * 8;                            // uniform
+                const bf16x8 o = *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const __bf16 *>(stg) + lay(j * 8 + er, ec));
+                if (col_ok && r < rows_left)
+                    // streamed out: the output is far larger than L2 and must not push the weights out of it
+                    __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(cp + (int64_t)r * a.ldc));
+            }
         }
     } else {
-        // residual and/or fp32 output: stage fp32, 32 features (128 bytes per row) at a time
+        // residual and/or fp32 output: stage fp32, 64 tokens x 32 features (128 bytes per row) at a time
         float *stf = reinterpret_cast<float *>(stg);
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int qp = 0; qp < 2; ++qp) {
-                    float v[8];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[tn][tm][(2 * qp) * 4 + e]),
-                                                                        __float_as_uint(acc[tn][tm][(2 * qp + 1) * 4 + e]),
-                                                                        false, false);
-                        v[e] = __uint_as_float(r[0]);
-                        v[4 + e] = __uint_as_float(r[1]);
-                    }
-                    const int f0 = (qp * 2 + lhi) * 8;                 // first of this lane's 8 features within the 32
-                    if (bias) {
-                        const int n = min(ncol0 + tn * 32 + f0, a.N - 8);
-                        const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(bias + n);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] += (float)bv[e];
-                    }
-                    f32x4 o0, o1;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { o0[e] = activate<ACT>(v[e]); o1[e] = activate<ACT>(v[4 + e]); }
-                    // a 16-byte chunk holds 4 floats: this lane fills chunks f0/4 and f0/4 + 1
-                    *reinterpret_cast<f32x4 *>(stf + lay(tm * 32 + l32, f0 / 4) / 2) = o0;
-                    *reinterpret_cast<f32x4 *>(stf + lay(tm * 32 + l32, f0 / 4 + 1) / 2) = o1;
-                }
-            // rows out: 8 lanes x 16 bytes = 128 bytes of one row, 8 rows per instruction.  The residual
-            // reads of the whole pass are issued first (the accumulators just staged have freed the
-            // registers), so their latency is paid once per pass and not once per row group.
-            const int er = lane >> 3, ec = lane & 7;
             const int n = ncol0 + tn * 32 + ec * 4;
-            auto finish = [&](int j, f32x4 v) {
-                const int i = mrow0 + j * 8 + er;
-                if (i < a.L && n < a.N) {
-                    const int64_t co = (grow0 + i) * a.ldc + a.c0 + n;
-                    if (a.c_f32) {
-                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co));
-                    } else {
-                        bf16x4 o;
+            const bool col_ok = n < Np;
+            const int64_t co0 = (grow0 + mrow0 + er) * a.ldc + a.c0 + n;      // output element of row er
+            const int64_t ro0 = (grow0 + min(mrow0 + er, a.L - 1)) * a.ldr + a.r0 + min(n, Np - 4);   // clamped: never stored when out of range
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
-                        __builtin_nontemporal_store(o, reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co));
+            for (int half = 0; half < 2; ++half) {
+#pragma unroll
+                for (int th = 0; th < 2; ++th)
+#pragma unroll
+                    for (int qp = 0; qp < 2; ++qp) {
+                        const int tm = half * 2 + th;
+                        float v[8];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[tn][tm][(2 * qp) * 4 + e]),
+                                                                            __float_as_uint(acc[tn][tm][(2 * qp + 1) * 4 + e]),
+                                                                            false, false);
+                            v[e] = __uint_as_float(r[0]);
+                            v[4 + e] = __uint_as_float(r[1]);
+                        }
+                        const int f0 = (qp * 2 + lhie) * 8;                // first of this lane's 8 features within the 32
+                        f32x4 o0, o1;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { o0[e] = activate<ACT>(v[e]); o1[e] = activate<ACT>(v[4 + e]); }
+                        // a 16-byte chunk holds 4 floats: this lane fills chunks f0/4 and f0/4 + 1
+                        *reinterpret_cast<f32x4 *>(stf + lay(th * 32 + l32e, f0 / 4) / 2) = o0;
+                        *reinterpret_cast<f32x4 *>(stf + lay(th * 32 + l32e, f0 / 4 + 1) / 2) = o1;
                     }
+                // rows out: 8 lanes x 16 bytes = 128 bytes of one row, 8 rows per instruction.  The residual
+                // reads of the whole pass are issued first, so their latency is paid once per pass and not
+                // once per row group.
+                auto finish = [&](int j, f32x4 v) {
+                    const int r = half * 64 + j * 8;                        // uniform
+                    if (col_ok && r < rows_left) {
+                        const int64_t co = co0 + (int64_t)r * a.ldc;
+                        if (a.c_f32) {
+                            __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co));
+                        } else {
+                            bf16x4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
+                            __builtin_nontemporal_store(o, reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co));
+                        }
+                    }
+                };
+                // rows beyond the sample read the clamped row again (never stored)
+                auto rrow = [&](int j) { return ro0 + (int64_t)min(half * 64 + j * 8, max(rows_left - 1, 0)) * a.ldr; };
+                if (a.R && a.r_f32) {
+                    f32x4 rr[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        rr[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(a.R) + rrow(j)));
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += rr[j][e];
+                        finish(j, v);
+                    }
+                } else if (a.R) {
+                    bf16x4 rr[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        rr[j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + rrow(j)));
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += (float)rr[j][e];
+                        finish(j, v);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        finish(j, *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2));
                 }
-            };
-            if (a.R && a.r_f32) {
-                f32x4 rr[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int i = min(mrow0 + j * 8 + er, a.L - 1);          // clamped: never stored when out of range
-                    const int64_t ro = (grow0 + i) * a.ldr + a.r0 + min(n, a.N - 4);
-                    rr[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(a.R) + ro));
-                }
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += rr[j][e];
-                    finish(j, v);
-                }
-            } else if (a.R) {
-                bf16x4 rr[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int i = min(mrow0 + j * 8 + er, a.L - 1);
-                    const int64_t ro = (grow0 + i) * a.ldr + a.r0 + min(n, a.N - 4);
-                    rr[j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + ro));
-                }
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += (float)rr[j][e];
-                    finish(j, v);
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    finish(j, *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2));
             }
         }
     }
+    }   // tile loop
 }
 
 }  // namespace
@@ -358,8 +449,18 @@ static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
     const int tiles_m = ceil_div(a.L, BM), tiles_n = ceil_div(a.N, BN);
     const int total = a.B * tiles_m * tiles_n;
     const int per_xcd = a.xcd_rows ? ceil_div(a.B * tiles_m, N_XCD) * tiles_n : ceil_div(total, N_XCD);
+    // persistent: one workgroup per compute unit (160 KB of LDS each), the same number on every XCD
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < N_XCD)
+            n = 256;
+        cus = n;
+    }
+    const int wg_per_xcd = std::min(cus / N_XCD, per_xcd);
     ProfScope prof(SF_KERNEL_GEMM, st);
-    hipLaunchKernelGGL(kern, dim3(per_xcd * N_XCD), dim3(64 * (NCW + NLW)), lds, st, a, tiles_m, tiles_n, total, per_xcd);
+    hipLaunchKernelGGL(kern, dim3(wg_per_xcd * N_XCD), dim3(64 * (NCW + NLW)), lds, st, a, tiles_m, tiles_n, total, per_xcd);
     return SF_OK;
 }
 
