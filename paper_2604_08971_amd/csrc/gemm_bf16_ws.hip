@@ -308,9 +308,14 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     const int rows_left = a.L - mrow0 - er;                        // row r of the sub-tile (r = er mod 8) exists iff r - er < rows_left
 
     if (!a.c_f32 && !a.R) {
-        // bf16 output, no residual: stage 64 x 64 of the 128 x 64 sub-tile at a time as bf16 rows of 128 bytes
+        // bf16 output, no residual: stage 64 x 64 of the 128 x 64 sub-tile at a time as bf16 rows of 128 bytes.
+        // A lane owns 4 consecutive features per (tile, q): they go to LDS as one 8-byte write, with no lane
+        // exchange.  In lay() the chunk index only flips bits 4..6 of the byte address, so one base address
+        // per lane serves all chunks (XOR) and both 32-row halves (+4096 bytes).
         __bf16 *cp = static_cast<__bf16 *>(a.C) + (grow0 + mrow0 + er) * a.ldc + a.c0 + ncol0 + ec * 8;
         const bool col_ok = ncol0 + ec * 8 < Np;
+        const uint32_t wbase = (uint32_t)lay(l32e, 0) * 2u + (uint32_t)lhie * 8u;
+        typedef short i16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -318,22 +323,26 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                    for (int qp = 0; qp < 2; ++qp) {
+                    for (int q = 0; q < 4; ++q) {
                         const int tm = half * 2 + th;
-                        float v[8];
+                        // round first, then (ReLU) clamp the packed values with 16-bit integer maxima: the
+                        // sign of a bf16 is its top bit and rounding never changes the sign
+                        float vf[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[tn][tm][(2 * qp) * 4 + e]),
-                                                                            __float_as_uint(acc[tn][tm][(2 * qp + 1) * 4 + e]),
-                                                                            false, false);
-                            v[e] = __uint_as_float(r[0]);
-                            v[4 + e] = __uint_as_float(r[1]);
+                        for (int e = 0; e < 4; ++e)
+                            vf[e] = ACT == ACT_RELU ? acc[tn][tm][q * 4 + e] : activate<ACT>(acc[tn][tm][q * 4 + e]);
+                        // one packed conversion per pair (written out: the compiler converts the elements of
+                        // an accumulator tuple one by one and merges them with a byte permute)
+                        uint2 pw;
+                        asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pw.x) : "v"(vf[0]), "v"(vf[1]));
+                        asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pw.y) : "v"(vf[2]), "v"(vf[3]));
+                        i16x4 m = __builtin_bit_cast(i16x4, pw);
+                        if (ACT == ACT_RELU) {
+                            const i16x4 z = {0, 0, 0, 0};
+                            m = __builtin_elementwise_max(m, z);
                         }
-                        const int c = tn * 4 + qp * 2 + lhie;               // 16-byte chunk = 8 features
-                        bf16x8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = (__bf16)activate<ACT>(v[e]);
-                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(stg) + lay(th * 32 + l32e, c)) = o;
+                        const uint2 o = __builtin_bit_cast(uint2, m);
+                        *reinterpret_cast<uint2 *>(stg + ((wbase ^ ((uint32_t)(tn * 4 + q) << 4)) + (uint32_t)th * 4096u)) = o;
                     }
             // rows out: 8 lanes x 16 bytes = one 128-byte row, 8 rows per instruction
 #pragma unroll
