@@ -368,6 +368,8 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     } else {
         // residual and/or fp32 output: stage fp32, 64 tokens x 32 features (128 bytes per row) at a time
         float *stf = reinterpret_cast<float *>(stg);
+        // byte address of chunk lhi of row l32 in the staging tile; chunk c flips address bits 4..6 (see lay())
+        const uint32_t wbase32 = (uint32_t)lay(l32e, lhie) * 2u;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const int n = ncol0 + tn * 32 + ec * 4;
@@ -379,24 +381,14 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
 #pragma unroll
                 for (int th = 0; th < 2; ++th)
 #pragma unroll
-                    for (int qp = 0; qp < 2; ++qp) {
+                    for (int q = 0; q < 4; ++q) {
+                        // the lane's 4 consecutive features of (tile, q) are one 16-byte chunk of the fp32 row:
+                        // chunk q*2 + lhi, written as it is (no lane exchange)
                         const int tm = half * 2 + th;
-                        float v[8];
+                        f32x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[tn][tm][(2 * qp) * 4 + e]),
-                                                                            __float_as_uint(acc[tn][tm][(2 * qp + 1) * 4 + e]),
-                                                                            false, false);
-                            v[e] = __uint_as_float(r[0]);
-                            v[4 + e] = __uint_as_float(r[1]);
-                        }
-                        const int f0 = (qp * 2 + lhie) * 8;                // first of this lane's 8 features within the 32
-                        f32x4 o0, o1;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) { o0[e] = activate<ACT>(v[e]); o1[e] = activate<ACT>(v[4 + e]); }
-                        // a 16-byte chunk holds 4 floats: this lane fills chunks f0/4 and f0/4 + 1
-                        *reinterpret_cast<f32x4 *>(stf + lay(th * 32 + l32e, f0 / 4) / 2) = o0;
-                        *reinterpret_cast<f32x4 *>(stf + lay(th * 32 + l32e, f0 / 4 + 1) / 2) = o1;
+                        for (int e = 0; e < 4; ++e) o[e] = activate<ACT>(acc[tn][tm][q * 4 + e]);
+                        *reinterpret_cast<f32x4 *>(stg + ((wbase32 ^ ((uint32_t)(q * 2) << 4)) + (uint32_t)th * 4096u)) = o;
                     }
                 // rows out: 8 lanes x 16 bytes = 128 bytes of one row, 8 rows per instruction.  The residual
                 // reads of the whole pass are issued first, so their latency is paid once per pass and not
