@@ -52,6 +52,8 @@ def lib():
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_max_threads.restype = C.c_int32
+        _lib.orc_fp8_e4m3_decode.restype = C.c_double
+        _lib.orc_fp8_e4m3_decode.argtypes = [C.c_uint8]
         for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_moe_ffn",
                   "orc_gate_eval", "orc_budget_search"):
             getattr(_lib, f).restype = C.c_int32
@@ -267,6 +269,18 @@ def budget_search(g_head, g_ffn, Hk: int, c_head, c_group, c_ffn, c_fixed: int, 
     if rc < 0:
         raise ValueError("orc_budget_search: bad arguments")
     return {"feasible": bool(rc), "tau": np.float32(tau.value), "k_head": k_head, "k_ffn": k_ffn, "cost": int(cost.value)}
+
+
+def fp8_e4m3_decode(b: int) -> float:
+    return float(lib().orc_fp8_e4m3_decode(C.c_uint8(int(b))))
+
+
+def dequant_fp8(q, scale: float, bf16: bool) -> np.ndarray:
+    """q uint8 (OCP E4M3 codes) -> decode(q) * scale rounded to the model dtype, as fp64."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    out = np.empty(q.shape, np.float64)
+    lib().orc_dequant_fp8(_p(q), C.c_int64(q.size), C.c_float(float(scale)), C.c_int32(int(bf16)), _p(out))
+    return out
 
 
 def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,

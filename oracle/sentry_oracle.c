@@ -99,6 +99,25 @@ int32_t orc_budget_search(int32_t nl, int32_t Hq, int32_t Hk, int32_t F, const f
     return found;
 }
 
+/* ---- FP8 (OCP E4M3) weights ---------------------------------------------- */
+double orc_fp8_e4m3_decode(uint8_t byte)
+{
+    const int sign = byte >> 7, e = (byte >> 3) & 15, m = byte & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;                       /* the only non-finite code */
+    if (e == 0) v = ldexp((double)m, -9);                    /* subnormal: (m/8) * 2^-6 */
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+void orc_dequant_fp8(const uint8_t *q, int64_t n, float scale, int32_t bf16, double *out)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const double w = orc_fp8_e4m3_decode(q[i]) * (double)scale;      /* exact */
+        out[i] = bf16 ? orc_round_bf16(w) : (double)(float)w;
+    }
+}
+
 int32_t orc_max_threads(void)
 {
 #ifdef _OPENMP

@@ -224,6 +224,19 @@ int32_t orc_budget_search(int32_t nl, int32_t Hq, int32_t Hk, int32_t F, const f
                           const int64_t *c_ffn, int64_t c_fixed, int64_t budget, float *tau,
                           int32_t *k_head, int32_t *k_ffn, int64_t *cost);
 
+/*
+ * FP8 post-training quantisation of the weights (Sec. 6, "Compatibility with quantization": FP8 PTQ on top of the
+ * pruned model; the paper names neither the format nor the scaling).  Reading: weights are stored as OCP E4M3
+ * bytes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, S.1111.111 is NaN, largest finite
+ * value 448, subnormals m * 2^-9) with one fp32 scale per weight matrix; the pruned forward runs on the
+ * dequantised weight w = decode(byte) * scale, rounded to the model dtype (bf16, ties to even, when bf16 != 0;
+ * fp32 otherwise).  The product of a 4-bit and a 24-bit significand is exact in double, so there is one rounding.
+ *   orc_fp8_e4m3_decode: the value of one byte.
+ *   orc_dequant_fp8: out[i] = round(decode(q[i]) * scale), n elements.
+ */
+double orc_fp8_e4m3_decode(uint8_t byte);
+void orc_dequant_fp8(const uint8_t *q, int64_t n, float scale, int32_t bf16, double *out);
+
 int32_t orc_max_threads(void);
 
 #ifdef __cplusplus

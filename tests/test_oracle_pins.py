@@ -790,3 +790,39 @@ def test_budget_search_properties():
             assert np.array_equal(m["head_mask"][l, 0].astype(bool), gh[l] >= tau)
         if (gf[l] >= tau).any():
             assert np.array_equal(m["ffn_mask"][l, 0].astype(bool), gf[l] >= tau)
+
+
+# ------------------------------------------------ FP8 (OCP E4M3) weight storage
+def test_fp8_e4m3_decode_against_library_type():
+    """All 256 codes against PyTorch's float8_e4m3fn (a library implementation of the same OCP format)."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    lib_vals = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    ours = np.array([orc.fp8_e4m3_decode(int(c)) for c in codes])
+    assert np.array_equal(np.isnan(ours), np.isnan(lib_vals)) and int(np.isnan(ours).sum()) == 2
+    ok = ~np.isnan(ours)
+    assert np.array_equal(ours[ok], lib_vals[ok])
+    # landmarks of the format: largest finite 448, smallest subnormal 2^-9, smallest normal 2^-6, both zeros
+    assert orc.fp8_e4m3_decode(0x7E) == 448.0 and orc.fp8_e4m3_decode(0xFE) == -448.0
+    assert orc.fp8_e4m3_decode(0x01) == 2.0 ** -9 and orc.fp8_e4m3_decode(0x08) == 2.0 ** -6
+    assert orc.fp8_e4m3_decode(0x00) == 0.0 and orc.fp8_e4m3_decode(0x80) == 0.0
+    assert math.copysign(1.0, orc.fp8_e4m3_decode(0x80)) == -1.0
+    assert orc.fp8_e4m3_decode(0x38) == 1.0 and orc.fp8_e4m3_decode(0x3C) == 1.5
+
+
+def test_fp8_dequant_rounding():
+    import torch
+    rng = np.random.default_rng(41)
+    q = rng.integers(0, 256, 4096).astype(np.uint8)
+    q = q[(q & 0x7F) != 0x7F]
+    scale = np.float32(0.0123456)
+    vals = torch.from_numpy(q).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    exact = vals * np.float64(scale)                        # exact: 4-bit x 24-bit significands
+    w32 = orc.dequant_fp8(q, scale, bf16=False)
+    assert np.array_equal(w32, exact.astype(np.float32).astype(np.float64))
+    w16 = orc.dequant_fp8(q, scale, bf16=True)
+    # one rounding from the exact product: equal to the library's fp64 -> bf16 conversion (ties to even)
+    lib16 = torch.from_numpy(exact).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(w16, lib16)
+    # scale = 1: every code is a bf16 number already
+    assert np.array_equal(orc.dequant_fp8(q, 1.0, bf16=True), vals)
