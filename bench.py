@@ -348,6 +348,43 @@ def bench_gate_plan(wl, reps=50):
             "note": "sf_gate_eval + sf_budget_search (plan construction from the gating module); not part of `value`"}
 
 
+def bench_fp8_plan(wl, dm, reps=50):
+    """Plan construction from FP8-stored weights (OCP E4M3 codes + one scale per matrix): the compaction reads one
+    byte per weight and dequantises in the same pass; the forward path is the same."""
+    import numpy as np
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from gpu_utils import to_dev
+    s = wl.spec
+    names = ("Wq", "Wk", "Wv", "Wo", "W1", "W2")
+    d8, sc = [], []
+    for l in range(s.n_layers):
+        q, c = dict(dm.dense[l]), {}
+        for n in names:
+            w = dm.dense[l][n].float()
+            c[n] = float(w.abs().max() / 448.0)
+            q[n] = (w / c[n]).to(torch.float8_e4m3fn).view(torch.uint8).contiguous()
+        d8.append(q); sc.append(c)
+    layers8 = [sf.compact_heads_channels_fp8(dm.desc, l, d8[l], sc[l], dm.masks, int(wl.k_head[l]), int(wl.k_ffn[l]))
+               for l in range(s.n_layers)]
+
+    def plan8():
+        for l in range(s.n_layers):
+            sf.compact_heads_channels_fp8(dm.desc, l, d8[l], sc[l], dm.masks, int(wl.k_head[l]), int(wl.k_ffn[l]), out=layers8[l])
+
+    def plan16():
+        for l in range(s.n_layers):
+            sf.compact_heads_channels(dm.desc, l, dm.dense[l], dm.masks, int(wl.k_head[l]), int(wl.k_ffn[l]), out=dm.layers[l])
+
+    ms8, _ = time_steps(plan8, reps, 5)
+    ms16, _ = time_steps(plan16, reps, 5)
+    nbytes = sum(int(d8[0][n].numel()) for n in names) * s.n_layers
+    del layers8
+    return {"us_compaction_from_fp8": ms8 * 1e3, "us_compaction_from_16bit": ms16 * 1e3, "weight_bytes_fp8": nbytes,
+            "weight_bytes_16bit": 2 * nbytes,
+            "note": "sf_compact_heads_channels_fp8 vs sf_compact_heads_channels, all layers; the forward is unchanged"}
+
+
 def cpu_baseline(wl, flops_total):
     """The CPU oracle, as it stands, on a bounded number of whole samples of the same workload."""
     import numpy as np
@@ -457,6 +494,7 @@ def main():
         out["sampled_score"] = bench_sampled_score(wl, args.steps, args.warmup)
         out["moe_ffn"] = bench_moe(wl, args.steps, args.warmup)
         out["gate_plan"] = bench_gate_plan(wl)
+        out["fp8_weights"] = bench_fp8_plan(wl, dm)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(wl, flops["total"])

@@ -163,6 +163,31 @@ int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
                                   const int32_t *n_groups, const int32_t *ffn_idx,
                                   const sf_compact_layer *compact_host, void *stream);
 
+/* ------------------------------------------------------------------------
+ * FP8 post-training quantisation of the weights (the paper's "compatibility
+ * with quantization" experiment applies FP8 PTQ on top of the pruned model;
+ * it names neither format nor scaling).  Here the six weight matrices of a
+ * layer are stored as OCP E4M3 bytes (1-4-3, bias 7, finite only, 0x7F / 0xFF
+ * = NaN, largest value 448) in the shapes of sf_dense_layer, with one fp32
+ * scale per matrix; w = decode(byte) * scale.  Biases and LayerNorm vectors
+ * stay in the model dtype.  sf_compact_heads_channels_fp8 is
+ * sf_compact_heads_channels reading this storage: it gathers the kept blocks
+ * and dequantises in the same pass (one rounding, from the exact product, to
+ * the model dtype), so the forward path is unchanged and dense 16-bit weights
+ * never exist.  d_model must be a multiple of 4, the matrices 4-byte aligned.
+ */
+typedef struct sf_dense_layer_fp8 {
+    const void *Wq, *Wk, *Wv, *Wo, *W1, *W2;          /* uint8 E4M3 */
+    float sq, sk, sv, so, s1, s2;                     /* per-matrix scales */
+    const void *bq, *bk, *bv, *bo, *b1, *b2;          /* model dtype, any may be NULL */
+    const void *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+} sf_dense_layer_fp8;
+int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t layer,
+                                      const sf_dense_layer_fp8 *dense_host,
+                                      const int32_t *head_idx, const int32_t *group_idx,
+                                      const int32_t *n_groups, const int32_t *ffn_idx,
+                                      const sf_compact_layer *compact_host, void *stream);
+
 /* Element strides of a [B, heads, L, dh] tensor whose last dimension is
  * contiguous (for V with v_transposed: a [B, groups, dh, L] tensor whose L
  * dimension is contiguous and `l` is the stride between dh rows). */

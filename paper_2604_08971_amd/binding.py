@@ -25,7 +25,8 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_compact_heads_channels", "sf_sparse_gqa_workspace_bytes", "sf_sparse_gqa_forward",
            "sf_pruned_ffn_workspace_bytes", "sf_pruned_ffn_forward", "sf_encoder_workspace_bytes",
            "sf_encoder_forward", "sf_profile_begin", "sf_profile_end", "sf_compact_moe_experts",
-           "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search"]
+           "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search",
+           "sf_compact_heads_channels_fp8"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -57,6 +58,12 @@ class SfCompactLayer(C.Structure):
 
 
 _MOE_DENSE_FIELDS = ("Wr", "br", "W1", "b1", "W2", "b2", "ln_g", "ln_b")
+
+
+class SfDenseLayerFp8(C.Structure):
+    _fields_ = ([(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2")]
+                + [(n, C.c_float) for n in ("sq", "sk", "sv", "so", "s1", "s2")]
+                + [(n, C.c_void_p) for n in ("bq", "bk", "bv", "bo", "b1", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")])
 
 
 class SfMoeDense(C.Structure):
@@ -91,7 +98,7 @@ def lib():
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
                   "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward", "sf_gate_eval",
-                  "sf_budget_search"):
+                  "sf_budget_search", "sf_compact_heads_channels_fp8"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -101,6 +108,9 @@ def lib():
         L.sf_compact_heads_channels.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayer),
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                 C.POINTER(SfCompactLayer), C.c_void_p]
+        L.sf_compact_heads_channels_fp8.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayerFp8),
+                                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                    C.POINTER(SfCompactLayer), C.c_void_p]
         L.sf_pruned_ffn_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.c_void_p, C.c_void_p,
                                             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_encoder_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.c_void_p, C.c_void_p,
@@ -319,6 +329,25 @@ def compact_heads_channels(desc: SfDesc, layer: int, dense: Dict[str, torch.Tens
 
 
 # ------------------------------------------------------------------------ a4-a7
+def compact_heads_channels_fp8(desc: SfDesc, layer: int, dense8: Dict[str, torch.Tensor], scales: Dict[str, float],
+                               masks: Dict[str, torch.Tensor], k_head: int, k_ffn: int,
+                               out: Optional[CompactLayer] = None) -> CompactLayer:
+    """dense8: Wq, Wk, Wv, Wo, W1, W2 as uint8 (OCP E4M3 codes, shapes of the dense layer) plus the biases and
+    LayerNorm vectors in the model dtype; scales: one float per weight matrix, keyed like the matrices."""
+    for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2"):
+        assert dense8[n].dtype == torch.uint8 and dense8[n].is_contiguous(), n
+    cl = out if out is not None else CompactLayer(desc, dense8, k_head, k_ffn, masks["head_group"][layer],
+                                                  masks["n_groups"][layer])
+    ds = SfDenseLayerFp8(*[_ptr(dense8[n]) for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2")],
+                         *[float(scales[n]) for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2")],
+                         *[_ptr(dense8.get(n)) for n in ("bq", "bk", "bv", "bo", "b1", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")])
+    rc = lib().sf_compact_heads_channels_fp8(C.byref(desc), layer, C.byref(ds), _ptr(masks["head_idx"]),
+                                             _ptr(masks["group_idx"]), _ptr(masks["n_groups"]), _ptr(masks["ffn_idx"]),
+                                             C.byref(cl.struct), _stream())
+    _check(rc, "sf_compact_heads_channels_fp8")
+    return cl
+
+
 def _strides4(t: torch.Tensor) -> SfStrides:
     assert t.dim() == 4 and t.stride(3) == 1
     return SfStrides(t.stride(0), t.stride(1), t.stride(2))

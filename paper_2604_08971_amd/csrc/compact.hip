@@ -105,6 +105,93 @@ static void gather_transpose(hipStream_t st, int dtype, const void *src, void *d
                            cols_out, d, dst_pstride);
 }
 
+// ---- FP8 (OCP E4M3) weight storage: the same gathers, reading one byte per element and writing
+// decode(byte) * scale rounded once to the model dtype (the product of a 4-bit and a 24-bit significand is
+// exact in double).
+__device__ inline double fp8_e4m3_value(uint32_t b)
+{
+    const uint32_t e = (b >> 3) & 15u, m = b & 7u;
+    float v;
+    if (e == 15u && m == 7u) v = __uint_as_float(0x7fc00000u);               // the only non-finite code
+    else if (e == 0u) v = (float)m * 0x1p-9f;                                // subnormal
+    else v = __uint_as_float(((e + 120u) << 23) | (m << 20));                // (1 + m/8) * 2^(e-7)
+    return (b & 0x80u) ? -(double)v : (double)v;
+}
+
+template <class T> __device__ inline T round_from_double(double x);
+template <> __device__ inline float round_from_double<float>(double x) { return (float)x; }
+template <> __device__ inline uint16_t round_from_double<uint16_t>(double x)      // bf16 bits, ties to even
+{
+    // double -> fp32 towards zero with the lost bits folded into the last bit (round to odd) keeps every
+    // tie / non-tie decision of the following 16-bit rounding
+    float f = __double2float_rz(x);
+    uint32_t u = __float_as_uint(f);
+    if ((double)f != x && x == x) u |= 1u;
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+struct Fp8Region {
+    const uint8_t *src; void *dst; const int32_t *idx; const int32_t *n_dev;
+    int idx_stride, block, n_static, rows; size_t dst_pstride /* elements */; float scale;
+};
+struct Fp8Regions { Fp8Region r[4]; int n; };
+
+// as gather_rows_kernel, rows of row_len elements (a multiple of 4); a thread converts 4 elements at a time
+template <class T>
+__global__ __launch_bounds__(256) void gather_rows_fp8_kernel(Fp8Regions regs, int row_len)
+{
+    const int p = blockIdx.y;
+    int R = blockIdx.x, g = 0;
+    while (g + 1 < regs.n && R >= regs.r[g].rows) { R -= regs.r[g].rows; ++g; }
+    const Fp8Region &rg = regs.r[g];
+    const int slot = R / rg.block, r = R % rg.block;
+    const int n_valid = rg.n_dev ? rg.n_dev[p] : rg.n_static;
+    int src_unit = -1;
+    if (slot < n_valid) src_unit = rg.idx[(size_t)p * rg.idx_stride + slot];
+    T *d = static_cast<T *>(rg.dst) + (size_t)p * rg.dst_pstride + (size_t)R * row_len;
+    const uint8_t *s = rg.src + ((size_t)(src_unit < 0 ? 0 : src_unit) * rg.block + r) * row_len;
+    const double sc = (double)rg.scale;
+    for (int i = threadIdx.x * 4; i < row_len; i += blockDim.x * 4) {
+        uint32_t w = 0u;
+        if (src_unit >= 0) w = *reinterpret_cast<const uint32_t *>(s + i);
+        struct alignas(sizeof(T) * 4) Pack { T v[4]; } o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o.v[e] = src_unit < 0 ? T(0) : round_from_double<T>(fp8_e4m3_value((w >> (8 * e)) & 0xffu) * sc);
+        *reinterpret_cast<Pack *>(d + i) = o;
+    }
+}
+
+// as gather_transpose_kernel with an FP8 source
+template <class T>
+__global__ __launch_bounds__(256) void gather_transpose_fp8_kernel(
+    const uint8_t *__restrict__ src, T *__restrict__ dstT, const int32_t *__restrict__ idx,
+    int idx_stride, int block, int n_valid, int cols_out, int d, size_t dst_pstride, float scale)
+{
+    __shared__ T tile[32][33];
+    const int p = blockIdx.z;
+    const int J0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    for (int jj = ty; jj < 32; jj += 8) {
+        const int J = J0 + jj, n = n0 + tx;
+        T v = T(0);
+        if (J < cols_out && n < d) {
+            const int slot = J / block;
+            const int unit = slot < n_valid ? idx[(size_t)p * idx_stride + slot] : -1;
+            if (unit >= 0)
+                v = round_from_double<T>(fp8_e4m3_value(src[((size_t)unit * block + J % block) * d + n]) * (double)scale);
+        }
+        tile[jj][tx] = v;
+    }
+    __syncthreads();
+    for (int nn = ty; nn < 32; nn += 8) {
+        const int n = n0 + nn, J = J0 + tx;
+        if (n < d && J < cols_out) dstT[(size_t)p * dst_pstride + (size_t)n * cols_out + J] = tile[tx][nn];
+    }
+}
+
 struct ExpertCounts { int32_t k[64]; };
 __global__ void store_expert_counts_kernel(ExpertCounts ec, int E, int32_t *__restrict__ out)
 {
@@ -239,4 +326,94 @@ extern "C" int32_t sf_compact_moe_experts(const sf_desc *desc, const sf_moe_dens
                                hipMemcpyDeviceToDevice, st) != hipSuccess)
                 return fail(SF_ERR_HIP, "compact_moe_experts: copy of b2 failed");
     return check_launch("compact_moe_experts");
+}
+
+// FP8-stored dense weights (OCP E4M3 bytes + one fp32 scale per matrix): gather and dequantise in one pass.
+extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense,
+                                                 const int32_t *head_idx, const int32_t *group_idx,
+                                                 const int32_t *n_groups, const int32_t *ffn_idx,
+                                                 const sf_compact_layer *c, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!dense || !c || !head_idx || !group_idx || !n_groups || !ffn_idx)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: NULL argument");
+    if (layer < 0 || layer >= D.nl)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: layer %d out of range", layer);
+    if (c->k_head < 1 || c->k_head > D.Hq || c->k_ffn < 1 || c->k_ffn > D.F)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: keep counts out of range");
+    if (!dense->Wq || !dense->Wk || !dense->Wv || !dense->Wo || !dense->W1 || !dense->W2 ||
+        !c->Wqkv || !c->WoT || !c->W1 || !c->W2T)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: NULL weight pointer");
+    if (D.d % 4) return fail(SF_ERR_SHAPE, "compact_heads_channels_fp8: d_model must be a multiple of 4");
+    if (((uintptr_t)dense->Wq | (uintptr_t)dense->Wk | (uintptr_t)dense->Wv | (uintptr_t)dense->W1) & 3)
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: weight matrices must be 4-byte aligned");
+    const bool qkv_bias = dense->bq || dense->bk || dense->bv;
+    if (qkv_bias && !(dense->bq && dense->bk && dense->bv))
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: bq, bk, bv must be all set or all NULL");
+    if ((qkv_bias && !c->bqkv) || (dense->b1 && !c->b1))
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: compact bias buffer missing");
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t es = elem_size(D.dtype);
+    const bool bf = D.dtype == SF_BF16;
+    const int P = D.P, dh = D.dh, d = D.d, kh = c->k_head, kf = c->k_ffn;
+    const int Fp = (int)align_up(kf, D.ffn_pad);
+    const int Nqkv = (kh + 2 * D.Hk) * dh;
+    const int32_t *hi = head_idx + (size_t)layer * P * D.Hq;
+    const int32_t *gi = group_idx + (size_t)layer * P * D.Hk;
+    const int32_t *ng = n_groups + (size_t)layer * P;
+    const int32_t *fi = ffn_idx + (size_t)layer * P * D.F;
+
+    auto wreg = [&](const void *src, void *dst, size_t row_off, const int32_t *idx, int idx_stride, int block, int n_static,
+                    const int32_t *n_dev, int rows, size_t rows_per_pattern, float scale) {
+        Fp8Region r{};
+        r.src = static_cast<const uint8_t *>(src); r.dst = (char *)dst + row_off * d * es; r.idx = idx; r.n_dev = n_dev;
+        r.idx_stride = idx_stride; r.block = block; r.n_static = n_static; r.rows = rows;
+        r.dst_pstride = rows_per_pattern * d; r.scale = scale;
+        return r;
+    };
+    Fp8Regions wr{};
+    wr.r[0] = wreg(dense->Wq, c->Wqkv, 0, hi, D.Hq, dh, kh, nullptr, kh * dh, Nqkv, dense->sq);
+    wr.r[1] = wreg(dense->Wk, c->Wqkv, (size_t)kh * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, dense->sk);
+    wr.r[2] = wreg(dense->Wv, c->Wqkv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, dense->sv);
+    wr.r[3] = wreg(dense->W1, c->W1, 0, fi, D.F, 1, kf, nullptr, Fp, Fp, dense->s1);
+    wr.n = 4;
+    {
+        dim3 grid(kh * dh + 2 * D.Hk * dh + Fp, P);
+        const int nt = d >= 1024 ? 256 : (d >= 512 ? 128 : 64);
+        if (bf) hipLaunchKernelGGL(gather_rows_fp8_kernel<uint16_t>, grid, dim3(nt), 0, st, wr, d);
+        else hipLaunchKernelGGL(gather_rows_fp8_kernel<float>, grid, dim3(nt), 0, st, wr, d);
+    }
+    // biases are stored in the model dtype: the plain gathers
+    auto region = [&](const void *src, void *dst, size_t elem_off, const int32_t *idx, int idx_stride, int block,
+                      int n_static, const int32_t *n_dev, int rows, size_t rows_per_pattern, size_t row_bytes) {
+        GatherRegion r{};
+        r.src = src; r.dst = (char *)dst + elem_off * row_bytes; r.idx = idx; r.n_dev = n_dev;
+        r.idx_stride = idx_stride; r.block = block; r.n_static = n_static; r.rows = rows;
+        r.dst_pstride = rows_per_pattern;
+        return r;
+    };
+    GatherRegions br{};
+    if (qkv_bias) {
+        br.r[br.n++] = region(dense->bq, c->bqkv, 0, hi, D.Hq, dh, kh, nullptr, kh * dh, Nqkv, es);
+        br.r[br.n++] = region(dense->bk, c->bqkv, (size_t)kh * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, es);
+        br.r[br.n++] = region(dense->bv, c->bqkv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, es);
+    }
+    if (dense->b1) br.r[br.n++] = region(dense->b1, c->b1, 0, fi, D.F, 1, kf, nullptr, Fp, Fp, es);
+    if (br.n) gather_rows(st, br, es, P);
+    auto transpose8 = [&](const void *src, void *dst, const int32_t *idx, int idx_stride, int block, int n_valid, int cols_out,
+                          float scale) {
+        dim3 grid(ceil_div(cols_out, 32), ceil_div(d, 32), P);
+        const size_t ps = (size_t)d * cols_out;
+        if (bf)
+            hipLaunchKernelGGL(gather_transpose_fp8_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint8_t *)src,
+                               (uint16_t *)dst, idx, idx_stride, block, n_valid, cols_out, d, ps, scale);
+        else
+            hipLaunchKernelGGL(gather_transpose_fp8_kernel<float>, grid, dim3(256), 0, st, (const uint8_t *)src,
+                               (float *)dst, idx, idx_stride, block, n_valid, cols_out, d, ps, scale);
+    };
+    transpose8(dense->W2, c->W2T, fi, D.F, 1, kf, Fp, dense->s2);
+    transpose8(dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, dense->so);
+    return check_launch("compact_heads_channels_fp8");
 }

@@ -33,6 +33,7 @@ def test_struct_layout_matches_header():
     assert C.sizeof(sf.SfMoeDense) == 8 * 8
     assert C.sizeof(sf.SfMoeCompact) == 16 + 9 * 8
     assert C.sizeof(sf.SfGateParams) == 16 + 6 * 8
+    assert C.sizeof(sf.SfDenseLayerFp8) == 6 * 8 + 6 * 4 + 10 * 8
 
 
 def test_num_active_matches_paper_example():
@@ -115,6 +116,11 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_budget_search(C.byref(d), one, one, 0, cp(c1), cp(c1), cp(c1), 0, 10, None, one, one, one, one, None) == -1
     assert L.sf_budget_search(C.byref(d), one, one, 3, cp(c1), cp(c1), cp(c1), 0, 10, one, one, one, one, one, None) == -1
     assert L.sf_budget_search(C.byref(d), one, one, 0, cp(c1), cp(neg), cp(c1), 0, 10, one, one, one, one, one, None) == -1
+    d8 = sf.SfDenseLayerFp8()
+    cl8 = sf.SfCompactLayer()
+    cl8.k_head, cl8.k_ffn = 4, 10
+    assert L.sf_compact_heads_channels_fp8(C.byref(d), 0, C.byref(d8), one, one, one, one, C.byref(cl8), None) == -1   # NULL matrices
+    assert L.sf_compact_heads_channels_fp8(C.byref(d), 5, C.byref(d8), one, one, one, one, C.byref(cl8), None) == -1   # layer out of range
     # host-side keep counts out of range
     kh, kf = (C.c_int32 * 1)(9), (C.c_int32 * 1)(3)
     one = C.c_void_p(256)                 # never dereferenced: the count check comes first

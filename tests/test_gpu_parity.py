@@ -122,6 +122,71 @@ def test_compaction_keep_all_is_identity():
         assert np.array_equal(to_host(cl.WoT[p]), w["Wo"].T)
 
 
+# -------------------------------------------------- FP8 (OCP E4M3) weight storage
+W8 = ("Wq", "Wk", "Wv", "Wo", "W1", "W2")
+
+
+def _quantise_fp8(wl):
+    """Per-matrix scale = amax / 448 and PyTorch's float8_e4m3fn cast as the (library) quantiser.  Returns the
+    codes, the scales, and a copy of the workload whose dense weights are the ORACLE's dequantised values."""
+    import copy
+    bf = wl.spec.dtype == "bf16"
+    codes, scales = [], []
+    wl2 = copy.copy(wl)
+    wl2.layers = []
+    for lw in wl.layers:
+        q, sc, lw2 = {}, {}, dict(lw)
+        for n in W8:
+            w = lw[n].astype(np.float32)
+            sc[n] = float(np.float32(np.abs(w).max() / 448.0))
+            q[n] = torch.from_numpy(w / np.float32(sc[n])).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            assert not ((q[n] & 0x7F) == 0x7F).any()
+            lw2[n] = orc.dequant_fp8(q[n], sc[n], bf).astype(np.float32)
+        codes.append(q); scales.append(sc); wl2.layers.append(lw2)
+    return codes, scales, wl2
+
+
+def _fp8_case(wl):
+    s = wl.spec
+    codes, scales, wl2 = _quantise_fp8(wl)
+    dm = DeviceModel(wl2).build_plan()                       # the 16/32-bit path on the oracle's dequantised weights
+    for l in range(s.n_layers):
+        d8 = {n: (to_dev(codes[l][n], s.dtype) if n in W8 else dm.dense[l][n]) for n in dm.dense[l]}
+        cl = sf.compact_heads_channels_fp8(dm.desc, l, d8, scales[l], dm.masks, int(wl.k_head[l]), int(wl.k_ffn[l]))
+        torch.cuda.synchronize()
+        ref = dm.layers[l]
+        for n in ("Wqkv", "bqkv", "WoT", "W1", "b1", "W2T"):
+            a, b = getattr(cl, n), getattr(ref, n)
+            assert (a is None) == (b is None), n
+            if a is not None:
+                assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
+                                   b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32)), (l, n)
+        dm.layers[l] = cl                                    # the forward below runs on the FP8-sourced buffers
+    return wl2, dm
+
+
+@pytest.mark.parametrize("kw", [dict(dtype="f32"), dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=3),
+                                dict(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=320, seg=(100, 133, 64), extra=3, B=4, act=1,
+                                     dropout="upto:2")])
+def test_fp8_weight_storage_small(kw):
+    """Compaction from FP8 storage is bit-identical to compaction of the oracle's dequantised weights, and the
+    encoder on those buffers matches the oracle run on the dequantised weights."""
+    _say(f"fp8 storage {kw}")
+    wl = W.make_workload(W.small_spec(**kw))
+    wl2, dm = _fp8_case(wl)
+    y8 = dm.forward()[0].clone()
+    torch.cuda.synchronize()
+    _encoder_parity(wl2)
+    dm2 = DeviceModel(wl2).build_plan()
+    assert torch.equal(y8, dm2.forward()[0])
+
+
+@pytest.mark.parametrize("name", ["C2", "C5"])
+def test_fp8_weight_storage_full_size(name):
+    _say(f"fp8 storage {name}")
+    _fp8_case(W.make_workload(W.CONFIGS[name]))
+
+
 # -------------------------------------------------- SentryGate: Eq. (1) and the global threshold
 def _gate_case(nl, M, Hq, Hk, F, Hd, nonlin, seed):
     gp = W.make_gate_params(nl, M, Hq, F, Hd, seed)
