@@ -50,6 +50,6 @@ int32_t score_bf16(const AttnArgs &a, const void *Kx, sf_strides skx, int Lk, co
 int32_t attend_bf16(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_strides svt,
                     const int32_t *sel, int selH, hipStream_t st);
 
-constexpr int STAT_CHUNK = 512;     // keys per partial-sum block of the K/V statistics
+constexpr int STAT_CHUNK = 128;     // keys per partial-sum block of the K/V statistics
 
 }  // namespace sf

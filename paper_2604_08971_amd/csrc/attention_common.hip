@@ -109,7 +109,8 @@ __global__ __launch_bounds__(256) void kv_stats_final_kernel(
     const float inv = c > 0 ? 1.0f / (float)c : 0.f;
     for (int t = threadIdx.x; t < 2 * dh; t += 256) {
         float s = 0.f;
-        for (int ch = 0; ch < chunks; ++ch) s += part[(((int64_t)bg * chunks + ch) * 2) * dh + t];
+#pragma unroll 8
+        for (int ch = 0; ch < chunks; ++ch) s += part[(((int64_t)bg * chunks + ch) * 2) * dh + t];      // loads in flight together
         stats[(int64_t)bg * 2 * dh + t] = s * inv;
     }
 }
@@ -118,36 +119,37 @@ __global__ __launch_bounds__(256) void kv_stats_final_kernel(
 // One block per (b, head): the U_eff = min(U, #allowed) queries with the
 // highest score, ties to the lower index; emitted ascending.  score == NULL
 // means "every allowed query" (used when U >= L).
-__global__ __launch_bounds__(256) void select_kernel(
+template <int NT>
+__global__ __launch_bounds__(NT) void select_kernel(
     const float *__restrict__ score, int scoreH, const uint8_t *__restrict__ key_valid, int nH, int L,
     int U, int32_t *__restrict__ sel, int selH, int32_t *__restrict__ slot)
 {
     extern __shared__ uint32_t keys[];
     __shared__ int scratch[TOPK_SCRATCH];
-    __shared__ int red[4];          // not part of `scratch`: block_topk clears its histogram there right away
+    __shared__ int red[NT / 64];    // not part of `scratch`: block_topk clears its histogram there right away
     const int bh = blockIdx.x, b = bh / nH, h = bh % nH;
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     const float *M = score ? score + ((int64_t)b * scoreH + h) * L : nullptr;
     int32_t *sl = slot + (int64_t)bh * L;
     int32_t *se = sel + ((int64_t)b * selH + h) * U;
     int c = 0;
-    for (int i = threadIdx.x; i < L; i += 256) {
+    for (int i = threadIdx.x; i < L; i += NT) {
         const bool ok = !kv || kv[i];
         // allowed queries get a key >= 1 (sortable_key(-inf) > 0), others key 0
         keys[i] = ok ? (M ? sortable_key(M[i]) : 1u) : 0u;
         c += ok;
     }
-    const int n_ok = block_sum<256>(c, red);        // also orders the LDS writes
+    const int n_ok = block_sum<NT>(c, red);        // also orders the LDS writes
     const int k = min(U, n_ok);
     if (k == 0) {
-        for (int i = threadIdx.x; i < L; i += 256) sl[i] = -1;
+        for (int i = threadIdx.x; i < L; i += NT) sl[i] = -1;
     } else {
-        block_topk<256>(keys, L, k, scratch, [&](int i, bool kept, int pos) {
+        block_topk<NT>(keys, L, k, scratch, [&](int i, bool kept, int pos) {
             sl[i] = kept ? pos : -1;
             if (kept) se[pos] = i;
         });
     }
-    for (int r = k + threadIdx.x; r < U; r += 256) se[r] = -1;
+    for (int r = k + threadIdx.x; r < U; r += NT) se[r] = -1;
 }
 
 // Caller-supplied active set: build the row -> slot map and copy the list.
@@ -580,8 +582,13 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
             }
             M = score;
         }
-        hipLaunchKernelGGL(select_kernel, dim3(BH), dim3(256), a.L * sizeof(uint32_t), st, M, scoreH,
-                           a.key_valid, a.nH, a.L, a.U, sel, selH, pl.slot);
+        // few blocks (one per sample and head): long rows get 1024 threads so that a radix pass is 4 keys per thread
+        if (a.L >= 2048)
+            hipLaunchKernelGGL(select_kernel<1024>, dim3(BH), dim3(1024), a.L * sizeof(uint32_t), st, M, scoreH,
+                               a.key_valid, a.nH, a.L, a.U, sel, selH, pl.slot);
+        else
+            hipLaunchKernelGGL(select_kernel<256>, dim3(BH), dim3(256), a.L * sizeof(uint32_t), st, M, scoreH,
+                               a.key_valid, a.nH, a.L, a.U, sel, selH, pl.slot);
     }
 
     // 3. active rows

@@ -12,8 +12,8 @@ struct KeepCounts { int k[MAX_LAYERS]; };
 
 // One block per (layer, pattern): top-k of n scores.
 // GROUPS: additionally derive the kept K/V groups of the kept heads.
-template <bool GROUPS>
-__global__ __launch_bounds__(MASK_NT) void keep_topk_kernel(
+template <bool GROUPS, int NT>
+__global__ __launch_bounds__(NT) void keep_topk_kernel(
     const float *__restrict__ g, int n, int P, KeepCounts kc, uint8_t *__restrict__ mask,
     int32_t *__restrict__ idx, int Hk, int32_t *__restrict__ group_idx,
     int32_t *__restrict__ n_groups, int32_t *__restrict__ head_group)
@@ -26,13 +26,13 @@ __global__ __launch_bounds__(MASK_NT) void keep_topk_kernel(
     uint8_t *m = mask + (size_t)lp * n;
     int32_t *ix = idx + (size_t)lp * n;
 
-    for (int i = threadIdx.x; i < n; i += MASK_NT) keys[i] = sortable_key(gs[i]);
+    for (int i = threadIdx.x; i < n; i += NT) keys[i] = sortable_key(gs[i]);
     __syncthreads();
-    block_topk<MASK_NT>(keys, n, k, scratch, [&](int i, bool kept, int pos) {
+    block_topk<NT>(keys, n, k, scratch, [&](int i, bool kept, int pos) {
         m[i] = kept ? 1 : 0;
         if (kept) ix[pos] = i;
     });
-    for (int i = k + threadIdx.x; i < n; i += MASK_NT) ix[i] = -1;
+    for (int i = k + threadIdx.x; i < n; i += NT) ix[i] = -1;
 
     if (GROUPS) {
         // K_keep = floor(H_keep / (Hq/Hk)); groups no kept head refers to are dropped.
@@ -83,9 +83,14 @@ extern "C" int32_t sf_gate_scores_to_masks(const sf_desc *desc, const float *g_h
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int blocks = D.nl * D.P;
-    hipLaunchKernelGGL(keep_topk_kernel<true>, dim3(blocks), dim3(MASK_NT), D.Hq * sizeof(uint32_t), st,
+    hipLaunchKernelGGL((keep_topk_kernel<true, MASK_NT>), dim3(blocks), dim3(MASK_NT), D.Hq * sizeof(uint32_t), st,
                        g_head, D.Hq, D.P, kh, head_mask, head_idx, D.Hk, group_idx, n_groups, head_group);
-    hipLaunchKernelGGL(keep_topk_kernel<false>, dim3(blocks), dim3(MASK_NT), D.F * sizeof(uint32_t), st,
-                       g_ffn, D.F, D.P, kf, ffn_mask, ffn_idx, 0, nullptr, nullptr, nullptr);
+    // few blocks (one per layer and pattern): wide layers get 1024 threads, 2-4 keys per thread and radix pass
+    if (D.F >= 2048)
+        hipLaunchKernelGGL((keep_topk_kernel<false, 1024>), dim3(blocks), dim3(1024), D.F * sizeof(uint32_t), st,
+                           g_ffn, D.F, D.P, kf, ffn_mask, ffn_idx, 0, nullptr, nullptr, nullptr);
+    else
+        hipLaunchKernelGGL((keep_topk_kernel<false, MASK_NT>), dim3(blocks), dim3(MASK_NT), D.F * sizeof(uint32_t), st,
+                           g_ffn, D.F, D.P, kf, ffn_mask, ffn_idx, 0, nullptr, nullptr, nullptr);
     return check_launch("gate_scores_to_masks");
 }
