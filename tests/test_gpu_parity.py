@@ -843,6 +843,60 @@ def test_step_under_hip_graph_replay(which):
         assert torch.equal(y, y_eager)
 
 
+@pytest.mark.parametrize("which", ["small-f32", "C2"])
+def test_moe_block_under_hip_graph_replay(which):
+    """Expert compaction + the MoE forward (router, counting sort, grouped GEMMs, combine) recorded into a HIP
+    graph: every replay, with eager work and synchronisations in between, reproduces the eager result."""
+    _say(f"moe graph replay {which}")
+    if which == "C2":
+        wl, E, k = W.make_workload(W.CONFIGS["C2"]), 8, 2
+    else:
+        wl, E, k = W.make_workload(W.small_spec(dtype="f32", B=3, seg=(40, 30, 50), F=96)), 4, 2
+    s = wl.spec
+    dtype = s.dtype
+    mb = W.make_moe_block(wl, E, k)
+    B, L, d, F, P = wl.x.shape[0], s.L, s.d, s.F, wl.P
+    dt = sf.SF_BF16 if dtype == "bf16" else sf.SF_F32
+    dmask = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=E, P=P, dtype=dt, act=s.act)
+    desc = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=1, P=P, dtype=dt, act=s.act)
+    g_head = torch.zeros((E, P, 8), dtype=torch.float32, device="cuda")
+    masks = sf.gate_scores_to_masks(dmask, g_head, to_dev(mb.g_ffn, "f32"), [1] * E, mb.k_ffn.tolist())
+    dense = {n: to_dev(v, dtype) for n, v in mb.dense.items()}
+    cm = sf.compact_moe_experts(desc, dense, masks["ffn_idx"], k, mb.k_ffn.tolist())
+    X, pid = to_dev(wl.x.reshape(B * L, d), dtype), to_dev(wl.pattern_id, dtype)
+    ws = sf.workspace(sf.moe_ffn_workspace_bytes(desc, cm))
+    Y = torch.empty_like(X)
+
+    def step():
+        sf.compact_moe_experts(desc, dense, masks["ffn_idx"], k, mb.k_ffn.tolist(), out=cm)
+        sf.moe_ffn_forward(desc, cm, X, pid, out=Y, ws=ws)
+
+    step()
+    torch.cuda.synchronize()
+    y_eager = Y.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        Y.fill_(float("nan"))
+        ws.zero_()
+        cm.W1.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, y_eager), f"replay {rep} differs from the eager result"
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, y_eager)
+
+
 def test_encoder_rejects_small_workspace():
     wl = W.make_workload(W.small_spec(dtype="f32", B=2))
     dm = DeviceModel(wl).build_plan()
