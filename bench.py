@@ -304,7 +304,7 @@ def bench_moe(wl, steps, warmup, E=8, top_k=2):
     _, route, _, _ = sf.moe_ffn_forward(desc, cm, X, pid, want_route=True, ws=ws)
     load = np.bincount(to_host(route).ravel(), minlength=E).astype(np.int64)
     flops = int((load * 4 * d * mb.k_ffn.astype(np.int64)).sum()) + B * L * 2 * d * E
-    sf.profile_begin(0, 64)
+    sf.profile_begin(sf.SF_KERNEL_GEMM, 64)
     fwd()
     _, _, each = sf.profile_end(each=True)
     del cm, ws, dense

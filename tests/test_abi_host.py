@@ -126,3 +126,12 @@ def test_null_and_range_errors_before_any_launch():
     one = C.c_void_p(256)                 # never dereferenced: the count check comes first
     assert L.sf_gate_scores_to_masks(C.byref(d), one, one, C.cast(kh, C.c_void_p), C.cast(kf, C.c_void_p),
                                      one, one, one, one, one, one, one, None) == -1
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the public header compiles as C99 with no C++ or HIP types."""
+    import subprocess
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "sentryfuse.h"\nint main(void) { sf_desc d; (void)d; return (int)sizeof(sf_moe_compact) == 0; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           "-fsyntax-only", str(src)])
