@@ -66,6 +66,85 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(
     }
 }
 
+// One launch for a whole layer when every weight row is a multiple of 16 bytes: blockIdx.x selects the job -
+// [0, n_rows) one weight row each (regions of wr), then blocks of 256 bias elements (regions of br), then the
+// 32x32 tiles of the two transposed gathers; blockIdx.y is the pattern.  Four launches of a few microseconds
+// each became one.
+struct TransposeJob {
+    const void *src; void *dst; const int32_t *idx;
+    int idx_stride, block, n_valid, cols_out, tiles_j, tiles_n; size_t dst_pstride;
+};
+struct LayerJobs {
+    GatherRegions wr; int n_rows, row_vecs;        // dst_pstride in uint4
+    GatherRegions br; int n_bias, bias_blocks;     // dst_pstride in elements
+    TransposeJob tr[2]; int d;
+};
+
+template <class T>
+__global__ __launch_bounds__(256) void compact_layer_kernel(LayerJobs J)
+{
+    __shared__ T tile[32][33];
+    const int p = blockIdx.y;
+    int x = blockIdx.x;
+    if (x < J.n_rows) {
+        int R = x, g = 0;
+        while (g + 1 < J.wr.n && R >= J.wr.r[g].rows) { R -= J.wr.r[g].rows; ++g; }
+        const GatherRegion &rg = J.wr.r[g];
+        const int slot = R / rg.block, r = R % rg.block;
+        const int n_valid = rg.n_dev ? rg.n_dev[p] : rg.n_static;
+        int src_unit = -1;
+        if (slot < n_valid) src_unit = rg.idx[(size_t)p * rg.idx_stride + slot];
+        uint4 *d = static_cast<uint4 *>(rg.dst) + (size_t)p * rg.dst_pstride + (size_t)R * J.row_vecs;
+        if (src_unit < 0) {
+            for (int i = threadIdx.x; i < J.row_vecs; i += 256) d[i] = make_uint4(0, 0, 0, 0);
+        } else {
+            const uint4 *sv = static_cast<const uint4 *>(rg.src) + ((size_t)src_unit * rg.block + r) * J.row_vecs;
+            for (int i = threadIdx.x; i < J.row_vecs; i += 256) d[i] = sv[i];
+        }
+        return;
+    }
+    x -= J.n_rows;
+    if (x < J.bias_blocks) {
+        int R = x * 256 + threadIdx.x;
+        if (R >= J.n_bias) return;
+        int g = 0;
+        while (g + 1 < J.br.n && R >= J.br.r[g].rows) { R -= J.br.r[g].rows; ++g; }
+        const GatherRegion &rg = J.br.r[g];
+        const int slot = R / rg.block, r = R % rg.block;
+        const int n_valid = rg.n_dev ? rg.n_dev[p] : rg.n_static;
+        T v = T(0);
+        if (slot < n_valid) {
+            const int unit = rg.idx[(size_t)p * rg.idx_stride + slot];
+            if (unit >= 0) v = static_cast<const T *>(rg.src)[(size_t)unit * rg.block + r];
+        }
+        static_cast<T *>(rg.dst)[(size_t)p * rg.dst_pstride + R] = v;
+        return;
+    }
+    x -= J.bias_blocks;
+    int t = 0;
+    if (x >= J.tr[0].tiles_j * J.tr[0].tiles_n) { x -= J.tr[0].tiles_j * J.tr[0].tiles_n; t = 1; }
+    const TransposeJob &tj = J.tr[t];
+    const int J0 = (x % tj.tiles_j) * 32, n0 = (x / tj.tiles_j) * 32;
+    const T *src = static_cast<const T *>(tj.src);
+    T *dstT = static_cast<T *>(tj.dst);
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    for (int jj = ty; jj < 32; jj += 8) {
+        const int Jc = J0 + jj, n = n0 + tx;
+        T v = T(0);
+        if (Jc < tj.cols_out && n < J.d) {
+            const int slot = Jc / tj.block;
+            const int unit = slot < tj.n_valid ? tj.idx[(size_t)p * tj.idx_stride + slot] : -1;
+            if (unit >= 0) v = src[((size_t)unit * tj.block + Jc % tj.block) * J.d + n];
+        }
+        tile[jj][tx] = v;
+    }
+    __syncthreads();
+    for (int nn = ty; nn < 32; nn += 8) {
+        const int n = n0 + nn, Jc = J0 + tx;
+        if (n < J.d && Jc < tj.cols_out) dstT[(size_t)p * tj.dst_pstride + (size_t)n * tj.cols_out + Jc] = tile[tx][nn];
+    }
+}
+
 // regs.r[g].dst_pstride is given in ROWS here and converted to VECs
 static void gather_rows(hipStream_t st, GatherRegions regs, size_t row_bytes, int P)
 {
@@ -252,7 +331,6 @@ extern "C" int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
     wr.r[2] = region(dense->Wv, c->Wqkv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, rowW);
     wr.r[3] = region(dense->W1, c->W1, 0, fi, D.F, 1, kf, nullptr, Fp, Fp, rowW);
     wr.n = 4;
-    gather_rows(st, wr, rowW, P);
     GatherRegions br{};
     if (qkv_bias) {
         br.r[br.n++] = region(dense->bq, c->bqkv, 0, hi, D.Hq, dh, kh, nullptr, kh * dh, Nqkv, es);
@@ -260,8 +338,29 @@ extern "C" int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
         br.r[br.n++] = region(dense->bv, c->bqkv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, dh, 0, ng, D.Hk * dh, Nqkv, es);
     }
     if (dense->b1) br.r[br.n++] = region(dense->b1, c->b1, 0, fi, D.F, 1, kf, nullptr, Fp, Fp, es);
+    bool aligned = rowW % 16 == 0 && P <= 65535;
+    for (int g = 0; g < wr.n; ++g)
+        aligned = aligned && ((uintptr_t)wr.r[g].src % 16 == 0) && ((uintptr_t)wr.r[g].dst % 16 == 0);
+    if (aligned) {
+        // everything in one launch (weight rows, bias elements, the two transposed gathers)
+        LayerJobs J{};
+        J.wr = wr; J.row_vecs = (int)(rowW / 16);
+        for (int g = 0; g < wr.n; ++g) { J.n_rows += wr.r[g].rows; J.wr.r[g].dst_pstride = wr.r[g].dst_pstride * J.row_vecs; }
+        J.br = br;
+        for (int g = 0; g < br.n; ++g) J.n_bias += br.r[g].rows;
+        J.bias_blocks = ceil_div(J.n_bias, 256);
+        J.d = d;
+        // W2'^T and Wo'^T: unit rows become columns so the GEMMs read K-contiguous operands
+        J.tr[0] = TransposeJob{dense->W2, c->W2T, fi, D.F, 1, kf, Fp, ceil_div(Fp, 32), ceil_div(d, 32), (size_t)d * Fp};
+        J.tr[1] = TransposeJob{dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, ceil_div(kh * dh, 32), ceil_div(d, 32),
+                               (size_t)d * kh * dh};
+        dim3 grid(J.n_rows + J.bias_blocks + J.tr[0].tiles_j * J.tr[0].tiles_n + J.tr[1].tiles_j * J.tr[1].tiles_n, P);
+        if (D.dtype == SF_BF16) hipLaunchKernelGGL(compact_layer_kernel<uint16_t>, grid, dim3(256), 0, st, J);
+        else hipLaunchKernelGGL(compact_layer_kernel<uint32_t>, grid, dim3(256), 0, st, J);
+        return check_launch("compact_heads_channels");
+    }
+    gather_rows(st, wr, rowW, P);
     if (br.n) gather_rows(st, br, es, P);
-    // W2'^T and Wo'^T: unit rows become columns so the GEMMs read K-contiguous operands
     gather_transpose(st, D.dtype, dense->W2, c->W2T, fi, D.F, 1, kf, Fp, d, P);
     gather_transpose(st, D.dtype, dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, d, P);
     return check_launch("compact_heads_channels");

@@ -10,18 +10,14 @@ constexpr int MASK_NT = 256;
 constexpr int MAX_LAYERS = 128;
 struct KeepCounts { int k[MAX_LAYERS]; };
 
-// One block per (layer, pattern): top-k of n scores.
+// Top-k of n scores of one (layer, pattern); called by every thread of the block.
 // GROUPS: additionally derive the kept K/V groups of the kept heads.
 template <bool GROUPS, int NT>
-__global__ __launch_bounds__(NT) void keep_topk_kernel(
-    const float *__restrict__ g, int n, int P, KeepCounts kc, uint8_t *__restrict__ mask,
-    int32_t *__restrict__ idx, int Hk, int32_t *__restrict__ group_idx,
-    int32_t *__restrict__ n_groups, int32_t *__restrict__ head_group)
+__device__ void keep_topk_block(const float *__restrict__ g, int n, int lp, int k, uint8_t *__restrict__ mask,
+                                int32_t *__restrict__ idx, int Hk, int32_t *__restrict__ group_idx,
+                                int32_t *__restrict__ n_groups, int32_t *__restrict__ head_group, uint32_t *keys,
+                                int *scratch)
 {
-    extern __shared__ uint32_t keys[];
-    __shared__ int scratch[TOPK_SCRATCH];
-    const int lp = blockIdx.x;
-    const int k = kc.k[lp / P];
     const float *gs = g + (size_t)lp * n;
     uint8_t *m = mask + (size_t)lp * n;
     int32_t *ix = idx + (size_t)lp * n;
@@ -55,6 +51,28 @@ __global__ __launch_bounds__(NT) void keep_topk_kernel(
     }
 }
 
+// One launch for both unit types: blocks [0, nl*P) take the FFN channels of one (layer, pattern) - the long
+// rows, scheduled first -, blocks [nl*P, 2*nl*P) its heads and K/V groups.  There are few blocks, so wide
+// layers get NT = 1024 threads (2-4 keys per thread and radix pass).
+template <int NT>
+__global__ __launch_bounds__(NT) void keep_masks_kernel(
+    const float *__restrict__ g_head, const float *__restrict__ g_ffn, int Hq, int Hk, int F, int P, int n_lp,
+    KeepCounts kh, KeepCounts kf, uint8_t *__restrict__ head_mask, uint8_t *__restrict__ ffn_mask,
+    int32_t *__restrict__ head_idx, int32_t *__restrict__ ffn_idx, int32_t *__restrict__ group_idx,
+    int32_t *__restrict__ n_groups, int32_t *__restrict__ head_group)
+{
+    extern __shared__ uint32_t keys[];
+    __shared__ int scratch[TOPK_SCRATCH];
+    if ((int)blockIdx.x < n_lp) {
+        const int lp = blockIdx.x;
+        keep_topk_block<false, NT>(g_ffn, F, lp, kf.k[lp / P], ffn_mask, ffn_idx, 0, nullptr, nullptr, nullptr, keys, scratch);
+    } else {
+        const int lp = blockIdx.x - n_lp;
+        keep_topk_block<true, NT>(g_head, Hq, lp, kh.k[lp / P], head_mask, head_idx, Hk, group_idx, n_groups, head_group,
+                                  keys, scratch);
+    }
+}
+
 }  // namespace sf
 
 using namespace sf;
@@ -83,14 +101,16 @@ extern "C" int32_t sf_gate_scores_to_masks(const sf_desc *desc, const float *g_h
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int blocks = D.nl * D.P;
-    hipLaunchKernelGGL((keep_topk_kernel<true, MASK_NT>), dim3(blocks), dim3(MASK_NT), D.Hq * sizeof(uint32_t), st,
-                       g_head, D.Hq, D.P, kh, head_mask, head_idx, D.Hk, group_idx, n_groups, head_group);
-    // few blocks (one per layer and pattern): wide layers get 1024 threads, 2-4 keys per thread and radix pass
-    if (D.F >= 2048)
-        hipLaunchKernelGGL((keep_topk_kernel<false, 1024>), dim3(blocks), dim3(1024), D.F * sizeof(uint32_t), st,
-                           g_ffn, D.F, D.P, kf, ffn_mask, ffn_idx, 0, nullptr, nullptr, nullptr);
-    else
-        hipLaunchKernelGGL((keep_topk_kernel<false, MASK_NT>), dim3(blocks), dim3(MASK_NT), D.F * sizeof(uint32_t), st,
-                           g_ffn, D.F, D.P, kf, ffn_mask, ffn_idx, 0, nullptr, nullptr, nullptr);
+    const size_t lds = (size_t)(D.F > D.Hq ? D.F : D.Hq) * sizeof(uint32_t);
+#define SF_MASK_ARGS dim3(2 * blocks), dim3(NT_), lds, st, g_head, g_ffn, D.Hq, D.Hk, D.F, D.P, blocks, kh, kf, head_mask, \
+                     ffn_mask, head_idx, ffn_idx, group_idx, n_groups, head_group
+    if (D.F >= 2048) {
+        constexpr int NT_ = 1024;
+        hipLaunchKernelGGL(keep_masks_kernel<NT_>, SF_MASK_ARGS);
+    } else {
+        constexpr int NT_ = MASK_NT;
+        hipLaunchKernelGGL(keep_masks_kernel<NT_>, SF_MASK_ARGS);
+    }
+#undef SF_MASK_ARGS
     return check_launch("gate_scores_to_masks");
 }
