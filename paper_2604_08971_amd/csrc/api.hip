@@ -331,10 +331,20 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
         g.bias = ly.bqkv; g.bias_pstride = Nqkv; g.pattern_id = pattern_id;
         g.B = D.B; g.L = D.L; g.K = D.d; g.act = ACT_NONE; g.epi = EPI_ROWMAJOR;
         g.C = w.qkv; g.ldc = ldq; g.n0 = 0; g.N = bf ? Nqk : Nqkv;
-        if (int32_t rc = gemm(D.dtype, g, st)) return rc;
         if (bf) {
-            g.n0 = Nqk; g.N = Hk * dh; g.epi = EPI_VT; g.C = w.vt;
-            g.vt_b = (int64_t)Hk * dh * w.Lp; g.vt_n = w.Lp;
+            // one launch for Q, K and V when the large-tile kernel takes it (V is the transposed column range:
+            // the normalised input is read once); otherwise Q/K and V separately
+            GemmArgs q3 = g;
+            q3.N = Nqkv; q3.VT = w.vt; q3.vt_from = Nqk; q3.vt_b = (int64_t)Hk * dh * w.Lp; q3.vt_n = w.Lp;
+            if (gemm_takes_vt_split(D.dtype, q3)) {
+                if (int32_t rc = gemm(D.dtype, q3, st)) return rc;
+            } else {
+                if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+                g.n0 = Nqk; g.N = Hk * dh; g.epi = EPI_VT; g.C = w.vt;
+                g.vt_b = q3.vt_b; g.vt_n = q3.vt_n;
+                if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+            }
+        } else {
             if (int32_t rc = gemm(D.dtype, g, st)) return rc;
         }
 

@@ -32,6 +32,9 @@ struct GemmArgs {
                                                          // contiguous ranges (rows of unequal cost, e.g. n_lim / k_lim)
     int r_f32, c_f32;                                    // bf16 GEMM only: R / C hold fp32 (the residual stream)
     int64_t vt_b, vt_n;                                  // EPI_VT: strides of b and n (i contiguous)
+    void *VT; int vt_from;                               // large bf16 row-major problems only (gemm_takes_vt_split):
+                                                         // features n >= vt_from go to VT[b, n - vt_from, i] (strides
+                                                         // vt_b, vt_n, both % 8 == 0; vt_from % 8 == 0) instead of C
 };
 
 // dtype SF_BF16: bf16 MFMA, fp32 accumulate (K % 8 == 0, lda/ldw/ldr % 8 == 0,
@@ -40,6 +43,9 @@ int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st);
 
 // True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).
 bool gemm_takes_row_map(int dtype, const GemmArgs &a);
+
+// True when gemm() honours a.VT / a.vt_from for this problem (else it fails with SF_ERR_UNSUPPORTED).
+bool gemm_takes_vt_split(int dtype, const GemmArgs &a);
 
 // LayerNorm over rows of d elements (biased variance).  gamma/beta are in the
 // model dtype; x is fp32 when x_f32 (or dtype is SF_F32), y is in the model dtype.

@@ -242,10 +242,16 @@ int32_t gemm_bf16_ws(const GemmArgs &a, hipStream_t st, bool &done);
 bool gemm_bf16_ws_eligible(const GemmArgs &a);
 
 bool gemm_takes_row_map(int dtype, const GemmArgs &a) { return dtype == SF_BF16 && gemm_bf16_ws_eligible(a); }
+bool gemm_takes_vt_split(int dtype, const GemmArgs &a)
+{
+    return dtype == SF_BF16 && gemm_bf16_ws_eligible(a) && a.vt_from > 0 && a.vt_from < a.N && a.vt_from % 8 == 0 &&
+           a.vt_b % 8 == 0 && a.vt_n % 8 == 0 && !a.R && !a.c_f32 && !a.n_lim;
+}
 
 int32_t gemm_bf16(const GemmArgs &a, hipStream_t st)
 {
     if (a.B <= 0 || a.N <= 0) return SF_OK;
+    if (a.VT && !gemm_takes_vt_split(SF_BF16, a)) return fail(SF_ERR_UNSUPPORTED, "gemm(bf16): transposed column range on a problem the large-tile kernel does not take");
     if (a.row_map && !gemm_bf16_ws_eligible(a)) return fail(SF_ERR_UNSUPPORTED, "gemm(bf16): row_map on a problem the large-tile kernel does not take");
     {
         bool done = false;

@@ -73,7 +73,7 @@ __device__ __forceinline__ float activate(float z)
 }
 
 // One output tile of the walk below
-struct Tile { int b, m0, nt0, p, N, nk; };
+struct Tile { int b, m0, nt0, p, N, nk, vt; };
 
 // The tiles of this workgroup, in order.  The launch has the same number of workgroups on every XCD
 // (workgroup w runs on XCD w % 8); an XCD owns `per_xcd` tile slots: a contiguous range of the tile list
@@ -97,13 +97,26 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int tiles_m, int ti
             if (w >= total_tiles) continue;
             tn_i = w % tiles_n;
             tm_i = w / tiles_n;
+            // when the workgroups of an XCD are a multiple of the tiles per row, a workgroup would meet the same
+            // column in every round: rotate the columns from round to round (tiles of unequal cost then spread
+            // over all workgroups)
+            if (stride % tiles_n == 0) tn_i = (tn_i + s / stride) % tiles_n;
         }
         t.b = tm_i / tiles_m;
         t.m0 = (tm_i % tiles_m) * BM;
-        t.nt0 = tn_i * BN;
         t.p = a.pattern_id ? a.pattern_id[t.b] : 0;
         if (t.p < 0) continue;                                     // sample not in use
-        t.N = a.n_lim ? min(a.N, a.n_lim[t.p]) : a.N;
+        if (a.VT) {
+            // two column ranges, each with its own tiles: [0, vt_from) row-major, [vt_from, N) transposed
+            const int ta = (a.vt_from + BN - 1) / BN;
+            t.vt = tn_i >= ta;
+            t.nt0 = t.vt ? a.vt_from + (tn_i - ta) * BN : tn_i * BN;
+            t.N = t.vt ? a.N : a.vt_from;
+        } else {
+            t.vt = 0;
+            t.nt0 = tn_i * BN;
+            t.N = a.n_lim ? min(a.N, a.n_lim[t.p]) : a.N;
+        }
         if (t.nt0 >= t.N) continue;
         t.nk = (a.k_lim ? min(a.K, a.k_lim[t.p]) : a.K) / BKT;
         if (t.nk < 1) continue;
@@ -223,6 +236,12 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     // layout of lay(), MFMA tile t adds t * 4096 bytes and k-step s flips bits 5..6 (XOR with s << 5).
     const uint32_t xlane = (uint32_t)lay(wm * TM * 32 + l32, lhi) * 2u;
     const uint32_t wlane = (uint32_t)(NXS * XSLOT) * 2u + (uint32_t)lay(wn * TN * 32 + l32, lhi) * 2u;
+    // Transposed column range: the same instruction stream with the operand roles exchanged.  The two-fragment
+    // ("A") side reads token rows, the four-fragment ("B") side reads feature rows, so the wave covers 64 tokens x
+    // 128 features (waves 4 x 2) and an accumulator lane owns one feature and 4 consecutive tokens.
+    const int wmv = wave & 3, wnv = wave >> 2;
+    const uint32_t xlane_vt = (uint32_t)lay(wmv * TN * 32 + l32, lhi) * 2u;                                   // A side, in an X slot
+    const uint32_t wlane_vt = (uint32_t)(NXS * XSLOT) * 2u + (uint32_t)lay(wnv * TM * 32 + l32, lhi) * 2u;    // B side, in a W slot
     static_assert(TN == 2 && TM == 4 && BKT == 64, "the interleaving below is written for 2 x 4 MFMA tiles per wave");
     uint32_t xslot = 0, wslot = 0;          // byte offsets of the ring slots of the next step
     int sm = s0;
@@ -236,6 +255,18 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         int lb = lane;
         asm volatile("" : "+v"(lb));
         const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)tl.p * a.bias_pstride + a.n0 : nullptr;
+        if (tl.vt) {
+            // every entry of MFMA tile (tn, tm) of this lane belongs to feature wnv*128 + tm*32 + l32
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                const int n = min(tl.nt0 + wnv * 128 + j * 32 + (lb & 31), tl.N - 1);   // clamped: never stored
+                const float f = bias ? (float)bias[n] : 0.f;
+#pragma unroll
+                for (int i = 0; i < TN; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = f;
+            }
+        } else
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -259,7 +290,8 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         // bare barrier: no global memory traffic of this wave needs ordering here
         __builtin_amdgcn_s_barrier();                             // barrier of this step
         asm volatile("" ::: "memory");
-        const uint32_t xb = xlane + xslot, wb = wlane + wslot;
+        // xb: base of the four-fragment side, wb: base of the two-fragment side
+        const uint32_t xb = tl.vt ? wlane_vt + wslot : xlane + xslot, wb = tl.vt ? xlane_vt + xslot : wlane + wslot;
         xdone = xslot;
         wdone = wslot;
         xslot = (xslot + XSLOT * 2 == NXS * XSLOT * 2) ? 0u : xslot + XSLOT * 2;
@@ -318,8 +350,10 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     const bool inside = mrow0 + 128 <= a.L && ncol0 + 64 <= Np;   // uniform: the whole sub-tile exists, no per-row checks
     const int rows_left = a.L - mrow0 - er;                        // row r of the sub-tile (r = er mod 8) exists iff r - er < rows_left
 
-    if (!a.c_f32 && !a.R) {
+    if (tl.vt || (!a.c_f32 && !a.R)) {
         // bf16 output, no residual: stage 64 x 64 of the 128 x 64 sub-tile at a time as bf16 rows of 128 bytes.
+        // (Transposed column range: the same code with tokens and features exchanged - a staged row is a feature
+        // and holds 64 tokens - and the rows go to VT[b, n - vt_from, i].)
         // A lane owns 4 consecutive features per (tile, q): they go to LDS as one 8-byte write, with no lane
         // exchange.  In lay() the chunk index only flips bits 4..6 of the byte address, so one base address
         // per lane serves all chunks (XOR) and both 32-row halves (+4096 bytes).
@@ -360,7 +394,17 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
             for (int j = 0; j < 8; ++j) {
                 const int r = half * 64 + j * 8;                            // uniform
                 const bf16x8 o = *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const __bf16 *>(stg) + lay(j * 8 + er, ec));
-                if (inside || (col_ok && r < rows_left))
+                if (tl.vt) {
+                    const int n = tl.nt0 + wnv * 128 + r + er, i = tl.m0 + wmv * 64 + ec * 8;
+                    __bf16 *dst = static_cast<__bf16 *>(a.VT) + (int64_t)tl.b * a.vt_b + (int64_t)(n - a.vt_from) * a.vt_n + i;
+                    if (n < Np && i + 7 < a.L) {
+                        __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(dst));
+                    } else if (n < Np) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (i + e < a.L) dst[e] = o[e];
+                    }
+                } else if (inside || (col_ok && r < rows_left))
                     // streamed out: the output is far larger than L2 and must not push the weights out of it
                     __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(cp + (int64_t)r * a.ldc));
             }
@@ -458,7 +502,8 @@ static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
             return fail(SF_ERR_HIP, "gemm: cannot reserve %zu bytes of LDS", lds);
         attr_set = true;
     }
-    const int tiles_m = ceil_div(a.L, BM), tiles_n = ceil_div(a.N, BN);
+    const int tiles_m = ceil_div(a.L, BM);
+    const int tiles_n = a.VT ? ceil_div(a.vt_from, BN) + ceil_div(a.N - a.vt_from, BN) : ceil_div(a.N, BN);
     const int total = a.B * tiles_m * tiles_n;
     const int per_xcd = a.xcd_rows ? ceil_div(a.B * tiles_m, N_XCD) * tiles_n : ceil_div(total, N_XCD);
     // persistent: one workgroup per compute unit (160 KB of LDS each), the same number on every XCD

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a)
 int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st)
 {
     if (dtype == SF_BF16) return gemm_bf16(a, st);
-    if (a.row_map) return fail(SF_ERR_UNSUPPORTED, "gemm(f32): row_map is not supported");
+    if (a.row_map || a.VT) return fail(SF_ERR_UNSUPPORTED, "gemm(f32): row_map / transposed column range are not supported");
     if (a.B <= 0 || a.N <= 0) return SF_OK;
     dim3 grid(ceil_div(a.L, FT) * a.B, ceil_div(a.N, FT));
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, a);
