@@ -236,6 +236,9 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(
     const int h = (int)(bh % nH);
     const int64_t b = bh / nH;
     const int64_t base = bh * splits;
+    // an empty slot (fewer allowed queries than U) has no row and no partials: nothing to merge
+    const int qi = sel[((int64_t)b * selH + h) * U + s];
+    if (qi < 0) return;                                     // wave-uniform
     float ms = -INFINITY, ls = 0.f;
     if (lane < splits) {
         const int64_t q = (base + lane) * Upad + s;
@@ -250,7 +253,6 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o);
     const float inv = den > 0.f ? 1.0f / den : 0.f;
-    const int qi = sel[((int64_t)b * selH + h) * U + s];
     T *orow = O + ((int64_t)b * L + qi) * ldo + (int64_t)h * dh;
     for (int e = lane; e < dh; e += 64) {
         float acc = 0.f;

@@ -541,6 +541,31 @@ def test_sparse_gqa_parity(dtype, B, nH, nG, L, dh, Uo, mask):
     _gqa_case(dtype, B, nH, nG, L, dh, Uo, mask, seed=L * 7 + dh)
 
 
+def test_sparse_gqa_empty_slots_with_key_splits():
+    """Fewer active rows than U on a long sequence (the active pass runs in key splits and a merge kernel
+    finishes the rows): the empty slots of sample 1 must not touch any row - in particular not the last row of
+    sample 0, which is made an active row here so that the lazy-row fill cannot paper over a stray write."""
+    B, nH, nG, L, dh = 2, 2, 1, 4096, 64
+    rng = np.random.default_rng(77)
+    Q = W.to_bf16_values(rng.standard_normal((B, nH, L, dh)).astype(np.float32))
+    K = W.to_bf16_values(rng.standard_normal((B, nG, L, dh)).astype(np.float32))
+    V = W.to_bf16_values(rng.standard_normal((B, nG, L, dh)).astype(np.float32))
+    hg = np.zeros((1, nH), np.int32)
+    desc = sf.make_desc(B, L, 64, 8, 2, dh, 64, dtype=sf.SF_BF16)
+    U = sf.num_active(desc)
+    fs = np.full((B, nH, U), -1, np.int32)
+    fs[0, :, :3] = [5, 100, L - 1]
+    fs[1, :, :1] = [7]
+    O, sel, _ = sf.sparse_gqa_forward(desc, to_dev(Q, "bf16"), to_dev(K, "bf16"), to_dev(V, "bf16"), to_dev(hg, "bf16"),
+                                      None, None, to_dev(fs, "bf16"), want_sel=True)
+    torch.cuda.synchronize()
+    O, sel = to_host(O), to_host(sel)
+    assert np.array_equal(sel, fs)
+    O_ref, _, _, _ = orc.sparse_gqa(Q, K, V, hg[0], U, None, fs, True, None)
+    assert np.isfinite(O).all()
+    assert err_metric(O, O_ref) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_sparse_gqa_variants(dtype):
     dh = 16 if dtype == "f32" else 64
