@@ -241,6 +241,17 @@ def bench_sparse_gqa(dm, wl, steps):
             fl += int((kh * 2 * n_allowed * n_allowed * dh).sum())
         out[tag] = {"U": U, "ms": ms, "tflops": fl / (ms * 1e-3) / 1e12,
                     "frac_of_bf16_peak": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        # the same call with V handed over key-contiguous ([B, Hk, dh, Lp], the layout the encoder's projection
+        # writes): no transposition pass inside the entry point
+        Lp = (L + 7) // 8 * 8
+        VT = torch.zeros((B, s.Hk, dh, Lp), dtype=torch.bfloat16, device="cuda")
+        VT[..., :L] = V.permute(0, 1, 3, 2)
+        fn_t = lambda: sf.sparse_gqa_forward(desc, Q, K, VT, hg, dm.pattern_id, dm.key_valid, v_transposed=True,
+                                             want_sel=False, ws=ws)
+        ms_t, _ = time_steps(fn_t, steps, 2)
+        out[tag + "_v_transposed"] = {"U": U, "ms": ms_t, "tflops": fl / (ms_t * 1e-3) / 1e12,
+                                      "frac_of_bf16_peak": fl / (ms_t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        del VT
     return out
 
 
