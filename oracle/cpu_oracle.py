@@ -53,6 +53,9 @@ def lib():
         _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_max_threads.restype = C.c_int32
         _lib.orc_fp8_e4m3_decode.restype = C.c_double
+        _lib.orc_fp8_e4m3_encode.restype = C.c_uint8
+        _lib.orc_pruned_ffn_fp8.restype = None
+        _lib.orc_quantize_fp8.restype = None
         _lib.orc_fp8_e4m3_decode.argtypes = [C.c_uint8]
         for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_moe_ffn",
                   "orc_gate_eval", "orc_budget_search"):
@@ -281,6 +284,43 @@ def dequant_fp8(q, scale: float, bf16: bool) -> np.ndarray:
     out = np.empty(q.shape, np.float64)
     lib().orc_dequant_fp8(_p(q), C.c_int64(q.size), C.c_float(float(scale)), C.c_int32(int(bf16)), _p(out))
     return out
+
+
+def fp8_e4m3_encode(t: float) -> int:
+    return int(lib().orc_fp8_e4m3_encode(C.c_float(float(t))))
+
+
+def quantize_fp8(x, scale: float) -> np.ndarray:
+    """x (taken as fp32) -> E4M3 codes of fl32(x * fl32(1/scale)), ties to even, saturating at +-448."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, np.uint8)
+    lib().orc_quantize_fp8(_p(x), C.c_int64(x.size), C.c_float(float(scale)), _p(out))
+    return out
+
+
+def pruned_ffn_fp8(x, W1q, s1: float, b1, W2q, s2: float, b2, ln_g, ln_b, sx: float, sh: float, ffn_mask=None,
+                   act: int = 0, eps: float = 1e-5, pre_ln: bool = True, add_residual: bool = True,
+                   bf16: bool = True):
+    """FFN block in FP8 arithmetic (see orc_pruned_ffn_fp8).  W1q, W2q [F,d] uint8 codes (dense layout).
+    Returns (y [rows,d] fp64, xq [rows,d] uint8, hq [rows,F] uint8)."""
+    x = _f64(x)
+    d = x.shape[-1]
+    rows = x.size // d
+    W1q = np.ascontiguousarray(W1q, dtype=np.uint8)
+    W2q = np.ascontiguousarray(W2q, dtype=np.uint8)
+    F = W1q.shape[0]
+    assert W1q.shape == (F, d) and W2q.shape == (F, d)
+    b1, b2, ln_g, ln_b = _f64(b1), _f64(b2), _f64(ln_g), _f64(ln_b)
+    fm = None if ffn_mask is None else np.ascontiguousarray(ffn_mask, dtype=np.uint8)
+    y = np.empty_like(x)
+    xq = np.empty((rows, d), np.uint8)
+    hq = np.empty((rows, F), np.uint8)
+    lib().orc_pruned_ffn_fp8(C.c_int32(d), C.c_int32(F), _p(W1q), C.c_float(float(s1)), _p(b1), _p(W2q),
+                             C.c_float(float(s2)), _p(b2), _p(ln_g), _p(ln_b), _p(fm), C.c_float(float(sx)),
+                             C.c_float(float(sh)), _p(x), C.c_int64(rows), C.c_int32(act), C.c_double(eps),
+                             C.c_int32(int(pre_ln)), C.c_int32(int(add_residual)), C.c_int32(int(bf16)), _p(y),
+                             _p(xq), _p(hq))
+    return y, xq, hq
 
 
 def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,

@@ -512,6 +512,83 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
     ffn_core(w, x, rows, act, eps, pre_ln, add_residual, bf16, bf16, y);
 }
 
+/* ---- FP8 arithmetic (W8A8) for the pruned FFN ------------------------------ */
+uint8_t orc_fp8_e4m3_encode(float t)
+{
+    if (isnan(t)) return 0x7F;
+    const uint8_t sign = signbit(t) ? 0x80 : 0x00;
+    const double a = fabs((double)t);
+    if (a > 448.0) return sign | 0x7E;                        /* saturate (also infinities) */
+    if (a < ldexp(1.0, -6)) {
+        /* subnormal range, spacing 2^-9; 8 * 2^-9 is the smallest normal value, code 0x08 */
+        return sign | (uint8_t)nearbyint(ldexp(a, 9));
+    }
+    int e;
+    (void)frexp(a, &e);                                       /* a = 1.x * 2^(e-1) */
+    int E = e - 1;
+    int q = (int)nearbyint(ldexp(a, 3 - E));                  /* 8..16, ties to even */
+    if (q == 16) { q = 8; ++E; }
+    return sign | (uint8_t)(((E + 7) << 3) | (q - 8));
+}
+
+void orc_quantize_fp8(const float *x, int64_t n, float scale, uint8_t *codes)
+{
+    const volatile float r = 1.0f / scale;                    /* volatile: rounded to fp32 here */
+    for (int64_t i = 0; i < n; ++i) {
+        const volatile float t = x[i] * r;
+        codes[i] = orc_fp8_e4m3_encode(t);
+    }
+}
+
+void orc_pruned_ffn_fp8(int32_t d, int32_t F, const uint8_t *W1q, float s1, const double *b1,
+                        const uint8_t *W2q, float s2, const double *b2, const double *ln_g,
+                        const double *ln_b, const uint8_t *ffn_mask, float sx, float sh,
+                        const double *x, int64_t rows, int32_t act, double eps, int32_t pre_ln,
+                        int32_t add_residual, int32_t bf16, double *y, uint8_t *xq_out, uint8_t *hq_out)
+{
+    double *xn = (double *)malloc(sizeof(double) * (size_t)rows * d);
+    float *t32 = (float *)malloc(sizeof(float) * (size_t)rows * (d > F ? d : F));
+    uint8_t *xq = (uint8_t *)malloc((size_t)rows * d);
+    uint8_t *hq = (uint8_t *)malloc((size_t)rows * F);
+    if (pre_ln) orc_layernorm(x, rows, d, ln_g, ln_b, eps, 0, xn);
+    else memcpy(xn, x, sizeof(double) * (size_t)rows * d);
+    for (int64_t i = 0; i < rows * d; ++i) t32[i] = (float)xn[i];
+    orc_quantize_fp8(t32, rows * d, sx, xq);
+    const volatile float os1 = sx * s1, os2 = sh * s2;        /* fp32 products */
+
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int32_t f = 0; f < F; ++f) {
+            if (ffn_mask && !ffn_mask[f]) { t32[r * F + f] = 0.f; continue; }
+            double acc = 0.0;                                 /* products and sum exact in double */
+            for (int32_t k = 0; k < d; ++k)
+                acc += orc_fp8_e4m3_decode(xq[r * d + k]) * orc_fp8_e4m3_decode(W1q[(int64_t)f * d + k]);
+            acc = acc * (double)os1 + (b1 ? b1[f] : 0.0);
+            t32[r * F + f] = (float)activation((double)(float)acc, act);
+        }
+    orc_quantize_fp8(t32, rows * F, sh, hq);
+    if (ffn_mask)
+        for (int64_t r = 0; r < rows; ++r)
+            for (int32_t f = 0; f < F; ++f)
+                if (!ffn_mask[f]) hq[r * F + f] = 0;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int32_t n = 0; n < d; ++n) {
+            double acc = 0.0;
+            for (int32_t f = 0; f < F; ++f) {
+                if (ffn_mask && !ffn_mask[f]) continue;
+                acc += orc_fp8_e4m3_decode(hq[r * F + f]) * orc_fp8_e4m3_decode(W2q[(int64_t)f * d + n]);
+            }
+            acc = acc * (double)os2 + (b2 ? b2[n] : 0.0);
+            if (add_residual) acc += x[r * d + n];
+            y[r * d + n] = rnd(acc, bf16);
+        }
+    if (xq_out) memcpy(xq_out, xq, (size_t)rows * d);
+    if (hq_out) memcpy(hq_out, hq, (size_t)rows * F);
+    free(hq); free(xq); free(t32); free(xn);
+}
+
 /* ---- Sparse-MoE FFN ------------------------------------------------------- */
 int32_t orc_moe_ffn(const orc_moe *m, const double *x, int64_t rows, int32_t act, double eps,
                     int32_t pre_ln, int32_t add_residual, int32_t bf16,

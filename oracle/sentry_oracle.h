@@ -237,6 +237,30 @@ int32_t orc_budget_search(int32_t nl, int32_t Hq, int32_t Hk, int32_t F, const f
 double orc_fp8_e4m3_decode(uint8_t byte);
 void orc_dequant_fp8(const uint8_t *q, int64_t n, float scale, int32_t bf16, double *out);
 
+/*
+ * FP8 arithmetic for the pruned FFN (the second half of the same experiment: the paper reports FP8 models but
+ * not how they compute).  Reading: both operands of the two FFN contractions are E4M3 codes with one fp32
+ * scale per tensor (W8A8, static scales chosen offline), products are exact and sums wide:
+ *     xq  = Q(LN2(x), sx)                                    (LN2 in fp64, its result rounded to fp32)
+ *     z   = (sum_k dec(xq_k) dec(W1q_fk)) * fl32(sx*s1) + b1_f      rounded to fp32
+ *     hq  = Q(act(z), sh)
+ *     y   = (sum_f dec(hq_f) dec(W2q_fn)) * fl32(sh*s2) + b2_n (+ x)   rounded to bf16 when bf16 != 0
+ * with Q(t, s) = E4M3( fl32( t * fl32(1/s) ) ): one fp32 reciprocal, one fp32 product, then round to nearest,
+ * ties to the even code, values beyond +-448 saturate to +-448, NaN gives 0x7F.  The code is decided from fp32
+ * values because that is the precision the device path holds them in.  Removed channels (ffn_mask[f] = 0)
+ * contribute nothing.  W1q, W2q [F,d] codes of the dense layout (one row per channel).
+ *   orc_fp8_e4m3_encode: the code of one fp32 value.
+ *   orc_quantize_fp8:    codes[i] = Q(x[i], scale).
+ *   orc_pruned_ffn_fp8:  the block; xq_out [rows,d] and hq_out [rows,F] (codes, 0 for removed channels) may be NULL.
+ */
+uint8_t orc_fp8_e4m3_encode(float t);
+void orc_quantize_fp8(const float *x, int64_t n, float scale, uint8_t *codes);
+void orc_pruned_ffn_fp8(int32_t d, int32_t F, const uint8_t *W1q, float s1, const double *b1,
+                        const uint8_t *W2q, float s2, const double *b2, const double *ln_g,
+                        const double *ln_b, const uint8_t *ffn_mask, float sx, float sh,
+                        const double *x, int64_t rows, int32_t act, double eps, int32_t pre_ln,
+                        int32_t add_residual, int32_t bf16, double *y, uint8_t *xq_out, uint8_t *hq_out);
+
 int32_t orc_max_threads(void);
 
 #ifdef __cplusplus

@@ -826,3 +826,137 @@ def test_fp8_dequant_rounding():
     assert np.array_equal(w16, lib16)
     # scale = 1: every code is a bf16 number already
     assert np.array_equal(orc.dequant_fp8(q, 1.0, bf16=True), vals)
+
+
+# ------------------------------------------------ FP8 arithmetic of the pruned FFN (W8A8)
+def test_fp8_e4m3_encode_round_trip_ties_and_saturation():
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    vals = np.array([orc.fp8_e4m3_decode(int(c)) for c in codes])
+    # every finite code is a fixed point (both zeros keep their sign)
+    assert [orc.fp8_e4m3_encode(v) for v in vals] == [int(c) for c in codes]
+    # midpoints of neighbouring positive values go to the code with the even low bit; just beside them to the nearer
+    pos = np.sort(vals[(codes < 0x80)])
+    pc = np.array(sorted(int(c) for c in codes if c < 0x80))
+    for lo, hi, clo, chi in zip(pos[:-1], pos[1:], pc[:-1], pc[1:]):
+        mid = (lo + hi) / 2                      # exact in fp32: at most 5 significant bits
+        even = clo if clo % 2 == 0 else chi
+        assert orc.fp8_e4m3_encode(mid) == even
+        assert orc.fp8_e4m3_encode(np.nextafter(np.float32(mid), np.float32(0))) == clo
+        assert orc.fp8_e4m3_encode(np.nextafter(np.float32(mid), np.float32(1e9))) == chi
+        assert orc.fp8_e4m3_encode(-mid) == even | 0x80
+    # beyond the largest value: saturation, never NaN or a wrapped exponent
+    for t in (448.0001, 463.9, 464.0, 480.0, 512.0, 1e30, float("inf")):
+        assert orc.fp8_e4m3_encode(t) == 0x7E and orc.fp8_e4m3_encode(-t) == 0xFE
+    assert orc.fp8_e4m3_encode(float("nan")) == 0x7F
+    # below half the smallest subnormal: zero with the sign kept; exactly half ties to zero (even)
+    assert orc.fp8_e4m3_encode(2.0 ** -10) == 0x00 and orc.fp8_e4m3_encode(-(2.0 ** -11)) == 0x80
+    assert orc.fp8_e4m3_encode(np.nextafter(np.float32(2.0 ** -10), np.float32(1))) == 0x01
+
+
+def test_fp8_e4m3_encode_against_library_type():
+    """Random fp32 values inside the finite range against PyTorch's fp32 -> float8_e4m3fn conversion."""
+    rng = np.random.default_rng(52)
+    t = np.concatenate([rng.standard_normal(20000) * 3, rng.standard_normal(20000) * 1e-2,
+                        rng.uniform(-448, 448, 20000), rng.standard_normal(5000) * 2e-3]).astype(np.float32)
+    t = t[np.abs(t) <= 448]
+    lib_codes = torch.from_numpy(t).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    ours = orc.quantize_fp8(t, 1.0)
+    assert np.array_equal(ours, lib_codes)
+    # with a scale: the code of the fp32 product with the fp32 reciprocal
+    s = np.float32(0.0371)
+    r = np.float32(1.0) / s
+    lib_codes = torch.from_numpy((t * r).astype(np.float32)).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(orc.quantize_fp8(t, s), lib_codes)
+
+
+def _fp8_ffn_inputs(rng, rows, d, F):
+    x = rng.standard_normal((rows, d)) * 1.5 + 0.3
+    W1 = rng.standard_normal((F, d)) / math.sqrt(d)
+    W2 = rng.standard_normal((F, d)) / math.sqrt(F)
+    b1, b2 = rng.standard_normal(F) * 0.1, rng.standard_normal(d) * 0.1
+    g, b = 1 + 0.1 * rng.standard_normal(d), 0.1 * rng.standard_normal(d)
+    s1, s2 = np.float32(np.abs(W1).max() / 448), np.float32(np.abs(W2).max() / 448)
+    W1q = torch.from_numpy((W1 / s1).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    W2q = torch.from_numpy((W2 / s2).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    return x, W1q, s1, b1, W2q, s2, b2, g, b
+
+
+def _dec(codes):
+    return torch.from_numpy(np.ascontiguousarray(codes)).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+
+
+def test_pruned_ffn_fp8_against_library_steps():
+    """The block rebuilt from library pieces: torch LayerNorm, torch's float8 conversion as the quantiser,
+    float8 -> fp64 decoding and fp64 matmul; outputs to 1e-12, codes bit for bit."""
+    rng = np.random.default_rng(53)
+    rows, d, F = 37, 48, 80
+    x, W1q, s1, b1, W2q, s2, b2, g, b = _fp8_ffn_inputs(rng, rows, d, F)
+    mask = (rng.random(F) < 0.7).astype(np.uint8)
+    sx, sh = np.float32(4.0 / 448), np.float32(6.0 / 448)
+    for act in (0, 1):
+        y, xq, hq = orc.pruned_ffn_fp8(x, W1q, s1, b1, W2q, s2, b2, g, b, sx, sh, ffn_mask=mask, act=act,
+                                       eps=1e-5, bf16=False)
+        xn = torch.nn.functional.layer_norm(torch.from_numpy(x), (d,), torch.from_numpy(g), torch.from_numpy(b), 1e-5)
+        quant = lambda t, s: (t.to(torch.float32) * (np.float32(1) / s)).clamp(-448, 448).to(torch.float8_e4m3fn)
+        xq_l = quant(xn, sx)
+        assert np.array_equal(xq, xq_l.view(torch.uint8).numpy())
+        z = (xq_l.to(torch.float64) @ torch.from_numpy(_dec(W1q)).T) * float(np.float32(sx * s1)) + torch.from_numpy(b1)
+        z = z.to(torch.float32)
+        h = torch.relu(z) if act == 0 else torch.nn.functional.gelu(z.to(torch.float64)).to(torch.float32)
+        hq_l = quant(h, sh).view(torch.uint8).numpy() * mask[None, :]
+        assert np.array_equal(hq, hq_l)
+        yl = (torch.from_numpy(_dec(hq_l)) @ torch.from_numpy(_dec(W2q) * mask[:, None])) * float(np.float32(sh * s2))
+        yl = yl + torch.from_numpy(b2) + torch.from_numpy(x)
+        assert np.abs(y - yl.numpy()).max() < 1e-12
+
+
+def test_pruned_ffn_fp8_exact_when_nothing_rounds():
+    """Inputs on the E4M3 grid, power-of-two scales, small integers: no quantiser rounds anything, so the block
+    must equal the unquantised pruned FFN of the decoded weights exactly."""
+    rng = np.random.default_rng(54)
+    rows, d, F = 19, 16, 24
+    x = rng.integers(-3, 4, (rows, d)).astype(np.float64) / 4         # multiples of 1/4, |x| <= 3/4
+    W1 = rng.integers(-2, 3, (F, d)).astype(np.float64) / 2
+    W2 = rng.integers(-2, 3, (F, d)).astype(np.float64) / 4
+    b1 = rng.integers(-2, 3, F).astype(np.float64) / 2
+    b2 = rng.integers(-4, 5, d).astype(np.float64) / 8
+    s1, s2, sx, sh = 0.5, 0.25, 0.125, 0.5
+    enc = lambda a, s: np.array([orc.fp8_e4m3_encode(v / s) for v in a.ravel()], np.uint8).reshape(a.shape)
+    W1q, W2q = enc(W1, s1), enc(W2, s2)
+    assert np.array_equal(_dec(W1q) * s1, W1) and np.array_equal(_dec(W2q) * s2, W2)
+    mask = (rng.random(F) < 0.6).astype(np.uint8)
+    y, xq, hq = orc.pruned_ffn_fp8(x, W1q, s1, b1, W2q, s2, b2, None, None, sx, sh, ffn_mask=mask, act=0,
+                                   pre_ln=False, bf16=False)
+    assert np.array_equal(_dec(xq) * sx, x)
+    # hidden values: |z| <= 16 * (3/4) * 1 + 1 = 13, multiples of 1/8 -> /sh = multiples of 1/4 below 32: exact only
+    # where at most 4 significant bits are needed, so compare against the plain FFN fed with the decoded hidden
+    h = np.maximum(x @ W1.T + b1, 0) * mask[None, :]
+    hd = _dec(hq) * sh
+    grid = np.array([orc.fp8_e4m3_decode(orc.fp8_e4m3_encode(v / sh)) * sh for v in h.ravel()]).reshape(h.shape)
+    assert np.array_equal(hd, grid)
+    assert np.array_equal(y, x + hd @ (W2 * mask[:, None]) + b2)
+    # and wherever the hidden value is on the grid the whole block is the unquantised one
+    on_grid = (hd == h).all(axis=1)
+    assert on_grid.any()
+    yref = x + h @ (W2 * mask[:, None]) + b2
+    assert np.array_equal(y[on_grid], yref[on_grid])
+
+
+def test_pruned_ffn_fp8_error_bound_against_unquantised():
+    """E4M3 has 4 significant bits: each quantiser changes a value by at most 2^-4 relative (inside the range), so
+    the block stays within a few percent of the fp64 FFN on the same (decoded) weights."""
+    rng = np.random.default_rng(55)
+    rows, d, F = 64, 128, 192
+    x, W1q, s1, b1, W2q, s2, b2, g, b = _fp8_ffn_inputs(rng, rows, d, F)
+    W1, W2 = _dec(W1q) * s1, _dec(W2q) * s2
+    xn = torch.nn.functional.layer_norm(torch.from_numpy(x), (d,), torch.from_numpy(g), torch.from_numpy(b), 1e-5).numpy()
+    h = np.maximum(xn @ W1.T + b1, 0)
+    ref = x + h @ W2 + b2
+    sx, sh = np.float32(np.abs(xn).max() / 448), np.float32(np.abs(h).max() / 448)
+    y, xq, hq = orc.pruned_ffn_fp8(x, W1q, s1, b1, W2q, s2, b2, g, b, sx, sh, act=0, bf16=False)
+    upd, upd_ref = y - x, ref - x
+    rel = np.linalg.norm(upd - upd_ref) / np.linalg.norm(upd_ref)
+    assert 1e-3 < rel < 0.06                     # quantisation is visible, and bounded
+    # decoded activations are within half a grid step (2^-4 relative) of what they encode, subnormals aside
+    big = np.abs(xn) > sx * 2.0 ** -5
+    assert (np.abs(_dec(xq) * sx - xn)[big] <= np.abs(xn)[big] * 2.0 ** -4 * 1.0001).all()
