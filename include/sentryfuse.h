@@ -188,6 +188,57 @@ int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t layer,
                                       const int32_t *n_groups, const int32_t *ffn_idx,
                                       const sf_compact_layer *compact_host, void *stream);
 
+/* ------------------------------------------------------------------------
+ * FP8 arithmetic for the pruned FFN (same experiment; the paper does not say
+ * how its FP8 models compute).  Here both operands of the two FFN contractions
+ * are E4M3 codes with one fp32 scale per tensor (W8A8, scales fixed offline),
+ * products are exact, sums are fp32 on the matrix cores:
+ *     xq = Q(LN2(x), sx)                  (LayerNorm in fp32, quantised from fp32)
+ *     z  = (sum_k dec(xq) dec(W1q)) * (sx*s1) + b1        (fp32)
+ *     hq = Q(act(z), sh)
+ *     y  = (sum_f dec(hq) dec(W2q)) * (sh*s2) + b2 (+ x)  -> bf16
+ * Q(t, s) = E4M3(t * (1/s)) with the reciprocal and the product in fp32, round
+ * to nearest (ties to the even code), saturating at +-448.  NaN gives 0x7F in
+ * sf_quantize_fp8 and after LayerNorm; the code of a NaN hidden value is
+ * unspecified.
+ *
+ * sf_ffn_fp8: compact FFN weights of one layer for all P patterns.
+ *   Fp8 = sf_ffn_fp8_padded(k_ffn): k_ffn rounded up to a multiple of 128
+ *   W1q  [P, Fp8, d]  codes of the kept channels (ascending), zero above F'
+ *   b1   [P, Fp8]     bf16, zeros above F' (NULL iff the dense b1 is NULL)
+ *   W2Tq [P, d, Fp8]  W2Tq[n, j] = W2q[ffn_idx[j], n], zero above F'
+ *   b2, ln2_g, ln2_b [d] bf16: the dense arrays;  s1, s2: the dense scales
+ *   sx, sh: scales of the block's input (after LayerNorm when pre_ln) and of
+ *           the hidden activations
+ * sf_compact_ffn_fp8 fills W1q, b1, W2Tq from a dense FP8 layer (uses W1, W2,
+ * b1 of `dense_host` and this layer's slice of ffn_idx; pure byte movement,
+ * bit-exact); the caller sets k_ffn and the other fields.
+ * sf_quantize_fp8: codes[i] = Q(x[i], scale), x of dtype SF_F32 or SF_BF16
+ * (16-byte aligned), codes 8-byte aligned.
+ * sf_pruned_ffn_fp8_forward: X, Y [B*L, d] bf16 (desc->dtype must be SF_BF16),
+ * pattern_id as in sf_pruned_ffn_forward.  xq_out [B*L, d], hq_out [B*L, Fp8]
+ * (16-byte aligned) receive the codes when not NULL.  Limits: d a multiple of
+ * 128 (256 <= d, d <= 4096 with pre_ln), L >= 192, k_ffn > 128; anything else
+ * returns SF_ERR_SHAPE / SF_ERR_UNSUPPORTED before a kernel is launched.
+ */
+typedef struct sf_ffn_fp8 {
+    int32_t k_ffn;             /* F' */
+    int32_t reserved;
+    void *W1q, *b1, *W2Tq;
+    const void *b2, *ln2_g, *ln2_b;
+    float s1, s2, sx, sh;
+} sf_ffn_fp8;
+int32_t sf_ffn_fp8_padded(int32_t k_ffn);
+int32_t sf_compact_ffn_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense_host,
+                           const int32_t *ffn_idx, const sf_ffn_fp8 *ffn_host, void *stream);
+int32_t sf_quantize_fp8(const void *x, int32_t dtype, int64_t n, float scale, uint8_t *codes,
+                        void *stream);
+size_t sf_pruned_ffn_fp8_workspace_bytes(const sf_desc *desc, int32_t k_ffn);
+int32_t sf_pruned_ffn_fp8_forward(const sf_desc *desc, const sf_ffn_fp8 *ffn_host, const void *X,
+                                  const int32_t *pattern_id, int32_t pre_ln, int32_t add_residual,
+                                  void *Y, uint8_t *xq_out, uint8_t *hq_out, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
 /* Element strides of a [B, heads, L, dh] tensor whose last dimension is
  * contiguous (for V with v_transposed: a [B, groups, dh, L] tensor whose L
  * dimension is contiguous and `l` is the stride between dh rows). */

@@ -300,9 +300,10 @@ def quantize_fp8(x, scale: float) -> np.ndarray:
 
 def pruned_ffn_fp8(x, W1q, s1: float, b1, W2q, s2: float, b2, ln_g, ln_b, sx: float, sh: float, ffn_mask=None,
                    act: int = 0, eps: float = 1e-5, pre_ln: bool = True, add_residual: bool = True,
-                   bf16: bool = True):
+                   bf16: bool = True, xq_forced=None, hq_forced=None, want_z: bool = False):
     """FFN block in FP8 arithmetic (see orc_pruned_ffn_fp8).  W1q, W2q [F,d] uint8 codes (dense layout).
-    Returns (y [rows,d] fp64, xq [rows,d] uint8, hq [rows,F] uint8)."""
+    xq_forced [rows,d] / hq_forced [rows,F]: codes to use instead of the block's own.
+    Returns (y [rows,d] fp64, xq [rows,d] uint8, hq [rows,F] uint8) and, with want_z, z [rows,F]."""
     x = _f64(x)
     d = x.shape[-1]
     rows = x.size // d
@@ -315,12 +316,15 @@ def pruned_ffn_fp8(x, W1q, s1: float, b1, W2q, s2: float, b2, ln_g, ln_b, sx: fl
     y = np.empty_like(x)
     xq = np.empty((rows, d), np.uint8)
     hq = np.empty((rows, F), np.uint8)
+    xf = None if xq_forced is None else np.ascontiguousarray(xq_forced, dtype=np.uint8).reshape(rows, d)
+    hf = None if hq_forced is None else np.ascontiguousarray(hq_forced, dtype=np.uint8).reshape(rows, F)
+    z = np.empty((rows, F), np.float64) if want_z else None
     lib().orc_pruned_ffn_fp8(C.c_int32(d), C.c_int32(F), _p(W1q), C.c_float(float(s1)), _p(b1), _p(W2q),
                              C.c_float(float(s2)), _p(b2), _p(ln_g), _p(ln_b), _p(fm), C.c_float(float(sx)),
                              C.c_float(float(sh)), _p(x), C.c_int64(rows), C.c_int32(act), C.c_double(eps),
-                             C.c_int32(int(pre_ln)), C.c_int32(int(add_residual)), C.c_int32(int(bf16)), _p(y),
-                             _p(xq), _p(hq))
-    return y, xq, hq
+                             C.c_int32(int(pre_ln)), C.c_int32(int(add_residual)), C.c_int32(int(bf16)), _p(xf),
+                             _p(hf), _p(y), _p(xq), _p(hq), _p(z))
+    return (y, xq, hq, z) if want_z else (y, xq, hq)
 
 
 def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,

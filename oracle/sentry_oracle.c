@@ -544,7 +544,8 @@ void orc_pruned_ffn_fp8(int32_t d, int32_t F, const uint8_t *W1q, float s1, cons
                         const uint8_t *W2q, float s2, const double *b2, const double *ln_g,
                         const double *ln_b, const uint8_t *ffn_mask, float sx, float sh,
                         const double *x, int64_t rows, int32_t act, double eps, int32_t pre_ln,
-                        int32_t add_residual, int32_t bf16, double *y, uint8_t *xq_out, uint8_t *hq_out)
+                        int32_t add_residual, int32_t bf16, const uint8_t *xq_forced,
+                        const uint8_t *hq_forced, double *y, uint8_t *xq_out, uint8_t *hq_out, double *z_out)
 {
     double *xn = (double *)malloc(sizeof(double) * (size_t)rows * d);
     float *t32 = (float *)malloc(sizeof(float) * (size_t)rows * (d > F ? d : F));
@@ -554,19 +555,22 @@ void orc_pruned_ffn_fp8(int32_t d, int32_t F, const uint8_t *W1q, float s1, cons
     else memcpy(xn, x, sizeof(double) * (size_t)rows * d);
     for (int64_t i = 0; i < rows * d; ++i) t32[i] = (float)xn[i];
     orc_quantize_fp8(t32, rows * d, sx, xq);
+    if (xq_forced) memcpy(xq, xq_forced, (size_t)rows * d);
     const volatile float os1 = sx * s1, os2 = sh * s2;        /* fp32 products */
 
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r)
         for (int32_t f = 0; f < F; ++f) {
-            if (ffn_mask && !ffn_mask[f]) { t32[r * F + f] = 0.f; continue; }
+            if (ffn_mask && !ffn_mask[f]) { t32[r * F + f] = 0.f; if (z_out) z_out[r * F + f] = 0.0; continue; }
             double acc = 0.0;                                 /* products and sum exact in double */
             for (int32_t k = 0; k < d; ++k)
                 acc += orc_fp8_e4m3_decode(xq[r * d + k]) * orc_fp8_e4m3_decode(W1q[(int64_t)f * d + k]);
             acc = acc * (double)os1 + (b1 ? b1[f] : 0.0);
+            if (z_out) z_out[r * F + f] = (double)(float)acc;
             t32[r * F + f] = (float)activation((double)(float)acc, act);
         }
     orc_quantize_fp8(t32, rows * F, sh, hq);
+    if (hq_forced) memcpy(hq, hq_forced, (size_t)rows * F);
     if (ffn_mask)
         for (int64_t r = 0; r < rows; ++r)
             for (int32_t f = 0; f < F; ++f)

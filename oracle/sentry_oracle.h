@@ -251,7 +251,11 @@ void orc_dequant_fp8(const uint8_t *q, int64_t n, float scale, int32_t bf16, dou
  * contribute nothing.  W1q, W2q [F,d] codes of the dense layout (one row per channel).
  *   orc_fp8_e4m3_encode: the code of one fp32 value.
  *   orc_quantize_fp8:    codes[i] = Q(x[i], scale).
- *   orc_pruned_ffn_fp8:  the block; xq_out [rows,d] and hq_out [rows,F] (codes, 0 for removed channels) may be NULL.
+ *   orc_pruned_ffn_fp8:  the block; xq_out [rows,d], hq_out [rows,F] (codes, 0 for removed channels) and z_out
+ *                        [rows,F] (the fp32 value z, 0 for removed channels) may be NULL.  xq_forced / hq_forced
+ *                        (NULL = none) replace the block's own codes of the input / of the hidden activations:
+ *                        a code is a floating-point decision, and a test that has checked another
+ *                        implementation's decisions compares the rest of the block on those.
  */
 uint8_t orc_fp8_e4m3_encode(float t);
 void orc_quantize_fp8(const float *x, int64_t n, float scale, uint8_t *codes);
@@ -259,7 +263,8 @@ void orc_pruned_ffn_fp8(int32_t d, int32_t F, const uint8_t *W1q, float s1, cons
                         const uint8_t *W2q, float s2, const double *b2, const double *ln_g,
                         const double *ln_b, const uint8_t *ffn_mask, float sx, float sh,
                         const double *x, int64_t rows, int32_t act, double eps, int32_t pre_ln,
-                        int32_t add_residual, int32_t bf16, double *y, uint8_t *xq_out, uint8_t *hq_out);
+                        int32_t add_residual, int32_t bf16, const uint8_t *xq_forced,
+                        const uint8_t *hq_forced, double *y, uint8_t *xq_out, uint8_t *hq_out, double *z_out);
 
 int32_t orc_max_threads(void);
 

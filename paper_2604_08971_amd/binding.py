@@ -26,7 +26,8 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_pruned_ffn_workspace_bytes", "sf_pruned_ffn_forward", "sf_encoder_workspace_bytes",
            "sf_encoder_forward", "sf_profile_begin", "sf_profile_end", "sf_compact_moe_experts",
            "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search",
-           "sf_compact_heads_channels_fp8"]
+           "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8", "sf_quantize_fp8",
+           "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -66,6 +67,12 @@ class SfDenseLayerFp8(C.Structure):
                 + [(n, C.c_void_p) for n in ("bq", "bk", "bv", "bo", "b1", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")])
 
 
+class SfFfnFp8(C.Structure):
+    _fields_ = ([("k_ffn", C.c_int32), ("reserved", C.c_int32)]
+                + [(n, C.c_void_p) for n in ("W1q", "b1", "W2Tq", "b2", "ln2_g", "ln2_b")]
+                + [(n, C.c_float) for n in ("s1", "s2", "sx", "sh")])
+
+
 class SfMoeDense(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _MOE_DENSE_FIELDS]
 
@@ -93,12 +100,13 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.sf_last_error.restype = C.c_char_p
         for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes",
-                  "sf_moe_ffn_workspace_bytes"):
+                  "sf_moe_ffn_workspace_bytes", "sf_pruned_ffn_fp8_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
                   "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward", "sf_gate_eval",
-                  "sf_budget_search", "sf_compact_heads_channels_fp8"):
+                  "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
+                  "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -119,6 +127,14 @@ def lib():
         L.sf_encoder_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)]
         L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
         L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        L.sf_pruned_ffn_fp8_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        L.sf_ffn_fp8_padded.argtypes = [C.c_int32]
+        L.sf_compact_ffn_fp8.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayerFp8), C.c_void_p,
+                                         C.POINTER(SfFfnFp8), C.c_void_p]
+        L.sf_quantize_fp8.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
+        L.sf_pruned_ffn_fp8_forward.argtypes = [C.POINTER(SfDesc), C.POINTER(SfFfnFp8), C.c_void_p, C.c_void_p,
+                                                C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_compact_moe_experts.argtypes = [C.POINTER(SfDesc), C.POINTER(SfMoeDense), C.c_void_p, C.c_void_p,
                                              C.POINTER(SfMoeCompact), C.c_void_p]
         L.sf_moe_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfMoeCompact)]
@@ -404,6 +420,70 @@ def pruned_ffn_forward(desc: SfDesc, layer: CompactLayer, X: torch.Tensor,
                                      int(pre_ln), int(add_residual), _ptr(Y), _ptr(ws), ws.numel(), _stream())
     _check(rc, "sf_pruned_ffn_forward")
     return Y
+
+
+# ---------------------------------------------------------- pruned FFN in FP8 arithmetic
+class CompactFfnFp8:
+    """FFN weights of one layer as E4M3 codes, compacted for all patterns: owns the padded device buffers."""
+
+    def __init__(self, desc: SfDesc, dense8: Dict[str, torch.Tensor], scales: Dict[str, float], k_ffn: int,
+                 sx: float, sh: float):
+        P, d = desc.P, desc.d_model
+        dev = dense8["W1"].device
+        self.k_ffn = int(k_ffn)
+        self.Fp8 = int(lib().sf_ffn_fp8_padded(self.k_ffn))
+        self.dense8 = dense8
+        self.W1q = torch.empty((P, self.Fp8, d), dtype=torch.uint8, device=dev)
+        self.W2Tq = torch.empty((P, d, self.Fp8), dtype=torch.uint8, device=dev)
+        self.b1 = (torch.empty((P, self.Fp8), dtype=dense8["b1"].dtype, device=dev)
+                   if dense8.get("b1") is not None else None)
+        self.struct = SfFfnFp8(self.k_ffn, 0, _ptr(self.W1q), _ptr(self.b1), _ptr(self.W2Tq), _ptr(dense8.get("b2")),
+                               _ptr(dense8.get("ln2_g")), _ptr(dense8.get("ln2_b")), float(scales["W1"]),
+                               float(scales["W2"]), float(sx), float(sh))
+
+
+def compact_ffn_fp8(desc: SfDesc, layer: int, dense8: Dict[str, torch.Tensor], scales: Dict[str, float],
+                    masks: Dict[str, torch.Tensor], k_ffn: int, sx: float, sh: float) -> CompactFfnFp8:
+    """dense8: W1, W2 [d_ff, d] uint8 (E4M3 codes), b1, b2, ln2_g, ln2_b in bf16; scales: W1, W2."""
+    for n in ("W1", "W2"):
+        assert dense8[n].dtype == torch.uint8 and dense8[n].is_contiguous(), n
+    cf = CompactFfnFp8(desc, dense8, scales, k_ffn, sx, sh)
+    nul = C.c_void_p(None)
+    ds = SfDenseLayerFp8(nul, nul, nul, nul, _ptr(dense8["W1"]), _ptr(dense8["W2"]), 0.0, 0.0, 0.0, 0.0,
+                         float(scales["W1"]), float(scales["W2"]), nul, nul, nul, nul, _ptr(dense8.get("b1")),
+                         _ptr(dense8.get("b2")), nul, nul, _ptr(dense8.get("ln2_g")), _ptr(dense8.get("ln2_b")))
+    rc = lib().sf_compact_ffn_fp8(C.byref(desc), layer, C.byref(ds), _ptr(masks["ffn_idx"]), C.byref(cf.struct),
+                                  _stream())
+    _check(rc, "sf_compact_ffn_fp8")
+    return cf
+
+
+def quantize_fp8(x: torch.Tensor, scale: float) -> torch.Tensor:
+    """E4M3 codes of x / scale (x fp32 or bf16, contiguous)."""
+    assert x.is_contiguous() and x.dtype in (torch.float32, torch.bfloat16)
+    codes = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    rc = lib().sf_quantize_fp8(_ptr(x), SF_F32 if x.dtype == torch.float32 else SF_BF16, x.numel(), float(scale),
+                               _ptr(codes), _stream())
+    _check(rc, "sf_quantize_fp8")
+    return codes
+
+
+def pruned_ffn_fp8_forward(desc: SfDesc, ffn: CompactFfnFp8, X: torch.Tensor,
+                           pattern_id: Optional[torch.Tensor] = None, pre_ln: bool = True,
+                           add_residual: bool = True, want_codes: bool = False, ws: Optional[torch.Tensor] = None):
+    """X [B, L, d] bf16.  Returns Y, or (Y, xq [B*L, d], hq [B*L, Fp8]) with want_codes."""
+    assert X.is_contiguous() and X.dtype == torch.bfloat16
+    Y = torch.empty_like(X)
+    rows = X.numel() // X.shape[-1]
+    xq = torch.empty((rows, X.shape[-1]), dtype=torch.uint8, device=X.device) if want_codes else None
+    hq = torch.empty((rows, ffn.Fp8), dtype=torch.uint8, device=X.device) if want_codes else None
+    if ws is None:
+        ws = workspace(lib().sf_pruned_ffn_fp8_workspace_bytes(C.byref(desc), ffn.k_ffn), X.device)
+    rc = lib().sf_pruned_ffn_fp8_forward(C.byref(desc), C.byref(ffn.struct), _ptr(X), _ptr(pattern_id), int(pre_ln),
+                                         int(add_residual), _ptr(Y), _ptr(xq), _ptr(hq), _ptr(ws), ws.numel(),
+                                         _stream())
+    _check(rc, "sf_pruned_ffn_fp8_forward")
+    return (Y, xq, hq) if want_codes else Y
 
 
 # ---------------------------------------------------------- Sparse-MoE FFN with pruned experts

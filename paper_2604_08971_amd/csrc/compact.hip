@@ -516,3 +516,41 @@ extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t la
     transpose8(dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, dense->so);
     return check_launch("compact_heads_channels_fp8");
 }
+
+// FFN weights kept as E4M3 codes for the FP8 arithmetic path: the same gathers on bytes, nothing is decoded.
+extern "C" int32_t sf_compact_ffn_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense,
+                                      const int32_t *ffn_idx, const sf_ffn_fp8 *f, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!dense || !f || !ffn_idx) return fail(SF_ERR_INVALID_ARG, "compact_ffn_fp8: NULL argument");
+    if (layer < 0 || layer >= D.nl) return fail(SF_ERR_INVALID_ARG, "compact_ffn_fp8: layer %d out of range", layer);
+    if (f->k_ffn < 1 || f->k_ffn > D.F) return fail(SF_ERR_INVALID_ARG, "compact_ffn_fp8: k_ffn out of range");
+    if (!dense->W1 || !dense->W2 || !f->W1q || !f->W2Tq)
+        return fail(SF_ERR_INVALID_ARG, "compact_ffn_fp8: NULL weight pointer");
+    if (dense->b1 && !f->b1) return fail(SF_ERR_INVALID_ARG, "compact_ffn_fp8: compact bias buffer missing");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t es = elem_size(D.dtype);
+    const int P = D.P, d = D.d, kf = f->k_ffn;
+    const int Fp8 = (int)align_up((size_t)kf, 128);
+    const int32_t *fi = ffn_idx + (size_t)layer * P * D.F;
+    auto region = [&](const void *src, void *dst) {
+        GatherRegion r{};
+        r.src = src; r.dst = dst; r.idx = fi; r.n_dev = nullptr;
+        r.idx_stride = D.F; r.block = 1; r.n_static = kf; r.rows = Fp8;
+        r.dst_pstride = (size_t)Fp8;
+        return r;
+    };
+    GatherRegions wr{};
+    wr.r[wr.n++] = region(dense->W1, f->W1q);
+    gather_rows(st, wr, (size_t)d, P);
+    if (dense->b1) {
+        GatherRegions br{};
+        br.r[br.n++] = region(dense->b1, f->b1);
+        gather_rows(st, br, es, P);
+    }
+    dim3 grid(ceil_div(Fp8, 32), ceil_div(d, 32), P);
+    hipLaunchKernelGGL(gather_transpose_kernel<uint8_t>, grid, dim3(256), 0, st, (const uint8_t *)dense->W2,
+                       (uint8_t *)f->W2Tq, fi, D.F, 1, kf, Fp8, d, (size_t)d * Fp8);
+    return check_launch("compact_ffn_fp8");
+}

@@ -32,6 +32,10 @@ struct GemmArgs {
                                                          // contiguous ranges (rows of unequal cost, e.g. n_lim / k_lim)
     int r_f32, c_f32;                                    // bf16 GEMM only: R / C hold fp32 (the residual stream)
     int64_t vt_b, vt_n;                                  // EPI_VT: strides of b and n (i contiguous)
+    int f8;                                              // gemm_fp8() only: A and W hold E4M3 codes (lda, ldw, w_pstride in
+                                                         // elements = bytes), K % 128 == 0
+    float out_scale;                                     // f8: factor of the sum of code products (the two tensor scales)
+    int c_f8; float c_scale;                             // f8: C receives E4M3 codes of act(value) * c_scale (ldc in bytes)
     void *VT; int vt_from;                               // large bf16 row-major problems only (gemm_takes_vt_split):
                                                          // features n >= vt_from go to VT[b, n - vt_from, i] (strides
                                                          // vt_b, vt_n, both % 8 == 0; vt_from % 8 == 0) instead of C
@@ -40,6 +44,9 @@ struct GemmArgs {
 // dtype SF_BF16: bf16 MFMA, fp32 accumulate (K % 8 == 0, lda/ldw/ldr % 8 == 0,
 // ldc % 4 == 0, 16-byte aligned bases).  dtype SF_F32: fp32 FMA.
 int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st);
+
+// E4M3 x E4M3 -> fp32 accumulate (large row-major problems only, else SF_ERR_UNSUPPORTED / SF_ERR_SHAPE).
+int32_t gemm_fp8(const GemmArgs &a, hipStream_t st);
 
 // True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).
 bool gemm_takes_row_map(int dtype, const GemmArgs &a);

@@ -82,6 +82,7 @@ struct Tile { int b, m0, nt0, p, N, nk, vt; };
 // XCD's L2).  Slots past the end, samples with a negative pattern and tiles beyond the pattern's own
 // width are skipped.  Every wave of the workgroup calls this with the same arguments, so loader and MFMA
 // waves see the same sequence.
+template <int KSTEP>
 __device__ __forceinline__ bool next_tile(const GemmArgs &a, int tiles_m, int tiles_n, int total_tiles, int per_xcd,
                                           int stride, int &s, Tile &t)
 {
@@ -118,7 +119,7 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int tiles_m, int ti
             t.N = a.n_lim ? min(a.N, a.n_lim[t.p]) : a.N;
         }
         if (t.nt0 >= t.N) continue;
-        t.nk = (a.k_lim ? min(a.K, a.k_lim[t.p]) : a.K) / BKT;
+        t.nk = (a.k_lim ? min(a.K, a.k_lim[t.p]) : a.K) / KSTEP;
         if (t.nk < 1) continue;
         s += stride;
         return true;
@@ -126,12 +127,22 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int tiles_m, int ti
     return false;
 }
 
-template <int ACT>
-__global__ __launch_bounds__(64 * (NCW + NLW)) __attribute__((amdgpu_waves_per_eu(3, 3)))
-void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd)
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+// F8: A and W hold E4M3 codes (one byte per element).  A K tile is still 128 bytes of a row, i.e. 128 elements,
+// so the loaders, the LDS ring and its layout are those of the bf16 kernel byte for byte; the MFMA waves issue
+// v_mfma_f32_32x32x64_f8f6f4 (twice the multiply-adds per matrix-pipe cycle of the bf16 instruction, 32 bytes of a
+// row per lane and instruction).  Which 64 of the 128 k of a row an instruction sees only has to agree between
+// the two operands: lane (l32, lhi) takes 16-byte chunks 4m + lhi and 4m + 2 + lhi for instruction m, the two
+// reads the bf16 loop issues for k-steps 2m and 2m + 1.
+template <int ACT, bool F8>
+__device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd)
 {
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NXS][X rows][64] | [NWS][W rows][64]
+    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NXS][X rows][128 bytes] | [NWS][W rows][128 bytes]
+    constexpr int ESZ = F8 ? 1 : 2;                           // bytes per element of A and W
+    constexpr int KSTEP = 128 / ESZ;                          // elements of K per ring slot
 
     const int stride = gridDim.x / N_XCD;                     // workgroups per XCD
     const int s0 = blockIdx.x / N_XCD;                        // this workgroup's first slot
@@ -153,11 +164,11 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         uint32_t xoff[LPW], woff[LPW];
         int ktx = 0, ktw = 0, xs = 0, wsl = 0;
         auto open_x = [&]() {
-            vx = next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sx, tx);
+            vx = next_tile<KSTEP>(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sx, tx);
             ktx = 0;
             if (!vx) return;
-            xbase = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.A) +
-                                                   (a.row_map ? (int64_t)0 : ((int64_t)tx.b * a.L + tx.m0) * a.lda));
+            xbase = static_cast<const char *>(a.A) +
+                    (a.row_map ? (int64_t)0 : ((int64_t)tx.b * a.L + tx.m0) * a.lda) * ESZ;
             const int32_t *rmap = a.row_map ? a.row_map + (int64_t)tx.b * a.L + tx.m0 : nullptr;
             const int rows_x = min(BM, a.L - tx.m0);
 #pragma unroll
@@ -166,27 +177,26 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                 const int t = (lane & 15) ^ (sr & 7);
                 const int r = sr * 2 + (t >> 3), c = t & 7;
                 const int rx = min(r, rows_x - 1);
-                xoff[j] = ((uint32_t)(rmap ? rmap[rx] : rx) * (uint32_t)a.lda + (uint32_t)(c * 8)) * 2u;
+                xoff[j] = (uint32_t)(rmap ? rmap[rx] : rx) * (uint32_t)a.lda * (uint32_t)ESZ + (uint32_t)(c * 16);
             }
         };
         auto open_w = [&]() {
-            vw = next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sw, tw);
+            vw = next_tile<KSTEP>(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sw, tw);
             ktw = 0;
             if (!vw) return;
-            wbase = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.W) + (int64_t)tw.p * a.w_pstride +
-                                                   (int64_t)(a.n0 + tw.nt0) * a.ldw);
+            wbase = static_cast<const char *>(a.W) + ((int64_t)tw.p * a.w_pstride + (int64_t)(a.n0 + tw.nt0) * a.ldw) * ESZ;
             const int rows_w = min(BN, tw.N - tw.nt0);
 #pragma unroll
             for (int j = 0; j < LPW; ++j) {
                 const int sr = (lw * LPW + j) * 4 + (lane >> 4);
                 const int t = (lane & 15) ^ (sr & 7);
                 const int r = sr * 2 + (t >> 3), c = t & 7;
-                woff[j] = (uint32_t)(min(r, rows_w - 1) * (int)a.ldw + c * 8) * 2u;
+                woff[j] = (uint32_t)(min(r, rows_w - 1) * (int)a.ldw) * (uint32_t)ESZ + (uint32_t)(c * 16);
             }
         };
         auto issue_x = [&]() {
             __bf16 *base = smem + xs * XSLOT;
-            const int64_t koff = (int64_t)ktx * BKT * 2;
+            const int64_t koff = (int64_t)ktx * 128;
 #pragma unroll
             for (int j = 0; j < LPW; ++j)
                 __builtin_amdgcn_global_load_lds((glb_void *)(xbase + koff + xoff[j]),
@@ -196,7 +206,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         };
         auto issue_w = [&]() {
             __bf16 *base = smem + NXS * XSLOT + wsl * WSLOT;
-            const int64_t koff = (int64_t)ktw * BKT * 2;
+            const int64_t koff = (int64_t)ktw * 128;
 #pragma unroll
             for (int j = 0; j < LPW; ++j)
                 __builtin_amdgcn_global_load_lds((glb_void *)(wbase + koff + woff[j]),
@@ -212,7 +222,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         if (vx) issue_x();
         if (vw) issue_w();
         if (vx) { issue_x(); x_ahead = true; }
-        while (next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sc, tc)) {
+        while (next_tile<KSTEP>(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sc, tc)) {
             for (int kt = 0; kt < tc.nk; ++kt) {
                 if (x_ahead) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");   // X(g), W(g) landed
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -246,7 +256,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     uint32_t xslot = 0, wslot = 0;          // byte offsets of the ring slots of the next step
     int sm = s0;
     Tile tl;
-    while (next_tile(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sm, tl)) {
+    while (next_tile<KSTEP>(a, tiles_m, tiles_n, total_tiles, per_xcd, stride, sm, tl)) {
     // The accumulators start at the bias (fp32), so the epilogue has no bias pass.  Entry q*4+e of lane
     // (l32, lhi) of MFMA tile (tn, tm) is feature tn*32 + q*8 + lhi*4 + e.  The lane number goes through an
     // opaque copy so that these per-tile values are not hoisted out of the tile loop into long-lived registers.
@@ -255,7 +265,9 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         int lb = lane;
         asm volatile("" : "+v"(lb));
         const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)tl.p * a.bias_pstride + a.n0 : nullptr;
-        if (tl.vt) {
+        // F8: the sum of code products is multiplied by out_scale in the epilogue, so the bias enters divided by it
+        const float bscale = F8 ? 1.0f / a.out_scale : 1.0f;
+        if (!F8 && tl.vt) {
             // every entry of MFMA tile (tn, tm) of this lane belongs to feature wnv*128 + tm*32 + l32
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
@@ -278,7 +290,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float f = (float)bv[e];
+                    const float f = F8 ? (float)bv[e] * bscale : (float)bv[e];
 #pragma unroll
                     for (int j = 0; j < TM; ++j) acc[i][j][q * 4 + e] = f;
                 }
@@ -291,7 +303,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         __builtin_amdgcn_s_barrier();                             // barrier of this step
         asm volatile("" ::: "memory");
         // xb: base of the four-fragment side, wb: base of the two-fragment side
-        const uint32_t xb = tl.vt ? wlane_vt + wslot : xlane + xslot, wb = tl.vt ? xlane_vt + xslot : wlane + wslot;
+        const uint32_t xb = !F8 && tl.vt ? wlane_vt + wslot : xlane + xslot, wb = !F8 && tl.vt ? xlane_vt + xslot : wlane + wslot;
         xdone = xslot;
         wdone = wslot;
         xslot = (xslot + XSLOT * 2 == NXS * XSLOT * 2) ? 0u : xslot + XSLOT * 2;
@@ -300,6 +312,32 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
         // the X fragments are single-buffered and X fragment j of the next k-step is read right after
         // its last use in this k-step, so every read has about six MFMAs of cover.  The order below is
         // kept as written (sched_barrier), one address register per operand and k-step.
+        if constexpr (F8) {
+            // Two instructions of K = 64 per (MFMA tile, ring slot), 8 registers per operand.  Next to the 128
+            // accumulators there is room for three operands only: the two W fragments of instruction m stay
+            // resident, the X fragment is a single buffer refilled right after the second instruction that
+            // uses it has issued.  The wait for that read is covered by the other MFMA wave of the SIMD.
+            auto rd32 = [&](uint32_t base, int m) {
+                const i32x4 lo = *reinterpret_cast<const i32x4 *>(smem_raw + (base ^ ((uint32_t)(2 * m) << 5)));
+                const i32x4 hi = *reinterpret_cast<const i32x4 *>(smem_raw + (base ^ ((uint32_t)(2 * m + 1) << 5)));
+                return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            };
+            i32x8 xv, wv[2];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                wv[0] = rd32(wb, m); wv[1] = rd32(wb + 4096, m);
+                xv = rd32(xb, m);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    acc[0][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wv[0], xv, acc[0][j], 0, 0, 0, 0, 0, 0);
+                    acc[1][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wv[1], xv, acc[1][j], 0, 0, 0, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (j + 1 < TM) xv = rd32(xb + (uint32_t)(j + 1) * 4096u, m);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else {
         bf16x8 xf[TM], wf[2][TN];
         auto rd = [&](uint32_t addr) { return *reinterpret_cast<const bf16x8 *>(smem_raw + addr); };
         {
@@ -322,6 +360,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                 }
                 __builtin_amdgcn_sched_barrier(0);      // keep exactly this order: MFMA MFMA read(s)
             }
+        }
         }
     } while (++kt < tl.nk);
     // Every MFMA wave is done reading the step consumed last (its fragments went into MFMAs that have
@@ -349,7 +388,52 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     const int64_t grow0 = (int64_t)tl.b * a.L;
     const bool inside = mrow0 + 128 <= a.L && ncol0 + 64 <= Np;   // uniform: the whole sub-tile exists, no per-row checks
 
-    if (tl.vt || (!a.c_f32 && !a.R)) {
+    const float os = F8 ? a.out_scale : 1.0f;                      // F8: value = sum of code products x out_scale
+    bool stored = false;
+    if constexpr (F8) {
+        if (a.c_f8) {
+            // E4M3 codes out (the quantised hidden activations): code = E4M3(act(value) * c_scale), saturating.
+            // The whole 128 x 64 sub-tile is staged at once: staged row r (128 bytes) holds the 64 codes of token r
+            // and, in its upper half, those of token r + 64.  A lane owns 4 consecutive features per (tile, q):
+            // two packed conversions make one dword.
+            stored = true;
+            const float cs = a.c_scale;
+            const uint32_t wbase8 = (uint32_t)lay(l32e, 0) * 2u + (uint32_t)lhie * 4u;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float t[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float z = activate<ACT>(acc[tn][tm][q * 4 + e] * os) * cs;
+                            t[e] = __builtin_amdgcn_fmed3f(z, -448.f, 448.f);
+                        }
+                        int w = 0;
+                        w = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], w, false);
+                        w = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], w, true);
+                        const uint32_t chunk = (uint32_t)((tm >> 1) * 4 + tn * 2 + (q >> 1));
+                        *reinterpret_cast<int *>(stg + ((wbase8 ^ (chunk << 4)) + (uint32_t)(tm & 1) * 4096u + (uint32_t)(q & 1) * 8u)) = w;
+                    }
+            int lo = le;
+            asm volatile("" : "+v"(lo));
+            const int er = lo >> 3, ec = lo & 7;
+            const int tok0 = er + (ec >> 2) * 64;                  // token of this lane in row group 0
+            const int rows_left = a.L - mrow0 - tok0;
+            const bool col_ok = ncol0 + (ec & 3) * 16 < Np;
+            uint8_t *cp = static_cast<uint8_t *>(a.C) + (grow0 + mrow0 + tok0) * a.ldc + a.c0 + ncol0 + (ec & 3) * 16;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const i32x4 o = *reinterpret_cast<const i32x4 *>(reinterpret_cast<const __bf16 *>(stg) + lay(j * 8 + er, ec));
+                if (inside || (col_ok && j * 8 < rows_left))
+                    __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(cp + (int64_t)(j * 8) * a.ldc));
+            }
+        }
+    }
+    if (stored) {
+    } else if ((!F8 && tl.vt) || (!a.c_f32 && !a.R)) {
         // bf16 output, no residual: stage 64 x 64 of the 128 x 64 sub-tile at a time as bf16 rows of 128 bytes.
         // (Transposed column range: the same code with tokens and features exchanged - a staged row is a feature
         // and holds 64 tokens - and the rows go to VT[b, n - vt_from, i].)
@@ -372,7 +456,8 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                         float vf[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            vf[e] = ACT == ACT_RELU ? acc[tn][tm][q * 4 + e] : activate<ACT>(acc[tn][tm][q * 4 + e]);
+                            if constexpr (F8) vf[e] = ACT == ACT_RELU ? acc[tn][tm][q * 4 + e] * os : activate<ACT>(acc[tn][tm][q * 4 + e] * os);
+                            else vf[e] = ACT == ACT_RELU ? acc[tn][tm][q * 4 + e] : activate<ACT>(acc[tn][tm][q * 4 + e]);
                         // one packed conversion per pair (written out: the compiler converts the elements of
                         // an accumulator tuple one by one and merges them with a byte permute)
                         uint2 pw;
@@ -400,7 +485,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
             for (int j = 0; j < 8; ++j) {
                 const int r = half * 64 + j * 8;                            // uniform
                 const bf16x8 o = *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const __bf16 *>(stg) + lay(j * 8 + er, ec));
-                if (tl.vt) {
+                if (!F8 && tl.vt) {
                     const int n = tl.nt0 + wnv * 128 + r + er, i = tl.m0 + wmv * 64 + ec * 8;
                     __bf16 *dst = static_cast<__bf16 *>(a.VT) + (int64_t)tl.b * a.vt_b + (int64_t)(n - a.vt_from) * a.vt_n + i;
                     if (n < Np && i + 7 < a.L) {
@@ -433,7 +518,7 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
                         const int tm = half * 2 + th;
                         f32x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = activate<ACT>(acc[tn][tm][q * 4 + e]);
+                        for (int e = 0; e < 4; ++e) o[e] = activate<ACT>(F8 ? acc[tn][tm][q * 4 + e] * os : acc[tn][tm][q * 4 + e]);
                         *reinterpret_cast<f32x4 *>(stg + ((wbase32 ^ ((uint32_t)(q * 2) << 4)) + (uint32_t)th * 4096u)) = o;
                     }
                 // rows out: 8 lanes x 16 bytes = 128 bytes of one row, 8 rows per instruction.  The residual
@@ -498,14 +583,28 @@ void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, 
     }   // tile loop
 }
 
-}  // namespace
+template <int ACT>
+__global__ __launch_bounds__(64 * (NCW + NLW)) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void gemm_bf16_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd)
+{
+    ws_body<ACT, false>(a, tiles_m, tiles_n, total_tiles, per_xcd);
+}
 
 template <int ACT>
+__global__ __launch_bounds__(64 * (NCW + NLW)) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void gemm_fp8_ws_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd)
+{
+    ws_body<ACT, true>(a, tiles_m, tiles_n, total_tiles, per_xcd);
+}
+
+}  // namespace
+
+template <int ACT, bool F8>
 static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
 {
-    auto kern = gemm_bf16_ws_kernel<ACT>;
+    auto kern = F8 ? gemm_fp8_ws_kernel<ACT> : gemm_bf16_ws_kernel<ACT>;
     constexpr size_t lds = ((size_t)NXS * XSLOT + (size_t)NWS * WSLOT) * sizeof(__bf16);     // 160 KB
-    static bool attr_set = false;
+    static bool attr_set = false;     // one flag per instantiation (ACT, F8)
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -549,9 +648,35 @@ int32_t gemm_bf16_ws(const GemmArgs &a, hipStream_t st, bool &done)
     if (!gemm_bf16_ws_eligible(a)) return SF_OK;
     done = true;
     switch (a.act) {
-    case ACT_RELU: return launch_ws<ACT_RELU>(a, st);
-    case ACT_GELU: return launch_ws<ACT_GELU>(a, st);
-    default: return launch_ws<ACT_NONE>(a, st);
+    case ACT_RELU: return launch_ws<ACT_RELU, false>(a, st);
+    case ACT_GELU: return launch_ws<ACT_GELU, false>(a, st);
+    default: return launch_ws<ACT_NONE, false>(a, st);
+    }
+}
+
+// E4M3 x E4M3 GEMM (a.f8): the persistent kernel is the only implementation.
+//   value[b*L+i, n] = out_scale * sum_k dec(A[..]) dec(W[..]) + bias
+// written as bf16 (with activation), as fp32 / with a residual like the bf16 GEMM, or (c_f8) as E4M3 codes of
+// act(value) * c_scale with ldc in bytes.
+int32_t gemm_fp8(const GemmArgs &a, hipStream_t st)
+{
+    if (a.B <= 0 || a.N <= 0) return SF_OK;
+    if (a.epi != EPI_ROWMAJOR || a.VT || a.row_map)
+        return fail(SF_ERR_UNSUPPORTED, "gemm(fp8): row-major output without row map only");
+    if (a.K % 128 || a.K < 128 || a.lda % 16 || a.ldw % 16 || a.N % 16 || a.n0 % 16 || a.c0 % 16 ||
+        a.ldc % (a.c_f8 ? 16 : 8) || (a.R && (a.ldr % 8 || a.r0 % 8)))
+        return fail(SF_ERR_SHAPE, "gemm(fp8): K %% 128 == 0, N %% 16 == 0 and 16-byte aligned rows required");
+    if (a.L < 192 || a.N < 192)
+        return fail(SF_ERR_UNSUPPORTED, "gemm(fp8): at least 192 rows per sample and 192 output features required (got %d, %d)",
+                    a.L, a.N);
+    if ((int64_t)a.L * a.lda >= ((int64_t)1 << 32) || (int64_t)a.N * a.ldw >= ((int64_t)1 << 32))
+        return fail(SF_ERR_SHAPE, "gemm(fp8): a sample of A and a pattern of W must stay below 4 GiB");
+    if (!(a.out_scale > 0.f) || (a.c_f8 && (!(a.c_scale > 0.f) || a.R || a.c_f32)))
+        return fail(SF_ERR_INVALID_ARG, "gemm(fp8): scales must be positive; code output takes no residual");
+    switch (a.act) {
+    case ACT_RELU: return launch_ws<ACT_RELU, true>(a, st);
+    case ACT_GELU: return launch_ws<ACT_GELU, true>(a, st);
+    default: return launch_ws<ACT_NONE, true>(a, st);
     }
 }
 

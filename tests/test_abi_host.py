@@ -34,6 +34,7 @@ def test_struct_layout_matches_header():
     assert C.sizeof(sf.SfMoeCompact) == 16 + 9 * 8
     assert C.sizeof(sf.SfGateParams) == 16 + 6 * 8
     assert C.sizeof(sf.SfDenseLayerFp8) == 6 * 8 + 6 * 4 + 10 * 8
+    assert C.sizeof(sf.SfFfnFp8) == 8 + 6 * 8 + 4 * 4
 
 
 def test_num_active_matches_paper_example():
@@ -121,6 +122,33 @@ def test_null_and_range_errors_before_any_launch():
     cl8.k_head, cl8.k_ffn = 4, 10
     assert L.sf_compact_heads_channels_fp8(C.byref(d), 0, C.byref(d8), one, one, one, one, C.byref(cl8), None) == -1   # NULL matrices
     assert L.sf_compact_heads_channels_fp8(C.byref(d), 5, C.byref(d8), one, one, one, one, C.byref(cl8), None) == -1   # layer out of range
+    # FP8 arithmetic of the FFN: every check comes before the first launch
+    assert L.sf_ffn_fp8_padded(2150) == 2176 and L.sf_ffn_fp8_padded(128) == 128 and L.sf_ffn_fp8_padded(129) == 256
+    assert L.sf_ffn_fp8_padded(0) == 0
+    assert L.sf_quantize_fp8(None, sf.SF_F32, 8, 1.0, None, None) == -1
+    assert L.sf_quantize_fp8(one, 7, 8, 1.0, one, None) == -1
+    assert L.sf_quantize_fp8(one, sf.SF_F32, 8, 0.0, one, None) == -1
+    assert L.sf_quantize_fp8(one, sf.SF_F32, 8, float("inf"), one, None) == -1
+    assert L.sf_quantize_fp8(C.c_void_p(260), sf.SF_F32, 8, 1.0, one, None) == -1          # misaligned
+    assert L.sf_quantize_fp8(None, sf.SF_F32, 0, 1.0, None, None) == 0                      # nothing to do
+    f8 = sf.SfFfnFp8()
+    f8.k_ffn, f8.s1, f8.s2, f8.sx, f8.sh = 200, 1.0, 1.0, 1.0, 1.0
+    f8.W1q = f8.W2Tq = 256
+    d8ok = sf.make_desc(1, 256, 256, 8, 2, 8, 512, dtype=sf.SF_BF16)
+    args = (one, None, 1, 1, C.c_void_p(512), None, None, None, 0, None)
+    assert L.sf_pruned_ffn_fp8_forward(C.byref(d8ok), C.byref(f8), *args) == -4            # no workspace
+    assert L.sf_pruned_ffn_fp8_forward(C.byref(d), C.byref(f8), *args) in (-2, -3)          # fp32 descriptor
+    for kw in (dict(L=100), dict(d_model=192), dict(d_model=200)):
+        base = dict(B=1, L=256, d_model=256, Hq=8, Hk=2, dh=8, d_ff=512, dtype=sf.SF_BF16)
+        base.update(kw)
+        assert L.sf_pruned_ffn_fp8_forward(C.byref(sf.make_desc(**base)), C.byref(f8), *args) in (-2, -3)
+    f8.k_ffn = 100
+    assert L.sf_pruned_ffn_fp8_forward(C.byref(d8ok), C.byref(f8), *args) == -3            # too few channels
+    f8.k_ffn, f8.sh = 200, -1.0
+    assert L.sf_pruned_ffn_fp8_forward(C.byref(d8ok), C.byref(f8), *args) == -1
+    assert L.sf_compact_ffn_fp8(C.byref(d8ok), 0, C.byref(d8), one, C.byref(f8), None) == -1   # NULL dense matrices
+    assert L.sf_compact_ffn_fp8(C.byref(d8ok), 3, C.byref(d8), one, C.byref(f8), None) == -1   # layer out of range
+    assert L.sf_pruned_ffn_fp8_workspace_bytes(C.byref(d8ok), 200) == 256 * 256 + 256 * 256
     # host-side keep counts out of range
     kh, kf = (C.c_int32 * 1)(9), (C.c_int32 * 1)(3)
     one = C.c_void_p(256)                 # never dereferenced: the count check comes first

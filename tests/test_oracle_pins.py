@@ -960,3 +960,26 @@ def test_pruned_ffn_fp8_error_bound_against_unquantised():
     # decoded activations are within half a grid step (2^-4 relative) of what they encode, subnormals aside
     big = np.abs(xn) > sx * 2.0 ** -5
     assert (np.abs(_dec(xq) * sx - xn)[big] <= np.abs(xn)[big] * 2.0 ** -4 * 1.0001).all()
+
+
+def test_pruned_ffn_fp8_forced_codes_and_z():
+    """Forcing the block's own codes changes nothing; forced hidden codes feed the second contraction as they are;
+    z is the value the hidden code was decided from."""
+    rng = np.random.default_rng(56)
+    rows, d, F = 9, 32, 40
+    x, W1q, s1, b1, W2q, s2, b2, g, b = _fp8_ffn_inputs(rng, rows, d, F)
+    sx, sh = np.float32(0.01), np.float32(0.013)
+    args = (x, W1q, s1, b1, W2q, s2, b2, g, b, sx, sh)
+    y, xq, hq, z = orc.pruned_ffn_fp8(*args, bf16=False, want_z=True)
+    y2, xq2, hq2 = orc.pruned_ffn_fp8(*args, bf16=False, xq_forced=xq, hq_forced=hq)
+    assert np.array_equal(y, y2) and np.array_equal(xq, xq2) and np.array_equal(hq, hq2)
+    assert np.array_equal(hq, orc.quantize_fp8(np.maximum(z, 0).astype(np.float32), sh))
+    assert np.array_equal(z, ((_dec(xq) @ _dec(W1q).T) * float(np.float32(sx * s1)) + b1).astype(np.float32))
+    hf = rng.integers(0, 0x7F, (rows, F)).astype(np.uint8)
+    y3, _, hq3 = orc.pruned_ffn_fp8(*args, bf16=False, hq_forced=hf)
+    assert np.array_equal(hq3, hf)
+    assert np.abs(y3 - (x + (_dec(hf) @ _dec(W2q)) * float(np.float32(sh * s2)) + b2)).max() < 1e-12
+    xf = rng.integers(0, 0x7F, (rows, d)).astype(np.uint8)
+    _, xq4, _, z4 = orc.pruned_ffn_fp8(*args, bf16=False, xq_forced=xf, want_z=True)
+    assert np.array_equal(xq4, xf)
+    assert np.array_equal(z4, ((_dec(xf) @ _dec(W1q).T) * float(np.float32(sx * s1)) + b1).astype(np.float32))
