@@ -415,6 +415,77 @@ def bench_fp8_plan(wl, dm, reps=50):
             "note": "sf_compact_heads_channels_fp8 vs sf_compact_heads_channels, all layers; the forward is unchanged"}
 
 
+def bench_ffn_fp8(wl, dm, steps, warmup):
+    """The pruned FFN of layer 0 on the workload's tokens in FP8 arithmetic (E4M3 codes on both operands of the two
+    contractions, static per-tensor scales) next to the same block in bf16; per-launch times of the two GEMMs of
+    each, FLOP/s of the FP8 launches against the published dense FP8 rate."""
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from gpu_utils import to_dev
+    s = wl.spec
+    if s.dtype != "bf16" or s.d % 128 or s.d < 256 or s.L < 192 or int(wl.k_ffn[0]) <= 128:
+        return None
+    B, L, d = wl.x.shape[0], s.L, s.d
+    kf = int(wl.k_ffn[0])
+    dense = dm.dense[0]
+    d8, sc = dict(dense), {}
+    for n in ("W1", "W2"):
+        w = dense[n].float()
+        sc[n] = float(w.abs().max() / 448.0)
+        d8[n] = (w / sc[n]).to(torch.float8_e4m3fn).view(torch.uint8).contiguous()
+    X = to_dev(wl.x, "bf16")
+    pid = to_dev(wl.pattern_id, "bf16")
+    # activation scales as an offline calibration would set them: amax / 448 of LN2(x) and of the hidden
+    # activations, here from the bf16 block's own tensors on this batch
+    xn = torch.nn.functional.layer_norm(X.float(), (d,), dense["ln2_g"].float(), dense["ln2_b"].float(), 1e-5)
+    sx = float(xn.abs().max() / 448.0)
+    pm = dm.masks["ffn_idx"][0, int(wl.pattern_id[0]), :kf].long()
+    h0 = torch.relu(xn[0] @ dense["W1"].float()[pm].T + dense["b1"].float()[pm])
+    sh = float(h0.abs().max() / 448.0) * 1.25          # one sample seen, some headroom
+    del xn, h0
+    cf = sf.compact_ffn_fp8(dm.desc, 0, d8, sc, dm.masks, kf, sx, sh)
+    ws8 = sf.workspace(sf.lib().sf_pruned_ffn_fp8_workspace_bytes(C_byref(dm.desc), kf))
+    ws16 = sf.workspace(sf.lib().sf_pruned_ffn_workspace_bytes(C_byref(dm.desc), kf))
+
+    def f8():
+        sf.pruned_ffn_fp8_forward(dm.desc, cf, X, pid, ws=ws8)
+
+    def f16():
+        sf.pruned_ffn_forward(dm.desc, dm.layers[0], X, pid, ws=ws16)
+
+    ms8, _ = time_steps(f8, steps, warmup)
+    ms16, _ = time_steps(f16, steps, warmup)
+    each = {}
+    for name, fn in (("fp8", f8), ("bf16", f16)):
+        sf.profile_begin(sf.SF_KERNEL_GEMM, 8 * steps)
+        for _ in range(steps):
+            fn()
+        _, _, e = sf.profile_end(each=True)
+        each[name] = [sum(e[i::2]) / len(e[i::2]) * 1e3 for i in range(2)]      # us: up, down
+    y8 = sf.pruned_ffn_fp8_forward(dm.desc, cf, X, pid, ws=ws8).float()
+    y16 = sf.pruned_ffn_forward(dm.desc, dm.layers[0], X, pid, ws=ws16).float()
+    upd8, upd16 = y8 - X.float(), y16 - X.float()
+    rel = float((upd8 - upd16).norm() / upd16.norm())
+    flop = 2.0 * B * L * d * kf                      # per GEMM, unpadded
+    out = {"k_ffn": kf, "ms_block_fp8": ms8, "ms_block_bf16": ms16,
+           "gemm_launch_us_fp8": {"ffn_up": each["fp8"][0], "ffn_down": each["fp8"][1]},
+           "gemm_launch_us_bf16": {"ffn_up": each["bf16"][0], "ffn_down": each["bf16"][1]},
+           "tflops_fp8": {"ffn_up": flop / each["fp8"][0] / 1e6, "ffn_down": flop / each["fp8"][1] / 1e6},
+           "frac_of_fp8_peak": {"ffn_up": flop / each["fp8"][0] / 1e6 / 5000.0,
+                                "ffn_down": flop / each["fp8"][1] / 1e6 / 5000.0},
+           "rel_diff_of_ffn_update_vs_bf16": rel, "scales": {"sx": sx, "sh": sh, "s1": sc["W1"], "s2": sc["W2"]},
+           "note": "sf_pruned_ffn_fp8_forward vs sf_pruned_ffn_forward (LayerNorm + two GEMMs, layer 0); "
+                   "not part of `value`"}
+    del cf, ws8, ws16
+    torch.cuda.empty_cache()
+    return out
+
+
+def C_byref(x):
+    import ctypes
+    return ctypes.byref(x)
+
+
 def cpu_baseline(wl, flops_total):
     """The CPU oracle, as it stands, on a bounded number of whole samples of the same workload."""
     import numpy as np
@@ -452,6 +523,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB (known traffic, for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--ffn-fp8-only", action="store_true",
+                    help="time only the FP8-arithmetic FFN block (and its bf16 twin) on the workload's tokens and "
+                         "print its object (for profiling)")
     ap.add_argument("--moe-only", action="store_true",
                     help="time only the Sparse-MoE FFN block on the workload's tokens and print its object (for profiling)")
     args = ap.parse_args()
@@ -468,6 +542,13 @@ def main():
 
     if args.moe_only:
         print(json.dumps(bench_moe(W.make_workload(W.CONFIGS[args.config]), args.steps, args.warmup)), flush=True)
+        return
+
+    if args.ffn_fp8_only:
+        from gpu_utils import DeviceModel
+        wl = W.make_workload(W.CONFIGS[args.config])
+        dm = DeviceModel(wl).build_plan()
+        print(json.dumps(bench_ffn_fp8(wl, dm, args.steps, args.warmup)), flush=True)
         return
 
     if args.copy_calibration > 0:
@@ -525,6 +606,7 @@ def main():
         out["moe_ffn"] = bench_moe(wl, args.steps, args.warmup)
         out["gate_plan"] = bench_gate_plan(wl)
         out["fp8_weights"] = bench_fp8_plan(wl, dm)
+        out["ffn_fp8"] = bench_ffn_fp8(wl, dm, args.steps, args.warmup)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(wl, flops["total"])
