@@ -481,6 +481,65 @@ def bench_ffn_fp8(wl, dm, steps, warmup):
     return out
 
 
+def bench_tokens(name, steps, warmup):
+    """Token compaction on a dropout workload: the masked encoder step (absent modalities kept in place and masked as
+    keys) against dropping their tokens - all samples in one compacted batch padded to the longest sample, and one
+    compacted batch per presence pattern (the caller groups samples by pattern, so every group has one length)."""
+    import numpy as np
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from paper_2604_08971_amd import workloads as W
+    from gpu_utils import DeviceModel, desc_for
+    wl = W.make_workload(W.CONFIGS[name])
+    if wl.key_valid is None:
+        return None
+    s = wl.spec
+    dm = DeviceModel(wl).build_plan()
+    B = wl.x.shape[0]
+    lens = wl.key_valid.sum(axis=1).astype(int)
+    u = np.array([min(s.c * int(np.ceil(np.log(t))), t) if t > 0 else 0 for t in lens])
+
+    def masked():
+        dm.forward()
+
+    def make_group(idx):
+        idx_t = torch.from_numpy(np.asarray(idx)).to("cuda")
+        X = dm.x[idx_t].contiguous()
+        kv = dm.key_valid[idx_t].contiguous()
+        pid = dm.pattern_id[idx_t].contiguous()
+        Lc = min(int(-(-lens[idx].max() // 8) * 8), s.L)
+        dfull = desc_for(wl, B=len(idx))
+        dc = desc_for(wl, B=len(idx), U_override=int(u[idx].max()))
+        dc.L = Lc
+        ws = sf.workspace(sf.encoder_workspace_bytes(dc, dm.layers))
+        return X, kv, pid, Lc, dfull, dc, ws
+
+    def run_group(g):
+        X, kv, pid, Lc, dfull, dc, ws = g
+        tc = sf.token_compact(dfull, X, kv, Lc)
+        Yc, _, _ = sf.encoder_forward_ragged(dc, dm.layers, tc["Xc"], pid, tc["valid_c"], tc["u_active"],
+                                             final_ln=dm.final_ln, ws=ws)
+        return sf.token_scatter(dfull, Yc, tc["slot_of"])
+
+    one = [make_group(np.arange(B))]
+    by_pattern = [make_group(np.nonzero(wl.pattern_id == p)[0]) for p in np.unique(wl.pattern_id)]
+    # two length buckets, each padded to its longest sample: samples that fit one 256-row GEMM tile, and the rest
+    cut = 256
+    short, long_ = np.nonzero(lens <= cut)[0], np.nonzero(lens > cut)[0]
+    two = [make_group(ix) for ix in (short, long_) if len(ix)]
+    ms_masked, _ = time_steps(masked, steps, warmup)
+    ms_two, _ = time_steps(lambda: [run_group(g) for g in two], steps, warmup)
+    ms_one, _ = time_steps(lambda: [run_group(g) for g in one], steps, warmup)
+    ms_grp, _ = time_steps(lambda: [run_group(g) for g in by_pattern], steps, warmup)
+    rows_grp = int(sum(g[3] * g[0].shape[0] for g in by_pattern))
+    return {"workload": name, "tokens_total": int(B * s.L), "tokens_present": int(lens.sum()),
+            "ms_masked": ms_masked, "ms_compacted_one_batch": ms_one, "Lc_one_batch": one[0][3],
+            "ms_compacted_two_buckets": ms_two, "rows_two_buckets": int(sum(g[3] * g[0].shape[0] for g in two)),
+            "ms_compacted_per_pattern": ms_grp, "pattern_groups": len(by_pattern), "rows_per_pattern_batches": rows_grp,
+            "note": "encoder step only (plan excluded); compaction + ragged encoder + scatter per batch, eager launches; "
+                    "not part of `value`"}
+
+
 def C_byref(x):
     import ctypes
     return ctypes.byref(x)
@@ -526,6 +585,8 @@ def main():
     ap.add_argument("--ffn-fp8-only", action="store_true",
                     help="time only the FP8-arithmetic FFN block (and its bf16 twin) on the workload's tokens and "
                          "print its object (for profiling)")
+    ap.add_argument("--tokens-only", action="store_true",
+                    help="time only the token-compaction comparison on the dropout workload C3 and print its object")
     ap.add_argument("--moe-only", action="store_true",
                     help="time only the Sparse-MoE FFN block on the workload's tokens and print its object (for profiling)")
     args = ap.parse_args()
@@ -542,6 +603,10 @@ def main():
 
     if args.moe_only:
         print(json.dumps(bench_moe(W.make_workload(W.CONFIGS[args.config]), args.steps, args.warmup)), flush=True)
+        return
+
+    if args.tokens_only:
+        print(json.dumps(bench_tokens("C3", args.steps, args.warmup)), flush=True)
         return
 
     if args.ffn_fp8_only:
@@ -607,6 +672,7 @@ def main():
         out["gate_plan"] = bench_gate_plan(wl)
         out["fp8_weights"] = bench_fp8_plan(wl, dm)
         out["ffn_fp8"] = bench_ffn_fp8(wl, dm, args.steps, args.warmup)
+        out["token_compaction"] = bench_tokens("C3", args.steps, args.warmup)
     if not args.no_cpu:
         log("timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(wl, flops["total"])

@@ -323,6 +323,48 @@ int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers_h
                            void *stream);
 
 /* ------------------------------------------------------------------------
+ * Token compaction -- Sec. 4.2 / 4.4: the encoder runs over the concatenated
+ * tokens of the modalities that are present.  sf_encoder_forward keeps the
+ * tokens of absent modalities in place and masks them as keys (key_valid);
+ * here they are dropped: every sample keeps its valid tokens, in order, at the
+ * front of a shorter padded sequence of Lc positions, and its number of active
+ * queries follows its own length T_b: u_active[b] = min(c*ceil(ln T_b), T_b)
+ * (Sec. 4.4 with T = T_b; c = desc->c_factor).
+ *
+ * sf_token_compact (desc: B, L, d_model, dtype, c_factor of the full sequence):
+ *   X           [B,L,d]  in;  token_valid [B,L] (non-zero = token exists)
+ *   Lc          positions per compacted sample, 1 <= Lc <= L; the caller knows
+ *               the presence patterns and passes at least the largest T_b
+ *   Xc          [B,Lc,d]  valid tokens first, then zero rows
+ *   valid_c     [B,Lc]    1 for positions < T_b
+ *   row_index   [B,Lc]    token at each position, -1 behind T_b
+ *   slot_of     [B,L]     position of each token, -1 for dropped tokens
+ *   len         [B]       T_b (not clamped: a value above Lc says that tokens
+ *                         were lost and the outputs must not be used)
+ *   u_active    [B]
+ * sf_encoder_forward_ragged is sf_encoder_forward on the compacted batch (a
+ * descriptor with L = Lc whose U is at least the largest u_active[b], e.g.
+ * U_override = c*ceil(ln Lc); U < Lc is required) with key_valid = valid_c and
+ * u_active: sample b selects min(u_active[b], U) queries per head; sel_out rows
+ * are padded with -1.  No forced selection.  The same workspace size applies.
+ * sf_token_scatter writes Y[b,i,:] = Yc[b,slot_of[b,i],:] and zero rows for
+ * dropped tokens (desc as for sf_token_compact).
+ * All index outputs are bit-exact; no workspace.
+ */
+int32_t sf_token_compact(const sf_desc *desc, const void *X, const uint8_t *token_valid, int32_t Lc,
+                         void *Xc, uint8_t *valid_c, int32_t *row_index, int32_t *slot_of,
+                         int32_t *len, int32_t *u_active, void *stream);
+int32_t sf_token_scatter(const sf_desc *desc, const void *Yc, const int32_t *slot_of, int32_t Lc,
+                         void *Y, void *stream);
+int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compact_layer *layers_host,
+                                  const void *X, const int32_t *pattern_id,
+                                  const uint8_t *key_valid, const int32_t *u_active,
+                                  const int32_t *sample_idx, const void *final_g,
+                                  const void *final_b, void *Y, int32_t *sel_out,
+                                  float *score_out, void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/* ------------------------------------------------------------------------
  * Sparse-MoE FFN with pruned experts -- Sec. 4.5 "Sparse-MoE FFN pruning":
  * the number of experts E and the Top-k routing stay fixed; expert e keeps
  * its own channel set, W1_e' = W1_e[:, N_keep_e], W2_e' = W2_e[N_keep_e, :].

@@ -27,7 +27,8 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_encoder_forward", "sf_profile_begin", "sf_profile_end", "sf_compact_moe_experts",
            "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search",
            "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8", "sf_quantize_fp8",
-           "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward"]
+           "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
+           "sf_encoder_forward_ragged"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -106,7 +107,8 @@ def lib():
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
                   "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward", "sf_gate_eval",
                   "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
-                  "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward"):
+                  "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
+                  "sf_encoder_forward_ragged"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -128,6 +130,10 @@ def lib():
         L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
         L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
         L.sf_pruned_ffn_fp8_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        L.sf_token_compact.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 7
+        L.sf_token_scatter.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.sf_encoder_forward_ragged.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)] + [C.c_void_p] * 11 + [
+            C.c_size_t, C.c_void_p]
         L.sf_ffn_fp8_padded.argtypes = [C.c_int32]
         L.sf_compact_ffn_fp8.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayerFp8), C.c_void_p,
                                          C.POINTER(SfFfnFp8), C.c_void_p]
@@ -592,4 +598,59 @@ def encoder_forward(desc: SfDesc, layers: List[CompactLayer], X: torch.Tensor,
                                   _ptr(sample_idx), _ptr(fg), _ptr(fb), _ptr(forced_sel), _ptr(Y), _ptr(sel if U > 0 else None),
                                   _ptr(score), _ptr(ws), ws.numel(), _stream())
     _check(rc, "sf_encoder_forward")
+    return Y, sel, score
+
+
+# ---------------------------------------------------------- token compaction (absent modalities contribute no tokens)
+def token_compact(desc: SfDesc, X: torch.Tensor, token_valid: torch.Tensor, Lc: int) -> Dict[str, torch.Tensor]:
+    """X [B,L,d], token_valid [B,L] uint8.  Returns Xc [B,Lc,d], valid_c [B,Lc] u8, row_index [B,Lc], slot_of [B,L],
+    len [B], u_active [B] (int32)."""
+    assert X.is_contiguous() and token_valid.is_contiguous() and token_valid.dtype == torch.uint8
+    B, L, d = X.shape
+    dev = X.device
+    i32 = lambda *sh: torch.empty(sh, dtype=torch.int32, device=dev)
+    out = dict(Xc=torch.empty((B, Lc, d), dtype=X.dtype, device=dev),
+               valid_c=torch.empty((B, Lc), dtype=torch.uint8, device=dev), row_index=i32(B, Lc), slot_of=i32(B, L),
+               len=i32(B), u_active=i32(B))
+    rc = lib().sf_token_compact(C.byref(desc), _ptr(X), _ptr(token_valid), int(Lc), _ptr(out["Xc"]), _ptr(out["valid_c"]),
+                                _ptr(out["row_index"]), _ptr(out["slot_of"]), _ptr(out["len"]), _ptr(out["u_active"]),
+                                _stream())
+    _check(rc, "sf_token_compact")
+    return out
+
+
+def token_scatter(desc: SfDesc, Yc: torch.Tensor, slot_of: torch.Tensor) -> torch.Tensor:
+    """Yc [B,Lc,d] -> Y [B,L,d] (desc of the full sequence), zero rows for dropped tokens."""
+    assert Yc.is_contiguous()
+    B, Lc, d = Yc.shape
+    Y = torch.empty((B, desc.L, d), dtype=Yc.dtype, device=Yc.device)
+    _check(lib().sf_token_scatter(C.byref(desc), _ptr(Yc), _ptr(slot_of), int(Lc), _ptr(Y), _stream()), "sf_token_scatter")
+    return Y
+
+
+def encoder_forward_ragged(desc: SfDesc, layers: List[CompactLayer], X: torch.Tensor, pattern_id, key_valid: torch.Tensor,
+                           u_active: torch.Tensor, final_ln: Optional[Dict[str, torch.Tensor]] = None,
+                           want_sel: bool = False, want_score: bool = False, ws: Optional[torch.Tensor] = None,
+                           sample_idx: Optional[torch.Tensor] = None):
+    """sf_encoder_forward on a compacted batch: sample b selects min(u_active[b], U) queries per head.
+    Returns (Y [B,L,d], sel [nl,B,Hq'max,U] | None, score [nl,B,Hq'max,L] | None)."""
+    assert X.is_contiguous()
+    _check_sample(desc, sample_idx, X.shape[0])
+    B, L, _ = X.shape
+    nl = desc.n_layers
+    U = num_active(desc)
+    khmax = max(l.k_head for l in layers)
+    dev = X.device
+    Y = torch.empty_like(X)
+    sel = torch.full((nl, B, khmax, max(U, 1)), -1, dtype=torch.int32, device=dev) if want_sel else None
+    score = torch.full((nl, B, khmax, L), float("-inf"), dtype=torch.float32, device=dev) if want_score else None
+    arr = layer_array(layers)
+    if ws is None:
+        ws = workspace(lib().sf_encoder_workspace_bytes(C.byref(desc), arr), dev)
+    fg = None if final_ln is None else final_ln["g"]
+    fb = None if final_ln is None else final_ln["b"]
+    rc = lib().sf_encoder_forward_ragged(C.byref(desc), arr, _ptr(X), _ptr(pattern_id), _ptr(key_valid), _ptr(u_active),
+                                         _ptr(sample_idx), _ptr(fg), _ptr(fb), _ptr(Y), _ptr(sel), _ptr(score), _ptr(ws),
+                                         ws.numel(), _stream())
+    _check(rc, "sf_encoder_forward_ragged")
     return Y, sel, score

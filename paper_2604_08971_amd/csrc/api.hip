@@ -275,15 +275,17 @@ extern "C" size_t sf_encoder_workspace_bytes(const sf_desc *desc, const sf_compa
     return w.bytes;
 }
 
-extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers, const void *X,
-                                      const int32_t *pattern_id, const uint8_t *key_valid,
-                                      const int32_t *sample_idx, const void *final_g, const void *final_b,
-                                      const int32_t *forced_sel,
-                                      void *Y, int32_t *sel_out, float *score_out, void *workspace,
-                                      size_t workspace_bytes, void *stream)
+static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer *layers, const void *X,
+                                    const int32_t *pattern_id, const uint8_t *key_valid,
+                                    const int32_t *sample_idx, const int32_t *u_active, const void *final_g,
+                                    const void *final_b, const int32_t *forced_sel,
+                                    void *Y, int32_t *sel_out, float *score_out, void *workspace,
+                                    size_t workspace_bytes, void *stream)
 {
     Dims D;
     if (int32_t rc = read_desc(desc, D)) return rc;
+    if (u_active && D.U >= D.L)
+        return fail(SF_ERR_UNSUPPORTED, "encoder: per-sample active counts need U < L (U = %d, L = %d)", D.U, D.L);
     if (!layers || !X || !Y) return fail(SF_ERR_INVALID_ARG, "encoder: NULL argument");
     if (X == Y) return fail(SF_ERR_INVALID_ARG, "encoder: Y may not alias X");
     if (D.P > 1 && !pattern_id) return fail(SF_ERR_INVALID_ARG, "encoder: pattern_id required when P > 1");
@@ -359,6 +361,7 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
         }
         a.head_group = ly.head_group; a.hg_stride = D.Hq; a.pattern_id = pattern_id; a.key_valid = key_valid;
         a.sample_idx = D.n_sample > 0 ? sample_idx : nullptr;
+        a.u_active = u_active;
         a.selH = w.kh_max;
         const size_t sel_layer = (size_t)D.B * w.kh_max * D.U, score_layer = (size_t)D.B * w.kh_max * D.L;
         a.forced_sel = forced_sel ? forced_sel + l * sel_layer : nullptr;
@@ -386,4 +389,27 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
     }
     if (final_ln) layernorm(D.dtype, 1, w.x2, final_g, final_b, D.eps, rows, D.d, Y, st);
     return check_launch("encoder_forward");
+}
+
+extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers, const void *X,
+                                      const int32_t *pattern_id, const uint8_t *key_valid,
+                                      const int32_t *sample_idx, const void *final_g, const void *final_b,
+                                      const int32_t *forced_sel,
+                                      void *Y, int32_t *sel_out, float *score_out, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    return encoder_forward_impl(desc, layers, X, pattern_id, key_valid, sample_idx, nullptr, final_g, final_b,
+                                forced_sel, Y, sel_out, score_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compact_layer *layers, const void *X,
+                                             const int32_t *pattern_id, const uint8_t *key_valid,
+                                             const int32_t *u_active, const int32_t *sample_idx,
+                                             const void *final_g, const void *final_b, void *Y,
+                                             int32_t *sel_out, float *score_out, void *workspace,
+                                             size_t workspace_bytes, void *stream)
+{
+    if (!u_active) return fail(SF_ERR_INVALID_ARG, "encoder_ragged: u_active is NULL");
+    return encoder_forward_impl(desc, layers, X, pattern_id, key_valid, sample_idx, u_active, final_g, final_b,
+                                nullptr, Y, sel_out, score_out, workspace, workspace_bytes, stream);
 }

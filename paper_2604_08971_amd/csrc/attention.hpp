@@ -15,6 +15,7 @@ struct AttnArgs {
     const int32_t *pattern_id;               // [B] or NULL
     const uint8_t *key_valid;                // [B,L] or NULL
     const int32_t *sample_idx; int n_sample; // [B,n_sample] key sample of the sparsity score, or NULL / 0
+    const int32_t *u_active;                 // [B] or NULL: sample b selects min(u_active[b], U) queries (needs U < L)
     const int32_t *forced_sel;               // [B,selH,U] or NULL
     void *O; int64_t ldo;                    // [B,L,nH*dh]
     int32_t *sel_out;                        // [B,selH,U] or NULL

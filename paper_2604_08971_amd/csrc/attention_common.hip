@@ -116,13 +116,13 @@ __global__ __launch_bounds__(256) void kv_stats_final_kernel(
 }
 
 // ------------------------------------------------------------------- selection
-// One block per (b, head): the U_eff = min(U, #allowed) queries with the
+// One block per (b, head): the U_eff = min(U, u_active[b], #allowed) queries with the
 // highest score, ties to the lower index; emitted ascending.  score == NULL
 // means "every allowed query" (used when U >= L).
 template <int NT>
 __global__ __launch_bounds__(NT) void select_kernel(
     const float *__restrict__ score, int scoreH, const uint8_t *__restrict__ key_valid, int nH, int L,
-    int U, int32_t *__restrict__ sel, int selH, int32_t *__restrict__ slot)
+    int U, const int32_t *__restrict__ u_active, int32_t *__restrict__ sel, int selH, int32_t *__restrict__ slot)
 {
     extern __shared__ uint32_t keys[];
     __shared__ int scratch[TOPK_SCRATCH];
@@ -140,7 +140,8 @@ __global__ __launch_bounds__(NT) void select_kernel(
         c += ok;
     }
     const int n_ok = block_sum<NT>(c, red);        // also orders the LDS writes
-    const int k = min(U, n_ok);
+    // u_active: this sample's own number of active queries (samples of different length in one batch)
+    const int k = min(u_active ? min(max(u_active[b], 0), U) : U, n_ok);
     if (k == 0) {
         for (int i = threadIdx.x; i < L; i += NT) sl[i] = -1;
     } else {
@@ -587,10 +588,10 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         // few blocks (one per sample and head): long rows get 1024 threads so that a radix pass is 4 keys per thread
         if (a.L >= 2048)
             hipLaunchKernelGGL(select_kernel<1024>, dim3(BH), dim3(1024), a.L * sizeof(uint32_t), st, M, scoreH,
-                               a.key_valid, a.nH, a.L, a.U, sel, selH, pl.slot);
+                               a.key_valid, a.nH, a.L, a.U, a.u_active, sel, selH, pl.slot);
         else
             hipLaunchKernelGGL(select_kernel<256>, dim3(BH), dim3(256), a.L * sizeof(uint32_t), st, M, scoreH,
-                               a.key_valid, a.nH, a.L, a.U, sel, selH, pl.slot);
+                               a.key_valid, a.nH, a.L, a.U, a.u_active, sel, selH, pl.slot);
     }
 
     // 3. active rows

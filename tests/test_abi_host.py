@@ -149,6 +149,19 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_compact_ffn_fp8(C.byref(d8ok), 0, C.byref(d8), one, C.byref(f8), None) == -1   # NULL dense matrices
     assert L.sf_compact_ffn_fp8(C.byref(d8ok), 3, C.byref(d8), one, C.byref(f8), None) == -1   # layer out of range
     assert L.sf_pruned_ffn_fp8_workspace_bytes(C.byref(d8ok), 200) == 256 * 256 + 256 * 256
+    # token compaction
+    assert L.sf_token_compact(C.byref(d), None, one, 8, one, one, one, one, one, one, None) == -1
+    assert L.sf_token_compact(C.byref(d), one, one, 0, C.c_void_p(512), one, one, one, one, one, None) == -1      # Lc < 1
+    assert L.sf_token_compact(C.byref(d), one, one, d.L + 1, C.c_void_p(512), one, one, one, one, one, None) == -1
+    assert L.sf_token_compact(C.byref(d), one, one, 8, one, one, one, one, one, one, None) == -1                  # Xc aliases X
+    assert L.sf_token_scatter(C.byref(d), one, None, 8, C.c_void_p(512), None) == -1
+    assert L.sf_token_scatter(C.byref(d), one, one, 8, one, None) == -1                                           # Y aliases Yc
+    cl9 = sf.SfCompactLayer()
+    assert L.sf_encoder_forward_ragged(C.byref(d), C.byref(cl9), one, None, one, None, None, None, None,
+                                       C.c_void_p(512), None, None, None, 0, None) == -1                          # no u_active
+    du = sf.make_desc(1, 16, 64, 8, 2, 8, 64, dtype=sf.SF_F32, U_override=16)
+    assert L.sf_encoder_forward_ragged(C.byref(du), C.byref(cl9), one, None, one, one, None, None, None,
+                                       C.c_void_p(512), None, None, None, 0, None) == -3                          # U >= L
     # host-side keep counts out of range
     kh, kf = (C.c_int32 * 1)(9), (C.c_int32 * 1)(3)
     one = C.c_void_p(256)                 # never dereferenced: the count check comes first
