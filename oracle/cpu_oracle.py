@@ -57,10 +57,15 @@ def lib():
         _lib.orc_pruned_ffn_fp8.restype = None
         _lib.orc_quantize_fp8.restype = None
         _lib.orc_fp8_e4m3_decode.argtypes = [C.c_uint8]
-        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_moe_ffn",
+        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_encoder_forward_fp8ffn", "orc_moe_ffn",
                   "orc_gate_eval", "orc_budget_search"):
             getattr(_lib, f).restype = C.c_int32
     return _lib
+
+
+class _Ffn8(C.Structure):
+    _fields_ = [("W1q", C.c_void_p), ("W2q", C.c_void_p), ("s1", C.c_float), ("s2", C.c_float), ("sx", C.c_float),
+                ("sh", C.c_float)]
 
 
 def _p(a):
@@ -330,9 +335,13 @@ def pruned_ffn_fp8(x, W1q, s1: float, b1, W2q, s2: float, b2, ln_g, ln_b, sx: fl
 def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=None,
                     key_valid=None, act: int = 0, eps: float = 1e-5, forced_sel=None,
                     final_ln: Optional[Dict[str, np.ndarray]] = None, bf16: bool = False,
-                    want_sel: bool = True, want_score: bool = False, sample_idx=None):
+                    want_sel: bool = True, want_score: bool = False, sample_idx=None, ffn8=None, xq_forced=None,
+                    hq_forced=None, want_codes: bool = False):
     """packs[l][p] = LayerPack of layer l, pattern p.
-    Returns (y [B,L,d], sel [nl,B,nHmax,U] or None, score [nl,B,nHmax,L] or None)."""
+    ffn8: per layer a dict W1q, W2q [F,d] uint8, s1, s2, sx, sh - the layer's FFN runs in FP8 arithmetic;
+    xq_forced [nl,B,L,d], hq_forced [nl,B,L,F] uint8: codes to use instead of the oracle's own.
+    Returns (y [B,L,d], sel [nl,B,nHmax,U] or None, score [nl,B,nHmax,L] or None) and, with want_codes,
+    xq [nl,B,L,d], hq [nl,B,L,F]."""
     x = _f64(x)
     B, L, d = x.shape
     nl, P = len(packs), len(packs[0])
@@ -354,12 +363,29 @@ def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=
     sel = np.full((nl, B, nHmax, max(U, 1)), -1, np.int32) if want_sel else None
     score = np.full((nl, B, nHmax, L), -np.inf, np.float64) if want_score else None
     si, ns = _sample(sample_idx, B)
-    rc = lib().orc_encoder_forward(
-        C.c_int32(B), C.c_int32(L), C.c_int32(nl), C.c_int32(P), arr, _p(pid), _p(kv),
+    f8 = keep8 = xf = hf = xq = hq = None
+    if ffn8 is not None:
+        assert len(ffn8) == nl
+        F = packs[0][0].struct.F
+        f8 = (_Ffn8 * nl)()
+        keep8 = []
+        for l, f in enumerate(ffn8):
+            a, b = np.ascontiguousarray(f["W1q"], dtype=np.uint8), np.ascontiguousarray(f["W2q"], dtype=np.uint8)
+            assert a.shape == (F, d) and b.shape == (F, d)
+            keep8 += [a, b]
+            f8[l] = _Ffn8(_p(a), _p(b), float(f["s1"]), float(f["s2"]), float(f["sx"]), float(f["sh"]))
+        if xq_forced is not None:
+            xf = np.ascontiguousarray(xq_forced, dtype=np.uint8).reshape(nl, B, L, d)
+        if hq_forced is not None:
+            hf = np.ascontiguousarray(hq_forced, dtype=np.uint8).reshape(nl, B, L, F)
+        if want_codes:
+            xq, hq = np.empty((nl, B, L, d), np.uint8), np.empty((nl, B, L, F), np.uint8)
+    rc = lib().orc_encoder_forward_fp8ffn(
+        C.c_int32(B), C.c_int32(L), C.c_int32(nl), C.c_int32(P), arr, f8, _p(pid), _p(kv),
         _p(si), C.c_int32(ns), C.c_int32(U), C.c_int32(act), C.c_double(eps), _p(fs), C.c_int32(nHmax), _p(fg), _p(fb),
-        C.c_int32(int(bf16)), _p(x), _p(y), _p(sel), _p(score))
+        C.c_int32(int(bf16)), _p(xf), _p(hf), _p(x), _p(y), _p(sel), _p(score), _p(xq), _p(hq))
     if rc != 0:
         raise ValueError("orc_encoder_forward: bad arguments")
     if sel is not None:
         sel = sel[..., :U]
-    return y, sel, score
+    return (y, sel, score, xq, hq) if want_codes else (y, sel, score)

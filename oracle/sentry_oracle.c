@@ -681,6 +681,21 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                             const double *final_g, const double *final_b, int32_t bf16,
                             const double *x, double *y, int32_t *sel_out, double *score_out)
 {
+    return orc_encoder_forward_fp8ffn(B, L, nl, P, layers, NULL, pattern_id, key_valid, sample_idx, n_sample, U,
+                                      act, eps, forced_sel, nHmax, final_g, final_b, bf16, NULL, NULL, x, y,
+                                      sel_out, score_out, NULL, NULL);
+}
+
+int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
+                                   const orc_layer *layers, const orc_ffn8 *ffn8, const int32_t *pattern_id,
+                                   const uint8_t *key_valid, const int32_t *sample_idx, int32_t n_sample,
+                                   int32_t U, int32_t act, double eps,
+                                   const int32_t *forced_sel, int32_t nHmax,
+                                   const double *final_g, const double *final_b, int32_t bf16,
+                                   const uint8_t *xq_forced, const uint8_t *hq_forced,
+                                   const double *x, double *y, int32_t *sel_out, double *score_out,
+                                   uint8_t *xq_out, uint8_t *hq_out)
+{
     if (B < 0 || L < 1 || nl < 1 || P < 1 || U < 0) return -1;
     const int32_t d = layers[0].d;
     const int64_t Ld = (int64_t)L * d;
@@ -756,6 +771,17 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
             memcpy(cur, xn, sizeof(double) * (size_t)Ld);
 
             /* x <- x + FFN(LN2(x)) */
+            if (ffn8) {
+                /* the FFN of this layer in FP8 arithmetic; the stream stays unrounded */
+                const orc_ffn8 *f = &ffn8[l];
+                const int64_t blk = (int64_t)l * B + b;
+                orc_pruned_ffn_fp8(d, w->F, f->W1q, f->s1, w->b1, f->W2q, f->s2, w->b2, w->ln2_g, w->ln2_b,
+                                   w->ffn_mask, f->sx, f->sh, cur, L, act, eps, 1, 1, 0,
+                                   xq_forced ? xq_forced + blk * L * d : NULL,
+                                   hq_forced ? hq_forced + blk * L * w->F : NULL, xn,
+                                   xq_out ? xq_out + blk * L * d : NULL, hq_out ? hq_out + blk * L * w->F : NULL,
+                                   NULL);
+            } else
             ffn_core(w, cur, L, act, eps, 1, 1, bf16, 0, xn);
             memcpy(cur, xn, sizeof(double) * (size_t)Ld);
 

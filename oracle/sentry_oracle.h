@@ -266,6 +266,27 @@ void orc_pruned_ffn_fp8(int32_t d, int32_t F, const uint8_t *W1q, float s1, cons
                         int32_t add_residual, int32_t bf16, const uint8_t *xq_forced,
                         const uint8_t *hq_forced, double *y, uint8_t *xq_out, uint8_t *hq_out, double *z_out);
 
+/* The encoder with the FFN of every layer in FP8 arithmetic (orc_pruned_ffn_fp8 on the unrounded residual stream,
+ * LayerNorm vectors, biases and channel masks of `layers`); everything else as orc_encoder_forward, which is this
+ * function with ffn8 = NULL.
+ *   ffn8 [nl]          codes and scales of each layer's FFN in the layout of that layer's W1 / W2 (shared by all
+ *                      patterns, so `layers` must hold the dense weights with their 0/1 channel masks)
+ *   xq_forced [nl,B,L,d], hq_forced [nl,B,L,F] or NULL: codes to use instead of the oracle's own (see
+ *              orc_pruned_ffn_fp8);  xq_out, hq_out: the codes used, same shapes, or NULL */
+typedef struct {
+    const uint8_t *W1q, *W2q;       /* [F,d] E4M3 codes */
+    float s1, s2, sx, sh;
+} orc_ffn8;
+int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
+                                   const orc_layer *layers, const orc_ffn8 *ffn8, const int32_t *pattern_id,
+                                   const uint8_t *key_valid, const int32_t *sample_idx, int32_t n_sample,
+                                   int32_t U, int32_t act, double eps,
+                                   const int32_t *forced_sel, int32_t nHmax,
+                                   const double *final_g, const double *final_b, int32_t bf16,
+                                   const uint8_t *xq_forced, const uint8_t *hq_forced,
+                                   const double *x, double *y, int32_t *sel_out, double *score_out,
+                                   uint8_t *xq_out, uint8_t *hq_out);
+
 int32_t orc_max_threads(void);
 
 #ifdef __cplusplus

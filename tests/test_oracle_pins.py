@@ -983,3 +983,41 @@ def test_pruned_ffn_fp8_forced_codes_and_z():
     _, xq4, _, z4 = orc.pruned_ffn_fp8(*args, bf16=False, xq_forced=xf, want_z=True)
     assert np.array_equal(xq4, xf)
     assert np.array_equal(z4, ((_dec(xf) @ _dec(W1q).T) * float(np.float32(sx * s1)) + b1).astype(np.float32))
+
+
+def test_encoder_with_fp8_ffn_is_the_composition_of_its_blocks():
+    """The encoder with FP8 FFNs against its own parts: attention block of the plain encoder (taken as the
+    difference to a run whose FFN weights are zero) followed by orc_pruned_ffn_fp8 on that stream; with ffn8 = None
+    the function is the plain encoder."""
+    spec = W.small_spec(dtype="f32", B=2, nl=1, dropout="none", final_ln=False)
+    wl = W.make_workload(spec)
+    masks = oracle_masks(wl)
+    packs = dense_packs(wl, masks)          # dense weights + 0/1 masks: the FFN codes are in the dense layout too
+    U = orc.num_active(spec.L, spec.c)
+    y0, sel0, _ = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid)
+    rng = np.random.default_rng(57)
+    lw = wl.layers[0]
+    s1, s2 = np.float32(np.abs(lw["W1"]).max() / 448), np.float32(np.abs(lw["W2"]).max() / 448)
+    f8 = dict(W1q=torch.from_numpy(lw["W1"] / s1).to(torch.float8_e4m3fn).view(torch.uint8).numpy(),
+              W2q=torch.from_numpy(lw["W2"] / s2).to(torch.float8_e4m3fn).view(torch.uint8).numpy(),
+              s1=s1, s2=s2, sx=np.float32(4.0 / 448), sh=np.float32(4.0 / 448))
+    y8, sel8, _, xq, hq = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, ffn8=[f8], want_codes=True)
+    assert np.array_equal(sel8, sel0)                       # the attention block does not see the FFN
+    # the stream after the attention block: the plain encoder with an FFN that contributes nothing
+    import copy
+    wl_z = copy.copy(wl)
+    wl_z.layers = [dict(lw, W2=np.zeros_like(lw["W2"]), b2=np.zeros_like(lw["b2"]))]
+    x1, _, _ = orc.encoder_forward(wl.x, dense_packs(wl_z, masks), U, wl.pattern_id, wl.key_valid)
+    for b in range(2):
+        p = int(wl.pattern_id[b])
+        yb, xqb, hqb = orc.pruned_ffn_fp8(x1[b], f8["W1q"], s1, lw["b1"], f8["W2q"], s2, lw["b2"], lw["ln2_g"],
+                                          lw["ln2_b"], f8["sx"], f8["sh"], ffn_mask=masks["ffn_mask"][0, p], bf16=False)
+        assert np.array_equal(xq[0, b], xqb) and np.array_equal(hq[0, b], hqb)
+        assert np.abs(y8[b] - yb).max() < 1e-12
+    # forced codes are used as they are
+    hf = rng.integers(0, 0x40, hq.shape).astype(np.uint8)
+    _, _, _, _, hq2 = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, ffn8=[f8], hq_forced=hf,
+                                          want_codes=True)
+    for b in range(2):
+        keep = masks["ffn_mask"][0, int(wl.pattern_id[b])].astype(bool)
+        assert np.array_equal(hq2[0, b][:, keep], hf[0, b][:, keep]) and not hq2[0, b][:, ~keep].any()
