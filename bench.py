@@ -462,6 +462,23 @@ def bench_ffn_fp8(wl, dm, steps, warmup):
             fn()
         _, _, e = sf.profile_end(each=True)
         each[name] = [sum(e[i::2]) / len(e[i::2]) * 1e3 for i in range(2)]      # us: up, down
+    # the whole encoder step with the FFN in FP8 arithmetic (single-layer workloads: one calibrated FFN is all it needs)
+    enc = None
+    if s.n_layers == 1:
+        wse = sf.workspace(sf.encoder_workspace_bytes(dm.desc, dm.layers))
+        Ye = torch.empty_like(X)
+
+        def e8():
+            sf.encoder_forward_fp8ffn(dm.desc, dm.layers, [cf], X, pid, dm.key_valid, dm.final_ln, out=Ye, ws=wse)
+
+        def e16():
+            sf.encoder_forward(dm.desc, dm.layers, X, pid, dm.key_valid, dm.final_ln, out=Ye, ws=wse)
+
+        ms_e8, _ = time_steps(e8, steps, warmup)
+        ms_e16, _ = time_steps(e16, steps, warmup)
+        enc = {"ms_encoder_fp8_ffn": ms_e8, "ms_encoder_bf16": ms_e16, "tokens_per_s_fp8_ffn": B * L / (ms_e8 * 1e-3),
+               "tokens_per_s_bf16": B * L / (ms_e16 * 1e-3)}
+        del wse, Ye
     y8 = sf.pruned_ffn_fp8_forward(dm.desc, cf, X, pid, ws=ws8).float()
     y16 = sf.pruned_ffn_forward(dm.desc, dm.layers[0], X, pid, ws=ws16).float()
     upd8, upd16 = y8 - X.float(), y16 - X.float()
@@ -473,9 +490,10 @@ def bench_ffn_fp8(wl, dm, steps, warmup):
            "tflops_fp8": {"ffn_up": flop / each["fp8"][0] / 1e6, "ffn_down": flop / each["fp8"][1] / 1e6},
            "frac_of_fp8_peak": {"ffn_up": flop / each["fp8"][0] / 1e6 / 5000.0,
                                 "ffn_down": flop / each["fp8"][1] / 1e6 / 5000.0},
-           "rel_diff_of_ffn_update_vs_bf16": rel, "scales": {"sx": sx, "sh": sh, "s1": sc["W1"], "s2": sc["W2"]},
-           "note": "sf_pruned_ffn_fp8_forward vs sf_pruned_ffn_forward (LayerNorm + two GEMMs, layer 0); "
-                   "not part of `value`"}
+           "encoder_step": enc, "rel_diff_of_ffn_update_vs_bf16": rel, "scales": {"sx": sx, "sh": sh, "s1": sc["W1"], "s2": sc["W2"]},
+           "note": "sf_pruned_ffn_fp8_forward vs sf_pruned_ffn_forward (LayerNorm + two GEMMs, layer 0), and the encoder "
+                   "forward (plan excluded) with that FFN in FP8 arithmetic, sf_encoder_forward_fp8ffn, vs "
+                   "sf_encoder_forward; not part of `value`"}
     del cf, ws8, ws16
     torch.cuda.empty_cache()
     return out

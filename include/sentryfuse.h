@@ -239,6 +239,23 @@ int32_t sf_pruned_ffn_fp8_forward(const sf_desc *desc, const sf_ffn_fp8 *ffn_hos
                                   void *Y, uint8_t *xq_out, uint8_t *hq_out, void *workspace,
                                   size_t workspace_bytes, void *stream);
 
+/* sf_encoder_forward with the FFN of every layer in FP8 arithmetic (the
+ * attention block is unchanged).  ffn_host [n_layers]: HOST array, entry l
+ * built from layer l's FFN with k_ffn equal to layers_host[l].k_ffn; sx is the
+ * scale of LN2 of the residual stream.  The limits of
+ * sf_pruned_ffn_fp8_forward apply to every layer; the workspace is that of
+ * sf_encoder_forward.  xq_out [n_layers, B*L, d] and hq_out (layer l's codes,
+ * a [B*L, Fp8_l] array, at hq_out + l*B*L*max_l Fp8_l) receive the codes when
+ * not NULL (16-byte aligned). */
+int32_t sf_encoder_forward_fp8ffn(const sf_desc *desc, const sf_compact_layer *layers_host,
+                                  const sf_ffn_fp8 *ffn_host, const void *X,
+                                  const int32_t *pattern_id, const uint8_t *key_valid,
+                                  const int32_t *sample_idx, const void *final_g,
+                                  const void *final_b, const int32_t *forced_sel, void *Y,
+                                  int32_t *sel_out, float *score_out, uint8_t *xq_out,
+                                  uint8_t *hq_out, void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
 /* Element strides of a [B, heads, L, dh] tensor whose last dimension is
  * contiguous (for V with v_transposed: a [B, groups, dh, L] tensor whose L
  * dimension is contiguous and `l` is the stride between dh rows). */

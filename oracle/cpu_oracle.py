@@ -336,10 +336,11 @@ def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=
                     key_valid=None, act: int = 0, eps: float = 1e-5, forced_sel=None,
                     final_ln: Optional[Dict[str, np.ndarray]] = None, bf16: bool = False,
                     want_sel: bool = True, want_score: bool = False, sample_idx=None, ffn8=None, xq_forced=None,
-                    hq_forced=None, want_codes: bool = False):
+                    hq_forced=None, want_codes: bool = False, n_forced_x=None, n_forced_h=None):
     """packs[l][p] = LayerPack of layer l, pattern p.
     ffn8: per layer a dict W1q, W2q [F,d] uint8, s1, s2, sx, sh - the layer's FFN runs in FP8 arithmetic;
-    xq_forced [nl,B,L,d], hq_forced [nl,B,L,F] uint8: codes to use instead of the oracle's own.
+    xq_forced [nl,B,L,d], hq_forced [nl,B,L,F] uint8: codes to use instead of the oracle's own, in the layers
+    l < n_forced_x / l < n_forced_h (default: every layer).
     Returns (y [B,L,d], sel [nl,B,nHmax,U] or None, score [nl,B,nHmax,L] or None) and, with want_codes,
     xq [nl,B,L,d], hq [nl,B,L,F]."""
     x = _f64(x)
@@ -383,7 +384,8 @@ def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=
     rc = lib().orc_encoder_forward_fp8ffn(
         C.c_int32(B), C.c_int32(L), C.c_int32(nl), C.c_int32(P), arr, f8, _p(pid), _p(kv),
         _p(si), C.c_int32(ns), C.c_int32(U), C.c_int32(act), C.c_double(eps), _p(fs), C.c_int32(nHmax), _p(fg), _p(fb),
-        C.c_int32(int(bf16)), _p(xf), _p(hf), _p(x), _p(y), _p(sel), _p(score), _p(xq), _p(hq))
+        C.c_int32(int(bf16)), _p(xf), _p(hf), C.c_int32(nl if n_forced_x is None else int(n_forced_x)),
+        C.c_int32(nl if n_forced_h is None else int(n_forced_h)), _p(x), _p(y), _p(sel), _p(score), _p(xq), _p(hq))
     if rc != 0:
         raise ValueError("orc_encoder_forward: bad arguments")
     if sel is not None:

@@ -682,7 +682,7 @@ int32_t orc_encoder_forward(int32_t B, int32_t L, int32_t nl, int32_t P,
                             const double *x, double *y, int32_t *sel_out, double *score_out)
 {
     return orc_encoder_forward_fp8ffn(B, L, nl, P, layers, NULL, pattern_id, key_valid, sample_idx, n_sample, U,
-                                      act, eps, forced_sel, nHmax, final_g, final_b, bf16, NULL, NULL, x, y,
+                                      act, eps, forced_sel, nHmax, final_g, final_b, bf16, NULL, NULL, 0, 0, x, y,
                                       sel_out, score_out, NULL, NULL);
 }
 
@@ -693,6 +693,7 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
                                    const int32_t *forced_sel, int32_t nHmax,
                                    const double *final_g, const double *final_b, int32_t bf16,
                                    const uint8_t *xq_forced, const uint8_t *hq_forced,
+                                   int32_t n_forced_x, int32_t n_forced_h,
                                    const double *x, double *y, int32_t *sel_out, double *score_out,
                                    uint8_t *xq_out, uint8_t *hq_out)
 {
@@ -777,8 +778,8 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
                 const int64_t blk = (int64_t)l * B + b;
                 orc_pruned_ffn_fp8(d, w->F, f->W1q, f->s1, w->b1, f->W2q, f->s2, w->b2, w->ln2_g, w->ln2_b,
                                    w->ffn_mask, f->sx, f->sh, cur, L, act, eps, 1, 1, 0,
-                                   xq_forced ? xq_forced + blk * L * d : NULL,
-                                   hq_forced ? hq_forced + blk * L * w->F : NULL, xn,
+                                   xq_forced && l < n_forced_x ? xq_forced + blk * L * d : NULL,
+                                   hq_forced && l < n_forced_h ? hq_forced + blk * L * w->F : NULL, xn,
                                    xq_out ? xq_out + blk * L * d : NULL, hq_out ? hq_out + blk * L * w->F : NULL,
                                    NULL);
             } else

@@ -272,7 +272,9 @@ void orc_pruned_ffn_fp8(int32_t d, int32_t F, const uint8_t *W1q, float s1, cons
  *   ffn8 [nl]          codes and scales of each layer's FFN in the layout of that layer's W1 / W2 (shared by all
  *                      patterns, so `layers` must hold the dense weights with their 0/1 channel masks)
  *   xq_forced [nl,B,L,d], hq_forced [nl,B,L,F] or NULL: codes to use instead of the oracle's own (see
- *              orc_pruned_ffn_fp8);  xq_out, hq_out: the codes used, same shapes, or NULL */
+ *              orc_pruned_ffn_fp8) in the layers l < n_forced_x / l < n_forced_h: a test walks the layers and takes
+ *              the oracle's own decision of layer l on the other implementation's decisions of the layers before
+ *   xq_out, hq_out: the codes used, same shapes, or NULL */
 typedef struct {
     const uint8_t *W1q, *W2q;       /* [F,d] E4M3 codes */
     float s1, s2, sx, sh;
@@ -284,6 +286,7 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
                                    const int32_t *forced_sel, int32_t nHmax,
                                    const double *final_g, const double *final_b, int32_t bf16,
                                    const uint8_t *xq_forced, const uint8_t *hq_forced,
+                                   int32_t n_forced_x, int32_t n_forced_h,
                                    const double *x, double *y, int32_t *sel_out, double *score_out,
                                    uint8_t *xq_out, uint8_t *hq_out);
 

@@ -28,7 +28,7 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search",
            "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8", "sf_quantize_fp8",
            "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
-           "sf_encoder_forward_ragged"]
+           "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -108,7 +108,7 @@ def lib():
                   "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward", "sf_gate_eval",
                   "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
-                  "sf_encoder_forward_ragged"):
+                  "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -130,6 +130,8 @@ def lib():
         L.sf_sparse_gqa_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32, C.c_int32]
         L.sf_pruned_ffn_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
         L.sf_pruned_ffn_fp8_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
+        L.sf_encoder_forward_fp8ffn.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.POINTER(SfFfnFp8)] + [
+            C.c_void_p] * 13 + [C.c_size_t, C.c_void_p]
         L.sf_token_compact.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 7
         L.sf_token_scatter.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.sf_encoder_forward_ragged.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)] + [C.c_void_p] * 11 + [
@@ -654,3 +656,37 @@ def encoder_forward_ragged(desc: SfDesc, layers: List[CompactLayer], X: torch.Te
                                          ws.numel(), _stream())
     _check(rc, "sf_encoder_forward_ragged")
     return Y, sel, score
+
+
+def encoder_forward_fp8ffn(desc: SfDesc, layers: List[CompactLayer], ffn8: List[CompactFfnFp8], X: torch.Tensor,
+                           pattern_id: Optional[torch.Tensor] = None, key_valid: Optional[torch.Tensor] = None,
+                           final_ln: Optional[Dict[str, torch.Tensor]] = None,
+                           forced_sel: Optional[torch.Tensor] = None, want_sel: bool = False, want_codes: bool = False,
+                           out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """sf_encoder_forward with every layer's FFN in FP8 arithmetic.  Returns (Y, sel | None) and, with want_codes,
+    xq [nl, B*L, d] and a list of hq_l [B*L, Fp8_l]."""
+    assert X.is_contiguous() and len(ffn8) == desc.n_layers
+    B, L, d = X.shape
+    nl = desc.n_layers
+    U = num_active(desc)
+    khmax = max(l.k_head for l in layers)
+    dev = X.device
+    Y = torch.empty_like(X) if out is None else out
+    sel = torch.full((nl, B, khmax, max(U, 1)), -1, dtype=torch.int32, device=dev) if want_sel else None
+    arr = layer_array(layers)
+    farr = (SfFfnFp8 * nl)(*[f.struct for f in ffn8])
+    if ws is None:
+        ws = workspace(lib().sf_encoder_workspace_bytes(C.byref(desc), arr), dev)
+    F8max = max(f.Fp8 for f in ffn8)
+    xq = torch.empty((nl, B * L, d), dtype=torch.uint8, device=dev) if want_codes else None
+    hq = torch.zeros((nl, B * L * F8max), dtype=torch.uint8, device=dev) if want_codes else None
+    fg = None if final_ln is None else final_ln["g"]
+    fb = None if final_ln is None else final_ln["b"]
+    rc = lib().sf_encoder_forward_fp8ffn(C.byref(desc), arr, farr, _ptr(X), _ptr(pattern_id), _ptr(key_valid), None,
+                                         _ptr(fg), _ptr(fb), _ptr(forced_sel), _ptr(Y), _ptr(sel if U > 0 else None),
+                                         None, _ptr(xq), _ptr(hq), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "sf_encoder_forward_fp8ffn")
+    if want_codes:
+        hql = [hq[l, :B * L * f.Fp8].view(B * L, f.Fp8) for l, f in enumerate(ffn8)]
+        return Y, sel, xq, hql
+    return Y, sel

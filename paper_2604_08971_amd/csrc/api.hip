@@ -1,6 +1,7 @@
 // Descriptor handling, error reporting, pruned_ffn_forward and encoder_forward
 // (the pre-norm layer stack around SentryAttend and the pruned FFN; Sec. 4.4
 // and Sec. 4.5 of the paper).
+#include <algorithm>
 #include <math.h>
 #include <string.h>
 
@@ -280,10 +281,23 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
                                     const int32_t *sample_idx, const int32_t *u_active, const void *final_g,
                                     const void *final_b, const int32_t *forced_sel,
                                     void *Y, int32_t *sel_out, float *score_out, void *workspace,
-                                    size_t workspace_bytes, void *stream)
+                                    size_t workspace_bytes, void *stream, const sf_ffn_fp8 *ffn8 = nullptr,
+                                    uint8_t *xq_out = nullptr, uint8_t *hq_out = nullptr)
 {
     Dims D;
     if (int32_t rc = read_desc(desc, D)) return rc;
+    int Fp8_max = 0;
+    if (ffn8) {
+        if (!layers) return fail(SF_ERR_INVALID_ARG, "encoder: NULL argument");
+        for (int l = 0; l < D.nl; ++l) {
+            if (int32_t rc = ffn_fp8_check("encoder(fp8 ffn)", D, &ffn8[l], true)) return rc;
+            if (ffn8[l].k_ffn != layers[l].k_ffn)
+                return fail(SF_ERR_INVALID_ARG, "encoder(fp8 ffn): k_ffn of layer %d differs from the compact layer's", l);
+            Fp8_max = std::max(Fp8_max, (int)sf_ffn_fp8_padded(ffn8[l].k_ffn));
+        }
+        if (((uintptr_t)xq_out | (uintptr_t)hq_out) & 15)
+            return fail(SF_ERR_INVALID_ARG, "encoder(fp8 ffn): 16-byte aligned code buffers required");
+    }
     if (u_active && D.U >= D.L)
         return fail(SF_ERR_UNSUPPORTED, "encoder: per-sample active counts need U < L (U = %d, L = %d)", D.U, D.L);
     if (!layers || !X || !Y) return fail(SF_ERR_INVALID_ARG, "encoder: NULL argument");
@@ -381,8 +395,16 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
 
         // x2 = x1 + FFN(LN2(x1)); the last layer without a final LN writes Y directly
         const bool to_y = l == D.nl - 1 && !final_ln;
-        if (int32_t rc = ffn_forward(D, ly, w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y, w.xn,
-                                     w.hid, st))
+        if (ffn8) {
+            // the codes of LN2(x1) take the place of the normalised input, those of the hidden activations the
+            // place of the 16-bit hidden buffer (both are smaller)
+            uint8_t *xq = xq_out ? xq_out + (size_t)l * rows * D.d : static_cast<uint8_t *>(w.xn);
+            uint8_t *hq = hq_out ? hq_out + (size_t)l * rows * Fp8_max : static_cast<uint8_t *>(w.hid);
+            if (int32_t rc = ffn_fp8_forward(D, ffn8[l], w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y,
+                                             xq, hq, st))
+                return rc;
+        } else if (int32_t rc = ffn_forward(D, ly, w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y, w.xn,
+                                            w.hid, st))
             return rc;
         in = w.x2;
         in_f32 = true;
@@ -400,6 +422,19 @@ extern "C" int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_laye
 {
     return encoder_forward_impl(desc, layers, X, pattern_id, key_valid, sample_idx, nullptr, final_g, final_b,
                                 forced_sel, Y, sel_out, score_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t sf_encoder_forward_fp8ffn(const sf_desc *desc, const sf_compact_layer *layers,
+                                             const sf_ffn_fp8 *ffn8, const void *X, const int32_t *pattern_id,
+                                             const uint8_t *key_valid, const int32_t *sample_idx,
+                                             const void *final_g, const void *final_b, const int32_t *forced_sel,
+                                             void *Y, int32_t *sel_out, float *score_out, uint8_t *xq_out,
+                                             uint8_t *hq_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ffn8) return fail(SF_ERR_INVALID_ARG, "encoder(fp8 ffn): ffn8 is NULL");
+    return encoder_forward_impl(desc, layers, X, pattern_id, key_valid, sample_idx, nullptr, final_g, final_b,
+                                forced_sel, Y, sel_out, score_out, workspace, workspace_bytes, stream, ffn8, xq_out,
+                                hq_out);
 }
 
 extern "C" int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compact_layer *layers, const void *X,

@@ -57,15 +57,15 @@ __global__ __launch_bounds__(256) void quantize_fp8_kernel(const T *__restrict__
 
 // LayerNorm (statistics in fp32, biased variance) with the quantiser applied to the fp32 result: one wave per
 // row, the row is read once and kept in registers (d % 8 == 0, d <= 512 * NCH), 8 codes per store.
-template <int NCH>
-__global__ __launch_bounds__(256) void layernorm_q8_kernel(const __bf16 *__restrict__ x, const __bf16 *__restrict__ gamma,
+template <class TI, int NCH>
+__global__ __launch_bounds__(256) void layernorm_q8_kernel(const TI *__restrict__ x, const __bf16 *__restrict__ gamma,
                                                            const __bf16 *__restrict__ beta, float eps, int64_t rows,
                                                            int d, float inv_scale, uint8_t *__restrict__ y)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const __bf16 *xr = x + row * d;
+    const TI *xr = x + row * d;
     const int nch = d >> 3;
     float v[NCH][8];
     float s = 0.f;
@@ -73,9 +73,18 @@ __global__ __launch_bounds__(256) void layernorm_q8_kernel(const __bf16 *__restr
     for (int c = 0; c < NCH; ++c) {
         const int ch = lane + c * 64;
         if (ch < nch) {
-            const bf16x8 t = *reinterpret_cast<const bf16x8 *>(xr + ch * 8);
+            if constexpr (sizeof(TI) == 2) {
+                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(xr + ch * 8);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { v[c][e] = (float)t[e]; s += v[c][e]; }
+                for (int e = 0; e < 8; ++e) v[c][e] = (float)t[e];
+            } else {
+                const f32x4 t0 = *reinterpret_cast<const f32x4 *>(xr + ch * 8);
+                const f32x4 t1 = *reinterpret_cast<const f32x4 *>(xr + ch * 8 + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[c][e] = t0[e]; v[c][4 + e] = t1[e]; }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += v[c][e];
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
@@ -181,6 +190,66 @@ extern "C" size_t sf_pruned_ffn_fp8_workspace_bytes(const sf_desc *desc, int32_t
     return fp8_ffn_ws(D, sf_ffn_fp8_padded(k_ffn), nullptr).bytes;
 }
 
+template <class TI>
+static void launch_ln_q8(const void *X, const sf_ffn_fp8 &f, const Dims &D, int64_t rows, float inv_sx, uint8_t *xq,
+                         hipStream_t st)
+{
+    dim3 grid((unsigned)((rows + 3) / 4));
+#define SF_LNQ_ARGS grid, dim3(256), 0, st, (const TI *)X, (const __bf16 *)f.ln2_g, (const __bf16 *)f.ln2_b, D.eps, rows, D.d, inv_sx, xq
+    if (D.d <= 512) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 1>), SF_LNQ_ARGS);
+    else if (D.d <= 1024) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 2>), SF_LNQ_ARGS);
+    else if (D.d <= 2048) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 4>), SF_LNQ_ARGS);
+    else hipLaunchKernelGGL((layernorm_q8_kernel<TI, 8>), SF_LNQ_ARGS);
+#undef SF_LNQ_ARGS
+}
+
+namespace sf {
+
+int32_t ffn_fp8_check(const char *who, const Dims &D, const sf_ffn_fp8 *f, bool pre_ln)
+{
+    if (int32_t rc = check_ffn_fp8(who, D, f)) return rc;
+    if (pre_ln && D.d > 4096) return fail(SF_ERR_SHAPE, "%s: d_model <= 4096 required with the LayerNorm", who);
+    if (((uintptr_t)f->ln2_g | (uintptr_t)f->ln2_b) & 15)
+        return fail(SF_ERR_INVALID_ARG, "%s: 16-byte aligned LayerNorm vectors required", who);
+    return SF_OK;
+}
+
+// x_f32 / y_f32: X / Y hold fp32 (the encoder's residual stream); with x_f32 the LayerNorm is required.
+int32_t ffn_fp8_forward(const Dims &D, const sf_ffn_fp8 &f, const void *X, bool x_f32, const int32_t *pattern_id,
+                        bool pre_ln, bool add_residual, void *Y, bool y_f32, uint8_t *xq, uint8_t *hq, hipStream_t st)
+{
+    const int Fp8 = sf_ffn_fp8_padded(f.k_ffn);
+    const int64_t rows = (int64_t)D.B * D.L;
+    const float inv_sx = 1.0f / f.sx;
+    if (pre_ln) {
+        if (x_f32) launch_ln_q8<float>(X, f, D, rows, inv_sx, xq, st);
+        else launch_ln_q8<__bf16>(X, f, D, rows, inv_sx, xq, st);
+    } else {
+        if (x_f32) return fail(SF_ERR_UNSUPPORTED, "ffn_fp8: an fp32 input needs the LayerNorm");
+        const int64_t n = rows * D.d;
+        hipLaunchKernelGGL(quantize_fp8_kernel<__bf16>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, st,
+                           (const __bf16 *)X, n, inv_sx, xq);
+    }
+    GemmArgs g{};
+    g.f8 = 1; g.A = xq; g.lda = D.d; g.W = f.W1q; g.ldw = D.d; g.w_pstride = (int64_t)Fp8 * D.d;
+    g.bias = f.b1; g.bias_pstride = Fp8; g.pattern_id = pattern_id;
+    g.B = D.B; g.L = D.L; g.N = Fp8; g.K = D.d; g.epi = EPI_ROWMAJOR; g.act = gemm_act(D.act);
+    g.out_scale = f.sx * f.s1;
+    g.c_f8 = 1; g.c_scale = 1.0f / f.sh; g.C = hq; g.ldc = Fp8;
+    if (int32_t rc = gemm_fp8(g, st)) return rc;
+
+    GemmArgs h{};
+    h.f8 = 1; h.A = hq; h.lda = Fp8; h.W = f.W2Tq; h.ldw = Fp8; h.w_pstride = (int64_t)D.d * Fp8;
+    h.bias = f.b2; h.bias_pstride = 0; h.pattern_id = pattern_id;
+    h.B = D.B; h.L = D.L; h.N = D.d; h.K = Fp8; h.epi = EPI_ROWMAJOR; h.act = ACT_NONE;
+    h.out_scale = f.sh * f.s2;
+    h.R = add_residual ? X : nullptr; h.ldr = D.d; h.r_f32 = x_f32;
+    h.C = Y; h.ldc = D.d; h.c_f32 = y_f32;
+    return gemm_fp8(h, st);
+}
+
+}  // namespace sf
+
 extern "C" int32_t sf_pruned_ffn_fp8_forward(const sf_desc *desc, const sf_ffn_fp8 *f, const void *X,
                                              const int32_t *pattern_id, int32_t pre_ln, int32_t add_residual,
                                              void *Y, uint8_t *xq_out, uint8_t *hq_out, void *workspace,
@@ -188,12 +257,11 @@ extern "C" int32_t sf_pruned_ffn_fp8_forward(const sf_desc *desc, const sf_ffn_f
 {
     Dims D;
     if (int32_t rc = read_desc(desc, D)) return rc;
-    if (int32_t rc = check_ffn_fp8("pruned_ffn_fp8", D, f)) return rc;
+    if (int32_t rc = ffn_fp8_check("pruned_ffn_fp8", D, f, pre_ln != 0)) return rc;
     if (!X || !Y) return fail(SF_ERR_INVALID_ARG, "pruned_ffn_fp8: NULL argument");
     if (X == Y) return fail(SF_ERR_INVALID_ARG, "pruned_ffn_fp8: Y may not alias X");
     if (D.P > 1 && !pattern_id) return fail(SF_ERR_INVALID_ARG, "pruned_ffn_fp8: pattern_id required when P > 1");
-    if (pre_ln && D.d > 4096) return fail(SF_ERR_SHAPE, "pruned_ffn_fp8: d_model <= 4096 required with pre_ln");
-    if (((uintptr_t)X | (uintptr_t)Y | (uintptr_t)xq_out | (uintptr_t)hq_out | (uintptr_t)f->ln2_g | (uintptr_t)f->ln2_b) & 15)
+    if (((uintptr_t)X | (uintptr_t)Y | (uintptr_t)xq_out | (uintptr_t)hq_out) & 15)
         return fail(SF_ERR_INVALID_ARG, "pruned_ffn_fp8: 16-byte aligned pointers required");
     const int Fp8 = sf_ffn_fp8_padded(f->k_ffn);
     Fp8FfnWs w = fp8_ffn_ws(D, Fp8, workspace);
@@ -201,37 +269,8 @@ extern "C" int32_t sf_pruned_ffn_fp8_forward(const sf_desc *desc, const sf_ffn_f
         return fail(SF_ERR_WORKSPACE, "pruned_ffn_fp8: workspace of %zu bytes (256-byte aligned) required, got %zu",
                     w.bytes, workspace_bytes);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    uint8_t *xq = xq_out ? xq_out : w.xq, *hq = hq_out ? hq_out : w.hq;
-    const int64_t rows = (int64_t)D.B * D.L;
-    const float inv_sx = 1.0f / f->sx;
-    if (pre_ln) {
-        dim3 grid((unsigned)((rows + 3) / 4));
-#define SF_LNQ_ARGS grid, dim3(256), 0, st, (const __bf16 *)X, (const __bf16 *)f->ln2_g, (const __bf16 *)f->ln2_b, D.eps, rows, D.d, inv_sx, xq
-        if (D.d <= 512) hipLaunchKernelGGL(layernorm_q8_kernel<1>, SF_LNQ_ARGS);
-        else if (D.d <= 1024) hipLaunchKernelGGL(layernorm_q8_kernel<2>, SF_LNQ_ARGS);
-        else if (D.d <= 2048) hipLaunchKernelGGL(layernorm_q8_kernel<4>, SF_LNQ_ARGS);
-        else hipLaunchKernelGGL(layernorm_q8_kernel<8>, SF_LNQ_ARGS);
-#undef SF_LNQ_ARGS
-    } else {
-        const int64_t n = rows * D.d;
-        hipLaunchKernelGGL(quantize_fp8_kernel<__bf16>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, st,
-                           (const __bf16 *)X, n, inv_sx, xq);
-    }
-    GemmArgs g{};
-    g.f8 = 1; g.A = xq; g.lda = D.d; g.W = f->W1q; g.ldw = D.d; g.w_pstride = (int64_t)Fp8 * D.d;
-    g.bias = f->b1; g.bias_pstride = Fp8; g.pattern_id = pattern_id;
-    g.B = D.B; g.L = D.L; g.N = Fp8; g.K = D.d; g.epi = EPI_ROWMAJOR; g.act = gemm_act(D.act);
-    g.out_scale = f->sx * f->s1;
-    g.c_f8 = 1; g.c_scale = 1.0f / f->sh; g.C = hq; g.ldc = Fp8;
-    if (int32_t rc = gemm_fp8(g, st)) return rc;
-
-    GemmArgs h{};
-    h.f8 = 1; h.A = hq; h.lda = Fp8; h.W = f->W2Tq; h.ldw = Fp8; h.w_pstride = (int64_t)D.d * Fp8;
-    h.bias = f->b2; h.bias_pstride = 0; h.pattern_id = pattern_id;
-    h.B = D.B; h.L = D.L; h.N = D.d; h.K = Fp8; h.epi = EPI_ROWMAJOR; h.act = ACT_NONE;
-    h.out_scale = f->sh * f->s2;
-    h.R = add_residual ? X : nullptr; h.ldr = D.d;
-    h.C = Y; h.ldc = D.d;
-    if (int32_t rc = gemm_fp8(h, st)) return rc;
+    if (int32_t rc = ffn_fp8_forward(D, *f, X, false, pattern_id, pre_ln != 0, add_residual != 0, Y, false,
+                                     xq_out ? xq_out : w.xq, hq_out ? hq_out : w.hq, st))
+        return rc;
     return check_launch("pruned_ffn_fp8_forward");
 }

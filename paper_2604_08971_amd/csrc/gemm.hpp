@@ -48,6 +48,14 @@ int32_t gemm(int dtype, const GemmArgs &a, hipStream_t st);
 // E4M3 x E4M3 -> fp32 accumulate (large row-major problems only, else SF_ERR_UNSUPPORTED / SF_ERR_SHAPE).
 int32_t gemm_fp8(const GemmArgs &a, hipStream_t st);
 
+// The pruned FFN in FP8 arithmetic (fp8_ffn.hip): checks, then LayerNorm + quantiser, up-projection writing codes,
+// down-projection with the residual.  x_f32 / y_f32: X / Y hold fp32 (the encoder's residual stream).
+// xq [B*L, d], hq [B*L, Fp8] receive the codes.
+struct Dims;
+int32_t ffn_fp8_check(const char *who, const Dims &D, const sf_ffn_fp8 *f, bool pre_ln);
+int32_t ffn_fp8_forward(const Dims &D, const sf_ffn_fp8 &f, const void *X, bool x_f32, const int32_t *pattern_id,
+                        bool pre_ln, bool add_residual, void *Y, bool y_f32, uint8_t *xq, uint8_t *hq, hipStream_t st);
+
 // True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).
 bool gemm_takes_row_map(int dtype, const GemmArgs &a);
 

@@ -149,6 +149,15 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_compact_ffn_fp8(C.byref(d8ok), 0, C.byref(d8), one, C.byref(f8), None) == -1   # NULL dense matrices
     assert L.sf_compact_ffn_fp8(C.byref(d8ok), 3, C.byref(d8), one, C.byref(f8), None) == -1   # layer out of range
     assert L.sf_pruned_ffn_fp8_workspace_bytes(C.byref(d8ok), 200) == 256 * 256 + 256 * 256
+    # encoder with FP8 FFNs: the checks of every layer's FFN come before anything is enqueued
+    f8.k_ffn, f8.sh = 200, 1.0
+    cl8f = sf.SfCompactLayer()
+    cl8f.k_head, cl8f.k_ffn = 4, 200
+    eargs = (one, None, None, None, None, None, None, C.c_void_p(512), None, None, None, None, None, 0, None)
+    assert L.sf_encoder_forward_fp8ffn(C.byref(d8ok), C.byref(cl8f), None, *eargs) == -1          # no FFN array
+    assert L.sf_encoder_forward_fp8ffn(C.byref(d), C.byref(cl8f), C.byref(f8), *eargs) in (-2, -3)  # fp32 descriptor
+    cl8f.k_ffn = 300
+    assert L.sf_encoder_forward_fp8ffn(C.byref(d8ok), C.byref(cl8f), C.byref(f8), *eargs) == -1   # k_ffn mismatch
     # token compaction
     assert L.sf_token_compact(C.byref(d), None, one, 8, one, one, one, one, one, one, None) == -1
     assert L.sf_token_compact(C.byref(d), one, one, 0, C.c_void_p(512), one, one, one, one, one, None) == -1      # Lc < 1

@@ -254,3 +254,79 @@ def test_pruned_ffn_fp8_rejects_what_it_cannot_run():
     cf.struct.sh = 0.0
     with pytest.raises(sf.SentryFuseError):
         sf.pruned_ffn_fp8_forward(desc, cf, x)
+
+
+# ------------------------------------------------------------- the encoder with FP8 FFNs
+def _encoder_fp8_case(kw):
+    from paper_2604_08971_amd import workloads as W
+    from gpu_utils import DeviceModel
+    from helpers import dense_packs, oracle_masks
+    wl = W.make_workload(W.small_spec(**kw))
+    s = wl.spec
+    dm = DeviceModel(wl).build_plan()
+    ref_masks = oracle_masks(wl)
+    packs = dense_packs(wl, ref_masks)                 # dense weights + channel masks: the codes are dense too
+    U = sf.num_active(dm.desc)
+    B, L, d, F, nl = wl.x.shape[0], s.L, s.d, s.F, s.n_layers
+    sx, sh = 4.0 / 448, 4.0 / 448
+    f8, cfs = [], []
+    for l in range(nl):
+        lw = wl.layers[l]
+        s1, s2 = float(np.float32(np.abs(lw["W1"]).max() / 448)), float(np.float32(np.abs(lw["W2"]).max() / 448))
+        W1q, W2q = _cast_e4m3(lw["W1"] / np.float32(s1)), _cast_e4m3(lw["W2"] / np.float32(s2))
+        f8.append(dict(W1q=W1q, W2q=W2q, s1=s1, s2=s2, sx=sx, sh=sh))
+        d8 = dict(dm.dense[l], W1=to_dev(W1q, "bf16"), W2=to_dev(W2q, "bf16"))
+        cfs.append(sf.compact_ffn_fp8(dm.desc, l, d8, dict(W1=s1, W2=s2), dm.masks, int(wl.k_ffn[l]), sx, sh))
+    Y, sel, xq, hq = sf.encoder_forward_fp8ffn(dm.desc, dm.layers, cfs, dm.x, dm.pattern_id, dm.key_valid, dm.final_ln,
+                                               want_sel=True, want_codes=True)
+    torch.cuda.synchronize()
+    Y, sel, xq = to_host(Y), to_host(sel), to_host(xq).reshape(nl, B, L, d)
+    # the device's hidden codes in the dense channel layout of each sample's pattern
+    hq_dense = np.zeros((nl, B, L, F), np.uint8)
+    for l in range(nl):
+        kf = int(wl.k_ffn[l])
+        h = to_host(hq[l]).reshape(B, L, -1)
+        assert not h[:, :, kf:].any()
+        for b in range(B):
+            hq_dense[l, b][:, ref_masks["ffn_idx"][l, int(wl.pattern_id[b]), :kf]] = h[b, :, :kf]
+    bf = True
+    # the device lists the active queries per kept head (rank order); the dense packs index heads by their number
+    sel_dense = np.full((nl, B, s.Hq, U), -1, np.int32)
+    for l in range(nl):
+        kh = int(wl.k_head[l])
+        for b in range(B):
+            sel_dense[l, b, ref_masks["head_idx"][l, int(wl.pattern_id[b]), :kh]] = sel[l, b, :kh]
+    common = dict(act=s.act, final_ln=wl.final_ln, bf16=bf, ffn8=f8, forced_sel=sel_dense)
+    # the oracle on the device's decisions (active queries, codes): the output reference
+    y_ref, _, _ = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, xq_forced=xq, hq_forced=hq_dense, **common)
+    e = err_metric(Y, y_ref)
+    # the decisions themselves, layer by layer: the oracle's own input codes of layer l on the device's decisions of
+    # the layers before it, then its own hidden codes of layer l on the device's input codes of layer l
+    xq_own, hq_own = np.zeros_like(xq), np.zeros_like(hq_dense)
+    for l in range(nl):
+        forced = dict(xq_forced=xq, hq_forced=hq_dense, want_codes=True, **common)
+        xq_own[l] = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, n_forced_x=l, n_forced_h=l,
+                                        **forced)[3][l]
+        hq_own[l] = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, n_forced_x=l + 1, n_forced_h=l,
+                                        **forced)[4][l]
+    vx_d, vx_o = DEC[xq] * sx, DEC[xq_own] * sx
+    # the streams differ by the bf16 path's rounding noise, the codes by at most that plus one grid step
+    assert (np.abs(vx_d - vx_o) <= 2.0 ** -3 * np.abs(vx_o) + 2e-2 * np.maximum(1.0, np.abs(vx_o))).all()
+    vh_d, vh_o = DEC[hq_dense] * sh, DEC[hq_own] * sh
+    assert (np.abs(vh_d - vh_o) <= 2.0 ** -3 * np.abs(vh_o) + 2e-3).all()
+    same = float((hq_dense == hq_own).mean())
+    _say(f"   encoder with fp8 ffn: err {e:.3e}; hidden codes equal to the oracle's on the device's input codes: {same:.5f}; "
+         f"input codes equal to the oracle's own: {float((xq == xq_own).mean()):.4f}")
+    assert same >= 0.995
+    assert e <= 2e-2, e
+
+
+@pytest.mark.parametrize("kw", [
+    dict(dtype="bf16", d=256, dh=64, Hq=4, Hk=2, F=512, seg=(100, 60, 70), extra=2, B=3, nl=2, ffn_keep=0.6,
+         dropout="bernoulli:0.3"),
+    dict(dtype="bf16", d=384, dh=32, Hq=12, Hk=4, F=640, seg=(128, 128), extra=0, B=2, nl=1, ffn_keep=0.8, act=1,
+         dropout="none", final_ln=False),
+])
+def test_encoder_with_fp8_ffn_parity(kw):
+    _say(f"encoder fp8 ffn {kw}")
+    _encoder_fp8_case(kw)
