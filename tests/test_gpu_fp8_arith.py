@@ -330,3 +330,39 @@ def _encoder_fp8_case(kw):
 def test_encoder_with_fp8_ffn_parity(kw):
     _say(f"encoder fp8 ffn {kw}")
     _encoder_fp8_case(kw)
+
+
+def test_ffn_fp8_under_hip_graph_replay():
+    """The FP8 block (LayerNorm + quantiser, two GEMMs) recorded into a HIP graph: every replay, with eager work and
+    synchronisations in between, reproduces the eager result bit for bit."""
+    _say("ffn fp8 graph replay")
+    c = _case(66, B=3, L=300, d=256, F=640, P=2, kf=300)
+    desc = sf.make_desc(c["B"], c["L"], c["d"], 1, 1, 8, c["F"], 1, c["P"], sf.SF_BF16)
+    d8 = dict(W1=to_dev(c["W1q"], "bf16"), W2=to_dev(c["W2q"], "bf16"), b1=to_dev(c["b1"], "bf16"),
+              b2=to_dev(c["b2"], "bf16"), ln2_g=to_dev(c["g"], "bf16"), ln2_b=to_dev(c["b"], "bf16"))
+    masks = dict(ffn_idx=to_dev(c["ffn_idx"], "bf16"))
+    cf = sf.compact_ffn_fp8(desc, 0, d8, dict(W1=c["s1"], W2=c["s2"]), masks, c["kf"], c["sx"], c["sh"])
+    X, pid = to_dev(c["x"], "bf16"), to_dev(c["pid"], "bf16")
+    import ctypes
+    ws = sf.workspace(sf.lib().sf_pruned_ffn_fp8_workspace_bytes(ctypes.byref(desc), c["kf"]))
+    y_eager = sf.pruned_ffn_fp8_forward(desc, cf, X, pid, ws=ws).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sf.pruned_ffn_fp8_forward(desc, cf, X, pid, ws=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        y_graph = sf.pruned_ffn_fp8_forward(desc, cf, X, pid, ws=ws)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        y_graph.fill_(float("nan"))
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), f"replay {rep} differs from the eager result"
+        assert torch.equal(sf.pruned_ffn_fp8_forward(desc, cf, X, pid, ws=ws), y_eager)
+        torch.cuda.synchronize()

@@ -166,3 +166,45 @@ def test_ragged_entry_rejects_what_it_cannot_run():
                                   final_ln=dm.final_ln)
     with pytest.raises(sf.SentryFuseError):
         sf.token_compact(dm.desc, dm.x, dm.key_valid, wl.spec.L + 1)
+
+
+def test_compact_encode_scatter_under_hip_graph_replay():
+    """Compaction, the ragged encoder and the scatter recorded into one HIP graph: every replay, with eager work and
+    synchronisations in between, reproduces the eager result (no step of the chain needs the host)."""
+    _say("token compaction graph replay")
+    wl = W.make_workload(W.small_spec(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90, 40), B=6, dropout="upto:2"))
+    s = wl.spec
+    dm = DeviceModel(wl).build_plan()
+    lens = wl.key_valid.sum(axis=1).astype(int)
+    Lc = min(int(-(-lens.max() // 8) * 8), s.L)
+    dc = desc_for(wl, U_override=max(orc.num_active(int(t), s.c) for t in lens))
+    dc.L = Lc
+    ws = sf.workspace(sf.encoder_workspace_bytes(dc, dm.layers))
+
+    def chain():
+        tc = sf.token_compact(dm.desc, dm.x, dm.key_valid, Lc)
+        Yc, _, _ = sf.encoder_forward_ragged(dc, dm.layers, tc["Xc"], dm.pattern_id, tc["valid_c"], tc["u_active"],
+                                             final_ln=dm.final_ln, ws=ws)
+        return sf.token_scatter(dm.desc, Yc, tc["slot_of"])
+
+    y_eager = chain().clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        y_graph = chain()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        y_graph.fill_(float("nan"))
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), f"replay {rep} differs from the eager result"
+        assert torch.equal(chain(), y_eager)
+        torch.cuda.synchronize()
