@@ -54,6 +54,8 @@ def lib():
         _lib.orc_max_threads.restype = C.c_int32
         _lib.orc_fp8_e4m3_decode.restype = C.c_double
         _lib.orc_fp8_e4m3_encode.restype = C.c_uint8
+        _lib.orc_f16_decode.restype = C.c_double
+        _lib.orc_dequant_f16.restype = None
         _lib.orc_pruned_ffn_fp8.restype = None
         _lib.orc_quantize_fp8.restype = None
         _lib.orc_fp8_e4m3_decode.argtypes = [C.c_uint8]
@@ -288,6 +290,18 @@ def dequant_fp8(q, scale: float, bf16: bool) -> np.ndarray:
     q = np.ascontiguousarray(q, dtype=np.uint8)
     out = np.empty(q.shape, np.float64)
     lib().orc_dequant_fp8(_p(q), C.c_int64(q.size), C.c_float(float(scale)), C.c_int32(int(bf16)), _p(out))
+    return out
+
+
+def f16_decode(bits: int) -> float:
+    return float(lib().orc_f16_decode(C.c_uint16(int(bits))))
+
+
+def dequant_f16(q, bf16: bool) -> np.ndarray:
+    """q uint16 (IEEE binary16 bit patterns) -> their values rounded to the model dtype, as fp64."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    out = np.empty(q.shape, np.float64)
+    lib().orc_dequant_f16(_p(q), C.c_int64(q.size), C.c_int32(int(bf16)), _p(out))
     return out
 
 

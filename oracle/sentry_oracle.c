@@ -512,6 +512,25 @@ void orc_pruned_ffn(const orc_layer *w, const double *x, int64_t rows, int32_t a
     ffn_core(w, x, rows, act, eps, pre_ln, add_residual, bf16, bf16, y);
 }
 
+/* ---- FP16 (IEEE binary16) weight storage ---------------------------------- */
+double orc_f16_decode(uint16_t bits)
+{
+    const int sign = bits >> 15, e = (bits >> 10) & 31, m = bits & 1023;
+    double v;
+    if (e == 31) v = m ? NAN : INFINITY;
+    else if (e == 0) v = ldexp((double)m, -24);               /* subnormal: m * 2^-10 * 2^-14 */
+    else v = ldexp(1.0 + (double)m / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
+void orc_dequant_f16(const uint16_t *q, int64_t n, int32_t bf16, double *out)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const double w = orc_f16_decode(q[i]);                /* exact in fp32 as well */
+        out[i] = bf16 ? orc_round_bf16(w) : w;
+    }
+}
+
 /* ---- FP8 arithmetic (W8A8) for the pruned FFN ------------------------------ */
 uint8_t orc_fp8_e4m3_encode(float t)
 {

@@ -238,6 +238,16 @@ double orc_fp8_e4m3_decode(uint8_t byte);
 void orc_dequant_fp8(const uint8_t *q, int64_t n, float scale, int32_t bf16, double *out);
 
 /*
+ * FP16 post-training quantisation of the weights (same experiment, the FP16 points).  Reading: weights are stored
+ * as IEEE binary16 (1-5-10, subnormals, infinities, NaN), no scale; the forward runs on the stored value in the
+ * model dtype: every binary16 value is an fp32 value, so an fp32 model computes on exactly the stored weights, and a
+ * bf16 model on their one rounding to bf16 (ties to even).
+ *   orc_f16_decode: the value of one bit pattern;  orc_dequant_f16: out[i] = round(decode(q[i])).
+ */
+double orc_f16_decode(uint16_t bits);
+void orc_dequant_f16(const uint16_t *q, int64_t n, int32_t bf16, double *out);
+
+/*
  * FP8 arithmetic for the pruned FFN (the second half of the same experiment: the paper reports FP8 models but
  * not how they compute).  Reading: both operands of the two FFN contractions are E4M3 codes with one fp32
  * scale per tensor (W8A8, static scales chosen offline), products are exact and sums wide:

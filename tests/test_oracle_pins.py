@@ -1021,3 +1021,25 @@ def test_encoder_with_fp8_ffn_is_the_composition_of_its_blocks():
     for b in range(2):
         keep = masks["ffn_mask"][0, int(wl.pattern_id[b])].astype(bool)
         assert np.array_equal(hq2[0, b][:, keep], hf[0, b][:, keep]) and not hq2[0, b][:, ~keep].any()
+
+
+# ------------------------------------------------ FP16 (IEEE binary16) weight storage
+def test_f16_decode_and_dequant_against_library_type():
+    """All 65536 bit patterns against numpy's float16 (a library implementation of IEEE binary16); the bf16 rounding
+    against PyTorch's conversion."""
+    bits = np.arange(65536, dtype=np.uint16)
+    lib_vals = bits.view(np.float16).astype(np.float64)
+    w32 = orc.dequant_f16(bits, bf16=False)
+    assert np.array_equal(np.isnan(w32), np.isnan(lib_vals))
+    ok = ~np.isnan(lib_vals)
+    assert np.array_equal(w32[ok], lib_vals[ok])
+    assert np.array_equal(np.signbit(w32[ok]), np.signbit(lib_vals[ok]))
+    # landmarks: largest finite value, smallest subnormal, smallest normal, one, infinities
+    assert orc.f16_decode(0x7BFF) == 65504.0 and orc.f16_decode(0x0001) == 2.0 ** -24
+    assert orc.f16_decode(0x0400) == 2.0 ** -14 and orc.f16_decode(0x3C00) == 1.0 and orc.f16_decode(0xC000) == -2.0
+    assert orc.f16_decode(0x7C00) == np.inf and orc.f16_decode(0xFC00) == -np.inf and np.isnan(orc.f16_decode(0x7E00))
+    # a bf16 model: one rounding of the stored value (11 significant bits -> 8), ties to even
+    w16 = orc.dequant_f16(bits[ok], bf16=True)
+    lib16 = torch.from_numpy(lib_vals[ok]).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(w16, lib16)
+    assert (w16 != lib_vals[ok]).any()                       # the rounding is real
