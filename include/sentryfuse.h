@@ -188,6 +188,20 @@ int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t layer,
                                       const int32_t *n_groups, const int32_t *ffn_idx,
                                       const sf_compact_layer *compact_host, void *stream);
 
+/* FP16 post-training quantisation of the weights (the FP16 points of the same
+ * experiment): sf_compact_heads_channels reading the six weight matrices of
+ * `dense_host` as IEEE binary16 (2 bytes per element, no scale; biases and
+ * LayerNorm vectors in the model dtype).  The stored value is rounded once to
+ * the model dtype in the gather: exact for an fp32 model (every binary16 value
+ * is an fp32 value), one rounding to bf16 otherwise.  bf16 stays the 16-bit
+ * compute type; there is no fp16 arithmetic.  d_model a multiple of 4, the
+ * matrices 8-byte aligned. */
+int32_t sf_compact_heads_channels_f16(const sf_desc *desc, int32_t layer,
+                                      const sf_dense_layer *dense_host,
+                                      const int32_t *head_idx, const int32_t *group_idx,
+                                      const int32_t *n_groups, const int32_t *ffn_idx,
+                                      const sf_compact_layer *compact_host, void *stream);
+
 /* ------------------------------------------------------------------------
  * FP8 arithmetic for the pruned FFN (same experiment; the paper does not say
  * how its FP8 models compute).  Here both operands of the two FFN contractions

@@ -28,7 +28,7 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search",
            "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8", "sf_quantize_fp8",
            "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
-           "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn"]
+           "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -108,7 +108,7 @@ def lib():
                   "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward", "sf_gate_eval",
                   "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
-                  "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn"):
+                  "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -118,6 +118,8 @@ def lib():
         L.sf_compact_heads_channels.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayer),
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                 C.POINTER(SfCompactLayer), C.c_void_p]
+        L.sf_compact_heads_channels_f16.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayer)] + [
+            C.c_void_p] * 4 + [C.POINTER(SfCompactLayer), C.c_void_p]
         L.sf_compact_heads_channels_fp8.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayerFp8),
                                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                     C.POINTER(SfCompactLayer), C.c_void_p]
@@ -369,6 +371,23 @@ def compact_heads_channels_fp8(desc: SfDesc, layer: int, dense8: Dict[str, torch
                                              _ptr(masks["group_idx"]), _ptr(masks["n_groups"]), _ptr(masks["ffn_idx"]),
                                              C.byref(cl.struct), _stream())
     _check(rc, "sf_compact_heads_channels_fp8")
+    return cl
+
+
+def compact_heads_channels_f16(desc: SfDesc, layer: int, dense16: Dict[str, torch.Tensor],
+                               masks: Dict[str, torch.Tensor], k_head: int, k_ffn: int,
+                               out: Optional[CompactLayer] = None) -> CompactLayer:
+    """dense16: Wq, Wk, Wv, Wo, W1, W2 as torch.float16 (shapes of the dense layer), biases and LayerNorm vectors in
+    the model dtype."""
+    for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2"):
+        assert dense16[n].dtype == torch.float16 and dense16[n].is_contiguous(), n
+    cl = out if out is not None else CompactLayer(desc, dense16, k_head, k_ffn, masks["head_group"][layer],
+                                                  masks["n_groups"][layer])
+    ds = SfDenseLayer(*[_ptr(dense16.get(n)) for n in _DENSE_FIELDS])
+    rc = lib().sf_compact_heads_channels_f16(C.byref(desc), layer, C.byref(ds), _ptr(masks["head_idx"]),
+                                             _ptr(masks["group_idx"]), _ptr(masks["n_groups"]), _ptr(masks["ffn_idx"]),
+                                             C.byref(cl.struct), _stream())
+    _check(rc, "sf_compact_heads_channels_f16")
     return cl
 
 

@@ -197,6 +197,20 @@ __device__ inline double fp8_e4m3_value(uint32_t b)
     return (b & 0x80u) ? -(double)v : (double)v;
 }
 
+// IEEE binary16 bit pattern -> value (every binary16 value is an fp32 value)
+__device__ inline double f16_value(uint32_t bits)
+{
+    const uint16_t h = (uint16_t)bits;
+    return (double)(float)__builtin_bit_cast(_Float16, h);
+}
+
+// value of one stored code: S = uint8_t is E4M3, S = uint16_t is binary16
+template <class S> __device__ inline double code_value(uint32_t c)
+{
+    if constexpr (sizeof(S) == 1) return fp8_e4m3_value(c);
+    else return f16_value(c);
+}
+
 template <class T> __device__ inline T round_from_double(double x);
 template <> __device__ inline float round_from_double<float>(double x) { return (float)x; }
 template <> __device__ inline uint16_t round_from_double<uint16_t>(double x)      // bf16 bits, ties to even
@@ -212,13 +226,13 @@ template <> __device__ inline uint16_t round_from_double<uint16_t>(double x)    
 }
 
 struct Fp8Region {
-    const uint8_t *src; void *dst; const int32_t *idx; const int32_t *n_dev;
+    const void *src; void *dst; const int32_t *idx; const int32_t *n_dev;
     int idx_stride, block, n_static, rows; size_t dst_pstride /* elements */; float scale;
 };
 struct Fp8Regions { Fp8Region r[4]; int n; };
 
 // as gather_rows_kernel, rows of row_len elements (a multiple of 4); a thread converts 4 elements at a time
-template <class T>
+template <class T, class S>
 __global__ __launch_bounds__(256) void gather_rows_fp8_kernel(Fp8Regions regs, int row_len)
 {
     const int p = blockIdx.y;
@@ -230,23 +244,28 @@ __global__ __launch_bounds__(256) void gather_rows_fp8_kernel(Fp8Regions regs, i
     int src_unit = -1;
     if (slot < n_valid) src_unit = rg.idx[(size_t)p * rg.idx_stride + slot];
     T *d = static_cast<T *>(rg.dst) + (size_t)p * rg.dst_pstride + (size_t)R * row_len;
-    const uint8_t *s = rg.src + ((size_t)(src_unit < 0 ? 0 : src_unit) * rg.block + r) * row_len;
+    const S *s = static_cast<const S *>(rg.src) + ((size_t)(src_unit < 0 ? 0 : src_unit) * rg.block + r) * row_len;
     const double sc = (double)rg.scale;
+    constexpr int SB = 8 * sizeof(S);
     for (int i = threadIdx.x * 4; i < row_len; i += blockDim.x * 4) {
-        uint32_t w = 0u;
-        if (src_unit >= 0) w = *reinterpret_cast<const uint32_t *>(s + i);
+        uint64_t w = 0u;                                       // four codes
+        if (src_unit >= 0) {
+            if constexpr (sizeof(S) == 1) w = *reinterpret_cast<const uint32_t *>(s + i);
+            else w = *reinterpret_cast<const uint64_t *>(s + i);
+        }
         struct alignas(sizeof(T) * 4) Pack { T v[4]; } o;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            o.v[e] = src_unit < 0 ? T(0) : round_from_double<T>(fp8_e4m3_value((w >> (8 * e)) & 0xffu) * sc);
+            o.v[e] = src_unit < 0 ? T(0)
+                                  : round_from_double<T>(code_value<S>((uint32_t)(w >> (SB * e)) & ((1u << SB) - 1u)) * sc);
         *reinterpret_cast<Pack *>(d + i) = o;
     }
 }
 
 // as gather_transpose_kernel with an FP8 source
-template <class T>
+template <class T, class S>
 __global__ __launch_bounds__(256) void gather_transpose_fp8_kernel(
-    const uint8_t *__restrict__ src, T *__restrict__ dstT, const int32_t *__restrict__ idx,
+    const S *__restrict__ src, T *__restrict__ dstT, const int32_t *__restrict__ idx,
     int idx_stride, int block, int n_valid, int cols_out, int d, size_t dst_pstride, float scale)
 {
     __shared__ T tile[32][33];
@@ -260,7 +279,7 @@ __global__ __launch_bounds__(256) void gather_transpose_fp8_kernel(
             const int slot = J / block;
             const int unit = slot < n_valid ? idx[(size_t)p * idx_stride + slot] : -1;
             if (unit >= 0)
-                v = round_from_double<T>(fp8_e4m3_value(src[((size_t)unit * block + J % block) * d + n]) * (double)scale);
+                v = round_from_double<T>(code_value<S>(src[((size_t)unit * block + J % block) * d + n]) * (double)scale);
         }
         tile[jj][tx] = v;
     }
@@ -427,11 +446,13 @@ extern "C" int32_t sf_compact_moe_experts(const sf_desc *desc, const sf_moe_dens
     return check_launch("compact_moe_experts");
 }
 
-// FP8-stored dense weights (OCP E4M3 bytes + one fp32 scale per matrix): gather and dequantise in one pass.
-extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense,
-                                                 const int32_t *head_idx, const int32_t *group_idx,
-                                                 const int32_t *n_groups, const int32_t *ffn_idx,
-                                                 const sf_compact_layer *c, void *stream)
+// Dense weights stored as codes - S = uint8_t: OCP E4M3 bytes + one fp32 scale per matrix, S = uint16_t: IEEE
+// binary16, scale 1: gather and dequantise in one pass.
+template <class S>
+static int32_t compact_coded(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense,
+                             const int32_t *head_idx, const int32_t *group_idx,
+                             const int32_t *n_groups, const int32_t *ffn_idx,
+                             const sf_compact_layer *c, void *stream)
 {
     Dims D;
     if (int32_t rc = read_desc(desc, D)) return rc;
@@ -445,8 +466,8 @@ extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t la
         !c->Wqkv || !c->WoT || !c->W1 || !c->W2T)
         return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: NULL weight pointer");
     if (D.d % 4) return fail(SF_ERR_SHAPE, "compact_heads_channels_fp8: d_model must be a multiple of 4");
-    if (((uintptr_t)dense->Wq | (uintptr_t)dense->Wk | (uintptr_t)dense->Wv | (uintptr_t)dense->W1) & 3)
-        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: weight matrices must be 4-byte aligned");
+    if (((uintptr_t)dense->Wq | (uintptr_t)dense->Wk | (uintptr_t)dense->Wv | (uintptr_t)dense->W1) & (4 * sizeof(S) - 1))
+        return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: weight matrices must be %zu-byte aligned", 4 * sizeof(S));
     const bool qkv_bias = dense->bq || dense->bk || dense->bv;
     if (qkv_bias && !(dense->bq && dense->bk && dense->bv))
         return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_fp8: bq, bk, bv must be all set or all NULL");
@@ -467,7 +488,7 @@ extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t la
     auto wreg = [&](const void *src, void *dst, size_t row_off, const int32_t *idx, int idx_stride, int block, int n_static,
                     const int32_t *n_dev, int rows, size_t rows_per_pattern, float scale) {
         Fp8Region r{};
-        r.src = static_cast<const uint8_t *>(src); r.dst = (char *)dst + row_off * d * es; r.idx = idx; r.n_dev = n_dev;
+        r.src = src; r.dst = (char *)dst + row_off * d * es; r.idx = idx; r.n_dev = n_dev;
         r.idx_stride = idx_stride; r.block = block; r.n_static = n_static; r.rows = rows;
         r.dst_pstride = rows_per_pattern * d; r.scale = scale;
         return r;
@@ -481,8 +502,8 @@ extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t la
     {
         dim3 grid(kh * dh + 2 * D.Hk * dh + Fp, P);
         const int nt = d >= 1024 ? 256 : (d >= 512 ? 128 : 64);
-        if (bf) hipLaunchKernelGGL(gather_rows_fp8_kernel<uint16_t>, grid, dim3(nt), 0, st, wr, d);
-        else hipLaunchKernelGGL(gather_rows_fp8_kernel<float>, grid, dim3(nt), 0, st, wr, d);
+        if (bf) hipLaunchKernelGGL((gather_rows_fp8_kernel<uint16_t, S>), grid, dim3(nt), 0, st, wr, d);
+        else hipLaunchKernelGGL((gather_rows_fp8_kernel<float, S>), grid, dim3(nt), 0, st, wr, d);
     }
     // biases are stored in the model dtype: the plain gathers
     auto region = [&](const void *src, void *dst, size_t elem_off, const int32_t *idx, int idx_stride, int block,
@@ -506,15 +527,38 @@ extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t la
         dim3 grid(ceil_div(cols_out, 32), ceil_div(d, 32), P);
         const size_t ps = (size_t)d * cols_out;
         if (bf)
-            hipLaunchKernelGGL(gather_transpose_fp8_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint8_t *)src,
+            hipLaunchKernelGGL((gather_transpose_fp8_kernel<uint16_t, S>), grid, dim3(256), 0, st, (const S *)src,
                                (uint16_t *)dst, idx, idx_stride, block, n_valid, cols_out, d, ps, scale);
         else
-            hipLaunchKernelGGL(gather_transpose_fp8_kernel<float>, grid, dim3(256), 0, st, (const uint8_t *)src,
+            hipLaunchKernelGGL((gather_transpose_fp8_kernel<float, S>), grid, dim3(256), 0, st, (const S *)src,
                                (float *)dst, idx, idx_stride, block, n_valid, cols_out, d, ps, scale);
     };
     transpose8(dense->W2, c->W2T, fi, D.F, 1, kf, Fp, dense->s2);
     transpose8(dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, dense->so);
     return check_launch("compact_heads_channels_fp8");
+}
+
+extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense,
+                                                 const int32_t *head_idx, const int32_t *group_idx,
+                                                 const int32_t *n_groups, const int32_t *ffn_idx,
+                                                 const sf_compact_layer *c, void *stream)
+{
+    return compact_coded<uint8_t>(desc, layer, dense, head_idx, group_idx, n_groups, ffn_idx, c, stream);
+}
+
+// FP16-stored dense weights: the six matrices of `dense` hold IEEE binary16, everything else is in the model dtype.
+extern "C" int32_t sf_compact_heads_channels_f16(const sf_desc *desc, int32_t layer, const sf_dense_layer *dense,
+                                                 const int32_t *head_idx, const int32_t *group_idx,
+                                                 const int32_t *n_groups, const int32_t *ffn_idx,
+                                                 const sf_compact_layer *c, void *stream)
+{
+    if (!dense) return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_f16: NULL argument");
+    sf_dense_layer_fp8 q{};
+    q.Wq = dense->Wq; q.Wk = dense->Wk; q.Wv = dense->Wv; q.Wo = dense->Wo; q.W1 = dense->W1; q.W2 = dense->W2;
+    q.sq = q.sk = q.sv = q.so = q.s1 = q.s2 = 1.0f;
+    q.bq = dense->bq; q.bk = dense->bk; q.bv = dense->bv; q.bo = dense->bo; q.b1 = dense->b1; q.b2 = dense->b2;
+    q.ln1_g = dense->ln1_g; q.ln1_b = dense->ln1_b; q.ln2_g = dense->ln2_g; q.ln2_b = dense->ln2_b;
+    return compact_coded<uint16_t>(desc, layer, &q, head_idx, group_idx, n_groups, ffn_idx, c, stream);
 }
 
 // FFN weights kept as E4M3 codes for the FP8 arithmetic path: the same gathers on bytes, nothing is decoded.

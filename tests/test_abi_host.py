@@ -158,6 +158,10 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_encoder_forward_fp8ffn(C.byref(d), C.byref(cl8f), C.byref(f8), *eargs) in (-2, -3)  # fp32 descriptor
     cl8f.k_ffn = 300
     assert L.sf_encoder_forward_fp8ffn(C.byref(d8ok), C.byref(cl8f), C.byref(f8), *eargs) == -1   # k_ffn mismatch
+    # FP16-stored weights
+    assert L.sf_compact_heads_channels_f16(C.byref(d), 0, None, one, one, one, one, C.byref(cl8), None) == -1
+    dl16 = sf.SfDenseLayer()
+    assert L.sf_compact_heads_channels_f16(C.byref(d), 0, C.byref(dl16), one, one, one, one, C.byref(cl8), None) == -1
     # token compaction
     assert L.sf_token_compact(C.byref(d), None, one, 8, one, one, one, one, one, one, None) == -1
     assert L.sf_token_compact(C.byref(d), one, one, 0, C.c_void_p(512), one, one, one, one, one, None) == -1      # Lc < 1

@@ -187,6 +187,52 @@ def test_fp8_weight_storage_full_size(name):
     _fp8_case(W.make_workload(W.CONFIGS[name]))
 
 
+def _f16_case(wl):
+    """Weights stored as binary16 (numpy's float16 cast as the offline quantiser): compaction from that storage is
+    bit-identical to compaction of the oracle's dequantised weights."""
+    import copy
+    s = wl.spec
+    bf = s.dtype == "bf16"
+    wl2 = copy.copy(wl)
+    wl2.layers, bits = [], []
+    for lw in wl.layers:
+        lw2, q = dict(lw), {}
+        for n in W8:
+            q[n] = lw[n].astype(np.float16).view(np.uint16)
+            lw2[n] = orc.dequant_f16(q[n], bf).astype(np.float32)
+        wl2.layers.append(lw2); bits.append(q)
+    dm = DeviceModel(wl2).build_plan()
+    for l in range(s.n_layers):
+        d16 = {n: (torch.from_numpy(bits[l][n].view(np.float16)).cuda() if n in W8 else dm.dense[l][n]) for n in dm.dense[l]}
+        cl = sf.compact_heads_channels_f16(dm.desc, l, d16, dm.masks, int(wl.k_head[l]), int(wl.k_ffn[l]))
+        torch.cuda.synchronize()
+        ref = dm.layers[l]
+        for n in ("Wqkv", "bqkv", "WoT", "W1", "b1", "W2T"):
+            a, b = getattr(cl, n), getattr(ref, n)
+            assert (a is None) == (b is None), n
+            if a is not None:
+                assert torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
+                                   b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32)), (l, n)
+        dm.layers[l] = cl
+    return wl2, dm
+
+
+@pytest.mark.parametrize("kw", [dict(dtype="f32"), dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=3)])
+def test_f16_weight_storage_small(kw):
+    _say(f"f16 storage {kw}")
+    wl2, dm = _f16_case(W.make_workload(W.small_spec(**kw)))
+    y16 = dm.forward()[0].clone()
+    torch.cuda.synchronize()
+    _encoder_parity(wl2)                                     # the oracle on the dequantised weights
+    assert torch.equal(y16, DeviceModel(wl2).build_plan().forward()[0])
+
+
+@pytest.mark.parametrize("name", ["C1", "C5"])
+def test_f16_weight_storage_full_size(name):
+    _say(f"f16 storage {name}")
+    _f16_case(W.make_workload(W.CONFIGS[name]))
+
+
 # -------------------------------------------------- SentryGate: Eq. (1) and the global threshold
 def _gate_case(nl, M, Hq, Hk, F, Hd, nonlin, seed):
     gp = W.make_gate_params(nl, M, Hq, F, Hd, seed)
