@@ -205,6 +205,8 @@ def _compare(c, got, pre_ln, residual, rows_of, exact):
     dict(B=2, L=520, d=384, F=900, P=3, kf=513, act=1),               # GELU, three K steps up, five down
     dict(B=1, L=192, d=256, F=256, P=1, kf=129),                      # the smallest accepted shape
     dict(B=5, L=256, d=512, F=1024, P=2, kf=1024),                    # nothing pruned, exact tiles
+    dict(B=1, L=200, d=1280, F=384, P=1, kf=200),                     # wide rows: four chunks per lane in the LayerNorm
+    dict(B=2, L=193, d=2176, F=256, P=2, kf=129),                     # eight chunks per lane, 17 K steps up
 ])
 @pytest.mark.parametrize("pre_ln,residual", [(True, True), (False, False)])
 def test_pruned_ffn_fp8_parity_small(kw, pre_ln, residual):
