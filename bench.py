@@ -30,7 +30,7 @@ GEMM_KERNEL_NAMES = {
     "qkv_proj": "gemm_bf16_ws_kernel<0> (Q/K/V projection, V as the transposed column range)",
     "qk_proj": "gemm_bf16_ws_kernel<0> (Q/K projection)",
     "v_proj": "gemm_bf16_fast_kernel<..., true, 0> (V projection, transposed output)",
-    "o_proj": "gemm_bf16_ws_kernel<0> (output projection + residual)",
+    "o_proj": "gemm_bf16_ws_kernel<0> (output projection + residual), or gemm_bf16_fast_kernel on the active rows only",
     "ffn_up": "gemm_bf16_ws_kernel<1> (FFN up-projection + ReLU)",
     "ffn_down": "gemm_bf16_ws_kernel<0> (FFN down-projection + residual)",
 }
@@ -46,8 +46,10 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_flops(wl, masks_host, U):
-    """Flops credited per step: kept heads / kept groups / kept channels only, no padding."""
+def algorithmic_flops(wl, masks_host, U, oproj_rows=None):
+    """Flops credited per step: kept heads / kept groups / kept channels only, no padding.  oproj_rows[l]: rows
+    per sample that go through the output projection of layer l when the library projects the active rows only
+    (the distinct rows that are active in some head, counted from the selection; None: every row)."""
     import numpy as np
     s = wl.spec
     B, L, d, dh = wl.x.shape[0], s.L, s.d, s.dh
@@ -57,7 +59,8 @@ def algorithmic_flops(wl, masks_host, U):
         kh, kf = int(wl.k_head[l]), int(wl.k_ffn[l])
         ng = masks_host["n_groups"][l][wl.pattern_id].astype(np.int64)          # per sample
         gemm += int((2 * L * d * dh * (kh + 2 * ng)).sum())                     # Q, K, V projections
-        gemm += B * 2 * L * kh * dh * d                                         # output projection
+        rows_o = B * L if oproj_rows is None or oproj_rows[l] is None else int(oproj_rows[l].sum()) + B
+        gemm += 2 * rows_o * kh * dh * d                                        # output projection (+ one context row per sample)
         gemm += B * 4 * L * d * kf                                              # both FFN GEMMs
         if 0 < U < L:
             score += int((kh * 2 * n_allowed * n_allowed * dh).sum())           # QK^T stream of the sparsity score
@@ -65,7 +68,7 @@ def algorithmic_flops(wl, masks_host, U):
     return {"gemm": gemm, "score": score, "active": active, "total": gemm + score + active}
 
 
-def gemm_flops_by_launch(wl, masks_host):
+def gemm_flops_by_launch(wl, masks_host, oproj_rows=None):
     """Algorithmic flops of the five GEMM launches of a layer, summed over layers."""
     import numpy as np
     s = wl.spec
@@ -76,7 +79,8 @@ def gemm_flops_by_launch(wl, masks_host):
         ng = masks_host["n_groups"][l][wl.pattern_id].astype(np.int64)
         out["qk_proj"] += int((2 * L * d * dh * (kh + ng)).sum())
         out["v_proj"] += int((2 * L * d * dh * ng).sum())
-        out["o_proj"] += B * 2 * L * kh * dh * d
+        rows_o = B * L if oproj_rows is None or oproj_rows[l] is None else int(oproj_rows[l].sum())
+        out["o_proj"] += 2 * rows_o * kh * dh * d
         out["ffn_up"] += B * 2 * L * d * kf
         out["ffn_down"] += B * 2 * L * d * kf
     return out
@@ -127,7 +131,15 @@ def bench_config(name, steps, warmup, extras, cpu, use_graph=False, repeats=1):
     U = sf.num_active(dm.desc)
     y = torch.empty_like(dm.x)
     masks_host = {k: to_host(v) for k, v in dm.masks.items()}
-    flops = algorithmic_flops(wl, masks_host, U)
+    # layers whose output projection runs on the active rows only: count those rows from one forward's selection
+    oproj_rows = [None] * s.n_layers
+    if any(sf.active_projection_rows(dm.desc, int(k)) > 0 for k in wl.k_head):
+        _, sel, _ = dm.forward(want_sel=True)
+        sel_h = to_host(sel)
+        for l in range(s.n_layers):
+            if sf.active_projection_rows(dm.desc, int(wl.k_head[l])) > 0:
+                oproj_rows[l] = np.array([len(np.unique(sel_h[l, b][sel_h[l, b] >= 0])) for b in range(B)])
+    flops = algorithmic_flops(wl, masks_host, U, oproj_rows)
 
     def step():                       # the whole hot path
         dm.build_plan()
@@ -201,7 +213,7 @@ def bench_config(name, steps, warmup, extras, cpu, use_graph=False, repeats=1):
                 per = n // steps
                 nper = per // s.n_layers
                 names = (["qkv_proj"] if nper == 4 else ["qk_proj", "v_proj"]) + ["o_proj", "ffn_up", "ffn_down"]
-                fl = gemm_flops_by_launch(wl, masks_host)
+                fl = gemm_flops_by_launch(wl, masks_host, oproj_rows)
                 fl["qkv_proj"] = fl["qk_proj"] + fl["v_proj"]
                 by = {}
                 for j, nm in enumerate(names):
@@ -211,6 +223,13 @@ def bench_config(name, steps, warmup, extras, cpu, use_graph=False, repeats=1):
                               "tflops": fl[nm] / s.n_layers / (us * 1e-6) / 1e12}
                 prof["gemm"]["by_launch"] = by
     res["kernels"] = prof
+    if any(r is not None for r in oproj_rows):
+        res["active_row_projection"] = {
+            "layers": [l for l in range(s.n_layers) if oproj_rows[l] is not None],
+            "rows_projected_per_sample_mean": float(np.mean([r.mean() for r in oproj_rows if r is not None])),
+            "rows_per_sample": L,
+            "note": "output projection on the rows that are active in some head; the other rows of a sample take the "
+                    "projection of its context vectors (computed once); flops are credited for the projected rows only"}
     return res, dm, wl, flops
 
 

@@ -346,6 +346,15 @@ int32_t sf_pruned_ffn_forward(const sf_desc *desc, const sf_compact_layer *layer
  *   score_out   [n_layers,B,Hq'max,L] fp32 or NULL
  */
 size_t sf_encoder_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers_host);
+/* How sf_encoder_forward projects the attention output of a layer with k_head
+ * kept heads (Sec. 4.4: the rows that are not selected all take their group's
+ * context vector).  0: every row goes through the output projection.  n > 0:
+ * at most a quarter of a sample's rows can be active in some head; only those (at
+ * most n = k_head*U rounded up to 128 per sample) are projected, every other
+ * row of a sample receives the projection of its context vectors, computed
+ * once.  Same results up to the summation order of that one vector.  (A
+ * reporting aid: the count of arithmetic actually done differs.) */
+int32_t sf_active_projection_rows(const sf_desc *desc, int32_t k_head);
 int32_t sf_encoder_forward(const sf_desc *desc, const sf_compact_layer *layers_host,
                            const void *X, const int32_t *pattern_id, const uint8_t *key_valid,
                            const int32_t *sample_idx, const void *final_g, const void *final_b,

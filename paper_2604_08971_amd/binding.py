@@ -28,7 +28,8 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_moe_ffn_workspace_bytes", "sf_moe_ffn_forward", "sf_gate_eval", "sf_budget_search",
            "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8", "sf_quantize_fp8",
            "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
-           "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16"]
+           "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
+           "sf_active_projection_rows"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -108,7 +109,8 @@ def lib():
                   "sf_profile_end", "sf_compact_moe_experts", "sf_moe_ffn_forward", "sf_gate_eval",
                   "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
-                  "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16"):
+                  "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
+                  "sf_active_projection_rows"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -159,6 +161,7 @@ def lib():
         L.sf_profile_begin.argtypes = [C.c_int32, C.c_int32]
         L.sf_profile_end.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
         L.sf_num_active.argtypes = [C.POINTER(SfDesc)]
+        L.sf_active_projection_rows.argtypes = [C.POINTER(SfDesc), C.c_int32]
         L.sf_ffn_padded.argtypes = [C.POINTER(SfDesc), C.c_int32]
         _lib = L
     return _lib
@@ -192,6 +195,13 @@ def num_active(desc: SfDesc) -> int:
     if u < 0:
         _check(u, "sf_num_active")
     return int(u)
+
+
+def active_projection_rows(desc: SfDesc, k_head: int) -> int:
+    r = lib().sf_active_projection_rows(C.byref(desc), int(k_head))
+    if r < 0:
+        _check(r, "sf_active_projection_rows")
+    return int(r)
 
 
 def ffn_padded(desc: SfDesc, k_ffn: int) -> int:

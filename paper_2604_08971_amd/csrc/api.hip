@@ -102,11 +102,13 @@ static FfnWs ffn_ws(const Dims &D, int Fp, bool pre_ln, void *ws)
 // encoder's residual stream).  With x_f32, pre_ln is required (the GEMM reads bf16).
 static int32_t ffn_forward(const Dims &D, const sf_compact_layer &ly, const void *X, bool x_f32,
                            const int32_t *pattern_id, bool pre_ln, bool add_residual, void *Y, bool y_f32,
-                           void *xn, void *hid, hipStream_t st)
+                           void *xn, void *hid, hipStream_t st, bool xn_ready = false)
 {
     const int Fp = (int)align_up(ly.k_ffn, D.ffn_pad);
     const void *in = X;
-    if (pre_ln) {
+    if (xn_ready) {
+        in = xn;                              // LN2(X) is already there (written together with X)
+    } else if (pre_ln) {
         layernorm(D.dtype, x_f32, X, ly.ln2_g, ly.ln2_b, D.eps, (int64_t)D.B * D.L, D.d, xn, st);
         in = xn;
     }
@@ -129,6 +131,8 @@ static int32_t ffn_forward(const Dims &D, const sf_compact_layer &ly, const void
 // ---- encoder ----------------------------------------------------------------------
 struct EncWs {
     void *xn, *qkv, *vt, *att, *x1, *x2, *hid, *attn_ws;     // x1, x2: the fp32 residual stream
+    // output projection of the active rows only (lazy_proj.hip): compact rows, their projection, row maps, c_b
+    void *lz_A; float *lz_C, *lz_c; int32_t *lz_arow, *lz_pos, *lz_n, *lz_cnt, *lz_blk; int lz_cap;
     size_t attn_ws_bytes, bytes;
     int kh_max, Fp_max, Lp;
 };
@@ -172,6 +176,18 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     }
     w.attn_ws_bytes = amax;
     w.attn_ws = c.take<char>(amax);
+    w.lz_cap = bf ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
+    if (w.lz_cap) {
+        const size_t crow = (size_t)D.B * w.lz_cap;
+        w.lz_A = c.take<char>(crow * kh_max * D.dh * es);
+        w.lz_C = c.take<float>(crow * D.d);
+        w.lz_c = c.take<float>((size_t)D.B * D.d);
+        w.lz_arow = c.take<int32_t>(crow);
+        w.lz_pos = c.take<int32_t>(rows);
+        w.lz_n = c.take<int32_t>(D.B);
+        w.lz_cnt = c.take<int32_t>((size_t)D.B * ceil_div(D.L, 256));
+        w.lz_blk = c.take<int32_t>((size_t)D.B * (w.lz_cap / 128));
+    }
     w.bytes = c.off;
     return SF_OK;
 }
@@ -266,6 +282,14 @@ extern "C" int32_t sf_pruned_ffn_forward(const sf_desc *desc, const sf_compact_l
                                  w.hid, st))
         return rc;
     return check_launch("pruned_ffn_forward");
+}
+
+extern "C" int32_t sf_active_projection_rows(const sf_desc *desc, int32_t k_head)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (k_head < 1 || k_head > D.Hq) return fail(SF_ERR_INVALID_ARG, "active_projection_rows: k_head out of range");
+    return D.dtype == SF_BF16 ? lazy_cap(D.L, k_head, D.U, D.dh, D.d) : 0;
 }
 
 extern "C" size_t sf_encoder_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers)
@@ -383,7 +407,38 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         a.score_out = score_out ? score_out + l * score_layer : nullptr;
         a.O = w.att; a.ldo = (int64_t)kh * dh;
         a.ws = w.attn_ws; a.ws_bytes = w.attn_ws_bytes;
+        // Most rows lazy in every head: project only the active rows, the rest of a sample shares one vector
+        // (the FP8-FFN variant keeps the plain path: its LayerNorm is fused with the quantiser)
+        const int capA = (w.lz_cap && !ffn8) ? lazy_cap(D.L, kh, D.U, dh, D.d) : 0;
+        const bool lazy = capA > 0 && capA <= w.lz_cap &&
+                          !(((uintptr_t)ly.bo | (uintptr_t)ly.ln2_g | (uintptr_t)ly.ln2_b | (uintptr_t)in) & 15);
+        a.skip_fill = lazy;
         if (int32_t rc = attention_forward(D.dtype, a, st)) return rc;
+        if (lazy) {
+            const AttnPlan pl = attn_plan(D.dtype, a, a.ws);
+            lazy_rows_active(pl.slot, pattern_id, D.B, kh, D.L, capA, w.lz_cnt, w.lz_arow, w.lz_pos, w.lz_n, w.lz_blk, st);
+            lazy_att_compact(w.att, a.ldo, pl.slot, pl.stats, ly.head_group, D.Hq, pattern_id, w.lz_arow, w.lz_n, D.B, kh,
+                             Hk, D.L, dh, capA, w.lz_A, st);
+            GemmArgs o{};
+            o.A = w.lz_A; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
+            // 128-row blocks of the compact buffer, each with its sample's pattern (-1: no rows, skipped)
+            o.w_pstride = (int64_t)D.d * kh * dh; o.pattern_id = w.lz_blk;
+            o.B = D.B * (capA / 128); o.L = 128; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
+            o.C = w.lz_C; o.ldc = D.d; o.c_f32 = 1;
+            if (int32_t rc = gemm(D.dtype, o, st)) return rc;
+            lazy_ctx_proj(pl.stats, ly.head_group, D.Hq, pattern_id, ly.WoT, (int64_t)D.d * kh * dh, ly.bo, D.B, kh, Hk, dh,
+                          D.d, w.lz_c, st);
+            // x1 = x + projection, and xn = LN2(x1), in one pass over the rows
+            lazy_combine_ln(in, in_f32, w.lz_pos, w.lz_C, ly.bo, w.lz_c, D.B, D.L, capA, ly.ln2_g, ly.ln2_b, D.eps, D.d,
+                            static_cast<float *>(w.x1), w.xn, st);
+            const bool to_y = l == D.nl - 1 && !final_ln;
+            if (int32_t rc = ffn_forward(D, ly, w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y, w.xn,
+                                         w.hid, st, true))
+                return rc;
+            in = w.x2;
+            in_f32 = true;
+            continue;
+        }
 
         // x1 = x + att Wo' + bo   (only the kept heads' rows of Wo exist)
         GemmArgs o{};

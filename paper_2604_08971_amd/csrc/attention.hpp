@@ -21,6 +21,7 @@ struct AttnArgs {
     int32_t *sel_out;                        // [B,selH,U] or NULL
     float *score_out;                        // [B,selH,L] or NULL
     int selH;                                // heads per sample in forced_sel / sel_out / score_out (0 = nH)
+    int skip_fill;                           // leave the lazy rows of O unwritten (the caller projects them itself)
     void *ws; size_t ws_bytes;
 };
 
@@ -50,6 +51,21 @@ int32_t score_bf16(const AttnArgs &a, const void *Kx, sf_strides skx, int Lk, co
                    const float *stats, float *score, int scoreH, hipStream_t st);
 int32_t attend_bf16(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_strides svt,
                     const int32_t *sel, int selH, hipStream_t st);
+
+// Output projection when most rows are lazy (lazy_proj.hip).  lazy_cap: rows per sample of the compact buffers, 0
+// when the shortcut does not apply.  slot [B,nH,L] and stats are the pieces of the attention plan.
+int lazy_cap(int L, int nH, int U, int dh, int d);
+void lazy_rows_active(const int32_t *slot, const int32_t *pattern_id, int B, int nH, int L, int capA, int32_t *counts,
+                      int32_t *arow, int32_t *pos_of, int32_t *n_act, int32_t *blk_pattern, hipStream_t st);
+void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const float *stats, const int32_t *head_group,
+                      int hg_stride, const int32_t *pattern_id, const int32_t *arow, const int32_t *n_act, int B, int nH,
+                      int nG, int L, int dh, int capA, void *Ac, hipStream_t st);
+void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
+                   const void *WoT, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d, float *cvec,
+                   hipStream_t st);
+void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const float *Cc, const void *bo, const float *cvec,
+                     int B, int L, int capA, const void *gamma, const void *beta, float eps, int d, float *x1, void *xn,
+                     hipStream_t st);
 
 constexpr int STAT_CHUNK = 128;     // keys per partial-sum block of the K/V statistics
 

@@ -614,7 +614,7 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
                            a.nH, a.L, a.dh, a.U, pl.Upad, pl.splits, n_waves, sel, selH, pl.part_o, pl.part_ml,
                            (__bf16 *)a.O, a.ldo);
     }
-    {   // with U == L rows can still be lazy (fewer allowed rows than U)
+    if (!a.skip_fill) {   // with U == L rows can still be lazy (fewer allowed rows than U)
         const bool v8 = dtype == SF_BF16 && a.dh % 8 == 0 && a.ldo % 8 == 0 && ((uintptr_t)a.O % 16 == 0);
         dim3 grid(ceil_div(a.L, 32), a.B);
         const size_t fl = (size_t)a.nH * a.dh * 4 + (size_t)a.nH * 32 * 4;

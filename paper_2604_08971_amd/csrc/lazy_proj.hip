@@ -1,0 +1,296 @@
+// Output projection after SentryAttend when most rows are lazy (Sec. 4.4: the T - U rows that are not selected
+// take a context vector aggregated from V_g).  Every row that is lazy in ALL kept heads of its sample carries the
+// same attention output - the concatenated group context vectors - so its projection is one vector per sample,
+//     c_b = ctx_b Wo' + bo.
+// Only the rows that are active in some head (at most Hq'*U per sample) go through the GEMM, from a compact buffer;
+// one pass then forms the residual stream x1 = x + (projection of the row | c_b) and the LayerNorm that follows it.
+// The arithmetic is that of fill + projection + residual + LayerNorm; only the summation order of c_b differs.
+#include "attention.hpp"
+
+namespace sf {
+
+namespace {
+
+// The rows with an active head, ascending, in two passes over 256-row chunks (one block per sample and chunk).
+// Pass 1 counts, pass 2 places: arow[b, j] = row of compact position j, pos_of[b, i] = compact position of row i
+// or -1, n_act[b] = their number (<= capA by construction: a head has at most U active rows and capA >= nH*U), and
+// blk_pattern[b, k] = the sample's pattern for the 128-row blocks of the compact buffer that hold rows, -1 for the
+// empty ones (the GEMM skips those).
+__device__ __forceinline__ bool row_active(const int32_t *__restrict__ slot, int b, int nH, int L, int i)
+{
+    bool act = false;
+    if (i < L)
+        for (int h = 0; h < nH; ++h) act = act || slot[((int64_t)b * nH + h) * L + i] >= 0;
+    return act;
+}
+
+__global__ __launch_bounds__(256) void rows_active_count_kernel(const int32_t *__restrict__ slot, int nH, int L,
+                                                                int32_t *__restrict__ counts)
+{
+    __shared__ int wsum[4];
+    const int c = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t m = __ballot(row_active(slot, b, nH, L, c * 256 + (int)threadIdx.x));
+    if (lane == 0) wsum[wave] = __popcll(m);
+    __syncthreads();
+    if (threadIdx.x == 0) counts[(int64_t)b * gridDim.x + c] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+__global__ __launch_bounds__(256) void rows_active_place_kernel(const int32_t *__restrict__ slot, int nH, int L, int capA,
+                                                                const int32_t *__restrict__ counts,
+                                                                const int32_t *__restrict__ pattern_id,
+                                                                int32_t *__restrict__ arow, int32_t *__restrict__ pos_of,
+                                                                int32_t *__restrict__ n_act, int32_t *__restrict__ blk_pattern)
+{
+    __shared__ int wsum[4];
+    __shared__ int base_s, total_s;
+    const int c = blockIdx.x, b = blockIdx.y, nchunk = gridDim.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x < 64) {                                   // nchunk <= 64 (L <= 16384)
+        const int v = (int)threadIdx.x < nchunk ? counts[(int64_t)b * nchunk + threadIdx.x] : 0;
+        int before = (int)threadIdx.x < c ? v : 0, all = v;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) { before += __shfl_xor(before, o); all += __shfl_xor(all, o); }
+        if (threadIdx.x == 0) { base_s = before; total_s = all; }
+    }
+    const int i = c * 256 + (int)threadIdx.x;
+    const bool act = row_active(slot, b, nH, L, i);
+    const uint64_t m = __ballot(act);
+    if (lane == 0) wsum[wave] = __popcll(m);
+    __syncthreads();
+    int pos = base_s + __popcll(m & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) pos += wsum[w];
+    const bool keep = act && pos < capA;
+    if (i < L) pos_of[(int64_t)b * L + i] = keep ? pos : -1;
+    if (keep) arow[(int64_t)b * capA + pos] = i;
+    if (c == 0) {
+        const int total = min(total_s, capA);
+        if (threadIdx.x == 0) n_act[b] = total;
+        const int p = pattern_id ? pattern_id[b] : 0;
+        for (int k = threadIdx.x; k < capA / 128; k += 256) blk_pattern[(int64_t)b * (capA / 128) + k] = k * 128 < total ? p : -1;
+    }
+}
+
+// 8 consecutive context values of head h (group g of sample b), rounded to bf16 as the attention output stores them
+__device__ __forceinline__ bf16x8 ctx8(const float *__restrict__ stats, int b, int nG, int g, int dh, int e0)
+{
+    const float *c = stats + (((int64_t)b * nG + g) * 2 + 1) * dh + e0;
+    bf16x8 o;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) o[t] = (__bf16)c[t];
+    return o;
+}
+
+// One wave per compact row: the attention output of an active row - its active heads from `att`, its lazy heads from
+// the context vectors - or a zero row behind n_act[b].  K = nH*dh, a multiple of 8; dh a multiple of 8.
+__global__ __launch_bounds__(256) void att_compact_kernel(const __bf16 *__restrict__ att, int64_t ldo,
+                                                          const int32_t *__restrict__ slot, const float *__restrict__ stats,
+                                                          const int32_t *__restrict__ head_group, int hg_stride,
+                                                          const int32_t *__restrict__ pattern_id,
+                                                          const int32_t *__restrict__ arow, const int32_t *__restrict__ n_act,
+                                                          int B, int nH, int nG, int L, int dh, int capA,
+                                                          __bf16 *__restrict__ Ac)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= (int64_t)B * capA) return;
+    const int b = (int)(r / capA), j = (int)(r % capA);
+    const int K = nH * dh;
+    __bf16 *dst = Ac + r * K;
+    if (j >= n_act[b]) {
+        const bf16x8 z = {};
+        for (int c = lane; c < K / 8; c += 64) *reinterpret_cast<bf16x8 *>(dst + c * 8) = z;
+        return;
+    }
+    const int i = arow[r];
+    const int p = pattern_id ? pattern_id[b] : 0;
+    for (int c = lane; c < K / 8; c += 64) {
+        const int h = (c * 8) / dh, e0 = (c * 8) % dh;
+        bf16x8 v;
+        if (slot[((int64_t)b * nH + h) * L + i] >= 0)
+            v = *reinterpret_cast<const bf16x8 *>(att + ((int64_t)b * L + i) * ldo + c * 8);
+        else
+            v = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
+        *reinterpret_cast<bf16x8 *>(dst + c * 8) = v;
+    }
+}
+
+// One wave per (sample, output feature n): c[b, n] = sum_k bf16(ctx_b[k]) WoT[p_b][n, k] + bo[n], fp32.
+__global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__ stats, const int32_t *__restrict__ head_group,
+                                                       int hg_stride, const int32_t *__restrict__ pattern_id,
+                                                       const __bf16 *__restrict__ WoT, int64_t w_pstride,
+                                                       const __bf16 *__restrict__ bo, int B, int nH, int nG, int dh,
+                                                       int d, float *__restrict__ cvec)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= (int64_t)B * d) return;
+    const int b = (int)(r / d), n = (int)(r % d);
+    const int p = pattern_id ? pattern_id[b] : 0;
+    const int K = nH * dh;
+    const __bf16 *w = WoT + (int64_t)p * w_pstride + (int64_t)n * K;
+    float acc = 0.f;
+    for (int c = lane; c < K / 8; c += 64) {
+        const int h = (c * 8) / dh, e0 = (c * 8) % dh;
+        const bf16x8 x = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
+        const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(w + c * 8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc = fmaf((float)x[t], (float)wv[t], acc);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) cvec[r] = acc + (bo ? (float)bo[n] : 0.f);
+}
+
+// One wave per token row: x1 = x + (row active ? Cc[b, pos] + bo : c_b), written as fp32, then the LayerNorm of x1
+// (statistics in fp32, biased variance) written as bf16.  d % 8 == 0, d <= 512 * NCH.
+template <class TI, int NCH>
+__global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ x, const int32_t *__restrict__ pos_of,
+                                                         const float *__restrict__ Cc, const __bf16 *__restrict__ bo,
+                                                         const float *__restrict__ cvec, int L, int capA,
+                                                         const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ beta,
+                                                         float eps, int64_t rows, int d, float *__restrict__ x1,
+                                                         __bf16 *__restrict__ xn)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int64_t b = row / L;
+    const int j = pos_of[row];
+    const float *add = j >= 0 ? Cc + (b * capA + j) * d : cvec + b * d;
+    const TI *xr = x + row * d;
+    const int nch = d >> 3;
+    float v[NCH][8];
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int ch = lane + c * 64;
+        if (ch < nch) {
+            if constexpr (sizeof(TI) == 2) {
+                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(xr + ch * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[c][e] = (float)t[e];
+            } else {
+                const f32x4 t0 = *reinterpret_cast<const f32x4 *>(xr + ch * 8);
+                const f32x4 t1 = *reinterpret_cast<const f32x4 *>(xr + ch * 8 + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[c][e] = t0[e]; v[c][4 + e] = t1[e]; }
+            }
+            const f32x4 a0 = *reinterpret_cast<const f32x4 *>(add + ch * 8);
+            const f32x4 a1 = *reinterpret_cast<const f32x4 *>(add + ch * 8 + 4);
+            float bb[8];
+            if (j >= 0 && bo) {
+                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(bo + ch * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bb[e] = (float)t[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bb[e] = 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[c][e] += a0[e] + bb[e];
+                v[c][4 + e] += a1[e] + bb[4 + e];
+            }
+            f32x4 o0, o1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { o0[e] = v[c][e]; o1[e] = v[c][4 + e]; }
+            __builtin_nontemporal_store(o0, reinterpret_cast<f32x4 *>(x1 + row * d + ch * 8));
+            __builtin_nontemporal_store(o1, reinterpret_cast<f32x4 *>(x1 + row * d + ch * 8 + 4));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += v[c][e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    const float mean = s / d;
+    float q = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+        if (lane + c * 64 < nch) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { const float t = v[c][e] - mean; q += t * t; }
+        }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o);
+    const float inv = 1.0f / sqrtf(q / d + eps);
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int ch = lane + c * 64;
+        if (ch >= nch) continue;
+        bf16x8 gm, bt, o;
+        if (gamma) gm = *reinterpret_cast<const bf16x8 *>(gamma + ch * 8);
+        if (beta) bt = *reinterpret_cast<const bf16x8 *>(beta + ch * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float z = (v[c][e] - mean) * inv;
+            if (gamma) z *= (float)gm[e];
+            if (beta) z += (float)bt[e];
+            o[e] = (__bf16)z;
+        }
+        *reinterpret_cast<bf16x8 *>(xn + row * d + ch * 8) = o;
+    }
+}
+
+}  // namespace
+
+// Rows per sample of the compact buffers (a multiple of 128: the GEMM takes them as 128-row blocks), or 0 when the
+// shortcut does not apply: it needs the sparse pattern, 16-byte rows, and at most a quarter of the rows can be active
+// (measured: with half of the rows in the compact projection the extra passes cost more than the projection saves).
+int lazy_cap(int L, int nH, int U, int dh, int d)
+{
+    if (U <= 0 || U >= L || L > 16384 || dh % 8 || d % 8 || d > 2048) return 0;
+    const int64_t cap = (int64_t)align_up((size_t)nH * U, 128);
+    if (cap * 4 > L) return 0;
+    return (int)cap;
+}
+
+void lazy_rows_active(const int32_t *slot, const int32_t *pattern_id, int B, int nH, int L, int capA, int32_t *counts,
+                      int32_t *arow, int32_t *pos_of, int32_t *n_act, int32_t *blk_pattern, hipStream_t st)
+{
+    dim3 grid(ceil_div(L, 256), B);
+    hipLaunchKernelGGL(rows_active_count_kernel, grid, dim3(256), 0, st, slot, nH, L, counts);
+    hipLaunchKernelGGL(rows_active_place_kernel, grid, dim3(256), 0, st, slot, nH, L, capA, counts, pattern_id, arow,
+                       pos_of, n_act, blk_pattern);
+}
+
+void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const float *stats, const int32_t *head_group,
+                      int hg_stride, const int32_t *pattern_id, const int32_t *arow, const int32_t *n_act, int B, int nH,
+                      int nG, int L, int dh, int capA, void *Ac, hipStream_t st)
+{
+    const int64_t rows = (int64_t)B * capA;
+    hipLaunchKernelGGL(att_compact_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, (const __bf16 *)att, ldo,
+                       slot, stats, head_group, hg_stride, pattern_id, arow, n_act, B, nH, nG, L, dh, capA, (__bf16 *)Ac);
+}
+
+void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
+                   const void *WoT, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d, float *cvec,
+                   hipStream_t st)
+{
+    const int64_t rows = (int64_t)B * d;
+    hipLaunchKernelGGL(ctx_proj_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, stats, head_group, hg_stride,
+                       pattern_id, (const __bf16 *)WoT, w_pstride, (const __bf16 *)bo, B, nH, nG, dh, d, cvec);
+}
+
+void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const float *Cc, const void *bo, const float *cvec,
+                     int B, int L, int capA, const void *gamma, const void *beta, float eps, int d, float *x1, void *xn,
+                     hipStream_t st)
+{
+    const int64_t rows = (int64_t)B * L;
+    dim3 grid((unsigned)((rows + 3) / 4));
+#define SF_CLN_ARGS(TI) grid, dim3(256), 0, st, (const TI *)x, pos_of, Cc, (const __bf16 *)bo, cvec, L, capA, \
+                        (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, x1, (__bf16 *)xn
+    if (x_f32) {
+        if (d <= 512) hipLaunchKernelGGL((combine_ln_kernel<float, 1>), SF_CLN_ARGS(float));
+        else if (d <= 1024) hipLaunchKernelGGL((combine_ln_kernel<float, 2>), SF_CLN_ARGS(float));
+        else hipLaunchKernelGGL((combine_ln_kernel<float, 4>), SF_CLN_ARGS(float));
+    } else {
+        if (d <= 512) hipLaunchKernelGGL((combine_ln_kernel<__bf16, 1>), SF_CLN_ARGS(__bf16));
+        else if (d <= 1024) hipLaunchKernelGGL((combine_ln_kernel<__bf16, 2>), SF_CLN_ARGS(__bf16));
+        else hipLaunchKernelGGL((combine_ln_kernel<__bf16, 4>), SF_CLN_ARGS(__bf16));
+    }
+#undef SF_CLN_ARGS
+}
+
+}  // namespace sf

@@ -778,6 +778,13 @@ def _encoder_parity(wl, samples=None, U_override=-1, max_pick_diff_frac=0.03, sa
     dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90), B=4),
     dict(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=300, seg=(100, 33, 64), extra=3, B=3, nl=3,
          head_keep=(0.4, 0.9), act=1, c=3),
+    # long enough that at most a quarter of the rows are active in some head: the output projection then runs on the
+    # active rows only and the others take their sample's projected context vector
+    dict(dtype="bf16", d=64, dh=32, Hq=4, Hk=2, F=192, seg=(250, 150, 112), B=4, c=2),
+    dict(dtype="bf16", d=128, dh=32, Hq=8, Hk=4, F=256, seg=(200, 120, 130, 70), extra=2, B=5, nl=3, head_keep=(0.3, 0.6),
+         act=1, c=1, dropout="upto:2"),
+    dict(dtype="bf16", d=128, dh=32, Hq=4, Hk=1, F=128, seg=(300, 213), extra=0, B=2, nl=2, head_keep=0.25, c=3,
+         dropout="none", final_ln=False),
 ])
 def test_encoder_parity_small(kw):
     _say(f"encoder small {kw}")
