@@ -408,8 +408,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         a.O = w.att; a.ldo = (int64_t)kh * dh;
         a.ws = w.attn_ws; a.ws_bytes = w.attn_ws_bytes;
         // Most rows lazy in every head: project only the active rows, the rest of a sample shares one vector
-        // (the FP8-FFN variant keeps the plain path: its LayerNorm is fused with the quantiser)
-        const int capA = (w.lz_cap && !ffn8) ? lazy_cap(D.L, kh, D.U, dh, D.d) : 0;
+        const int capA = w.lz_cap ? lazy_cap(D.L, kh, D.U, dh, D.d) : 0;
         const bool lazy = capA > 0 && capA <= w.lz_cap &&
                           !(((uintptr_t)ly.bo | (uintptr_t)ly.ln2_g | (uintptr_t)ly.ln2_b | (uintptr_t)in) & 15);
         a.skip_fill = lazy;
@@ -428,13 +427,23 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             if (int32_t rc = gemm(D.dtype, o, st)) return rc;
             lazy_ctx_proj(pl.stats, ly.head_group, D.Hq, pattern_id, ly.WoT, (int64_t)D.d * kh * dh, ly.bo, D.B, kh, Hk, dh,
                           D.d, w.lz_c, st);
-            // x1 = x + projection, and xn = LN2(x1), in one pass over the rows
-            lazy_combine_ln(in, in_f32, w.lz_pos, w.lz_C, ly.bo, w.lz_c, D.B, D.L, capA, ly.ln2_g, ly.ln2_b, D.eps, D.d,
-                            static_cast<float *>(w.x1), w.xn, st);
+            // x1 = x + projection, and xn = LN2(x1) (bf16, or E4M3 codes for an FFN in FP8 arithmetic), in one pass
             const bool to_y = l == D.nl - 1 && !final_ln;
-            if (int32_t rc = ffn_forward(D, ly, w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y, w.xn,
-                                         w.hid, st, true))
-                return rc;
+            if (ffn8) {
+                uint8_t *xq = xq_out ? xq_out + (size_t)l * rows * D.d : static_cast<uint8_t *>(w.xn);
+                uint8_t *hq = hq_out ? hq_out + (size_t)l * rows * Fp8_max : static_cast<uint8_t *>(w.hid);
+                lazy_combine_ln(in, in_f32, w.lz_pos, w.lz_C, ly.bo, w.lz_c, D.B, D.L, capA, ly.ln2_g, ly.ln2_b, D.eps,
+                                D.d, static_cast<float *>(w.x1), xq, 1.0f / ffn8[l].sx, st);
+                if (int32_t rc = ffn_fp8_forward(D, ffn8[l], w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y,
+                                                 xq, hq, st, true))
+                    return rc;
+            } else {
+                lazy_combine_ln(in, in_f32, w.lz_pos, w.lz_C, ly.bo, w.lz_c, D.B, D.L, capA, ly.ln2_g, ly.ln2_b, D.eps,
+                                D.d, static_cast<float *>(w.x1), w.xn, 0.f, st);
+                if (int32_t rc = ffn_forward(D, ly, w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y, w.xn,
+                                             w.hid, st, true))
+                    return rc;
+            }
             in = w.x2;
             in_f32 = true;
             continue;

@@ -65,7 +65,7 @@ void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride,
                    hipStream_t st);
 void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const float *Cc, const void *bo, const float *cvec,
                      int B, int L, int capA, const void *gamma, const void *beta, float eps, int d, float *x1, void *xn,
-                     hipStream_t st);
+                     float q_inv, hipStream_t st);
 
 constexpr int STAT_CHUNK = 128;     // keys per partial-sum block of the K/V statistics
 

@@ -2,28 +2,12 @@
 // but not how they compute; here both operands of the two FFN contractions are OCP E4M3 codes with one fp32
 // scale per tensor).  This file holds the quantisers (plain, and fused into LayerNorm) and the block's entry
 // points; the contraction itself is gemm_fp8() in gemm_bf16_ws.hip.
+#include "fp8.hpp"
 #include "gemm.hpp"
 
 namespace sf {
 
 namespace {
-
-// Four fp32 values (already multiplied by the reciprocal scale) -> four E4M3 codes, round to nearest even,
-// saturating at +-448 (the conversion instruction alone would overflow to NaN), NaN -> 0x7F.
-__device__ __forceinline__ uint32_t e4m3_pack4(float t0, float t1, float t2, float t3)
-{
-    const float c0 = __builtin_amdgcn_fmed3f(t0, -448.f, 448.f), c1 = __builtin_amdgcn_fmed3f(t1, -448.f, 448.f);
-    const float c2 = __builtin_amdgcn_fmed3f(t2, -448.f, 448.f), c3 = __builtin_amdgcn_fmed3f(t3, -448.f, 448.f);
-    int w = 0;
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(c0, c1, w, false);
-    w = __builtin_amdgcn_cvt_pk_fp8_f32(c2, c3, w, true);
-    uint32_t u = (uint32_t)w;
-    if (t0 != t0) u = (u & 0xffffff00u) | 0x0000007fu;
-    if (t1 != t1) u = (u & 0xffff00ffu) | 0x00007f00u;
-    if (t2 != t2) u = (u & 0xff00ffffu) | 0x007f0000u;
-    if (t3 != t3) u = (u & 0x00ffffffu) | 0x7f000000u;
-    return u;
-}
 
 // codes[i] = E4M3(x[i] * inv_scale), 8 elements per thread (n8 groups of 8), tail element-wise
 template <class T>
@@ -216,12 +200,15 @@ int32_t ffn_fp8_check(const char *who, const Dims &D, const sf_ffn_fp8 *f, bool 
 
 // x_f32 / y_f32: X / Y hold fp32 (the encoder's residual stream); with x_f32 the LayerNorm is required.
 int32_t ffn_fp8_forward(const Dims &D, const sf_ffn_fp8 &f, const void *X, bool x_f32, const int32_t *pattern_id,
-                        bool pre_ln, bool add_residual, void *Y, bool y_f32, uint8_t *xq, uint8_t *hq, hipStream_t st)
+                        bool pre_ln, bool add_residual, void *Y, bool y_f32, uint8_t *xq, uint8_t *hq, hipStream_t st,
+                        bool xq_ready)
 {
     const int Fp8 = sf_ffn_fp8_padded(f.k_ffn);
     const int64_t rows = (int64_t)D.B * D.L;
     const float inv_sx = 1.0f / f.sx;
-    if (pre_ln) {
+    if (xq_ready) {
+        // the codes of LN2(X) were written together with X
+    } else if (pre_ln) {
         if (x_f32) launch_ln_q8<float>(X, f, D, rows, inv_sx, xq, st);
         else launch_ln_q8<__bf16>(X, f, D, rows, inv_sx, xq, st);
     } else {
@@ -270,7 +257,7 @@ extern "C" int32_t sf_pruned_ffn_fp8_forward(const sf_desc *desc, const sf_ffn_f
                     w.bytes, workspace_bytes);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (int32_t rc = ffn_fp8_forward(D, *f, X, false, pattern_id, pre_ln != 0, add_residual != 0, Y, false,
-                                     xq_out ? xq_out : w.xq, hq_out ? hq_out : w.hq, st))
+                                     xq_out ? xq_out : w.xq, hq_out ? hq_out : w.hq, st, false))
         return rc;
     return check_launch("pruned_ffn_fp8_forward");
 }

@@ -54,7 +54,8 @@ int32_t gemm_fp8(const GemmArgs &a, hipStream_t st);
 struct Dims;
 int32_t ffn_fp8_check(const char *who, const Dims &D, const sf_ffn_fp8 *f, bool pre_ln);
 int32_t ffn_fp8_forward(const Dims &D, const sf_ffn_fp8 &f, const void *X, bool x_f32, const int32_t *pattern_id,
-                        bool pre_ln, bool add_residual, void *Y, bool y_f32, uint8_t *xq, uint8_t *hq, hipStream_t st);
+                        bool pre_ln, bool add_residual, void *Y, bool y_f32, uint8_t *xq, uint8_t *hq, hipStream_t st,
+                        bool xq_ready = false);      // xq_ready: xq already holds the codes of LN2(X)
 
 // True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).
 bool gemm_takes_row_map(int dtype, const GemmArgs &a);

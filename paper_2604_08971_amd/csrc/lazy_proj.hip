@@ -6,6 +6,7 @@
 // one pass then forms the residual stream x1 = x + (projection of the row | c_b) and the LayerNorm that follows it.
 // The arithmetic is that of fill + projection + residual + LayerNorm; only the summation order of c_b differs.
 #include "attention.hpp"
+#include "fp8.hpp"
 
 namespace sf {
 
@@ -141,14 +142,15 @@ __global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__
 }
 
 // One wave per token row: x1 = x + (row active ? Cc[b, pos] + bo : c_b), written as fp32, then the LayerNorm of x1
-// (statistics in fp32, biased variance) written as bf16.  d % 8 == 0, d <= 512 * NCH.
-template <class TI, int NCH>
+// (statistics in fp32, biased variance) written as bf16, or (Q8) as E4M3 codes of LN(x1) * q_inv for an FFN in FP8
+// arithmetic.  d % 8 == 0, d <= 512 * NCH.
+template <class TI, int NCH, bool Q8>
 __global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ x, const int32_t *__restrict__ pos_of,
                                                          const float *__restrict__ Cc, const __bf16 *__restrict__ bo,
                                                          const float *__restrict__ cvec, int L, int capA,
                                                          const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ beta,
                                                          float eps, int64_t rows, int d, float *__restrict__ x1,
-                                                         __bf16 *__restrict__ xn)
+                                                         void *__restrict__ xn_out, float q_inv)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -220,16 +222,24 @@ __global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ 
         const int ch = lane + c * 64;
         if (ch >= nch) continue;
         bf16x8 gm, bt, o;
+        float z[8];
         if (gamma) gm = *reinterpret_cast<const bf16x8 *>(gamma + ch * 8);
         if (beta) bt = *reinterpret_cast<const bf16x8 *>(beta + ch * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float z = (v[c][e] - mean) * inv;
-            if (gamma) z *= (float)gm[e];
-            if (beta) z += (float)bt[e];
-            o[e] = (__bf16)z;
+            z[e] = (v[c][e] - mean) * inv;
+            if (gamma) z[e] *= (float)gm[e];
+            if (beta) z[e] += (float)bt[e];
+            o[e] = (__bf16)z[e];
         }
-        *reinterpret_cast<bf16x8 *>(xn + row * d + ch * 8) = o;
+        if constexpr (Q8) {
+            uint2 q;
+            q.x = e4m3_pack4(z[0] * q_inv, z[1] * q_inv, z[2] * q_inv, z[3] * q_inv);
+            q.y = e4m3_pack4(z[4] * q_inv, z[5] * q_inv, z[6] * q_inv, z[7] * q_inv);
+            *reinterpret_cast<uint2 *>(static_cast<uint8_t *>(xn_out) + row * d + ch * 8) = q;
+        } else {
+            *reinterpret_cast<bf16x8 *>(static_cast<__bf16 *>(xn_out) + row * d + ch * 8) = o;
+        }
     }
 }
 
@@ -275,21 +285,25 @@ void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride,
 
 void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const float *Cc, const void *bo, const float *cvec,
                      int B, int L, int capA, const void *gamma, const void *beta, float eps, int d, float *x1, void *xn,
-                     hipStream_t st)
+                     float q_inv, hipStream_t st)
 {
+    // q_inv > 0: xn receives E4M3 codes of LN(x1) * q_inv (one byte per element) instead of bf16
     const int64_t rows = (int64_t)B * L;
     dim3 grid((unsigned)((rows + 3) / 4));
 #define SF_CLN_ARGS(TI) grid, dim3(256), 0, st, (const TI *)x, pos_of, Cc, (const __bf16 *)bo, cvec, L, capA, \
-                        (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, x1, (__bf16 *)xn
-    if (x_f32) {
-        if (d <= 512) hipLaunchKernelGGL((combine_ln_kernel<float, 1>), SF_CLN_ARGS(float));
-        else if (d <= 1024) hipLaunchKernelGGL((combine_ln_kernel<float, 2>), SF_CLN_ARGS(float));
-        else hipLaunchKernelGGL((combine_ln_kernel<float, 4>), SF_CLN_ARGS(float));
+                        (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, x1, xn, q_inv
+#define SF_CLN_LAUNCH(TI, Q)                                                                            \
+    do {                                                                                                \
+        if (d <= 512) hipLaunchKernelGGL((combine_ln_kernel<TI, 1, Q>), SF_CLN_ARGS(TI));               \
+        else if (d <= 1024) hipLaunchKernelGGL((combine_ln_kernel<TI, 2, Q>), SF_CLN_ARGS(TI));         \
+        else hipLaunchKernelGGL((combine_ln_kernel<TI, 4, Q>), SF_CLN_ARGS(TI));                        \
+    } while (0)
+    if (q_inv > 0.f) {
+        if (x_f32) SF_CLN_LAUNCH(float, true); else SF_CLN_LAUNCH(__bf16, true);
     } else {
-        if (d <= 512) hipLaunchKernelGGL((combine_ln_kernel<__bf16, 1>), SF_CLN_ARGS(__bf16));
-        else if (d <= 1024) hipLaunchKernelGGL((combine_ln_kernel<__bf16, 2>), SF_CLN_ARGS(__bf16));
-        else hipLaunchKernelGGL((combine_ln_kernel<__bf16, 4>), SF_CLN_ARGS(__bf16));
+        if (x_f32) SF_CLN_LAUNCH(float, false); else SF_CLN_LAUNCH(__bf16, false);
     }
+#undef SF_CLN_LAUNCH
 #undef SF_CLN_ARGS
 }
 

@@ -328,6 +328,10 @@ def _encoder_fp8_case(kw):
          dropout="bernoulli:0.3"),
     dict(dtype="bf16", d=384, dh=32, Hq=12, Hk=4, F=640, seg=(128, 128), extra=0, B=2, nl=1, ffn_keep=0.8, act=1,
          dropout="none", final_ln=False),
+    # long enough for the output projection to run on the active rows only: LN2 and the quantiser are then fused
+    # with the pass that forms the residual stream
+    dict(dtype="bf16", d=256, dh=64, Hq=4, Hk=2, F=512, seg=(260, 140, 120), extra=2, B=2, nl=2, ffn_keep=0.6,
+         dropout="bernoulli:0.3"),
 ])
 def test_encoder_with_fp8_ffn_parity(kw):
     _say(f"encoder fp8 ffn {kw}")
