@@ -138,6 +138,8 @@ def _ragged_case(wl, samples=None):
     dict(dtype="f32", dropout="upto:2", B=4, nl=2, act=1, c=2),
     dict(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90, 40), B=6, dropout="upto:2"),
     dict(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=300, seg=(100, 33, 64, 120), B=5, nl=2, dropout="upto:3", act=1),
+    # long enough for the output projection to run on the active rows only, with per-sample active counts
+    dict(dtype="bf16", d=64, dh=32, Hq=4, Hk=2, F=192, seg=(260, 140, 120, 60), B=6, nl=2, dropout="upto:2", c=1),
 ])
 def test_encoder_ragged_parity_small(kw):
     _say(f"ragged encoder {kw}")
