@@ -226,7 +226,8 @@ int32_t orc_budget_search(int32_t nl, int32_t Hq, int32_t Hk, int32_t F, const f
 
 /*
  * FP8 post-training quantisation of the weights (Sec. 6, "Compatibility with quantization": FP8 PTQ on top of the
- * pruned model; the paper names neither the format nor the scaling).  Reading: weights are stored as OCP E4M3
+ * pruned model; the paper names neither the format nor the scaling: "parity unpinned" for that choice, the format's
+ * decode and the rounding are pinned against a library implementation).  Reading: weights are stored as OCP E4M3
  * bytes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities, S.1111.111 is NaN, largest finite
  * value 448, subnormals m * 2^-9) with one fp32 scale per weight matrix; the pruned forward runs on the
  * dequantised weight w = decode(byte) * scale, rounded to the model dtype (bf16, ties to even, when bf16 != 0;
@@ -238,7 +239,9 @@ double orc_fp8_e4m3_decode(uint8_t byte);
 void orc_dequant_fp8(const uint8_t *q, int64_t n, float scale, int32_t bf16, double *out);
 
 /*
- * FP16 post-training quantisation of the weights (same experiment, the FP16 points).  Reading: weights are stored
+ * FP16 post-training quantisation of the weights (same experiment, the FP16 points; the paper does not say what is
+ * stored or how it is used: "parity unpinned" for that reading, the decode itself is pinned against a library
+ * binary16).  Reading: weights are stored
  * as IEEE binary16 (1-5-10, subnormals, infinities, NaN), no scale; the forward runs on the stored value in the
  * model dtype: every binary16 value is an fp32 value, so an fp32 model computes on exactly the stored weights, and a
  * bf16 model on their one rounding to bf16 (ties to even).
@@ -249,7 +252,8 @@ void orc_dequant_f16(const uint16_t *q, int64_t n, int32_t bf16, double *out);
 
 /*
  * FP8 arithmetic for the pruned FFN (the second half of the same experiment: the paper reports FP8 models but
- * not how they compute).  Reading: both operands of the two FFN contractions are E4M3 codes with one fp32
+ * not how they compute; the scheme below is this build's reading, "parity unpinned" as far as the paper goes, pinned
+ * against library casts, LayerNorm and matmul in the tests).  Reading: both operands of the two FFN contractions are E4M3 codes with one fp32
  * scale per tensor (W8A8, static scales chosen offline), products are exact and sums wide:
  *     xq  = Q(LN2(x), sx)                                    (LN2 in fp64, its result rounded to fp32)
  *     z   = (sum_k dec(xq_k) dec(W1q_fk)) * fl32(sx*s1) + b1_f      rounded to fp32
