@@ -14,6 +14,8 @@
 // stores are 8-byte vectors.  With SWAP = true the roles flip and a lane holds
 // one feature and 4 consecutive tokens: that is the store pattern of the
 // transposed V layout the attention kernels read.
+#include <atomic>
+
 #include "gemm.hpp"
 
 namespace sf {
@@ -224,7 +226,7 @@ static int32_t launch_cfg(const GemmArgs &a, hipStream_t st)
 {
     auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, SWAP>;
     constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(__bf16);
-    static bool attr_set = false;          // per template instance; benign if set twice
+    static std::atomic<bool> attr_set{false};     // per template instance; setting the attribute twice is harmless
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)

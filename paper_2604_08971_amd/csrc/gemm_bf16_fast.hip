@@ -18,6 +18,8 @@
 //    lane owns 8 consecutive features of a token: 16-byte stores.
 #include <type_traits>
 
+#include <atomic>
+
 #include "gemm.hpp"
 
 namespace sf {
@@ -322,7 +324,7 @@ static int32_t launch_fast(const GemmArgs &a, hipStream_t st)
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
     auto kern = gemm_bf16_fast_kernel<WAVES_M, WAVES_N, TM, TN, BKT, NSTAGE, SWAP, ACT>;
     constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * BKT * sizeof(__bf16);
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};     // per template instance; setting the attribute twice is harmless
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)

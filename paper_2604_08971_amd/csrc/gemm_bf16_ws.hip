@@ -39,6 +39,8 @@
 #include <algorithm>
 #include <type_traits>
 
+#include <atomic>
+
 #include "gemm.hpp"
 
 namespace sf {
@@ -604,7 +606,7 @@ static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
 {
     auto kern = F8 ? gemm_fp8_ws_kernel<ACT> : gemm_bf16_ws_kernel<ACT>;
     constexpr size_t lds = ((size_t)NXS * XSLOT + (size_t)NWS * WSLOT) * sizeof(__bf16);     // 160 KB
-    static bool attr_set = false;     // one flag per instantiation (ACT, F8)
+    static std::atomic<bool> attr_set{false};     // per template instance; setting the attribute twice is harmless
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -616,7 +618,7 @@ static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
     const int total = a.B * tiles_m * tiles_n;
     const int per_xcd = a.xcd_rows ? ceil_div(a.B * tiles_m, N_XCD) * tiles_n : ceil_div(total, N_XCD);
     // persistent: one workgroup per compute unit (160 KB of LDS each), the same number on every XCD
-    static int cus = 0;
+    static std::atomic<int> cus{0};
     if (!cus) {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
