@@ -59,7 +59,7 @@ def lib():
         _lib.orc_pruned_ffn_fp8.restype = None
         _lib.orc_quantize_fp8.restype = None
         _lib.orc_fp8_e4m3_decode.argtypes = [C.c_uint8]
-        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_encoder_forward_fp8ffn", "orc_moe_ffn",
+        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_encoder_forward_fp8ffn", "orc_encoder_forward_fp8", "orc_moe_ffn",
                   "orc_gate_eval", "orc_budget_search"):
             getattr(_lib, f).restype = C.c_int32
     return _lib
@@ -68,6 +68,17 @@ def lib():
 class _Ffn8(C.Structure):
     _fields_ = [("W1q", C.c_void_p), ("W2q", C.c_void_p), ("s1", C.c_float), ("s2", C.c_float), ("sx", C.c_float),
                 ("sh", C.c_float)]
+
+
+class _Proj8(C.Structure):
+    _fields_ = [("Wq8", C.c_void_p), ("Wk8", C.c_void_p), ("Wv8", C.c_void_p), ("Wo8", C.c_void_p),
+                ("s_qkv", C.c_float), ("so", C.c_float), ("sx1", C.c_float), ("sa", C.c_float)]
+
+
+class _Fp8Io(C.Structure):
+    _fields_ = ([(n, C.c_void_p) for n in ("xq_forced", "hq_forced", "aq_forced", "oq_forced")]
+                + [(n, C.c_int32) for n in ("n_forced_x", "n_forced_h", "n_forced_a", "n_forced_o")]
+                + [(n, C.c_void_p) for n in ("xq_out", "hq_out", "aq_out", "oq_out")])
 
 
 def _p(a):
@@ -350,13 +361,17 @@ def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=
                     key_valid=None, act: int = 0, eps: float = 1e-5, forced_sel=None,
                     final_ln: Optional[Dict[str, np.ndarray]] = None, bf16: bool = False,
                     want_sel: bool = True, want_score: bool = False, sample_idx=None, ffn8=None, xq_forced=None,
-                    hq_forced=None, want_codes: bool = False, n_forced_x=None, n_forced_h=None):
+                    hq_forced=None, want_codes: bool = False, n_forced_x=None, n_forced_h=None, proj8=None,
+                    aq_forced=None, oq_forced=None, n_forced_a=None, n_forced_o=None):
     """packs[l][p] = LayerPack of layer l, pattern p.
     ffn8: per layer a dict W1q, W2q [F,d] uint8, s1, s2, sx, sh - the layer's FFN runs in FP8 arithmetic;
     xq_forced [nl,B,L,d], hq_forced [nl,B,L,F] uint8: codes to use instead of the oracle's own, in the layers
     l < n_forced_x / l < n_forced_h (default: every layer).
+    proj8: per layer a dict Wq8 [nH*dh,d], Wk8, Wv8 [nG*dh,d], Wo8 [nH*dh,d] uint8, s_qkv, so, sx1, sa - the
+    layer's Q/K/V and output projections run in FP8 arithmetic; aq_forced [nl,B,L,d] (codes of LN1(x)) and
+    oq_forced [nl,B,L,nH*dh] (codes of the attention output) work like xq_forced.
     Returns (y [B,L,d], sel [nl,B,nHmax,U] or None, score [nl,B,nHmax,L] or None) and, with want_codes,
-    xq [nl,B,L,d], hq [nl,B,L,F]."""
+    xq [nl,B,L,d], hq [nl,B,L,F] (None without ffn8) and, with proj8, aq [nl,B,L,d], oq [nl,B,L,nH*dh]."""
     x = _f64(x)
     B, L, d = x.shape
     nl, P = len(packs), len(packs[0])
@@ -378,12 +393,13 @@ def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=
     sel = np.full((nl, B, nHmax, max(U, 1)), -1, np.int32) if want_sel else None
     score = np.full((nl, B, nHmax, L), -np.inf, np.float64) if want_score else None
     si, ns = _sample(sample_idx, B)
-    f8 = keep8 = xf = hf = xq = hq = None
+    f8 = p8 = xf = hf = af = of = xq = hq = aq = oq = None
+    keep8 = []
+    F = packs[0][0].struct.F
+    nH, dh, nG = packs[0][0].struct.nH, packs[0][0].struct.dh, packs[0][0].struct.nG
     if ffn8 is not None:
         assert len(ffn8) == nl
-        F = packs[0][0].struct.F
         f8 = (_Ffn8 * nl)()
-        keep8 = []
         for l, f in enumerate(ffn8):
             a, b = np.ascontiguousarray(f["W1q"], dtype=np.uint8), np.ascontiguousarray(f["W2q"], dtype=np.uint8)
             assert a.shape == (F, d) and b.shape == (F, d)
@@ -395,13 +411,36 @@ def encoder_forward(x, packs: Sequence[Sequence[LayerPack]], U: int, pattern_id=
             hf = np.ascontiguousarray(hq_forced, dtype=np.uint8).reshape(nl, B, L, F)
         if want_codes:
             xq, hq = np.empty((nl, B, L, d), np.uint8), np.empty((nl, B, L, F), np.uint8)
-    rc = lib().orc_encoder_forward_fp8ffn(
-        C.c_int32(B), C.c_int32(L), C.c_int32(nl), C.c_int32(P), arr, f8, _p(pid), _p(kv),
+    if proj8 is not None:
+        assert len(proj8) == nl and nH == nHmax
+        p8 = (_Proj8 * nl)()
+        for l, f in enumerate(proj8):
+            ws = [np.ascontiguousarray(f[k], dtype=np.uint8) for k in ("Wq8", "Wk8", "Wv8", "Wo8")]
+            assert ws[0].shape == (nH * dh, d) and ws[1].shape == (nG * dh, d) and ws[2].shape == (nG * dh, d)
+            assert ws[3].shape == (nH * dh, d)
+            keep8 += ws
+            p8[l] = _Proj8(_p(ws[0]), _p(ws[1]), _p(ws[2]), _p(ws[3]), float(f["s_qkv"]), float(f["so"]),
+                           float(f["sx1"]), float(f["sa"]))
+        if aq_forced is not None:
+            af = np.ascontiguousarray(aq_forced, dtype=np.uint8).reshape(nl, B, L, d)
+        if oq_forced is not None:
+            of = np.ascontiguousarray(oq_forced, dtype=np.uint8).reshape(nl, B, L, nH * dh)
+        if want_codes:
+            aq, oq = np.empty((nl, B, L, d), np.uint8), np.empty((nl, B, L, nH * dh), np.uint8)
+
+    def cnt(v):
+        return nl if v is None else int(v)
+
+    io = _Fp8Io(_p(xf), _p(hf), _p(af), _p(of), cnt(n_forced_x), cnt(n_forced_h), cnt(n_forced_a), cnt(n_forced_o),
+                _p(xq), _p(hq), _p(aq), _p(oq))
+    rc = lib().orc_encoder_forward_fp8(
+        C.c_int32(B), C.c_int32(L), C.c_int32(nl), C.c_int32(P), arr, f8, p8, _p(pid), _p(kv),
         _p(si), C.c_int32(ns), C.c_int32(U), C.c_int32(act), C.c_double(eps), _p(fs), C.c_int32(nHmax), _p(fg), _p(fb),
-        C.c_int32(int(bf16)), _p(xf), _p(hf), C.c_int32(nl if n_forced_x is None else int(n_forced_x)),
-        C.c_int32(nl if n_forced_h is None else int(n_forced_h)), _p(x), _p(y), _p(sel), _p(score), _p(xq), _p(hq))
+        C.c_int32(int(bf16)), C.byref(io), _p(x), _p(y), _p(sel), _p(score))
     if rc != 0:
         raise ValueError("orc_encoder_forward: bad arguments")
     if sel is not None:
         sel = sel[..., :U]
-    return (y, sel, score, xq, hq) if want_codes else (y, sel, score)
+    if not want_codes:
+        return y, sel, score
+    return (y, sel, score, xq, hq, aq, oq) if proj8 is not None else (y, sel, score, xq, hq)

@@ -716,6 +716,45 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
                                    const double *x, double *y, int32_t *sel_out, double *score_out,
                                    uint8_t *xq_out, uint8_t *hq_out)
 {
+    orc_fp8_io io;
+    memset(&io, 0, sizeof io);
+    io.xq_forced = xq_forced; io.hq_forced = hq_forced; io.n_forced_x = n_forced_x; io.n_forced_h = n_forced_h;
+    io.xq_out = xq_out; io.hq_out = hq_out;
+    return orc_encoder_forward_fp8(B, L, nl, P, layers, ffn8, NULL, pattern_id, key_valid, sample_idx, n_sample, U,
+                                   act, eps, forced_sel, nHmax, final_g, final_b, bf16, &io, x, y, sel_out, score_out);
+}
+
+/* acc[r, n] = (sum_k code(a[r,k]) * code(W[unit0+n, k])) * os + b[unit0+n]: the products of two E4M3 values and their
+ * sum are exact in double */
+static void project_units8(const uint8_t *aq, int64_t rows, int32_t d, const uint8_t *Wq8, double os,
+                           const double *b, int32_t unit0, int32_t n_units, int32_t bf16, double *y,
+                           int64_t out_stride, int32_t out0)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int32_t n = 0; n < n_units; ++n) {
+            const uint8_t *wn = Wq8 + (int64_t)(unit0 + n) * d;
+            double acc = 0.0;
+            for (int32_t k = 0; k < d; ++k) acc += orc_fp8_e4m3_decode(aq[r * d + k]) * orc_fp8_e4m3_decode(wn[k]);
+            acc = acc * os + (b ? b[unit0 + n] : 0.0);
+            y[r * out_stride + out0 + n] = rnd(acc, bf16);
+        }
+}
+
+int32_t orc_encoder_forward_fp8(int32_t B, int32_t L, int32_t nl, int32_t P,
+                                const orc_layer *layers, const orc_ffn8 *ffn8, const orc_proj8 *proj8,
+                                const int32_t *pattern_id, const uint8_t *key_valid, const int32_t *sample_idx,
+                                int32_t n_sample, int32_t U, int32_t act, double eps,
+                                const int32_t *forced_sel, int32_t nHmax,
+                                const double *final_g, const double *final_b, int32_t bf16,
+                                const orc_fp8_io *io, const double *x, double *y, int32_t *sel_out, double *score_out)
+{
+    orc_fp8_io none;
+    memset(&none, 0, sizeof none);
+    if (!io) io = &none;
+    const uint8_t *xq_forced = io->xq_forced, *hq_forced = io->hq_forced;
+    const int32_t n_forced_x = io->n_forced_x, n_forced_h = io->n_forced_h;
+    uint8_t *xq_out = io->xq_out, *hq_out = io->hq_out;
     if (B < 0 || L < 1 || nl < 1 || P < 1 || U < 0) return -1;
     const int32_t d = layers[0].d;
     const int64_t Ld = (int64_t)L * d;
@@ -744,11 +783,28 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
             double *Vg = (double *)calloc((size_t)nG * L * dh, sizeof(double));
             double *O = (double *)calloc((size_t)L * nH * dh, sizeof(double));
 
+            const orc_proj8 *pj = proj8 ? &proj8[l] : NULL;
+            const int64_t blk = (int64_t)l * B + b;
+            uint8_t *aq = NULL;
+            if (pj) {
+                /* FP8 arithmetic for the projections: LN1(x) in fp32 -> E4M3 codes with the layer's scale */
+                orc_layernorm(cur, L, d, w->ln1_g, w->ln1_b, eps, 0, xn);
+                float *t32 = (float *)malloc(sizeof(float) * (size_t)Ld);
+                aq = (uint8_t *)malloc((size_t)Ld);
+                for (int64_t t = 0; t < Ld; ++t) t32[t] = (float)xn[t];
+                orc_quantize_fp8(t32, Ld, pj->sx1, aq);
+                if (io->aq_forced && l < io->n_forced_a) memcpy(aq, io->aq_forced + blk * Ld, (size_t)Ld);
+                if (io->aq_out) memcpy(io->aq_out + blk * Ld, aq, (size_t)Ld);
+                free(t32);
+            } else
             orc_layernorm(cur, L, d, w->ln1_g, w->ln1_b, eps, bf16, xn);
+            const volatile float os_qkv = pj ? pj->sx1 * pj->s_qkv : 0.f;      /* fp32 product */
 
             /* per-head Q, per-group K/V (only for units that survive) */
             for (int32_t h = 0; h < nH; ++h) {
                 if (w->head_mask && !w->head_mask[h]) continue;
+                if (pj) project_units8(aq, L, d, pj->Wq8, (double)os_qkv, w->bq, h * dh, dh, bf16, Q + (int64_t)h * L * dh, dh, 0);
+                else
                 project_units(xn, L, d, w->Wq, w->bq, h * dh, dh, bf16, Q + (int64_t)h * L * dh, dh, 0);
             }
             for (int32_t g = 0; g < nG; ++g) {
@@ -756,9 +812,15 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
                 for (int32_t h = 0; h < nH; ++h)
                     if ((!w->head_mask || w->head_mask[h]) && w->head_group[h] == g) used = 1;
                 if (!used) continue;
+                if (pj) {
+                    project_units8(aq, L, d, pj->Wk8, (double)os_qkv, w->bk, g * dh, dh, bf16, Kg + (int64_t)g * L * dh, dh, 0);
+                    project_units8(aq, L, d, pj->Wv8, (double)os_qkv, w->bv, g * dh, dh, bf16, Vg + (int64_t)g * L * dh, dh, 0);
+                    continue;
+                }
                 project_units(xn, L, d, w->Wk, w->bk, g * dh, dh, bf16, Kg + (int64_t)g * L * dh, dh, 0);
                 project_units(xn, L, d, w->Wv, w->bv, g * dh, dh, bf16, Vg + (int64_t)g * L * dh, dh, 0);
             }
+            free(aq);
 
             /* SentryAttend per surviving head; a removed head's output is 0 */
             for (int32_t h = 0; h < nH; ++h) {
@@ -773,19 +835,46 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
                               sel_out ? sel_out + slot * U : NULL, NULL);
             }
 
-            /* x <- x + O Wo + bo  (rows of Wo belonging to removed heads never enter) */
+            if (pj) {
+                /* x <- x + (codes(O) . codes(Wo)) * (sa * so) + bo: the attention output is quantised with the
+                 * layer's scale; a removed head's output is 0, code 0 */
+                const int64_t no = (int64_t)L * nH * dh;
+                float *t32 = (float *)malloc(sizeof(float) * (size_t)no);
+                uint8_t *oq = (uint8_t *)malloc((size_t)no);
+                for (int64_t t = 0; t < no; ++t) t32[t] = (float)O[t];
+                orc_quantize_fp8(t32, no, pj->sa, oq);
+                if (io->oq_forced && l < io->n_forced_o) memcpy(oq, io->oq_forced + blk * no, (size_t)no);
+                for (int32_t i = 0; i < L; ++i)
+                    for (int32_t h = 0; h < nH; ++h)
+                        if (w->head_mask && !w->head_mask[h]) memset(oq + ((int64_t)i * nH + h) * dh, 0, (size_t)dh);
+                if (io->oq_out) memcpy(io->oq_out + blk * no, oq, (size_t)no);
+                const volatile float os_o = pj->sa * pj->so;
 #pragma omp parallel for schedule(static)
-            for (int32_t i = 0; i < L; ++i) {
-                for (int32_t n = 0; n < d; ++n) {
-                    double acc = 0.0;
-                    for (int32_t h = 0; h < nH; ++h) {
-                        if (w->head_mask && !w->head_mask[h]) continue;
-                        for (int32_t e = 0; e < dh; ++e)
-                            acc += O[(int64_t)i * nH * dh + h * dh + e] *
-                                   w->Wo[((int64_t)h * dh + e) * d + n];
+                for (int32_t i = 0; i < L; ++i)
+                    for (int32_t n = 0; n < d; ++n) {
+                        double acc = 0.0;
+                        for (int32_t c = 0; c < nH * dh; ++c)
+                            acc += orc_fp8_e4m3_decode(oq[(int64_t)i * nH * dh + c]) *
+                                   orc_fp8_e4m3_decode(pj->Wo8[(int64_t)c * d + n]);
+                        acc = acc * (double)os_o + (w->bo ? w->bo[n] : 0.0);
+                        xn[(int64_t)i * d + n] = cur[(int64_t)i * d + n] + acc;
                     }
-                    if (w->bo) acc += w->bo[n];
-                    xn[(int64_t)i * d + n] = cur[(int64_t)i * d + n] + acc;   /* stream stays unrounded */
+                free(oq); free(t32);
+            } else {
+                /* x <- x + O Wo + bo  (rows of Wo belonging to removed heads never enter) */
+#pragma omp parallel for schedule(static)
+                for (int32_t i = 0; i < L; ++i) {
+                    for (int32_t n = 0; n < d; ++n) {
+                        double acc = 0.0;
+                        for (int32_t h = 0; h < nH; ++h) {
+                            if (w->head_mask && !w->head_mask[h]) continue;
+                            for (int32_t e = 0; e < dh; ++e)
+                                acc += O[(int64_t)i * nH * dh + h * dh + e] *
+                                       w->Wo[((int64_t)h * dh + e) * d + n];
+                        }
+                        if (w->bo) acc += w->bo[n];
+                        xn[(int64_t)i * d + n] = cur[(int64_t)i * d + n] + acc;   /* stream stays unrounded */
+                    }
                 }
             }
             memcpy(cur, xn, sizeof(double) * (size_t)Ld);
@@ -794,7 +883,6 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
             if (ffn8) {
                 /* the FFN of this layer in FP8 arithmetic; the stream stays unrounded */
                 const orc_ffn8 *f = &ffn8[l];
-                const int64_t blk = (int64_t)l * B + b;
                 orc_pruned_ffn_fp8(d, w->F, f->W1q, f->s1, w->b1, f->W2q, f->s2, w->b2, w->ln2_g, w->ln2_b,
                                    w->ffn_mask, f->sx, f->sh, cur, L, act, eps, 1, 1, 0,
                                    xq_forced && l < n_forced_x ? xq_forced + blk * L * d : NULL,

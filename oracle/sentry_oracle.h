@@ -304,6 +304,38 @@ int32_t orc_encoder_forward_fp8ffn(int32_t B, int32_t L, int32_t nl, int32_t P,
                                    const double *x, double *y, int32_t *sel_out, double *score_out,
                                    uint8_t *xq_out, uint8_t *hq_out);
 
+/* FP8 arithmetic for the attention projections of one layer (used by every pattern).  The paper reports FP8 models
+ * without saying which contractions run in FP8 or how: this reading is "parity unpinned" as far as the paper goes and
+ * pinned in the tests against a numpy matrix form built on the library's float8 casts.  Reading, with Q(t, s) and
+ * dec() as in the FFN block above:
+ *     aq      = Q(LN1(x), sx1)                                     (LN1 in fp64, its result rounded to fp32)
+ *     q, k, v = (sum_c dec(aq_c) dec(W8_uc)) * fl32(sx1*s_qkv) + b_u     stored as bf16 when bf16 != 0
+ *     oq      = Q(attention output, sa)                            (0 for a removed head)
+ *     x      <- x + (sum_c dec(oq_c) dec(Wo8_cn)) * fl32(sa*so) + bo_n
+ * SentryAttend between the two runs on q, k, v as in the plain encoder.  E4M3 codes of the dense Wq [nH*dh, d],
+ * Wk, Wv [nG*dh, d] carry ONE scale s_qkv (the three are one fused operand of one GEMM), those of Wo [nH*dh, d]
+ * carry so. */
+typedef struct {
+    const uint8_t *Wq8, *Wk8, *Wv8, *Wo8;
+    float s_qkv, so, sx1, sa;
+} orc_proj8;
+/* codes forced in / reported: xq = LN2 output [nl,B,L,d], hq = hidden [nl,B,L,F], aq = LN1 output [nl,B,L,d],
+ * oq = attention output [nl,B,L,nH*dh]; forced in layers l < n_forced_* only */
+typedef struct {
+    const uint8_t *xq_forced, *hq_forced, *aq_forced, *oq_forced;
+    int32_t n_forced_x, n_forced_h, n_forced_a, n_forced_o;
+    uint8_t *xq_out, *hq_out, *aq_out, *oq_out;
+} orc_fp8_io;
+/* The encoder with the FFN (ffn8 != NULL) and / or the attention projections (proj8 != NULL) in FP8 arithmetic;
+ * SentryAttend itself and the residual stream are unchanged.  io may be NULL. */
+int32_t orc_encoder_forward_fp8(int32_t B, int32_t L, int32_t nl, int32_t P,
+                                const orc_layer *layers, const orc_ffn8 *ffn8, const orc_proj8 *proj8,
+                                const int32_t *pattern_id, const uint8_t *key_valid, const int32_t *sample_idx,
+                                int32_t n_sample, int32_t U, int32_t act, double eps,
+                                const int32_t *forced_sel, int32_t nHmax,
+                                const double *final_g, const double *final_b, int32_t bf16,
+                                const orc_fp8_io *io, const double *x, double *y, int32_t *sel_out, double *score_out);
+
 int32_t orc_max_threads(void);
 
 #ifdef __cplusplus

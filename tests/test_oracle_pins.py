@@ -1023,6 +1023,114 @@ def test_encoder_with_fp8_ffn_is_the_composition_of_its_blocks():
         assert np.array_equal(hq2[0, b][:, keep], hf[0, b][:, keep]) and not hq2[0, b][:, ~keep].any()
 
 
+def _to_codes(a, scale):
+    """fp32 values -> E4M3 codes with the library type: t = fp32(a) * fp32(1/scale), clamped to the finite range."""
+    t = a.astype(np.float32) * (np.float32(1.0) / np.float32(scale))
+    return torch.from_numpy(t.astype(np.float32)).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def _proj8_of(lw, sx1=8.0 / 448, sa=4.0 / 448):
+    s_qkv = np.float32(max(np.abs(lw[k]).max() for k in ("Wq", "Wk", "Wv")) / 448)
+    so = np.float32(np.abs(lw["Wo"]).max() / 448)
+    return dict(Wq8=_to_codes(lw["Wq"], s_qkv), Wk8=_to_codes(lw["Wk"], s_qkv), Wv8=_to_codes(lw["Wv"], s_qkv),
+                Wo8=_to_codes(lw["Wo"], so), s_qkv=s_qkv, so=so, sx1=np.float32(sx1), sa=np.float32(sa))
+
+
+@pytest.mark.parametrize("dropout", ["none", "bernoulli:0.3"])
+def test_encoder_with_fp8_projections_against_matrix_form(dropout):
+    """One layer with the Q/K/V and output projections in FP8 arithmetic against a numpy matrix form written from
+    the reading: codes of LN1(x) and of the attention output from the library's fp32 -> float8_e4m3fn conversion,
+    products of decoded codes, one fp32 scale product per GEMM, attention and FFN as in the plain encoder."""
+    spec = W.small_spec(dtype="f32", B=3, nl=1, dropout=dropout, final_ln=False, Hq=4, Hk=2, head_keep=0.75)
+    wl = W.make_workload(spec)
+    masks = oracle_masks(wl)
+    packs = dense_packs(wl, masks)
+    U = orc.num_active(spec.L, spec.c)
+    lw = wl.layers[0]
+    pj = _proj8_of(lw)
+    y, sel, _, _, _, aq, oq = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, proj8=[pj],
+                                                  want_codes=True)
+    s, per = spec, spec.Hq // spec.Hk
+    w = {k: v.astype(np.float64) for k, v in lw.items()}
+    os_qkv, os_o = float(np.float32(pj["sx1"] * pj["s_qkv"])), float(np.float32(pj["sa"] * pj["so"]))
+
+    def ln(z, g, b):
+        mu = z.mean(-1, keepdims=True)
+        return (z - mu) / np.sqrt(((z - mu) ** 2).mean(-1, keepdims=True) + 1e-5) * g + b
+
+    for b in range(3):
+        p = int(wl.pattern_id[b])
+        x = wl.x[b].astype(np.float64)
+        valid = np.ones(s.L, bool) if wl.key_valid is None else wl.key_valid[b].astype(bool)
+        heads = np.flatnonzero(masks["head_mask"][0, p])
+        chans = np.flatnonzero(masks["ffn_mask"][0, p])
+        a8 = _to_codes(ln(x, w["ln1_g"], w["ln1_b"]), pj["sx1"])
+        assert np.array_equal(aq[0, b], a8)
+        a = _dec(a8)
+        att = np.zeros((s.L, s.Hq * s.dh))
+        for h in heads:
+            g = h // per
+            hs, gs = slice(h * s.dh, (h + 1) * s.dh), slice(g * s.dh, (g + 1) * s.dh)
+            q = (a @ _dec(pj["Wq8"][hs]).T) * os_qkv + w["bq"][hs]
+            k = (a @ _dec(pj["Wk8"][gs]).T) * os_qkv + w["bk"][gs]
+            v = (a @ _dec(pj["Wv8"][gs]).T) * os_qkv + w["bv"][gs]
+            sc_a = (q @ k.T / math.sqrt(s.dh))[:, valid]
+            M = np.where(valid, sc_a.max(1) - sc_a.mean(1), -np.inf)
+            order = [i for i in np.lexsort((np.arange(s.L), -M.astype(np.float32))) if valid[i]][:U]
+            assert sorted(order) == sorted(int(i) for i in sel[0, b, h] if i >= 0)
+            pr = np.exp(sc_a - sc_a.max(1, keepdims=True))
+            pr /= pr.sum(1, keepdims=True)
+            o = np.tile(v[valid].mean(0), (s.L, 1))
+            o[order] = (pr @ v[valid])[order]
+            att[:, hs] = o
+        o8 = _to_codes(att, pj["sa"])
+        # a code may differ where the attention output sits on a rounding boundary of the grid (the two sides sum the
+        # softmax in different orders): the comparison of y below uses the oracle's codes
+        assert (oq[0, b] != o8).mean() < 2e-3
+        x = x + (_dec(oq[0, b]) @ _dec(pj["Wo8"])) * os_o + w["bo"]
+        hid = np.maximum(ln(x, w["ln2_g"], w["ln2_b"]) @ w["W1"][chans].T + w["b1"][chans], 0)
+        x = x + hid @ w["W2"][chans] + w["b2"]
+        assert np.abs(y[b] - x).max() < 1e-10
+        # removed heads: code 0 in every row
+        dead = np.setdiff1d(np.arange(s.Hq), heads)
+        for h in dead:
+            assert not oq[0, b][:, h * s.dh:(h + 1) * s.dh].any()
+    # close to the unquantised encoder (E4M3 keeps 4 significant bits), and not equal to it
+    y0, _, _ = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid)
+    rel = np.abs(y - y0).max() / np.abs(y0).max()
+    assert 1e-4 < rel < 0.2, rel
+
+
+def test_encoder_fp8_projections_forced_codes_and_bf16_mode():
+    """Forced codes replace the oracle's own in the layers asked for; in the bf16 model Q, K, V are bf16 numbers,
+    so the layer output with forced codes is a function of the codes alone; with the FFN in FP8 too the FFN codes
+    are those of orc_pruned_ffn_fp8 on the stream after the attention block."""
+    spec = W.small_spec(dtype="bf16", B=2, nl=2, dropout="none", final_ln=False, Hq=4, Hk=2)
+    wl = W.make_workload(spec)
+    masks = oracle_masks(wl)
+    packs = dense_packs(wl, masks)
+    U = orc.num_active(spec.L, spec.c)
+    pjs = [_proj8_of(lw) for lw in wl.layers]
+    kw = dict(pattern_id=wl.pattern_id, key_valid=wl.key_valid, bf16=True, proj8=pjs, want_codes=True)
+    y, sel, _, _, _, aq, oq = orc.encoder_forward(wl.x, packs, U, **kw)
+    # own codes forced back in: the same result
+    y2, sel2, _, _, _, aq2, oq2 = orc.encoder_forward(wl.x, packs, U, aq_forced=aq, oq_forced=oq, **kw)
+    assert np.array_equal(y, y2) and np.array_equal(sel, sel2) and np.array_equal(aq, aq2) and np.array_equal(oq, oq2)
+    # other codes in layer 0 only: layer 0 reports them, layer 1 quantises its own input
+    rng = np.random.default_rng(3)
+    af = aq.copy()
+    af[0] = rng.integers(0x20, 0x48, aq[0].shape).astype(np.uint8)
+    y3, _, _, _, _, aq3, _ = orc.encoder_forward(wl.x, packs, U, aq_forced=af, n_forced_a=1, **kw)
+    assert np.array_equal(aq3[0], af[0]) and not np.array_equal(aq3[1], af[1]) and not np.array_equal(y3, y)
+    # a perturbed input with the same forced LN1 codes in every layer... changes the residual only
+    y4, _, _, _, _, _, oq4 = orc.encoder_forward(wl.x, packs, U, aq_forced=aq, oq_forced=oq, n_forced_o=1, **kw)
+    assert np.array_equal(y4, y) and np.array_equal(oq4, oq)
+    # scales enter as one fp32 product per GEMM: doubling sx1 and halving s_qkv is the same computation on the same codes
+    pj2 = [dict(p, sx1=np.float32(2 * p["sx1"]), s_qkv=np.float32(p["s_qkv"] / 2)) for p in pjs]
+    y5, _, _, _, _, _, _ = orc.encoder_forward(wl.x, packs, U, aq_forced=aq, **dict(kw, proj8=pj2))
+    assert np.array_equal(y5, y)
+
+
 # ------------------------------------------------ FP16 (IEEE binary16) weight storage
 def test_f16_decode_and_dequant_against_library_type():
     """All 65536 bit patterns against numpy's float16 (a library implementation of IEEE binary16); the bf16 rounding
