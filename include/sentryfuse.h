@@ -270,6 +270,56 @@ int32_t sf_encoder_forward_fp8ffn(const sf_desc *desc, const sf_compact_layer *l
                                   uint8_t *hq_out, void *workspace, size_t workspace_bytes,
                                   void *stream);
 
+/*
+ * The attention projections in FP8 arithmetic (the other contractions of the
+ * FP8 models of the quantisation experiment; this build's reading, the paper
+ * does not say which contractions run in FP8).  Per layer:
+ *     aq      = E4M3(LN1(x) / sx1)                        LN1 in fp32
+ *     q, k, v = (aq . Wqkv8^T) * (sx1 * s_qkv) + bqkv     fp32 accumulation, stored as bf16
+ *     oq      = E4M3(attention output / sa)
+ *     x1      = x + (oq . WoT8^T) * (sa * so) + bo        fp32
+ * SentryAttend runs unchanged on q, k, v.  Wq, Wk, Wv carry ONE scale (they are
+ * one GEMM operand).  sf_compact_proj_fp8 gathers the kept rows of the dense
+ * codes (sf_dense_layer_fp8 with sq == sk == sv) into
+ *     Wqkv8 [P, (k_head + 2*Hk)*dh, d]      kept Q heads, K rows, V rows of the
+ *                                           used groups (zero rows for unused slots)
+ *     WoT8  [P, d, k_head*dh]
+ * both DEVICE buffers of the caller, uint8, 16-byte aligned; biases bqkv, bo
+ * and the LayerNorm vectors are those of the sf_compact_layer of the layer.
+ * s_qkv, so must equal the dense scales; sx1, sa are chosen by the caller
+ * (static activation scales).  Limits: bf16 model, d and k_head*dh multiples
+ * of 128, d >= 256, (k_head + 2*Hk)*dh >= 192, L >= 192; anything else returns
+ * SF_ERR_SHAPE / SF_ERR_UNSUPPORTED before a kernel is launched.
+ */
+typedef struct sf_proj_fp8 {
+    int32_t k_head;            /* Hq' */
+    int32_t reserved;
+    void *Wqkv8, *WoT8;
+    float s_qkv, so, sx1, sa;
+} sf_proj_fp8;
+int32_t sf_compact_proj_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense_host,
+                            const int32_t *head_idx, const int32_t *group_idx,
+                            const int32_t *n_groups, const sf_proj_fp8 *proj_host, void *stream);
+
+/* sf_encoder_forward with the attention projections (proj_host != NULL) and /
+ * or the FFNs (ffn_host != NULL) of every layer in FP8 arithmetic; at least one
+ * of the two is given.  proj_host [n_layers]: HOST array, k_head equal to
+ * layers_host[l].k_head.  The workspace is sf_encoder_fp8_workspace_bytes
+ * (larger than sf_encoder_workspace_bytes: token-major V and the codes of the
+ * attention output).  aq_out [n_layers, B*L, d] and oq_out (layer l's codes, a
+ * [B*L, k_head_l*dh] array over the KEPT heads in rank order, at
+ * oq_out + l*B*L*max_l k_head_l*dh) receive the codes when not NULL (16-byte
+ * aligned); xq_out, hq_out as in sf_encoder_forward_fp8ffn. */
+size_t sf_encoder_fp8_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers_host);
+int32_t sf_encoder_forward_fp8(const sf_desc *desc, const sf_compact_layer *layers_host,
+                               const sf_ffn_fp8 *ffn_host, const sf_proj_fp8 *proj_host,
+                               const void *X, const int32_t *pattern_id, const uint8_t *key_valid,
+                               const int32_t *sample_idx, const void *final_g, const void *final_b,
+                               const int32_t *forced_sel, void *Y, int32_t *sel_out,
+                               float *score_out, uint8_t *xq_out, uint8_t *hq_out, uint8_t *aq_out,
+                               uint8_t *oq_out, void *workspace, size_t workspace_bytes,
+                               void *stream);
+
 /* Element strides of a [B, heads, L, dh] tensor whose last dimension is
  * contiguous (for V with v_transposed: a [B, groups, dh, L] tensor whose L
  * dimension is contiguous and `l` is the stride between dh rows). */

@@ -29,7 +29,8 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8", "sf_quantize_fp8",
            "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
            "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
-           "sf_active_projection_rows"]
+           "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_fp8_workspace_bytes",
+           "sf_encoder_forward_fp8"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -75,6 +76,11 @@ class SfFfnFp8(C.Structure):
                 + [(n, C.c_float) for n in ("s1", "s2", "sx", "sh")])
 
 
+class SfProjFp8(C.Structure):
+    _fields_ = ([("k_head", C.c_int32), ("reserved", C.c_int32), ("Wqkv8", C.c_void_p), ("WoT8", C.c_void_p)]
+                + [(n, C.c_float) for n in ("s_qkv", "so", "sx1", "sa")])
+
+
 class SfMoeDense(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _MOE_DENSE_FIELDS]
 
@@ -102,7 +108,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.sf_last_error.restype = C.c_char_p
         for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes",
-                  "sf_moe_ffn_workspace_bytes", "sf_pruned_ffn_fp8_workspace_bytes"):
+                  "sf_moe_ffn_workspace_bytes", "sf_pruned_ffn_fp8_workspace_bytes", "sf_encoder_fp8_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
@@ -110,7 +116,7 @@ def lib():
                   "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
                   "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
-                  "sf_active_projection_rows"):
+                  "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_forward_fp8"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -136,6 +142,11 @@ def lib():
         L.sf_pruned_ffn_fp8_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.c_int32]
         L.sf_encoder_forward_fp8ffn.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.POINTER(SfFfnFp8)] + [
             C.c_void_p] * 13 + [C.c_size_t, C.c_void_p]
+        L.sf_compact_proj_fp8.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayerFp8), C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.POINTER(SfProjFp8), C.c_void_p]
+        L.sf_encoder_fp8_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)]
+        L.sf_encoder_forward_fp8.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.POINTER(SfFfnFp8),
+                                             C.POINTER(SfProjFp8)] + [C.c_void_p] * 15 + [C.c_size_t, C.c_void_p]
         L.sf_token_compact.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_int32] + [C.c_void_p] * 7
         L.sf_token_scatter.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.sf_encoder_forward_ragged.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)] + [C.c_void_p] * 11 + [
@@ -719,3 +730,84 @@ def encoder_forward_fp8ffn(desc: SfDesc, layers: List[CompactLayer], ffn8: List[
         hql = [hq[l, :B * L * f.Fp8].view(B * L, f.Fp8) for l, f in enumerate(ffn8)]
         return Y, sel, xq, hql
     return Y, sel
+
+
+# ---------------------------------------------------------- attention projections in FP8 arithmetic
+class CompactProjFp8:
+    """Q/K/V and output projection weights of one layer as E4M3 codes, compacted for all patterns."""
+
+    def __init__(self, desc: SfDesc, dev, k_head: int, s_qkv: float, so: float, sx1: float, sa: float):
+        P, d, dh, Hk = desc.P, desc.d_model, desc.dh, desc.Hk
+        self.k_head = int(k_head)
+        self.Wqkv8 = torch.empty((P, (self.k_head + 2 * Hk) * dh, d), dtype=torch.uint8, device=dev)
+        self.WoT8 = torch.empty((P, d, self.k_head * dh), dtype=torch.uint8, device=dev)
+        self.struct = SfProjFp8(self.k_head, 0, _ptr(self.Wqkv8), _ptr(self.WoT8), float(s_qkv), float(so),
+                                float(sx1), float(sa))
+
+
+def compact_proj_fp8(desc: SfDesc, layer: int, dense8: Dict[str, torch.Tensor], s_qkv: float, so: float,
+                     masks: Dict[str, torch.Tensor], k_head: int, sx1: float, sa: float) -> CompactProjFp8:
+    """dense8: Wq [Hq*dh, d], Wk, Wv [Hk*dh, d], Wo [Hq*dh, d] uint8 (E4M3 codes; Wq, Wk, Wv with the one scale
+    s_qkv, Wo with so)."""
+    for n in ("Wq", "Wk", "Wv", "Wo"):
+        assert dense8[n].dtype == torch.uint8 and dense8[n].is_contiguous(), n
+    cp = CompactProjFp8(desc, dense8["Wq"].device, k_head, s_qkv, so, sx1, sa)
+    nul = C.c_void_p(None)
+    ds = SfDenseLayerFp8(_ptr(dense8["Wq"]), _ptr(dense8["Wk"]), _ptr(dense8["Wv"]), _ptr(dense8["Wo"]), nul, nul,
+                         float(s_qkv), float(s_qkv), float(s_qkv), float(so), 0.0, 0.0, *([nul] * 10))
+    rc = lib().sf_compact_proj_fp8(C.byref(desc), layer, C.byref(ds), _ptr(masks["head_idx"]),
+                                   _ptr(masks["group_idx"]), _ptr(masks["n_groups"]), C.byref(cp.struct), _stream())
+    _check(rc, "sf_compact_proj_fp8")
+    return cp
+
+
+def encoder_fp8_workspace_bytes(desc: SfDesc, layers: List[CompactLayer]) -> int:
+    return int(lib().sf_encoder_fp8_workspace_bytes(C.byref(desc), layer_array(layers)))
+
+
+def encoder_forward_fp8(desc: SfDesc, layers: List[CompactLayer], X: torch.Tensor,
+                        ffn8: Optional[List[CompactFfnFp8]] = None, proj8: Optional[List[CompactProjFp8]] = None,
+                        pattern_id: Optional[torch.Tensor] = None, key_valid: Optional[torch.Tensor] = None,
+                        final_ln: Optional[Dict[str, torch.Tensor]] = None,
+                        forced_sel: Optional[torch.Tensor] = None, want_sel: bool = False, want_codes: bool = False,
+                        out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """sf_encoder_forward with the FFNs (ffn8) and / or the attention projections (proj8) in FP8 arithmetic.
+    Returns (Y, sel | None) and, with want_codes, a dict of the codes: xq [nl, B*L, d], hq (list of [B*L, Fp8_l]),
+    aq [nl, B*L, d], oq (list of [B*L, k_head_l*dh]); entries of a part that is not in FP8 are None."""
+    assert X.is_contiguous()
+    B, L, d = X.shape
+    nl = desc.n_layers
+    U = num_active(desc)
+    khmax = max(l.k_head for l in layers)
+    dev = X.device
+    Y = torch.empty_like(X) if out is None else out
+    sel = torch.full((nl, B, khmax, max(U, 1)), -1, dtype=torch.int32, device=dev) if want_sel else None
+    arr = layer_array(layers)
+    farr = None if ffn8 is None else (SfFfnFp8 * nl)(*[f.struct for f in ffn8])
+    parr = None if proj8 is None else (SfProjFp8 * nl)(*[p.struct for p in proj8])
+    if ws is None:
+        ws = workspace(lib().sf_encoder_fp8_workspace_bytes(C.byref(desc), arr), dev)
+    xq = hq = aq = oq = None
+    if want_codes and ffn8 is not None:
+        F8max = max(f.Fp8 for f in ffn8)
+        xq = torch.empty((nl, B * L, d), dtype=torch.uint8, device=dev)
+        hq = torch.zeros((nl, B * L * F8max), dtype=torch.uint8, device=dev)
+    if want_codes and proj8 is not None:
+        aq = torch.empty((nl, B * L, d), dtype=torch.uint8, device=dev)
+        oq = torch.zeros((nl, B * L * khmax * desc.dh), dtype=torch.uint8, device=dev)
+    fg = None if final_ln is None else final_ln["g"]
+    fb = None if final_ln is None else final_ln["b"]
+    rc = lib().sf_encoder_forward_fp8(C.byref(desc), arr, farr, parr, _ptr(X), _ptr(pattern_id), _ptr(key_valid),
+                                      None, _ptr(fg), _ptr(fb), _ptr(forced_sel), _ptr(Y),
+                                      _ptr(sel if U > 0 else None), None, _ptr(xq), _ptr(hq), _ptr(aq), _ptr(oq),
+                                      _ptr(ws), ws.numel(), _stream())
+    _check(rc, "sf_encoder_forward_fp8")
+    if not want_codes:
+        return Y, sel
+    codes = dict(xq=xq, hq=None, aq=aq, oq=None)
+    if hq is not None:
+        codes["hq"] = [hq[l, :B * L * f.Fp8].view(B * L, f.Fp8) for l, f in enumerate(ffn8)]
+    if oq is not None:
+        codes["oq"] = [oq[l, :B * L * p.k_head * desc.dh].view(B * L, p.k_head * desc.dh)
+                       for l, p in enumerate(proj8)]
+    return Y, sel, codes

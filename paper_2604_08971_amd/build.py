@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsentryfuse.so")
 
-SOURCES = ["api.hip", "masks.hip", "compact.hip", "gemm_bf16.hip", "gemm_bf16_fast.hip", "gemm_bf16_ws.hip", "gemm_f32.hip", "moe.hip", "gate.hip", "fp8_ffn.hip", "tokens.hip", "lazy_proj.hip",
+SOURCES = ["api.hip", "masks.hip", "compact.hip", "gemm_bf16.hip", "gemm_bf16_fast.hip", "gemm_bf16_ws.hip", "gemm_f32.hip", "moe.hip", "gate.hip", "fp8_ffn.hip", "tokens.hip", "lazy_proj.hip", "fp8_proj.hip",
            "attention_common.hip", "attention_bf16.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

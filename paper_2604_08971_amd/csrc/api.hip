@@ -133,6 +133,7 @@ struct EncWs {
     void *xn, *qkv, *vt, *att, *x1, *x2, *hid, *attn_ws;     // x1, x2: the fp32 residual stream
     // output projection of the active rows only (lazy_proj.hip): compact rows, their projection, row maps, c_b
     void *lz_A; float *lz_C, *lz_c; int32_t *lz_arow, *lz_pos, *lz_n, *lz_cnt, *lz_blk; int lz_cap;
+    uint8_t *oq;                                             // projections in FP8 arithmetic: codes of the attention output
     size_t attn_ws_bytes, bytes;
     int kh_max, Fp_max, Lp;
 };
@@ -145,7 +146,7 @@ static AttnArgs enc_attn_args(const Dims &D, int kh)
     return a;
 }
 
-static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, EncWs &w)
+static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, EncWs &w, bool proj8 = false)
 {
     w = EncWs{};
     int kh_max = 0, kf_max = 0;
@@ -163,7 +164,8 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     Carver c(ws);
     w.xn = c.take<char>(rows * D.d * es);
     // bf16: Q and K token-major, V transposed [B,Hk,dh,Lp]; fp32: Q, K, V token-major
-    w.qkv = c.take<char>(rows * (size_t)(kh_max + (bf ? 1 : 2) * D.Hk) * D.dh * es);
+    // (projections in FP8 arithmetic: the GEMM writes V token-major too, a second pass transposes it)
+    w.qkv = c.take<char>(rows * (size_t)(kh_max + (bf && !proj8 ? 1 : 2) * D.Hk) * D.dh * es);
     w.vt = bf ? c.take<char>((size_t)D.B * D.Hk * D.dh * w.Lp * es) : nullptr;
     w.att = c.take<char>(rows * (size_t)kh_max * D.dh * es);
     w.x1 = c.take<float>(rows * D.d);
@@ -176,7 +178,8 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     }
     w.attn_ws_bytes = amax;
     w.attn_ws = c.take<char>(amax);
-    w.lz_cap = bf ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
+    w.oq = proj8 ? c.take<uint8_t>(rows * (size_t)kh_max * D.dh) : nullptr;
+    w.lz_cap = bf && !proj8 ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
     if (w.lz_cap) {
         const size_t crow = (size_t)D.B * w.lz_cap;
         w.lz_A = c.take<char>(crow * kh_max * D.dh * es);
@@ -306,7 +309,9 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
                                     const void *final_b, const int32_t *forced_sel,
                                     void *Y, int32_t *sel_out, float *score_out, void *workspace,
                                     size_t workspace_bytes, void *stream, const sf_ffn_fp8 *ffn8 = nullptr,
-                                    uint8_t *xq_out = nullptr, uint8_t *hq_out = nullptr)
+                                    uint8_t *xq_out = nullptr, uint8_t *hq_out = nullptr,
+                                    const sf_proj_fp8 *proj8 = nullptr, uint8_t *aq_out = nullptr,
+                                    uint8_t *oq_out = nullptr)
 {
     Dims D;
     if (int32_t rc = read_desc(desc, D)) return rc;
@@ -321,6 +326,13 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         }
         if (((uintptr_t)xq_out | (uintptr_t)hq_out) & 15)
             return fail(SF_ERR_INVALID_ARG, "encoder(fp8 ffn): 16-byte aligned code buffers required");
+    }
+    if (proj8) {
+        if (!layers) return fail(SF_ERR_INVALID_ARG, "encoder: NULL argument");
+        for (int l = 0; l < D.nl; ++l)
+            if (int32_t rc = proj_fp8_check("encoder(fp8 projections)", D, &proj8[l], layers[l].k_head)) return rc;
+        if (((uintptr_t)aq_out | (uintptr_t)oq_out) & 15)
+            return fail(SF_ERR_INVALID_ARG, "encoder(fp8 projections): 16-byte aligned code buffers required");
     }
     if (u_active && D.U >= D.L)
         return fail(SF_ERR_UNSUPPORTED, "encoder: per-sample active counts need U < L (U = %d, L = %d)", D.U, D.L);
@@ -343,7 +355,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         return fail(SF_ERR_SHAPE, "encoder(f32): dh must be a multiple of 4, at most 256");
     if (D.Hq > 64) return fail(SF_ERR_SHAPE, "encoder: Hq <= 64 required");
     EncWs w;
-    if (int32_t rc = enc_ws(D, layers, workspace, w)) return rc;
+    if (int32_t rc = enc_ws(D, layers, workspace, w, proj8 != nullptr)) return rc;
     if (!workspace || workspace_bytes < w.bytes || ((uintptr_t)workspace & 255))
         return fail(SF_ERR_WORKSPACE, "encoder: workspace of %zu bytes (256-byte aligned) required, got %zu",
                     w.bytes, workspace_bytes);
@@ -362,9 +374,24 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         const sf_compact_layer &ly = layers[l];
         const int kh = ly.k_head, dh = D.dh, Hk = D.Hk;
         const int Nqk = (kh + Hk) * dh, Nqkv = (kh + 2 * Hk) * dh;
-        const int ldq = bf ? Nqk : Nqkv;                    // row length of the token-major buffer
+        const int ldq = bf && !proj8 ? Nqk : Nqkv;          // row length of the token-major buffer
 
         // x' = LN1(x);  Q, K (token-major) and V (bf16: transposed) = x' Wqkv'^T + b
+        if (proj8) {
+            // the same in FP8 arithmetic: codes of LN1(x), one GEMM for Q, K, V (token-major), V transposed after it
+            const sf_proj_fp8 &pj = proj8[l];
+            if (((uintptr_t)ly.ln1_g | (uintptr_t)ly.ln1_b | (uintptr_t)in) & 15)
+                return fail(SF_ERR_INVALID_ARG, "encoder(fp8 projections): 16-byte aligned input and LayerNorm vectors required");
+            uint8_t *aq = aq_out ? aq_out + (size_t)l * rows * D.d : static_cast<uint8_t *>(w.xn);
+            layernorm_q8(in, in_f32, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, 1.0f / pj.sx1, aq, st);
+            GemmArgs q8{};
+            q8.f8 = 1; q8.A = aq; q8.lda = D.d; q8.W = pj.Wqkv8; q8.ldw = D.d; q8.w_pstride = (int64_t)Nqkv * D.d;
+            q8.bias = ly.bqkv; q8.bias_pstride = Nqkv; q8.pattern_id = pattern_id;
+            q8.B = D.B; q8.L = D.L; q8.N = Nqkv; q8.K = D.d; q8.epi = EPI_ROWMAJOR; q8.act = ACT_NONE;
+            q8.out_scale = pj.sx1 * pj.s_qkv; q8.C = w.qkv; q8.ldc = Nqkv;
+            if (int32_t rc = gemm_fp8(q8, st)) return rc;
+            transpose_v(w.qkv, Nqkv, Nqk, Hk * dh, D.B, D.L, w.Lp, w.vt, st);
+        } else {
         layernorm(D.dtype, in_f32, in, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, w.xn, st);
         GemmArgs g{};
         g.A = w.xn; g.lda = D.d; g.W = ly.Wqkv; g.ldw = D.d; g.w_pstride = (int64_t)Nqkv * D.d;
@@ -386,6 +413,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             }
         } else {
             if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+        }
         }
 
         // SentryAttend over the kept heads
@@ -450,12 +478,26 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         }
 
         // x1 = x + att Wo' + bo   (only the kept heads' rows of Wo exist)
+        if (proj8) {
+            const sf_proj_fp8 &pj = proj8[l];
+            const int64_t Ko = (int64_t)kh * dh;
+            uint8_t *oq = oq_out ? oq_out + (size_t)l * rows * w.kh_max * dh : w.oq;
+            quantize_fp8_bf16(w.att, rows * Ko, 1.0f / pj.sa, oq, st);
+            GemmArgs o8{};
+            o8.f8 = 1; o8.A = oq; o8.lda = Ko; o8.W = pj.WoT8; o8.ldw = Ko; o8.w_pstride = (int64_t)D.d * Ko;
+            o8.bias = ly.bo; o8.bias_pstride = 0; o8.pattern_id = pattern_id;
+            o8.B = D.B; o8.L = D.L; o8.N = D.d; o8.K = (int)Ko; o8.epi = EPI_ROWMAJOR; o8.act = ACT_NONE;
+            o8.out_scale = pj.sa * pj.so;
+            o8.R = in; o8.ldr = D.d; o8.r_f32 = in_f32; o8.C = w.x1; o8.ldc = D.d; o8.c_f32 = 1;
+            if (int32_t rc = gemm_fp8(o8, st)) return rc;
+        } else {
         GemmArgs o{};
         o.A = w.att; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
         o.w_pstride = (int64_t)D.d * kh * dh; o.bias = ly.bo; o.bias_pstride = 0; o.pattern_id = pattern_id;
         o.B = D.B; o.L = D.L; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
         o.R = in; o.ldr = D.d; o.r_f32 = in_f32; o.C = w.x1; o.ldc = D.d; o.c_f32 = 1;
         if (int32_t rc = gemm(D.dtype, o, st)) return rc;
+        }
 
         // x2 = x1 + FFN(LN2(x1)); the last layer without a final LN writes Y directly
         const bool to_y = l == D.nl - 1 && !final_ln;
@@ -511,4 +553,25 @@ extern "C" int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compa
     if (!u_active) return fail(SF_ERR_INVALID_ARG, "encoder_ragged: u_active is NULL");
     return encoder_forward_impl(desc, layers, X, pattern_id, key_valid, sample_idx, u_active, final_g, final_b,
                                 nullptr, Y, sel_out, score_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t sf_encoder_fp8_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers)
+{
+    Dims D;
+    EncWs w;
+    if (read_desc(desc, D) || !layers || enc_ws(D, layers, nullptr, w, true)) return 0;
+    return w.bytes;
+}
+
+extern "C" int32_t sf_encoder_forward_fp8(const sf_desc *desc, const sf_compact_layer *layers, const sf_ffn_fp8 *ffn8,
+                                          const sf_proj_fp8 *proj8, const void *X, const int32_t *pattern_id,
+                                          const uint8_t *key_valid, const int32_t *sample_idx, const void *final_g,
+                                          const void *final_b, const int32_t *forced_sel, void *Y, int32_t *sel_out,
+                                          float *score_out, uint8_t *xq_out, uint8_t *hq_out, uint8_t *aq_out,
+                                          uint8_t *oq_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ffn8 && !proj8) return fail(SF_ERR_INVALID_ARG, "encoder(fp8): ffn_host and proj_host are both NULL");
+    return encoder_forward_impl(desc, layers, X, pattern_id, key_valid, sample_idx, nullptr, final_g, final_b,
+                                forced_sel, Y, sel_out, score_out, workspace, workspace_bytes, stream, ffn8, xq_out,
+                                hq_out, proj8, aq_out, oq_out);
 }

@@ -598,3 +598,48 @@ extern "C" int32_t sf_compact_ffn_fp8(const sf_desc *desc, int32_t layer, const 
                        (uint8_t *)f->W2Tq, fi, D.F, 1, kf, Fp8, d, (size_t)d * Fp8);
     return check_launch("compact_ffn_fp8");
 }
+
+// Attention projection weights kept as E4M3 codes for the FP8 arithmetic path: Wqkv8 [P, (k_head + 2 Hk) dh, d]
+// (kept Q heads, then the K and the V rows of the used groups, zero rows for unused group slots) and
+// WoT8 [P, d, k_head dh], the same gathers as for the 16-bit weights on bytes.
+extern "C" int32_t sf_compact_proj_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense,
+                                       const int32_t *head_idx, const int32_t *group_idx, const int32_t *n_groups,
+                                       const sf_proj_fp8 *pj, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (!dense || !pj || !head_idx || !group_idx || !n_groups)
+        return fail(SF_ERR_INVALID_ARG, "compact_proj_fp8: NULL argument");
+    if (layer < 0 || layer >= D.nl) return fail(SF_ERR_INVALID_ARG, "compact_proj_fp8: layer %d out of range", layer);
+    if (pj->k_head < 1 || pj->k_head > D.Hq) return fail(SF_ERR_INVALID_ARG, "compact_proj_fp8: k_head out of range");
+    if (!dense->Wq || !dense->Wk || !dense->Wv || !dense->Wo || !pj->Wqkv8 || !pj->WoT8)
+        return fail(SF_ERR_INVALID_ARG, "compact_proj_fp8: NULL weight pointer");
+    if (!(dense->sq == dense->sk && dense->sk == dense->sv))
+        return fail(SF_ERR_INVALID_ARG, "compact_proj_fp8: Wq, Wk, Wv must share one scale (they form one GEMM operand)");
+    if (pj->s_qkv != dense->sq || pj->so != dense->so)
+        return fail(SF_ERR_INVALID_ARG, "compact_proj_fp8: s_qkv / so differ from the scales of the dense codes");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int P = D.P, dh = D.dh, d = D.d, kh = pj->k_head;
+    const int Nqkv = (kh + 2 * D.Hk) * dh;
+    const int32_t *hi = head_idx + (size_t)layer * P * D.Hq;
+    const int32_t *gi = group_idx + (size_t)layer * P * D.Hk;
+    const int32_t *ng = n_groups + (size_t)layer * P;
+    auto region = [&](const void *src, size_t row_off, const int32_t *idx, int idx_stride, int n_static,
+                      const int32_t *n_dev, int rows) {
+        GatherRegion r{};
+        r.src = src; r.dst = (char *)pj->Wqkv8 + row_off * d; r.idx = idx; r.n_dev = n_dev;
+        r.idx_stride = idx_stride; r.block = dh; r.n_static = n_static; r.rows = rows;
+        r.dst_pstride = (size_t)Nqkv;
+        return r;
+    };
+    GatherRegions wr{};
+    wr.r[wr.n++] = region(dense->Wq, 0, hi, D.Hq, kh, nullptr, kh * dh);
+    wr.r[wr.n++] = region(dense->Wk, (size_t)kh * dh, gi, D.Hk, 0, ng, D.Hk * dh);
+    wr.r[wr.n++] = region(dense->Wv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, 0, ng, D.Hk * dh);
+    if (d % 2) return fail(SF_ERR_SHAPE, "compact_proj_fp8: d_model must be even");
+    gather_rows(st, wr, (size_t)d, P);
+    dim3 grid(ceil_div(kh * dh, 32), ceil_div(d, 32), P);
+    hipLaunchKernelGGL(gather_transpose_kernel<uint8_t>, grid, dim3(256), 0, st, (const uint8_t *)dense->Wo,
+                       (uint8_t *)pj->WoT8, hi, D.Hq, dh, kh, kh * dh, d, (size_t)d * kh * dh);
+    return check_launch("compact_proj_fp8");
+}

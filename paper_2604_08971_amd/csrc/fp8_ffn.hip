@@ -174,18 +174,35 @@ extern "C" size_t sf_pruned_ffn_fp8_workspace_bytes(const sf_desc *desc, int32_t
     return fp8_ffn_ws(D, sf_ffn_fp8_padded(k_ffn), nullptr).bytes;
 }
 
-template <class TI>
-static void launch_ln_q8(const void *X, const sf_ffn_fp8 &f, const Dims &D, int64_t rows, float inv_sx, uint8_t *xq,
-                         hipStream_t st)
+namespace sf {
+
+void layernorm_q8(const void *X, bool x_f32, const void *gamma, const void *beta, float eps, int64_t rows, int d,
+                  float inv_scale, uint8_t *y, hipStream_t st)
 {
+    if (rows == 0) return;
     dim3 grid((unsigned)((rows + 3) / 4));
-#define SF_LNQ_ARGS grid, dim3(256), 0, st, (const TI *)X, (const __bf16 *)f.ln2_g, (const __bf16 *)f.ln2_b, D.eps, rows, D.d, inv_sx, xq
-    if (D.d <= 512) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 1>), SF_LNQ_ARGS);
-    else if (D.d <= 1024) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 2>), SF_LNQ_ARGS);
-    else if (D.d <= 2048) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 4>), SF_LNQ_ARGS);
-    else hipLaunchKernelGGL((layernorm_q8_kernel<TI, 8>), SF_LNQ_ARGS);
+#define SF_LNQ_ARGS(TI) grid, dim3(256), 0, st, (const TI *)X, (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, inv_scale, y
+#define SF_LNQ(TI) \
+    do { \
+        if (d <= 512) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 1>), SF_LNQ_ARGS(TI)); \
+        else if (d <= 1024) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 2>), SF_LNQ_ARGS(TI)); \
+        else if (d <= 2048) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 4>), SF_LNQ_ARGS(TI)); \
+        else hipLaunchKernelGGL((layernorm_q8_kernel<TI, 8>), SF_LNQ_ARGS(TI)); \
+    } while (0)
+    if (x_f32) SF_LNQ(float);
+    else SF_LNQ(__bf16);
+#undef SF_LNQ
 #undef SF_LNQ_ARGS
 }
+
+void quantize_fp8_bf16(const void *x, int64_t n, float inv_scale, uint8_t *codes, hipStream_t st)
+{
+    if (n == 0) return;
+    hipLaunchKernelGGL(quantize_fp8_kernel<__bf16>, dim3((unsigned)(((n + 7) / 8 + 255) / 256)), dim3(256), 0, st,
+                       (const __bf16 *)x, n, inv_scale, codes);
+}
+
+}  // namespace sf
 
 namespace sf {
 
@@ -209,13 +226,10 @@ int32_t ffn_fp8_forward(const Dims &D, const sf_ffn_fp8 &f, const void *X, bool 
     if (xq_ready) {
         // the codes of LN2(X) were written together with X
     } else if (pre_ln) {
-        if (x_f32) launch_ln_q8<float>(X, f, D, rows, inv_sx, xq, st);
-        else launch_ln_q8<__bf16>(X, f, D, rows, inv_sx, xq, st);
+        layernorm_q8(X, x_f32, f.ln2_g, f.ln2_b, D.eps, rows, D.d, inv_sx, xq, st);
     } else {
         if (x_f32) return fail(SF_ERR_UNSUPPORTED, "ffn_fp8: an fp32 input needs the LayerNorm");
-        const int64_t n = rows * D.d;
-        hipLaunchKernelGGL(quantize_fp8_kernel<__bf16>, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, st,
-                           (const __bf16 *)X, n, inv_sx, xq);
+        quantize_fp8_bf16(X, rows * D.d, inv_sx, xq, st);
     }
     GemmArgs g{};
     g.f8 = 1; g.A = xq; g.lda = D.d; g.W = f.W1q; g.ldw = D.d; g.w_pstride = (int64_t)Fp8 * D.d;

@@ -1,0 +1,58 @@
+// FP8 arithmetic for the attention projections (Sec. 6, "Compatibility with quantization": the FP8 models; which
+// contractions run in FP8 is this build's reading).  The contractions are gemm_fp8() launches issued by the encoder;
+// this file holds the argument checks and the V transposition that the bf16 GEMM does in its epilogue.
+#include "gemm.hpp"
+
+namespace sf {
+
+namespace {
+
+// 64 tokens x 64 features per block through LDS: reads along the features, writes along the tokens
+__global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restrict__ src, int64_t ld, int col0, int ncols,
+                                                          int L, int Lp, __bf16 *__restrict__ vt)
+{
+    __shared__ uint16_t tile[64][66];
+    const int b = blockIdx.z, j0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const uint16_t *s = reinterpret_cast<const uint16_t *>(src) + (int64_t)b * L * ld + col0;
+    uint16_t *dst = reinterpret_cast<uint16_t *>(vt) + (int64_t)b * ncols * Lp;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int jj = ty; jj < 64; jj += 4) {
+        const int j = j0 + jj, c = c0 + tx;
+        tile[jj][tx] = (j < L && c < ncols) ? s[(int64_t)j * ld + c] : (uint16_t)0;
+    }
+    __syncthreads();
+    for (int cc = ty; cc < 64; cc += 4) {
+        const int c = c0 + cc, j = j0 + tx;
+        if (c < ncols && j < Lp) dst[(int64_t)c * Lp + j] = tile[tx][cc];
+    }
+}
+
+}  // namespace
+
+void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st)
+{
+    if (B == 0 || ncols == 0) return;
+    dim3 grid((unsigned)ceil_div(Lp, 64), (unsigned)ceil_div(ncols, 64), (unsigned)B);
+    hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, st, (const __bf16 *)src, ld, col0, ncols, L, Lp,
+                       (__bf16 *)vt);
+}
+
+int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int k_head)
+{
+    if (!p) return fail(SF_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: the FP8 path takes bf16 activations (dtype SF_BF16)", who);
+    if (p->k_head != k_head) return fail(SF_ERR_INVALID_ARG, "%s: k_head differs from the compact layer's", who);
+    if (!p->Wqkv8 || !p->WoT8) return fail(SF_ERR_INVALID_ARG, "%s: NULL weight pointer", who);
+    if (((uintptr_t)p->Wqkv8 | (uintptr_t)p->WoT8) & 15)
+        return fail(SF_ERR_INVALID_ARG, "%s: 16-byte aligned weight codes required", who);
+    if (!(p->s_qkv > 0.f) || !(p->so > 0.f) || !(p->sx1 > 0.f) || !(p->sa > 0.f))
+        return fail(SF_ERR_INVALID_ARG, "%s: the four scales must be positive", who);
+    if (D.d % 128 || D.d < 256 || D.d > 4096)
+        return fail(SF_ERR_SHAPE, "%s: d_model must be a multiple of 128 in [256, 4096]", who);
+    if ((k_head * D.dh) % 128) return fail(SF_ERR_SHAPE, "%s: k_head * dh must be a multiple of 128", who);
+    if ((k_head + 2 * D.Hk) * D.dh < 192) return fail(SF_ERR_UNSUPPORTED, "%s: at least 192 Q/K/V features required", who);
+    if (D.L < 192) return fail(SF_ERR_UNSUPPORTED, "%s: at least 192 tokens per sample required", who);
+    return SF_OK;
+}
+
+}  // namespace sf

@@ -57,6 +57,18 @@ int32_t ffn_fp8_forward(const Dims &D, const sf_ffn_fp8 &f, const void *X, bool 
                         bool pre_ln, bool add_residual, void *Y, bool y_f32, uint8_t *xq, uint8_t *hq, hipStream_t st,
                         bool xq_ready = false);      // xq_ready: xq already holds the codes of LN2(X)
 
+// Quantisers of fp8_ffn.hip: y = E4M3(LayerNorm(x) * inv_scale) for rows of d elements (d % 8 == 0, d <= 4096, gamma /
+// beta bf16, 16-byte aligned), and codes = E4M3(x * inv_scale) for n bf16 values (x 16-byte, codes 8-byte aligned).
+void layernorm_q8(const void *X, bool x_f32, const void *gamma, const void *beta, float eps, int64_t rows, int d,
+                  float inv_scale, uint8_t *y, hipStream_t st);
+void quantize_fp8_bf16(const void *x, int64_t n, float inv_scale, uint8_t *codes, hipStream_t st);
+
+// The attention projections in FP8 arithmetic (fp8_proj.hip).
+int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int k_head);
+// vt[b, c, j] = src[b, j, col0 + c] for c < ncols, j < L (zeros for L <= j < Lp): the V columns of a token-major
+// bf16 buffer into the key-contiguous layout the attention kernels read.
+void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st);
+
 // True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).
 bool gemm_takes_row_map(int dtype, const GemmArgs &a);
 

@@ -35,6 +35,7 @@ def test_struct_layout_matches_header():
     assert C.sizeof(sf.SfGateParams) == 16 + 6 * 8
     assert C.sizeof(sf.SfDenseLayerFp8) == 6 * 8 + 6 * 4 + 10 * 8
     assert C.sizeof(sf.SfFfnFp8) == 8 + 6 * 8 + 4 * 4
+    assert C.sizeof(sf.SfProjFp8) == 8 + 2 * 8 + 4 * 4
 
 
 def test_num_active_matches_paper_example():
@@ -158,6 +159,26 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_encoder_forward_fp8ffn(C.byref(d), C.byref(cl8f), C.byref(f8), *eargs) in (-2, -3)  # fp32 descriptor
     cl8f.k_ffn = 300
     assert L.sf_encoder_forward_fp8ffn(C.byref(d8ok), C.byref(cl8f), C.byref(f8), *eargs) == -1   # k_ffn mismatch
+    # encoder with FP8 projections: checked before anything is enqueued
+    cl8f.k_ffn = 200
+    pj = sf.SfProjFp8()
+    pj.k_head, pj.s_qkv, pj.so, pj.sx1, pj.sa = 4, 1.0, 1.0, 1.0, 1.0
+    pj.Wqkv8 = pj.WoT8 = 256
+    dp = sf.make_desc(1, 256, 256, 8, 2, 32, 512, dtype=sf.SF_BF16)
+    pargs = eargs[:12] + (None, None) + eargs[12:]
+    assert L.sf_encoder_forward_fp8(C.byref(dp), C.byref(cl8f), None, None, *pargs) == -1         # neither part in FP8
+    assert L.sf_encoder_forward_fp8(C.byref(d), C.byref(cl8f), None, C.byref(pj), *pargs) in (-2, -3)   # fp32 descriptor
+    pj.k_head = 3
+    assert L.sf_encoder_forward_fp8(C.byref(dp), C.byref(cl8f), None, C.byref(pj), *pargs) == -1  # k_head mismatch
+    pj.k_head, cl8f.k_head = 3, 3
+    assert L.sf_encoder_forward_fp8(C.byref(dp), C.byref(cl8f), None, C.byref(pj), *pargs) == -2  # 3*32 not a multiple of 128
+    pj.k_head, cl8f.k_head, pj.sa = 4, 4, 0.0
+    assert L.sf_encoder_forward_fp8(C.byref(dp), C.byref(cl8f), None, C.byref(pj), *pargs) == -1
+    pj.sa = 1.0
+    d8.sq, d8.sk, d8.sv, d8.so = 1.0, 1.0, 1.0, 1.0
+    assert L.sf_compact_proj_fp8(C.byref(dp), 0, C.byref(d8), one, one, one, C.byref(pj), None) == -1   # NULL dense matrices
+    assert L.sf_compact_proj_fp8(C.byref(dp), 5, C.byref(d8), one, one, one, C.byref(pj), None) == -1   # layer out of range
+    assert L.sf_encoder_fp8_workspace_bytes(C.byref(dp), C.byref(cl8f)) > L.sf_encoder_workspace_bytes(C.byref(dp), C.byref(cl8f))
     # FP16-stored weights
     assert L.sf_compact_heads_channels_f16(C.byref(d), 0, None, one, one, one, one, C.byref(cl8), None) == -1
     dl16 = sf.SfDenseLayer()
