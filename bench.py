@@ -497,6 +497,35 @@ def bench_ffn_fp8(wl, dm, steps, warmup):
         ms_e16, _ = time_steps(e16, steps, warmup)
         enc = {"ms_encoder_fp8_ffn": ms_e8, "ms_encoder_bf16": ms_e16, "tokens_per_s_fp8_ffn": B * L / (ms_e8 * 1e-3),
                "tokens_per_s_bf16": B * L / (ms_e16 * 1e-3)}
+        kh = int(wl.k_head[0])
+        if (kh * s.dh) % 128 == 0 and (kh + 2 * s.Hk) * s.dh >= 192:
+            # and with the Q/K/V and output projections in FP8 arithmetic too (static scales: weights amax / 448;
+            # LN1(x) amax / 448; the attention output is a convex combination of V rows, so amax |V| / 448 bounds it)
+            p8 = {}
+            s_qkv = float(max(dense[n].float().abs().max() for n in ("Wq", "Wk", "Wv")) / 448.0)
+            so = float(dense["Wo"].float().abs().max() / 448.0)
+            for n in ("Wq", "Wk", "Wv", "Wo"):
+                p8[n] = (dense[n].float() / (so if n == "Wo" else s_qkv)).to(torch.float8_e4m3fn).view(torch.uint8).contiguous()
+            xn1 = torch.nn.functional.layer_norm(X[0].float(), (d,), dense["ln1_g"].float(), dense["ln1_b"].float(), 1e-5)
+            sx1 = float(torch.nn.functional.layer_norm(X.float(), (d,), dense["ln1_g"].float(), dense["ln1_b"].float(),
+                                                       1e-5).abs().max() / 448.0)
+            sa = float((xn1 @ dense["Wv"].float().T + dense["bv"].float()).abs().max() / 448.0) * 1.25
+            cp = sf.compact_proj_fp8(dm.desc, 0, p8, s_qkv, so, dm.masks, kh, sx1, sa)
+            wsp = sf.workspace(sf.encoder_fp8_workspace_bytes(dm.desc, dm.layers))
+
+            def e8p():
+                sf.encoder_forward_fp8(dm.desc, dm.layers, X, ffn8=[cf], proj8=[cp], pattern_id=pid, key_valid=dm.key_valid,
+                                       final_ln=dm.final_ln, out=Ye, ws=wsp)
+
+            ms_e8p, _ = time_steps(e8p, steps, warmup)
+            e16()
+            y16e = Ye.float().clone()
+            e8p()
+            rel_e = float((Ye.float() - y16e).norm() / (y16e - X.float()).norm())
+            enc.update({"ms_encoder_fp8_proj_ffn": ms_e8p, "tokens_per_s_fp8_proj_ffn": B * L / (ms_e8p * 1e-3),
+                        "rel_diff_of_layer_update_fp8_proj_ffn_vs_bf16": rel_e,
+                        "proj_scales": {"s_qkv": s_qkv, "so": so, "sx1": sx1, "sa": sa}})
+            del wsp, cp, p8, y16e
         del wse, Ye
     y8 = sf.pruned_ffn_fp8_forward(dm.desc, cf, X, pid, ws=ws8).float()
     y16 = sf.pruned_ffn_forward(dm.desc, dm.layers[0], X, pid, ws=ws16).float()
@@ -511,8 +540,9 @@ def bench_ffn_fp8(wl, dm, steps, warmup):
                                 "ffn_down": flop / each["fp8"][1] / 1e6 / 5000.0},
            "encoder_step": enc, "rel_diff_of_ffn_update_vs_bf16": rel, "scales": {"sx": sx, "sh": sh, "s1": sc["W1"], "s2": sc["W2"]},
            "note": "sf_pruned_ffn_fp8_forward vs sf_pruned_ffn_forward (LayerNorm + two GEMMs, layer 0), and the encoder "
-                   "forward (plan excluded) with that FFN in FP8 arithmetic, sf_encoder_forward_fp8ffn, vs "
-                   "sf_encoder_forward; not part of `value`"}
+                   "forward (plan excluded) with that FFN in FP8 arithmetic, sf_encoder_forward_fp8ffn, and with the "
+                   "attention projections in FP8 arithmetic as well, sf_encoder_forward_fp8, vs sf_encoder_forward; "
+                   "not part of `value`"}
     del cf, ws8, ws16
     torch.cuda.empty_cache()
     return out

@@ -133,6 +133,7 @@ struct EncWs {
     void *xn, *qkv, *vt, *att, *x1, *x2, *hid, *attn_ws;     // x1, x2: the fp32 residual stream
     // output projection of the active rows only (lazy_proj.hip): compact rows, their projection, row maps, c_b
     void *lz_A; float *lz_C, *lz_c; int32_t *lz_arow, *lz_pos, *lz_n, *lz_cnt, *lz_blk; int lz_cap;
+    uint8_t *lz_A8;                                          // ... and of the compact rows
     uint8_t *oq;                                             // projections in FP8 arithmetic: codes of the attention output
     size_t attn_ws_bytes, bytes;
     int kh_max, Fp_max, Lp;
@@ -179,10 +180,11 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     w.attn_ws_bytes = amax;
     w.attn_ws = c.take<char>(amax);
     w.oq = proj8 ? c.take<uint8_t>(rows * (size_t)kh_max * D.dh) : nullptr;
-    w.lz_cap = bf && !proj8 ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
+    w.lz_cap = bf ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
     if (w.lz_cap) {
         const size_t crow = (size_t)D.B * w.lz_cap;
         w.lz_A = c.take<char>(crow * kh_max * D.dh * es);
+        w.lz_A8 = proj8 ? c.take<uint8_t>(crow * kh_max * D.dh) : nullptr;
         w.lz_C = c.take<float>(crow * D.d);
         w.lz_c = c.take<float>((size_t)D.B * D.d);
         w.lz_arow = c.take<int32_t>(crow);
@@ -436,16 +438,34 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         a.O = w.att; a.ldo = (int64_t)kh * dh;
         a.ws = w.attn_ws; a.ws_bytes = w.attn_ws_bytes;
         // Most rows lazy in every head: project only the active rows, the rest of a sample shares one vector
+        // (in FP8 arithmetic the compact rows go through the FP8 GEMM, which wants at least 192 rows per sample)
         const int capA = w.lz_cap ? lazy_cap(D.L, kh, D.U, dh, D.d) : 0;
-        const bool lazy = capA > 0 && capA <= w.lz_cap &&
+        const bool lazy = capA > 0 && capA <= w.lz_cap && (!proj8 || capA >= 256) &&
                           !(((uintptr_t)ly.bo | (uintptr_t)ly.ln2_g | (uintptr_t)ly.ln2_b | (uintptr_t)in) & 15);
-        a.skip_fill = lazy;
+        a.skip_fill = lazy && !(proj8 && oq_out);        // a caller who wants the codes of every row gets the rows filled
         if (int32_t rc = attention_forward(D.dtype, a, st)) return rc;
         if (lazy) {
             const AttnPlan pl = attn_plan(D.dtype, a, a.ws);
             lazy_rows_active(pl.slot, pattern_id, D.B, kh, D.L, capA, w.lz_cnt, w.lz_arow, w.lz_pos, w.lz_n, w.lz_blk, st);
             lazy_att_compact(w.att, a.ldo, pl.slot, pl.stats, ly.head_group, D.Hq, pattern_id, w.lz_arow, w.lz_n, D.B, kh,
                              Hk, D.L, dh, capA, w.lz_A, st);
+            if (proj8) {
+                // the same rows in FP8 arithmetic: codes of the compact rows, FP8 GEMM per sample, and the shared
+                // vector from the codes of the context vector
+                const sf_proj_fp8 &pj = proj8[l];
+                const int64_t Ko = (int64_t)kh * dh;
+                quantize_fp8_bf16(w.lz_A, (int64_t)D.B * capA * Ko, 1.0f / pj.sa, w.lz_A8, st);
+                if (oq_out)
+                    quantize_fp8_bf16(w.att, rows * Ko, 1.0f / pj.sa, oq_out + (size_t)l * rows * w.kh_max * dh, st);
+                GemmArgs o8{};
+                o8.f8 = 1; o8.A = w.lz_A8; o8.lda = Ko; o8.W = pj.WoT8; o8.ldw = Ko; o8.w_pstride = (int64_t)D.d * Ko;
+                o8.pattern_id = pattern_id;
+                o8.B = D.B; o8.L = capA; o8.N = D.d; o8.K = (int)Ko; o8.epi = EPI_ROWMAJOR; o8.act = ACT_NONE;
+                o8.out_scale = pj.sa * pj.so; o8.C = w.lz_C; o8.ldc = D.d; o8.c_f32 = 1;
+                if (int32_t rc = gemm_fp8(o8, st)) return rc;
+                lazy_ctx_proj_q8(pl.stats, ly.head_group, D.Hq, pattern_id, pj.WoT8, (int64_t)D.d * Ko, ly.bo, D.B, kh, Hk,
+                                 dh, D.d, 1.0f / pj.sa, pj.sa * pj.so, w.lz_c, st);
+            } else {
             GemmArgs o{};
             o.A = w.lz_A; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
             // 128-row blocks of the compact buffer, each with its sample's pattern (-1: no rows, skipped)
@@ -455,6 +475,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             if (int32_t rc = gemm(D.dtype, o, st)) return rc;
             lazy_ctx_proj(pl.stats, ly.head_group, D.Hq, pattern_id, ly.WoT, (int64_t)D.d * kh * dh, ly.bo, D.B, kh, Hk, dh,
                           D.d, w.lz_c, st);
+            }
             // x1 = x + projection, and xn = LN2(x1) (bf16, or E4M3 codes for an FFN in FP8 arithmetic), in one pass
             const bool to_y = l == D.nl - 1 && !final_ln;
             if (ffn8) {

@@ -22,4 +22,13 @@ __device__ __forceinline__ uint32_t e4m3_pack4(float t0, float t1, float t2, flo
     return u;
 }
 
+// The value of one E4M3 code (exact in fp32): subnormals m * 2^-9, normals (1 + m/8) * 2^(e-7), 0x7F / 0xFF NaN.
+__device__ __forceinline__ float e4m3_value(uint32_t code)
+{
+    const uint32_t e = (code >> 3) & 0xFu, m = code & 7u;
+    float v = e ? __uint_as_float(((e + 120u) << 23) | (m << 20)) : (float)m * 0x1p-9f;
+    if ((code & 0x7Fu) == 0x7Fu) v = __builtin_nanf("");
+    return (code & 0x80u) ? -v : v;
+}
+
 }  // namespace sf

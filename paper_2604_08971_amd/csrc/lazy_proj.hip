@@ -141,6 +141,39 @@ __global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__
     if (lane == 0) cvec[r] = acc + (bo ? (float)bo[n] : 0.f);
 }
 
+// The same in FP8 arithmetic: the context vector is quantised like every other row of the attention output,
+// c[b, n] = (sum_k dec(E4M3(bf16(ctx_b[k]) * inv_sa)) dec(WoT8[p_b][n, k])) * out_scale + bo[n].
+__global__ __launch_bounds__(256) void ctx_proj_q8_kernel(const float *__restrict__ stats, const int32_t *__restrict__ head_group,
+                                                          int hg_stride, const int32_t *__restrict__ pattern_id,
+                                                          const uint8_t *__restrict__ WoT8, int64_t w_pstride,
+                                                          const __bf16 *__restrict__ bo, int B, int nH, int nG, int dh,
+                                                          int d, float inv_sa, float out_scale, float *__restrict__ cvec)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= (int64_t)B * d) return;
+    const int b = (int)(r / d), n = (int)(r % d);
+    const int p = pattern_id ? pattern_id[b] : 0;
+    const int K = nH * dh;
+    const uint8_t *w = WoT8 + (int64_t)p * w_pstride + (int64_t)n * K;
+    float acc = 0.f;
+    for (int c = lane; c < K / 8; c += 64) {
+        const int h = (c * 8) / dh, e0 = (c * 8) % dh;
+        const bf16x8 x = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
+        const uint2 wv = *reinterpret_cast<const uint2 *>(w + c * 8);
+        const uint32_t q0 = e4m3_pack4((float)x[0] * inv_sa, (float)x[1] * inv_sa, (float)x[2] * inv_sa, (float)x[3] * inv_sa);
+        const uint32_t q1 = e4m3_pack4((float)x[4] * inv_sa, (float)x[5] * inv_sa, (float)x[6] * inv_sa, (float)x[7] * inv_sa);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            acc = fmaf(e4m3_value((q0 >> (8 * t)) & 0xFFu), e4m3_value((wv.x >> (8 * t)) & 0xFFu), acc);
+            acc = fmaf(e4m3_value((q1 >> (8 * t)) & 0xFFu), e4m3_value((wv.y >> (8 * t)) & 0xFFu), acc);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+    if (lane == 0) cvec[r] = acc * out_scale + (bo ? (float)bo[n] : 0.f);
+}
+
 // One wave per token row: x1 = x + (row active ? Cc[b, pos] + bo : c_b), written as fp32, then the LayerNorm of x1
 // (statistics in fp32, biased variance) written as bf16, or (Q8) as E4M3 codes of LN(x1) * q_inv for an FFN in FP8
 // arithmetic.  d % 8 == 0, d <= 512 * NCH.
@@ -281,6 +314,16 @@ void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride,
     const int64_t rows = (int64_t)B * d;
     hipLaunchKernelGGL(ctx_proj_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, stats, head_group, hg_stride,
                        pattern_id, (const __bf16 *)WoT, w_pstride, (const __bf16 *)bo, B, nH, nG, dh, d, cvec);
+}
+
+void lazy_ctx_proj_q8(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
+                      const void *WoT8, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d,
+                      float inv_sa, float out_scale, float *cvec, hipStream_t st)
+{
+    const int64_t rows = (int64_t)B * d;
+    hipLaunchKernelGGL(ctx_proj_q8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, stats, head_group, hg_stride,
+                       pattern_id, (const uint8_t *)WoT8, w_pstride, (const __bf16 *)bo, B, nH, nG, dh, d, inv_sa, out_scale,
+                       cvec);
 }
 
 void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const float *Cc, const void *bo, const float *cvec,

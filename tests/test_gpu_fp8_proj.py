@@ -155,6 +155,12 @@ def _case(kw, with_ffn8):
           ffn_keep=0.8, act=1, dropout="none", final_ln=False), False),
     (dict(dtype="bf16", d=256, dh=64, Hq=4, Hk=2, F=512, seg=(260, 140, 120), extra=2, B=2, nl=2, head_keep=0.5,
           ffn_keep=0.6, dropout="bernoulli:0.3"), True),
+    # long enough for the output projection to run on the active rows only (256 compact rows per sample): codes of
+    # the compact rows, FP8 GEMM on them, the lazy rows' shared vector from the codes of the context vector
+    (dict(dtype="bf16", d=256, dh=32, Hq=8, Hk=2, F=512, seg=(600, 300, 200), extra=0, B=2, nl=2, head_keep=0.5, c=5,
+          ffn_keep=0.6, dropout="bernoulli:0.3"), True),
+    (dict(dtype="bf16", d=256, dh=32, Hq=8, Hk=2, F=512, seg=(600, 300, 200), extra=0, B=2, nl=1, head_keep=0.5, c=5,
+          ffn_keep=0.6, dropout="none", final_ln=False), False),
 ])
 def test_encoder_with_fp8_projections_parity(kw, with_ffn8):
     _say(f"encoder fp8 projections {kw} ffn8={with_ffn8}")
