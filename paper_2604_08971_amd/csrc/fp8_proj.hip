@@ -7,23 +7,34 @@ namespace sf {
 
 namespace {
 
-// 64 tokens x 64 features per block through LDS: reads along the features, writes along the tokens
+// 64 tokens x 64 features per block through LDS, 16 bytes per lane on both sides: 8 features of a token on the way
+// in, 8 tokens of a feature on the way out (ld, col0, ncols, Lp multiples of 8).
 __global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restrict__ src, int64_t ld, int col0, int ncols,
                                                           int L, int Lp, __bf16 *__restrict__ vt)
 {
-    __shared__ uint16_t tile[64][66];
+    __shared__ uint16_t tile[64][66];                          // row stride 33 words: the column reads spread over the banks
     const int b = blockIdx.z, j0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
     const uint16_t *s = reinterpret_cast<const uint16_t *>(src) + (int64_t)b * L * ld + col0;
     uint16_t *dst = reinterpret_cast<uint16_t *>(vt) + (int64_t)b * ncols * Lp;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int jj = ty; jj < 64; jj += 4) {
-        const int j = j0 + jj, c = c0 + tx;
-        tile[jj][tx] = (j < L && c < ncols) ? s[(int64_t)j * ld + c] : (uint16_t)0;
+    const int ch = threadIdx.x & 7, r = threadIdx.x >> 3;      // 8 chunks x 32 rows per pass
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int jj = r + pass * 32, j = j0 + jj, c = c0 + ch * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (j < L && c < ncols) v = *reinterpret_cast<const uint4 *>(s + (int64_t)j * ld + c);
+        uint32_t *t = reinterpret_cast<uint32_t *>(&tile[jj][ch * 8]);
+        t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
     }
     __syncthreads();
-    for (int cc = ty; cc < 64; cc += 4) {
-        const int c = c0 + cc, j = j0 + tx;
-        if (c < ncols && j < Lp) dst[(int64_t)c * Lp + j] = tile[tx][cc];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int cc = r + pass * 32, c = c0 + cc, j = j0 + ch * 8;
+        if (c >= ncols || j >= Lp) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            w[k] = (uint32_t)tile[ch * 8 + 2 * k][cc] | ((uint32_t)tile[ch * 8 + 2 * k + 1][cc] << 16);
+        *reinterpret_cast<uint4 *>(dst + (int64_t)c * Lp + j) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
