@@ -199,3 +199,43 @@ def test_encoder_fp8_projections_rejects_what_it_cannot_run():
                                       sf._ptr(dm.masks["group_idx"]), sf._ptr(dm.masks["n_groups"]),
                                       sf.C.byref(cps[0].struct), None)
     assert rc != 0
+
+
+def test_encoder_fp8_under_hip_graph_replay():
+    """The encoder with projections and FFNs in FP8 arithmetic (active-row output projection included) recorded into
+    a HIP graph: every replay, with eager work and synchronisations in between, reproduces the eager result bit for
+    bit."""
+    _say("encoder fp8 graph replay")
+    kw = dict(dtype="bf16", d=256, dh=32, Hq=8, Hk=2, F=512, seg=(600, 300, 200), extra=0, B=2, nl=2, head_keep=0.5,
+              c=5, ffn_keep=0.6, dropout="bernoulli:0.3")
+    wl, dm, masks, p8, cps, f8, cfs = _build(kw, True)
+    ws = sf.workspace(sf.encoder_fp8_workspace_bytes(dm.desc, dm.layers), dm.x.device)
+    out = torch.empty_like(dm.x)
+
+    def run():
+        sf.encoder_forward_fp8(dm.desc, dm.layers, dm.x, ffn8=cfs, proj8=cps, pattern_id=dm.pattern_id,
+                               key_valid=dm.key_valid, final_ln=dm.final_ln, out=out, ws=ws)
+
+    run()
+    torch.cuda.synchronize()
+    y_eager = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        out.fill_(float("nan"))
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, y_eager), f"replay {rep} differs from the eager result"
+        run()
+        torch.cuda.synchronize()
+        assert torch.equal(out, y_eager)
