@@ -35,7 +35,7 @@ def _cast_e4m3(a):
 
 
 def _build(kw, with_ffn8):
-    wl = W.make_workload(W.small_spec(**kw))
+    wl = W.make_workload(kw if isinstance(kw, W.Spec) else W.small_spec(**kw))
     s = wl.spec
     dm = DeviceModel(wl).build_plan()
     masks = oracle_masks(wl)
@@ -77,52 +77,59 @@ def _compacted_ok(wl, masks, p8, cps):
             assert np.array_equal(WoT8[p], pj["Wo8"][rows(hi)].T), (l, p)
 
 
-def _case(kw, with_ffn8):
+def _case(kw, with_ffn8, samples=None):
+    """samples: the samples the oracle recomputes (all by default); the device always runs the whole batch"""
     wl, dm, masks, p8, cps, f8, cfs = _build(kw, with_ffn8)
     s = wl.spec
     _compacted_ok(wl, masks, p8, cps)
     packs = dense_packs(wl, masks)
     U = sf.num_active(dm.desc)
-    B, L, d, F, nl, dh = wl.x.shape[0], s.L, s.d, s.F, s.n_layers, s.dh
+    L, d, F, nl, dh = s.L, s.d, s.F, s.n_layers, s.dh
+    Bd = wl.x.shape[0]
+    samples = list(range(Bd)) if samples is None else samples
+    B = len(samples)
+    x_s, pid_s = wl.x[samples], wl.pattern_id[samples]
+    kv_s = None if wl.key_valid is None else wl.key_valid[samples]
     Y, sel, codes = sf.encoder_forward_fp8(dm.desc, dm.layers, dm.x, ffn8=cfs, proj8=cps, pattern_id=dm.pattern_id,
                                            key_valid=dm.key_valid, final_ln=dm.final_ln, want_sel=True, want_codes=True)
     torch.cuda.synchronize()
     Y, sel = to_host(Y), to_host(sel)
     assert np.isfinite(Y).all()
-    aq = to_host(codes["aq"]).reshape(nl, B, L, d)
+    Y, sel = Y[samples], sel[:, samples]
+    aq = to_host(codes["aq"]).reshape(nl, Bd, L, d)[:, samples]
     # the device's decisions in the dense head / channel layout of each sample's pattern
     oq = np.zeros((nl, B, L, s.Hq * dh), np.uint8)
     sel_dense = np.full((nl, B, s.Hq, U), -1, np.int32)
     hq = np.zeros((nl, B, L, F), np.uint8)
     for l in range(nl):
         kh, kf = int(wl.k_head[l]), int(wl.k_ffn[l])
-        o = to_host(codes["oq"][l]).reshape(B, L, kh, dh)
+        o = to_host(codes["oq"][l]).reshape(Bd, L, kh, dh)[samples]
         for b in range(B):
-            p = int(wl.pattern_id[b])
+            p = int(pid_s[b])
             hi = masks["head_idx"][l, p, :kh]
             oq[l, b].reshape(L, s.Hq, dh)[:, hi] = o[b]
             sel_dense[l, b, hi] = sel[l, b, :kh]
             if with_ffn8:
-                h = to_host(codes["hq"][l]).reshape(B, L, -1)
+                h = to_host(codes["hq"][l]).reshape(Bd, L, -1)[samples]
                 hq[l, b][:, masks["ffn_idx"][l, p, :kf]] = h[b, :, :kf]
     common = dict(act=s.act, final_ln=wl.final_ln, bf16=True, proj8=p8, forced_sel=sel_dense)
     forced = dict(aq_forced=aq, oq_forced=oq)
     if with_ffn8:
         common["ffn8"] = f8
-        forced.update(xq_forced=to_host(codes["xq"]).reshape(nl, B, L, d), hq_forced=hq)
+        forced.update(xq_forced=to_host(codes["xq"]).reshape(nl, Bd, L, d)[:, samples], hq_forced=hq)
     # the oracle on all of the device's decisions: the output reference, and the scores its choices are judged on
-    y_ref, _, score_f = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, want_score=True, **forced,
+    y_ref, _, score_f = orc.encoder_forward(x_s, packs, U, pid_s, kv_s, want_score=True, **forced,
                                             **common)
     e = err_metric(Y, y_ref)
     picks_diff = picks_tot = 0
     if 0 < U < L:
         for l in range(nl):
             for b in range(B):
-                for h in masks["head_idx"][l, int(wl.pattern_id[b]), :int(wl.k_head[l])]:
+                for h in masks["head_idx"][l, int(pid_s[b]), :int(wl.k_head[l])]:
                     m = score_f[l, b, h]
                     got = sel_dense[l, b, h]
                     ref_sel = np.sort(np.lexsort((np.arange(L), -m.astype(np.float32)))[:np.sum(got >= 0)])
-                    ok, _ = selection_report(m, got, ref_sel, None if wl.key_valid is None else wl.key_valid[b], 2e-2)
+                    ok, _ = selection_report(m, got, ref_sel, None if kv_s is None else kv_s[b], 2e-2)
                     assert ok, (l, b, h)
                     picks_diff += len(np.setdiff1d(got[got >= 0], ref_sel))
                     picks_tot += len(ref_sel)
@@ -133,9 +140,9 @@ def _case(kw, with_ffn8):
         kw_l = dict(want_codes=True, **forced, **common)
         if with_ffn8:
             kw_l.update(n_forced_x=l, n_forced_h=l)
-        r = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, n_forced_a=l, n_forced_o=l, **kw_l)
+        r = orc.encoder_forward(x_s, packs, U, pid_s, kv_s, n_forced_a=l, n_forced_o=l, **kw_l)
         aq_own[l] = r[5][l]
-        r = orc.encoder_forward(wl.x, packs, U, wl.pattern_id, wl.key_valid, n_forced_a=l + 1, n_forced_o=l, **kw_l)
+        r = orc.encoder_forward(x_s, packs, U, pid_s, kv_s, n_forced_a=l + 1, n_forced_o=l, **kw_l)
         oq_own[l] = r[6][l]
     va_d, va_o = DEC[aq] * SX1, DEC[aq_own] * SX1
     assert (np.abs(va_d - va_o) <= 2.0 ** -3 * np.abs(va_o) + 2e-2 * np.maximum(1.0, np.abs(va_o))).all()
@@ -165,6 +172,13 @@ def _case(kw, with_ffn8):
 def test_encoder_with_fp8_projections_parity(kw, with_ffn8):
     _say(f"encoder fp8 projections {kw} ffn8={with_ffn8}")
     _case(kw, with_ffn8)
+
+
+def test_encoder_fp8_C5_full_size_sampled():
+    """The launch bench.py times for this path (C5, projections and FFN in FP8 arithmetic, active-row output
+    projection); the oracle recomputes one whole sample, which is independent of the others."""
+    _say("encoder fp8 projections + ffn, C5 (full batch on the GPU, 1 sample through the oracle)")
+    _case(W.CONFIGS["C5"], True, samples=[11])
 
 
 def test_encoder_fp8_projections_rejects_what_it_cannot_run():
