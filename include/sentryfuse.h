@@ -283,12 +283,15 @@ int32_t sf_encoder_forward_fp8ffn(const sf_desc *desc, const sf_compact_layer *l
  * codes (sf_dense_layer_fp8 with sq == sk == sv) into
  *     Wqkv8 [P, (k_head + 2*Hk)*dh, d]      kept Q heads, K rows, V rows of the
  *                                           used groups (zero rows for unused slots)
- *     WoT8  [P, d, k_head*dh]
+ *     WoT8  [P, d, Kp]                      Kp = sf_proj_fp8_padded(k_head, dh) =
+ *                                           k_head*dh rounded up to a multiple of 128
+ *                                           (zero columns: the FP8 GEMM contracts over
+ *                                           multiples of 128)
  * both DEVICE buffers of the caller, uint8, 16-byte aligned; biases bqkv, bo
  * and the LayerNorm vectors are those of the sf_compact_layer of the layer.
  * s_qkv, so must equal the dense scales; sx1, sa are chosen by the caller
- * (static activation scales).  Limits: bf16 model, d and k_head*dh multiples
- * of 128, d >= 256, (k_head + 2*Hk)*dh >= 192, L >= 192; anything else returns
+ * (static activation scales).  Limits: bf16 model, d a multiple of 128 in
+ * [256, 4096], (k_head + 2*Hk)*dh >= 192, L >= 192; anything else returns
  * SF_ERR_SHAPE / SF_ERR_UNSUPPORTED before a kernel is launched.
  */
 typedef struct sf_proj_fp8 {
@@ -297,6 +300,7 @@ typedef struct sf_proj_fp8 {
     void *Wqkv8, *WoT8;
     float s_qkv, so, sx1, sa;
 } sf_proj_fp8;
+int32_t sf_proj_fp8_padded(int32_t k_head, int32_t d_head);
 int32_t sf_compact_proj_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense_host,
                             const int32_t *head_idx, const int32_t *group_idx,
                             const int32_t *n_groups, const sf_proj_fp8 *proj_host, void *stream);
@@ -307,8 +311,8 @@ int32_t sf_compact_proj_fp8(const sf_desc *desc, int32_t layer, const sf_dense_l
  * layers_host[l].k_head.  The workspace is sf_encoder_fp8_workspace_bytes
  * (larger than sf_encoder_workspace_bytes: token-major V and the codes of the
  * attention output).  aq_out [n_layers, B*L, d] and oq_out (layer l's codes, a
- * [B*L, k_head_l*dh] array over the KEPT heads in rank order, at
- * oq_out + l*B*L*max_l k_head_l*dh) receive the codes when not NULL (16-byte
+ * [B*L, Kp_l] array over the KEPT heads in rank order followed by zero
+ * padding, at oq_out + l*B*L*max_l Kp_l) receive the codes when not NULL (16-byte
  * aligned); xq_out, hq_out as in sf_encoder_forward_fp8ffn. */
 size_t sf_encoder_fp8_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers_host);
 int32_t sf_encoder_forward_fp8(const sf_desc *desc, const sf_compact_layer *layers_host,

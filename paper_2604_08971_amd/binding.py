@@ -30,7 +30,7 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
            "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
            "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_fp8_workspace_bytes",
-           "sf_encoder_forward_fp8"]
+           "sf_encoder_forward_fp8", "sf_proj_fp8_padded"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -116,7 +116,7 @@ def lib():
                   "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
                   "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
-                  "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_forward_fp8"):
+                  "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_forward_fp8", "sf_proj_fp8_padded"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
@@ -144,6 +144,7 @@ def lib():
             C.c_void_p] * 13 + [C.c_size_t, C.c_void_p]
         L.sf_compact_proj_fp8.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayerFp8), C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.POINTER(SfProjFp8), C.c_void_p]
+        L.sf_proj_fp8_padded.argtypes = [C.c_int32, C.c_int32]
         L.sf_encoder_fp8_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer)]
         L.sf_encoder_forward_fp8.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.POINTER(SfFfnFp8),
                                              C.POINTER(SfProjFp8)] + [C.c_void_p] * 15 + [C.c_size_t, C.c_void_p]
@@ -739,8 +740,9 @@ class CompactProjFp8:
     def __init__(self, desc: SfDesc, dev, k_head: int, s_qkv: float, so: float, sx1: float, sa: float):
         P, d, dh, Hk = desc.P, desc.d_model, desc.dh, desc.Hk
         self.k_head = int(k_head)
+        self.Kp = int(lib().sf_proj_fp8_padded(self.k_head, dh))
         self.Wqkv8 = torch.empty((P, (self.k_head + 2 * Hk) * dh, d), dtype=torch.uint8, device=dev)
-        self.WoT8 = torch.empty((P, d, self.k_head * dh), dtype=torch.uint8, device=dev)
+        self.WoT8 = torch.empty((P, d, self.Kp), dtype=torch.uint8, device=dev)
         self.struct = SfProjFp8(self.k_head, 0, _ptr(self.Wqkv8), _ptr(self.WoT8), float(s_qkv), float(so),
                                 float(sx1), float(sa))
 
@@ -773,7 +775,8 @@ def encoder_forward_fp8(desc: SfDesc, layers: List[CompactLayer], X: torch.Tenso
                         out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
     """sf_encoder_forward with the FFNs (ffn8) and / or the attention projections (proj8) in FP8 arithmetic.
     Returns (Y, sel | None) and, with want_codes, a dict of the codes: xq [nl, B*L, d], hq (list of [B*L, Fp8_l]),
-    aq [nl, B*L, d], oq (list of [B*L, k_head_l*dh]); entries of a part that is not in FP8 are None."""
+    aq [nl, B*L, d], oq (list of [B*L, Kp_l], kept heads in rank order then zero padding); entries of a part that
+    is not in FP8 are None."""
     assert X.is_contiguous()
     B, L, d = X.shape
     nl = desc.n_layers
@@ -794,7 +797,8 @@ def encoder_forward_fp8(desc: SfDesc, layers: List[CompactLayer], X: torch.Tenso
         hq = torch.zeros((nl, B * L * F8max), dtype=torch.uint8, device=dev)
     if want_codes and proj8 is not None:
         aq = torch.empty((nl, B * L, d), dtype=torch.uint8, device=dev)
-        oq = torch.zeros((nl, B * L * khmax * desc.dh), dtype=torch.uint8, device=dev)
+        Kpmax = max(p.Kp for p in proj8)
+        oq = torch.zeros((nl, B * L * Kpmax), dtype=torch.uint8, device=dev)
     fg = None if final_ln is None else final_ln["g"]
     fb = None if final_ln is None else final_ln["b"]
     rc = lib().sf_encoder_forward_fp8(C.byref(desc), arr, farr, parr, _ptr(X), _ptr(pattern_id), _ptr(key_valid),
@@ -808,6 +812,5 @@ def encoder_forward_fp8(desc: SfDesc, layers: List[CompactLayer], X: torch.Tenso
     if hq is not None:
         codes["hq"] = [hq[l, :B * L * f.Fp8].view(B * L, f.Fp8) for l, f in enumerate(ffn8)]
     if oq is not None:
-        codes["oq"] = [oq[l, :B * L * p.k_head * desc.dh].view(B * L, p.k_head * desc.dh)
-                       for l, p in enumerate(proj8)]
+        codes["oq"] = [oq[l, :B * L * p.Kp].view(B * L, p.Kp) for l, p in enumerate(proj8)]
     return Y, sel, codes

@@ -179,12 +179,13 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     }
     w.attn_ws_bytes = amax;
     w.attn_ws = c.take<char>(amax);
-    w.oq = proj8 ? c.take<uint8_t>(rows * (size_t)kh_max * D.dh) : nullptr;
+    const size_t Kp_max = align_up((size_t)kh_max * D.dh, 128);      // code rows are padded to the FP8 GEMM's K step
+    w.oq = proj8 ? c.take<uint8_t>(rows * Kp_max) : nullptr;
     w.lz_cap = bf ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
     if (w.lz_cap) {
         const size_t crow = (size_t)D.B * w.lz_cap;
         w.lz_A = c.take<char>(crow * kh_max * D.dh * es);
-        w.lz_A8 = proj8 ? c.take<uint8_t>(crow * kh_max * D.dh) : nullptr;
+        w.lz_A8 = proj8 ? c.take<uint8_t>(crow * Kp_max) : nullptr;
         w.lz_C = c.take<float>(crow * D.d);
         w.lz_c = c.take<float>((size_t)D.B * D.d);
         w.lz_arow = c.take<int32_t>(crow);
@@ -453,17 +454,19 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
                 // the same rows in FP8 arithmetic: codes of the compact rows, FP8 GEMM per sample, and the shared
                 // vector from the codes of the context vector
                 const sf_proj_fp8 &pj = proj8[l];
-                const int64_t Ko = (int64_t)kh * dh;
-                quantize_fp8_bf16(w.lz_A, (int64_t)D.B * capA * Ko, 1.0f / pj.sa, w.lz_A8, st);
+                const int Kh = kh * dh;
+                const int64_t Ko = (int64_t)align_up((size_t)Kh, 128);
+                quantize_rows_fp8(w.lz_A, Kh, (int64_t)D.B * capA, Kh, (int)Ko, 1.0f / pj.sa, w.lz_A8, st);
                 if (oq_out)
-                    quantize_fp8_bf16(w.att, rows * Ko, 1.0f / pj.sa, oq_out + (size_t)l * rows * w.kh_max * dh, st);
+                    quantize_rows_fp8(w.att, Kh, rows, Kh, (int)Ko, 1.0f / pj.sa,
+                                      oq_out + (size_t)l * rows * align_up((size_t)w.kh_max * dh, 128), st);
                 GemmArgs o8{};
                 o8.f8 = 1; o8.A = w.lz_A8; o8.lda = Ko; o8.W = pj.WoT8; o8.ldw = Ko; o8.w_pstride = (int64_t)D.d * Ko;
                 o8.pattern_id = pattern_id;
                 o8.B = D.B; o8.L = capA; o8.N = D.d; o8.K = (int)Ko; o8.epi = EPI_ROWMAJOR; o8.act = ACT_NONE;
                 o8.out_scale = pj.sa * pj.so; o8.C = w.lz_C; o8.ldc = D.d; o8.c_f32 = 1;
                 if (int32_t rc = gemm_fp8(o8, st)) return rc;
-                lazy_ctx_proj_q8(pl.stats, ly.head_group, D.Hq, pattern_id, pj.WoT8, (int64_t)D.d * Ko, ly.bo, D.B, kh, Hk,
+                lazy_ctx_proj_q8(pl.stats, ly.head_group, D.Hq, pattern_id, pj.WoT8, (int64_t)D.d * Ko, (int)Ko, ly.bo, D.B, kh, Hk,
                                  dh, D.d, 1.0f / pj.sa, pj.sa * pj.so, w.lz_c, st);
             } else {
             GemmArgs o{};
@@ -501,9 +504,10 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         // x1 = x + att Wo' + bo   (only the kept heads' rows of Wo exist)
         if (proj8) {
             const sf_proj_fp8 &pj = proj8[l];
-            const int64_t Ko = (int64_t)kh * dh;
-            uint8_t *oq = oq_out ? oq_out + (size_t)l * rows * w.kh_max * dh : w.oq;
-            quantize_fp8_bf16(w.att, rows * Ko, 1.0f / pj.sa, oq, st);
+            const int Kh = kh * dh;
+            const int64_t Ko = (int64_t)align_up((size_t)Kh, 128);
+            uint8_t *oq = oq_out ? oq_out + (size_t)l * rows * align_up((size_t)w.kh_max * dh, 128) : w.oq;
+            quantize_rows_fp8(w.att, Kh, rows, Kh, (int)Ko, 1.0f / pj.sa, oq, st);
             GemmArgs o8{};
             o8.f8 = 1; o8.A = oq; o8.lda = Ko; o8.W = pj.WoT8; o8.ldw = Ko; o8.w_pstride = (int64_t)D.d * Ko;
             o8.bias = ly.bo; o8.bias_pstride = 0; o8.pattern_id = pattern_id;

@@ -63,9 +63,10 @@ void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const f
 void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
                    const void *WoT, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d, float *cvec,
                    hipStream_t st);
-// FP8 arithmetic: the context vector quantised with 1/inv_sa, weights as E4M3 codes [P][d, nH*dh] (8-byte aligned rows)
+// FP8 arithmetic: the context vector quantised with 1/inv_sa, weights as E4M3 codes [P][d, ldw], ldw >= nH*dh
+// (8-byte aligned rows)
 void lazy_ctx_proj_q8(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
-                      const void *WoT8, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d,
+                      const void *WoT8, int64_t w_pstride, int ldw, const void *bo, int B, int nH, int nG, int dh, int d,
                       float inv_sa, float out_scale, float *cvec, hipStream_t st);
 void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const float *Cc, const void *bo, const float *cvec,
                      int B, int L, int capA, const void *gamma, const void *beta, float eps, int d, float *x1, void *xn,

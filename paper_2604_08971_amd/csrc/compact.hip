@@ -601,7 +601,8 @@ extern "C" int32_t sf_compact_ffn_fp8(const sf_desc *desc, int32_t layer, const 
 
 // Attention projection weights kept as E4M3 codes for the FP8 arithmetic path: Wqkv8 [P, (k_head + 2 Hk) dh, d]
 // (kept Q heads, then the K and the V rows of the used groups, zero rows for unused group slots) and
-// WoT8 [P, d, k_head dh], the same gathers as for the 16-bit weights on bytes.
+// WoT8 [P, d, Kp] with Kp = k_head dh rounded up to 128 (zero columns: the FP8 GEMM contracts over multiples of 128),
+// the same gathers as for the 16-bit weights on bytes.
 extern "C" int32_t sf_compact_proj_fp8(const sf_desc *desc, int32_t layer, const sf_dense_layer_fp8 *dense,
                                        const int32_t *head_idx, const int32_t *group_idx, const int32_t *n_groups,
                                        const sf_proj_fp8 *pj, void *stream)
@@ -638,8 +639,9 @@ extern "C" int32_t sf_compact_proj_fp8(const sf_desc *desc, int32_t layer, const
     wr.r[wr.n++] = region(dense->Wv, (size_t)(kh + D.Hk) * dh, gi, D.Hk, 0, ng, D.Hk * dh);
     if (d % 2) return fail(SF_ERR_SHAPE, "compact_proj_fp8: d_model must be even");
     gather_rows(st, wr, (size_t)d, P);
-    dim3 grid(ceil_div(kh * dh, 32), ceil_div(d, 32), P);
+    const int Kp = (int)align_up((size_t)kh * dh, 128);
+    dim3 grid(ceil_div(Kp, 32), ceil_div(d, 32), P);
     hipLaunchKernelGGL(gather_transpose_kernel<uint8_t>, grid, dim3(256), 0, st, (const uint8_t *)dense->Wo,
-                       (uint8_t *)pj->WoT8, hi, D.Hq, dh, kh, kh * dh, d, (size_t)d * kh * dh);
+                       (uint8_t *)pj->WoT8, hi, D.Hq, dh, kh, Kp, d, (size_t)d * Kp);
     return check_launch("compact_proj_fp8");
 }

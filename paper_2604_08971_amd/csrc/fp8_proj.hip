@@ -1,6 +1,7 @@
 // FP8 arithmetic for the attention projections (Sec. 6, "Compatibility with quantization": the FP8 models; which
 // contractions run in FP8 is this build's reading).  The contractions are gemm_fp8() launches issued by the encoder;
 // this file holds the argument checks and the V transposition that the bf16 GEMM does in its epilogue.
+#include "fp8.hpp"
 #include "gemm.hpp"
 
 namespace sf {
@@ -38,7 +39,34 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restri
     }
 }
 
+// codes[r, c] = E4M3(x[r, c] * inv_scale) for c < K, 0 for K <= c < Kp: rows of a bf16 matrix into code rows padded to
+// the FP8 GEMM's K granularity.  8 elements per thread (K, Kp, ld multiples of 8).
+__global__ __launch_bounds__(256) void quantize_rows_fp8_kernel(const __bf16 *__restrict__ x, int64_t ld, int64_t rows, int K,
+                                                                int Kp, float inv_scale, uint8_t *__restrict__ codes)
+{
+    const int per_row = Kp / 8;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= rows * per_row) return;
+    const int64_t r = t / per_row;
+    const int c = (int)(t % per_row) * 8;
+    uint2 o = make_uint2(0, 0);
+    if (c < K) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8 *>(x + r * ld + c);
+        o.x = e4m3_pack4((float)v[0] * inv_scale, (float)v[1] * inv_scale, (float)v[2] * inv_scale, (float)v[3] * inv_scale);
+        o.y = e4m3_pack4((float)v[4] * inv_scale, (float)v[5] * inv_scale, (float)v[6] * inv_scale, (float)v[7] * inv_scale);
+    }
+    *reinterpret_cast<uint2 *>(codes + r * Kp + c) = o;
+}
+
 }  // namespace
+
+void quantize_rows_fp8(const void *x, int64_t ld, int64_t rows, int K, int Kp, float inv_scale, uint8_t *codes, hipStream_t st)
+{
+    const int64_t n = rows * (Kp / 8);
+    if (n == 0) return;
+    hipLaunchKernelGGL(quantize_rows_fp8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const __bf16 *)x, ld,
+                       rows, K, Kp, inv_scale, codes);
+}
 
 void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st)
 {
@@ -60,10 +88,16 @@ int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int
         return fail(SF_ERR_INVALID_ARG, "%s: the four scales must be positive", who);
     if (D.d % 128 || D.d < 256 || D.d > 4096)
         return fail(SF_ERR_SHAPE, "%s: d_model must be a multiple of 128 in [256, 4096]", who);
-    if ((k_head * D.dh) % 128) return fail(SF_ERR_SHAPE, "%s: k_head * dh must be a multiple of 128", who);
     if ((k_head + 2 * D.Hk) * D.dh < 192) return fail(SF_ERR_UNSUPPORTED, "%s: at least 192 Q/K/V features required", who);
     if (D.L < 192) return fail(SF_ERR_UNSUPPORTED, "%s: at least 192 tokens per sample required", who);
     return SF_OK;
 }
 
 }  // namespace sf
+
+using namespace sf;
+
+extern "C" int32_t sf_proj_fp8_padded(int32_t k_head, int32_t d_head)
+{
+    return k_head < 1 || d_head < 1 ? 0 : (int32_t)align_up((size_t)k_head * d_head, 128);
+}

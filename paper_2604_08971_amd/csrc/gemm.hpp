@@ -67,6 +67,8 @@ void quantize_fp8_bf16(const void *x, int64_t n, float inv_scale, uint8_t *codes
 int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int k_head);
 // vt[b, c, j] = src[b, j, col0 + c] for c < ncols, j < L (zeros for L <= j < Lp): the V columns of a token-major
 // bf16 buffer into the key-contiguous layout the attention kernels read.
+// codes[r, 0:K] = E4M3(x[r, 0:K] * inv_scale), codes[r, K:Kp] = 0 (x bf16 with row stride ld; K, Kp, ld % 8 == 0)
+void quantize_rows_fp8(const void *x, int64_t ld, int64_t rows, int K, int Kp, float inv_scale, uint8_t *codes, hipStream_t st);
 void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st);
 
 // True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).

@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__
 // c[b, n] = (sum_k dec(E4M3(bf16(ctx_b[k]) * inv_sa)) dec(WoT8[p_b][n, k])) * out_scale + bo[n].
 __global__ __launch_bounds__(256) void ctx_proj_q8_kernel(const float *__restrict__ stats, const int32_t *__restrict__ head_group,
                                                           int hg_stride, const int32_t *__restrict__ pattern_id,
-                                                          const uint8_t *__restrict__ WoT8, int64_t w_pstride,
+                                                          const uint8_t *__restrict__ WoT8, int64_t w_pstride, int ldw,
                                                           const __bf16 *__restrict__ bo, int B, int nH, int nG, int dh,
                                                           int d, float inv_sa, float out_scale, float *__restrict__ cvec)
 {
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) void ctx_proj_q8_kernel(const float *__restric
     const int b = (int)(r / d), n = (int)(r % d);
     const int p = pattern_id ? pattern_id[b] : 0;
     const int K = nH * dh;
-    const uint8_t *w = WoT8 + (int64_t)p * w_pstride + (int64_t)n * K;
+    const uint8_t *w = WoT8 + (int64_t)p * w_pstride + (int64_t)n * ldw;
     float acc = 0.f;
     for (int c = lane; c < K / 8; c += 64) {
         const int h = (c * 8) / dh, e0 = (c * 8) % dh;
@@ -317,12 +317,12 @@ void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride,
 }
 
 void lazy_ctx_proj_q8(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
-                      const void *WoT8, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d,
+                      const void *WoT8, int64_t w_pstride, int ldw, const void *bo, int B, int nH, int nG, int dh, int d,
                       float inv_sa, float out_scale, float *cvec, hipStream_t st)
 {
     const int64_t rows = (int64_t)B * d;
     hipLaunchKernelGGL(ctx_proj_q8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, stats, head_group, hg_stride,
-                       pattern_id, (const uint8_t *)WoT8, w_pstride, (const __bf16 *)bo, B, nH, nG, dh, d, inv_sa, out_scale,
+                       pattern_id, (const uint8_t *)WoT8, w_pstride, ldw, (const __bf16 *)bo, B, nH, nG, dh, d, inv_sa, out_scale,
                        cvec);
 }
 

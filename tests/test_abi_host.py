@@ -170,8 +170,11 @@ def test_null_and_range_errors_before_any_launch():
     assert L.sf_encoder_forward_fp8(C.byref(d), C.byref(cl8f), None, C.byref(pj), *pargs) in (-2, -3)   # fp32 descriptor
     pj.k_head = 3
     assert L.sf_encoder_forward_fp8(C.byref(dp), C.byref(cl8f), None, C.byref(pj), *pargs) == -1  # k_head mismatch
-    pj.k_head, cl8f.k_head = 3, 3
-    assert L.sf_encoder_forward_fp8(C.byref(dp), C.byref(cl8f), None, C.byref(pj), *pargs) == -2  # 3*32 not a multiple of 128
+    assert L.sf_proj_fp8_padded(3, 32) == 128 and L.sf_proj_fp8_padded(8, 64) == 512 and L.sf_proj_fp8_padded(5, 64) == 384
+    assert L.sf_proj_fp8_padded(0, 64) == 0
+    dnarrow = sf.make_desc(1, 256, 256, 2, 1, 32, 512, dtype=sf.SF_BF16)
+    pj.k_head, cl8f.k_head = 1, 1
+    assert L.sf_encoder_forward_fp8(C.byref(dnarrow), C.byref(cl8f), None, C.byref(pj), *pargs) == -3  # 96 Q/K/V features
     pj.k_head, cl8f.k_head, pj.sa = 4, 4, 0.0
     assert L.sf_encoder_forward_fp8(C.byref(dp), C.byref(cl8f), None, C.byref(pj), *pargs) == -1
     pj.sa = 1.0

@@ -74,7 +74,8 @@ def _compacted_ok(wl, masks, p8, cps):
             want[kh * s.dh:kh * s.dh + ng * s.dh] = pj["Wk8"][rows(gi)]
             want[(kh + s.Hk) * s.dh:(kh + s.Hk) * s.dh + ng * s.dh] = pj["Wv8"][rows(gi)]
             assert np.array_equal(Wqkv8[p], want), (l, p)
-            assert np.array_equal(WoT8[p], pj["Wo8"][rows(hi)].T), (l, p)
+            assert np.array_equal(WoT8[p][:, :kh * s.dh], pj["Wo8"][rows(hi)].T), (l, p)
+            assert not WoT8[p][:, kh * s.dh:].any()
 
 
 def _case(kw, with_ffn8, samples=None):
@@ -103,7 +104,9 @@ def _case(kw, with_ffn8, samples=None):
     hq = np.zeros((nl, B, L, F), np.uint8)
     for l in range(nl):
         kh, kf = int(wl.k_head[l]), int(wl.k_ffn[l])
-        o = to_host(codes["oq"][l]).reshape(Bd, L, kh, dh)[samples]
+        o = to_host(codes["oq"][l]).reshape(Bd, L, -1)[samples]
+        assert not o[:, :, kh * dh:].any()                              # padding columns: code 0
+        o = o[:, :, :kh * dh].reshape(B, L, kh, dh)
         for b in range(B):
             p = int(pid_s[b])
             hi = masks["head_idx"][l, p, :kh]
@@ -162,6 +165,11 @@ def _case(kw, with_ffn8, samples=None):
           ffn_keep=0.8, act=1, dropout="none", final_ln=False), False),
     (dict(dtype="bf16", d=256, dh=64, Hq=4, Hk=2, F=512, seg=(260, 140, 120), extra=2, B=2, nl=2, head_keep=0.5,
           ffn_keep=0.6, dropout="bernoulli:0.3"), True),
+    # 3 kept heads of 64: 192 attention-output features, code rows padded to 256
+    (dict(dtype="bf16", d=256, dh=64, Hq=4, Hk=2, F=512, seg=(100, 60, 70), extra=2, B=3, nl=2, head_keep=0.75,
+          ffn_keep=0.6, dropout="bernoulli:0.3"), False),
+    (dict(dtype="bf16", d=256, dh=32, Hq=8, Hk=2, F=512, seg=(600, 300, 200), extra=0, B=2, nl=1, head_keep=0.6, c=4,
+          ffn_keep=0.6, dropout="upto:1", final_ln=False), True),
     # long enough for the output projection to run on the active rows only (256 compact rows per sample): codes of
     # the compact rows, FP8 GEMM on them, the lazy rows' shared vector from the codes of the context vector
     (dict(dtype="bf16", d=256, dh=32, Hq=8, Hk=2, F=512, seg=(600, 300, 200), extra=0, B=2, nl=2, head_keep=0.5, c=5,
