@@ -384,7 +384,8 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             // the same in FP8 arithmetic: codes of LN1(x), one GEMM for Q, K, V (token-major), V transposed after it
             const sf_proj_fp8 &pj = proj8[l];
             if (((uintptr_t)ly.ln1_g | (uintptr_t)ly.ln1_b | (uintptr_t)in) & 15)
-                return fail(SF_ERR_INVALID_ARG, "encoder(fp8 projections): 16-byte aligned input and LayerNorm vectors required");
+                return fail(SF_ERR_INVALID_ARG,
+                            "encoder(fp8 projections): 16-byte aligned input and LayerNorm vectors required");
             uint8_t *aq = aq_out ? aq_out + (size_t)l * rows * D.d : static_cast<uint8_t *>(w.xn);
             layernorm_q8(in, in_f32, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, 1.0f / pj.sx1, aq, st);
             GemmArgs q8{};
@@ -395,28 +396,28 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             if (int32_t rc = gemm_fp8(q8, st)) return rc;
             transpose_v(w.qkv, Nqkv, Nqk, Hk * dh, D.B, D.L, w.Lp, w.vt, st);
         } else {
-        layernorm(D.dtype, in_f32, in, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, w.xn, st);
-        GemmArgs g{};
-        g.A = w.xn; g.lda = D.d; g.W = ly.Wqkv; g.ldw = D.d; g.w_pstride = (int64_t)Nqkv * D.d;
-        g.bias = ly.bqkv; g.bias_pstride = Nqkv; g.pattern_id = pattern_id;
-        g.B = D.B; g.L = D.L; g.K = D.d; g.act = ACT_NONE; g.epi = EPI_ROWMAJOR;
-        g.C = w.qkv; g.ldc = ldq; g.n0 = 0; g.N = bf ? Nqk : Nqkv;
-        if (bf) {
-            // one launch for Q, K and V when the large-tile kernel takes it (V is the transposed column range:
-            // the normalised input is read once); otherwise Q/K and V separately
-            GemmArgs q3 = g;
-            q3.N = Nqkv; q3.VT = w.vt; q3.vt_from = Nqk; q3.vt_b = (int64_t)Hk * dh * w.Lp; q3.vt_n = w.Lp;
-            if (gemm_takes_vt_split(D.dtype, q3)) {
-                if (int32_t rc = gemm(D.dtype, q3, st)) return rc;
+            layernorm(D.dtype, in_f32, in, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, w.xn, st);
+            GemmArgs g{};
+            g.A = w.xn; g.lda = D.d; g.W = ly.Wqkv; g.ldw = D.d; g.w_pstride = (int64_t)Nqkv * D.d;
+            g.bias = ly.bqkv; g.bias_pstride = Nqkv; g.pattern_id = pattern_id;
+            g.B = D.B; g.L = D.L; g.K = D.d; g.act = ACT_NONE; g.epi = EPI_ROWMAJOR;
+            g.C = w.qkv; g.ldc = ldq; g.n0 = 0; g.N = bf ? Nqk : Nqkv;
+            if (bf) {
+                // one launch for Q, K and V when the large-tile kernel takes it (V is the transposed column range:
+                // the normalised input is read once); otherwise Q/K and V separately
+                GemmArgs q3 = g;
+                q3.N = Nqkv; q3.VT = w.vt; q3.vt_from = Nqk; q3.vt_b = (int64_t)Hk * dh * w.Lp; q3.vt_n = w.Lp;
+                if (gemm_takes_vt_split(D.dtype, q3)) {
+                    if (int32_t rc = gemm(D.dtype, q3, st)) return rc;
+                } else {
+                    if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+                    g.n0 = Nqk; g.N = Hk * dh; g.epi = EPI_VT; g.C = w.vt;
+                    g.vt_b = q3.vt_b; g.vt_n = q3.vt_n;
+                    if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+                }
             } else {
                 if (int32_t rc = gemm(D.dtype, g, st)) return rc;
-                g.n0 = Nqk; g.N = Hk * dh; g.epi = EPI_VT; g.C = w.vt;
-                g.vt_b = q3.vt_b; g.vt_n = q3.vt_n;
-                if (int32_t rc = gemm(D.dtype, g, st)) return rc;
             }
-        } else {
-            if (int32_t rc = gemm(D.dtype, g, st)) return rc;
-        }
         }
 
         // SentryAttend over the kept heads
@@ -466,18 +467,18 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
                 o8.B = D.B; o8.L = capA; o8.N = D.d; o8.K = (int)Ko; o8.epi = EPI_ROWMAJOR; o8.act = ACT_NONE;
                 o8.out_scale = pj.sa * pj.so; o8.C = w.lz_C; o8.ldc = D.d; o8.c_f32 = 1;
                 if (int32_t rc = gemm_fp8(o8, st)) return rc;
-                lazy_ctx_proj_q8(pl.stats, ly.head_group, D.Hq, pattern_id, pj.WoT8, (int64_t)D.d * Ko, (int)Ko, ly.bo, D.B, kh, Hk,
-                                 dh, D.d, 1.0f / pj.sa, pj.sa * pj.so, w.lz_c, st);
+                lazy_ctx_proj_q8(pl.stats, ly.head_group, D.Hq, pattern_id, pj.WoT8, (int64_t)D.d * Ko, (int)Ko, ly.bo,
+                                 D.B, kh, Hk, dh, D.d, 1.0f / pj.sa, pj.sa * pj.so, w.lz_c, st);
             } else {
-            GemmArgs o{};
-            o.A = w.lz_A; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
-            // 128-row blocks of the compact buffer, each with its sample's pattern (-1: no rows, skipped)
-            o.w_pstride = (int64_t)D.d * kh * dh; o.pattern_id = w.lz_blk;
-            o.B = D.B * (capA / 128); o.L = 128; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
-            o.C = w.lz_C; o.ldc = D.d; o.c_f32 = 1;
-            if (int32_t rc = gemm(D.dtype, o, st)) return rc;
-            lazy_ctx_proj(pl.stats, ly.head_group, D.Hq, pattern_id, ly.WoT, (int64_t)D.d * kh * dh, ly.bo, D.B, kh, Hk, dh,
-                          D.d, w.lz_c, st);
+                GemmArgs o{};
+                o.A = w.lz_A; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
+                // 128-row blocks of the compact buffer, each with its sample's pattern (-1: no rows, skipped)
+                o.w_pstride = (int64_t)D.d * kh * dh; o.pattern_id = w.lz_blk;
+                o.B = D.B * (capA / 128); o.L = 128; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
+                o.C = w.lz_C; o.ldc = D.d; o.c_f32 = 1;
+                if (int32_t rc = gemm(D.dtype, o, st)) return rc;
+                lazy_ctx_proj(pl.stats, ly.head_group, D.Hq, pattern_id, ly.WoT, (int64_t)D.d * kh * dh, ly.bo, D.B, kh,
+                              Hk, dh, D.d, w.lz_c, st);
             }
             // x1 = x + projection, and xn = LN2(x1) (bf16, or E4M3 codes for an FFN in FP8 arithmetic), in one pass
             const bool to_y = l == D.nl - 1 && !final_ln;
@@ -516,12 +517,12 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             o8.R = in; o8.ldr = D.d; o8.r_f32 = in_f32; o8.C = w.x1; o8.ldc = D.d; o8.c_f32 = 1;
             if (int32_t rc = gemm_fp8(o8, st)) return rc;
         } else {
-        GemmArgs o{};
-        o.A = w.att; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
-        o.w_pstride = (int64_t)D.d * kh * dh; o.bias = ly.bo; o.bias_pstride = 0; o.pattern_id = pattern_id;
-        o.B = D.B; o.L = D.L; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
-        o.R = in; o.ldr = D.d; o.r_f32 = in_f32; o.C = w.x1; o.ldc = D.d; o.c_f32 = 1;
-        if (int32_t rc = gemm(D.dtype, o, st)) return rc;
+            GemmArgs o{};
+            o.A = w.att; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
+            o.w_pstride = (int64_t)D.d * kh * dh; o.bias = ly.bo; o.bias_pstride = 0; o.pattern_id = pattern_id;
+            o.B = D.B; o.L = D.L; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
+            o.R = in; o.ldr = D.d; o.r_f32 = in_f32; o.C = w.x1; o.ldc = D.d; o.c_f32 = 1;
+            if (int32_t rc = gemm(D.dtype, o, st)) return rc;
         }
 
         // x2 = x1 + FFN(LN2(x1)); the last layer without a final LN writes Y directly
