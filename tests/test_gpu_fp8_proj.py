@@ -189,6 +189,14 @@ def test_encoder_fp8_C5_full_size_sampled():
     _case(W.CONFIGS["C5"], True, samples=[11])
 
 
+@pytest.mark.parametrize("name,samples", [("C3", [5, 77]), ("C4", [100])])
+def test_encoder_fp8_other_configs_full_size_sampled(name, samples):
+    """The other single-GPU configurations at full size: many presence patterns (C3); six layers with kept-head
+    counts whose code rows need padding, and a final LayerNorm (C4)."""
+    _say(f"encoder fp8 projections + ffn, {name} (full batch on the GPU, samples {samples} through the oracle)")
+    _case(W.CONFIGS[name], True, samples=samples)
+
+
 def test_encoder_fp8_projections_rejects_what_it_cannot_run():
     kw = dict(dtype="bf16", d=256, dh=64, Hq=4, Hk=2, F=512, seg=(100, 60, 70), extra=2, B=2, nl=1, head_keep=0.5,
               ffn_keep=0.6, dropout="none")
