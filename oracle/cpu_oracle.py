@@ -51,6 +51,8 @@ def lib():
         _lib.orc_num_active.restype = C.c_int32
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
+        _lib.orc_round_f16.restype = C.c_double
+        _lib.orc_round_f16.argtypes = [C.c_double]
         _lib.orc_max_threads.restype = C.c_int32
         _lib.orc_fp8_e4m3_decode.restype = C.c_double
         _lib.orc_fp8_e4m3_encode.restype = C.c_uint8
@@ -101,6 +103,18 @@ def round_bf16(a) -> np.ndarray:
     a = np.asarray(a, dtype=np.float64)
     out = np.empty_like(a)
     f = lib().orc_round_bf16
+    flat_in, flat_out = a.reshape(-1), out.reshape(-1)
+    for i in range(flat_in.size):
+        flat_out[i] = f(float(flat_in[i]))
+    return out
+
+
+def round_f16(a) -> np.ndarray:
+    """nearest IEEE binary16 values.  Functions that take `bf16` accept 0 / False (no storage rounding), 1 / True
+    (bfloat16) and 2 (binary16, the FP16 variant of the model)."""
+    a = np.asarray(a, dtype=np.float64)
+    out = np.empty_like(a)
+    f = lib().orc_round_f16
     flat_in, flat_out = a.reshape(-1), out.reshape(-1)
     for i in range(flat_in.size):
         flat_out[i] = f(float(flat_in[i]))

@@ -114,7 +114,7 @@ void orc_dequant_fp8(const uint8_t *q, int64_t n, float scale, int32_t bf16, dou
 {
     for (int64_t i = 0; i < n; ++i) {
         const double w = orc_fp8_e4m3_decode(q[i]) * (double)scale;      /* exact */
-        out[i] = bf16 ? orc_round_bf16(w) : (double)(float)w;
+        out[i] = bf16 == 1 ? orc_round_bf16(w) : bf16 == 2 ? orc_round_f16(w) : (double)(float)w;
     }
 }
 
@@ -149,7 +149,25 @@ double orc_round_bf16(double x)
     return r;
 }
 
-static inline double rnd(double x, int32_t bf16) { return bf16 ? orc_round_bf16(x) : x; }
+/* ---- binary16: 11 significant bits, normal exponents -14..15 ------------ */
+double orc_round_f16(double x)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(x, &e);               /* |x| = m * 2^e, m in [0.5, 1) */
+    int q = e - 11;                   /* spacing of binary16 values near x is 2^q */
+    if (q < -24) q = -24;             /* subnormal range: fixed spacing 2^-24 */
+    double r = ldexp(nearbyint(ldexp(x, -q)), q);   /* nearbyint: ties to even */
+    if (fabs(r) > 65504.0) r = (x > 0) ? INFINITY : -INFINITY;
+    return r;
+}
+
+/* The `bf16` argument of every function below is the model's storage type: 0 = none (fp64 throughout, or fp32 where
+ * stated), 1 = bfloat16, 2 = IEEE binary16 (the FP16 variant of the model: the same rounding points) */
+static inline double rnd(double x, int32_t bf16)
+{
+    return bf16 == 1 ? orc_round_bf16(x) : bf16 == 2 ? orc_round_f16(x) : x;
+}
 
 /* ---- Sec. 4.5: gate scores -> keep sets -------------------------------- */
 typedef struct { float g; int32_t i; } scored;
@@ -527,7 +545,7 @@ void orc_dequant_f16(const uint16_t *q, int64_t n, int32_t bf16, double *out)
 {
     for (int64_t i = 0; i < n; ++i) {
         const double w = orc_f16_decode(q[i]);                /* exact in fp32 as well */
-        out[i] = bf16 ? orc_round_bf16(w) : w;
+        out[i] = rnd(w, bf16);
     }
 }
 

@@ -36,6 +36,9 @@ int32_t orc_num_active(int32_t T, int32_t c);
 
 /* Round a double to the nearest bf16-representable value, ties to even. */
 double orc_round_bf16(double x);
+/* nearest IEEE binary16 value (ties to even, overflow to infinity, subnormals kept).  Wherever a function below takes
+ * `bf16`, 0 = no storage rounding, 1 = bfloat16, 2 = binary16: the FP16 variant of the model has the same rounding points. */
+double orc_round_f16(double x);
 
 /*
  * Sec. 4.5 "Head pruning with GQA consistency" / "FFN pruning", with integer

@@ -253,6 +253,72 @@ def test_moe_special_cases():
     assert np.max(np.abs(yb - orc.moe_ffn(xb, mb, 2)[0]) / np.maximum(1, np.abs(yb))) < 0.1
 
 
+# ------------------------------------------------ binary16 as the model's storage type (FP16 variant)
+def test_round_f16_against_library_and_ties():
+    """orc_round_f16 against numpy's float16 cast (a library implementation of IEEE binary16 rounding): random values
+    over the whole range, the overflow threshold, subnormals, ties."""
+    rng = np.random.default_rng(21)
+    x = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-9, 6, 4000),
+                        [65504.0, 65519.99, 65520.0, 65536.0, 1e6, -65520.0, -1e9, 2.0 ** -24, 2.0 ** -25,
+                         1.5 * 2.0 ** -25, 2.0 ** -26, 3 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -25, 0.0, -0.0]])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).astype(np.float64)
+    got = orc.round_f16(x)
+    assert np.array_equal(got, want)
+    assert np.isinf(want).any() and (np.abs(want[want != 0]) < 2.0 ** -14).any()      # both ends were exercised
+    # ties to even at 11 significant bits
+    assert orc.round_f16([1 + 2.0 ** -11])[0] == 1.0 and orc.round_f16([1 + 3 * 2.0 ** -11])[0] == 1 + 2 * 2.0 ** -10
+    assert orc.round_f16([1 + 2.0 ** -11 + 2.0 ** -40])[0] == 1 + 2.0 ** -10
+
+
+def test_f16_mode_has_the_rounding_points_of_the_bf16_mode():
+    """Mode 2 rounds exactly where mode 1 does: stored outputs are binary16 numbers; a block whose intermediate
+    values are all binary16-representable is unchanged by the mode; the FFN against a numpy evaluation with float16
+    casts at the stated points (LN output, hidden activations, y)."""
+    rng = np.random.default_rng(22)
+    h16 = lambda a: np.asarray(a, np.float64).astype(np.float16).astype(np.float64)
+    Q, K, V = (h16(rng.standard_normal((1, 2, 10, 4))) for _ in range(3))
+    O, M, sel, _ = orc.sparse_gqa(Q, K, V, [0, 1], U=3)
+    Oh, Mh, selh, _ = orc.sparse_gqa(Q, K, V, [0, 1], U=3, bf16=2)
+    assert np.array_equal(Oh, h16(O)) and np.array_equal(M, Mh) and np.array_equal(sel, selh)
+    assert not np.array_equal(Oh, orc.sparse_gqa(Q, K, V, [0, 1], U=3, bf16=1)[0])
+    # the pruned FFN
+    spec = W.small_spec(dtype="f32", B=2, nl=1, dropout="none", final_ln=False)
+    wl = W.make_workload(spec)
+    masks = oracle_masks(wl)
+    pack = dense_packs(wl, masks)[0][0]
+    lw = {k: h16(v) for k, v in wl.layers[0].items()}
+    wl.layers[0] = {k: v.astype(np.float32) for k, v in lw.items()}
+    pack = dense_packs(wl, masks)[0][0]
+    x = h16(wl.x[0])
+    y = orc.pruned_ffn(pack, x, bf16=2)
+    keep = np.flatnonzero(masks["ffn_mask"][0, 0])
+    mu = x.mean(-1, keepdims=True)
+    xn = h16((x - mu) / np.sqrt(((x - mu) ** 2).mean(-1, keepdims=True) + 1e-5) * lw["ln2_g"] + lw["ln2_b"])
+    hid = h16(np.maximum(xn @ lw["W1"][keep].T + lw["b1"][keep], 0))
+    want = h16(x + hid @ lw["W2"][keep] + lw["b2"])
+    assert np.array_equal(y, want)
+    # the encoder's output is a stored tensor; the residual stream between layers is not
+    wl2 = W.make_workload(W.small_spec(dtype="f32", B=2, nl=2))
+    m2 = oracle_masks(wl2)
+    U = orc.num_active(wl2.spec.L, wl2.spec.c)
+    yh, _, _ = orc.encoder_forward(wl2.x, dense_packs(wl2, m2), U, wl2.pattern_id, wl2.key_valid, final_ln=wl2.final_ln,
+                                   bf16=2)
+    y0, _, _ = orc.encoder_forward(wl2.x, dense_packs(wl2, m2), U, wl2.pattern_id, wl2.key_valid, final_ln=wl2.final_ln)
+    assert np.array_equal(yh, h16(yh)) and not np.array_equal(yh, y0)
+    assert np.abs(yh - y0).max() < 2e-2 * max(1.0, np.abs(y0).max())
+    # storage dequantisation into an FP16 model: binary16 codes are exact, E4M3 products round once
+    bits = np.arange(0, 65536, 7, dtype=np.uint16)
+    vals = bits.view(np.float16).astype(np.float64)
+    ok = ~np.isnan(vals)
+    assert np.array_equal(orc.dequant_f16(bits[ok], bf16=2), vals[ok])
+    q = np.arange(256, dtype=np.uint8)
+    q = q[(q & 0x7F) != 0x7F]
+    with np.errstate(over="ignore"):
+        assert np.array_equal(orc.dequant_fp8(q, 0.37, bf16=2),
+                              h16(np.array([orc.fp8_e4m3_decode(int(c)) for c in q]) * float(np.float32(0.37))))
+
+
 # --------------------------------------------------------- SentryAttend (a4-a7)
 def _mha_textbook(Q, K, V):
     """Independent multi-head attention: [B,H,L,dh] -> [B,L,H*dh]."""
