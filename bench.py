@@ -313,6 +313,34 @@ def bench_sampled_score(wl, steps, warmup):
                     "`value` above is the score over all allowed keys"}
 
 
+def bench_f16(wl, steps, warmup):
+    """The same step with the model in IEEE binary16 (the FP16 build of the library, libsentryfuse_f16.so: same
+    sources, same launches, fp16 MFMA at the bf16 rate): same shapes and seeds, values rounded to binary16."""
+    import dataclasses
+    import torch
+    from paper_2604_08971_amd import binding as sf
+    from paper_2604_08971_amd import workloads as W
+    from gpu_utils import DeviceModel
+    if wl.spec.dtype != "bf16":
+        return None
+    wl16 = W.make_workload(dataclasses.replace(wl.spec, dtype="f16"))
+    with sf.use_half("f16"):
+        dm = DeviceModel(wl16).build_plan()
+        y = torch.empty_like(dm.x)
+
+        def step():
+            dm.build_plan()
+            dm.forward(out=y)
+
+        ms, _ = time_steps(step, steps, warmup)
+        finite = bool(torch.isfinite(y.float()).all())
+        del dm
+    torch.cuda.empty_cache()
+    B, L = wl.x.shape[0], wl.spec.L
+    return {"ms_per_step": ms, "tokens_per_s": B * L / (ms * 1e-3), "output_finite": finite,
+            "note": "sf_* entry points of libsentryfuse_f16.so (dtype SF_F16) on the same workload; not part of `value`"}
+
+
 def bench_moe(wl, steps, warmup, E=8, top_k=2):
     """The workload's tokens through one Sparse-MoE FFN block with pruned experts (E experts, Top-k routing,
     every expert keeps its own channel set): masks of the experts -> compaction -> forward."""
@@ -735,6 +763,7 @@ def main():
         out["kernels"] = k
         out["sparse_gqa"] = bench_sparse_gqa(dm, wl, args.steps)
         out["sampled_score"] = bench_sampled_score(wl, args.steps, args.warmup)
+        out["f16_build"] = bench_f16(wl, args.steps, args.warmup)
         out["moe_ffn"] = bench_moe(wl, args.steps, args.warmup)
         out["gate_plan"] = bench_gate_plan(wl)
         out["fp8_weights"] = bench_fp8_plan(wl, dm)

@@ -27,6 +27,16 @@
  *    the activation, and the output Y of each entry point.  Inside
  *    sf_encoder_forward the residual stream between layers is an fp32
  *    accumulation and is not rounded.
+ *    dtype SF_F16: the FP16 variant of the model - the same, with IEEE
+ *    binary16 in place of bf16 everywhere (fp16 MFMA, fp32 accumulation,
+ *    round to nearest even at the same points; values beyond +-65504
+ *    overflow to infinity, the caller's weights and activations must fit).
+ *    It is served by a second build of these sources, libsentryfuse_f16.so
+ *    (same entry points); libsentryfuse.so takes SF_F32 and SF_BF16 models,
+ *    libsentryfuse_f16.so SF_F32 and SF_F16 models, the other 16-bit type
+ *    returns SF_ERR_UNSUPPORTED.  The FP8 entry points (E4M3-stored weights,
+ *    FP8 arithmetic) are built for bf16 models only.  Wherever a comment
+ *    below says "bf16" for the model dtype, the FP16 build reads "binary16".
  *  - Gate scores, sparsity scores and all index tensors are fp32 / int32 /
  *    uint8 regardless of dtype.
  */
@@ -49,7 +59,7 @@ typedef enum sf_status {
     SF_ERR_HIP = -5            /* a HIP launch failed; see sf_last_error() */
 } sf_status;
 
-enum { SF_F32 = 0, SF_BF16 = 1 };
+enum { SF_F32 = 0, SF_BF16 = 1, SF_F16 = 2 };
 enum { SF_RELU = 0, SF_GELU_ERF = 1 };
 enum { SF_FLAG_FINAL_LN = 1u };
 
@@ -65,7 +75,7 @@ typedef struct sf_desc {
     int32_t d_ff;       /* FFN hidden width of the dense model */
     int32_t n_layers;
     int32_t P;          /* number of modality-presence patterns in use */
-    int32_t dtype;      /* SF_F32 | SF_BF16 */
+    int32_t dtype;      /* SF_F32 | SF_BF16 (libsentryfuse.so) | SF_F16 (libsentryfuse_f16.so) */
     int32_t act;        /* SF_RELU | SF_GELU_ERF */
     int32_t c_factor;   /* c of U = c*ceil(ln L) (Sec. 4.4); 5 if <= 0 */
     int32_t U_override; /* < 0: use c_factor; >= 0: this many active queries (clipped to L) */

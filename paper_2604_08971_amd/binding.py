@@ -7,6 +7,7 @@ raises.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes as C
 import os
 from typing import Dict, List, Optional, Sequence
@@ -15,9 +16,12 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsentryfuse.so")
-_lib = None
+# the build of the same sources whose 16-bit type is IEEE binary16 (dtype SF_F16); selected with use_half("f16")
+LIB_PATHS = {"bf16": LIB_PATH, "f16": os.path.join(_HERE, "libsentryfuse_f16.so")}
+_libs = {}
+_half = "bf16"
 
-SF_F32, SF_BF16 = 0, 1
+SF_F32, SF_BF16, SF_F16 = 0, 1, 2
 SF_RELU, SF_GELU_ERF = 0, 1
 SF_FLAG_FINAL_LN = 1
 
@@ -99,13 +103,25 @@ class SentryFuseError(RuntimeError):
     pass
 
 
+@contextlib.contextmanager
+def use_half(half: str):
+    """Within the block every call goes to the library build whose 16-bit type is `half` ("bf16" or "f16")."""
+    global _half
+    assert half in LIB_PATHS, half
+    prev, _half = _half, half
+    try:
+        yield
+    finally:
+        _half = prev
+
+
 def lib():
-    """Load the HIP library; never falls back to anything else."""
-    global _lib
-    if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise SentryFuseError(f"{LIB_PATH} is missing: run `python -m paper_2604_08971_amd.build` first")
-        L = C.CDLL(LIB_PATH)
+    """Load the HIP library (the build selected by use_half); never falls back to anything else."""
+    if _half not in _libs:
+        path = LIB_PATHS[_half]
+        if not os.path.exists(path):
+            raise SentryFuseError(f"{path} is missing: run `python -m paper_2604_08971_amd.build` first")
+        L = C.CDLL(path)
         L.sf_last_error.restype = C.c_char_p
         for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes",
                   "sf_moe_ffn_workspace_bytes", "sf_pruned_ffn_fp8_workspace_bytes", "sf_encoder_fp8_workspace_bytes"):
@@ -175,8 +191,8 @@ def lib():
         L.sf_num_active.argtypes = [C.POINTER(SfDesc)]
         L.sf_active_projection_rows.argtypes = [C.POINTER(SfDesc), C.c_int32]
         L.sf_ffn_padded.argtypes = [C.POINTER(SfDesc), C.c_int32]
-        _lib = L
-    return _lib
+        _libs[_half] = L
+    return _libs[_half]
 
 
 def _check(rc: int, what: str):
@@ -193,7 +209,7 @@ def _stream():
 
 
 def torch_dtype(dtype: int):
-    return torch.bfloat16 if dtype == SF_BF16 else torch.float32
+    return torch.bfloat16 if dtype == SF_BF16 else torch.float16 if dtype == SF_F16 else torch.float32
 
 
 def make_desc(B, L, d_model, Hq, Hk, dh, d_ff, n_layers=1, P=1, dtype=SF_BF16, act=SF_RELU, c_factor=5,

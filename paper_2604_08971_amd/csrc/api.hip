@@ -67,7 +67,12 @@ int32_t read_desc(const sf_desc *desc, Dims &D)
     if (D.B < 1 || D.L < 1 || D.d < 1 || D.Hq < 1 || D.Hk < 1 || D.dh < 1 || D.F < 1 || D.nl < 1 || D.P < 1)
         return fail(SF_ERR_INVALID_ARG, "descriptor: sizes must be positive");
     if (D.Hq % D.Hk) return fail(SF_ERR_INVALID_ARG, "descriptor: Hq %% Hk != 0");
-    if (D.dtype != SF_F32 && D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "descriptor: unknown dtype");
+    if (D.dtype == SF_DTYPE_16_OTHER)
+        return fail(SF_ERR_UNSUPPORTED, "descriptor: this build of the library computes 16-bit models in %s; %s",
+                    SF_DTYPE_16 == SF_F16 ? "IEEE binary16 (SF_F16)" : "bfloat16 (SF_BF16)",
+                    SF_DTYPE_16 == SF_F16 ? "SF_BF16 models take libsentryfuse.so" : "SF_F16 models take libsentryfuse_f16.so");
+    if (D.dtype != SF_F32 && D.dtype != SF_DTYPE_16) return fail(SF_ERR_UNSUPPORTED, "descriptor: unknown dtype");
+    if (D.dtype == SF_DTYPE_16) D.dtype = SF_BF16;      // from here on SF_BF16 stands for "the 16-bit type of this build"
     if (D.act != SF_RELU && D.act != SF_GELU_ERF) return fail(SF_ERR_UNSUPPORTED, "descriptor: unknown activation");
     if (D.ffn_pad % 64) return fail(SF_ERR_SHAPE, "descriptor: ffn_pad must be a multiple of 64");
     if (D.dtype == SF_BF16 && (D.d % 8 || D.dh % 8))

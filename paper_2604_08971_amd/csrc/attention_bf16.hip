@@ -63,7 +63,7 @@ __device__ __forceinline__ void build_tile_list(const uint32_t *words, int nword
 template <int DH, int NT>
 struct KTile {
     static constexpr int CH = DH / 8, TOTAL = BKEY * CH, N = (TOTAL + NT - 1) / NT;
-    static __device__ __forceinline__ void fetch(const __bf16 *Kb, int64_t sl, int j0, int L, uint4 (&r)[N])
+    static __device__ __forceinline__ void fetch(const h16 *Kb, int64_t sl, int j0, int L, uint4 (&r)[N])
     {
         const char *base = reinterpret_cast<const char *>(Kb + (int64_t)j0 * sl);
 #pragma unroll
@@ -75,7 +75,7 @@ struct KTile {
                        ? *reinterpret_cast<const uint4 *>(base + off) : make_uint4(0, 0, 0, 0);
         }
     }
-    static __device__ __forceinline__ void put(const uint4 (&r)[N], __bf16 *Ks)
+    static __device__ __forceinline__ void put(const uint4 (&r)[N], h16 *Ks)
     {
 #pragma unroll
         for (int u = 0; u < N; ++u) {
@@ -98,14 +98,14 @@ struct KTile {
 // while the current one is multiplied, so one barrier per tile suffices.
 template <int DH, int QBS>
 __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
-    const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
+    const h16 *__restrict__ Q, sf_strides sq, const h16 *__restrict__ K, sf_strides sk,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
     const uint8_t *__restrict__ query_valid, const uint8_t *__restrict__ key_mask,
     const float *__restrict__ stats, int nH, int nG, int L, int Lk, float *__restrict__ score, int scoreH,
     int qblocks, int n_items)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                              // [2][BKEY][DH+PAD]
+    h16 *Ks = reinterpret_cast<h16 *>(smem);                              // [2][BKEY][DH+PAD]
     float *kbar = reinterpret_cast<float *>(Ks + 2 * BKEY * (DH + PAD));        // [DH]
     uint32_t *words = reinterpret_cast<uint32_t *>(kbar + DH);                  // [ceil(Lk/32)]
     uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (Lk + 31) / 32);     // [ceil(Lk/64)]
@@ -121,18 +121,18 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     build_mask_words(key_mask ? key_mask + (int64_t)b * Lk : nullptr, Lk, words, nwords);
     if (threadIdx.x < DH) kbar[threadIdx.x] = stats[((int64_t)b * nG + g) * 2 * DH + threadIdx.x];
 
-    const __bf16 *Qb = Q + (int64_t)b * sq.b + (int64_t)h * sq.h;
-    const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const h16 *Qb = Q + (int64_t)b * sq.b + (int64_t)h * sq.h;
+    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
     const int q0 = (qblk * NWAVE + wave) * QBS * 32;
 
-    bf16x8 qf[QBS][DH / 16];
+    h16x8 qf[QBS][DH / 16];
     float rmax[QBS];
 #pragma unroll
     for (int qq = 0; qq < QBS; ++qq) {
         const int i = min(q0 + qq * 32 + l32, L - 1);
 #pragma unroll
         for (int kk = 0; kk < DH / 16; ++kk)
-            qf[qq][kk] = *reinterpret_cast<const bf16x8 *>(Qb + (int64_t)i * sq.l + kk * 16 + lhi * 8);
+            qf[qq][kk] = *reinterpret_cast<const h16x8 *>(Qb + (int64_t)i * sq.l + kk * 16 + lhi * 8);
         rmax[qq] = -INFINITY;
     }
     __syncthreads();
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     if (nt > 0) KT_::fetch(Kb, sk.l, tile_j0(0), Lk, kreg);
     for (int it = 0; it < nt; ++it) {
         const int j0 = tile_j0(it);
-        __bf16 *Kt = Ks + (it & 1) * BKEY * (DH + PAD);
+        h16 *Kt = Ks + (it & 1) * BKEY * (DH + PAD);
         KT_::put(kreg, Kt);
         __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffer)
         if (it + 1 < nt) KT_::fetch(Kb, sk.l, tile_j0(it + 1), Lk, kreg);
@@ -157,10 +157,10 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
         for (int kb = 0; kb < 2; ++kb) {
             const uint32_t w = kb ? w1 : w0;
             if (w == 0u) continue;
-            bf16x8 kf[DH / 16];
+            h16x8 kf[DH / 16];
 #pragma unroll
             for (int kk = 0; kk < DH / 16; ++kk)
-                kf[kk] = *reinterpret_cast<const bf16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+                kf[kk] = *reinterpret_cast<const h16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
             if (w == 0xffffffffu) {                 // scalar branch: the usual tile, no masking
 #pragma unroll
                 for (int qq = 0; qq < QBS; ++qq) {
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
                     for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
                     for (int kk = 0; kk < DH / 16; ++kk)
-                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s, 0, 0, 0);
+                        s = SF_MFMA16(kf[kk], qf[qq][kk], s, 0, 0, 0);
                     float m = rmax[qq];
 #pragma unroll
                     for (int e = 0; e < 16; e += 2) m = fmaxf(fmaxf(m, s[e]), s[e + 1]);
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
                     for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
                     for (int kk = 0; kk < DH / 16; ++kk)
-                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s, 0, 0, 0);
+                        s = SF_MFMA16(kf[kk], qf[qq][kk], s, 0, 0, 0);
                     float m = rmax[qq];
 #pragma unroll
                     for (int e = 0; e < 16; ++e)       // key row of s[e]: (e/4)*8 + lhi*4 + e%4
@@ -225,18 +225,18 @@ constexpr int AWAVE = 8;
 
 template <int DH, int QB>
 __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
-    const __bf16 *__restrict__ Q, sf_strides sq, const __bf16 *__restrict__ K, sf_strides sk,
-    const __bf16 *__restrict__ VT, sf_strides svt, const int32_t *__restrict__ head_group, int hg_stride,
+    const h16 *__restrict__ Q, sf_strides sq, const h16 *__restrict__ K, sf_strides sk,
+    const h16 *__restrict__ VT, sf_strides svt, const int32_t *__restrict__ head_group, int hg_stride,
     const int32_t *__restrict__ pattern_id, const uint8_t *__restrict__ key_valid,
     const int32_t *__restrict__ sel, int selH, int nH, int nG, int BG, int chunks, int L, int Lp, int U,
-    int Upad, int splits, int keys_per_split, __bf16 *__restrict__ O, int64_t ldo,
+    int Upad, int splits, int keys_per_split, h16 *__restrict__ O, int64_t ldo,
     float *__restrict__ part_o, float *__restrict__ part_ml)
 {
     constexpr int NT = AWAVE * 64;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int KT = BKEY * (DH + PAD), VT_ = DH * (BKEY + PAD);          // elements of one K / V^T tile
-    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                         // [2][BKEY][DH+PAD]
-    __bf16 *Vs = Ks + 2 * KT;                                              // [2][DH][BKEY+PAD]
+    h16 *Ks = reinterpret_cast<h16 *>(smem);                         // [2][BKEY][DH+PAD]
+    h16 *Vs = Ks + 2 * KT;                                              // [2][DH][BKEY+PAD]
     uint32_t *words = reinterpret_cast<uint32_t *>(Vs + 2 * VT_);          // [ceil(L/32)]
     uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (L + 31) / 32); // [ceil(L/64)]
     __shared__ int heads[64];
@@ -268,8 +268,8 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     const int nqb = Upad / 32;
     const int npairs = n_heads * nqb;
 
-    const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const __bf16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
     const float sc = LOG2E / sqrtf((float)DH);
 
     // V^T tile chunks of this thread -> registers; keys at or beyond L are zeroed
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             r[u] = v;
         }
     };
-    auto put_v = [&](const uint4 (&r)[NV], __bf16 *Vt) {
+    auto put_v = [&](const uint4 (&r)[NV], h16 *Vt) {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
             const int c = threadIdx.x + u * NT;
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
 
     for (int pair0 = chunk * (AWAVE * QB); pair0 < npairs; pair0 += chunks * (AWAVE * QB)) {
         int head[QB], qidx[QB], slot[QB];
-        bf16x8 qf[QB][DH / 16];
+        h16x8 qf[QB][DH / 16];
 #pragma unroll
         for (int qq = 0; qq < QB; ++qq) {
             const int pi = pair0 + wave * QB + qq;
@@ -317,11 +317,11 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
                 slot[qq] = (pi % nqb) * 32 + l32;
                 if (slot[qq] < U) qidx[qq] = sel[((int64_t)b * selH + head[qq]) * U + slot[qq]];
             }
-            const __bf16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
+            const h16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
                                  (int64_t)max(qidx[qq], 0) * sq.l;
 #pragma unroll
             for (int kk = 0; kk < DH / 16; ++kk)
-                qf[qq][kk] = *reinterpret_cast<const bf16x8 *>(qrow + kk * 16 + lhi * 8);
+                qf[qq][kk] = *reinterpret_cast<const h16x8 *>(qrow + kk * 16 + lhi * 8);
         }
         const bool idle = pair0 + wave * QB >= npairs;        // wave-uniform: no pair at all
 
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
 
         for (int it = 0; it < nt; ++it) {
             const int j0 = tile_j0(it);
-            __bf16 *Kt = Ks + (it & 1) * KT, *Vt = Vs + (it & 1) * VT_;
+            h16 *Kt = Ks + (it & 1) * KT, *Vt = Vs + (it & 1) * VT_;
             KT_::put(kreg, Kt);
             put_v(vreg, Vt);
             __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffers)
@@ -355,22 +355,22 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             f32x16 s[QB][2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                bf16x8 kf[DH / 16];
+                h16x8 kf[DH / 16];
 #pragma unroll
                 for (int kk = 0; kk < DH / 16; ++kk)
-                    kf[kk] = *reinterpret_cast<const bf16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+                    kf[kk] = *reinterpret_cast<const h16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
 #pragma unroll
                 for (int qq = 0; qq < QB; ++qq) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) s[qq][kb][e] = 0.f;
 #pragma unroll
                     for (int kk = 0; kk < DH / 16; ++kk)
-                        s[qq][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[qq][kk], s[qq][kb], 0, 0, 0);
+                        s[qq][kb] = SF_MFMA16(kf[kk], qf[qq][kk], s[qq][kb], 0, 0, 0);
                 }
             }
 
             // online softmax per query (per lane), log2 domain
-            bf16x8 pf[QB][4];
+            h16x8 pf[QB][4];
 #pragma unroll
             for (int qq = 0; qq < QB; ++qq) {
                 if (!all_allowed) {
@@ -412,7 +412,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[qq][t][e] = (__bf16)s[qq][t / 2][(t % 2) * 8 + e];
+                    for (int e = 0; e < 8; ++e) pf[qq][t][e] = (h16)s[qq][t / 2][(t % 2) * 8 + e];
             }
 
             // O^T += V^T . P^T
@@ -420,15 +420,15 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             for (int db = 0; db < DH / 32; ++db) {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const __bf16 *vrow = Vt + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 4;
-                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vrow);
-                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vrow + 8);
-                    bf16x8 vf;
+                    const h16 *vrow = Vt + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 4;
+                    const h16x4 lo = *reinterpret_cast<const h16x4 *>(vrow);
+                    const h16x4 hi = *reinterpret_cast<const h16x4 *>(vrow + 8);
+                    h16x8 vf;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
 #pragma unroll
                     for (int qq = 0; qq < QB; ++qq)
-                        oacc[qq][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qq][t], oacc[qq][db], 0, 0, 0);
+                        oacc[qq][db] = SF_MFMA16(vf, pf[qq][t], oacc[qq][db], 0, 0, 0);
                 }
             }
         }
@@ -440,15 +440,15 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             if (qidx[qq] < 0) continue;
             if (splits <= 1) {
                 const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-                __bf16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
+                h16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
 #pragma unroll
                 for (int db = 0; db < DH / 32; ++db)
 #pragma unroll
                     for (int ig = 0; ig < 4; ++ig) {
-                        bf16x4 o;
+                        h16x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)(oacc[qq][db][ig * 4 + e] * inv);
-                        *reinterpret_cast<bf16x4 *>(orow + db * 32 + ig * 8 + lhi * 4) = o;
+                        for (int e = 0; e < 4; ++e) o[e] = (h16)(oacc[qq][db][ig * 4 + e] * inv);
+                        *reinterpret_cast<h16x4 *>(orow + db * 32 + ig * 8 + lhi * 4) = o;
                     }
             } else {
                 const int64_t base = (((int64_t)b * nH + head[qq]) * splits + sp) * Upad + slot[qq];   // [b, head, split, slot]
@@ -484,8 +484,8 @@ static int32_t launch_score(const AttnArgs &a, const void *Kx, sf_strides skx, i
     if (items > (1 << 30)) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): too many work items");
     dim3 grid((unsigned)align_up(items, 8));
     ProfScope prof(SF_KERNEL_SCORE, st);
-    hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const __bf16 *)a.Q,
-                       a.sq, (const __bf16 *)Kx, skx, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
+    hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const h16 *)a.Q,
+                       a.sq, (const h16 *)Kx, skx, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
                        key_mask, stats, a.nH, a.nG, a.L, Lk, score, scoreH, qblocks, (int)items);
     return SF_OK;
 }
@@ -517,10 +517,10 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
     if (items > (1 << 30)) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): too many work items");
     dim3 grid((unsigned)align_up(items, 8));
     ProfScope prof(SF_KERNEL_ATTEND, st);
-    hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const __bf16 *)a.Q,
-                       a.sq, (const __bf16 *)a.K, a.sk, (const __bf16 *)vt, svt, a.head_group, a.hg_stride,
+    hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
+                       a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
                        a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
-                       pl.splits, pl.keys_per_split, (__bf16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
+                       pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
     return SF_OK;
 }
 

@@ -46,15 +46,15 @@ __global__ __launch_bounds__(256) void kv_stats_partial_kernel(
 // its key-contiguous transposed layout [dh][Lp].  Same outputs as above.
 template <int DH>
 __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
-    const __bf16 *__restrict__ K, sf_strides sk, const __bf16 *__restrict__ VT, sf_strides svt,
+    const h16 *__restrict__ K, sf_strides sk, const h16 *__restrict__ VT, sf_strides svt,
     const uint8_t *__restrict__ key_valid, int nG, int L, float *__restrict__ part)
 {
     constexpr int CH = DH / 8, RP = 256 / CH, TPR = 256 / DH;
     __shared__ float red[RP][DH];
     const int bg = blockIdx.y, b = bg / nG, g = bg % nG, tid = threadIdx.x;
     const int j0 = blockIdx.x * STAT_CHUNK, j1 = min(L, j0 + STAT_CHUNK);
-    const __bf16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const __bf16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     float *o = part + (((int64_t)bg * gridDim.x + blockIdx.x) * 2) * DH;
 
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         for (int j = j0 + r; j < j1; j += RP) {
             if (kv && !kv[j]) continue;
-            const bf16x8 t = *reinterpret_cast<const bf16x8 *>(Kb + (int64_t)j * sk.l + c * 8);
+            const h16x8 t = *reinterpret_cast<const h16x8 *>(Kb + (int64_t)j * sk.l + c * 8);
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] += (float)t[e];
         }
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
         const int e = tid / TPR, q = tid % TPR;
         float s = 0.f;
         for (int j = j0 + q * 8; j < j1; j += TPR * 8) {
-            const bf16x8 t = *reinterpret_cast<const bf16x8 *>(Vb + (int64_t)e * svt.l + j);   // j + 8 <= Lp
+            const h16x8 t = *reinterpret_cast<const h16x8 *>(Vb + (int64_t)e * svt.l + j);   // j + 8 <= Lp
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (j + u < j1 && (!kv || kv[j + u])) s += (float)t[u];
@@ -208,10 +208,10 @@ __global__ __launch_bounds__(256) void fill_kernel(
         for (int t = 0; t < VEC; ++t) v[t] = ctx[h * dh + e + t];
         T *o = O + ((int64_t)b * L + i) * ldo + (int64_t)h * dh + e;
         if constexpr (sizeof(T) == 2 && VEC == 8) {
-            bf16x8 ov;
+            h16x8 ov;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) ov[t] = (__bf16)v[t];
-            *reinterpret_cast<bf16x8 *>(o) = ov;             // ldo % 8 == 0 and 16-byte aligned O checked on the host
+            for (int t = 0; t < 8; ++t) ov[t] = (h16)v[t];
+            *reinterpret_cast<h16x8 *>(o) = ov;             // ldo % 8 == 0 and 16-byte aligned O checked on the host
         } else {
 #pragma unroll
             for (int t = 0; t < VEC; ++t) o[t] = from_f32<T>(v[t]);
@@ -521,17 +521,17 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         while (DHP < a.dh) DHP *= 2;
         dim3 grid(pl.stat_chunks, BG);
         if (dtype == SF_BF16 && vT && a.dh == 32)
-            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<32>, grid, dim3(256), 0, st, (const __bf16 *)a.K, a.sk,
-                               (const __bf16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<32>, grid, dim3(256), 0, st, (const h16 *)a.K, a.sk,
+                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
         else if (dtype == SF_BF16 && vT && a.dh == 64)
-            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<64>, grid, dim3(256), 0, st, (const __bf16 *)a.K, a.sk,
-                               (const __bf16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<64>, grid, dim3(256), 0, st, (const h16 *)a.K, a.sk,
+                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
         else if (dtype == SF_BF16 && vT && a.dh == 128)
-            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<128>, grid, dim3(256), 0, st, (const __bf16 *)a.K, a.sk,
-                               (const __bf16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+            hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<128>, grid, dim3(256), 0, st, (const h16 *)a.K, a.sk,
+                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
         else if (dtype == SF_BF16)
-            hipLaunchKernelGGL(kv_stats_partial_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)a.K,
-                               a.sk, (const __bf16 *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
+            hipLaunchKernelGGL(kv_stats_partial_kernel<h16>, grid, dim3(256), 0, st, (const h16 *)a.K,
+                               a.sk, (const h16 *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
                                DHP, pl.stat_part);
         else
             hipLaunchKernelGGL(kv_stats_partial_kernel<float>, grid, dim3(256), 0, st, (const float *)a.K,
@@ -564,9 +564,9 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
             if (a.sample_idx && pl.Sp > 0) {
                 const size_t gl = (size_t)ceil_div(a.L, 32) * 4 + (size_t)pl.Sp * 4;
                 if (dtype == SF_BF16)
-                    hipLaunchKernelGGL(gather_key_sample_kernel<__bf16>, dim3(BG), dim3(256), gl, st,
-                                       (const __bf16 *)a.K, a.sk, a.key_valid, a.sample_idx, a.n_sample, a.nG, a.L,
-                                       a.dh, pl.Sp, (__bf16 *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys);
+                    hipLaunchKernelGGL(gather_key_sample_kernel<h16>, dim3(BG), dim3(256), gl, st,
+                                       (const h16 *)a.K, a.sk, a.key_valid, a.sample_idx, a.n_sample, a.nG, a.L,
+                                       a.dh, pl.Sp, (h16 *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys);
                 else
                     hipLaunchKernelGGL(gather_key_sample_kernel<float>, dim3(BG), dim3(256), gl, st,
                                        (const float *)a.K, a.sk, a.key_valid, a.sample_idx, a.n_sample, a.nG, a.L,
@@ -610,9 +610,9 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
     // 4. merge of the key splits, then the lazy rows
     if (pl.splits > 1) {
         const int64_t n_waves = (int64_t)BH * a.U;
-        hipLaunchKernelGGL(merge_splits_kernel<__bf16>, dim3((unsigned)((n_waves + 3) / 4)), dim3(256), 0, st,
+        hipLaunchKernelGGL(merge_splits_kernel<h16>, dim3((unsigned)((n_waves + 3) / 4)), dim3(256), 0, st,
                            a.nH, a.L, a.dh, a.U, pl.Upad, pl.splits, n_waves, sel, selH, pl.part_o, pl.part_ml,
-                           (__bf16 *)a.O, a.ldo);
+                           (h16 *)a.O, a.ldo);
     }
     if (!a.skip_fill) {   // with U == L rows can still be lazy (fewer allowed rows than U)
         const bool v8 = dtype == SF_BF16 && a.dh % 8 == 0 && a.ldo % 8 == 0 && ((uintptr_t)a.O % 16 == 0);
@@ -620,8 +620,8 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         const size_t fl = (size_t)a.nH * a.dh * 4 + (size_t)a.nH * 32 * 4;
 #define SF_FILL_ARGS grid, dim3(256), fl, st, a.nH, a.nG, a.L, a.dh, pl.slot, a.head_group, a.hg_stride, \
                      a.pattern_id, pl.stats
-        if (dtype == SF_BF16 && v8) hipLaunchKernelGGL((fill_kernel<__bf16, 8>), SF_FILL_ARGS, (__bf16 *)a.O, a.ldo);
-        else if (dtype == SF_BF16) hipLaunchKernelGGL((fill_kernel<__bf16, 4>), SF_FILL_ARGS, (__bf16 *)a.O, a.ldo);
+        if (dtype == SF_BF16 && v8) hipLaunchKernelGGL((fill_kernel<h16, 8>), SF_FILL_ARGS, (h16 *)a.O, a.ldo);
+        else if (dtype == SF_BF16) hipLaunchKernelGGL((fill_kernel<h16, 4>), SF_FILL_ARGS, (h16 *)a.O, a.ldo);
         else hipLaunchKernelGGL((fill_kernel<float, 4>), SF_FILL_ARGS, (float *)a.O, a.ldo);
 #undef SF_FILL_ARGS
     }

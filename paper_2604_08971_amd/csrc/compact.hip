@@ -543,6 +543,9 @@ extern "C" int32_t sf_compact_heads_channels_fp8(const sf_desc *desc, int32_t la
                                                  const int32_t *n_groups, const int32_t *ffn_idx,
                                                  const sf_compact_layer *c, void *stream)
 {
+    // the single rounding from the exact product to a 16-bit model type is written for bfloat16
+    if (SF_DTYPE_16 == SF_F16 && desc && desc->dtype == SF_F16)
+        return fail(SF_ERR_UNSUPPORTED, "compact_heads_channels_fp8: E4M3-stored weights are built for fp32 and bfloat16 models");
     return compact_coded<uint8_t>(desc, layer, dense, head_idx, group_idx, n_groups, ffn_idx, c, stream);
 }
 
@@ -553,6 +556,9 @@ extern "C" int32_t sf_compact_heads_channels_f16(const sf_desc *desc, int32_t la
                                                  const sf_compact_layer *c, void *stream)
 {
     if (!dense) return fail(SF_ERR_INVALID_ARG, "compact_heads_channels_f16: NULL argument");
+    // a binary16 model stores these very bits: the plain gathers
+    if (SF_DTYPE_16 == SF_F16 && desc && desc->dtype == SF_F16)
+        return sf_compact_heads_channels(desc, layer, dense, head_idx, group_idx, n_groups, ffn_idx, c, stream);
     sf_dense_layer_fp8 q{};
     q.Wq = dense->Wq; q.Wk = dense->Wk; q.Wv = dense->Wv; q.Wo = dense->Wo; q.W1 = dense->W1; q.W2 = dense->W2;
     q.sq = q.sk = q.sv = q.so = q.s1 = q.s2 = 1.0f;

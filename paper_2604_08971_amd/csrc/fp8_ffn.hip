@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void quantize_fp8_kernel(const T *__restrict__
     float t[8];
     if (i8 + 8 <= n) {
         if constexpr (sizeof(T) == 2) {
-            const bf16x8 v = *reinterpret_cast<const bf16x8 *>(x + i8);
+            const h16x8 v = *reinterpret_cast<const h16x8 *>(x + i8);
 #pragma unroll
             for (int e = 0; e < 8; ++e) t[e] = (float)v[e] * inv_scale;
         } else {
@@ -42,8 +42,8 @@ __global__ __launch_bounds__(256) void quantize_fp8_kernel(const T *__restrict__
 // LayerNorm (statistics in fp32, biased variance) with the quantiser applied to the fp32 result: one wave per
 // row, the row is read once and kept in registers (d % 8 == 0, d <= 512 * NCH), 8 codes per store.
 template <class TI, int NCH>
-__global__ __launch_bounds__(256) void layernorm_q8_kernel(const TI *__restrict__ x, const __bf16 *__restrict__ gamma,
-                                                           const __bf16 *__restrict__ beta, float eps, int64_t rows,
+__global__ __launch_bounds__(256) void layernorm_q8_kernel(const TI *__restrict__ x, const h16 *__restrict__ gamma,
+                                                           const h16 *__restrict__ beta, float eps, int64_t rows,
                                                            int d, float inv_scale, uint8_t *__restrict__ y)
 {
     const int lane = threadIdx.x & 63;
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void layernorm_q8_kernel(const TI *__restrict_
         const int ch = lane + c * 64;
         if (ch < nch) {
             if constexpr (sizeof(TI) == 2) {
-                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(xr + ch * 8);
+                const h16x8 t = *reinterpret_cast<const h16x8 *>(xr + ch * 8);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[c][e] = (float)t[e];
             } else {
@@ -92,9 +92,9 @@ __global__ __launch_bounds__(256) void layernorm_q8_kernel(const TI *__restrict_
         const int ch = lane + c * 64;
         if (ch >= nch) continue;
         float z[8];
-        bf16x8 gm, bt;
-        if (gamma) gm = *reinterpret_cast<const bf16x8 *>(gamma + ch * 8);
-        if (beta) bt = *reinterpret_cast<const bf16x8 *>(beta + ch * 8);
+        h16x8 gm, bt;
+        if (gamma) gm = *reinterpret_cast<const h16x8 *>(gamma + ch * 8);
+        if (beta) bt = *reinterpret_cast<const h16x8 *>(beta + ch * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float t = (v[c][e] - mean) * inv;
@@ -137,7 +137,9 @@ extern "C" int32_t sf_ffn_fp8_padded(int32_t k_ffn)
 extern "C" int32_t sf_quantize_fp8(const void *x, int32_t dtype, int64_t n, float scale, uint8_t *codes, void *stream)
 {
     if (n < 0 || (n > 0 && (!x || !codes))) return fail(SF_ERR_INVALID_ARG, "quantize_fp8: NULL argument");
-    if (dtype != SF_BF16 && dtype != SF_F32) return fail(SF_ERR_INVALID_ARG, "quantize_fp8: dtype must be SF_F32 or SF_BF16");
+    if (dtype != SF_DTYPE_16 && dtype != SF_F32)
+        return fail(SF_ERR_INVALID_ARG, "quantize_fp8: dtype must be SF_F32 or the 16-bit type of this build of the library");
+    if (dtype == SF_DTYPE_16) dtype = SF_BF16;
     if (!(scale > 0.f) || !(scale < 3.0e38f)) return fail(SF_ERR_INVALID_ARG, "quantize_fp8: scale must be positive and finite");
     if (((uintptr_t)x & 15) || ((uintptr_t)codes & 7))
         return fail(SF_ERR_INVALID_ARG, "quantize_fp8: x must be 16-byte and codes 8-byte aligned");
@@ -147,7 +149,7 @@ extern "C" int32_t sf_quantize_fp8(const void *x, int32_t dtype, int64_t n, floa
     const int64_t groups = (n + 7) / 8;
     const unsigned grid = (unsigned)((groups + 255) / 256);
     if (dtype == SF_BF16)
-        hipLaunchKernelGGL(quantize_fp8_kernel<__bf16>, dim3(grid), dim3(256), 0, st, (const __bf16 *)x, n, inv, codes);
+        hipLaunchKernelGGL(quantize_fp8_kernel<h16>, dim3(grid), dim3(256), 0, st, (const h16 *)x, n, inv, codes);
     else
         hipLaunchKernelGGL(quantize_fp8_kernel<float>, dim3(grid), dim3(256), 0, st, (const float *)x, n, inv, codes);
     return check_launch("quantize_fp8");
@@ -156,6 +158,7 @@ extern "C" int32_t sf_quantize_fp8(const void *x, int32_t dtype, int64_t n, floa
 static int32_t check_ffn_fp8(const char *who, const Dims &D, const sf_ffn_fp8 *f)
 {
     if (!f) return fail(SF_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (SF_DTYPE_16 != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: FP8 arithmetic is built for bfloat16 models only", who);
     if (D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: the FP8 path takes bf16 activations (dtype SF_BF16)", who);
     if (f->k_ffn < 1 || f->k_ffn > D.F) return fail(SF_ERR_INVALID_ARG, "%s: k_ffn out of range", who);
     if (!f->W1q || !f->W2Tq) return fail(SF_ERR_INVALID_ARG, "%s: NULL weight pointer", who);
@@ -181,7 +184,7 @@ void layernorm_q8(const void *X, bool x_f32, const void *gamma, const void *beta
 {
     if (rows == 0) return;
     dim3 grid((unsigned)((rows + 3) / 4));
-#define SF_LNQ_ARGS(TI) grid, dim3(256), 0, st, (const TI *)X, (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, inv_scale, y
+#define SF_LNQ_ARGS(TI) grid, dim3(256), 0, st, (const TI *)X, (const h16 *)gamma, (const h16 *)beta, eps, rows, d, inv_scale, y
 #define SF_LNQ(TI) \
     do { \
         if (d <= 512) hipLaunchKernelGGL((layernorm_q8_kernel<TI, 1>), SF_LNQ_ARGS(TI)); \
@@ -190,7 +193,7 @@ void layernorm_q8(const void *X, bool x_f32, const void *gamma, const void *beta
         else hipLaunchKernelGGL((layernorm_q8_kernel<TI, 8>), SF_LNQ_ARGS(TI)); \
     } while (0)
     if (x_f32) SF_LNQ(float);
-    else SF_LNQ(__bf16);
+    else SF_LNQ(h16);
 #undef SF_LNQ
 #undef SF_LNQ_ARGS
 }
@@ -198,8 +201,8 @@ void layernorm_q8(const void *X, bool x_f32, const void *gamma, const void *beta
 void quantize_fp8_bf16(const void *x, int64_t n, float inv_scale, uint8_t *codes, hipStream_t st)
 {
     if (n == 0) return;
-    hipLaunchKernelGGL(quantize_fp8_kernel<__bf16>, dim3((unsigned)(((n + 7) / 8 + 255) / 256)), dim3(256), 0, st,
-                       (const __bf16 *)x, n, inv_scale, codes);
+    hipLaunchKernelGGL(quantize_fp8_kernel<h16>, dim3((unsigned)(((n + 7) / 8 + 255) / 256)), dim3(256), 0, st,
+                       (const h16 *)x, n, inv_scale, codes);
 }
 
 }  // namespace sf

@@ -10,8 +10,8 @@ namespace {
 
 // 64 tokens x 64 features per block through LDS, 16 bytes per lane on both sides: 8 features of a token on the way
 // in, 8 tokens of a feature on the way out (ld, col0, ncols, Lp multiples of 8).
-__global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restrict__ src, int64_t ld, int col0, int ncols,
-                                                          int L, int Lp, __bf16 *__restrict__ vt)
+__global__ __launch_bounds__(256) void transpose_v_kernel(const h16 *__restrict__ src, int64_t ld, int col0, int ncols,
+                                                          int L, int Lp, h16 *__restrict__ vt)
 {
     __shared__ uint16_t tile[64][66];                          // row stride 33 words: the column reads spread over the banks
     const int b = blockIdx.z, j0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const __bf16 *__restri
 
 // codes[r, c] = E4M3(x[r, c] * inv_scale) for c < K, 0 for K <= c < Kp: rows of a bf16 matrix into code rows padded to
 // the FP8 GEMM's K granularity.  8 elements per thread (K, Kp, ld multiples of 8).
-__global__ __launch_bounds__(256) void quantize_rows_fp8_kernel(const __bf16 *__restrict__ x, int64_t ld, int64_t rows, int K,
+__global__ __launch_bounds__(256) void quantize_rows_fp8_kernel(const h16 *__restrict__ x, int64_t ld, int64_t rows, int K,
                                                                 int Kp, float inv_scale, uint8_t *__restrict__ codes)
 {
     const int per_row = Kp / 8;
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void quantize_rows_fp8_kernel(const __bf16 *__
     const int c = (int)(t % per_row) * 8;
     uint2 o = make_uint2(0, 0);
     if (c < K) {
-        const bf16x8 v = *reinterpret_cast<const bf16x8 *>(x + r * ld + c);
+        const h16x8 v = *reinterpret_cast<const h16x8 *>(x + r * ld + c);
         o.x = e4m3_pack4((float)v[0] * inv_scale, (float)v[1] * inv_scale, (float)v[2] * inv_scale, (float)v[3] * inv_scale);
         o.y = e4m3_pack4((float)v[4] * inv_scale, (float)v[5] * inv_scale, (float)v[6] * inv_scale, (float)v[7] * inv_scale);
     }
@@ -64,7 +64,7 @@ void quantize_rows_fp8(const void *x, int64_t ld, int64_t rows, int K, int Kp, f
 {
     const int64_t n = rows * (Kp / 8);
     if (n == 0) return;
-    hipLaunchKernelGGL(quantize_rows_fp8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const __bf16 *)x, ld,
+    hipLaunchKernelGGL(quantize_rows_fp8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const h16 *)x, ld,
                        rows, K, Kp, inv_scale, codes);
 }
 
@@ -72,13 +72,14 @@ void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L,
 {
     if (B == 0 || ncols == 0) return;
     dim3 grid((unsigned)ceil_div(Lp, 64), (unsigned)ceil_div(ncols, 64), (unsigned)B);
-    hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, st, (const __bf16 *)src, ld, col0, ncols, L, Lp,
-                       (__bf16 *)vt);
+    hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, st, (const h16 *)src, ld, col0, ncols, L, Lp,
+                       (h16 *)vt);
 }
 
 int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int k_head)
 {
     if (!p) return fail(SF_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (SF_DTYPE_16 != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: FP8 arithmetic is built for bfloat16 models only", who);
     if (D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: the FP8 path takes bf16 activations (dtype SF_BF16)", who);
     if (p->k_head != k_head) return fail(SF_ERR_INVALID_ARG, "%s: k_head differs from the compact layer's", who);
     if (!p->Wqkv8 || !p->WoT8) return fail(SF_ERR_INVALID_ARG, "%s: NULL weight pointer", who);

@@ -41,8 +41,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
     static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
 
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-    __bf16 *Xs = reinterpret_cast<__bf16 *>(smem_raw);             // [2][BM*BK]
-    __bf16 *Ws = Xs + 2 * BM * BK;                                 // [2][BN*BK]
+    h16 *Xs = reinterpret_cast<h16 *>(smem_raw);             // [2][BM*BK]
+    h16 *Ws = Xs + 2 * BM * BK;                                 // [2][BN*BK]
 
     const int tiles_m = (a.L + BM - 1) / BM;
     const int b = blockIdx.x / tiles_m;
@@ -54,8 +54,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
     if (a.k_lim) a.K = min(a.K, a.k_lim[p]);
     if (nt0 >= a.N) return;
 
-    const __bf16 *A = static_cast<const __bf16 *>(a.A) + ((int64_t)b * a.L) * a.lda;
-    const __bf16 *W = static_cast<const __bf16 *>(a.W) + (int64_t)p * a.w_pstride + (int64_t)a.n0 * a.ldw;
+    const h16 *A = static_cast<const h16 *>(a.A) + ((int64_t)b * a.L) * a.lda;
+    const h16 *W = static_cast<const h16 *>(a.W) + (int64_t)p * a.w_pstride + (int64_t)a.n0 * a.ldw;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
         }
     };
     auto store_lds = [&](int buf) {
-        __bf16 *xs = Xs + buf * BM * BK, *ws = Ws + buf * BN * BK;
+        h16 *xs = Xs + buf * BM * BK, *ws = Ws + buf * BN * BK;
 #pragma unroll
         for (int j = 0; j < XCH; ++j) {
             const int r = lr + j * (NT / 8);
@@ -114,23 +114,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
 
     for (int kt = 0; kt < nk; ++kt) {
         if (kt + 1 < nk) load_global((kt + 1) * BK);
-        const __bf16 *xs = Xs + (kt & 1) * BM * BK, *ws = Ws + (kt & 1) * BN * BK;
+        const h16 *xs = Xs + (kt & 1) * BM * BK, *ws = Ws + (kt & 1) * BN * BK;
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
-            bf16x8 xf[TM], wf[TN];
+            h16x8 xf[TM], wf[TN];
             const int chunk = s * 2 + lhi;
 #pragma unroll
             for (int t = 0; t < TM; ++t)
-                xf[t] = *reinterpret_cast<const bf16x8 *>(xs + swz(wm * WTM + t * 32 + l32, chunk));
+                xf[t] = *reinterpret_cast<const h16x8 *>(xs + swz(wm * WTM + t * 32 + l32, chunk));
 #pragma unroll
             for (int t = 0; t < TN; ++t)
-                wf[t] = *reinterpret_cast<const bf16x8 *>(ws + swz(wn * WTN + t * 32 + l32, chunk));
+                wf[t] = *reinterpret_cast<const h16x8 *>(ws + swz(wn * WTN + t * 32 + l32, chunk));
 #pragma unroll
             for (int i = 0; i < TP; ++i)
 #pragma unroll
                 for (int j = 0; j < TQ; ++j) {
-                    if (SWAP) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[i], wf[j], acc[i][j], 0, 0, 0);
-                    else      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+                    if (SWAP) acc[i][j] = SF_MFMA16(xf[i], wf[j], acc[i][j], 0, 0, 0);
+                    else      acc[i][j] = SF_MFMA16(wf[i], xf[j], acc[i][j], 0, 0, 0);
                 }
         }
         if (kt + 1 < nk) store_lds((kt + 1) & 1);
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
     }
 
     // ---- epilogue -------------------------------------------------------------
-    const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)p * a.bias_pstride + a.n0 : nullptr;
+    const h16 *bias = a.bias ? static_cast<const h16 *>(a.bias) + (int64_t)p * a.bias_pstride + a.n0 : nullptr;
     if (!SWAP) {
         // lane: token i = m0 + wm*WTM + tm*32 + l32 ; features n = wn*WTN + tn*32 + q*8 + lhi*4 + {0..3}
 #pragma unroll
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][q * 4 + e];
                     if (bias) {
-                        const bf16x4 bv = *reinterpret_cast<const bf16x4 *>(bias + n);
+                        const h16x4 bv = *reinterpret_cast<const h16x4 *>(bias + n);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] += (float)bv[e];
                     }
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
 #pragma unroll
                             for (int e = 0; e < 4; ++e) v[e] += rv[e];
                         } else {
-                            const bf16x4 rv = *reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + ro);
+                            const h16x4 rv = *reinterpret_cast<const h16x4 *>(static_cast<const h16 *>(a.R) + ro);
 #pragma unroll
                             for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
                         }
@@ -181,17 +181,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
                         for (int e = 0; e < 4; ++e) o[e] = v[e];
                         *reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co) = o;
                     } else {
-                        bf16x4 o;
+                        h16x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
-                        *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co) = o;
+                        for (int e = 0; e < 4; ++e) o[e] = (h16)v[e];
+                        *reinterpret_cast<h16x4 *>(static_cast<h16 *>(a.C) + co) = o;
                     }
                 }
             }
         }
     } else {
         // lane: feature n = wn*WTN + tn*32 + l32 ; tokens i = m0 + wm*WTM + tm*32 + q*8 + lhi*4 + {0..3}
-        __bf16 *C = static_cast<__bf16 *>(a.C) + (int64_t)b * a.vt_b;
+        h16 *C = static_cast<h16 *>(a.C) + (int64_t)b * a.vt_b;
         const bool vec_ok = ((a.vt_b | a.vt_n) & 3) == 0;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
@@ -204,12 +204,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_kernel(GemmA
                 for (int q = 0; q < 4; ++q) {
                     const int i = m0 + wm * WTM + tm * 32 + q * 8 + lhi * 4;
                     if (i >= a.L) continue;
-                    bf16x4 o;
+                    h16x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)apply_act(acc[tm][tn][q * 4 + e] + bv, a.act);
-                    __bf16 *dst = C + (int64_t)n * a.vt_n + i;
+                    for (int e = 0; e < 4; ++e) o[e] = (h16)apply_act(acc[tm][tn][q * 4 + e] + bv, a.act);
+                    h16 *dst = C + (int64_t)n * a.vt_n + i;
                     if (vec_ok && i + 3 < a.L) {
-                        *reinterpret_cast<bf16x4 *>(dst) = o;
+                        *reinterpret_cast<h16x4 *>(dst) = o;
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
@@ -225,7 +225,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool SWAP>
 static int32_t launch_cfg(const GemmArgs &a, hipStream_t st)
 {
     auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, SWAP>;
-    constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(__bf16);
+    constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(h16);
     static std::atomic<bool> attr_set{false};     // per template instance; setting the attribute twice is harmless
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

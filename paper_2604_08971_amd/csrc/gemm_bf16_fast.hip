@@ -77,7 +77,7 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
     static_assert(NSTAGE >= 2 && NSTAGE <= 4 && (NSTAGE - 2) * LPW <= 63, "pipeline depth");
 
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NSTAGE][X rows | W rows][BKT]
+    h16 *smem = reinterpret_cast<h16 *>(smem_raw);      // [NSTAGE][X rows | W rows][BKT]
 
     // XCD-aware tile order
     const int wid = blockIdx.x;
@@ -101,8 +101,8 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
     // Sources of this wave's load instructions: a uniform base that advances by BKT per K
     // tile plus a fixed per-lane byte offset.  Lane -> LDS slot is fixed (lane*16 bytes), so
     // the slot's (row, chunk) is decoded here; rows beyond the edge are clamped.
-    const char *Ab = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.A) + ((int64_t)b * a.L + m0) * a.lda);
-    const char *Wb = reinterpret_cast<const char *>(static_cast<const __bf16 *>(a.W) + (int64_t)p * a.w_pstride +
+    const char *Ab = reinterpret_cast<const char *>(static_cast<const h16 *>(a.A) + ((int64_t)b * a.L + m0) * a.lda);
+    const char *Wb = reinterpret_cast<const char *>(static_cast<const h16 *>(a.W) + (int64_t)p * a.w_pstride +
                                                     (int64_t)(a.n0 + nt0) * a.ldw);
     uint32_t xoff[LX], woff[LW];
     {
@@ -125,7 +125,7 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
     }
     // load instruction j (0..LPW-1) of K tile `tile` into ring slot `stage`
     auto issue_load = [&](int j, int tile, int stage) {
-        __bf16 *base = smem + stage * STAGE;
+        h16 *base = smem + stage * STAGE;
         const int64_t koff = (int64_t)tile * BKT * 2;
         if (j < LX) {
             __builtin_amdgcn_global_load_lds((glb_void *)(Ab + koff + xoff[j]),
@@ -155,18 +155,18 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
     // the top of the iteration stalls instruction issue until the address unit has taken them).
     auto k_tile = [&](int kt, auto with_loads) {
         constexpr bool LOADS = decltype(with_loads)::value;
-        const __bf16 *xs = smem + (kt % NSTAGE) * STAGE;
-        const __bf16 *ws = xs + BM * BKT;
+        const h16 *xs = smem + (kt % NSTAGE) * STAGE;
+        const h16 *ws = xs + BM * BKT;
         const int load_tile = kt + NSTAGE - 1, load_stage = load_tile % NSTAGE;
-        bf16x8 xf[2][TM], wf[2][TN];
+        h16x8 xf[2][TM], wf[2][TN];
         auto load_frags = [&](int s, int slot) {
             const int chunk = s * 2 + lhi;
 #pragma unroll
             for (int t = 0; t < TM; ++t)
-                xf[slot][t] = *reinterpret_cast<const bf16x8 *>(xs + L::off((wm * TM + t) * 32 + l32, chunk));
+                xf[slot][t] = *reinterpret_cast<const h16x8 *>(xs + L::off((wm * TM + t) * 32 + l32, chunk));
 #pragma unroll
             for (int t = 0; t < TN; ++t)
-                wf[slot][t] = *reinterpret_cast<const bf16x8 *>(ws + L::off((wn * TN + t) * 32 + l32, chunk));
+                wf[slot][t] = *reinterpret_cast<const h16x8 *>(ws + L::off((wn * TN + t) * 32 + l32, chunk));
         };
         load_frags(0, 0);
 #pragma unroll
@@ -180,8 +180,8 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
             for (int i = 0; i < TP; ++i)
 #pragma unroll
                 for (int j = 0; j < TQ; ++j) {
-                    if (SWAP) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[s & 1][i], wf[s & 1][j], acc[i][j], 0, 0, 0);
-                    else      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s & 1][i], xf[s & 1][j], acc[i][j], 0, 0, 0);
+                    if (SWAP) acc[i][j] = SF_MFMA16(xf[s & 1][i], wf[s & 1][j], acc[i][j], 0, 0, 0);
+                    else      acc[i][j] = SF_MFMA16(wf[s & 1][i], xf[s & 1][j], acc[i][j], 0, 0, 0);
                 }
             // pin the interleaving: MFMA, LDS read, MFMA, LDS read, ..., the global loads last
             constexpr int NMFMA = TP * TQ, NVM = LOADS ? LPS : 0;
@@ -218,7 +218,7 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
     }
 
     // ---- epilogue -------------------------------------------------------------
-    const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)p * a.bias_pstride + a.n0 : nullptr;
+    const h16 *bias = a.bias ? static_cast<const h16 *>(a.bias) + (int64_t)p * a.bias_pstride + a.n0 : nullptr;
     if (!SWAP) {
         // accumulator entry q*4+e of lane (l32, lhi): token l32, feature q*8 + lhi*4 + e.
         // After swapping halves, lanes < 32 own features [q0*8, q0*8+8) and lanes >= 32 own
@@ -243,7 +243,7 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
                     const int n = nt0 + (wn * TN + tn) * 32 + (2 * qp + lhi) * 8;
                     if (i >= a.L || n >= a.N) continue;       // N % 8 == 0: a group of 8 is all in or all out
                     if (bias) {
-                        const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(bias + n);
+                        const h16x8 bv = *reinterpret_cast<const h16x8 *>(bias + n);
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] += (float)bv[e];
                     }
@@ -257,7 +257,7 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
 #pragma unroll
                             for (int e = 0; e < 4; ++e) { v[e] += r0[e]; v[4 + e] += r1[e]; }
                         } else {
-                            const bf16x8 rv = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(a.R) + ro);
+                            const h16x8 rv = *reinterpret_cast<const h16x8 *>(static_cast<const h16 *>(a.R) + ro);
 #pragma unroll
                             for (int e = 0; e < 8; ++e) v[e] += (float)rv[e];
                         }
@@ -271,17 +271,17 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
                         *reinterpret_cast<f32x4 *>(C) = o0;
                         *reinterpret_cast<f32x4 *>(C + 4) = o1;
                     } else {
-                        bf16x8 o;
+                        h16x8 o;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
-                        *reinterpret_cast<bf16x8 *>(static_cast<__bf16 *>(a.C) + co) = o;
+                        for (int e = 0; e < 8; ++e) o[e] = (h16)v[e];
+                        *reinterpret_cast<h16x8 *>(static_cast<h16 *>(a.C) + co) = o;
                     }
                 }
             }
         }
     } else {
         // transposed store: lane owns feature n and, after the swap, 8 consecutive tokens
-        __bf16 *C = static_cast<__bf16 *>(a.C) + (int64_t)b * a.vt_b;
+        h16 *C = static_cast<h16 *>(a.C) + (int64_t)b * a.vt_b;
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const int n = nt0 + (wn * TN + tn) * 32 + l32;
@@ -301,12 +301,12 @@ void gemm_bf16_fast_kernel(GemmArgs a, int tiles_m, int tiles_n, int total_tiles
                     }
                     const int i = m0 + (wm * TM + tm) * 32 + (2 * qp + lhi) * 8;
                     if (n >= a.N || i >= a.L) continue;
-                    bf16x8 o;
+                    h16x8 o;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] = (__bf16)fact<ACT>(v[e] + bv);
-                    __bf16 *dst = C + (int64_t)n * a.vt_n + i;
+                    for (int e = 0; e < 8; ++e) o[e] = (h16)fact<ACT>(v[e] + bv);
+                    h16 *dst = C + (int64_t)n * a.vt_n + i;
                     if (i + 7 < a.L) {
-                        *reinterpret_cast<bf16x8 *>(dst) = o;       // vt_b, vt_n % 8 == 0 checked on the host
+                        *reinterpret_cast<h16x8 *>(dst) = o;       // vt_b, vt_n % 8 == 0 checked on the host
                     } else {
 #pragma unroll
                         for (int e = 0; e < 8; ++e)
@@ -323,7 +323,7 @@ static int32_t launch_fast(const GemmArgs &a, hipStream_t st)
 {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
     auto kern = gemm_bf16_fast_kernel<WAVES_M, WAVES_N, TM, TN, BKT, NSTAGE, SWAP, ACT>;
-    constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * BKT * sizeof(__bf16);
+    constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * BKT * sizeof(h16);
     static std::atomic<bool> attr_set{false};     // per template instance; setting the attribute twice is harmless
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -142,7 +142,7 @@ template <int ACT, bool F8>
 __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles_n, int total_tiles, int per_xcd)
 {
     extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);      // [NXS][X rows][128 bytes] | [NWS][W rows][128 bytes]
+    h16 *smem = reinterpret_cast<h16 *>(smem_raw);      // [NXS][X rows][128 bytes] | [NWS][W rows][128 bytes]
     constexpr int ESZ = F8 ? 1 : 2;                           // bytes per element of A and W
     constexpr int KSTEP = 128 / ESZ;                          // elements of K per ring slot
 
@@ -197,7 +197,7 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
             }
         };
         auto issue_x = [&]() {
-            __bf16 *base = smem + xs * XSLOT;
+            h16 *base = smem + xs * XSLOT;
             const int64_t koff = (int64_t)ktx * 128;
 #pragma unroll
             for (int j = 0; j < LPW; ++j)
@@ -207,7 +207,7 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
             if (++ktx == tx.nk) open_x();
         };
         auto issue_w = [&]() {
-            __bf16 *base = smem + NXS * XSLOT + wsl * WSLOT;
+            h16 *base = smem + NXS * XSLOT + wsl * WSLOT;
             const int64_t koff = (int64_t)ktw * 128;
 #pragma unroll
             for (int j = 0; j < LPW; ++j)
@@ -266,7 +266,7 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
     {
         int lb = lane;
         asm volatile("" : "+v"(lb));
-        const __bf16 *bias = a.bias ? static_cast<const __bf16 *>(a.bias) + (int64_t)tl.p * a.bias_pstride + a.n0 : nullptr;
+        const h16 *bias = a.bias ? static_cast<const h16 *>(a.bias) + (int64_t)tl.p * a.bias_pstride + a.n0 : nullptr;
         // F8: the sum of code products is multiplied by out_scale in the epilogue, so the bias enters divided by it
         const float bscale = F8 ? 1.0f / a.out_scale : 1.0f;
         if (!F8 && tl.vt) {
@@ -285,10 +285,10 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                bf16x4 bv = {};
+                h16x4 bv = {};
                 if (bias) {
                     const int n = min(tl.nt0 + wn * 64 + i * 32 + q * 8 + (lb >> 5) * 4, tl.N - 4);   // clamped: never stored
-                    bv = *reinterpret_cast<const bf16x4 *>(bias + n);
+                    bv = *reinterpret_cast<const h16x4 *>(bias + n);
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -340,8 +340,8 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
                 }
             }
         } else {
-        bf16x8 xf[TM], wf[2][TN];
-        auto rd = [&](uint32_t addr) { return *reinterpret_cast<const bf16x8 *>(smem_raw + addr); };
+        h16x8 xf[TM], wf[2][TN];
+        auto rd = [&](uint32_t addr) { return *reinterpret_cast<const h16x8 *>(smem_raw + addr); };
         {
             wf[0][0] = rd(wb); wf[0][1] = rd(wb + 4096);
 #pragma unroll
@@ -354,8 +354,8 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
             const uint32_t xa = xb ^ ((uint32_t)(s + 1) << 5), wa = wb ^ ((uint32_t)(s + 1) << 5);
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
-                acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s & 1][0], xf[j], acc[0][j], 0, 0, 0);
-                acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s & 1][1], xf[j], acc[1][j], 0, 0, 0);
+                acc[0][j] = SF_MFMA16(wf[s & 1][0], xf[j], acc[0][j], 0, 0, 0);
+                acc[1][j] = SF_MFMA16(wf[s & 1][1], xf[j], acc[1][j], 0, 0, 0);
                 if (more) {
                     xf[j] = rd(xa + j * 4096);
                     if (j < TN) wf[(s + 1) & 1][j] = rd(wa + j * 4096);
@@ -428,7 +428,7 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
             uint8_t *cp = static_cast<uint8_t *>(a.C) + (grow0 + mrow0 + tok0) * a.ldc + a.c0 + ncol0 + (ec & 3) * 16;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const i32x4 o = *reinterpret_cast<const i32x4 *>(reinterpret_cast<const __bf16 *>(stg) + lay(j * 8 + er, ec));
+                const i32x4 o = *reinterpret_cast<const i32x4 *>(reinterpret_cast<const h16 *>(stg) + lay(j * 8 + er, ec));
                 if (inside || (col_ok && j * 8 < rows_left))
                     __builtin_nontemporal_store(o, reinterpret_cast<i32x4 *>(cp + (int64_t)(j * 8) * a.ldc));
             }
@@ -463,8 +463,8 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
                         // one packed conversion per pair (written out: the compiler converts the elements of
                         // an accumulator tuple one by one and merges them with a byte permute)
                         uint2 pw;
-                        asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pw.x) : "v"(vf[0]), "v"(vf[1]));
-                        asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pw.y) : "v"(vf[2]), "v"(vf[3]));
+                        pw.x = pack2_h16(vf[0], vf[1]);
+                        pw.y = pack2_h16(vf[2], vf[3]);
                         i16x4 m = __builtin_bit_cast(i16x4, pw);
                         if (ACT == ACT_RELU) {
                             const i16x4 z = {0, 0, 0, 0};
@@ -482,16 +482,16 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
             const int er = lo >> 3, ec = lo & 7;
             const int rows_left = a.L - mrow0 - er;
             const bool col_ok = ncol0 + ec * 8 < Np;
-            __bf16 *cp = static_cast<__bf16 *>(a.C) + (grow0 + mrow0 + er) * a.ldc + a.c0 + ncol0 + ec * 8;
+            h16 *cp = static_cast<h16 *>(a.C) + (grow0 + mrow0 + er) * a.ldc + a.c0 + ncol0 + ec * 8;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int r = half * 64 + j * 8;                            // uniform
-                const bf16x8 o = *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const __bf16 *>(stg) + lay(j * 8 + er, ec));
+                const h16x8 o = *reinterpret_cast<const h16x8 *>(reinterpret_cast<const h16 *>(stg) + lay(j * 8 + er, ec));
                 if (!F8 && tl.vt) {
                     const int n = tl.nt0 + wnv * 128 + r + er, i = tl.m0 + wmv * 64 + ec * 8;
-                    __bf16 *dst = static_cast<__bf16 *>(a.VT) + (int64_t)tl.b * a.vt_b + (int64_t)(n - a.vt_from) * a.vt_n + i;
+                    h16 *dst = static_cast<h16 *>(a.VT) + (int64_t)tl.b * a.vt_b + (int64_t)(n - a.vt_from) * a.vt_n + i;
                     if (n < Np && i + 7 < a.L) {
-                        __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(dst));
+                        __builtin_nontemporal_store(o, reinterpret_cast<h16x8 *>(dst));
                     } else if (n < Np) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e)
@@ -499,7 +499,7 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
                     }
                 } else if (inside || (col_ok && r < rows_left))
                     // streamed out: the output is far larger than L2 and must not push the weights out of it
-                    __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(cp + (int64_t)r * a.ldc));
+                    __builtin_nontemporal_store(o, reinterpret_cast<h16x8 *>(cp + (int64_t)r * a.ldc));
             }
         }
     } else {
@@ -541,10 +541,10 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
                         if (a.c_f32) {
                             __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(static_cast<float *>(a.C) + co));
                         } else {
-                            bf16x4 o;
+                            h16x4 o;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
-                            __builtin_nontemporal_store(o, reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(a.C) + co));
+                            for (int e = 0; e < 4; ++e) o[e] = (h16)v[e];
+                            __builtin_nontemporal_store(o, reinterpret_cast<h16x4 *>(static_cast<h16 *>(a.C) + co));
                         }
                     }
                 };
@@ -563,10 +563,10 @@ __device__ __forceinline__ void ws_body(const GemmArgs a, int tiles_m, int tiles
                         finish(j, v);
                     }
                 } else if (a.R) {
-                    bf16x4 rr[8];
+                    h16x4 rr[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        rr[j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(static_cast<const __bf16 *>(a.R) + rrow(j)));
+                        rr[j] = __builtin_nontemporal_load(reinterpret_cast<const h16x4 *>(static_cast<const h16 *>(a.R) + rrow(j)));
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         f32x4 v = *reinterpret_cast<const f32x4 *>(stf + lay(j * 8 + er, ec) / 2);
@@ -605,7 +605,7 @@ template <int ACT, bool F8>
 static int32_t launch_ws(const GemmArgs &a, hipStream_t st)
 {
     auto kern = F8 ? gemm_fp8_ws_kernel<ACT> : gemm_bf16_ws_kernel<ACT>;
-    constexpr size_t lds = ((size_t)NXS * XSLOT + (size_t)NWS * WSLOT) * sizeof(__bf16);     // 160 KB
+    constexpr size_t lds = ((size_t)NXS * XSLOT + (size_t)NWS * WSLOT) * sizeof(h16);     // 160 KB
     static std::atomic<bool> attr_set{false};     // per template instance; setting the attribute twice is harmless
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -120,7 +120,7 @@ __device__ __forceinline__ void load8(const TP *p, int off, float fill, float (&
 #pragma unroll
         for (int e = 0; e < 8; ++e) out[e] = fill;
     } else if constexpr (sizeof(TP) == 2) {
-        const bf16x8 t = *reinterpret_cast<const bf16x8 *>(p + off);
+        const h16x8 t = *reinterpret_cast<const h16x8 *>(p + off);
 #pragma unroll
         for (int e = 0; e < 8; ++e) out[e] = (float)t[e];
     } else {
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const TI *x, const T
         const int ch = lane + c * 64;
         if (ch < nch) {
             if constexpr (sizeof(TI) == 2) {
-                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(xr + ch * 8);
+                const h16x8 t = *reinterpret_cast<const h16x8 *>(xr + ch * 8);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[c][e] = (float)t[e];
             } else {
@@ -190,10 +190,10 @@ __global__ __launch_bounds__(256) void layernorm_vec_kernel(const TI *x, const T
 #pragma unroll
         for (int e = 0; e < 8; ++e) z[e] = (v[c][e] - mean) * inv * gm[e] + bt[e];
         if constexpr (sizeof(TO) == 2) {
-            bf16x8 o;
+            h16x8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (__bf16)z[e];
-            *reinterpret_cast<bf16x8 *>(yr + ch * 8) = o;
+            for (int e = 0; e < 8; ++e) o[e] = (h16)z[e];
+            *reinterpret_cast<h16x8 *>(yr + ch * 8) = o;
         } else {
             f32x4 o0, o1;
 #pragma unroll
@@ -223,8 +223,8 @@ void layernorm(int dtype, int x_f32, const void *x, const void *gamma, const voi
                int64_t rows, int d, void *y, hipStream_t st)
 {
     if (rows <= 0) return;
-    if (dtype == SF_BF16 && !x_f32) launch_ln<__bf16, __bf16, __bf16>(x, gamma, beta, eps, rows, d, y, st);
-    else if (dtype == SF_BF16) launch_ln<float, __bf16, __bf16>(x, gamma, beta, eps, rows, d, y, st);
+    if (dtype == SF_BF16 && !x_f32) launch_ln<h16, h16, h16>(x, gamma, beta, eps, rows, d, y, st);
+    else if (dtype == SF_BF16) launch_ln<float, h16, h16>(x, gamma, beta, eps, rows, d, y, st);
     else launch_ln<float, float, float>(x, gamma, beta, eps, rows, d, y, st);
 }
 

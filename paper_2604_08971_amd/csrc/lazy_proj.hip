@@ -71,54 +71,54 @@ __global__ __launch_bounds__(256) void rows_active_place_kernel(const int32_t *_
 }
 
 // 8 consecutive context values of head h (group g of sample b), rounded to bf16 as the attention output stores them
-__device__ __forceinline__ bf16x8 ctx8(const float *__restrict__ stats, int b, int nG, int g, int dh, int e0)
+__device__ __forceinline__ h16x8 ctx8(const float *__restrict__ stats, int b, int nG, int g, int dh, int e0)
 {
     const float *c = stats + (((int64_t)b * nG + g) * 2 + 1) * dh + e0;
-    bf16x8 o;
+    h16x8 o;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) o[t] = (__bf16)c[t];
+    for (int t = 0; t < 8; ++t) o[t] = (h16)c[t];
     return o;
 }
 
 // One wave per compact row: the attention output of an active row - its active heads from `att`, its lazy heads from
 // the context vectors - or a zero row behind n_act[b].  K = nH*dh, a multiple of 8; dh a multiple of 8.
-__global__ __launch_bounds__(256) void att_compact_kernel(const __bf16 *__restrict__ att, int64_t ldo,
+__global__ __launch_bounds__(256) void att_compact_kernel(const h16 *__restrict__ att, int64_t ldo,
                                                           const int32_t *__restrict__ slot, const float *__restrict__ stats,
                                                           const int32_t *__restrict__ head_group, int hg_stride,
                                                           const int32_t *__restrict__ pattern_id,
                                                           const int32_t *__restrict__ arow, const int32_t *__restrict__ n_act,
                                                           int B, int nH, int nG, int L, int dh, int capA,
-                                                          __bf16 *__restrict__ Ac)
+                                                          h16 *__restrict__ Ac)
 {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= (int64_t)B * capA) return;
     const int b = (int)(r / capA), j = (int)(r % capA);
     const int K = nH * dh;
-    __bf16 *dst = Ac + r * K;
+    h16 *dst = Ac + r * K;
     if (j >= n_act[b]) {
-        const bf16x8 z = {};
-        for (int c = lane; c < K / 8; c += 64) *reinterpret_cast<bf16x8 *>(dst + c * 8) = z;
+        const h16x8 z = {};
+        for (int c = lane; c < K / 8; c += 64) *reinterpret_cast<h16x8 *>(dst + c * 8) = z;
         return;
     }
     const int i = arow[r];
     const int p = pattern_id ? pattern_id[b] : 0;
     for (int c = lane; c < K / 8; c += 64) {
         const int h = (c * 8) / dh, e0 = (c * 8) % dh;
-        bf16x8 v;
+        h16x8 v;
         if (slot[((int64_t)b * nH + h) * L + i] >= 0)
-            v = *reinterpret_cast<const bf16x8 *>(att + ((int64_t)b * L + i) * ldo + c * 8);
+            v = *reinterpret_cast<const h16x8 *>(att + ((int64_t)b * L + i) * ldo + c * 8);
         else
             v = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
-        *reinterpret_cast<bf16x8 *>(dst + c * 8) = v;
+        *reinterpret_cast<h16x8 *>(dst + c * 8) = v;
     }
 }
 
 // One wave per (sample, output feature n): c[b, n] = sum_k bf16(ctx_b[k]) WoT[p_b][n, k] + bo[n], fp32.
 __global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__ stats, const int32_t *__restrict__ head_group,
                                                        int hg_stride, const int32_t *__restrict__ pattern_id,
-                                                       const __bf16 *__restrict__ WoT, int64_t w_pstride,
-                                                       const __bf16 *__restrict__ bo, int B, int nH, int nG, int dh,
+                                                       const h16 *__restrict__ WoT, int64_t w_pstride,
+                                                       const h16 *__restrict__ bo, int B, int nH, int nG, int dh,
                                                        int d, float *__restrict__ cvec)
 {
     const int lane = threadIdx.x & 63;
@@ -127,12 +127,12 @@ __global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__
     const int b = (int)(r / d), n = (int)(r % d);
     const int p = pattern_id ? pattern_id[b] : 0;
     const int K = nH * dh;
-    const __bf16 *w = WoT + (int64_t)p * w_pstride + (int64_t)n * K;
+    const h16 *w = WoT + (int64_t)p * w_pstride + (int64_t)n * K;
     float acc = 0.f;
     for (int c = lane; c < K / 8; c += 64) {
         const int h = (c * 8) / dh, e0 = (c * 8) % dh;
-        const bf16x8 x = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
-        const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(w + c * 8);
+        const h16x8 x = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
+        const h16x8 wv = *reinterpret_cast<const h16x8 *>(w + c * 8);
 #pragma unroll
         for (int t = 0; t < 8; ++t) acc = fmaf((float)x[t], (float)wv[t], acc);
     }
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__
 __global__ __launch_bounds__(256) void ctx_proj_q8_kernel(const float *__restrict__ stats, const int32_t *__restrict__ head_group,
                                                           int hg_stride, const int32_t *__restrict__ pattern_id,
                                                           const uint8_t *__restrict__ WoT8, int64_t w_pstride, int ldw,
-                                                          const __bf16 *__restrict__ bo, int B, int nH, int nG, int dh,
+                                                          const h16 *__restrict__ bo, int B, int nH, int nG, int dh,
                                                           int d, float inv_sa, float out_scale, float *__restrict__ cvec)
 {
     const int lane = threadIdx.x & 63;
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void ctx_proj_q8_kernel(const float *__restric
     float acc = 0.f;
     for (int c = lane; c < K / 8; c += 64) {
         const int h = (c * 8) / dh, e0 = (c * 8) % dh;
-        const bf16x8 x = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
+        const h16x8 x = ctx8(stats, b, nG, head_group[(int64_t)p * hg_stride + h], dh, e0);
         const uint2 wv = *reinterpret_cast<const uint2 *>(w + c * 8);
         const uint32_t q0 = e4m3_pack4((float)x[0] * inv_sa, (float)x[1] * inv_sa, (float)x[2] * inv_sa, (float)x[3] * inv_sa);
         const uint32_t q1 = e4m3_pack4((float)x[4] * inv_sa, (float)x[5] * inv_sa, (float)x[6] * inv_sa, (float)x[7] * inv_sa);
@@ -179,9 +179,9 @@ __global__ __launch_bounds__(256) void ctx_proj_q8_kernel(const float *__restric
 // arithmetic.  d % 8 == 0, d <= 512 * NCH.
 template <class TI, int NCH, bool Q8>
 __global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ x, const int32_t *__restrict__ pos_of,
-                                                         const float *__restrict__ Cc, const __bf16 *__restrict__ bo,
+                                                         const float *__restrict__ Cc, const h16 *__restrict__ bo,
                                                          const float *__restrict__ cvec, int L, int capA,
-                                                         const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ beta,
+                                                         const h16 *__restrict__ gamma, const h16 *__restrict__ beta,
                                                          float eps, int64_t rows, int d, float *__restrict__ x1,
                                                          void *__restrict__ xn_out, float q_inv)
 {
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ 
         const int ch = lane + c * 64;
         if (ch < nch) {
             if constexpr (sizeof(TI) == 2) {
-                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(xr + ch * 8);
+                const h16x8 t = *reinterpret_cast<const h16x8 *>(xr + ch * 8);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[c][e] = (float)t[e];
             } else {
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ 
             const f32x4 a1 = *reinterpret_cast<const f32x4 *>(add + ch * 8 + 4);
             float bb[8];
             if (j >= 0 && bo) {
-                const bf16x8 t = *reinterpret_cast<const bf16x8 *>(bo + ch * 8);
+                const h16x8 t = *reinterpret_cast<const h16x8 *>(bo + ch * 8);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) bb[e] = (float)t[e];
             } else {
@@ -254,16 +254,16 @@ __global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ 
     for (int c = 0; c < NCH; ++c) {
         const int ch = lane + c * 64;
         if (ch >= nch) continue;
-        bf16x8 gm, bt, o;
+        h16x8 gm, bt, o;
         float z[8];
-        if (gamma) gm = *reinterpret_cast<const bf16x8 *>(gamma + ch * 8);
-        if (beta) bt = *reinterpret_cast<const bf16x8 *>(beta + ch * 8);
+        if (gamma) gm = *reinterpret_cast<const h16x8 *>(gamma + ch * 8);
+        if (beta) bt = *reinterpret_cast<const h16x8 *>(beta + ch * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             z[e] = (v[c][e] - mean) * inv;
             if (gamma) z[e] *= (float)gm[e];
             if (beta) z[e] += (float)bt[e];
-            o[e] = (__bf16)z[e];
+            o[e] = (h16)z[e];
         }
         if constexpr (Q8) {
             uint2 q;
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void combine_ln_kernel(const TI *__restrict__ 
             q.y = e4m3_pack4(z[4] * q_inv, z[5] * q_inv, z[6] * q_inv, z[7] * q_inv);
             *reinterpret_cast<uint2 *>(static_cast<uint8_t *>(xn_out) + row * d + ch * 8) = q;
         } else {
-            *reinterpret_cast<bf16x8 *>(static_cast<__bf16 *>(xn_out) + row * d + ch * 8) = o;
+            *reinterpret_cast<h16x8 *>(static_cast<h16 *>(xn_out) + row * d + ch * 8) = o;
         }
     }
 }
@@ -303,8 +303,8 @@ void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const f
                       int nG, int L, int dh, int capA, void *Ac, hipStream_t st)
 {
     const int64_t rows = (int64_t)B * capA;
-    hipLaunchKernelGGL(att_compact_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, (const __bf16 *)att, ldo,
-                       slot, stats, head_group, hg_stride, pattern_id, arow, n_act, B, nH, nG, L, dh, capA, (__bf16 *)Ac);
+    hipLaunchKernelGGL(att_compact_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, (const h16 *)att, ldo,
+                       slot, stats, head_group, hg_stride, pattern_id, arow, n_act, B, nH, nG, L, dh, capA, (h16 *)Ac);
 }
 
 void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
@@ -313,7 +313,7 @@ void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride,
 {
     const int64_t rows = (int64_t)B * d;
     hipLaunchKernelGGL(ctx_proj_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, stats, head_group, hg_stride,
-                       pattern_id, (const __bf16 *)WoT, w_pstride, (const __bf16 *)bo, B, nH, nG, dh, d, cvec);
+                       pattern_id, (const h16 *)WoT, w_pstride, (const h16 *)bo, B, nH, nG, dh, d, cvec);
 }
 
 void lazy_ctx_proj_q8(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
@@ -322,7 +322,7 @@ void lazy_ctx_proj_q8(const float *stats, const int32_t *head_group, int hg_stri
 {
     const int64_t rows = (int64_t)B * d;
     hipLaunchKernelGGL(ctx_proj_q8_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, stats, head_group, hg_stride,
-                       pattern_id, (const uint8_t *)WoT8, w_pstride, ldw, (const __bf16 *)bo, B, nH, nG, dh, d, inv_sa, out_scale,
+                       pattern_id, (const uint8_t *)WoT8, w_pstride, ldw, (const h16 *)bo, B, nH, nG, dh, d, inv_sa, out_scale,
                        cvec);
 }
 
@@ -333,8 +333,8 @@ void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const flo
     // q_inv > 0: xn receives E4M3 codes of LN(x1) * q_inv (one byte per element) instead of bf16
     const int64_t rows = (int64_t)B * L;
     dim3 grid((unsigned)((rows + 3) / 4));
-#define SF_CLN_ARGS(TI) grid, dim3(256), 0, st, (const TI *)x, pos_of, Cc, (const __bf16 *)bo, cvec, L, capA, \
-                        (const __bf16 *)gamma, (const __bf16 *)beta, eps, rows, d, x1, xn, q_inv
+#define SF_CLN_ARGS(TI) grid, dim3(256), 0, st, (const TI *)x, pos_of, Cc, (const h16 *)bo, cvec, L, capA, \
+                        (const h16 *)gamma, (const h16 *)beta, eps, rows, d, x1, xn, q_inv
 #define SF_CLN_LAUNCH(TI, Q)                                                                            \
     do {                                                                                                \
         if (d <= 512) hipLaunchKernelGGL((combine_ln_kernel<TI, 1, Q>), SF_CLN_ARGS(TI));               \
@@ -342,9 +342,9 @@ void lazy_combine_ln(const void *x, bool x_f32, const int32_t *pos_of, const flo
         else hipLaunchKernelGGL((combine_ln_kernel<TI, 4, Q>), SF_CLN_ARGS(TI));                        \
     } while (0)
     if (q_inv > 0.f) {
-        if (x_f32) SF_CLN_LAUNCH(float, true); else SF_CLN_LAUNCH(__bf16, true);
+        if (x_f32) SF_CLN_LAUNCH(float, true); else SF_CLN_LAUNCH(h16, true);
     } else {
-        if (x_f32) SF_CLN_LAUNCH(float, false); else SF_CLN_LAUNCH(__bf16, false);
+        if (x_f32) SF_CLN_LAUNCH(float, false); else SF_CLN_LAUNCH(h16, false);
     }
 #undef SF_CLN_LAUNCH
 #undef SF_CLN_ARGS

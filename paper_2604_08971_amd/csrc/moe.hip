@@ -33,16 +33,12 @@ template <> struct Vec16<float> {
         v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3];
     }
 };
-template <> struct Vec16<__bf16> {
+template <> struct Vec16<h16> {
     static constexpr int N = 8;
-    static __device__ void load(const __bf16 *p, float (&v)[8]) {
-        const uint4 q = *reinterpret_cast<const uint4 *>(p);
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    static __device__ void load(const h16 *p, float (&v)[8]) {
+        const h16x8 q = *reinterpret_cast<const h16x8 *>(p);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
+        for (int i = 0; i < 8; ++i) v[i] = (float)q[i];
     }
 };
 
@@ -82,8 +78,7 @@ __global__ __launch_bounds__(256) void moe_router_kernel(
         for (int e = 0; e < EB; ++e) acc[e] = 0.f;
         for (int c = lane * VN; c < d; c += 64 * VN) {
             if constexpr (VN == 8) {
-                // bf16: two products per instruction, fp32 accumulate, no unpacking
-                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                // 16-bit: two products per instruction, fp32 accumulate, no unpacking
                 const uint4 xq = *reinterpret_cast<const uint4 *>(x + c);
                 const uint32_t xw[4] = {xq.x, xq.y, xq.z, xq.w};
 #pragma unroll
@@ -93,8 +88,7 @@ __global__ __launch_bounds__(256) void moe_router_kernel(
                         const uint32_t ww[4] = {wq.x, wq.y, wq.z, wq.w};
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            acc[e] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xw[i]),
-                                                                     __builtin_bit_cast(bf16x2, ww[i]), acc[e], false);
+                            acc[e] = SF_FDOT2(__builtin_bit_cast(h16x2, xw[i]), __builtin_bit_cast(h16x2, ww[i]), acc[e], false);
                     }
                 }
             } else {
@@ -371,7 +365,7 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const T *__restrict__ 
             uint32_t *ow = reinterpret_cast<uint32_t *>(&o);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const __bf16 lo = from_f32<__bf16>(acc[2 * e]), hi = from_f32<__bf16>(acc[2 * e + 1]);
+                const h16 lo = from_f32<h16>(acc[2 * e]), hi = from_f32<h16>(acc[2 * e + 1]);
                 ow[e] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
             }
             *reinterpret_cast<uint4 *>(Y + t * d + c) = o;
@@ -488,9 +482,9 @@ extern "C" int32_t sf_moe_ffn_forward(const sf_desc *desc, const sf_moe_compact 
                                logit_out);                                                                            \
     } while (0)
         if (bf) {
-            if (E <= 8) SF_ROUTER(__bf16, 8);
-            else if (E <= 16) SF_ROUTER(__bf16, 16);
-            else SF_ROUTER(__bf16, 64);
+            if (E <= 8) SF_ROUTER(h16, 8);
+            else if (E <= 16) SF_ROUTER(h16, 16);
+            else SF_ROUTER(h16, 64);
         } else {
             if (E <= 8) SF_ROUTER(float, 8);
             else if (E <= 16) SF_ROUTER(float, 16);
@@ -541,8 +535,8 @@ extern "C" int32_t sf_moe_ffn_forward(const sf_desc *desc, const sf_moe_compact 
     {
         dim3 grid((unsigned)((rows + 3) / 4));
         if (bf)
-            hipLaunchKernelGGL(moe_combine_kernel<__bf16>, grid, dim3(256), 0, st, (const __bf16 *)X, w.yg, w.pos,
-                               w.weight, rows, D.d, k, add_residual, (__bf16 *)Y);
+            hipLaunchKernelGGL(moe_combine_kernel<h16>, grid, dim3(256), 0, st, (const h16 *)X, w.yg, w.pos,
+                               w.weight, rows, D.d, k, add_residual, (h16 *)Y);
         else
             hipLaunchKernelGGL(moe_combine_kernel<float>, grid, dim3(256), 0, st, (const float *)X, w.yg, w.pos,
                                w.weight, rows, D.d, k, add_residual, (float *)Y);

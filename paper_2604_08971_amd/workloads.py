@@ -26,6 +26,20 @@ def to_bf16_values(a: np.ndarray) -> np.ndarray:
     return u.astype(np.uint32).view(np.float32).reshape(a.shape)
 
 
+def to_f16_values(a: np.ndarray) -> np.ndarray:
+    """Return fp32 array whose values are the nearest IEEE binary16 numbers (ties to even)."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def storage_rounding(dtype: str):
+    """The map that makes an fp32 array hold values of the model's storage type ("f32", "bf16" or "f16")."""
+    if dtype == "bf16":
+        return to_bf16_values
+    if dtype == "f16":
+        return to_f16_values
+    return lambda a: np.ascontiguousarray(a, dtype=np.float32)
+
+
 def bf16_bits(a: np.ndarray) -> np.ndarray:
     """uint16 bit patterns of an fp32 array that already holds bf16 values."""
     a = np.ascontiguousarray(a, dtype=np.float32)
@@ -41,7 +55,7 @@ def keep_count(ratio: float, n: int) -> int:
 class Spec:
     """Shape of one workload (the five named ones are in CONFIGS)."""
     name: str
-    dtype: str                      # "f32" | "bf16"
+    dtype: str                      # "f32" | "bf16" | "f16" (the FP16 build of the library)
     B: int
     seg_tokens: Sequence[int]       # tokens per modality, in sequence order
     extra_tokens: int               # always-present fusion tokens at the end
@@ -153,8 +167,7 @@ def make_workload(spec: Spec, B: Optional[int] = None, affine_noise: bool = True
     B = spec.B if B is None else int(B)
     L, d, M = spec.L, spec.d, spec.M
     Hq, Hk, dh, F, nl = spec.Hq, spec.Hk, spec.dh, spec.F, spec.n_layers
-    bf16 = spec.dtype == "bf16"
-    q = to_bf16_values if bf16 else (lambda a: np.ascontiguousarray(a, dtype=np.float32))
+    q = storage_rounding(spec.dtype)
     seed = spec.seed
 
     tok_mod = np.concatenate(
@@ -242,7 +255,7 @@ def make_moe_block(wl: Workload, E: int, top_k: int, keep=(0.4, 0.8), seed_offse
     logits are O(1); expert weights as the FFN of make_workload; keep ratios U(keep) per expert."""
     spec = wl.spec
     d, F, M = spec.d, spec.F, spec.M
-    q = to_bf16_values if spec.dtype == "bf16" else (lambda a: np.ascontiguousarray(a, dtype=np.float32))
+    q = storage_rounding(spec.dtype)
     r = _rng(spec.seed, seed_offset)
     sd, sF = np.float32(1.0 / math.sqrt(d)), np.float32(1.0 / math.sqrt(F))
     dense = {

@@ -13,6 +13,11 @@ from paper_2604_08971_amd import binding as sf
 from paper_2604_08971_amd import workloads as W
 
 
+SF_DTYPE = {"f32": sf.SF_F32, "bf16": sf.SF_BF16, "f16": sf.SF_F16}
+# the oracle's storage-rounding mode of each model dtype
+ORACLE_MODE = {"f32": 0, "bf16": 1, "f16": 2}
+
+
 def to_dev(a: Optional[np.ndarray], dtype: str, device="cuda") -> Optional[torch.Tensor]:
     """fp32 host array (bf16-valued when dtype == 'bf16') -> device tensor of the path's dtype."""
     if a is None:
@@ -20,12 +25,14 @@ def to_dev(a: Optional[np.ndarray], dtype: str, device="cuda") -> Optional[torch
     t = torch.from_numpy(np.ascontiguousarray(a))
     if t.dtype == torch.float32 and dtype == "bf16":
         t = t.to(torch.bfloat16)          # exact: the values are bf16 numbers already
+    if t.dtype == torch.float32 and dtype == "f16":
+        t = t.to(torch.float16)           # exact as well
     return t.to(device).contiguous()
 
 
 def to_host(t: torch.Tensor) -> np.ndarray:
     t = t.detach()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         t = t.to(torch.float32)
     return t.cpu().numpy()
 
@@ -35,7 +42,7 @@ def desc_for(wl: W.Workload, B: Optional[int] = None, U_override: int = -1, c: O
     s = wl.spec
     return sf.make_desc(B=wl.x.shape[0] if B is None else B, L=s.L, d_model=s.d, Hq=s.Hq, Hk=s.Hk, dh=s.dh,
                         d_ff=s.F, n_layers=s.n_layers, P=wl.P,
-                        dtype=sf.SF_BF16 if s.dtype == "bf16" else sf.SF_F32, act=s.act,
+                        dtype=SF_DTYPE[s.dtype], act=s.act,
                         c_factor=s.c if c is None else c, U_override=U_override,
                         final_ln=wl.final_ln is not None, n_sample=n_sample)
 

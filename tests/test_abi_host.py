@@ -23,6 +23,17 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert hasattr(L, name), name
     assert sorted(sf.EXPORTS) == declared
+    # the FP16 build of the same sources exports the same entry points
+    with sf.use_half("f16"):
+        L16 = sf.lib()
+        assert L16 is not L
+        for name in declared:
+            assert hasattr(L16, name), name
+        # each build takes 16-bit models of its own type only (checked on the host, before any launch)
+        d16, dbf = sf.make_desc(1, 64, 64, 4, 2, 16, 128, dtype=sf.SF_F16), sf.make_desc(1, 64, 64, 4, 2, 16, 128, dtype=sf.SF_BF16)
+        assert L16.sf_num_active(C.byref(d16)) > 0 and L16.sf_num_active(C.byref(dbf)) == -3
+        assert L.sf_num_active(C.byref(dbf)) > 0 and L.sf_num_active(C.byref(d16)) == -3
+        assert L16.sf_num_active(C.byref(sf.make_desc(1, 64, 64, 4, 2, 16, 128, dtype=sf.SF_F32))) > 0
 
 
 def test_struct_layout_matches_header():

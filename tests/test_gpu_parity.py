@@ -18,14 +18,14 @@ import torch
 from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import binding as sf
 from paper_2604_08971_amd import workloads as W
-from gpu_utils import DeviceModel, selection_report, to_dev, to_host
+from gpu_utils import ORACLE_MODE, SF_DTYPE, DeviceModel, selection_report, to_dev, to_host
 from helpers import compact_packs, compact_weights, err_metric, oracle_masks
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
-EPS_SEL_OP = {"f32": 1e-5, "bf16": 1e-4}       # sparse_gqa_forward on identical inputs
-EPS_SEL_ENC = {"f32": 1e-5, "bf16": 2e-2}      # inside the encoder (inputs differ by bf16 rounding)
+TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
+EPS_SEL_OP = {"f32": 1e-5, "bf16": 1e-4, "f16": 1e-4}       # sparse_gqa_forward on identical inputs
+EPS_SEL_ENC = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}      # inside the encoder (inputs differ by 16-bit rounding)
 
 
 def _say(msg):
@@ -313,21 +313,21 @@ def test_budget_search_ties_and_signs():
 
 
 # -------------------------------------------------- Sparse-MoE FFN with pruned experts (Sec. 4.5)
-EPS_ROUTE = {"f32": 1e-5, "bf16": 2e-2}
+EPS_ROUTE = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
 
 
 def _moe_case(wl, E, top_k, forced=False, pre_ln=True, add_residual=True, sample_rows=None):
     s = wl.spec
-    dtype, bf = s.dtype, s.dtype == "bf16"
+    dtype, bf = s.dtype, ORACLE_MODE[s.dtype]
     mb = W.make_moe_block(wl, E, top_k)
     B, L, d, F, P = wl.x.shape[0], s.L, s.d, s.F, wl.P
     # keep sets of the experts: the mask kernel with "layer" = expert
-    dm = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=E, P=P, dtype=sf.SF_BF16 if bf else sf.SF_F32, act=s.act)
+    dm = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=E, P=P, dtype=SF_DTYPE[dtype], act=s.act)
     g_head = np.zeros((E, P, 8), np.float32)
     masks = sf.gate_scores_to_masks(dm, to_dev(g_head, "f32"), to_dev(mb.g_ffn, "f32"), [1] * E, mb.k_ffn.tolist())
     ref = orc.gate_scores_to_masks(g_head, mb.g_ffn, np.ones(E, np.int32), mb.k_ffn, 2)
     assert np.array_equal(to_host(masks["ffn_idx"]), ref["ffn_idx"]) and np.array_equal(to_host(masks["ffn_mask"]), ref["ffn_mask"])
-    desc = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=1, P=P, dtype=sf.SF_BF16 if bf else sf.SF_F32, act=s.act)
+    desc = sf.make_desc(B, L, d, 8, 2, 8, F, n_layers=1, P=P, dtype=SF_DTYPE[dtype], act=s.act)
     dense_dev = {k: to_dev(v, dtype) for k, v in mb.dense.items()}
     cm = sf.compact_moe_experts(desc, dense_dev, masks["ffn_idx"], top_k, mb.k_ffn.tolist())
     torch.cuda.synchronize()
@@ -477,7 +477,7 @@ def test_moe_single_expert_equals_pruned_ffn():
 def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=False, forced=False,
               v_transposed=False, strided=False, n_sample=0):
     rng = np.random.default_rng(seed)
-    q = W.to_bf16_values if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    q = W.storage_rounding(dtype)
     Q = q(rng.standard_normal((B, nH, L, dh)).astype(np.float32))
     K = q(rng.standard_normal((B, nG, L, dh)).astype(np.float32))
     V = q(rng.standard_normal((B, nG, L, dh)).astype(np.float32))
@@ -494,8 +494,7 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
             kv[1] = 0
             kv[1, [1, L // 2, L - 1]] = 1        # fewer allowed queries than U
     # Hq/Hk of the descriptor describe the dense model and are not used by this entry point
-    desc = sf.make_desc(B, L, 64, 8, 2, dh, 64, dtype=sf.SF_BF16 if dtype == "bf16" else sf.SF_F32,
-                        U_override=U_override, n_sample=n_sample)
+    desc = sf.make_desc(B, L, 64, 8, 2, dh, 64, dtype=SF_DTYPE[dtype], U_override=U_override, n_sample=n_sample)
     U = sf.num_active(desc)
     samp = None
     if n_sample:
@@ -520,8 +519,7 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
                 fs[b, h, :n] = np.sort(rng.choice(L, n, replace=False))
     # device tensors (optionally as strided views of a token-major buffer, V transposed)
     if strided:
-        buf = torch.zeros((B, L, (nH + 2 * nG) * dh), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32,
-                          device="cuda")
+        buf = torch.zeros((B, L, (nH + 2 * nG) * dh), dtype=to_dev(Q[:1, :1, :1], dtype).dtype, device="cuda")
         buf[:, :, :nH * dh] = to_dev(Q, dtype).permute(0, 2, 1, 3).reshape(B, L, nH * dh)
         buf[:, :, nH * dh:(nH + nG) * dh] = to_dev(K, dtype).permute(0, 2, 1, 3).reshape(B, L, nG * dh)
         buf[:, :, (nH + nG) * dh:] = to_dev(V, dtype).permute(0, 2, 1, 3).reshape(B, L, nG * dh)
@@ -541,7 +539,7 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
     torch.cuda.synchronize()
     O, sel, score = to_host(O), to_host(sel), to_host(score)
 
-    bf = dtype == "bf16"
+    bf = ORACLE_MODE[dtype]
     _, M_ref, sel_ref, _ = orc.sparse_gqa(Q, K, V, hg[0], U, kv, fs, bf, hgb, sample_idx=samp)
     n_diff = 0
     if not forced:
@@ -694,6 +692,10 @@ def test_sparse_gqa_is_deterministic():
 ])
 def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
     _say(f"ffn {dtype} act={act} B={B} L={L} d={d} F={F}")
+    _ffn_case(dtype, act, B, L, d, F, keep)
+
+
+def _ffn_case(dtype, act, B, L, d, F, keep):
     spec = W.small_spec(dtype=dtype, B=B, seg=(L - 1,), extra=1, d=d, Hq=2, Hk=1, dh=32, F=F, nl=1,
                         head_keep=1.0, ffn_keep=keep, dropout="none", final_ln=False, act=act, seed=L + F)
     wl = W.make_workload(spec)
@@ -712,7 +714,7 @@ def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
         packs = compact_packs(wl, masks)
         for b in range(B):
             ref = orc.pruned_ffn(packs[0][wl.pattern_id[b]], wl.x[b], act=act, pre_ln=pre_ln,
-                                 add_residual=res, bf16=dtype == "bf16")
+                                 add_residual=res, bf16=ORACLE_MODE[dtype])
             e = err_metric(Y[b], ref)
             assert e <= TOL[dtype], (b, pre_ln, e)
 
@@ -720,7 +722,7 @@ def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
 # ------------------------------------------------------------ a10: encoder
 def _encoder_parity(wl, samples=None, U_override=-1, max_pick_diff_frac=0.03, sample_idx=None):
     s = wl.spec
-    bf = s.dtype == "bf16"
+    bf = ORACLE_MODE[s.dtype]
     dm = DeviceModel(wl, U_override=U_override, sample_idx=sample_idx).build_plan()
     U = sf.num_active(dm.desc)
     ref_masks = oracle_masks(wl)
