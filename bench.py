@@ -680,6 +680,9 @@ def main():
     ap.add_argument("--ffn-fp8-only", action="store_true",
                     help="time only the FP8-arithmetic FFN block (and its bf16 twin) on the workload's tokens and "
                          "print its object (for profiling)")
+    ap.add_argument("--f16-only", action="store_true",
+                    help="time only the step of the FP16 build of the library on the workload and print its object "
+                         "(for profiling)")
     ap.add_argument("--tokens-only", action="store_true",
                     help="time only the token-compaction comparison on the dropout workload C3 and print its object")
     ap.add_argument("--moe-only", action="store_true",
@@ -709,6 +712,10 @@ def main():
         wl = W.make_workload(W.CONFIGS[args.config])
         dm = DeviceModel(wl).build_plan()
         print(json.dumps(bench_ffn_fp8(wl, dm, args.steps, args.warmup)), flush=True)
+        return
+
+    if args.f16_only:
+        print(json.dumps(bench_f16(W.make_workload(W.CONFIGS[args.config]), args.steps, args.warmup)), flush=True)
         return
 
     if args.copy_calibration > 0:
