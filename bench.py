@@ -37,8 +37,8 @@ GEMM_KERNEL_NAMES = {
 # HBM-side bytes per launch, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs) and scaled by the
 # reading of the same counters for a plain 256 MiB device copy; the runs are summarised under profiles/.
 MEASURED_TRAFFIC = {
-    ("C5", "ffn_up"): 665.8e6,        # 368.6 MB fetched + 297.2 MB written; algorithmic 104.0 MB read + 281.8 MB written
-    ("C5", "ffn_down"): 694.3e6,      # 588.8 MB fetched + 105.5 MB written; algorithmic 486.4 MB read + 100.7 MB written
+    ("C5", "ffn_up"): 668.0e6,        # 371.0 MB fetched + 297.0 MB written; algorithmic 104.0 MB read + 281.8 MB written
+    ("C5", "ffn_down"): 694.8e6,      # 589.3 MB fetched + 105.6 MB written; algorithmic 486.4 MB read + 100.7 MB written
 }
 
 
