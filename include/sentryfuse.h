@@ -34,8 +34,12 @@
  *    It is served by a second build of these sources, libsentryfuse_f16.so
  *    (same entry points); libsentryfuse.so takes SF_F32 and SF_BF16 models,
  *    libsentryfuse_f16.so SF_F32 and SF_F16 models, the other 16-bit type
- *    returns SF_ERR_UNSUPPORTED.  The FP8 entry points (E4M3-stored weights,
- *    FP8 arithmetic) are built for bf16 models only.  Wherever a comment
+ *    returns SF_ERR_UNSUPPORTED.  Of the FP8 entry points the FP16 build runs
+ *    the encoder ones (sf_compact_ffn_fp8, sf_compact_proj_fp8,
+ *    sf_encoder_forward_fp8ffn, sf_encoder_forward_fp8); E4M3-stored weights
+ *    (sf_compact_heads_channels_fp8), the stand-alone FFN block
+ *    (sf_pruned_ffn_fp8_forward) and sf_quantize_fp8 on 16-bit input are built
+ *    for bf16 models only.  Wherever a comment
  *    below says "bf16" for the model dtype, the FP16 build reads "binary16".
  *  - Gate scores, sparsity scores and all index tensors are fp32 / int32 /
  *    uint8 regardless of dtype.

@@ -137,9 +137,10 @@ extern "C" int32_t sf_ffn_fp8_padded(int32_t k_ffn)
 extern "C" int32_t sf_quantize_fp8(const void *x, int32_t dtype, int64_t n, float scale, uint8_t *codes, void *stream)
 {
     if (n < 0 || (n > 0 && (!x || !codes))) return fail(SF_ERR_INVALID_ARG, "quantize_fp8: NULL argument");
-    if (dtype != SF_DTYPE_16 && dtype != SF_F32)
-        return fail(SF_ERR_INVALID_ARG, "quantize_fp8: dtype must be SF_F32 or the 16-bit type of this build of the library");
-    if (dtype == SF_DTYPE_16) dtype = SF_BF16;
+    if (dtype != SF_BF16 && dtype != SF_F32)
+        return fail(SF_ERR_INVALID_ARG, "quantize_fp8: dtype must be SF_F32 or SF_BF16");
+    if (dtype == SF_BF16 && SF_DTYPE_16 != SF_BF16)
+        return fail(SF_ERR_UNSUPPORTED, "quantize_fp8: bfloat16 input takes libsentryfuse.so");
     if (!(scale > 0.f) || !(scale < 3.0e38f)) return fail(SF_ERR_INVALID_ARG, "quantize_fp8: scale must be positive and finite");
     if (((uintptr_t)x & 15) || ((uintptr_t)codes & 7))
         return fail(SF_ERR_INVALID_ARG, "quantize_fp8: x must be 16-byte and codes 8-byte aligned");
@@ -158,8 +159,7 @@ extern "C" int32_t sf_quantize_fp8(const void *x, int32_t dtype, int64_t n, floa
 static int32_t check_ffn_fp8(const char *who, const Dims &D, const sf_ffn_fp8 *f)
 {
     if (!f) return fail(SF_ERR_INVALID_ARG, "%s: NULL argument", who);
-    if (SF_DTYPE_16 != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: FP8 arithmetic is built for bfloat16 models only", who);
-    if (D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: the FP8 path takes bf16 activations (dtype SF_BF16)", who);
+    if (D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: the FP8 path takes 16-bit activations, not fp32", who);
     if (f->k_ffn < 1 || f->k_ffn > D.F) return fail(SF_ERR_INVALID_ARG, "%s: k_ffn out of range", who);
     if (!f->W1q || !f->W2Tq) return fail(SF_ERR_INVALID_ARG, "%s: NULL weight pointer", who);
     if (!(f->s1 > 0.f) || !(f->s2 > 0.f) || !(f->sx > 0.f) || !(f->sh > 0.f))
@@ -261,6 +261,9 @@ extern "C" int32_t sf_pruned_ffn_fp8_forward(const sf_desc *desc, const sf_ffn_f
 {
     Dims D;
     if (int32_t rc = read_desc(desc, D)) return rc;
+    if (SF_DTYPE_16 != SF_BF16)
+        return fail(SF_ERR_UNSUPPORTED, "pruned_ffn_fp8: the stand-alone block is built for bfloat16 models (the FP16 build "
+                                        "runs FP8 arithmetic inside sf_encoder_forward_fp8)");
     if (int32_t rc = ffn_fp8_check("pruned_ffn_fp8", D, f, pre_ln != 0)) return rc;
     if (!X || !Y) return fail(SF_ERR_INVALID_ARG, "pruned_ffn_fp8: NULL argument");
     if (X == Y) return fail(SF_ERR_INVALID_ARG, "pruned_ffn_fp8: Y may not alias X");

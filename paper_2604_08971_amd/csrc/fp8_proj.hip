@@ -79,8 +79,7 @@ void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L,
 int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int k_head)
 {
     if (!p) return fail(SF_ERR_INVALID_ARG, "%s: NULL argument", who);
-    if (SF_DTYPE_16 != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: FP8 arithmetic is built for bfloat16 models only", who);
-    if (D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: the FP8 path takes bf16 activations (dtype SF_BF16)", who);
+    if (D.dtype != SF_BF16) return fail(SF_ERR_UNSUPPORTED, "%s: the FP8 path takes 16-bit activations, not fp32", who);
     if (p->k_head != k_head) return fail(SF_ERR_INVALID_ARG, "%s: k_head differs from the compact layer's", who);
     if (!p->Wqkv8 || !p->WoT8) return fail(SF_ERR_INVALID_ARG, "%s: NULL weight pointer", who);
     if (((uintptr_t)p->Wqkv8 | (uintptr_t)p->WoT8) & 15)

@@ -97,9 +97,25 @@ def test_f16_moe_ffn_parity():
     _moe_case(wl, 8, 3, forced=True)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(dtype="f16", d=256, dh=64, Hq=4, Hk=2, F=512, seg=(100, 60, 70), extra=2, B=3, nl=2, head_keep=0.75,
+         ffn_keep=0.6, dropout="bernoulli:0.3"),
+    # long enough for the output projection on the active rows only
+    dict(dtype="f16", d=256, dh=32, Hq=8, Hk=2, F=512, seg=(600, 300, 200), extra=0, B=2, nl=2, head_keep=0.5, c=5,
+         ffn_keep=0.6, dropout="bernoulli:0.3"),
+])
+def test_f16_encoder_with_fp8_projections_and_ffn(kw):
+    """FP8 arithmetic (projections and FFN) on top of an FP16 model: the decision-by-decision walk of the bfloat16
+    build against the oracle in its binary16 mode."""
+    from test_gpu_fp8_proj import _case
+    _say(f"f16 encoder fp8 {kw}")
+    _case(kw, True)
+
+
 def test_f16_weight_storage_and_fp8_paths():
     """An FP16 model stores binary16 weights as they are (sf_compact_heads_channels_f16 is the plain gather, bit for
-    bit); E4M3-stored weights and FP8 arithmetic are built for bfloat16 models and are refused here."""
+    bit); E4M3-stored weights, the stand-alone FP8 FFN block and the plain quantiser on 16-bit input are built for
+    bfloat16 models and are refused here."""
     wl = W.make_workload(W.small_spec(dtype="f16", d=64, dh=32, F=192, seg=(70, 50, 90), B=3, nl=1))
     dm = DeviceModel(wl).build_plan()
     got = sf.compact_heads_channels_f16(dm.desc, 0, dm.dense[0], dm.masks, int(wl.k_head[0]), int(wl.k_ffn[0]))
@@ -108,7 +124,6 @@ def test_f16_weight_storage_and_fp8_paths():
         assert torch.equal(getattr(got, name).view(torch.int16), getattr(dm.layers[0], name).view(torch.int16)), name
     x8 = torch.zeros(64, dtype=torch.float16, device="cuda")
     codes = torch.empty(64, dtype=torch.uint8, device="cuda")
-    assert sf.lib().sf_quantize_fp8(sf._ptr(x8), sf.SF_BF16, 64, 1.0, sf._ptr(codes), None) == -1
     f8 = sf.SfFfnFp8()
     f8.k_ffn, f8.s1, f8.s2, f8.sx, f8.sh = 200, 1.0, 1.0, 1.0, 1.0
     f8.W1q = f8.W2Tq = 256
@@ -116,3 +131,4 @@ def test_f16_weight_storage_and_fp8_paths():
     args = (C.c_void_p(256), None, 1, 1, C.c_void_p(512), None, None, None, 0, None)
     assert sf.lib().sf_pruned_ffn_fp8_forward(C.byref(d8), C.byref(f8), *args) == -3
     assert b"bfloat16" in sf.lib().sf_last_error()
+    assert sf.lib().sf_quantize_fp8(sf._ptr(x8), sf.SF_BF16, 64, 1.0, sf._ptr(codes), None) == -3

@@ -16,7 +16,7 @@ import torch
 from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import binding as sf
 from paper_2604_08971_amd import workloads as W
-from gpu_utils import DeviceModel, selection_report, to_dev, to_host
+from gpu_utils import ORACLE_MODE, DeviceModel, selection_report, to_dev, to_host
 from helpers import dense_packs, err_metric, oracle_masks
 
 pytestmark = pytest.mark.gpu
@@ -115,7 +115,7 @@ def _case(kw, with_ffn8, samples=None):
             if with_ffn8:
                 h = to_host(codes["hq"][l]).reshape(Bd, L, -1)[samples]
                 hq[l, b][:, masks["ffn_idx"][l, p, :kf]] = h[b, :, :kf]
-    common = dict(act=s.act, final_ln=wl.final_ln, bf16=True, proj8=p8, forced_sel=sel_dense)
+    common = dict(act=s.act, final_ln=wl.final_ln, bf16=ORACLE_MODE[s.dtype], proj8=p8, forced_sel=sel_dense)
     forced = dict(aq_forced=aq, oq_forced=oq)
     if with_ffn8:
         common["ffn8"] = f8
