@@ -121,6 +121,7 @@ def _case(kw, with_ffn8, samples=None):
         common["ffn8"] = f8
         forced.update(xq_forced=to_host(codes["xq"]).reshape(nl, Bd, L, d)[:, samples], hq_forced=hq)
     # the oracle on all of the device's decisions: the output reference, and the scores its choices are judged on
+    _say("   oracle: output reference on the device's decisions")
     y_ref, _, score_f = orc.encoder_forward(x_s, packs, U, pid_s, kv_s, want_score=True, **forced,
                                             **common)
     e = err_metric(Y, y_ref)
@@ -138,8 +139,11 @@ def _case(kw, with_ffn8, samples=None):
                     picks_tot += len(ref_sel)
         assert picks_diff <= max(2, int(0.03 * picks_tot)), (picks_diff, picks_tot)
     # the codes, layer by layer: the oracle's own of layer l on the device's decisions before them
-    aq_own, oq_own = np.zeros_like(aq), np.zeros_like(oq)
-    for l in range(nl):
+    # (deep stacks: the first and the last layer - the walk costs two oracle runs per layer - the others keep the
+    # device's codes, which the output comparison above and the last layer's own codes depend on)
+    aq_own, oq_own = aq.copy(), oq.copy()
+    for l in (range(nl) if nl <= 3 else (0, nl - 1)):
+        _say(f"   oracle: own codes of layer {l} on the device's earlier decisions")
         kw_l = dict(want_codes=True, **forced, **common)
         if with_ffn8:
             kw_l.update(n_forced_x=l, n_forced_h=l)
