@@ -17,9 +17,8 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-for p in (ROOT, os.path.join(ROOT, "tests")):
-    if p not in sys.path:
-        sys.path.insert(0, p)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 METRIC = "encoder tokens/sec + sparse-GQA TFLOP/s (% of bf16 MFMA peak), 1 MI355X"
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
@@ -46,14 +45,26 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_flops(wl, masks_host, U, oproj_rows=None):
+def key_valid_host(dm):
+    from paper_2604_08971_amd.device_model import key_valid_host as f
+    return f(dm)
+
+
+def n_allowed_keys(wl, key_valid):
+    """Allowed keys per sample from the device's key mask (host copy, or None = every position)."""
+    import numpy as np
+    B, L = wl.x.shape[0], wl.spec.L
+    return np.full(B, L) if key_valid is None else key_valid.sum(axis=1).astype(np.int64)
+
+
+def algorithmic_flops(wl, masks_host, U, oproj_rows=None, key_valid=None):
     """Flops credited per step: kept heads / kept groups / kept channels only, no padding.  oproj_rows[l]: rows
     per sample that go through the output projection of layer l when the library projects the active rows only
     (the distinct rows that are active in some head, counted from the selection; None: every row)."""
     import numpy as np
     s = wl.spec
     B, L, d, dh = wl.x.shape[0], s.L, s.d, s.dh
-    n_allowed = np.full(B, L) if wl.key_valid is None else wl.key_valid.sum(axis=1).astype(np.int64)
+    n_allowed = n_allowed_keys(wl, key_valid)
     gemm = score = active = 0
     for l in range(s.n_layers):
         kh, kf = int(wl.k_head[l]), int(wl.k_ffn[l])
@@ -118,7 +129,7 @@ def bench_config(name, steps, warmup, extras, cpu, use_graph=False, repeats=1):
     import torch
     from paper_2604_08971_amd import binding as sf
     from paper_2604_08971_amd import workloads as W
-    from gpu_utils import DeviceModel, to_host
+    from paper_2604_08971_amd.device_model import DeviceModel, to_host
 
     spec = W.CONFIGS[name]
     t0 = time.perf_counter()
@@ -139,7 +150,7 @@ def bench_config(name, steps, warmup, extras, cpu, use_graph=False, repeats=1):
         for l in range(s.n_layers):
             if sf.active_projection_rows(dm.desc, int(wl.k_head[l])) > 0:
                 oproj_rows[l] = np.array([len(np.unique(sel_h[l, b][sel_h[l, b] >= 0])) for b in range(B)])
-    flops = algorithmic_flops(wl, masks_host, U, oproj_rows)
+    flops = algorithmic_flops(wl, masks_host, U, oproj_rows, key_valid_host(dm))
 
     def step():                       # the whole hot path
         dm.build_plan()
@@ -247,7 +258,7 @@ def bench_sparse_gqa(dm, wl, steps):
     K = torch.randn((B, s.Hk, L, dh), generator=g, device="cuda").to(torch.bfloat16)
     V = torch.randn((B, s.Hk, L, dh), generator=g, device="cuda").to(torch.bfloat16)
     hg = dm.masks["head_group"][0][:, :kh].contiguous()
-    n_allowed = np.full(B, L) if wl.key_valid is None else wl.key_valid.sum(axis=1).astype(np.int64)
+    n_allowed = n_allowed_keys(wl, key_valid_host(dm))
     out = {}
     for tag, Uo in (("c5", -1), ("dense", L)):
         desc = sf.make_desc(B, L, s.d, s.Hq, s.Hk, dh, s.F, dtype=sf.SF_BF16, c_factor=s.c, U_override=Uo)
@@ -274,13 +285,13 @@ def bench_sparse_gqa(dm, wl, steps):
     return out
 
 
-def bench_sampled_score(wl, steps, warmup):
+def bench_sampled_score(wl, steps, warmup, kv_host):
     """The same step with the sampled-key sparsity score: n_sample = U = c*ceil(ln L) allowed keys per sample
     (drawn by the caller, seeded), which replaces the 2*L*L*dh score stream by 2*L*U*dh per head."""
     import numpy as np
     import torch
     from paper_2604_08971_amd import binding as sf
-    from gpu_utils import DeviceModel, to_host
+    from paper_2604_08971_amd.device_model import DeviceModel, to_host
     s = wl.spec
     B, L = wl.x.shape[0], s.L
     U = sf.num_active(sf.make_desc(B, L, s.d, s.Hq, s.Hk, s.dh, s.F, c_factor=s.c))
@@ -289,7 +300,7 @@ def bench_sampled_score(wl, steps, warmup):
     rng = np.random.default_rng(7)
     samp = np.full((B, U), -1, np.int32)
     for b in range(B):
-        allowed = np.arange(L) if wl.key_valid is None else np.flatnonzero(wl.key_valid[b])
+        allowed = np.arange(L) if kv_host is None else np.flatnonzero(kv_host[b])
         k = min(U, len(allowed))
         samp[b, :k] = np.sort(rng.choice(allowed, k, replace=False))
     dm = DeviceModel(wl, sample_idx=samp).build_plan()
@@ -301,8 +312,8 @@ def bench_sampled_score(wl, steps, warmup):
 
     ms, _ = time_steps(step, steps, warmup)
     masks_host = {k: to_host(v) for k, v in dm.masks.items()}
-    fl = algorithmic_flops(wl, masks_host, U)
-    n_allowed = np.full(B, L) if wl.key_valid is None else wl.key_valid.sum(axis=1).astype(np.int64)
+    fl = algorithmic_flops(wl, masks_host, U, None, kv_host)
+    n_allowed = n_allowed_keys(wl, kv_host)
     score = sum(int((int(wl.k_head[l]) * 2 * n_allowed * np.minimum(U, n_allowed) * s.dh).sum()) for l in range(s.n_layers))
     total = fl["gemm"] + fl["active"] + score
     del dm
@@ -320,7 +331,7 @@ def bench_f16(wl, steps, warmup):
     import torch
     from paper_2604_08971_amd import binding as sf
     from paper_2604_08971_amd import workloads as W
-    from gpu_utils import DeviceModel
+    from paper_2604_08971_amd.device_model import DeviceModel
     if wl.spec.dtype != "bf16":
         return None
     wl16 = W.make_workload(dataclasses.replace(wl.spec, dtype="f16"))
@@ -348,7 +359,7 @@ def bench_moe(wl, steps, warmup, E=8, top_k=2):
     import torch
     from paper_2604_08971_amd import binding as sf
     from paper_2604_08971_amd import workloads as W
-    from gpu_utils import to_dev, to_host
+    from paper_2604_08971_amd.device_model import to_dev, to_host
     s = wl.spec
     if s.dtype != "bf16":
         return None
@@ -401,7 +412,7 @@ def bench_gate_plan(wl, reps=50):
     import torch
     from paper_2604_08971_amd import binding as sf
     from paper_2604_08971_amd import workloads as W
-    from gpu_utils import to_dev, to_host
+    from paper_2604_08971_amd.device_model import to_dev, to_host
     s = wl.spec
     nl, P, Hq, Hk, F = s.n_layers, wl.P, s.Hq, s.Hk, s.F
     desc = sf.make_desc(1, s.L, s.d, Hq, Hk, s.dh, F, nl, P, sf.SF_F32)
@@ -431,7 +442,7 @@ def bench_fp8_plan(wl, dm, reps=50):
     import numpy as np
     import torch
     from paper_2604_08971_amd import binding as sf
-    from gpu_utils import to_dev
+    from paper_2604_08971_amd.device_model import to_dev
     s = wl.spec
     names = ("Wq", "Wk", "Wv", "Wo", "W1", "W2")
     d8, sc = [], []
@@ -468,7 +479,7 @@ def bench_ffn_fp8(wl, dm, steps, warmup):
     each, FLOP/s of the FP8 launches against the published dense FP8 rate."""
     import torch
     from paper_2604_08971_amd import binding as sf
-    from gpu_utils import to_dev
+    from paper_2604_08971_amd.device_model import to_dev
     s = wl.spec
     if s.dtype != "bf16" or s.d % 128 or s.d < 256 or s.L < 192 or int(wl.k_ffn[0]) <= 128:
         return None
@@ -584,14 +595,14 @@ def bench_tokens(name, steps, warmup):
     import torch
     from paper_2604_08971_amd import binding as sf
     from paper_2604_08971_amd import workloads as W
-    from gpu_utils import DeviceModel, desc_for
+    from paper_2604_08971_amd.device_model import DeviceModel, desc_for
     wl = W.make_workload(W.CONFIGS[name])
-    if wl.key_valid is None:
+    if wl.presence.all():
         return None
     s = wl.spec
     dm = DeviceModel(wl).build_plan()
     B = wl.x.shape[0]
-    lens = wl.key_valid.sum(axis=1).astype(int)
+    lens = key_valid_host(dm).sum(axis=1).astype(int)
     u = np.array([min(s.c * int(np.ceil(np.log(t))), t) if t > 0 else 0 for t in lens])
 
     def masked():
@@ -644,7 +655,7 @@ def cpu_baseline(wl, flops_total):
     """The CPU oracle, as it stands, on a bounded number of whole samples of the same workload."""
     import numpy as np
     from oracle import cpu_oracle as orc
-    from helpers import compact_packs, oracle_masks
+    from oracle.packs import compact_packs, key_valid_of, oracle_masks
     s = wl.spec
     B, L = wl.x.shape[0], s.L
     threads = orc.max_threads()
@@ -653,7 +664,8 @@ def cpu_baseline(wl, flops_total):
     masks = oracle_masks(wl)
     packs = compact_packs(wl, masks)
     U = orc.num_active(L, s.c)
-    kv = None if wl.key_valid is None else wl.key_valid[:n]
+    kv_all = key_valid_of(wl)            # the oracle's own key mask
+    kv = None if kv_all is None else kv_all[:n]
     t0 = time.perf_counter()
     orc.encoder_forward(wl.x[:n], packs, U, wl.pattern_id[:n], kv, act=s.act, final_ln=wl.final_ln,
                         bf16=s.dtype == "bf16", want_sel=False)
@@ -708,7 +720,7 @@ def main():
         return
 
     if args.ffn_fp8_only:
-        from gpu_utils import DeviceModel
+        from paper_2604_08971_amd.device_model import DeviceModel
         wl = W.make_workload(W.CONFIGS[args.config])
         dm = DeviceModel(wl).build_plan()
         print(json.dumps(bench_ffn_fp8(wl, dm, args.steps, args.warmup)), flush=True)
@@ -769,7 +781,7 @@ def main():
                                "avg_launch_us": g["avg_launch_us"], "launches_per_step": g["launches_per_step"]}
         out["kernels"] = k
         out["sparse_gqa"] = bench_sparse_gqa(dm, wl, args.steps)
-        out["sampled_score"] = bench_sampled_score(wl, args.steps, args.warmup)
+        out["sampled_score"] = bench_sampled_score(wl, args.steps, args.warmup, key_valid_host(dm))
         out["f16_build"] = bench_f16(wl, args.steps, args.warmup)
         out["moe_ffn"] = bench_moe(wl, args.steps, args.warmup)
         out["gate_plan"] = bench_gate_plan(wl)

@@ -101,6 +101,22 @@ int32_t sf_num_active(const sf_desc *desc);
 int32_t sf_ffn_padded(const sf_desc *desc, int32_t k_ffn);
 
 /* ------------------------------------------------------------------------
+ * presence_to_key_valid -- Sec. 4.2 (the presence mask m in {0,1}^M of a
+ * sample) and Sec. 4.4 (attention over the concatenated per-modality token
+ * sequence): which positions sample b may use as attention keys,
+ *   key_valid[b,j] = 1 if tok_modality[j] < 0 (a token of no modality, e.g. a
+ *                      fusion token) or presence[b, tok_modality[j]] != 0,
+ *                    0 otherwise.
+ *   presence     [B,M] u8 device;  tok_modality [L] int32 device, values < M
+ *                (an id >= M counts as absent);  key_valid [B,L] u8 device out.
+ * The result is the key_valid argument of sf_sparse_gqa_forward and the
+ * sf_encoder_forward family (a sample needs at least one allowed position;
+ * the host cannot check device data).  0 <= M <= 64.  No workspace.
+ */
+int32_t sf_presence_to_key_valid(const uint8_t *presence, const int32_t *tok_modality, int32_t B,
+                                 int32_t M, int32_t L, uint8_t *key_valid, void *stream);
+
+/* ------------------------------------------------------------------------
  * gate_scores_to_masks -- Sec. 4.5, "Head pruning with GQA consistency" and
  * "FFN pruning".  For every (layer l, pattern p) the k_head_host[l] heads and
  * k_ffn_host[l] channels with the highest gate score g (Eq. (1)) are kept;
@@ -117,6 +133,11 @@ int32_t sf_ffn_padded(const sf_desc *desc, int32_t k_ffn);
  *   head_group[n_layers,P,Hq]   for the i-th kept head: rank of its group in
  *                               group_idx; then -1
  * Limits: Hq <= 64, d_ff <= 16384.  No workspace.
+ * Keep counts, not a threshold, are the argument: one integer per layer makes
+ * the compacted shapes the same for every presence pattern of a batch, which
+ * the batched forward needs.  Sec. 4.5's global threshold for a pruning budget
+ * is sf_budget_search below: it returns tau together with the per-layer counts
+ * for which this call keeps exactly the units scoring >= tau.
  */
 int32_t sf_gate_scores_to_masks(const sf_desc *desc, const float *g_head, const float *g_ffn,
                                 const int32_t *k_head_host, const int32_t *k_ffn_host,

@@ -61,7 +61,7 @@ def lib():
         _lib.orc_pruned_ffn_fp8.restype = None
         _lib.orc_quantize_fp8.restype = None
         _lib.orc_fp8_e4m3_decode.argtypes = [C.c_uint8]
-        for f in ("orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_encoder_forward_fp8ffn", "orc_encoder_forward_fp8", "orc_moe_ffn",
+        for f in ("orc_key_valid", "orc_gate_scores_to_masks", "orc_sparse_gqa", "orc_encoder_forward", "orc_encoder_forward_fp8ffn", "orc_encoder_forward_fp8", "orc_moe_ffn",
                   "orc_gate_eval", "orc_budget_search"):
             getattr(_lib, f).restype = C.c_int32
     return _lib
@@ -118,6 +118,18 @@ def round_f16(a) -> np.ndarray:
     flat_in, flat_out = a.reshape(-1), out.reshape(-1)
     for i in range(flat_in.size):
         flat_out[i] = f(float(flat_in[i]))
+    return out
+
+
+def key_valid(presence, tok_modality) -> np.ndarray:
+    """[B, L] uint8: which positions of the token sequence sample b may use as keys (Sec. 4.2 / 4.4)."""
+    pres = np.ascontiguousarray(presence, dtype=np.uint8)
+    tm = np.ascontiguousarray(tok_modality, dtype=np.int32)
+    B, M = pres.shape
+    out = np.empty((B, tm.shape[0]), np.uint8)
+    rc = lib().orc_key_valid(B, M, tm.shape[0], _p(pres), _p(tm), _p(out))
+    if rc != 0:
+        raise ValueError(f"orc_key_valid: status {rc}")
     return out
 
 

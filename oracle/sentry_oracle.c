@@ -194,6 +194,26 @@ static void keep_top_k(const float *g, int32_t n, int32_t k, uint8_t *mask, int3
     free(s);
 }
 
+int32_t orc_key_valid(int32_t B, int32_t M, int32_t L, const uint8_t *presence, const int32_t *tok_modality,
+                      uint8_t *key_valid)
+{
+    if (B < 1 || M < 0 || L < 1 || !tok_modality || !key_valid || (M > 0 && !presence)) return -1;
+    for (int32_t j = 0; j < L; ++j)
+        if (tok_modality[j] >= M) return -1;
+    int32_t rc = 0;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t any = 0;
+        for (int32_t j = 0; j < L; ++j) {
+            const int32_t m = tok_modality[j];
+            const uint8_t ok = (m < 0 || presence[(size_t)b * M + m] != 0) ? 1 : 0;
+            key_valid[(size_t)b * L + j] = ok;
+            any |= ok;
+        }
+        if (!any) rc = -2;
+    }
+    return rc;
+}
+
 int32_t orc_gate_scores_to_masks(int32_t nl, int32_t P, int32_t Hq, int32_t Hk, int32_t F,
                                  const float *g_head, const float *g_ffn,
                                  const int32_t *k_head, const int32_t *k_ffn,

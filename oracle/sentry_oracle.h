@@ -41,6 +41,18 @@ double orc_round_bf16(double x);
 double orc_round_f16(double x);
 
 /*
+ * Sec. 4.2 / Sec. 4.4: a sample's presence mask m in {0,1}^M decides which positions of the concatenated
+ * per-modality token sequence may serve as attention keys (and as active queries):
+ *   key_valid[b, j] = 1  if tok_modality[j] < 0           (a token of no modality, e.g. a fusion token: always there)
+ *                        or presence[b, tok_modality[j]]   (token j belongs to a modality that sample b has)
+ *                   = 0  otherwise.
+ *   presence [B,M] (any non-zero byte = present), tok_modality [L] (values < M), key_valid [B,L] out.
+ * returns 0; -1 on bad arguments (a modality id >= M); -2 when some sample has no allowed position at all.
+ */
+int32_t orc_key_valid(int32_t B, int32_t M, int32_t L, const uint8_t *presence, const int32_t *tok_modality,
+                      uint8_t *key_valid);
+
+/*
  * Sec. 4.5 "Head pruning with GQA consistency" / "FFN pruning", with integer
  * keep counts per layer: for each (layer l, presence pattern p) keep the
  * k_head[l] heads and k_ffn[l] channels with the highest gate score (ties: the

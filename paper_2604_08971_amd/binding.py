@@ -34,7 +34,7 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
            "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
            "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_fp8_workspace_bytes",
-           "sf_encoder_forward_fp8", "sf_proj_fp8_padded"]
+           "sf_encoder_forward_fp8", "sf_proj_fp8_padded", "sf_presence_to_key_valid"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -132,13 +132,16 @@ def lib():
                   "sf_budget_search", "sf_compact_heads_channels_fp8", "sf_ffn_fp8_padded", "sf_compact_ffn_fp8",
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
                   "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
-                  "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_forward_fp8", "sf_proj_fp8_padded"):
+                  "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_forward_fp8", "sf_proj_fp8_padded",
+                  "sf_presence_to_key_valid"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
             SfStrides, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_gate_scores_to_masks.argtypes = [C.POINTER(SfDesc)] + [C.c_void_p] * 12
+        L.sf_presence_to_key_valid.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                               C.c_void_p]
         L.sf_compact_heads_channels.argtypes = [C.POINTER(SfDesc), C.c_int32, C.POINTER(SfDenseLayer),
                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                                 C.POINTER(SfCompactLayer), C.c_void_p]
@@ -298,6 +301,22 @@ def budget_search(desc: SfDesc, g_head: torch.Tensor, g_ffn: torch.Tensor, patte
                                   C.cast(cg, C.c_void_p), C.cast(cf, C.c_void_p), int(c_fixed), int(budget),
                                   _ptr(out["tau"]), _ptr(out["k_head"]), _ptr(out["k_ffn"]), _ptr(out["cost"]),
                                   _ptr(out["feasible"]), _stream()), "sf_budget_search")
+    return out
+
+
+# ------------------------------------------------------------- presence mask -> allowed keys
+def presence_to_key_valid(presence: torch.Tensor, tok_modality: torch.Tensor,
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """key_valid [B, L] u8 from the presence masks [B, M] u8 and the token -> modality map [L] int32 (-1: no modality)."""
+    assert presence.dtype == torch.uint8 and presence.is_contiguous() and presence.dim() == 2
+    assert tok_modality.dtype == torch.int32 and tok_modality.is_contiguous() and tok_modality.dim() == 1
+    B, M = presence.shape
+    L = tok_modality.shape[0]
+    if out is None:
+        out = torch.empty((B, L), dtype=torch.uint8, device=presence.device)
+    assert out.dtype == torch.uint8 and out.is_contiguous() and tuple(out.shape) == (B, L)
+    _check(lib().sf_presence_to_key_valid(_ptr(presence), _ptr(tok_modality), B, M, L, _ptr(out), _stream()),
+           "sf_presence_to_key_valid")
     return out
 
 

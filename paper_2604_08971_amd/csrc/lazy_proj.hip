@@ -1,5 +1,5 @@
-// Output projection after SentryAttend when most rows are lazy (Sec. 4.4: the T - U rows that are not selected
-// take a context vector aggregated from V_g).  Every row that is lazy in ALL kept heads of its sample carries the
+// Output projection after SentryAttend when most rows are lazy (Sec. 4.4: rows outside a head's top-U set receive
+// their group's mean-V context vector).  Every row that is lazy in ALL kept heads of its sample carries the
 // same attention output - the concatenated group context vectors - so its projection is one vector per sample,
 //     c_b = ctx_b Wo' + bo.
 // Only the rows that are active in some head (at most Hq'*U per sample) go through the GEMM, from a compact buffer;

@@ -73,9 +73,44 @@ __global__ __launch_bounds__(NT) void keep_masks_kernel(
     }
 }
 
+// Sec. 4.2 / 4.4: position j of the concatenated token sequence is an allowed key of sample b iff it belongs to
+// no modality (tok_modality < 0: fusion tokens) or to one that sample b has.  One thread per 4 positions.
+__global__ __launch_bounds__(256) void presence_to_key_valid_kernel(const uint8_t *__restrict__ presence,
+                                                                    const int32_t *__restrict__ tok_modality, int B,
+                                                                    int M, int L, uint8_t *__restrict__ key_valid)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;     // over B * ceil(L/4)
+    const int L4 = (L + 3) >> 2;
+    if (i >= (int64_t)B * L4) return;
+    const int b = (int)(i / L4), j0 = (int)(i % L4) * 4;
+    const uint8_t *pr = presence + (int64_t)b * M;
+    uint8_t *out = key_valid + (int64_t)b * L;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int j = j0 + e;
+        if (j < L) {
+            const int m = tok_modality[j];
+            out[j] = (m < 0 || (m < M && pr[m] != 0)) ? 1 : 0;     // an id >= M is refused by the host when it can see it
+        }
+    }
+}
+
 }  // namespace sf
 
 using namespace sf;
+
+extern "C" int32_t sf_presence_to_key_valid(const uint8_t *presence, const int32_t *tok_modality, int32_t B,
+                                            int32_t M, int32_t L, uint8_t *key_valid, void *stream)
+{
+    if (B < 1 || L < 1 || M < 0 || M > 64) return fail(SF_ERR_INVALID_ARG, "presence_to_key_valid: B, L >= 1 and 0 <= M <= 64 required");
+    if (!tok_modality || !key_valid || (M > 0 && !presence))
+        return fail(SF_ERR_INVALID_ARG, "presence_to_key_valid: NULL argument");
+    if ((int64_t)B * L > (int64_t)1 << 31) return fail(SF_ERR_SHAPE, "presence_to_key_valid: B*L too large");
+    const int64_t n = (int64_t)B * ((L + 3) / 4);
+    hipLaunchKernelGGL(presence_to_key_valid_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), presence, tok_modality, B, M, L, key_valid);
+    return check_launch("presence_to_key_valid");
+}
 
 extern "C" int32_t sf_gate_scores_to_masks(const sf_desc *desc, const float *g_head,
                                            const float *g_ffn, const int32_t *k_head_host,

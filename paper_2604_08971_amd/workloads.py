@@ -104,9 +104,8 @@ CONFIGS: Dict[str, Spec] = {
 class Workload:
     spec: Spec
     x: np.ndarray                       # [B, L, d] fp32 (bf16-valued when spec.dtype == "bf16")
-    presence: np.ndarray                # [B, M] uint8
-    tok_modality: np.ndarray            # [L] int32, -1 = always present
-    key_valid: Optional[np.ndarray]     # [B, L] uint8 or None when nothing is dropped
+    presence: np.ndarray                # [B, M] uint8; which positions a sample may attend to follows from it and
+    tok_modality: np.ndarray            # [L] int32, -1 = always present - derived by the library and by the oracle, each on its own
     pattern_bits: np.ndarray            # [P] presence bit patterns in use (ascending)
     pattern_id: np.ndarray              # [B] int32 index into pattern_bits
     g_head: np.ndarray                  # [nl, P, Hq] fp32 gate scores
@@ -177,13 +176,6 @@ def make_workload(spec: Spec, B: Optional[int] = None, affine_noise: bool = True
     bits = (presence.astype(np.int64) << np.arange(M)).sum(axis=1)
     pattern_bits = np.unique(bits)
     pattern_id = np.searchsorted(pattern_bits, bits).astype(np.int32)
-    if presence.all():
-        key_valid = None
-    else:
-        kv = np.ones((B, L), dtype=np.uint8)
-        has = tok_mod >= 0
-        kv[:, has] = presence[:, tok_mod[has]]
-        key_valid = kv
 
     x = q(_rng(seed, 2).standard_normal((B, L, d), dtype=np.float32)) if with_x else np.zeros((0, L, d), np.float32)
 
@@ -226,7 +218,7 @@ def make_workload(spec: Spec, B: Optional[int] = None, affine_noise: bool = True
         r = _rng(seed, 99)
         final_ln = {"g": vec(r, d, 0.05, 1.0, True), "b": vec(r, d, 0.05, 0.0, True)}
 
-    return Workload(spec, x, presence, tok_mod, key_valid, pattern_bits, pattern_id,
+    return Workload(spec, x, presence, tok_mod, pattern_bits, pattern_id,
                     g_head, g_ffn, k_head, k_ffn, layers, final_ln)
 
 

@@ -16,8 +16,9 @@ import torch
 from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import binding as sf
 from paper_2604_08971_amd import workloads as W
+from helpers import make_wl
 from gpu_utils import DeviceModel, to_dev, to_host
-from test_gpu_parity import _encoder_parity, _ffn_case, _gqa_case, _moe_case
+from test_gpu_parity import _encoder_parity, _ffn_case, _gqa_case, _moe_case, _spread_samples
 
 pytestmark = pytest.mark.gpu
 
@@ -75,23 +76,23 @@ def test_f16_pruned_ffn_parity(act, B, L, d, F, keep):
 ])
 def test_f16_encoder_parity_small(kw):
     _say(f"f16 encoder small {kw}")
-    _encoder_parity(W.make_workload(W.small_spec(**kw)))
+    _encoder_parity(make_wl(W.small_spec(**kw)))
 
 
-@pytest.mark.parametrize("name,n_samples", [("C2", 3), ("C4", 2), ("C5", 1)])
+@pytest.mark.parametrize("name,n_samples", [("C2", 12), ("C4", 6), ("C5", 4)])
 def test_f16_encoder_parity_full_size_sampled(name, n_samples):
-    """The configurations of the bfloat16 benchmark as FP16 models, at full size."""
+    """The configurations of the bfloat16 benchmark as FP16 models, at full size; the oracle takes the first and the
+    last sample, both ends of every presence pattern and a seeded draw of the rest."""
     import dataclasses
-    _say(f"f16 encoder {name} (full batch on the GPU, {n_samples} samples through the oracle)")
-    wl = W.make_workload(dataclasses.replace(W.CONFIGS[name], dtype="f16"))
-    rng = np.random.default_rng(2)
-    samples = sorted(rng.choice(wl.x.shape[0], n_samples, replace=False).tolist())
-    _encoder_parity(wl, samples=samples)
+    wl = make_wl(dataclasses.replace(W.CONFIGS[name], dtype="f16"))
+    samples = _spread_samples(wl, n_samples)
+    _say(f"f16 encoder {name} (full batch on the GPU, {len(samples)} samples through the oracle)")
+    _encoder_parity(wl, samples=samples, own_choice=False)
 
 
 def test_f16_moe_ffn_parity():
     _say("f16 moe")
-    wl = W.make_workload(W.small_spec(dtype="f16", d=128, dh=64, Hq=8, Hk=2, F=320, seg=(100, 133, 64), extra=3, B=5,
+    wl = make_wl(W.small_spec(dtype="f16", d=128, dh=64, Hq=8, Hk=2, F=320, seg=(100, 133, 64), extra=3, B=5,
                                       act=1, dropout="upto:2"))
     _moe_case(wl, 8, 3)
     _moe_case(wl, 8, 3, forced=True)
@@ -116,7 +117,7 @@ def test_f16_weight_storage_and_fp8_paths():
     """An FP16 model stores binary16 weights as they are (sf_compact_heads_channels_f16 is the plain gather, bit for
     bit); E4M3-stored weights, the stand-alone FP8 FFN block and the plain quantiser on 16-bit input are built for
     bfloat16 models and are refused here."""
-    wl = W.make_workload(W.small_spec(dtype="f16", d=64, dh=32, F=192, seg=(70, 50, 90), B=3, nl=1))
+    wl = make_wl(W.small_spec(dtype="f16", d=64, dh=32, F=192, seg=(70, 50, 90), B=3, nl=1))
     dm = DeviceModel(wl).build_plan()
     got = sf.compact_heads_channels_f16(dm.desc, 0, dm.dense[0], dm.masks, int(wl.k_head[0]), int(wl.k_ffn[0]))
     torch.cuda.synchronize()

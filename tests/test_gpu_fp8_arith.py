@@ -18,7 +18,7 @@ import torch
 from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import binding as sf
 from gpu_utils import to_dev, to_host
-from helpers import err_metric
+from helpers import err_metric, make_wl
 
 pytestmark = pytest.mark.gpu
 
@@ -263,7 +263,7 @@ def _encoder_fp8_case(kw):
     from paper_2604_08971_amd import workloads as W
     from gpu_utils import DeviceModel
     from helpers import dense_packs, oracle_masks
-    wl = W.make_workload(W.small_spec(**kw))
+    wl = make_wl(W.small_spec(**kw))
     s = wl.spec
     dm = DeviceModel(wl).build_plan()
     ref_masks = oracle_masks(wl)

@@ -17,7 +17,7 @@ from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import binding as sf
 from paper_2604_08971_amd import workloads as W
 from gpu_utils import ORACLE_MODE, DeviceModel, selection_report, to_dev, to_host
-from helpers import dense_packs, err_metric, oracle_masks
+from helpers import dense_packs, err_metric, make_wl, oracle_masks
 
 pytestmark = pytest.mark.gpu
 
@@ -35,7 +35,7 @@ def _cast_e4m3(a):
 
 
 def _build(kw, with_ffn8):
-    wl = W.make_workload(kw if isinstance(kw, W.Spec) else W.small_spec(**kw))
+    wl = make_wl(kw if isinstance(kw, W.Spec) else W.small_spec(**kw))
     s = wl.spec
     dm = DeviceModel(wl).build_plan()
     masks = oracle_masks(wl)
@@ -188,12 +188,12 @@ def test_encoder_with_fp8_projections_parity(kw, with_ffn8):
 
 def test_encoder_fp8_C5_full_size_sampled():
     """The launch bench.py times for this path (C5, projections and FFN in FP8 arithmetic, active-row output
-    projection); the oracle recomputes one whole sample, which is independent of the others."""
-    _say("encoder fp8 projections + ffn, C5 (full batch on the GPU, 1 sample through the oracle)")
-    _case(W.CONFIGS["C5"], True, samples=[11])
+    projection); the oracle recomputes three whole samples (first, last, one between), which are independent of the others."""
+    _say("encoder fp8 projections + ffn, C5 (full batch on the GPU, 3 samples through the oracle)")
+    _case(W.CONFIGS["C5"], True, samples=[0, 11, 15])
 
 
-@pytest.mark.parametrize("name,samples", [("C3", [5, 77]), ("C4", [100])])
+@pytest.mark.parametrize("name,samples", [("C3", [0, 5, 77, 255]), ("C4", [0, 127])])
 def test_encoder_fp8_other_configs_full_size_sampled(name, samples):
     """The other single-GPU configurations at full size: many presence patterns (C3); six layers with kept-head
     counts whose code rows need padding, and a final LayerNorm (C4)."""

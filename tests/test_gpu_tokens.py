@@ -16,7 +16,7 @@ from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import binding as sf
 from paper_2604_08971_amd import workloads as W
 from gpu_utils import DeviceModel, desc_for, selection_report, to_dev, to_host
-from helpers import compact_packs, err_metric, oracle_masks
+from helpers import compact_packs, err_metric, make_wl, oracle_masks
 
 pytestmark = pytest.mark.gpu
 
@@ -143,14 +143,14 @@ def _ragged_case(wl, samples=None):
 ])
 def test_encoder_ragged_parity_small(kw):
     _say(f"ragged encoder {kw}")
-    _ragged_case(W.make_workload(W.small_spec(**kw)))
+    _ragged_case(make_wl(W.small_spec(**kw)))
 
 
 def test_encoder_ragged_parity_C3_samples():
     """The dropout workload at full size (4 modalities of 256/128/64/32 tokens, up to two dropped): every sample at
     its own length in the launch configuration the benchmark times; the oracle on 6 samples of different lengths."""
     _say("ragged encoder C3")
-    wl = W.make_workload(W.CONFIGS["C3"])
+    wl = make_wl(W.CONFIGS["C3"])
     lens = wl.key_valid.sum(axis=1)
     pick = []
     for t in np.unique(lens):
@@ -159,7 +159,7 @@ def test_encoder_ragged_parity_C3_samples():
 
 
 def test_ragged_entry_rejects_what_it_cannot_run():
-    wl = W.make_workload(W.small_spec(dtype="f32", dropout="upto:2", B=3))
+    wl = make_wl(W.small_spec(dtype="f32", dropout="upto:2", B=3))
     dm = DeviceModel(wl).build_plan()
     tc = sf.token_compact(dm.desc, dm.x, dm.key_valid, wl.spec.L)
     dc = desc_for(wl, U_override=wl.spec.L)                 # U >= L: every row active, no per-sample counts
@@ -174,7 +174,7 @@ def test_compact_encode_scatter_under_hip_graph_replay():
     """Compaction, the ragged encoder and the scatter recorded into one HIP graph: every replay, with eager work and
     synchronisations in between, reproduces the eager result (no step of the chain needs the host)."""
     _say("token compaction graph replay")
-    wl = W.make_workload(W.small_spec(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90, 40), B=6, dropout="upto:2"))
+    wl = make_wl(W.small_spec(dtype="bf16", d=64, dh=32, F=192, seg=(70, 50, 90, 40), B=6, dropout="upto:2"))
     s = wl.spec
     dm = DeviceModel(wl).build_plan()
     lens = wl.key_valid.sum(axis=1).astype(int)

@@ -16,7 +16,7 @@ import torch
 
 from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import workloads as W
-from helpers import compact_packs, dense_packs, oracle_masks
+from helpers import compact_packs, dense_packs, make_wl, oracle_masks
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -284,7 +284,7 @@ def test_f16_mode_has_the_rounding_points_of_the_bf16_mode():
     assert not np.array_equal(Oh, orc.sparse_gqa(Q, K, V, [0, 1], U=3, bf16=1)[0])
     # the pruned FFN
     spec = W.small_spec(dtype="f32", B=2, nl=1, dropout="none", final_ln=False)
-    wl = W.make_workload(spec)
+    wl = make_wl(spec)
     masks = oracle_masks(wl)
     pack = dense_packs(wl, masks)[0][0]
     lw = {k: h16(v) for k, v in wl.layers[0].items()}
@@ -299,7 +299,7 @@ def test_f16_mode_has_the_rounding_points_of_the_bf16_mode():
     want = h16(x + hid @ lw["W2"][keep] + lw["b2"])
     assert np.array_equal(y, want)
     # the encoder's output is a stored tensor; the residual stream between layers is not
-    wl2 = W.make_workload(W.small_spec(dtype="f32", B=2, nl=2))
+    wl2 = make_wl(W.small_spec(dtype="f32", B=2, nl=2))
     m2 = oracle_masks(wl2)
     U = orc.num_active(wl2.spec.L, wl2.spec.c)
     yh, _, _ = orc.encoder_forward(wl2.x, dense_packs(wl2, m2), U, wl2.pattern_id, wl2.key_valid, final_ln=wl2.final_ln,
@@ -438,6 +438,37 @@ def test_softmax_invariants_under_key_mask():
         orc.sparse_gqa(Q[:1], K[:1], V[:1], [0, 0, 1, 1], U=5, key_valid=np.zeros((1, L), np.uint8))
 
 
+def test_key_valid_against_per_token_loop():
+    # Sec. 4.2 / 4.4: the allowed keys of a sample are the tokens of the modalities it has, plus the tokens that
+    # belong to no modality.  Pin: a per-token Python loop written from that sentence, on the four dropout / fusion
+    # workloads, on hand-made rows (all but one modality absent, nothing absent) and on the error cases.
+    for name in ("C1", "C2", "C3", "C4"):
+        wl = W.make_workload(W.CONFIGS[name], with_x=False)
+        kv = orc.key_valid(wl.presence, wl.tok_modality)
+        B, L = wl.presence.shape[0], wl.spec.L
+        assert kv.shape == (B, L) and kv.dtype == np.uint8
+        for b in list(range(min(B, 5))) + [B - 1]:
+            want = [1 if wl.tok_modality[j] < 0 or wl.presence[b, wl.tok_modality[j]] else 0 for j in range(L)]
+            assert kv[b].tolist() == want
+        # per-sample count = tokens of present modalities + modality-free tokens
+        seg = np.array(list(wl.spec.seg_tokens))
+        assert np.array_equal(kv.sum(axis=1), wl.presence.astype(int) @ seg + wl.spec.extra_tokens)
+    # C1: the third modality is dropped for both samples; C4: nothing dropped, two fusion tokens at the end
+    assert orc.key_valid(*[getattr(W.make_workload(W.CONFIGS["C1"], with_x=False), k) for k in ("presence", "tok_modality")])[0].tolist() \
+        == [1] * 32 + [0] * 16
+    # hand-made: interleaved modalities, a fusion token in the middle, one row with a single modality left
+    tm = np.array([2, 0, -1, 1, 0, 2, -1], np.int32)
+    pres = np.array([[0, 0, 1], [1, 1, 1], [0, 1, 0], [7, 0, 0]], np.uint8)        # any non-zero byte = present
+    assert orc.key_valid(pres, tm).tolist() == [[1, 0, 1, 0, 0, 1, 1], [1] * 7, [0, 0, 1, 1, 0, 0, 1], [0, 1, 1, 0, 1, 0, 1]]
+    # a modality id beyond M is refused; a sample with nothing to attend to is refused
+    with pytest.raises(ValueError):
+        orc.key_valid(pres, np.array([0, 3], np.int32))
+    with pytest.raises(ValueError):
+        orc.key_valid(np.array([[0, 0]], np.uint8), np.array([0, 1, 1], np.int32))
+    # ... unless a modality-free token is there
+    assert orc.key_valid(np.array([[0, 0]], np.uint8), np.array([0, -1, 1], np.int32)).tolist() == [[0, 1, 0]]
+
+
 def test_all_ones_mask_equals_no_mask():
     rng = np.random.default_rng(7)
     Q, K, V = rng.standard_normal((2, 2, 11, 3)), rng.standard_normal((2, 1, 11, 3)), rng.standard_normal((2, 1, 11, 3))
@@ -496,7 +527,7 @@ def test_sampled_score_pins():
 def test_encoder_sampled_score_matches_operator():
     """The encoder passes the same key sample to SentryAttend in every layer: its active sets are those of the
     operator run on the encoder's own Q/K (checked through forced selection) and differ from the unsampled ones."""
-    wl = W.make_workload(W.small_spec(dtype="f32", B=3, nl=2, seg=(20, 13, 16)))
+    wl = make_wl(W.small_spec(dtype="f32", B=3, nl=2, seg=(20, 13, 16)))
     masks = oracle_masks(wl)
     packs = compact_packs(wl, masks)
     L = wl.spec.L
@@ -668,7 +699,7 @@ def _np_encoder(wl, masks, U):
 @pytest.mark.parametrize("act,dropout", [(0, "bernoulli:0.3"), (1, "upto:2"), (0, "none")])
 def test_encoder_against_matrix_form(act, dropout):
     spec = W.small_spec(act=act, dropout=dropout, B=4)
-    wl = W.make_workload(spec)
+    wl = make_wl(spec)
     masks = oracle_masks(wl)
     U = orc.num_active(spec.L, spec.c)
     y, sel, _ = orc.encoder_forward(wl.x, dense_packs(wl, masks), U, wl.pattern_id, wl.key_valid,
@@ -682,7 +713,7 @@ def test_compact_equals_masked_dense_bit_for_bit():
     function as masking the dense network; removed units contribute exactly 0."""
     for dtype in ("f32", "bf16"):
         spec = W.small_spec(dtype=dtype, B=5, Hq=6, Hk=3, F=40, head_keep=0.5, ffn_keep=0.4)
-        wl = W.make_workload(spec)
+        wl = make_wl(spec)
         masks = oracle_masks(wl)
         U = orc.num_active(spec.L, spec.c)
         bf = dtype == "bf16"
@@ -714,7 +745,7 @@ def test_compact_equals_masked_dense_bit_for_bit():
 
 def test_encoder_forced_selection_roundtrip():
     spec = W.small_spec(B=2, dropout="none")
-    wl = W.make_workload(spec)
+    wl = make_wl(spec)
     masks = oracle_masks(wl)
     U = orc.num_active(spec.L, spec.c)
     packs = compact_packs(wl, masks)
@@ -1056,7 +1087,7 @@ def test_encoder_with_fp8_ffn_is_the_composition_of_its_blocks():
     difference to a run whose FFN weights are zero) followed by orc_pruned_ffn_fp8 on that stream; with ffn8 = None
     the function is the plain encoder."""
     spec = W.small_spec(dtype="f32", B=2, nl=1, dropout="none", final_ln=False)
-    wl = W.make_workload(spec)
+    wl = make_wl(spec)
     masks = oracle_masks(wl)
     packs = dense_packs(wl, masks)          # dense weights + 0/1 masks: the FFN codes are in the dense layout too
     U = orc.num_active(spec.L, spec.c)
@@ -1108,7 +1139,7 @@ def test_encoder_with_fp8_projections_against_matrix_form(dropout):
     the reading: codes of LN1(x) and of the attention output from the library's fp32 -> float8_e4m3fn conversion,
     products of decoded codes, one fp32 scale product per GEMM, attention and FFN as in the plain encoder."""
     spec = W.small_spec(dtype="f32", B=3, nl=1, dropout=dropout, final_ln=False, Hq=4, Hk=2, head_keep=0.75)
-    wl = W.make_workload(spec)
+    wl = make_wl(spec)
     masks = oracle_masks(wl)
     packs = dense_packs(wl, masks)
     U = orc.num_active(spec.L, spec.c)
@@ -1172,7 +1203,7 @@ def test_encoder_fp8_projections_forced_codes_and_bf16_mode():
     so the layer output with forced codes is a function of the codes alone; with the FFN in FP8 too the FFN codes
     are those of orc_pruned_ffn_fp8 on the stream after the attention block."""
     spec = W.small_spec(dtype="bf16", B=2, nl=2, dropout="none", final_ln=False, Hq=4, Hk=2)
-    wl = W.make_workload(spec)
+    wl = make_wl(spec)
     masks = oracle_masks(wl)
     packs = dense_packs(wl, masks)
     U = orc.num_active(spec.L, spec.c)
