@@ -407,6 +407,31 @@ int32_t sf_sparse_gqa_forward(const sf_desc *desc, int32_t nH, int32_t nG,
                               void *O, int64_t ldo, int32_t *sel_out, float *score_out,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* sf_sparse_gqa_forward for callers that cannot allocate or hold a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that
+ * forbid device allocation.  Same arguments, same kernels and same results as
+ * sf_sparse_gqa_forward, but the scratch memory (transposed V, statistics,
+ * scores, active lists, key-split partials) is a buffer of
+ * SF_STATIC_SCRATCH_BYTES built into the library's device image, one copy per
+ * GPU, held until the process ends.  The call allocates and frees nothing.
+ * A problem whose sf_sparse_gqa_workspace_bytes() exceeds the buffer is refused
+ * with SF_ERR_WORKSPACE before anything is enqueued (the message names both
+ * sizes).  All calls on one GPU share the buffer, so two calls that overlap in
+ * time on one GPU (different streams or threads) race: serialise them, or use
+ * sf_sparse_gqa_forward with a workspace per stream.  Nothing in the buffer
+ * needs clearing between calls.  sf_sparse_gqa_static_capacity() returns
+ * SF_STATIC_SCRATCH_BYTES. */
+#define SF_STATIC_SCRATCH_BYTES (16u << 20)
+size_t sf_sparse_gqa_static_capacity(void);
+int32_t sf_sparse_gqa_forward_static(const sf_desc *desc, int32_t nH, int32_t nG,
+                                     const void *Q, sf_strides sq, const void *K, sf_strides sk,
+                                     const void *V, sf_strides sv, int32_t v_transposed,
+                                     const int32_t *head_group, const int32_t *pattern_id,
+                                     const uint8_t *key_valid, const int32_t *sample_idx,
+                                     const int32_t *forced_sel,
+                                     void *O, int64_t ldo, int32_t *sel_out, float *score_out,
+                                     void *stream);
+
 /* ------------------------------------------------------------------------
  * pruned_ffn_forward -- Sec. 4.5: Y = [X +] act(X' W1'^T + b1') W2' + b2 with
  * X' = LayerNorm(X) when pre_ln != 0, else X.  X, Y [B*L, d]; sample b uses
@@ -613,6 +638,26 @@ enum { SF_KERNEL_GEMM = 0,      /* bf16 MFMA GEMM (all projections and both FFN 
        SF_KERNEL_ATTEND = 2 };  /* active-row attention (Eq. (6)) */
 int32_t sf_profile_begin(int32_t kernel_class, int32_t max_launches);
 int32_t sf_profile_end(int32_t *n_launches_host, float *total_ms_host, float *each_ms_host);
+
+/* ------------------------------------------------------------------------
+ * Measurement aids: what this GPU reaches on the two resources the kernels
+ * are bound by, to be timed by the caller on the launch stream (the benchmark
+ * reports both next to the published peaks).  No part of the method.
+ *
+ * sf_ceiling_mfma_launch: `workgroups` workgroups of 8 waves (two per SIMD)
+ * each issue iters * 32 independent 32x32x16 bf16 (FP16 build: fp16) MFMAs
+ * from operands held in registers - no memory traffic.  random_operands = 0:
+ * one constant operand pattern; 1: rotating pseudo-random operands in [-1, 1)
+ * (the data-dependent power draw of a real contraction, which lowers the
+ * sustained clock).  sink [workgroups] fp32 device (never written in
+ * practice).  Returns the flops of the launch, or a negative status.
+ *
+ * sf_ceiling_copy_launch: dst[0:bytes] = src[0:bytes] with 16 bytes per lane
+ * (reads `bytes` and writes `bytes` of HBM); 16-byte aligned, bytes % 16 == 0.
+ */
+int64_t sf_ceiling_mfma_launch(int32_t workgroups, int32_t iters, int32_t random_operands,
+                               float *sink, void *stream);
+int32_t sf_ceiling_copy_launch(const void *src, void *dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

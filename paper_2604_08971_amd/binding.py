@@ -34,7 +34,9 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_pruned_ffn_fp8_workspace_bytes", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
            "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
            "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_fp8_workspace_bytes",
-           "sf_encoder_forward_fp8", "sf_proj_fp8_padded", "sf_presence_to_key_valid"]
+           "sf_encoder_forward_fp8", "sf_proj_fp8_padded", "sf_presence_to_key_valid",
+           "sf_sparse_gqa_static_capacity", "sf_sparse_gqa_forward_static", "sf_ceiling_mfma_launch",
+           "sf_ceiling_copy_launch"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -124,7 +126,8 @@ def lib():
         L = C.CDLL(path)
         L.sf_last_error.restype = C.c_char_p
         for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes",
-                  "sf_moe_ffn_workspace_bytes", "sf_pruned_ffn_fp8_workspace_bytes", "sf_encoder_fp8_workspace_bytes"):
+                  "sf_moe_ffn_workspace_bytes", "sf_pruned_ffn_fp8_workspace_bytes", "sf_encoder_fp8_workspace_bytes",
+                  "sf_sparse_gqa_static_capacity"):
             getattr(L, n).restype = C.c_size_t
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
@@ -133,12 +136,18 @@ def lib():
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
                   "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
                   "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_forward_fp8", "sf_proj_fp8_padded",
-                  "sf_presence_to_key_valid"):
+                  "sf_presence_to_key_valid", "sf_sparse_gqa_forward_static"):
             getattr(L, n).restype = C.c_int32
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
             SfStrides, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sf_sparse_gqa_forward_static.argtypes = L.sf_sparse_gqa_forward.argtypes[:19] + [C.c_void_p]
+        L.sf_sparse_gqa_static_capacity.argtypes = []
+        L.sf_ceiling_mfma_launch.restype = C.c_int64
+        L.sf_ceiling_mfma_launch.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.sf_ceiling_copy_launch.restype = C.c_int32
+        L.sf_ceiling_copy_launch.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.sf_gate_scores_to_masks.argtypes = [C.POINTER(SfDesc)] + [C.c_void_p] * 12
         L.sf_presence_to_key_valid.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                                C.c_void_p]
@@ -247,6 +256,21 @@ def workspace(nbytes: int, device="cuda") -> torch.Tensor:
 
 
 _prof_cap = 0
+
+
+def ceiling_mfma_launch(workgroups: int, iters: int, random_operands: bool, sink: torch.Tensor) -> int:
+    """One launch of the register-only MFMA loop; returns its flops."""
+    assert sink.dtype == torch.float32 and sink.numel() >= workgroups
+    fl = lib().sf_ceiling_mfma_launch(int(workgroups), int(iters), int(random_operands), _ptr(sink), _stream())
+    if fl < 0:
+        _check(int(fl), "sf_ceiling_mfma_launch")
+    return int(fl)
+
+
+def ceiling_copy_launch(src: torch.Tensor, dst: torch.Tensor):
+    assert src.is_contiguous() and dst.is_contiguous() and src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    _check(lib().sf_ceiling_copy_launch(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()),
+           "sf_ceiling_copy_launch")
 
 
 def profile_begin(kernel_class: int, max_launches: int):
@@ -484,6 +508,28 @@ def sparse_gqa_forward(desc: SfDesc, Q: torch.Tensor, K: torch.Tensor, V: torch.
     if sel is not None:
         sel = sel[:, :, :U]
     return O, sel, score
+
+
+def sparse_gqa_static_capacity() -> int:
+    return int(lib().sf_sparse_gqa_static_capacity())
+
+
+def sparse_gqa_forward_static(desc: SfDesc, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                              head_group: torch.Tensor, O: torch.Tensor, pattern_id: Optional[torch.Tensor] = None,
+                              key_valid: Optional[torch.Tensor] = None, forced_sel: Optional[torch.Tensor] = None,
+                              v_transposed: bool = False, sel: Optional[torch.Tensor] = None,
+                              score: Optional[torch.Tensor] = None, sample_idx: Optional[torch.Tensor] = None):
+    """sf_sparse_gqa_forward_static: every buffer (O [B,L,nH*dh], optionally sel [B,nH,U] and score [B,nH,L]) is the
+    caller's, the scratch memory is the library's built-in buffer; nothing is allocated by this call."""
+    _check_sample(desc, sample_idx, Q.shape[0])
+    B, nH, L, dh = Q.shape
+    nG = K.shape[1]
+    assert O.is_contiguous() and tuple(O.shape) == (B, L, nH * dh) and O.dtype == Q.dtype
+    rc = lib().sf_sparse_gqa_forward_static(
+        C.byref(desc), nH, nG, _ptr(Q), _strides4(Q), _ptr(K), _strides4(K), _ptr(V), _strides4(V),
+        int(v_transposed), _ptr(head_group), _ptr(pattern_id), _ptr(key_valid), _ptr(sample_idx),
+        _ptr(forced_sel), _ptr(O), nH * dh, _ptr(sel), _ptr(score), _stream())
+    _check(rc, "sf_sparse_gqa_forward_static")
 
 
 def _check_sample(desc: SfDesc, sample_idx: Optional[torch.Tensor], B: int):

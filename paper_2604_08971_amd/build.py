@@ -16,7 +16,7 @@ LIB = os.path.join(HERE, "libsentryfuse.so")
 LIB_F16 = os.path.join(HERE, "libsentryfuse_f16.so")
 
 SOURCES = ["api.hip", "masks.hip", "compact.hip", "gemm_bf16.hip", "gemm_bf16_fast.hip", "gemm_bf16_ws.hip", "gemm_f32.hip", "moe.hip", "gate.hip", "fp8_ffn.hip", "tokens.hip", "lazy_proj.hip", "fp8_proj.hip",
-           "attention_common.hip", "attention_bf16.hip"]
+           "attention_common.hip", "attention_bf16.hip", "ceilings.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms stay off on the test machines

@@ -341,6 +341,12 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             if (int32_t rc = proj_fp8_check("encoder(fp8 projections)", D, &proj8[l], layers[l].k_head)) return rc;
         if (((uintptr_t)aq_out | (uintptr_t)oq_out) & 15)
             return fail(SF_ERR_INVALID_ARG, "encoder(fp8 projections): 16-byte aligned code buffers required");
+        // the fused LayerNorm + quantiser reads 16 bytes per lane (layers after the first read the workspace)
+        uintptr_t al = (uintptr_t)X;
+        for (int l = 0; l < D.nl; ++l) al |= (uintptr_t)layers[l].ln1_g | (uintptr_t)layers[l].ln1_b;
+        if (al & 15)
+            return fail(SF_ERR_INVALID_ARG,
+                        "encoder(fp8 projections): 16-byte aligned input and LayerNorm vectors required");
     }
     if (u_active && D.U >= D.L)
         return fail(SF_ERR_UNSUPPORTED, "encoder: per-sample active counts need U < L (U = %d, L = %d)", D.U, D.L);
@@ -388,9 +394,6 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         if (proj8) {
             // the same in FP8 arithmetic: codes of LN1(x), one GEMM for Q, K, V (token-major), V transposed after it
             const sf_proj_fp8 &pj = proj8[l];
-            if (((uintptr_t)ly.ln1_g | (uintptr_t)ly.ln1_b | (uintptr_t)in) & 15)
-                return fail(SF_ERR_INVALID_ARG,
-                            "encoder(fp8 projections): 16-byte aligned input and LayerNorm vectors required");
             uint8_t *aq = aq_out ? aq_out + (size_t)l * rows * D.d : static_cast<uint8_t *>(w.xn);
             layernorm_q8(in, in_f32, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, 1.0f / pj.sx1, aq, st);
             GemmArgs q8{};

@@ -2,6 +2,8 @@
 // K/V statistics (mean key for the sparsity score, mean value = context
 // vector), the top-U query choice, the lazy-row fill -- plus the plain fp32
 // kernels and the dispatch.  The bf16 MFMA kernels are in attention_bf16.hip.
+#include <mutex>
+
 #include "attention.hpp"
 #include "topk.hpp"
 
@@ -493,6 +495,10 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
     } else if (a.dh > 256) {
         return fail(SF_ERR_SHAPE, "sparse_gqa(f32): dh <= 256 required");
     }
+    // limits of the bf16 launchers (their 1-D grids), checked here so that nothing is enqueued when they fail
+    if (dtype == SF_BF16 && a.nH > 64) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): at most 64 heads");
+    if ((int64_t)a.B * a.nH * ceil_div(a.L, 32) * 64 > ((int64_t)1 << 30))
+        return fail(SF_ERR_SHAPE, "sparse_gqa: too many work items (B * heads * L / 32 must stay below 2^24)");
     AttnPlan pl = attn_plan(dtype, a, a.ws);
     if (pl.bytes > 0 && (!a.ws || a.ws_bytes < pl.bytes || ((uintptr_t)a.ws & 255)))
         return fail(SF_ERR_WORKSPACE, "sparse_gqa: workspace of %zu bytes (256-byte aligned) required, got %zu",
@@ -668,4 +674,59 @@ extern "C" int32_t sf_sparse_gqa_forward(const sf_desc *desc, int32_t nH, int32_
     a.forced_sel = forced_sel; a.O = O; a.ldo = ldo; a.sel_out = sel_out; a.score_out = score_out;
     a.ws = workspace; a.ws_bytes = workspace_bytes;
     return attention_forward(D.dtype, a, static_cast<hipStream_t>(stream));
+}
+
+// ---- sparse_gqa_forward for callers that cannot allocate --------------------------------------------------------
+// The same launches as sf_sparse_gqa_forward with the workspace taken from a file-scope device array instead of a
+// caller's buffer.  Every GPU the library runs on holds its own copy of the array at its own address until the
+// process ends; the array's name is only a host-side handle, so its device address is looked up once per device
+// (with that device current) and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[SF_STATIC_SCRATCH_BYTES];
+
+static int32_t static_scratch(void **out)
+{
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void *per_device[MAX_DEV] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV)
+        return fail(SF_ERR_HIP, "sparse_gqa_static: no current device (or device index >= %d)", MAX_DEV);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(SF_ERR_HIP, "sparse_gqa_static: hipGetSymbolAddress failed on device %d: %s", dev,
+                        hipGetErrorString(e));
+        per_device[dev] = p;
+    }
+    *out = per_device[dev];
+    return SF_OK;
+}
+
+extern "C" size_t sf_sparse_gqa_static_capacity(void) { return SF_STATIC_SCRATCH_BYTES; }
+
+extern "C" int32_t sf_sparse_gqa_forward_static(const sf_desc *desc, int32_t nH, int32_t nG, const void *Q,
+                                                sf_strides sq, const void *K, sf_strides sk, const void *V,
+                                                sf_strides sv, int32_t v_transposed, const int32_t *head_group,
+                                                const int32_t *pattern_id, const uint8_t *key_valid,
+                                                const int32_t *sample_idx, const int32_t *forced_sel, void *O,
+                                                int64_t ldo, int32_t *sel_out, float *score_out, void *stream)
+{
+    Dims D; AttnArgs a;
+    if (int32_t rc = make_attn_args(desc, nH, nG, D, a)) return rc;
+    a.v_transposed = v_transposed != 0;
+    const size_t need = attn_plan(D.dtype, a, nullptr).bytes;
+    if (need > SF_STATIC_SCRATCH_BYTES)
+        return fail(SF_ERR_WORKSPACE,
+                    "sparse_gqa_static: this problem needs %zu bytes of scratch, the built-in buffer holds %zu; use "
+                    "sf_sparse_gqa_forward with a workspace of sf_sparse_gqa_workspace_bytes()",
+                    need, (size_t)SF_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (int32_t rc = static_scratch(&ws)) return rc;
+    // Nothing in the buffer has to start at zero: every piece (transposed V, K/V statistics, scores, active lists,
+    // row -> slot map, key-split partials) is written in full by an earlier kernel of the same call before a later
+    // one reads it, exactly as with a caller's uninitialised workspace.
+    return sf_sparse_gqa_forward(desc, nH, nG, Q, sq, K, sk, V, sv, v_transposed, head_group, pattern_id, key_valid,
+                                 sample_idx, forced_sel, O, ldo, sel_out, score_out, ws, SF_STATIC_SCRATCH_BYTES, stream);
 }
