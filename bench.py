@@ -767,6 +767,9 @@ def main():
                          "(for profiling)")
     ap.add_argument("--tokens-only", action="store_true",
                     help="time only the token-compaction comparison on the dropout workload C3 and print its object")
+    ap.add_argument("--sparse-gqa-only", action="store_true",
+                    help="time only sf_sparse_gqa_forward at the workload's kept shapes (c-sparse and dense pattern) and "
+                         "print its object (for profiling)")
     ap.add_argument("--moe-only", action="store_true",
                     help="time only the Sparse-MoE FFN block on the workload's tokens and print its object (for profiling)")
     args = ap.parse_args()
@@ -787,6 +790,13 @@ def main():
 
     if args.tokens_only:
         print(json.dumps(bench_tokens("C3", args.steps, args.warmup)), flush=True)
+        return
+
+    if args.sparse_gqa_only:
+        from paper_2604_08971_amd.device_model import DeviceModel
+        wl = W.make_workload(W.CONFIGS[args.config])
+        dm = DeviceModel(wl).build_plan()
+        print(json.dumps(bench_sparse_gqa(dm, wl, args.steps)), flush=True)
         return
 
     if args.ffn_fp8_only:

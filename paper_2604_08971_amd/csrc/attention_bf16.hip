@@ -19,6 +19,7 @@ constexpr int NWAVE = 4;
 constexpr int BKEY = 64;          // keys per LDS tile (two 32-key MFMA blocks)
 constexpr int PAD = 8;            // bf16 elements of row padding (16 bytes) against bank conflicts
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr float RESCALE_LOG2 = 8.0f;    // slack of the softmax reference below the running maximum, in powers of two
 #define SF_SCORE_OCC __attribute__((amdgpu_waves_per_eu(4, 4)))
 
 // Bit j%32 of word j/32 = key j of sample b is allowed (0 beyond L).
@@ -213,6 +214,20 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     }
 }
 
+// v_permlane32_swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its second: fed the same value
+// twice, lane l then holds v[l % 32] in the first result and v[32 + l % 32] in the second - the values of the two
+// lanes that share a query.
+__device__ __forceinline__ float both_halves_max(float v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float both_halves_sum(float v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // ---------------------------------------------------------------- active pass
 // A "pair" is (head of the group, block of 32 active queries).  A workgroup of
 // AWAVE waves serves one (sample, K/V group, key split): each wave owns QB
@@ -284,22 +299,26 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             if ((VTOTAL % NT == 0 || c < VTOTAL) && j < Lp) {
                 const uint32_t off = (uint32_t)e * (uint32_t)svt.l * 2u + (uint32_t)cc * 16u;   // < dh rows of Lp keys
                 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(Vb + j0) + off);
-                if (j + 8 > L) {
+            }
+            r[u] = v;          // (keys at or beyond L are zeroed when the chunk is written to LDS: touching the value
+                               // here would make the wave wait for the load it has just issued)
+        }
+    };
+    auto put_v = [&](const uint4 (&r)[NV], h16 *Vt, int j0) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int c = threadIdx.x + u * NT;
+            if (VTOTAL % NT == 0 || c < VTOTAL) {
+                uint4 v = r[u];
+                const int j = j0 + (c % (BKEY / 8)) * 8;
+                if (j + 8 > L) {                       // last tile of a ragged row only
                     uint16_t *hv = reinterpret_cast<uint16_t *>(&v);
 #pragma unroll
                     for (int t = 0; t < 8; ++t)
                         if (j + t >= L) hv[t] = 0;
                 }
+                *reinterpret_cast<uint4 *>(Vt + (c / (BKEY / 8)) * (BKEY + PAD) + (c % (BKEY / 8)) * 8) = v;
             }
-            r[u] = v;
-        }
-    };
-    auto put_v = [&](const uint4 (&r)[NV], h16 *Vt) {
-#pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            const int c = threadIdx.x + u * NT;
-            if (VTOTAL % NT == 0 || c < VTOTAL)
-                *reinterpret_cast<uint4 *>(Vt + (c / (BKEY / 8)) * (BKEY + PAD) + (c % (BKEY / 8)) * 8) = r[u];
         }
     };
     using KT_ = KTile<DH, NT>;
@@ -343,7 +362,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             const int j0 = tile_j0(it);
             h16 *Kt = Ks + (it & 1) * KT, *Vt = Vs + (it & 1) * VT_;
             KT_::put(kreg, Kt);
-            put_v(vreg, Vt);
+            put_v(vreg, Vt, j0);
             __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffers)
             if (it + 1 < nt) { const int jn = tile_j0(it + 1); KT_::fetch(Kb, sk.l, jn, L, kreg); fetch_v(jn, vreg); }
             if (idle) continue;
@@ -382,37 +401,43 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
                             if (!((wl >> ((e / 4) * 8 + (e % 4))) & 1u)) s[qq][kb][e] = -INFINITY;
                     }
                 }
-                float mt = -INFINITY;
+                float mt = fmaxf(fmaxf(s[qq][0][0], s[qq][0][1]), s[qq][1][0]);
+                mt = fmaxf(fmaxf(mt, s[qq][1][1]), s[qq][0][2]);
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int e = 3; e < 15; e += 2) mt = fmaxf(fmaxf(mt, s[qq][0][e]), s[qq][0][e + 1]);
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) mt = fmaxf(mt, s[qq][kb][e]);
-                mt *= sc;                                  // sc > 0: max and scaling commute
-                mt = fmaxf(mt, __shfl_xor(mt, 32));
-                const float m_new = fmaxf(m_run[qq], mt);
-                const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m_run[qq] - m_safe);
-                m_run[qq] = m_new;
-                float rs = 0.f;
+                for (int e = 2; e < 16; e += 2) mt = fmaxf(fmaxf(mt, s[qq][1][e]), s[qq][1][e + 1]);
+                mt = fmaxf(mt, s[qq][0][15]) * sc;         // sc > 0: max and scaling commute
+                mt = both_halves_max(mt);                  // the other 16 keys of each 32-key block sit in lane ^ 32
+                // The reference m_run of the exponentials only has to stay within 2^RESCALE_LOG2 of the true running
+                // maximum (sums and outputs are relative to the same reference, so the result does not depend on
+                // it): it moves, and the accumulators are rescaled, only when some query of the wave needs it.
+                // After the first tiles of a row that is rare, which removes the rescaling from the common path.
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(mt > m_run[qq] + RESCALE_LOG2) != 0ull, 0)) {
+                    const float m_new = fmaxf(m_run[qq], mt);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[qq] - (m_new == -INFINITY ? 0.f : m_new));
+                    m_run[qq] = m_new;
+                    l_run[qq] *= alpha;
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                    for (int db = 0; db < DH / 32; ++db)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(s[qq][kb][e], sc, -m_safe));
-                        s[qq][kb][e] = p;
-                        rs += p;
-                    }
-                l_run[qq] = l_run[qq] * alpha + rs;
-#pragma unroll
-                for (int db = 0; db < DH / 32; ++db)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[qq][db][e] *= alpha;
+                        for (int e = 0; e < 16; ++e) oacc[qq][db][e] *= alpha;
+                }
+                const float nm = m_run[qq] == -INFINITY ? 0.f : -m_run[qq];
+                float rs0 = 0.f, rs1 = 0.f;
                 // k-step t covers keys 16t..16t+15; this lane supplies keys
-                // {16t + lhi*4 + 0..3, 16t + 8 + lhi*4 + 0..3} = accumulator entries (t%2)*8 + 0..7
+                // {16t + lhi*4 + 0..3, 16t + 8 + lhi*4 + 0..3} = accumulator entries (t%2)*8 + 0..7 of block t/2
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[qq][t][e] = (h16)s[qq][t / 2][(t % 2) * 8 + e];
+                    for (int e = 0; e < 16; e += 2) {
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qq][kb][e], sc, nm));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qq][kb][e + 1], sc, nm));
+                        rs0 += p0;
+                        rs1 += p1;
+                        reinterpret_cast<uint32_t *>(&pf[qq][kb * 2 + e / 8])[(e % 8) / 2] = pack2_h16(p0, p1);
+                    }
+                l_run[qq] += rs0 + rs1;
             }
 
             // O^T += V^T . P^T
@@ -436,7 +461,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
         // lane owns query l32 and output dims db*32 + ig*8 + lhi*4 + {0..3}
 #pragma unroll
         for (int qq = 0; qq < QB; ++qq) {
-            const float l_tot = l_run[qq] + __shfl_xor(l_run[qq], 32);
+            const float l_tot = both_halves_sum(l_run[qq]);
             if (qidx[qq] < 0) continue;
             if (splits <= 1) {
                 const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
@@ -469,6 +494,335 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             }
         }
         __syncthreads();            // the next pass restages both tile buffers
+    }
+}
+
+// ------------------------------------------------- active pass, many active rows (dense-like patterns)
+// Two pairs per wave as above, but the two waves of a SIMD are kept in OPPOSITE phases.  Measured on the plain loop
+// (dense pattern, 16 x 8 heads x 4096^2): matrix-pipe work, softmax and tile staging took 430 + 220 + 125 us and
+// added up to the kernel's 775 us - nothing overlapped, because after the tile's barrier both waves of a SIMD issue
+// their MFMAs at the same time (the pipe alternates between them), then both run their softmax on the one vector
+// ALU.  Here waves 0-3 (group 0) and waves 4-7 (group 1; wave w runs on SIMD w % 4) alternate between two clusters
+// separated by workgroup barriers, group 1 one cluster behind group 0:
+//     V(t): softmax of S(t) -> P(t) on the vector ALU, plus the group's share of the tile staging
+//     M(t): P(t) V(t) and S(t+1) = K(t+1) Q^T on the matrix pipe
+// so in every slot between two barriers one wave of each SIMD is in V and the other in M.  S(t+1) overwrites the
+// registers of S(t), which V(t) has turned into P(t), so the register budget is that of the plain loop.
+// Staging: group 0 writes V(t) during its V(t) cluster, group 1 writes K(t+2) during its V(t) cluster; each lands in
+// a buffer whose last readers finished two slots earlier and is first read one slot later.
+template <int DH>
+__global__ __launch_bounds__(AWAVE * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attend_pp_bf16_kernel(
+    const h16 *__restrict__ Q, sf_strides sq, const h16 *__restrict__ K, sf_strides sk,
+    const h16 *__restrict__ VT, sf_strides svt, const int32_t *__restrict__ head_group, int hg_stride,
+    const int32_t *__restrict__ pattern_id, const uint8_t *__restrict__ key_valid,
+    const int32_t *__restrict__ sel, int selH, int nH, int nG, int BG, int chunks, int L, int Lp, int U,
+    int Upad, int splits, int keys_per_split, h16 *__restrict__ O, int64_t ldo,
+    float *__restrict__ part_o, float *__restrict__ part_ml)
+{
+    constexpr int QB = 2, GT = (AWAVE / 2) * 64;                         // threads of a wave group
+    static_assert(AWAVE == 8, "two groups of four waves, one wave of each per SIMD");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int KT = BKEY * (DH + PAD), VT_ = DH * (BKEY + PAD);          // elements of one K / V^T tile
+    h16 *Ks = reinterpret_cast<h16 *>(smem);                         // [2][BKEY][DH+PAD]
+    h16 *Vs = Ks + 2 * KT;                                              // [2][DH][BKEY+PAD]
+    uint32_t *words = reinterpret_cast<uint32_t *>(Vs + 2 * VT_);          // [ceil(L/32)]
+    uint16_t *tiles = reinterpret_cast<uint16_t *>(words + (L + 31) / 32); // [ceil(L/64)]
+    __shared__ int heads[64];
+    __shared__ int n_heads, n_tiles;
+
+    const int per_xcd = gridDim.x / 8;
+    const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (item >= chunks * BG * splits) return;             // uniform
+    const int chunk = item % chunks, bg = (item / chunks) % BG, sp = item / (chunks * BG);
+    const int b = bg / nG, g = bg % nG;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lhi = lane >> 5;
+    const int grp = __builtin_amdgcn_readfirstlane(wave >> 2), gtid = threadIdx.x & (GT - 1);
+    const int32_t *hg = head_group + (int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride;
+
+    if (wave == 0) {                      // ordered list of the group's heads (nH <= 64)
+        const bool mine = lane < nH && hg[lane] == g;
+        const unsigned long long bal = __ballot(mine);
+        if (mine) heads[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
+        if (lane == 0) n_heads = __popcll(bal);
+    }
+    const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
+    const int nwords = (L + 31) / 32;
+    build_mask_words(kv, L, words, nwords);
+    const int jbeg = sp * keys_per_split, jend = min(L, jbeg + keys_per_split);
+    __syncthreads();
+    build_tile_list(words, nwords, jbeg, jend, tiles, &n_tiles);
+    __syncthreads();
+    const int nt = n_tiles;
+    const int nqb = Upad / 32;
+    const int npairs = n_heads * nqb;
+
+    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const float sc = LOG2E / sqrtf((float)DH);
+
+    // Tile chunks (16 bytes) of one thread of a group -> registers -> LDS.  K rows at or beyond L and V^T keys at or
+    // beyond L are zero.  The thread's offsets are re-formed from an opaque copy of its index at every use: kept
+    // live across the loop they are spilled, and a reload from scratch inside the loop is a vector-memory operation
+    // whose wait also waits for the tile loads just issued (measured: 1200 clocks per tile in the fetch alone).
+    constexpr int KCH = DH / 8, KTOTAL = BKEY * KCH, NK = (KTOTAL + GT - 1) / GT;
+    constexpr int VTOTAL = DH * (BKEY / 8), NV = (VTOTAL + GT - 1) / GT;
+    auto fetch_k = [&](int j0, uint4 (&r)[NK]) {
+        int gt = gtid;
+        asm volatile("" : "+v"(gt));      // re-formed at every use, see below
+        const char *base = reinterpret_cast<const char *>(Kb + (int64_t)j0 * sk.l);
+#pragma unroll
+        for (int u = 0; u < NK; ++u) {
+            const int c = gt + u * GT;
+            const int row = c / KCH, cc = c % KCH;
+            const uint32_t off = (uint32_t)row * (uint32_t)sk.l * 2u + (uint32_t)cc * 16u;
+            r[u] = ((KTOTAL % GT == 0 || c < KTOTAL) && j0 + row < L)
+                       ? *reinterpret_cast<const uint4 *>(base + off) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto put_k = [&](const uint4 (&r)[NK], h16 *Kt) {
+        int gt = gtid;
+        asm volatile("" : "+v"(gt));      // re-formed at every use, see below
+#pragma unroll
+        for (int u = 0; u < NK; ++u) {
+            const int c = gt + u * GT;
+            if (KTOTAL % GT == 0 || c < KTOTAL)
+                *reinterpret_cast<uint4 *>(Kt + (c / KCH) * (DH + PAD) + (c % KCH) * 8) = r[u];
+        }
+    };
+    auto fetch_v = [&](int j0, uint4 (&r)[NV]) {
+        int gt = gtid;
+        asm volatile("" : "+v"(gt));      // re-formed at every use, see below
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int c = gt + u * GT;
+            const int e = c / (BKEY / 8), cc = c % (BKEY / 8);
+            const int j = j0 + cc * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if ((VTOTAL % GT == 0 || c < VTOTAL) && j < Lp) {
+                const uint32_t off = (uint32_t)e * (uint32_t)svt.l * 2u + (uint32_t)cc * 16u;   // < dh rows of Lp keys
+                v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(Vb + j0) + off);
+            }
+            r[u] = v;          // (keys at or beyond L are zeroed when the chunk is written to LDS: touching the value
+                               // here would make the wave wait for the load it has just issued)
+        }
+    };
+    auto put_v = [&](const uint4 (&r)[NV], h16 *Vt, int j0) {
+        int gt = gtid;
+        asm volatile("" : "+v"(gt));      // re-formed at every use, see below
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int c = gt + u * GT;
+            if (VTOTAL % GT == 0 || c < VTOTAL) {
+                uint4 v = r[u];
+                const int j = j0 + (c % (BKEY / 8)) * 8;
+                if (j + 8 > L) {                       // last tile of a ragged row only
+                    uint16_t *hv = reinterpret_cast<uint16_t *>(&v);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t)
+                        if (j + t >= L) hv[t] = 0;
+                }
+                // chunk cc holds keys 8cc..8cc+7 of the row; inside every group of 16 keys the LDS order is
+                // [0-3, 8-11, 4-7, 12-15], so that the 8 keys a lane supplies per MFMA are 16 contiguous bytes
+                const int cc = c % (BKEY / 8);
+                h16 *dst = Vt + (c / (BKEY / 8)) * (BKEY + PAD) + (cc >> 1) * 16 + (cc & 1) * 4;
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(v.x, v.y);
+                *reinterpret_cast<uint2 *>(dst + 8) = make_uint2(v.z, v.w);
+            }
+        }
+    };
+    auto tile_j0 = [&](int it) { return __builtin_amdgcn_readfirstlane((int)tiles[it]) * BKEY; };   // same for every lane
+
+    for (int pair0 = chunk * (AWAVE * QB); pair0 < npairs; pair0 += chunks * (AWAVE * QB)) {
+        int head[QB], qidx[QB], slot[QB];
+        h16x8 qf[QB][DH / 16];
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+            const int pi = pair0 + wave * QB + qq;
+            head[qq] = -1; qidx[qq] = -1; slot[qq] = 0;
+            if (pi < npairs) {
+                head[qq] = heads[pi / nqb];
+                slot[qq] = (pi % nqb) * 32 + l32;
+                if (slot[qq] < U) qidx[qq] = sel[((int64_t)b * selH + head[qq]) * U + slot[qq]];
+            }
+            const h16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
+                                 (int64_t)max(qidx[qq], 0) * sq.l;
+#pragma unroll
+            for (int kk = 0; kk < DH / 16; ++kk)
+                qf[qq][kk] = *reinterpret_cast<const h16x8 *>(qrow + kk * 16 + lhi * 8);
+        }
+        const bool idle = pair0 + wave * QB >= npairs;        // wave-uniform: no pair at all (still stages and syncs)
+
+        f32x16 oacc[QB][DH / 32];
+        float m_run[QB], l_run[QB];
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+            m_run[qq] = -INFINITY; l_run[qq] = 0.f;
+#pragma unroll
+            for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[qq][db][e] = 0.f;
+        }
+        f32x16 s[QB][2];
+        h16x8 pf[QB][4];
+
+        // S^T of both pairs for the 64 keys of a K tile (every K fragment serves both pairs)
+        auto s_tile = [&](const h16 *Kt) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                h16x8 kf[DH / 16];
+#pragma unroll
+                for (int kk = 0; kk < DH / 16; ++kk)
+                    kf[kk] = *reinterpret_cast<const h16x8 *>(Kt + (kb * 32 + l32) * (DH + PAD) + kk * 16 + lhi * 8);
+#pragma unroll
+                for (int qq = 0; qq < QB; ++qq) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) s[qq][kb][e] = 0.f;
+#pragma unroll
+                    for (int kk = 0; kk < DH / 16; ++kk)
+                        s[qq][kb] = SF_MFMA16(kf[kk], qf[qq][kk], s[qq][kb], 0, 0, 0);
+                }
+            }
+        };
+        // O^T += V^T . P^T of both pairs
+        auto pv_tile = [&](const h16 *Vt) {
+#pragma unroll
+            for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    // keys {16t + lhi*4 + 0..3, 16t + 8 + lhi*4 + 0..3}: one 16-byte read in the staged key order
+                    const h16x8 vf = *reinterpret_cast<const h16x8 *>(Vt + (db * 32 + l32) * (BKEY + PAD) + t * 16 + lhi * 8);
+#pragma unroll
+                    for (int qq = 0; qq < QB; ++qq)
+                        oacc[qq][db] = SF_MFMA16(vf, pf[qq][t], oacc[qq][db], 0, 0, 0);
+                }
+        };
+        // softmax of S(t) -> P(t); updates the running reference / sum / output scale of both pairs
+        auto softmax_tile = [&](int j0) {
+            const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
+            const bool all_allowed = (uint32_t)__builtin_amdgcn_readfirstlane((int)(w0 & w1)) == 0xffffffffu;
+#pragma unroll
+            for (int qq = 0; qq < QB; ++qq) {
+                if (!all_allowed) {
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb) {
+                        const uint32_t wl = (kb ? w1 : w0) >> (lhi * 4);
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            if (!((wl >> ((e / 4) * 8 + (e % 4))) & 1u)) s[qq][kb][e] = -INFINITY;
+                    }
+                }
+                float mt = fmaxf(fmaxf(s[qq][0][0], s[qq][0][1]), s[qq][1][0]);
+                mt = fmaxf(fmaxf(mt, s[qq][1][1]), s[qq][0][2]);
+#pragma unroll
+                for (int e = 3; e < 15; e += 2) mt = fmaxf(fmaxf(mt, s[qq][0][e]), s[qq][0][e + 1]);
+#pragma unroll
+                for (int e = 2; e < 16; e += 2) mt = fmaxf(fmaxf(mt, s[qq][1][e]), s[qq][1][e + 1]);
+                mt = fmaxf(mt, s[qq][0][15]) * sc;         // sc > 0: max and scaling commute
+                mt = both_halves_max(mt);
+                // the reference moves only when some query needs it (see attend_bf16_kernel)
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(mt > m_run[qq] + RESCALE_LOG2) != 0ull, 0)) {
+                    const float m_new = fmaxf(m_run[qq], mt);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[qq] - (m_new == -INFINITY ? 0.f : m_new));
+                    m_run[qq] = m_new;
+                    l_run[qq] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) oacc[qq][db][e] *= alpha;
+                }
+                const float nm = m_run[qq] == -INFINITY ? 0.f : -m_run[qq];
+                float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; e += 2) {
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[qq][kb][e], sc, nm));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[qq][kb][e + 1], sc, nm));
+                        rs0 += p0;
+                        rs1 += p1;
+                        reinterpret_cast<uint32_t *>(&pf[qq][kb * 2 + e / 8])[(e % 8) / 2] = pack2_h16(p0, p1);
+                    }
+                l_run[qq] += rs0 + rs1;
+            }
+        };
+
+        if (nt > 0) {
+            // K(0) and V(0) by group 0, K(1) by group 1; V(1) waits in group 0's registers, K(2) in group 1's
+            uint4 kreg[NK], vreg[NV];
+            if (grp == 0) {
+                fetch_k(tile_j0(0), kreg);
+                fetch_v(tile_j0(0), vreg);
+                put_k(kreg, Ks);
+                put_v(vreg, Vs, tile_j0(0));
+                if (nt > 1) fetch_v(tile_j0(1), vreg);
+            } else if (nt > 1) {
+                fetch_k(tile_j0(1), kreg);
+                put_k(kreg, Ks + KT);
+                if (nt > 2) fetch_k(tile_j0(2), kreg);
+            }
+            __syncthreads();
+            if (!idle) s_tile(Ks);
+            if (grp == 1) __syncthreads();                    // group 1 runs one cluster behind
+            for (int it = 0; it < nt; ++it) {
+                // ---- cluster V(it): vector ALU only
+                if (!idle) softmax_tile(tile_j0(it));
+                __syncthreads();
+                // ---- cluster M(it): matrix pipe, and the group's share of the staging (this wave has issue slots to
+                // spare while its MFMAs run; the buffers written here had their last readers one slot ago)
+                if (grp == 0) {
+                    if (it + 1 < nt) {
+                        put_v(vreg, Vs + ((it + 1) & 1) * VT_, tile_j0(it + 1));    // V(it+1) over V(it-1)
+                        if (it + 2 < nt) fetch_v(tile_j0(it + 2), vreg);
+                    }
+                } else if (it + 2 < nt) {
+                    put_k(kreg, Ks + (it & 1) * KT);                                // K(it+2) over K(it)
+                    if (it + 3 < nt) fetch_k(tile_j0(it + 3), kreg);
+                }
+                if (!idle) {
+                    pv_tile(Vs + (it & 1) * VT_);
+                    if (it + 1 < nt) s_tile(Ks + ((it + 1) & 1) * KT);
+                }
+                __syncthreads();
+            }
+            if (grp == 0) __syncthreads();                    // as many barriers as group 1
+        }
+
+        // lane owns query l32 and output dims db*32 + ig*8 + lhi*4 + {0..3}
+#pragma unroll
+        for (int qq = 0; qq < QB; ++qq) {
+            const float l_tot = both_halves_sum(l_run[qq]);
+            if (qidx[qq] < 0) continue;
+            if (splits <= 1) {
+                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+                h16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
+#pragma unroll
+                for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                    for (int ig = 0; ig < 4; ++ig) {
+                        uint2 o;
+                        o.x = pack2_h16(oacc[qq][db][ig * 4] * inv, oacc[qq][db][ig * 4 + 1] * inv);
+                        o.y = pack2_h16(oacc[qq][db][ig * 4 + 2] * inv, oacc[qq][db][ig * 4 + 3] * inv);
+                        *reinterpret_cast<uint2 *>(orow + db * 32 + ig * 8 + lhi * 4) = o;
+                    }
+            } else {
+                const int64_t base = (((int64_t)b * nH + head[qq]) * splits + sp) * Upad + slot[qq];   // [b, head, split, slot]
+                float *po = part_o + base * DH;
+#pragma unroll
+                for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                    for (int ig = 0; ig < 4; ++ig) {
+                        f32x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = oacc[qq][db][ig * 4 + e];
+                        *reinterpret_cast<f32x4 *>(po + db * 32 + ig * 8 + lhi * 4) = o;
+                    }
+                if (lhi == 0) {
+                    part_ml[base * 2] = m_run[qq];
+                    part_ml[base * 2 + 1] = l_tot;
+                }
+            }
+        }
+        __syncthreads();            // the next pass restages the tile buffers
     }
 }
 
@@ -517,6 +871,13 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
     if (items > (1 << 30)) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): too many work items");
     dim3 grid((unsigned)align_up(items, 8));
     ProfScope prof(SF_KERNEL_ATTEND, st);
+    if constexpr (QB == 2) {
+        hipLaunchKernelGGL((attend_pp_bf16_kernel<DH>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
+                           a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
+                           a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
+                           pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
+        return SF_OK;
+    }
     hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
                        a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
                        a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,

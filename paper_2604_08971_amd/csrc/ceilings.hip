@@ -51,12 +51,21 @@ void mfma_ceiling_kernel(int iters, int random_operands, float *__restrict__ sin
     if (v == 123.456f) sink[blockIdx.x] = v;      // keeps the loop alive; practically never true
 }
 
-// dst[i] = src[i], 16 bytes per lane, grid-stride
+// dst[i] = src[i], 16 bytes per lane, grid-stride, four independent loads in flight per lane; streamed (the data is
+// touched once)
 __global__ __launch_bounds__(256) void copy_ceiling_kernel(const f32x4 *__restrict__ src, f32x4 *__restrict__ dst,
                                                            int64_t n16)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        f32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 }  // namespace
@@ -85,7 +94,7 @@ extern "C" int32_t sf_ceiling_copy_launch(const void *src, void *dst, size_t byt
         return fail(SF_ERR_INVALID_ARG, "ceiling_copy: 16-byte aligned buffers and a multiple of 16 bytes required");
     const int64_t n16 = (int64_t)(bytes / 16);
     const int64_t want = (n16 + 255) / 256;
-    const unsigned blocks = (unsigned)(want < 256 * 16 ? want : 256 * 16);
+    const unsigned blocks = (unsigned)(want < 256 * 8 ? want : 256 * 8);
     hipLaunchKernelGGL(copy_ceiling_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const f32x4 *>(src), static_cast<f32x4 *>(dst), n16);
     return check_launch("ceiling_copy");

@@ -612,6 +612,10 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
     ("bf16", 2, 4, 2, 333, 128, -1, True),         # dh 128
     ("bf16", 2, 4, 2, 200, 64, 200, False),        # dense pattern (U = L): flash GQA
     ("bf16", 2, 4, 2, 300, 32, 300, True),         # dense pattern with a key mask
+    ("bf16", 2, 6, 2, 1024, 64, 1024, True),       # dense pattern, many tiles, 3 heads per group, key mask
+    ("bf16", 1, 4, 2, 1500, 64, 1500, False),      # dense pattern, ragged last tile
+    ("bf16", 2, 4, 2, 700, 32, 700, True),         # dense pattern, dh 32, key mask
+    ("bf16", 1, 4, 4, 2100, 64, 333, True),        # many active rows but not all (two pairs per wave), key mask
     ("bf16", 2, 2, 2, 96, 64, 0, True),            # U = 0
     ("bf16", 1, 2, 1, 40, 64, 7, False),           # fewer rows than one MFMA block
 ])
