@@ -754,33 +754,37 @@ __global__ __launch_bounds__(AWAVE * 64) __attribute__((amdgpu_waves_per_eu(2, 2
                 fetch_v(tile_j0(0), vreg);
                 put_k(kreg, Ks);
                 put_v(vreg, Vs, tile_j0(0));
-                if (nt > 1) fetch_v(tile_j0(1), vreg);
-            } else if (nt > 1) {
-                fetch_k(tile_j0(1), kreg);
+                fetch_v(tile_j0(min(1, nt - 1)), vreg);
+            } else {
+                fetch_k(tile_j0(min(1, nt - 1)), kreg);
                 put_k(kreg, Ks + KT);
-                if (nt > 2) fetch_k(tile_j0(2), kreg);
+                fetch_k(tile_j0(min(2, nt - 1)), kreg);
             }
             __syncthreads();
             if (!idle) s_tile(Ks);
             if (grp == 1) __syncthreads();                    // group 1 runs one cluster behind
             for (int it = 0; it < nt; ++it) {
+                // The tile numbers of this iteration, read at the top of the V cluster where the vector ALU work hides
+                // the LDS round trip.  Beyond the last tile the index is clamped: the staging and the S^T block of
+                // the last iterations are then redundant (they land in buffers nobody reads again), which keeps the
+                // M cluster free of data-dependent branches.
+                const int j_cur = tile_j0(it), j1 = tile_j0(min(it + 1, nt - 1));
+                const int j_far = tile_j0(min(it + 2 + grp, nt - 1));
                 // ---- cluster V(it): vector ALU only
-                if (!idle) softmax_tile(tile_j0(it));
+                if (!idle) softmax_tile(j_cur);
                 __syncthreads();
-                // ---- cluster M(it): matrix pipe, and the group's share of the staging (this wave has issue slots to
-                // spare while its MFMAs run; the buffers written here had their last readers one slot ago)
+                // ---- cluster M(it): matrix pipe, and the group's share of the staging (the buffers written here had
+                // their last readers one slot ago).  (Raising this wave's priority for the cluster changed nothing.)
                 if (grp == 0) {
-                    if (it + 1 < nt) {
-                        put_v(vreg, Vs + ((it + 1) & 1) * VT_, tile_j0(it + 1));    // V(it+1) over V(it-1)
-                        if (it + 2 < nt) fetch_v(tile_j0(it + 2), vreg);
-                    }
-                } else if (it + 2 < nt) {
+                    put_v(vreg, Vs + ((it + 1) & 1) * VT_, j1);                     // V(it+1) over V(it-1)
+                    fetch_v(j_far, vreg);                                           // V(it+2)
+                } else {
                     put_k(kreg, Ks + (it & 1) * KT);                                // K(it+2) over K(it)
-                    if (it + 3 < nt) fetch_k(tile_j0(it + 3), kreg);
+                    fetch_k(j_far, kreg);                                           // K(it+3)
                 }
                 if (!idle) {
                     pv_tile(Vs + (it & 1) * VT_);
-                    if (it + 1 < nt) s_tile(Ks + ((it + 1) & 1) * KT);
+                    s_tile(Ks + ((it + 1) & 1) * KT);
                 }
                 __syncthreads();
             }
