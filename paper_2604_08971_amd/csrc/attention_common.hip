@@ -447,10 +447,11 @@ AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws)
     pl.splits = 1;
     pl.keys_per_split = (int)align_up(a.L, 64);
     if (dtype == SF_BF16 && sparse && a.U > 0) {
-        // the active pass has only B*nG independent (sample, group) problems:
-        // split the keys until roughly 768 workgroups exist
+        // the active pass has only B*nG independent (sample, group) problems: with fewer than one per compute unit
+        // the keys are split until roughly 512 workgroups exist (measured on the four bf16 workloads against
+        // targets of 256, 768 and 1536: more splits cost more in partial sums and their merge than they gain)
         const int64_t bg = (int64_t)a.B * a.nG;
-        int want = (int)((768 + bg - 1) / bg);
+        int want = bg >= 256 ? 1 : (int)((512 + bg - 1) / bg);
         const int max_splits = a.L / 128 > 0 ? a.L / 128 : 1;
         if (want > max_splits) want = max_splits;
         if (want > 64) want = 64;                     // the merge holds one split per lane
