@@ -243,6 +243,13 @@ def bench_config(name, steps, warmup, extras, cpu, use_graph=False, repeats=1):
                              "ms_per_step": tot_ms / steps,
                              "tflops": flops[key] * steps / (tot_ms * 1e-3) / 1e12 if tot_ms > 0 else None}
                 prof[key]["frac_of_bf16_peak"] = prof[key]["tflops"] / PEAK_BF16_TFLOPS if prof[key]["tflops"] else None
+                if key == "active" and tot_ms > 0:
+                    # the bound that matters for the sparse pattern: K and V of every referenced (sample, group) once
+                    kv_bytes = sum(int(masks_host["n_groups"][l][wl.pattern_id].astype(np.int64).sum()) * 2 * L * s.dh * 2
+                                   for l in range(s.n_layers))
+                    prof[key]["kv_algorithmic_bytes_per_step"] = kv_bytes
+                    prof[key]["kv_GBs"] = kv_bytes * steps / (tot_ms * 1e-3) / 1e9
+                    prof[key]["kv_frac_of_hbm_peak"] = prof[key]["kv_GBs"] / PEAK_HBM_GBS
             if key == "gemm" and n and n % steps == 0 and n // steps in (4 * s.n_layers, 5 * s.n_layers):
                 # the GEMM launches of a layer, in launch order, averaged over steps and layers: four when the
                 # Q/K/V projection is one launch (large shapes), five when V is projected separately
@@ -784,6 +791,16 @@ def main():
     from paper_2604_08971_amd import workloads as W
     sf.lib()
 
+    if args.copy_calibration > 0:
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"copy calibration: 3 device copies of {args.copy_calibration} MiB (reads and writes that many bytes each)")
+        del src, dst
+
     if args.moe_only:
         print(json.dumps(bench_moe(W.make_workload(W.CONFIGS[args.config]), args.steps, args.warmup)), flush=True)
         return
@@ -809,16 +826,6 @@ def main():
     if args.f16_only:
         print(json.dumps(bench_f16(W.make_workload(W.CONFIGS[args.config]), args.steps, args.warmup)), flush=True)
         return
-
-    if args.copy_calibration > 0:
-        n = args.copy_calibration << 20
-        src = torch.ones(n, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        log(f"copy calibration: 3 device copies of {args.copy_calibration} MiB (reads and writes that many bytes each)")
-        del src, dst
 
     extras = not args.no_extras
     res, dm, wl, flops = bench_config(args.config, args.steps, args.warmup, extras, not args.no_cpu, args.graph)
