@@ -128,13 +128,16 @@ def time_steps(fn, steps, warmup):
     the GPU on the small workloads, whose steps are launch-bound)."""
     import gc
     import torch
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
+    # the collection runs before the warm-up: between the synchronisation and the first timed launch the GPU must not
+    # sit idle for the tens of milliseconds a collection takes (its clocks fall back and the first timed steps pay
+    # for the ramp: 1.8 ms per timed region measured, 9 % of 20 steps)
     gc.collect()
     gc_was = gc.isenabled()
     gc.disable()
     try:
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         ev0.record()
@@ -755,8 +758,8 @@ def cpu_baseline(wl, flops_total):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C5", help="workload timed for `value` (C1..C5)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="only the headline number")

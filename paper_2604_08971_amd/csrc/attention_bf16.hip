@@ -325,11 +325,21 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     auto tile_j0 = [&](int it) { return __builtin_amdgcn_readfirstlane((int)tiles[it]) * BKEY; };   // same for every lane
 
     for (int pair0 = chunk * (AWAVE * QB); pair0 < npairs; pair0 += chunks * (AWAVE * QB)) {
+        // When this pass has pairs for at most half of the waves (few active rows: U = c*ceil(ln L) gives one or two
+        // blocks of 32 per head), the others would only help with the staging: instead KG groups of waves take the
+        // same pairs and every KG-th key tile each, and their partial results are merged through LDS at the end.
+        int kg = 1;
+        {
+            const int waves_used = (min(npairs - pair0, AWAVE * QB) + QB - 1) / QB;
+            while (waves_used * kg * 2 <= AWAVE) kg *= 2;
+        }
+        const int pslots = AWAVE / kg;                  // waves that hold distinct pairs
+        const int pw = wave % pslots, kgi = wave / pslots;
         int head[QB], qidx[QB], slot[QB];
         h16x8 qf[QB][DH / 16];
 #pragma unroll
         for (int qq = 0; qq < QB; ++qq) {
-            const int pi = pair0 + wave * QB + qq;
+            const int pi = pair0 + pw * QB + qq;
             head[qq] = -1; qidx[qq] = -1; slot[qq] = 0;
             if (pi < npairs) {
                 head[qq] = heads[pi / nqb];
@@ -342,7 +352,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             for (int kk = 0; kk < DH / 16; ++kk)
                 qf[qq][kk] = *reinterpret_cast<const h16x8 *>(qrow + kk * 16 + lhi * 8);
         }
-        const bool idle = pair0 + wave * QB >= npairs;        // wave-uniform: no pair at all
+        const bool idle = pair0 + pw * QB >= npairs;          // wave-uniform: no pair at all
 
         f32x16 oacc[QB][DH / 32];
         float m_run[QB], l_run[QB];
@@ -365,7 +375,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             put_v(vreg, Vt, j0);
             __syncthreads();        // tile `it` visible; everyone is done with tile it-1 (the other buffers)
             if (it + 1 < nt) { const int jn = tile_j0(it + 1); KT_::fetch(Kb, sk.l, jn, L, kreg); fetch_v(jn, vreg); }
-            if (idle) continue;
+            if (idle || (it & (kg - 1)) != kgi) continue;          // not this wave's tile
             const uint32_t w0 = words[j0 / 32], w1 = (j0 / 32 + 1 < nwords) ? words[j0 / 32 + 1] : 0u;
             // the same for every lane: a tile with all 64 keys allowed skips the masking
             const bool all_allowed = (uint32_t)__builtin_amdgcn_readfirstlane((int)(w0 & w1)) == 0xffffffffu;
@@ -458,11 +468,52 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             }
         }
 
+        // merge of the key groups: in log2(KG) rounds the upper half of the groups hands its running reference, sum
+        // and accumulator over through the tile buffers (free now) and the lower half folds them into its own
+        if (kg > 1) {
+            float *mrg = reinterpret_cast<float *>(smem);              // [writer wave][QB * (DH/2 + 2)][64 lanes]
+            constexpr int PER = QB * ((DH / 32) * 16 + 2);
+            static_assert((AWAVE / 2) * PER * 64 * 4 <= 2 * KT * 2 + 2 * VT_ * 2, "merge scratch must fit in the tile buffers");
+            for (int step = kg / 2; step >= 1; step /= 2) {
+                __syncthreads();                                       // tile buffers (or the last round's slots) are free
+                if (kgi >= step && kgi < 2 * step) {
+                    float *dst = mrg + (size_t)(wave - step * pslots) * PER * 64 + lane;
+#pragma unroll
+                    for (int qq = 0; qq < QB; ++qq) {
+#pragma unroll
+                        for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) dst[((qq * (DH / 32) + db) * 16 + e) * 64] = oacc[qq][db][e];
+                        dst[(QB * (DH / 32) * 16 + qq * 2) * 64] = m_run[qq];
+                        dst[(QB * (DH / 32) * 16 + qq * 2 + 1) * 64] = l_run[qq];
+                    }
+                }
+                __syncthreads();
+                if (kgi < step) {
+                    const float *src = mrg + (size_t)wave * PER * 64 + lane;
+#pragma unroll
+                    for (int qq = 0; qq < QB; ++qq) {
+                        const float m_o = src[(QB * (DH / 32) * 16 + qq * 2) * 64], l_o = src[(QB * (DH / 32) * 16 + qq * 2 + 1) * 64];
+                        const float m_new = fmaxf(m_run[qq], m_o);
+                        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+                        const float a_me = __builtin_amdgcn_exp2f(m_run[qq] - m_safe), a_o = __builtin_amdgcn_exp2f(m_o - m_safe);
+                        m_run[qq] = m_new;
+                        l_run[qq] = l_run[qq] * a_me + l_o * a_o;
+#pragma unroll
+                        for (int db = 0; db < DH / 32; ++db)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e)
+                                oacc[qq][db][e] = oacc[qq][db][e] * a_me + src[((qq * (DH / 32) + db) * 16 + e) * 64] * a_o;
+                    }
+                }
+            }
+        }
+
         // lane owns query l32 and output dims db*32 + ig*8 + lhi*4 + {0..3}
 #pragma unroll
         for (int qq = 0; qq < QB; ++qq) {
             const float l_tot = both_halves_sum(l_run[qq]);
-            if (qidx[qq] < 0) continue;
+            if (qidx[qq] < 0 || kgi != 0) continue;
             if (splits <= 1) {
                 const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
                 h16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
@@ -880,12 +931,12 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
                            a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
                            a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
                            pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
-        return SF_OK;
+    } else {
+        hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
+                           a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
+                           a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
+                           pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
     }
-    hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
-                       a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
-                       a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
-                       pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
     return SF_OK;
 }
 

@@ -1035,3 +1035,20 @@ def test_encoder_rejects_small_workspace():
     with pytest.raises(sf.SentryFuseError, match="workspace"):
         sf.encoder_forward(dm.desc, dm.layers, dm.x, dm.pattern_id, dm.key_valid, dm.final_ln,
                            ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+
+def test_measurement_aids_run_and_copy_is_exact():
+    # the register-only MFMA loop reports its flops; the copy aid copies bit for bit (ragged tail of the 4-way unroll too)
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    assert sf.ceiling_mfma_launch(8, 10, False, sink) == 8 * 8 * 10 * 32 * 32768
+    assert sf.ceiling_mfma_launch(8, 10, True, sink) == 8 * 8 * 10 * 32 * 32768
+    torch.cuda.synchronize()
+    assert not sink.any()
+    for n in (16, 4096 + 16, (1 << 22) + 48):
+        src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+        dst = torch.zeros_like(src)
+        sf.ceiling_copy_launch(src, dst)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
+    with pytest.raises(sf.SentryFuseError):
+        sf.ceiling_mfma_launch(0, 10, False, sink)
