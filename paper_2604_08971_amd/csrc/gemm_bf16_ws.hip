@@ -102,8 +102,10 @@ __device__ __forceinline__ bool next_tile(const GemmArgs &a, int tiles_m, int ti
             tm_i = w / tiles_n;
             // when the workgroups of an XCD are a multiple of the tiles per row, a workgroup would meet the same
             // column in every round: rotate the columns from round to round (tiles of unequal cost then spread
-            // over all workgroups)
-            if (stride % tiles_n == 0) tn_i = (tn_i + s / stride) % tiles_n;
+            // over all workgroups).  Only when the XCD's range starts on a row boundary too: then the tiles of a
+            // row lie in one round of one XCD and the rotation permutes them; a row that straddles two rounds or
+            // two XCDs would get one column twice and another not at all.
+            if (stride % tiles_n == 0 && per_xcd % tiles_n == 0) tn_i = (tn_i + s / stride) % tiles_n;
         }
         t.b = tm_i / tiles_m;
         t.m0 = (tm_i % tiles_m) * BM;

@@ -728,6 +728,8 @@ def test_sparse_gqa_is_deterministic():
 @pytest.mark.parametrize("dtype,act,B,L,d,F,keep", [
     ("f32", 0, 2, 48, 64, 256, 0.5), ("f32", 1, 3, 37, 40, 100, 0.33),
     ("bf16", 0, 4, 384, 256, 1024, 0.6), ("bf16", 1, 3, 203, 128, 520, 0.71), ("bf16", 0, 2, 4096, 768, 3072, 0.7),
+    # 37 tile slots per XCD, four column tiles per row: rows of tiles that straddle two rounds of the persistent walk
+    ("bf16", 0, 37, 512, 256, 1280, 0.8),
 ])
 def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
     _say(f"ffn {dtype} act={act} B={B} L={L} d={d} F={F}")
