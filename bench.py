@@ -713,17 +713,40 @@ def bench_tokens(name, steps, warmup):
     cut = 256
     short, long_ = np.nonzero(lens <= cut)[0], np.nonzero(lens > cut)[0]
     two = [make_group(ix) for ix in (short, long_) if len(ix)]
+    # no padding: the valid tokens of all samples back to back, runs by pattern; the caller knows the presence counts
+    # and sizes the packed buffers for them
+    Tc = int(sum(-(-int(lens[wl.pattern_id == p].sum()) // 256) * 256 for p in np.unique(wl.pattern_id))
+             + -(-s.L // 256) * 256)
+    plan = sf.TokenPackPlan(B, s.L, Tc, dm.x.device)
+    dp = desc_for(wl, U_override=int(u.max()))
+    ws_p = sf.workspace(sf.encoder_packed_workspace_bytes(dp, dm.layers, Tc))
+    Xp = torch.empty((Tc, s.d), dtype=dm.x.dtype, device=dm.x.device)
+    Yp, Yfull = torch.empty_like(Xp), torch.empty_like(dm.x)
+
+    def packed():
+        sf.token_pack(dm.desc, dm.x, dm.key_valid, dm.pattern_id, plan=plan, out=Xp)
+        sf.encoder_forward_packed(dp, dm.layers, Xp, plan, dm.pattern_id, final_ln=dm.final_ln, ws=ws_p, out=Yp)
+        return sf.token_unpack(dm.desc, Yp, plan, out=Yfull)
+
+    def packed_encoder_only():
+        sf.encoder_forward_packed(dp, dm.layers, Xp, plan, dm.pattern_id, final_ln=dm.final_ln, ws=ws_p, out=Yp)
+
     ms_masked, _ = time_steps(masked, steps, warmup)
+    ms_packed, _ = time_steps(packed, steps, warmup)
+    ms_packed_enc, _ = time_steps(packed_encoder_only, steps, warmup)
+    n_rows = plan.n_rows.cpu().numpy()
+    assert n_rows[0] == n_rows[1] == Tc, (n_rows, Tc)
     ms_two, _ = time_steps(lambda: [run_group(g) for g in two], steps, warmup)
     ms_one, _ = time_steps(lambda: [run_group(g) for g in one], steps, warmup)
     ms_grp, _ = time_steps(lambda: [run_group(g) for g in by_pattern], steps, warmup)
     rows_grp = int(sum(g[3] * g[0].shape[0] for g in by_pattern))
     return {"workload": name, "tokens_total": int(B * s.L), "tokens_present": int(lens.sum()),
-            "ms_masked": ms_masked, "ms_compacted_one_batch": ms_one, "Lc_one_batch": one[0][3],
+            "ms_masked": ms_masked, "ms_packed": ms_packed, "ms_packed_encoder_only": ms_packed_enc, "rows_packed": Tc,
+            "ms_compacted_one_batch": ms_one, "Lc_one_batch": one[0][3],
             "ms_compacted_two_buckets": ms_two, "rows_two_buckets": int(sum(g[3] * g[0].shape[0] for g in two)),
             "ms_compacted_per_pattern": ms_grp, "pattern_groups": len(by_pattern), "rows_per_pattern_batches": rows_grp,
-            "note": "encoder step only (plan excluded); compaction + ragged encoder + scatter per batch, eager launches; "
-                    "not part of `value`"}
+            "note": "encoder step only (plan excluded); packed: pack + encoder over the packed rows + unpack; compacted: "
+                    "compaction + ragged encoder + scatter per padded batch; eager launches; not part of `value`"}
 
 
 def C_byref(x):

@@ -518,6 +518,75 @@ int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compact_layer *l
                                   float *score_out, void *workspace, size_t workspace_bytes,
                                   void *stream);
 
+/*
+ * Token compaction without padding (Sec. 4.2 / 4.4, as above; the layout is this
+ * library's).  The valid tokens of all samples lie back to back in one
+ * [Tc, d] buffer: samples ordered by presence pattern, then by sample number;
+ * every pattern's run of rows starts on a multiple of 256, so a 256-row block
+ * holds rows of one pattern (it may straddle samples).  LayerNorm and the four
+ * GEMMs of a layer then run over the blocks in use only; the attention steps
+ * see sample b as the rows row0[b] .. row0[b] + len[b] - 1 with at most L
+ * positions, and its number of active queries is u_active[b] (formula above).
+ * Behind the last run lie align(L, 256) rows of slack (zero input rows) that
+ * the attention kernels may read but never use.
+ *
+ * sf_token_pack_plan is a host struct of device pointers, all written by
+ * sf_token_pack (the caller allocates them and sets Tc):
+ *   Tc           rows of the packed buffers, a positive multiple of 256;
+ *                sf_token_pack_rows_max(desc) is enough for every input
+ *                (desc->P = number of presence patterns); a caller that knows
+ *                the presence counts can pass less
+ *   len          [B]      T_b, the valid tokens of sample b
+ *   u_active     [B]
+ *   row0         [B]      first packed row of sample b
+ *   ext          [B]      rows of the attention output that sample b answers
+ *                         for: len[b], plus - for the last sample of a run -
+ *                         the padding up to the next run (and the slack)
+ *   valid_c      [B,L]    1 for positions < T_b
+ *   blk_pattern  [Tc/256] presence pattern of each 256-row block, -1: unused
+ *   src_row      [Tc]     source row b*L + i of each packed row, -1: padding
+ *   dst_row      [B,L]    packed row of each token, -1 for dropped tokens
+ *   n_rows       [2]      [0] rows in use (runs + slack), [1] rows needed.
+ *                         n_rows[1] > Tc: the rows did not fit; the plan is
+ *                         then the empty one (no sample has rows, Xp is zero,
+ *                         the encoder does nothing) and the caller comes back
+ *                         with Tc >= n_rows[1].
+ * sf_token_pack: X [B,L,d], token_valid [B,L], pattern_id [B] (NULL with P = 1)
+ * in; the plan and Xp [Tc,d] (zero rows where src_row < 0) out.
+ * sf_encoder_forward_packed is sf_encoder_forward over the packed rows (desc
+ * as for the padded batch: B samples of at most L tokens, U >= every
+ * u_active[b] and U < L); Xp, Yp [Tc,d]; sel_out [n_layers,B,kmax_head,U] holds
+ * positions inside the sample, rows padded with -1; score_out
+ * [n_layers,B,kmax_head,L].  Rows of Yp that are padding hold unspecified finite
+ * or non-finite values and are never read by sf_token_unpack.  Projections and
+ * FFN in FP8 arithmetic are not offered on packed rows.
+ * sf_token_unpack writes Y[b,i,:] = Yp[dst_row[b,i],:], zero rows for dropped
+ * tokens.  All index outputs are bit-exact.
+ * Errors: SF_ERR_INVALID_ARG (NULL, Tc not a multiple of 256, aliasing),
+ * SF_ERR_SHAPE, SF_ERR_WORKSPACE (sf_encoder_packed_workspace_bytes), as for
+ * sf_encoder_forward.
+ */
+typedef struct sf_token_pack_plan {
+    int32_t Tc;
+    int32_t *len, *u_active, *row0, *ext;
+    uint8_t *valid_c;
+    int32_t *blk_pattern, *src_row, *dst_row, *n_rows;
+} sf_token_pack_plan;
+int32_t sf_token_pack_rows_max(const sf_desc *desc);
+int32_t sf_token_pack(const sf_desc *desc, const void *X, const uint8_t *token_valid,
+                      const int32_t *pattern_id, const sf_token_pack_plan *plan, void *Xp,
+                      void *stream);
+int32_t sf_token_unpack(const sf_desc *desc, const void *Yp, const sf_token_pack_plan *plan,
+                        void *Y, void *stream);
+size_t sf_encoder_packed_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers_host,
+                                         int32_t Tc);
+int32_t sf_encoder_forward_packed(const sf_desc *desc, const sf_compact_layer *layers_host,
+                                  const void *Xp, const sf_token_pack_plan *plan,
+                                  const int32_t *pattern_id, const int32_t *sample_idx,
+                                  const void *final_g, const void *final_b, void *Yp,
+                                  int32_t *sel_out, float *score_out, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------------
  * Sparse-MoE FFN with pruned experts -- Sec. 4.5 "Sparse-MoE FFN pruning":
  * the number of experts E and the Top-k routing stay fixed; expert e keeps

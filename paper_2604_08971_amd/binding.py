@@ -36,7 +36,8 @@ EXPORTS = ["sf_last_error", "sf_num_active", "sf_ffn_padded", "sf_gate_scores_to
            "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_fp8_workspace_bytes",
            "sf_encoder_forward_fp8", "sf_proj_fp8_padded", "sf_presence_to_key_valid",
            "sf_sparse_gqa_static_capacity", "sf_sparse_gqa_forward_static", "sf_ceiling_mfma_launch",
-           "sf_ceiling_copy_launch"]
+           "sf_ceiling_copy_launch", "sf_token_pack_rows_max", "sf_token_pack", "sf_token_unpack",
+           "sf_encoder_packed_workspace_bytes", "sf_encoder_forward_packed"]
 SF_GATE_RELU, SF_GATE_TANH = 0, 1
 SF_KERNEL_GEMM, SF_KERNEL_SCORE, SF_KERNEL_ATTEND = 0, 1, 2
 
@@ -87,6 +88,12 @@ class SfProjFp8(C.Structure):
                 + [(n, C.c_float) for n in ("s_qkv", "so", "sx1", "sa")])
 
 
+class SfTokenPackPlan(C.Structure):
+    _fields_ = ([("Tc", C.c_int32)]
+                + [(n, C.c_void_p) for n in ("len", "u_active", "row0", "ext", "valid_c", "blk_pattern", "src_row",
+                                             "dst_row", "n_rows")])
+
+
 class SfMoeDense(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _MOE_DENSE_FIELDS]
 
@@ -127,7 +134,7 @@ def lib():
         L.sf_last_error.restype = C.c_char_p
         for n in ("sf_sparse_gqa_workspace_bytes", "sf_pruned_ffn_workspace_bytes", "sf_encoder_workspace_bytes",
                   "sf_moe_ffn_workspace_bytes", "sf_pruned_ffn_fp8_workspace_bytes", "sf_encoder_fp8_workspace_bytes",
-                  "sf_sparse_gqa_static_capacity"):
+                  "sf_sparse_gqa_static_capacity", "sf_encoder_packed_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         for n in ("sf_num_active", "sf_ffn_padded", "sf_gate_scores_to_masks", "sf_compact_heads_channels",
                   "sf_sparse_gqa_forward", "sf_pruned_ffn_forward", "sf_encoder_forward", "sf_profile_begin",
@@ -136,8 +143,17 @@ def lib():
                   "sf_quantize_fp8", "sf_pruned_ffn_fp8_forward", "sf_token_compact", "sf_token_scatter",
                   "sf_encoder_forward_ragged", "sf_encoder_forward_fp8ffn", "sf_compact_heads_channels_f16",
                   "sf_active_projection_rows", "sf_compact_proj_fp8", "sf_encoder_forward_fp8", "sf_proj_fp8_padded",
-                  "sf_presence_to_key_valid", "sf_sparse_gqa_forward_static"):
+                  "sf_presence_to_key_valid", "sf_sparse_gqa_forward_static", "sf_token_pack_rows_max",
+                  "sf_token_pack", "sf_token_unpack", "sf_encoder_forward_packed"):
             getattr(L, n).restype = C.c_int32
+        L.sf_token_pack_rows_max.argtypes = [C.POINTER(SfDesc)]
+        L.sf_token_pack.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(SfTokenPackPlan),
+                                    C.c_void_p, C.c_void_p]
+        L.sf_token_unpack.argtypes = [C.POINTER(SfDesc), C.c_void_p, C.POINTER(SfTokenPackPlan), C.c_void_p, C.c_void_p]
+        L.sf_encoder_packed_workspace_bytes.argtypes = [C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.c_int32]
+        L.sf_encoder_forward_packed.argtypes = ([C.POINTER(SfDesc), C.POINTER(SfCompactLayer), C.c_void_p,
+                                                 C.POINTER(SfTokenPackPlan)] + [C.c_void_p] * 8
+                                                + [C.c_size_t, C.c_void_p])
         L.sf_sparse_gqa_forward.argtypes = [
             C.POINTER(SfDesc), C.c_int32, C.c_int32, C.c_void_p, SfStrides, C.c_void_p, SfStrides, C.c_void_p,
             SfStrides, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -750,6 +766,80 @@ def token_scatter(desc: SfDesc, Yc: torch.Tensor, slot_of: torch.Tensor) -> torc
     Y = torch.empty((B, desc.L, d), dtype=Yc.dtype, device=Yc.device)
     _check(lib().sf_token_scatter(C.byref(desc), _ptr(Yc), _ptr(slot_of), int(Lc), _ptr(Y), _stream()), "sf_token_scatter")
     return Y
+
+
+class TokenPackPlan:
+    """The device arrays of a packed token layout (sf_token_pack_plan) and the struct that points at them."""
+
+    def __init__(self, B: int, L: int, Tc: int, device):
+        i32 = lambda *sh: torch.empty(sh, dtype=torch.int32, device=device)
+        self.B, self.L, self.Tc = B, L, Tc
+        self.len, self.u_active, self.row0, self.ext = i32(B), i32(B), i32(B), i32(B)
+        self.valid_c = torch.empty((B, L), dtype=torch.uint8, device=device)
+        self.blk_pattern, self.src_row, self.dst_row, self.n_rows = i32(Tc // 256), i32(Tc), i32(B, L), i32(2)
+        self.c = SfTokenPackPlan()
+        self.c.Tc = Tc
+        for n in ("len", "u_active", "row0", "ext", "valid_c", "blk_pattern", "src_row", "dst_row", "n_rows"):
+            setattr(self.c, n, getattr(self, n).data_ptr())
+
+
+def token_pack_rows_max(desc: SfDesc) -> int:
+    n = lib().sf_token_pack_rows_max(C.byref(desc))
+    _check(min(n, 0), "sf_token_pack_rows_max")
+    return int(n)
+
+
+def encoder_packed_workspace_bytes(desc: SfDesc, layers: List[CompactLayer], Tc: int) -> int:
+    return int(lib().sf_encoder_packed_workspace_bytes(C.byref(desc), layer_array(layers), int(Tc)))
+
+
+def token_pack(desc: SfDesc, X: torch.Tensor, token_valid: torch.Tensor, pattern_id: Optional[torch.Tensor],
+               Tc: Optional[int] = None, plan: Optional[TokenPackPlan] = None, out: Optional[torch.Tensor] = None):
+    """X [B,L,d], token_valid [B,L] uint8, pattern_id [B] int32 | None.  Returns (Xp [Tc,d], plan); plan.n_rows[1] > Tc
+    says that Tc was too small (the plan is then empty)."""
+    assert X.is_contiguous() and token_valid.is_contiguous() and token_valid.dtype == torch.uint8
+    B, L, d = X.shape
+    if plan is None:
+        plan = TokenPackPlan(B, L, token_pack_rows_max(desc) if Tc is None else int(Tc), X.device)
+    Xp = torch.empty((plan.Tc, d), dtype=X.dtype, device=X.device) if out is None else out
+    rc = lib().sf_token_pack(C.byref(desc), _ptr(X), _ptr(token_valid), _ptr(pattern_id), C.byref(plan.c), _ptr(Xp),
+                             _stream())
+    _check(rc, "sf_token_pack")
+    return Xp, plan
+
+
+def token_unpack(desc: SfDesc, Yp: torch.Tensor, plan: TokenPackPlan, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Yp [Tc,d] -> Y [B,L,d], zero rows for dropped tokens."""
+    assert Yp.is_contiguous()
+    Y = torch.empty((plan.B, plan.L, Yp.shape[1]), dtype=Yp.dtype, device=Yp.device) if out is None else out
+    _check(lib().sf_token_unpack(C.byref(desc), _ptr(Yp), C.byref(plan.c), _ptr(Y), _stream()), "sf_token_unpack")
+    return Y
+
+
+def encoder_forward_packed(desc: SfDesc, layers: List[CompactLayer], Xp: torch.Tensor, plan: TokenPackPlan,
+                           pattern_id: Optional[torch.Tensor], final_ln: Optional[Dict[str, torch.Tensor]] = None,
+                           want_sel: bool = False, want_score: bool = False, ws: Optional[torch.Tensor] = None,
+                           sample_idx: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
+    """sf_encoder_forward over packed rows.  Returns (Yp [Tc,d], sel [nl,B,Hq'max,U] | None, score | None)."""
+    assert Xp.is_contiguous() and Xp.shape[0] == plan.Tc
+    _check_sample(desc, sample_idx, plan.B)
+    nl = desc.n_layers
+    U = num_active(desc)
+    khmax = max(l.k_head for l in layers)
+    dev = Xp.device
+    Yp = torch.empty_like(Xp) if out is None else out
+    sel = torch.full((nl, plan.B, khmax, max(U, 1)), -1, dtype=torch.int32, device=dev) if want_sel else None
+    score = torch.full((nl, plan.B, khmax, plan.L), float("-inf"), dtype=torch.float32, device=dev) if want_score else None
+    arr = layer_array(layers)
+    if ws is None:
+        ws = workspace(encoder_packed_workspace_bytes(desc, layers, plan.Tc), dev)
+    fg = None if final_ln is None else final_ln["g"]
+    fb = None if final_ln is None else final_ln["b"]
+    rc = lib().sf_encoder_forward_packed(C.byref(desc), arr, _ptr(Xp), C.byref(plan.c), _ptr(pattern_id), _ptr(sample_idx),
+                                         _ptr(fg), _ptr(fb), _ptr(Yp), _ptr(sel), _ptr(score), _ptr(ws), ws.numel(),
+                                         _stream())
+    _check(rc, "sf_encoder_forward_packed")
+    return Yp, sel, score
 
 
 def encoder_forward_ragged(desc: SfDesc, layers: List[CompactLayer], X: torch.Tensor, pattern_id, key_valid: torch.Tensor,

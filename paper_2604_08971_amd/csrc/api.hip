@@ -152,7 +152,10 @@ static AttnArgs enc_attn_args(const Dims &D, int kh)
     return a;
 }
 
-static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, EncWs &w, bool proj8 = false)
+// rows_tok > 0: the token-major buffers hold that many rows (samples packed back to back) instead of B*L, and Q, K
+// and V are all token-major (V is transposed by a pass of its own)
+static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, EncWs &w, bool proj8 = false,
+                      size_t rows_tok = 0)
 {
     w = EncWs{};
     int kh_max = 0, kf_max = 0;
@@ -165,8 +168,9 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     w.kh_max = kh_max;
     w.Fp_max = (int)align_up(kf_max, D.ffn_pad);
     w.Lp = (int)align_up(D.L, 8);
-    const size_t es = elem_size(D.dtype), rows = (size_t)D.B * D.L;
+    const size_t es = elem_size(D.dtype), rows = rows_tok ? rows_tok : (size_t)D.B * D.L;
     const bool bf = D.dtype == SF_BF16;
+    if (rows_tok) proj8 = true;              // same buffer shapes: Q, K, V token-major and a transposed copy of V
     Carver c(ws);
     w.xn = c.take<char>(rows * D.d * es);
     // bf16: Q and K token-major, V transposed [B,Hk,dh,Lp]; fp32: Q, K, V token-major
@@ -185,8 +189,8 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
     w.attn_ws_bytes = amax;
     w.attn_ws = c.take<char>(amax);
     const size_t Kp_max = align_up((size_t)kh_max * D.dh, 128);      // code rows are padded to the FP8 GEMM's K step
-    w.oq = proj8 ? c.take<uint8_t>(rows * Kp_max) : nullptr;
-    w.lz_cap = bf ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
+    w.oq = proj8 && !rows_tok ? c.take<uint8_t>(rows * Kp_max) : nullptr;
+    w.lz_cap = bf && !rows_tok ? lazy_cap(D.L, kh_max, D.U, D.dh, D.d) : 0;
     if (w.lz_cap) {
         const size_t crow = (size_t)D.B * w.lz_cap;
         w.lz_A = c.take<char>(crow * kh_max * D.dh * es);
@@ -319,10 +323,11 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
                                     size_t workspace_bytes, void *stream, const sf_ffn_fp8 *ffn8 = nullptr,
                                     uint8_t *xq_out = nullptr, uint8_t *hq_out = nullptr,
                                     const sf_proj_fp8 *proj8 = nullptr, uint8_t *aq_out = nullptr,
-                                    uint8_t *oq_out = nullptr)
+                                    uint8_t *oq_out = nullptr, const sf_token_pack_plan *pk = nullptr)
 {
     Dims D;
     if (int32_t rc = read_desc(desc, D)) return rc;
+    if (pk && (ffn8 || proj8)) return fail(SF_ERR_UNSUPPORTED, "encoder(packed): no FP8 arithmetic on packed rows");
     int Fp8_max = 0;
     if (ffn8) {
         if (!layers) return fail(SF_ERR_INVALID_ARG, "encoder: NULL argument");
@@ -369,7 +374,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         return fail(SF_ERR_SHAPE, "encoder(f32): dh must be a multiple of 4, at most 256");
     if (D.Hq > 64) return fail(SF_ERR_SHAPE, "encoder: Hq <= 64 required");
     EncWs w;
-    if (int32_t rc = enc_ws(D, layers, workspace, w, proj8 != nullptr)) return rc;
+    if (int32_t rc = enc_ws(D, layers, workspace, w, proj8 != nullptr, pk ? (size_t)pk->Tc : 0)) return rc;
     if (!workspace || workspace_bytes < w.bytes || ((uintptr_t)workspace & 255))
         return fail(SF_ERR_WORKSPACE, "encoder: workspace of %zu bytes (256-byte aligned) required, got %zu",
                     w.bytes, workspace_bytes);
@@ -377,7 +382,12 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf = D.dtype == SF_BF16;
     const size_t es = elem_size(D.dtype);
-    const int64_t rows = (int64_t)D.B * D.L;
+    // Packed rows: the row-wise steps (LayerNorm, GEMMs) see Tc/256 "samples" of 256 rows, each with the pattern of
+    // its block (negative: unused, skipped); only the attention steps see the real samples.
+    Dims Dg = D;
+    const int32_t *gpat = pattern_id;
+    if (pk) { Dg.B = pk->Tc / 256; Dg.L = 256; gpat = pk->blk_pattern; }
+    const int64_t rows = (int64_t)Dg.B * Dg.L;
     // The residual stream is kept in fp32 between layers (x1 after the attention
     // block, x2 after the FFN); only the tensors feeding a contraction and the
     // final output are stored in the model dtype.
@@ -388,7 +398,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         const sf_compact_layer &ly = layers[l];
         const int kh = ly.k_head, dh = D.dh, Hk = D.Hk;
         const int Nqk = (kh + Hk) * dh, Nqkv = (kh + 2 * Hk) * dh;
-        const int ldq = bf && !proj8 ? Nqk : Nqkv;          // row length of the token-major buffer
+        const int ldq = bf && !proj8 && !pk ? Nqk : Nqkv;   // row length of the token-major buffer
 
         // x' = LN1(x);  Q, K (token-major) and V (bf16: transposed) = x' Wqkv'^T + b
         if (proj8) {
@@ -407,10 +417,15 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             layernorm(D.dtype, in_f32, in, ly.ln1_g, ly.ln1_b, D.eps, rows, D.d, w.xn, st);
             GemmArgs g{};
             g.A = w.xn; g.lda = D.d; g.W = ly.Wqkv; g.ldw = D.d; g.w_pstride = (int64_t)Nqkv * D.d;
-            g.bias = ly.bqkv; g.bias_pstride = Nqkv; g.pattern_id = pattern_id;
-            g.B = D.B; g.L = D.L; g.K = D.d; g.act = ACT_NONE; g.epi = EPI_ROWMAJOR;
-            g.C = w.qkv; g.ldc = ldq; g.n0 = 0; g.N = bf ? Nqk : Nqkv;
-            if (bf) {
+            g.bias = ly.bqkv; g.bias_pstride = Nqkv; g.pattern_id = gpat;
+            g.B = Dg.B; g.L = Dg.L; g.K = D.d; g.act = ACT_NONE; g.epi = EPI_ROWMAJOR;
+            g.C = w.qkv; g.ldc = ldq; g.n0 = 0; g.N = bf && !pk ? Nqk : Nqkv;
+            if (bf && pk) {
+                // Q, K, V token-major in one launch; V^T per sample (what the attention kernels read) by a pass of
+                // its own, since a 256-row block of packed rows may straddle samples
+                if (int32_t rc = gemm(D.dtype, g, st)) return rc;
+                transpose_v(w.qkv, Nqkv, Nqk, Hk * dh, D.B, D.L, w.Lp, w.vt, st, pk->row0);
+            } else if (bf) {
                 // one launch for Q, K and V when the large-tile kernel takes it (V is the transposed column range:
                 // the normalised input is read once); otherwise Q/K and V separately
                 GemmArgs q3 = g;
@@ -438,6 +453,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             a.V = (const char *)w.qkv + (size_t)(kh + Hk) * dh * es; a.sv = a.sq;
         }
         a.head_group = ly.head_group; a.hg_stride = D.Hq; a.pattern_id = pattern_id; a.key_valid = key_valid;
+        if (pk) { a.row0 = pk->row0; a.ext = pk->ext; }
         a.sample_idx = D.n_sample > 0 ? sample_idx : nullptr;
         a.u_active = u_active;
         a.selH = w.kh_max;
@@ -450,7 +466,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         // Most rows lazy in every head: project only the active rows, the rest of a sample shares one vector
         // (in FP8 arithmetic the compact rows go through the FP8 GEMM, which wants at least 192 rows per sample)
         const int capA = w.lz_cap ? lazy_cap(D.L, kh, D.U, dh, D.d) : 0;
-        const bool lazy = capA > 0 && capA <= w.lz_cap && (!proj8 || capA >= 256) &&
+        const bool lazy = !pk && capA > 0 && capA <= w.lz_cap && (!proj8 || capA >= 256) &&
                           !(((uintptr_t)ly.bo | (uintptr_t)ly.ln2_g | (uintptr_t)ly.ln2_b | (uintptr_t)in) & 15);
         a.skip_fill = lazy && !(proj8 && oq_out);        // a caller who wants the codes of every row gets the rows filled
         if (int32_t rc = attention_forward(D.dtype, a, st)) return rc;
@@ -527,8 +543,8 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         } else {
             GemmArgs o{};
             o.A = w.att; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
-            o.w_pstride = (int64_t)D.d * kh * dh; o.bias = ly.bo; o.bias_pstride = 0; o.pattern_id = pattern_id;
-            o.B = D.B; o.L = D.L; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
+            o.w_pstride = (int64_t)D.d * kh * dh; o.bias = ly.bo; o.bias_pstride = 0; o.pattern_id = gpat;
+            o.B = Dg.B; o.L = Dg.L; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
             o.R = in; o.ldr = D.d; o.r_f32 = in_f32; o.C = w.x1; o.ldc = D.d; o.c_f32 = 1;
             if (int32_t rc = gemm(D.dtype, o, st)) return rc;
         }
@@ -543,7 +559,7 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
             if (int32_t rc = ffn_fp8_forward(D, ffn8[l], w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y,
                                              xq, hq, st))
                 return rc;
-        } else if (int32_t rc = ffn_forward(D, ly, w.x1, true, pattern_id, true, true, to_y ? Y : w.x2, !to_y, w.xn,
+        } else if (int32_t rc = ffn_forward(Dg, ly, w.x1, true, gpat, true, true, to_y ? Y : w.x2, !to_y, w.xn,
                                             w.hid, st))
             return rc;
         in = w.x2;
@@ -587,6 +603,30 @@ extern "C" int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compa
     if (!u_active) return fail(SF_ERR_INVALID_ARG, "encoder_ragged: u_active is NULL");
     return encoder_forward_impl(desc, layers, X, pattern_id, key_valid, sample_idx, u_active, final_g, final_b,
                                 nullptr, Y, sel_out, score_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t sf_encoder_packed_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers, int32_t Tc)
+{
+    Dims D;
+    EncWs w;
+    if (Tc < 256 || Tc % 256 || read_desc(desc, D) || !layers || enc_ws(D, layers, nullptr, w, false, (size_t)Tc)) return 0;
+    return w.bytes;
+}
+
+extern "C" int32_t sf_encoder_forward_packed(const sf_desc *desc, const sf_compact_layer *layers, const void *Xp,
+                                             const sf_token_pack_plan *plan, const int32_t *pattern_id,
+                                             const int32_t *sample_idx, const void *final_g, const void *final_b,
+                                             void *Yp, int32_t *sel_out, float *score_out, void *workspace,
+                                             size_t workspace_bytes, void *stream)
+{
+    if (!plan) return fail(SF_ERR_INVALID_ARG, "encoder_packed: plan is NULL");
+    if (plan->Tc < 256 || plan->Tc % 256 || (int64_t)plan->Tc > ((int64_t)1 << 30))
+        return fail(SF_ERR_INVALID_ARG, "encoder_packed: Tc must be a positive multiple of 256 (below 2^30)");
+    if (!plan->row0 || !plan->ext || !plan->blk_pattern || !plan->valid_c || !plan->u_active)
+        return fail(SF_ERR_INVALID_ARG, "encoder_packed: NULL pointer in the plan");
+    return encoder_forward_impl(desc, layers, Xp, pattern_id, plan->valid_c, sample_idx, plan->u_active, final_g,
+                                final_b, nullptr, Yp, sel_out, score_out, workspace, workspace_bytes, stream, nullptr,
+                                nullptr, nullptr, nullptr, nullptr, nullptr, plan);
 }
 
 extern "C" size_t sf_encoder_fp8_workspace_bytes(const sf_desc *desc, const sf_compact_layer *layers)

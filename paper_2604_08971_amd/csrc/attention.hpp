@@ -22,8 +22,24 @@ struct AttnArgs {
     float *score_out;                        // [B,selH,L] or NULL
     int selH;                                // heads per sample in forced_sel / sel_out / score_out (0 = nH)
     int skip_fill;                           // leave the lazy rows of O unwritten (the caller projects them itself)
+    // Samples packed back to back in token-major Q, K, V and O (token compaction without padding): sample b starts
+    // at row row0[b] (its batch strides are not used; V is token-major) and owns ext[b] >= its length rows of O,
+    // the rows behind its tokens being padding that the fill gives the context vector (so that every row of O is
+    // defined).  The per-sample arrays of the workspace, key_valid, sel and score keep their [B, ..., L] shape, L =
+    // the longest sequence a sample may have; key_valid marks the sample's own rows.  NULL: samples b*L apart.
+    const int32_t *row0, *ext;
     void *ws; size_t ws_bytes;
 };
+
+// Element offset of sample b in a token-major tensor with strides s, and its first row in O
+__device__ __forceinline__ int64_t sample_offset(const int32_t *row0, int b, const sf_strides &s)
+{
+    return row0 ? (int64_t)row0[b] * s.l : (int64_t)b * s.b;
+}
+__device__ __forceinline__ int64_t sample_row(const int32_t *row0, int b, int L)
+{
+    return row0 ? (int64_t)row0[b] : (int64_t)b * L;
+}
 
 // Pieces of the workspace (all sizes derive from the same few integers, so the
 // size query and the forward agree by construction).

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
     const uint8_t *__restrict__ query_valid, const uint8_t *__restrict__ key_mask,
     const float *__restrict__ stats, int nH, int nG, int L, int Lk, float *__restrict__ score, int scoreH,
-    int qblocks, int n_items)
+    int qblocks, int n_items, const int32_t *__restrict__ row0, const int32_t *__restrict__ row0_k)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     h16 *Ks = reinterpret_cast<h16 *>(smem);                              // [2][BKEY][DH+PAD]
@@ -122,8 +122,9 @@ __global__ __launch_bounds__(NWAVE * 64) SF_SCORE_OCC void score_bf16_kernel(
     build_mask_words(key_mask ? key_mask + (int64_t)b * Lk : nullptr, Lk, words, nwords);
     if (threadIdx.x < DH) kbar[threadIdx.x] = stats[((int64_t)b * nG + g) * 2 * DH + threadIdx.x];
 
-    const h16 *Qb = Q + (int64_t)b * sq.b + (int64_t)h * sq.h;
-    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    // packed samples: Q (and K, unless it is the gathered key sample of the workspace) start at the sample's own row
+    const h16 *Qb = Q + sample_offset(row0, b, sq) + (int64_t)h * sq.h;
+    const h16 *Kb = K + sample_offset(row0_k, b, sk) + (int64_t)g * sk.h;
     const int q0 = (qblk * NWAVE + wave) * QBS * 32;
 
     h16x8 qf[QBS][DH / 16];
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     const int32_t *__restrict__ pattern_id, const uint8_t *__restrict__ key_valid,
     const int32_t *__restrict__ sel, int selH, int nH, int nG, int BG, int chunks, int L, int Lp, int U,
     int Upad, int splits, int keys_per_split, h16 *__restrict__ O, int64_t ldo,
-    float *__restrict__ part_o, float *__restrict__ part_ml)
+    float *__restrict__ part_o, float *__restrict__ part_ml, const int32_t *__restrict__ row0)
 {
     constexpr int NT = AWAVE * 64;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -283,8 +284,8 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     const int nqb = Upad / 32;
     const int npairs = n_heads * nqb;
 
-    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const h16 *Kb = K + sample_offset(row0, b, sk) + (int64_t)g * sk.h;
+    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;        // the transposed V is always b-strided
     const float sc = LOG2E / sqrtf((float)DH);
 
     // V^T tile chunks of this thread -> registers; keys at or beyond L are zeroed
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
                 slot[qq] = (pi % nqb) * 32 + l32;
                 if (slot[qq] < U) qidx[qq] = sel[((int64_t)b * selH + head[qq]) * U + slot[qq]];
             }
-            const h16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
+            const h16 *qrow = Q + sample_offset(row0, b, sq) + (int64_t)max(head[qq], 0) * sq.h +
                                  (int64_t)max(qidx[qq], 0) * sq.l;
 #pragma unroll
             for (int kk = 0; kk < DH / 16; ++kk)
@@ -516,7 +517,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
             if (qidx[qq] < 0 || kgi != 0) continue;
             if (splits <= 1) {
                 const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-                h16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
+                h16 *orow = O + (sample_row(row0, b, L) + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
 #pragma unroll
                 for (int db = 0; db < DH / 32; ++db)
 #pragma unroll
@@ -568,7 +569,7 @@ __global__ __launch_bounds__(AWAVE * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     const int32_t *__restrict__ pattern_id, const uint8_t *__restrict__ key_valid,
     const int32_t *__restrict__ sel, int selH, int nH, int nG, int BG, int chunks, int L, int Lp, int U,
     int Upad, int splits, int keys_per_split, h16 *__restrict__ O, int64_t ldo,
-    float *__restrict__ part_o, float *__restrict__ part_ml)
+    float *__restrict__ part_o, float *__restrict__ part_ml, const int32_t *__restrict__ row0)
 {
     constexpr int QB = 2, GT = (AWAVE / 2) * 64;                         // threads of a wave group
     static_assert(AWAVE == 8, "two groups of four waves, one wave of each per SIMD");
@@ -607,8 +608,8 @@ __global__ __launch_bounds__(AWAVE * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     const int nqb = Upad / 32;
     const int npairs = n_heads * nqb;
 
-    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const h16 *Kb = K + sample_offset(row0, b, sk) + (int64_t)g * sk.h;
+    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;        // the transposed V is always b-strided
     const float sc = LOG2E / sqrtf((float)DH);
 
     // Tile chunks (16 bytes) of one thread of a group -> registers -> LDS.  K rows at or beyond L and V^T keys at or
@@ -695,7 +696,7 @@ __global__ __launch_bounds__(AWAVE * 64) __attribute__((amdgpu_waves_per_eu(2, 2
                 slot[qq] = (pi % nqb) * 32 + l32;
                 if (slot[qq] < U) qidx[qq] = sel[((int64_t)b * selH + head[qq]) * U + slot[qq]];
             }
-            const h16 *qrow = Q + (int64_t)b * sq.b + (int64_t)max(head[qq], 0) * sq.h +
+            const h16 *qrow = Q + sample_offset(row0, b, sq) + (int64_t)max(head[qq], 0) * sq.h +
                                  (int64_t)max(qidx[qq], 0) * sq.l;
 #pragma unroll
             for (int kk = 0; kk < DH / 16; ++kk)
@@ -849,7 +850,7 @@ __global__ __launch_bounds__(AWAVE * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             if (qidx[qq] < 0) continue;
             if (splits <= 1) {
                 const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-                h16 *orow = O + ((int64_t)b * L + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
+                h16 *orow = O + (sample_row(row0, b, L) + qidx[qq]) * ldo + (int64_t)head[qq] * DH;
 #pragma unroll
                 for (int db = 0; db < DH / 32; ++db)
 #pragma unroll
@@ -895,7 +896,8 @@ static int32_t launch_score(const AttnArgs &a, const void *Kx, sf_strides skx, i
     ProfScope prof(SF_KERNEL_SCORE, st);
     hipLaunchKernelGGL((score_bf16_kernel<DH, QBS>), grid, dim3(NWAVE * 64), lds, st, (const h16 *)a.Q,
                        a.sq, (const h16 *)Kx, skx, a.head_group, a.hg_stride, a.pattern_id, a.key_valid,
-                       key_mask, stats, a.nH, a.nG, a.L, Lk, score, scoreH, qblocks, (int)items);
+                       key_mask, stats, a.nH, a.nG, a.L, Lk, score, scoreH, qblocks, (int)items, a.row0,
+                       Kx == a.K ? a.row0 : nullptr);
     return SF_OK;
 }
 
@@ -930,12 +932,12 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
         hipLaunchKernelGGL((attend_pp_bf16_kernel<DH>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
                            a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
                            a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
-                           pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
+                           pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml, a.row0);
     } else {
         hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
                            a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
                            a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
-                           pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml);
+                           pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml, a.row0);
     }
     return SF_OK;
 }

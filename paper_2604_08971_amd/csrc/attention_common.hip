@@ -16,14 +16,14 @@ template <class T>
 __global__ __launch_bounds__(256) void kv_stats_partial_kernel(
     const T *__restrict__ K, sf_strides sk, const T *__restrict__ V, sf_strides sv, int64_t v_sj,
     int64_t v_se, const uint8_t *__restrict__ key_valid, int nG, int L, int dh, int DHP,
-    float *__restrict__ part)
+    float *__restrict__ part, const int32_t *__restrict__ row0, const int32_t *__restrict__ row0_v)
 {
     __shared__ float red[2][256];
     const int bg = blockIdx.y, b = bg / nG, g = bg % nG;
     const int e = threadIdx.x % DHP, rg = threadIdx.x / DHP, nrg = 256 / DHP;
     const int j0 = blockIdx.x * STAT_CHUNK, j1 = min(L, j0 + STAT_CHUNK);
-    const T *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const T *Vb = V + (int64_t)b * sv.b + (int64_t)g * sv.h;
+    const T *Kb = K + sample_offset(row0, b, sk) + (int64_t)g * sk.h;
+    const T *Vb = V + sample_offset(row0_v, b, sv) + (int64_t)g * sv.h;      // a transposed V is b-strided
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     float sk_ = 0.f, sv_ = 0.f;
     if (e < dh)
@@ -49,14 +49,15 @@ __global__ __launch_bounds__(256) void kv_stats_partial_kernel(
 template <int DH>
 __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
     const h16 *__restrict__ K, sf_strides sk, const h16 *__restrict__ VT, sf_strides svt,
-    const uint8_t *__restrict__ key_valid, int nG, int L, float *__restrict__ part)
+    const uint8_t *__restrict__ key_valid, int nG, int L, float *__restrict__ part,
+    const int32_t *__restrict__ row0)
 {
     constexpr int CH = DH / 8, RP = 256 / CH, TPR = 256 / DH;
     __shared__ float red[RP][DH];
     const int bg = blockIdx.y, b = bg / nG, g = bg % nG, tid = threadIdx.x;
     const int j0 = blockIdx.x * STAT_CHUNK, j1 = min(L, j0 + STAT_CHUNK);
-    const h16 *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;
+    const h16 *Kb = K + sample_offset(row0, b, sk) + (int64_t)g * sk.h;
+    const h16 *Vb = VT + (int64_t)b * svt.b + (int64_t)g * svt.h;        // the transposed copy: always b-strided
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     float *o = part + (((int64_t)bg * gridDim.x + blockIdx.x) * 2) * DH;
 
@@ -182,12 +183,17 @@ template <class T, int VEC>
 __global__ __launch_bounds__(256) void fill_kernel(
     int nH, int nG, int L, int dh, const int32_t *__restrict__ slot,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
-    const float *__restrict__ stats, T *__restrict__ O, int64_t ldo)
+    const float *__restrict__ stats, T *__restrict__ O, int64_t ldo, const int32_t *__restrict__ row0,
+    const int32_t *__restrict__ ext)
 {
     extern __shared__ __attribute__((aligned(16))) char fsm[];
     float *ctx = reinterpret_cast<float *>(fsm);                 // [nH][dh]
     int32_t *sl = reinterpret_cast<int32_t *>(ctx + nH * dh);    // [nH][32]
     const int b = blockIdx.y, i0 = blockIdx.x * 32;
+    // packed samples: the rows the sample owns (its tokens and the padding behind them); rows at or beyond L have no
+    // slot entry and are padding
+    const int rows_b = ext ? ext[b] : L;
+    if (i0 >= rows_b) return;
     const int p = pattern_id ? pattern_id[b] : 0;
     for (int t = threadIdx.x; t < nH * dh; t += 256) {
         const int h = t / dh, e = t % dh;
@@ -196,19 +202,19 @@ __global__ __launch_bounds__(256) void fill_kernel(
     }
     for (int t = threadIdx.x; t < nH * 32; t += 256) {
         const int h = t / 32, i = i0 + (t % 32);
-        sl[t] = i < L ? slot[((int64_t)b * nH + h) * L + i] : 0;
+        sl[t] = i < L ? slot[((int64_t)b * nH + h) * L + i] : -1;
     }
     __syncthreads();
     const int qv = dh / VEC, per_row = nH * qv;
     for (int c = threadIdx.x; c < 32 * per_row; c += 256) {
         const int r = c / per_row, h = (c % per_row) / qv, e = (c % qv) * VEC;
         const int i = i0 + r;
-        if (i >= L) break;
+        if (i >= rows_b) break;
         if (sl[h * 32 + r] >= 0) continue;                 // active row: written by the active pass / the merge
         float v[VEC];
 #pragma unroll
         for (int t = 0; t < VEC; ++t) v[t] = ctx[h * dh + e + t];
-        T *o = O + ((int64_t)b * L + i) * ldo + (int64_t)h * dh + e;
+        T *o = O + (sample_row(row0, b, L) + i) * ldo + (int64_t)h * dh + e;
         if constexpr (sizeof(T) == 2 && VEC == 8) {
             h16x8 ov;
 #pragma unroll
@@ -229,7 +235,7 @@ template <class T>
 __global__ __launch_bounds__(256) void merge_splits_kernel(
     int nH, int L, int dh, int U, int Upad, int splits, int64_t n_waves, const int32_t *__restrict__ sel,
     int selH, const float *__restrict__ part_o, const float *__restrict__ part_ml, T *__restrict__ O,
-    int64_t ldo)
+    int64_t ldo, const int32_t *__restrict__ row0)
 {
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -256,7 +262,7 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o);
     const float inv = den > 0.f ? 1.0f / den : 0.f;
-    T *orow = O + ((int64_t)b * L + qi) * ldo + (int64_t)h * dh;
+    T *orow = O + (sample_row(row0, (int)b, L) + qi) * ldo + (int64_t)h * dh;
     for (int e = lane; e < dh; e += 64) {
         float acc = 0.f;
         const float *po = part_o + (base * Upad + s) * dh + e;
@@ -268,13 +274,14 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(
 
 // V [B,nG,L,dh] -> VT [B,nG,dh,Lp] (bf16), 32x32 tiles through LDS.
 __global__ __launch_bounds__(256) void transpose_v_kernel(const uint16_t *__restrict__ V, sf_strides sv, int nG,
-                                                          int L, int dh, int Lp, uint16_t *__restrict__ VT)
+                                                          int L, int dh, int Lp, uint16_t *__restrict__ VT,
+                                                          const int32_t *__restrict__ row0)
 {
     __shared__ uint16_t tile[32][33];
     const int bg = blockIdx.z, b = bg / nG, g = bg % nG;
     const int j0 = blockIdx.x * 32, e0 = blockIdx.y * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const uint16_t *Vb = V + (int64_t)b * sv.b + (int64_t)g * sv.h;
+    const uint16_t *Vb = V + sample_offset(row0, b, sv) + (int64_t)g * sv.h;
     for (int jj = ty; jj < 32; jj += 8) {
         const int j = j0 + jj, e = e0 + tx;
         tile[jj][tx] = (j < L && e < dh) ? Vb[(int64_t)j * sv.l + e] : (uint16_t)0;
@@ -294,7 +301,8 @@ __global__ __launch_bounds__(256) void score_f32_kernel(
     const float *__restrict__ Q, sf_strides sq, const float *__restrict__ K, sf_strides sk,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
     const uint8_t *__restrict__ query_valid, const uint8_t *__restrict__ key_mask,
-    const int32_t *__restrict__ n_keys, int nH, int L, int Lk, int dh, float *__restrict__ score, int scoreH)
+    const int32_t *__restrict__ n_keys, int nH, int L, int Lk, int dh, float *__restrict__ score, int scoreH,
+    const int32_t *__restrict__ row0, int keys_packed)
 {
     const int bh = blockIdx.y, b = bh / nH, h = bh % nH;
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -304,8 +312,9 @@ __global__ __launch_bounds__(256) void score_f32_kernel(
     if (n_keys[b] == 0) { *out = 0.f; return; }
     const uint8_t *km = key_mask ? key_mask + (int64_t)b * Lk : nullptr;
     const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
-    const float *q = Q + (int64_t)b * sq.b + (int64_t)h * sq.h + (int64_t)i * sq.l;
-    const float *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const float *q = Q + sample_offset(row0, b, sq) + (int64_t)h * sq.h + (int64_t)i * sq.l;
+    // the gathered key sample lives in the workspace and is b-strided whatever the layout of K
+    const float *Kb = K + sample_offset(keys_packed ? row0 : nullptr, b, sk) + (int64_t)g * sk.h;
     const float scale = 1.0f / sqrtf((float)dh);
     float mx = -INFINITY, sum = 0.f;
     for (int j = 0; j < Lk; ++j) {
@@ -330,7 +339,7 @@ __global__ __launch_bounds__(256) void gather_key_sample_kernel(
     const T *__restrict__ K, sf_strides sk, const uint8_t *__restrict__ key_valid,
     const int32_t *__restrict__ sample_idx, int n_sample, int nG, int L, int dh, int Sp,
     T *__restrict__ Ks, uint8_t *__restrict__ ks_valid, float *__restrict__ ks_stats,
-    int32_t *__restrict__ n_keys)
+    int32_t *__restrict__ n_keys, const int32_t *__restrict__ row0)
 {
     extern __shared__ uint32_t gsm[];
     const int nwords = (L + 31) / 32;
@@ -369,7 +378,7 @@ __global__ __launch_bounds__(256) void gather_key_sample_kernel(
     }
     __syncthreads();
     const int nk = nk_s;                                          // <= n_sample <= Sp
-    const T *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
+    const T *Kb = K + sample_offset(row0, b, sk) + (int64_t)g * sk.h;
     T *out = Ks + (int64_t)bg * Sp * dh;
     for (int t = tid; t < Sp * dh; t += 256) {
         const int r = t / dh, e = t % dh;
@@ -392,7 +401,7 @@ __global__ __launch_bounds__(64) void attend_f32_kernel(
     const float *__restrict__ V, sf_strides sv, int64_t v_sj, int64_t v_se,
     const int32_t *__restrict__ head_group, int hg_stride, const int32_t *__restrict__ pattern_id,
     const uint8_t *__restrict__ key_valid, const int32_t *__restrict__ sel, int selH, int nH, int L, int dh,
-    int U, float *__restrict__ O, int64_t ldo)
+    int U, float *__restrict__ O, int64_t ldo, const int32_t *__restrict__ row0)
 {
     extern __shared__ float prob[];
     const int bh = blockIdx.y, b = bh / nH, h = bh % nH, lane = threadIdx.x;
@@ -400,9 +409,9 @@ __global__ __launch_bounds__(64) void attend_f32_kernel(
     if (qi < 0) return;
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     const int g = head_group[(int64_t)(pattern_id ? pattern_id[b] : 0) * hg_stride + h];
-    const float *q = Q + (int64_t)b * sq.b + (int64_t)h * sq.h + (int64_t)qi * sq.l;
-    const float *Kb = K + (int64_t)b * sk.b + (int64_t)g * sk.h;
-    const float *Vb = V + (int64_t)b * sv.b + (int64_t)g * sv.h;
+    const float *q = Q + sample_offset(row0, b, sq) + (int64_t)h * sq.h + (int64_t)qi * sq.l;
+    const float *Kb = K + sample_offset(row0, b, sk) + (int64_t)g * sk.h;
+    const float *Vb = V + sample_offset(row0, b, sv) + (int64_t)g * sv.h;
     const float scale = 1.0f / sqrtf((float)dh);
     float mx = -INFINITY;
     for (int j = lane; j < L; j += 64) {
@@ -431,7 +440,7 @@ __global__ __launch_bounds__(64) void attend_f32_kernel(
     for (int e = lane; e < dh; e += 64) {
         float acc = 0.f;
         for (int j = 0; j < L; ++j) acc = fmaf(prob[j], Vb[(int64_t)j * v_sj + (int64_t)e * v_se], acc);
-        O[((int64_t)b * L + qi) * ldo + (int64_t)h * dh + e] = acc * inv;
+        O[(sample_row(row0, b, L) + qi) * ldo + (int64_t)h * dh + e] = acc * inv;
     }
 }
 
@@ -513,7 +522,7 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
     if (dtype == SF_BF16 && !a.v_transposed) {
         dim3 grid(ceil_div(pl.Lp, 32), ceil_div(a.dh, 32), BG);
         hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, st, (const uint16_t *)a.V, a.sv, a.nG,
-                           a.L, a.dh, pl.Lp, (uint16_t *)pl.vt);
+                           a.L, a.dh, pl.Lp, (uint16_t *)pl.vt, a.row0);
         Vuse = pl.vt;
         svu.b = (int64_t)a.nG * a.dh * pl.Lp;
         svu.h = (int64_t)a.dh * pl.Lp;
@@ -529,21 +538,21 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         dim3 grid(pl.stat_chunks, BG);
         if (dtype == SF_BF16 && vT && a.dh == 32)
             hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<32>, grid, dim3(256), 0, st, (const h16 *)a.K, a.sk,
-                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part, a.row0);
         else if (dtype == SF_BF16 && vT && a.dh == 64)
             hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<64>, grid, dim3(256), 0, st, (const h16 *)a.K, a.sk,
-                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part, a.row0);
         else if (dtype == SF_BF16 && vT && a.dh == 128)
             hipLaunchKernelGGL(kv_stats_partial_bf16_kernel<128>, grid, dim3(256), 0, st, (const h16 *)a.K, a.sk,
-                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part);
+                               (const h16 *)Vuse, svu, a.key_valid, a.nG, a.L, pl.stat_part, a.row0);
         else if (dtype == SF_BF16)
             hipLaunchKernelGGL(kv_stats_partial_kernel<h16>, grid, dim3(256), 0, st, (const h16 *)a.K,
                                a.sk, (const h16 *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
-                               DHP, pl.stat_part);
+                               DHP, pl.stat_part, a.row0, vT ? nullptr : a.row0);
         else
             hipLaunchKernelGGL(kv_stats_partial_kernel<float>, grid, dim3(256), 0, st, (const float *)a.K,
                                a.sk, (const float *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
-                               DHP, pl.stat_part);
+                               DHP, pl.stat_part, a.row0, vT ? nullptr : a.row0);
         hipLaunchKernelGGL(kv_stats_final_kernel, dim3(BG), dim3(256), 0, st, pl.stat_part, pl.stat_chunks,
                            a.key_valid, a.nG, a.L, a.dh, pl.stats, pl.n_valid);
     }
@@ -573,11 +582,11 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
                 if (dtype == SF_BF16)
                     hipLaunchKernelGGL(gather_key_sample_kernel<h16>, dim3(BG), dim3(256), gl, st,
                                        (const h16 *)a.K, a.sk, a.key_valid, a.sample_idx, a.n_sample, a.nG, a.L,
-                                       a.dh, pl.Sp, (h16 *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys);
+                                       a.dh, pl.Sp, (h16 *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys, a.row0);
                 else
                     hipLaunchKernelGGL(gather_key_sample_kernel<float>, dim3(BG), dim3(256), gl, st,
                                        (const float *)a.K, a.sk, a.key_valid, a.sample_idx, a.n_sample, a.nG, a.L,
-                                       a.dh, pl.Sp, (float *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys);
+                                       a.dh, pl.Sp, (float *)pl.ks, pl.ks_valid, pl.ks_stats, pl.n_keys, a.row0);
                 Kx = pl.ks;
                 skx.b = (int64_t)a.nG * pl.Sp * a.dh; skx.h = (int64_t)pl.Sp * a.dh; skx.l = a.dh;
                 Lk = pl.Sp; key_mask = pl.ks_valid; kstats = pl.ks_stats; nkeys = pl.n_keys;
@@ -588,7 +597,8 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
                 dim3 grid(ceil_div(a.L, 256), BH);
                 hipLaunchKernelGGL(score_f32_kernel, grid, dim3(256), 0, st, (const float *)a.Q, a.sq,
                                    (const float *)Kx, skx, a.head_group, a.hg_stride, a.pattern_id,
-                                   a.key_valid, key_mask, nkeys, a.nH, a.L, Lk, a.dh, score, scoreH);
+                                   a.key_valid, key_mask, nkeys, a.nH, a.L, Lk, a.dh, score, scoreH, a.row0,
+                                   Kx == a.K);
             }
             M = score;
         }
@@ -610,7 +620,7 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
             hipLaunchKernelGGL(attend_f32_kernel, grid, dim3(64), a.L * sizeof(float), st, (const float *)a.Q,
                                a.sq, (const float *)a.K, a.sk, (const float *)Vuse, svu, v_sj, v_se,
                                a.head_group, a.hg_stride, a.pattern_id, a.key_valid, sel, selH, a.nH, a.L,
-                               a.dh, a.U, (float *)a.O, a.ldo);
+                               a.dh, a.U, (float *)a.O, a.ldo, a.row0);
         }
     }
 
@@ -619,17 +629,18 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         const int64_t n_waves = (int64_t)BH * a.U;
         hipLaunchKernelGGL(merge_splits_kernel<h16>, dim3((unsigned)((n_waves + 3) / 4)), dim3(256), 0, st,
                            a.nH, a.L, a.dh, a.U, pl.Upad, pl.splits, n_waves, sel, selH, pl.part_o, pl.part_ml,
-                           (h16 *)a.O, a.ldo);
+                           (h16 *)a.O, a.ldo, a.row0);
     }
     if (!a.skip_fill) {   // with U == L rows can still be lazy (fewer allowed rows than U)
         const bool v8 = dtype == SF_BF16 && a.dh % 8 == 0 && a.ldo % 8 == 0 && ((uintptr_t)a.O % 16 == 0);
-        dim3 grid(ceil_div(a.L, 32), a.B);
+        // packed samples: a sample may own up to 2 * 256 + L rows of padding behind its tokens
+        dim3 grid(ceil_div(a.ext ? 2 * a.L + 512 : a.L, 32), a.B);
         const size_t fl = (size_t)a.nH * a.dh * 4 + (size_t)a.nH * 32 * 4;
 #define SF_FILL_ARGS grid, dim3(256), fl, st, a.nH, a.nG, a.L, a.dh, pl.slot, a.head_group, a.hg_stride, \
                      a.pattern_id, pl.stats
-        if (dtype == SF_BF16 && v8) hipLaunchKernelGGL((fill_kernel<h16, 8>), SF_FILL_ARGS, (h16 *)a.O, a.ldo);
-        else if (dtype == SF_BF16) hipLaunchKernelGGL((fill_kernel<h16, 4>), SF_FILL_ARGS, (h16 *)a.O, a.ldo);
-        else hipLaunchKernelGGL((fill_kernel<float, 4>), SF_FILL_ARGS, (float *)a.O, a.ldo);
+        if (dtype == SF_BF16 && v8) hipLaunchKernelGGL((fill_kernel<h16, 8>), SF_FILL_ARGS, (h16 *)a.O, a.ldo, a.row0, a.ext);
+        else if (dtype == SF_BF16) hipLaunchKernelGGL((fill_kernel<h16, 4>), SF_FILL_ARGS, (h16 *)a.O, a.ldo, a.row0, a.ext);
+        else hipLaunchKernelGGL((fill_kernel<float, 4>), SF_FILL_ARGS, (float *)a.O, a.ldo, a.row0, a.ext);
 #undef SF_FILL_ARGS
     }
     return check_launch("sparse_gqa_forward");

@@ -11,11 +11,13 @@ namespace {
 // 64 tokens x 64 features per block through LDS, 16 bytes per lane on both sides: 8 features of a token on the way
 // in, 8 tokens of a feature on the way out (ld, col0, ncols, Lp multiples of 8).
 __global__ __launch_bounds__(256) void transpose_v_kernel(const h16 *__restrict__ src, int64_t ld, int col0, int ncols,
-                                                          int L, int Lp, h16 *__restrict__ vt)
+                                                          int L, int Lp, h16 *__restrict__ vt,
+                                                          const int32_t *__restrict__ row0)
 {
     __shared__ uint16_t tile[64][66];                          // row stride 33 words: the column reads spread over the banks
     const int b = blockIdx.z, j0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const uint16_t *s = reinterpret_cast<const uint16_t *>(src) + (int64_t)b * L * ld + col0;
+    // row0: samples packed back to back (sample b starts at row row0[b]); the transposed copy stays b-strided
+    const uint16_t *s = reinterpret_cast<const uint16_t *>(src) + (row0 ? (int64_t)row0[b] : (int64_t)b * L) * ld + col0;
     uint16_t *dst = reinterpret_cast<uint16_t *>(vt) + (int64_t)b * ncols * Lp;
     const int ch = threadIdx.x & 7, r = threadIdx.x >> 3;      // 8 chunks x 32 rows per pass
 #pragma unroll
@@ -68,12 +70,13 @@ void quantize_rows_fp8(const void *x, int64_t ld, int64_t rows, int K, int Kp, f
                        rows, K, Kp, inv_scale, codes);
 }
 
-void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st)
+void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st,
+                 const int32_t *row0)
 {
     if (B == 0 || ncols == 0) return;
     dim3 grid((unsigned)ceil_div(Lp, 64), (unsigned)ceil_div(ncols, 64), (unsigned)B);
     hipLaunchKernelGGL(transpose_v_kernel, grid, dim3(256), 0, st, (const h16 *)src, ld, col0, ncols, L, Lp,
-                       (h16 *)vt);
+                       (h16 *)vt, row0);
 }
 
 int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int k_head)

@@ -69,7 +69,8 @@ int32_t proj_fp8_check(const char *who, const Dims &D, const sf_proj_fp8 *p, int
 // bf16 buffer into the key-contiguous layout the attention kernels read.
 // codes[r, 0:K] = E4M3(x[r, 0:K] * inv_scale), codes[r, K:Kp] = 0 (x bf16 with row stride ld; K, Kp, ld % 8 == 0)
 void quantize_rows_fp8(const void *x, int64_t ld, int64_t rows, int K, int Kp, float inv_scale, uint8_t *codes, hipStream_t st);
-void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st);
+void transpose_v(const void *src, int64_t ld, int col0, int ncols, int B, int L, int Lp, void *vt, hipStream_t st,
+                 const int32_t *row0 = nullptr);
 
 // True when gemm() honours a.row_map for this problem (else it fails with SF_ERR_UNSUPPORTED).
 bool gemm_takes_row_map(int dtype, const GemmArgs &a);

@@ -99,11 +99,216 @@ int32_t move_rows(const char *who, const void *src, int64_t src_rows, const int3
     return check_launch(who);
 }
 
+// ---- packed layout: no padding to a common length ------------------------------------------------------------
+// The valid tokens of all samples back to back in one [Tc, d] buffer, the samples ordered by presence pattern (then
+// by sample number) and every pattern's run of rows starting on a multiple of 256, so that a 256-row block of the
+// buffer holds rows of one pattern only (it may straddle samples): the row-wise work of the encoder (LayerNorm, the
+// four GEMMs) runs over the blocks in use, with each block's pattern in blk_pattern, and only the attention kernels
+// see samples (first row row0[b], allowed positions valid_c[b, :]).  Behind the last run come align(L, 256) rows of
+// slack with the last run's pattern: an attention kernel reads up to L rows from a sample's first row whatever the
+// sample's own length (what lies behind its tokens is masked), so those rows must exist and hold finite numbers.
+// ext[b] >= len[b] is the number of rows sample b answers for in the attention output: its tokens, and for the last
+// sample of a run the padding up to the next run (for the last run: and the slack).
+
+// Pass 1, one block per sample: rank[b, i] = number of valid tokens before i (for a valid token: its position in
+// the compacted sample) and len[b].
+__global__ __launch_bounds__(256) void token_rank_kernel(const uint8_t *__restrict__ token_valid, int L,
+                                                         int32_t *__restrict__ rank, int32_t *__restrict__ len)
+{
+    __shared__ int wsum[4];
+    __shared__ int base_s;
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint8_t *tv = token_valid + (int64_t)b * L;
+    if (threadIdx.x == 0) base_s = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < L; i0 += 256) {
+        const int i = i0 + threadIdx.x;
+        const bool ok = i < L && tv[i];
+        const uint64_t m = __ballot(ok);
+        if (lane == 0) wsum[wave] = __popcll(m);
+        __syncthreads();
+        int off = base_s + __popcll(m & ((1ull << lane) - 1ull));
+        for (int w = 0; w < wave; ++w) off += wsum[w];
+        if (i < L) rank[(int64_t)b * L + i] = off;
+        __syncthreads();
+        if (threadIdx.x == 0) base_s += wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) len[b] = base_s;
+}
+
+// Pass 2, one block of 1024 threads: the layout.  n_rows[0] = rows in use (runs + slack, a multiple of 256; 0 when
+// no sample has a token), n_rows[1] = the same before the comparison with Tc.  When the rows do not fit
+// (n_rows[1] > Tc) the plan is the empty one - every sample at row 0 with no rows, every block unused - so that
+// whatever runs on it touches nothing; the caller reads n_rows[1] and comes back with a larger buffer.
+__global__ __launch_bounds__(1024) void pack_layout_kernel(const int32_t *__restrict__ len,
+                                                           const int32_t *__restrict__ pattern_id, int B, int P, int L,
+                                                           int Tc, int32_t *__restrict__ row0, int32_t *__restrict__ ext,
+                                                           int32_t *__restrict__ blk_pattern, int32_t *__restrict__ n_rows)
+{
+    __shared__ int wsum[16], wlast[16];
+    __shared__ int base_s, last_b_s, tail_b_s, tail_p_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nblk = Tc / 256;
+    if (tid == 0) { base_s = 0; tail_b_s = -1; tail_p_s = -1; }
+    for (int k = tid; k < nblk; k += 1024) blk_pattern[k] = -1;
+    __syncthreads();
+    for (int p = 0; p < P; ++p) {
+        const int seg0 = base_s;
+        if (tid == 0) last_b_s = -1;
+        __syncthreads();
+        for (int c0 = 0; c0 < B; c0 += 1024) {
+            const int b = c0 + tid;
+            const bool mine = b < B && (pattern_id ? pattern_id[b] : 0) == p;
+            const int v = mine ? len[b] : 0;
+            int incl = v;                                     // inclusive scan inside the wave
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane >= o) incl += t;
+            }
+            // the last sample of the run: the highest sample number of the pattern
+            const uint64_t mm = __ballot(mine);
+            if (lane == 63) wsum[wave] = incl;
+            if (lane == 0) wlast[wave] = mm ? c0 + wave * 64 + 63 - __builtin_clzll(mm) : -1;
+            __syncthreads();
+            int off = base_s + incl - v;
+            for (int w = 0; w < wave; ++w) off += wsum[w];
+            if (mine) { row0[b] = off; ext[b] = v; }
+            __syncthreads();
+            if (tid == 0) {
+                int tot = 0, lb = last_b_s;
+                for (int w = 0; w < 16; ++w) { tot += wsum[w]; lb = max(lb, wlast[w]); }
+                base_s += tot;
+                last_b_s = lb;
+            }
+            __syncthreads();
+        }
+        const int seg1 = base_s, lb = last_b_s;
+        const int seg1a = (seg1 + 255) & ~255;
+        __syncthreads();
+        if (seg1 > seg0) {                                    // the run has rows
+            for (int k = seg0 / 256 + tid; k < seg1a / 256; k += 1024)
+                if (k < nblk) blk_pattern[k] = p;
+            if (tid == 0) {
+                ext[lb] = seg1a - row0[lb];                   // its last sample also answers for the padding
+                base_s = seg1a;
+                tail_b_s = lb;
+                tail_p_s = p;
+            }
+        }
+        __syncthreads();
+    }
+    const int used = base_s, slack = (L + 255) & ~255;
+    const int need = used > 0 ? used + slack : 0;
+    __syncthreads();
+    if (need <= Tc) {
+        if (used > 0) {
+            for (int k = used / 256 + tid; k < need / 256; k += 1024) blk_pattern[k] = tail_p_s;
+            if (tid == 0) ext[tail_b_s] += slack;
+        }
+    } else {
+        for (int b = tid; b < B; b += 1024) { row0[b] = 0; ext[b] = 0; }
+        for (int k = tid; k < nblk; k += 1024) blk_pattern[k] = -1;
+    }
+    if (tid == 0) { n_rows[0] = need <= Tc ? need : 0; n_rows[1] = need; }
+}
+
+// Pass 3, grid (row chunks of 256, B + 1).  Samples: dst_row[b, i] (on entry the rank of token i) becomes the packed
+// row of a valid token or -1, src_row[r] the source row b*L + i of a packed row or -1 for the padding the sample
+// answers for, valid_c[b, j] = j < len[b], u_active[b] = min(c*ceil(ln T_b), T_b).  The extra grid row marks the
+// rows behind the ones in use as empty.
+__global__ __launch_bounds__(256) void pack_rows_kernel(const uint8_t *__restrict__ token_valid,
+                                                        const int32_t *__restrict__ len, const int32_t *__restrict__ row0,
+                                                        const int32_t *__restrict__ ext, const int32_t *__restrict__ n_rows,
+                                                        int B, int L, int Tc, int c_factor, int32_t *__restrict__ dst_row,
+                                                        int32_t *__restrict__ src_row, uint8_t *__restrict__ valid_c,
+                                                        int32_t *__restrict__ u_active)
+{
+    const int b = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+    const int used = n_rows[0];
+    if (b == B) {
+        for (int64_t r = (int64_t)used + j; r < Tc; r += (int64_t)gridDim.x * 256) src_row[r] = -1;
+        return;
+    }
+    const bool ok = used > 0;                              // else: the empty plan
+    const int T = ok ? len[b] : 0, r0 = row0[b], e = ext[b];
+    if (j < L) {
+        const int64_t t = (int64_t)b * L + j;
+        const bool tok = ok && token_valid[t];
+        const int r = r0 + dst_row[t];
+        dst_row[t] = tok ? r : -1;
+        if (tok) src_row[r] = (int32_t)t;
+        valid_c[t] = j < T;
+    }
+    if (j >= T && j < e) src_row[r0 + j] = -1;
+    if (j == 0) {
+        const long long u = T >= 1 ? (long long)c_factor * ceil_ln(T) : 0;
+        u_active[b] = (int32_t)(u < T ? u : T);
+    }
+}
+
 }  // namespace
 
 }  // namespace sf
 
 using namespace sf;
+
+static int32_t check_pack_plan(const char *who, const Dims &D, const sf_token_pack_plan *plan)
+{
+    if (!plan) return fail(SF_ERR_INVALID_ARG, "%s: plan is NULL", who);
+    if (plan->Tc < 256 || plan->Tc % 256) return fail(SF_ERR_INVALID_ARG, "%s: Tc must be a positive multiple of 256", who);
+    if (!plan->len || !plan->u_active || !plan->row0 || !plan->ext || !plan->valid_c || !plan->blk_pattern ||
+        !plan->src_row || !plan->dst_row || !plan->n_rows)
+        return fail(SF_ERR_INVALID_ARG, "%s: NULL pointer in the plan", who);
+    if ((int64_t)plan->Tc > ((int64_t)1 << 30)) return fail(SF_ERR_SHAPE, "%s: Tc too large", who);
+    (void)D;
+    return SF_OK;
+}
+
+extern "C" int32_t sf_token_pack_rows_max(const sf_desc *desc)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    const int64_t runs = D.P < D.B ? D.P : D.B;
+    const int64_t need = (int64_t)align_up((size_t)D.B * D.L, 256) + 256 * runs + (int64_t)align_up((size_t)D.L, 256);
+    if (need > ((int64_t)1 << 30)) return fail(SF_ERR_SHAPE, "token_pack_rows_max: B*L too large");
+    return (int32_t)need;
+}
+
+extern "C" int32_t sf_token_pack(const sf_desc *desc, const void *X, const uint8_t *token_valid,
+                                 const int32_t *pattern_id, const sf_token_pack_plan *plan, void *Xp, void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (int32_t rc = check_pack_plan("token_pack", D, plan)) return rc;
+    if (!X || !token_valid || !Xp) return fail(SF_ERR_INVALID_ARG, "token_pack: NULL argument");
+    if (X == Xp) return fail(SF_ERR_INVALID_ARG, "token_pack: Xp may not alias X");
+    if (D.P > 1 && !pattern_id) return fail(SF_ERR_INVALID_ARG, "token_pack: pattern_id required when P > 1");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int c = desc->c_factor > 0 ? desc->c_factor : 5;
+    hipLaunchKernelGGL(token_rank_kernel, dim3(D.B), dim3(256), 0, st, token_valid, D.L, plan->dst_row, plan->len);
+    hipLaunchKernelGGL(pack_layout_kernel, dim3(1), dim3(1024), 0, st, plan->len, pattern_id, D.B, D.P, D.L, plan->Tc,
+                       plan->row0, plan->ext, plan->blk_pattern, plan->n_rows);
+    // a sample answers for at most its L tokens, 255 rows of padding and the slack
+    dim3 grid((unsigned)ceil_div(2 * D.L + 512, 256), (unsigned)D.B + 1);
+    hipLaunchKernelGGL(pack_rows_kernel, grid, dim3(256), 0, st, token_valid, plan->len, plan->row0, plan->ext,
+                       plan->n_rows, D.B, D.L, plan->Tc, c, plan->dst_row, plan->src_row, plan->valid_c, plan->u_active);
+    // rows by global source row: one "sample" of Tc rows
+    return move_rows("token_pack", X, 0, plan->src_row, plan->Tc, 1, (size_t)D.d * elem_size(D.dtype), Xp, st);
+}
+
+extern "C" int32_t sf_token_unpack(const sf_desc *desc, const void *Yp, const sf_token_pack_plan *plan, void *Y,
+                                   void *stream)
+{
+    Dims D;
+    if (int32_t rc = read_desc(desc, D)) return rc;
+    if (int32_t rc = check_pack_plan("token_unpack", D, plan)) return rc;
+    if (!Yp || !Y) return fail(SF_ERR_INVALID_ARG, "token_unpack: NULL argument");
+    if (Y == Yp) return fail(SF_ERR_INVALID_ARG, "token_unpack: Y may not alias Yp");
+    return move_rows("token_unpack", Yp, 0, plan->dst_row, (int64_t)D.B * D.L, 1, (size_t)D.d * elem_size(D.dtype), Y,
+                     static_cast<hipStream_t>(stream));
+}
 
 extern "C" int32_t sf_token_compact(const sf_desc *desc, const void *X, const uint8_t *token_valid, int32_t Lc,
                                     void *Xc, uint8_t *valid_c, int32_t *row_index, int32_t *slot_of, int32_t *len,
