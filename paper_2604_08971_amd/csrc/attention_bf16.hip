@@ -239,6 +239,11 @@ __device__ __forceinline__ float both_halves_sum(float v)
 // XCD and share its L2, and the items are spread evenly over the XCDs.
 constexpr int AWAVE = 8;
 
+// (139 registers at dh = 64: one workgroup per compute unit.  Capping the allocation at 128 registers so that two fit
+// was faster where the launch has more workgroups than compute units - C5 active pass 40 -> 33.5 us, C3 66 -> 49.5 us -
+// but the build with its eight spilled registers gave wrong rows whenever a pass left waves without a pair, with or
+// without the key groups and with or without a second workgroup on the compute unit; no cause was found in the
+// source, so that build is not used.)
 template <int DH, int QB>
 __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     const h16 *__restrict__ Q, sf_strides sq, const h16 *__restrict__ K, sf_strides sk,
@@ -332,7 +337,9 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
         int kg = 1;
         {
             const int waves_used = (min(npairs - pair0, AWAVE * QB) + QB - 1) / QB;
-            while (waves_used * kg * 2 <= AWAVE) kg *= 2;
+            // only where the launch is short of workgroups (the host split the keys for that reason): with a
+            // (sample, group) problem per compute unit or more the idle waves cost nothing and the merge does
+            while (splits > 1 && waves_used * kg * 2 <= AWAVE) kg *= 2;
         }
         const int pslots = AWAVE / kg;                  // waves that hold distinct pairs
         const int pw = wave % pslots, kgi = wave / pslots;
@@ -934,10 +941,11 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
                            a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
                            pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml, a.row0);
     } else {
-        hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q,
-                           a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, svt, a.head_group, a.hg_stride,
-                           a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
-                           pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml, a.row0);
+#define SF_ATTEND_ARGS grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q, a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, \
+                       svt, a.head_group, a.hg_stride, a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, \
+                       pl.Lp, a.U, pl.Upad, pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml, a.row0
+        hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), SF_ATTEND_ARGS);
+#undef SF_ATTEND_ARGS
     }
     return SF_OK;
 }

@@ -46,6 +46,9 @@ __global__ __launch_bounds__(256) void kv_stats_partial_kernel(
 
 // bf16 variant with 16-byte loads: K rows are dh-contiguous, V is read from
 // its key-contiguous transposed layout [dh][Lp].  Same outputs as above.
+// Every load of the chunk (validity bytes, K rows, V^T pieces) is issued before the first use, so a block pays one
+// memory round trip instead of one per pass; validity is applied as a select afterwards (masked rows may hold
+// anything).  The order of the additions is that of the pass-by-pass loop.
 template <int DH>
 __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
     const h16 *__restrict__ K, sf_strides sk, const h16 *__restrict__ VT, sf_strides svt,
@@ -53,7 +56,10 @@ __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
     const int32_t *__restrict__ row0)
 {
     constexpr int CH = DH / 8, RP = 256 / CH, TPR = 256 / DH;
+    constexpr int NK = STAT_CHUNK / RP, NV = STAT_CHUNK / (TPR * 8);
+    static_assert(STAT_CHUNK % RP == 0 && STAT_CHUNK % (TPR * 8) == 0 && STAT_CHUNK <= 256, "chunk shape");
     __shared__ float red[RP][DH];
+    __shared__ uint8_t ok_s[STAT_CHUNK];
     const int bg = blockIdx.y, b = bg / nG, g = bg % nG, tid = threadIdx.x;
     const int j0 = blockIdx.x * STAT_CHUNK, j1 = min(L, j0 + STAT_CHUNK);
     const h16 *Kb = K + sample_offset(row0, b, sk) + (int64_t)g * sk.h;
@@ -61,17 +67,36 @@ __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
     const uint8_t *kv = key_valid ? key_valid + (int64_t)b * L : nullptr;
     float *o = part + (((int64_t)bg * gridDim.x + blockIdx.x) * 2) * DH;
 
+    const int r = tid / CH, c = tid % CH;          // K: row r of a pass, 16-byte chunk c
+    const int e = tid / TPR, q = tid % TPR;        // V^T: row e, 8 keys at q*8 of a pass
+    uint8_t okb = 0;
+    if (tid < STAT_CHUNK) okb = j0 + tid < j1 && (!kv || kv[j0 + tid]);
+    h16x8 kt[NK], vt[NV];
+#pragma unroll
+    for (int k = 0; k < NK; ++k) {
+        const int j = j0 + r + RP * k;
+        kt[k] = h16x8{};
+        if (j < j1) kt[k] = *reinterpret_cast<const h16x8 *>(Kb + (int64_t)j * sk.l + c * 8);
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int j = j0 + q * 8 + TPR * 8 * k;
+        vt[k] = h16x8{};
+        if (j < j1) vt[k] = *reinterpret_cast<const h16x8 *>(Vb + (int64_t)e * svt.l + j);   // j + 8 <= Lp
+    }
+    if (tid < STAT_CHUNK) ok_s[tid] = okb;
+    __syncthreads();
+
     {   // column sums of K over the allowed keys of this chunk
-        const int r = tid / CH, c = tid % CH;
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int j = j0 + r; j < j1; j += RP) {
-            if (kv && !kv[j]) continue;
-            const h16x8 t = *reinterpret_cast<const h16x8 *>(Kb + (int64_t)j * sk.l + c * 8);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] += (float)t[e];
-        }
+        for (int k = 0; k < NK; ++k)
+            if (ok_s[r + RP * k]) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) red[r][c * 8 + e] = acc[e];
+                for (int t = 0; t < 8; ++t) acc[t] += (float)kt[k][t];
+            }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) red[r][c * 8 + t] = acc[t];
         __syncthreads();
         if (tid < DH) {
             float s = 0.f;
@@ -80,14 +105,12 @@ __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
         }
     }
     {   // row sums of V^T over the allowed keys of this chunk
-        const int e = tid / TPR, q = tid % TPR;
         float s = 0.f;
-        for (int j = j0 + q * 8; j < j1; j += TPR * 8) {
-            const h16x8 t = *reinterpret_cast<const h16x8 *>(Vb + (int64_t)e * svt.l + j);   // j + 8 <= Lp
+#pragma unroll
+        for (int k = 0; k < NV; ++k)
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (j + u < j1 && (!kv || kv[j + u])) s += (float)t[u];
-        }
+                if (ok_s[q * 8 + TPR * 8 * k + u]) s += (float)vt[k][u];
 #pragma unroll
         for (int w = 1; w < TPR; w <<= 1) s += __shfl_xor(s, w);
         if (q == 0) o[DH + e] = s;
@@ -175,10 +198,12 @@ __global__ __launch_bounds__(256) void forced_slot_kernel(const int32_t *__restr
 
 // ------------------------------------------------------------------------ fill
 // Every row that is not active takes its group's context vector.  One block
-// per (sample, 32 rows): the row -> slot map of the 32 rows and the context
+// per (sample, FILL_ROWS rows): the row -> slot map of those rows and the context
 // vectors of all heads are staged in LDS (coalesced along the row index), then
 // every thread writes VEC consecutive output elements at a time, rows of O
 // contiguous.  Active rows are left alone.
+constexpr int FILL_ROWS = 64;      // rows per block: enough stores per block to cover its two dependent loads
+
 template <class T, int VEC>
 __global__ __launch_bounds__(256) void fill_kernel(
     int nH, int nG, int L, int dh, const int32_t *__restrict__ slot,
@@ -188,8 +213,8 @@ __global__ __launch_bounds__(256) void fill_kernel(
 {
     extern __shared__ __attribute__((aligned(16))) char fsm[];
     float *ctx = reinterpret_cast<float *>(fsm);                 // [nH][dh]
-    int32_t *sl = reinterpret_cast<int32_t *>(ctx + nH * dh);    // [nH][32]
-    const int b = blockIdx.y, i0 = blockIdx.x * 32;
+    int32_t *sl = reinterpret_cast<int32_t *>(ctx + nH * dh);    // [nH][FILL_ROWS]
+    const int b = blockIdx.y, i0 = blockIdx.x * FILL_ROWS;
     // packed samples: the rows the sample owns (its tokens and the padding behind them); rows at or beyond L have no
     // slot entry and are padding
     const int rows_b = ext ? ext[b] : L;
@@ -200,17 +225,17 @@ __global__ __launch_bounds__(256) void fill_kernel(
         const int g = head_group[(int64_t)p * hg_stride + h];
         ctx[t] = stats[(((int64_t)b * nG + g) * 2 + 1) * dh + e];
     }
-    for (int t = threadIdx.x; t < nH * 32; t += 256) {
-        const int h = t / 32, i = i0 + (t % 32);
+    for (int t = threadIdx.x; t < nH * FILL_ROWS; t += 256) {
+        const int h = t / FILL_ROWS, i = i0 + (t % FILL_ROWS);
         sl[t] = i < L ? slot[((int64_t)b * nH + h) * L + i] : -1;
     }
     __syncthreads();
     const int qv = dh / VEC, per_row = nH * qv;
-    for (int c = threadIdx.x; c < 32 * per_row; c += 256) {
+    for (int c = threadIdx.x; c < FILL_ROWS * per_row; c += 256) {
         const int r = c / per_row, h = (c % per_row) / qv, e = (c % qv) * VEC;
         const int i = i0 + r;
         if (i >= rows_b) break;
-        if (sl[h * 32 + r] >= 0) continue;                 // active row: written by the active pass / the merge
+        if (sl[h * FILL_ROWS + r] >= 0) continue;          // active row: written by the active pass / the merge
         float v[VEC];
 #pragma unroll
         for (int t = 0; t < VEC; ++t) v[t] = ctx[h * dh + e + t];
@@ -634,8 +659,8 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
     if (!a.skip_fill) {   // with U == L rows can still be lazy (fewer allowed rows than U)
         const bool v8 = dtype == SF_BF16 && a.dh % 8 == 0 && a.ldo % 8 == 0 && ((uintptr_t)a.O % 16 == 0);
         // packed samples: a sample may own up to 2 * 256 + L rows of padding behind its tokens
-        dim3 grid(ceil_div(a.ext ? 2 * a.L + 512 : a.L, 32), a.B);
-        const size_t fl = (size_t)a.nH * a.dh * 4 + (size_t)a.nH * 32 * 4;
+        dim3 grid(ceil_div(a.ext ? 2 * a.L + 512 : a.L, FILL_ROWS), a.B);
+        const size_t fl = (size_t)a.nH * a.dh * 4 + (size_t)a.nH * FILL_ROWS * 4;
 #define SF_FILL_ARGS grid, dim3(256), fl, st, a.nH, a.nG, a.L, a.dh, pl.slot, a.head_group, a.hg_stride, \
                      a.pattern_id, pl.stats
         if (dtype == SF_BF16 && v8) hipLaunchKernelGGL((fill_kernel<h16, 8>), SF_FILL_ARGS, (h16 *)a.O, a.ldo, a.row0, a.ext);

@@ -67,43 +67,54 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(
 }
 
 // One launch for a whole layer when every weight row is a multiple of 16 bytes: blockIdx.x selects the job -
-// [0, n_rows) one weight row each (regions of wr), then blocks of 256 bias elements (regions of br), then the
-// 32x32 tiles of the two transposed gathers; blockIdx.y is the pattern.  Four launches of a few microseconds
-// each became one.
+// blocks of CL_ROWS weight rows (regions of wr; a wave moves two rows, both loads in flight before the stores),
+// then blocks of 256 bias elements (regions of br), then the tiles of the two transposed gathers; blockIdx.y is
+// the pattern.  Four launches of a few microseconds each became one.
 struct TransposeJob {
     const void *src; void *dst; const int32_t *idx;
     int idx_stride, block, n_valid, cols_out, tiles_j, tiles_n; size_t dst_pstride;
 };
 struct LayerJobs {
-    GatherRegions wr; int n_rows, row_vecs;        // dst_pstride in uint4
-    GatherRegions br; int n_bias, bias_blocks;     // dst_pstride in elements
-    TransposeJob tr[2]; int d;
+    GatherRegions wr; int n_rows, row_vecs, row_blocks;   // dst_pstride in uint4
+    GatherRegions br; int n_bias, bias_blocks;            // dst_pstride in elements
+    TransposeJob tr[2]; int d, tr_tile;                   // tr_tile: 64 (16-bit types, 16-byte accesses) or 32
 };
+constexpr int CL_ROWS = 8;
 
 template <class T>
 __global__ __launch_bounds__(256) void compact_layer_kernel(LayerJobs J)
 {
-    __shared__ T tile[32][33];
+    __shared__ T tile[sizeof(T) == 2 ? 64 : 32][sizeof(T) == 2 ? 66 : 33];
     const int p = blockIdx.y;
     int x = blockIdx.x;
-    if (x < J.n_rows) {
-        int R = x, g = 0;
-        while (g + 1 < J.wr.n && R >= J.wr.r[g].rows) { R -= J.wr.r[g].rows; ++g; }
-        const GatherRegion &rg = J.wr.r[g];
-        const int slot = R / rg.block, r = R % rg.block;
-        const int n_valid = rg.n_dev ? rg.n_dev[p] : rg.n_static;
-        int src_unit = -1;
-        if (slot < n_valid) src_unit = rg.idx[(size_t)p * rg.idx_stride + slot];
-        uint4 *d = static_cast<uint4 *>(rg.dst) + (size_t)p * rg.dst_pstride + (size_t)R * J.row_vecs;
-        if (src_unit < 0) {
-            for (int i = threadIdx.x; i < J.row_vecs; i += 256) d[i] = make_uint4(0, 0, 0, 0);
-        } else {
-            const uint4 *sv = static_cast<const uint4 *>(rg.src) + ((size_t)src_unit * rg.block + r) * J.row_vecs;
-            for (int i = threadIdx.x; i < J.row_vecs; i += 256) d[i] = sv[i];
+    if (x < J.row_blocks) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const uint4 *sv[2] = {nullptr, nullptr};
+        uint4 *dv[2] = {nullptr, nullptr};
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            int R = x * CL_ROWS + wave * 2 + k, g = 0;
+            if (R >= J.n_rows) continue;
+            while (g + 1 < J.wr.n && R >= J.wr.r[g].rows) { R -= J.wr.r[g].rows; ++g; }
+            const GatherRegion &rg = J.wr.r[g];
+            const int slot = R / rg.block, r = R % rg.block;
+            const int n_valid = rg.n_dev ? rg.n_dev[p] : rg.n_static;
+            int src_unit = -1;
+            if (slot < n_valid) src_unit = rg.idx[(size_t)p * rg.idx_stride + slot];
+            dv[k] = static_cast<uint4 *>(rg.dst) + (size_t)p * rg.dst_pstride + (size_t)R * J.row_vecs;
+            if (src_unit >= 0) sv[k] = static_cast<const uint4 *>(rg.src) + ((size_t)src_unit * rg.block + r) * J.row_vecs;
+        }
+        for (int i = lane; i < J.row_vecs; i += 64) {
+            uint4 v[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) v[k] = sv[k] ? sv[k][i] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+                if (dv[k]) dv[k][i] = v[k];
         }
         return;
     }
-    x -= J.n_rows;
+    x -= J.row_blocks;
     if (x < J.bias_blocks) {
         int R = x * 256 + threadIdx.x;
         if (R >= J.n_bias) return;
@@ -124,9 +135,42 @@ __global__ __launch_bounds__(256) void compact_layer_kernel(LayerJobs J)
     int t = 0;
     if (x >= J.tr[0].tiles_j * J.tr[0].tiles_n) { x -= J.tr[0].tiles_j * J.tr[0].tiles_n; t = 1; }
     const TransposeJob &tj = J.tr[t];
-    const int J0 = (x % tj.tiles_j) * 32, n0 = (x / tj.tiles_j) * 32;
     const T *src = static_cast<const T *>(tj.src);
     T *dstT = static_cast<T *>(tj.dst);
+    if constexpr (sizeof(T) == 2) {
+        if (J.tr_tile == 64) {
+            // 64 unit rows x 64 features through LDS, 16 bytes per lane on both sides: 8 features of a unit row on
+            // the way in, 8 unit rows of a feature on the way out (d, cols_out multiples of 8, 16-byte aligned)
+            const int J0 = (x % tj.tiles_j) * 64, n0 = (x / tj.tiles_j) * 64;
+            const int ch = threadIdx.x & 7, r = threadIdx.x >> 3;      // 8 chunks x 32 rows per pass
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int jj = r + pass * 32, Jc = J0 + jj, n = n0 + ch * 8;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (Jc < tj.cols_out && n < J.d) {
+                    const int slot = Jc / tj.block;
+                    const int unit = slot < tj.n_valid ? tj.idx[(size_t)p * tj.idx_stride + slot] : -1;
+                    if (unit >= 0) v = *reinterpret_cast<const uint4 *>(src + ((size_t)unit * tj.block + Jc % tj.block) * J.d + n);
+                }
+                uint32_t *w = reinterpret_cast<uint32_t *>(&tile[jj][ch * 8]);
+                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int nn = r + pass * 32, n = n0 + nn, Jc = J0 + ch * 8;
+                if (n >= J.d || Jc >= tj.cols_out) continue;
+                uint32_t w[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    w[k] = (uint32_t)tile[ch * 8 + 2 * k][nn] | ((uint32_t)tile[ch * 8 + 2 * k + 1][nn] << 16);
+                *reinterpret_cast<uint4 *>(dstT + (size_t)p * tj.dst_pstride + (size_t)n * tj.cols_out + Jc) =
+                    make_uint4(w[0], w[1], w[2], w[3]);
+            }
+            return;
+        }
+    }
+    const int J0 = (x % tj.tiles_j) * 32, n0 = (x / tj.tiles_j) * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
     for (int jj = ty; jj < 32; jj += 8) {
         const int Jc = J0 + jj, n = n0 + tx;
@@ -368,12 +412,17 @@ extern "C" int32_t sf_compact_heads_channels(const sf_desc *desc, int32_t layer,
         J.br = br;
         for (int g = 0; g < br.n; ++g) J.n_bias += br.r[g].rows;
         J.bias_blocks = ceil_div(J.n_bias, 256);
+        J.row_blocks = ceil_div(J.n_rows, CL_ROWS);
         J.d = d;
         // W2'^T and Wo'^T: unit rows become columns so the GEMMs read K-contiguous operands
-        J.tr[0] = TransposeJob{dense->W2, c->W2T, fi, D.F, 1, kf, Fp, ceil_div(Fp, 32), ceil_div(d, 32), (size_t)d * Fp};
-        J.tr[1] = TransposeJob{dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, ceil_div(kh * dh, 32), ceil_div(d, 32),
+        const bool wide = D.dtype == SF_BF16 && d % 8 == 0 && Fp % 8 == 0 && (kh * dh) % 8 == 0 &&
+                          !(((uintptr_t)dense->W2 | (uintptr_t)dense->Wo | (uintptr_t)c->W2T | (uintptr_t)c->WoT) & 15);
+        const int tt = wide ? 64 : 32;
+        J.tr_tile = tt;
+        J.tr[0] = TransposeJob{dense->W2, c->W2T, fi, D.F, 1, kf, Fp, ceil_div(Fp, tt), ceil_div(d, tt), (size_t)d * Fp};
+        J.tr[1] = TransposeJob{dense->Wo, c->WoT, hi, D.Hq, dh, kh, kh * dh, ceil_div(kh * dh, tt), ceil_div(d, tt),
                                (size_t)d * kh * dh};
-        dim3 grid(J.n_rows + J.bias_blocks + J.tr[0].tiles_j * J.tr[0].tiles_n + J.tr[1].tiles_j * J.tr[1].tiles_n, P);
+        dim3 grid(J.row_blocks + J.bias_blocks + J.tr[0].tiles_j * J.tr[0].tiles_n + J.tr[1].tiles_j * J.tr[1].tiles_n, P);
         if (D.dtype == SF_BF16) hipLaunchKernelGGL(compact_layer_kernel<uint16_t>, grid, dim3(256), 0, st, J);
         else hipLaunchKernelGGL(compact_layer_kernel<uint32_t>, grid, dim3(256), 0, st, J);
         return check_launch("compact_heads_channels");

@@ -152,9 +152,12 @@ def _case(kw, with_ffn8, samples=None):
         r = orc.encoder_forward(x_s, packs, U, pid_s, kv_s, n_forced_a=l + 1, n_forced_o=l, **kw_l)
         oq_own[l] = r[6][l]
     va_d, va_o = DEC[aq] * SX1, DEC[aq_own] * SX1
-    assert (np.abs(va_d - va_o) <= 2.0 ** -3 * np.abs(va_o) + 2e-2 * np.maximum(1.0, np.abs(va_o))).all()
+    bad = np.argwhere(np.abs(va_d - va_o) > 2.0 ** -3 * np.abs(va_o) + 2e-2 * np.maximum(1.0, np.abs(va_o)))
+    assert len(bad) == 0, f"{len(bad)} LN1 codes off, first (layer, sample, row, column): {bad[:8].tolist()}"
     vo_d, vo_o = DEC[oq] * SA, DEC[oq_own] * SA
-    assert (np.abs(vo_d - vo_o) <= 2.0 ** -3 * np.abs(vo_o) + 2e-2 * np.maximum(1.0, np.abs(vo_o))).all()
+    bad = np.argwhere(np.abs(vo_d - vo_o) > 2.0 ** -3 * np.abs(vo_o) + 2e-2 * np.maximum(1.0, np.abs(vo_o)))
+    assert len(bad) == 0, (f"{len(bad)} attention-output codes off, first (layer, sample, row, column): {bad[:8].tolist()}, "
+                           f"rows {np.unique(bad[:, 2])[:16].tolist()}")
     same_a, same_o = float((aq == aq_own).mean()), float((oq == oq_own).mean())
     _say(f"   encoder with fp8 projections{' and fp8 ffn' if with_ffn8 else ''}: err {e:.3e}; LN1 codes equal to the "
          f"oracle's own {same_a:.4f}, attention-output codes {same_o:.4f}; picks differing {picks_diff}/{picks_tot}")

@@ -608,6 +608,8 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
     ("bf16", 3, 4, 4, 480, 64, -1, True),          # C3-shaped
     ("bf16", 2, 7, 2, 512, 64, -1, False),         # C4-shaped, 3+4 heads per group
     ("bf16", 1, 8, 4, 4096, 64, -1, False),        # C5-shaped: key splits
+    ("bf16", 16, 9, 3, 2048, 64, -1, False),       # key splits; groups of unequal size: passes that leave waves
+                                                   # without a pair, groups that need a second pass
     ("bf16", 2, 3, 1, 203, 64, -1, True),          # ragged L, one group
     ("bf16", 2, 4, 2, 333, 128, -1, True),         # dh 128
     ("bf16", 2, 4, 2, 200, 64, 200, False),        # dense pattern (U = L): flash GQA
