@@ -244,8 +244,10 @@ constexpr int AWAVE = 8;
 // but the build with its eight spilled registers gave wrong rows whenever a pass left waves without a pair, with or
 // without the key groups and with or without a second workgroup on the compute unit; no cause was found in the
 // source, so that build is not used.)
-template <int DH, int QB>
-__global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
+// NW = waves per workgroup.  Four instead of eight where a (sample, group) has at most four pairs: the same registers
+// per wave then leave room for three workgroups per compute unit, and no wave is without a pair.
+template <int DH, int QB, int NW>
+__global__ __launch_bounds__(NW * 64) void attend_bf16_kernel(
     const h16 *__restrict__ Q, sf_strides sq, const h16 *__restrict__ K, sf_strides sk,
     const h16 *__restrict__ VT, sf_strides svt, const int32_t *__restrict__ head_group, int hg_stride,
     const int32_t *__restrict__ pattern_id, const uint8_t *__restrict__ key_valid,
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     int Upad, int splits, int keys_per_split, h16 *__restrict__ O, int64_t ldo,
     float *__restrict__ part_o, float *__restrict__ part_ml, const int32_t *__restrict__ row0)
 {
-    constexpr int NT = AWAVE * 64;
+    constexpr int NT = NW * 64;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int KT = BKEY * (DH + PAD), VT_ = DH * (BKEY + PAD);          // elements of one K / V^T tile
     h16 *Ks = reinterpret_cast<h16 *>(smem);                         // [2][BKEY][DH+PAD]
@@ -330,18 +332,18 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
     using KT_ = KTile<DH, NT>;
     auto tile_j0 = [&](int it) { return __builtin_amdgcn_readfirstlane((int)tiles[it]) * BKEY; };   // same for every lane
 
-    for (int pair0 = chunk * (AWAVE * QB); pair0 < npairs; pair0 += chunks * (AWAVE * QB)) {
+    for (int pair0 = chunk * (NW * QB); pair0 < npairs; pair0 += chunks * (NW * QB)) {
         // When this pass has pairs for at most half of the waves (few active rows: U = c*ceil(ln L) gives one or two
         // blocks of 32 per head), the others would only help with the staging: instead KG groups of waves take the
         // same pairs and every KG-th key tile each, and their partial results are merged through LDS at the end.
         int kg = 1;
         {
-            const int waves_used = (min(npairs - pair0, AWAVE * QB) + QB - 1) / QB;
+            const int waves_used = (min(npairs - pair0, NW * QB) + QB - 1) / QB;
             // only where the launch is short of workgroups (the host split the keys for that reason): with a
             // (sample, group) problem per compute unit or more the idle waves cost nothing and the merge does
-            while (splits > 1 && waves_used * kg * 2 <= AWAVE) kg *= 2;
+            while (splits > 1 && waves_used * kg * 2 <= NW) kg *= 2;
         }
-        const int pslots = AWAVE / kg;                  // waves that hold distinct pairs
+        const int pslots = NW / kg;                  // waves that hold distinct pairs
         const int pw = wave % pslots, kgi = wave / pslots;
         int head[QB], qidx[QB], slot[QB];
         h16x8 qf[QB][DH / 16];
@@ -481,7 +483,7 @@ __global__ __launch_bounds__(AWAVE * 64) void attend_bf16_kernel(
         if (kg > 1) {
             float *mrg = reinterpret_cast<float *>(smem);              // [writer wave][QB * (DH/2 + 2)][64 lanes]
             constexpr int PER = QB * ((DH / 32) * 16 + 2);
-            static_assert((AWAVE / 2) * PER * 64 * 4 <= 2 * KT * 2 + 2 * VT_ * 2, "merge scratch must fit in the tile buffers");
+            static_assert((NW / 2) * PER * 64 * 4 <= 2 * KT * 2 + 2 * VT_ * 2, "merge scratch must fit in the tile buffers");
             for (int step = kg / 2; step >= 1; step /= 2) {
                 __syncthreads();                                       // tile buffers (or the last round's slots) are free
                 if (kgi >= step && kgi < 2 * step) {
@@ -930,7 +932,13 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
                        (size_t)ceil_div(a.L, 32) * 4 + (size_t)ceil_div(a.L, BKEY) * 2 + 16;
     const int nqb = pl.Upad / 32, BG = a.B * a.nG;
     // pair chunks per (sample, group) for evenly spread heads; a group with more heads takes several passes
-    const int chunks = ceil_div(ceil_div(a.nH, a.nG) * nqb, AWAVE * QB);
+    const int pairs = ceil_div(a.nH, a.nG) * nqb;
+    // four waves where the launch has a (sample, group) problem per compute unit or more (no key splits) and at most
+    // four pairs per problem (measured: C3 active pass 66 -> 49 us); with split keys the launch is short of work per
+    // compute unit and eight waves with key groups are faster (C5: 40 against 45 us); dh 128 needs 232 registers
+    // with four waves, i.e. one wave per SIMD
+    const int nw = (QB == 1 && DH <= 64 && pairs <= 4 && pl.splits == 1) ? 4 : AWAVE;
+    const int chunks = ceil_div(pairs, nw * QB);
     const int64_t items = (int64_t)chunks * BG * pl.splits;
     if (items > (1 << 30)) return fail(SF_ERR_SHAPE, "sparse_gqa(bf16): too many work items");
     dim3 grid((unsigned)align_up(items, 8));
@@ -941,10 +949,11 @@ static int32_t launch_attend(const AttnArgs &a, const AttnPlan &pl, const void *
                            a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, pl.Lp, a.U, pl.Upad,
                            pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml, a.row0);
     } else {
-#define SF_ATTEND_ARGS grid, dim3(AWAVE * 64), lds, st, (const h16 *)a.Q, a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, \
+#define SF_ATTEND_ARGS grid, dim3(nw * 64), lds, st, (const h16 *)a.Q, a.sq, (const h16 *)a.K, a.sk, (const h16 *)vt, \
                        svt, a.head_group, a.hg_stride, a.pattern_id, a.key_valid, sel, selH, a.nH, a.nG, BG, chunks, a.L, \
                        pl.Lp, a.U, pl.Upad, pl.splits, pl.keys_per_split, (h16 *)a.O, a.ldo, pl.part_o, pl.part_ml, a.row0
-        hipLaunchKernelGGL((attend_bf16_kernel<DH, QB>), SF_ATTEND_ARGS);
+        if (nw == 4) hipLaunchKernelGGL((attend_bf16_kernel<DH, QB, DH <= 64 ? 4 : AWAVE>), SF_ATTEND_ARGS);
+        else hipLaunchKernelGGL((attend_bf16_kernel<DH, QB, AWAVE>), SF_ATTEND_ARGS);
 #undef SF_ATTEND_ARGS
     }
     return SF_OK;

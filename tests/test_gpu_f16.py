@@ -90,6 +90,16 @@ def test_f16_encoder_parity_full_size_sampled(name, n_samples):
     _encoder_parity(wl, samples=samples, own_choice=False)
 
 
+def test_f16_encoder_on_packed_tokens():
+    """Token compaction without padding in the FP16 build: the packed-row encoder against the oracle in its binary16
+    mode, sample by sample at the sample's own length (the walk of tests/test_gpu_tokens_packed.py with the FP16 bar)."""
+    import test_gpu_tokens_packed as TP
+    TP.TOL["f16"], TP.EPS_SEL_ENC["f16"] = 4e-3, 2e-2
+    _say("f16 packed tokens")
+    TP._packed_case(make_wl(W.small_spec(dtype="f16", d=128, dh=64, Hq=8, Hk=2, F=300, seg=(100, 33, 64, 120), B=9, nl=2,
+                                         dropout="upto:3", act=1)))
+
+
 def test_f16_moe_ffn_parity():
     _say("f16 moe")
     wl = make_wl(W.small_spec(dtype="f16", d=128, dh=64, Hq=8, Hk=2, F=320, seg=(100, 133, 64), extra=3, B=5,

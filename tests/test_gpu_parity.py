@@ -610,6 +610,8 @@ def _gqa_case(dtype, B, nH, nG, L, dh, U_override, mask, seed, per_sample_map=Fa
     ("bf16", 1, 8, 4, 4096, 64, -1, False),        # C5-shaped: key splits
     ("bf16", 16, 9, 3, 2048, 64, -1, False),       # key splits; groups of unequal size: passes that leave waves
                                                    # without a pair, groups that need a second pass
+    ("bf16", 40, 16, 8, 300, 32, -1, True),        # a (sample, group) problem per compute unit and two pairs each: the
+                                                   # four-wave build of the active pass
     ("bf16", 2, 3, 1, 203, 64, -1, True),          # ragged L, one group
     ("bf16", 2, 4, 2, 333, 128, -1, True),         # dh 128
     ("bf16", 2, 4, 2, 200, 64, 200, False),        # dense pattern (U = L): flash GQA

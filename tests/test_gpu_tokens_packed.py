@@ -17,7 +17,7 @@ import torch
 from oracle import cpu_oracle as orc
 from paper_2604_08971_amd import binding as sf
 from paper_2604_08971_amd import workloads as W
-from gpu_utils import DeviceModel, desc_for, selection_report, to_dev, to_host
+from gpu_utils import ORACLE_MODE, DeviceModel, desc_for, selection_report, to_dev, to_host
 from helpers import compact_packs, err_metric, make_wl, oracle_masks
 
 pytestmark = pytest.mark.gpu
@@ -157,7 +157,7 @@ def test_token_pack_layout_and_rows(dtype, B, L, d, P, c, tight):
 
 def _packed_case(wl, samples=None, tight=True):
     s = wl.spec
-    bf = s.dtype == "bf16"
+    bf = ORACLE_MODE[s.dtype]
     assert wl.key_valid is not None
     dm = DeviceModel(wl).build_plan()
     ref_masks = oracle_masks(wl)
