@@ -482,11 +482,14 @@ AttnPlan attn_plan(int dtype, const AttnArgs &a, void *ws)
     pl.keys_per_split = (int)align_up(a.L, 64);
     if (dtype == SF_BF16 && sparse && a.U > 0) {
         // the active pass has only B*nG independent (sample, group) problems: with fewer than one per compute unit
-        // the keys are split until roughly 512 workgroups exist (measured on the four bf16 workloads against
-        // targets of 256, 768 and 1536: more splits cost more in partial sums and their merge than they gain)
+        // the keys are split until one workgroup per compute unit exists (256; the kernel keeps one workgroup per
+        // compute unit resident, so 384 or 512 workgroups run in two rounds: measured at C5 with the key groups
+        // inside a workgroup, active pass 36 us for 256 against 47 / 41 / 51 us for 384 / 512 / 1024 and 55 us for
+        // 128), and only into pieces of at least four key tiles (C2, 384 keys: unsplit and without the merge launch
+        // the step is 6 us shorter)
         const int64_t bg = (int64_t)a.B * a.nG;
-        int want = bg >= 256 ? 1 : (int)((512 + bg - 1) / bg);
-        const int max_splits = a.L / 128 > 0 ? a.L / 128 : 1;
+        int want = bg >= 256 ? 1 : (int)((256 + bg - 1) / bg);
+        const int max_splits = a.L / 256 > 0 ? a.L / 256 : 1;
         if (want > max_splits) want = max_splits;
         if (want > 64) want = 64;                     // the merge holds one split per lane
         if (want > 1) {
