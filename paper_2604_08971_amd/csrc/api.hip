@@ -473,9 +473,9 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         if (lazy) {
             const AttnPlan pl = attn_plan(D.dtype, a, a.ws);
             lazy_rows_active(pl.slot, pattern_id, D.B, kh, D.L, capA, w.lz_cnt, w.lz_arow, w.lz_pos, w.lz_n, w.lz_blk, st);
-            lazy_att_compact(w.att, a.ldo, pl.slot, pl.stats, ly.head_group, D.Hq, pattern_id, w.lz_arow, w.lz_n, D.B, kh,
-                             Hk, D.L, dh, capA, w.lz_A, st);
             if (proj8) {
+                lazy_att_compact(w.att, a.ldo, pl.slot, pl.stats, ly.head_group, D.Hq, pattern_id, w.lz_arow, w.lz_n, D.B,
+                                 kh, Hk, D.L, dh, capA, w.lz_A, st);
                 // the same rows in FP8 arithmetic: codes of the compact rows, FP8 GEMM per sample, and the shared
                 // vector from the codes of the context vector
                 const sf_proj_fp8 &pj = proj8[l];
@@ -494,6 +494,9 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
                 lazy_ctx_proj_q8(pl.stats, ly.head_group, D.Hq, pattern_id, pj.WoT8, (int64_t)D.d * Ko, (int)Ko, ly.bo,
                                  D.B, kh, Hk, dh, D.d, 1.0f / pj.sa, pj.sa * pj.so, w.lz_c, st);
             } else {
+                lazy_att_compact_ctx_proj(w.att, a.ldo, pl.slot, pl.stats, ly.head_group, D.Hq, pattern_id, w.lz_arow,
+                                          w.lz_n, D.B, kh, Hk, D.L, dh, capA, w.lz_A, ly.WoT, (int64_t)D.d * kh * dh, ly.bo,
+                                          D.d, w.lz_c, st);
                 GemmArgs o{};
                 o.A = w.lz_A; o.lda = (int64_t)kh * dh; o.W = ly.WoT; o.ldw = (int64_t)kh * dh;
                 // 128-row blocks of the compact buffer, each with its sample's pattern (-1: no rows, skipped)
@@ -501,8 +504,6 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
                 o.B = D.B * (capA / 128); o.L = 128; o.N = D.d; o.K = kh * dh; o.epi = EPI_ROWMAJOR; o.act = ACT_NONE;
                 o.C = w.lz_C; o.ldc = D.d; o.c_f32 = 1;
                 if (int32_t rc = gemm(D.dtype, o, st)) return rc;
-                lazy_ctx_proj(pl.stats, ly.head_group, D.Hq, pattern_id, ly.WoT, (int64_t)D.d * kh * dh, ly.bo, D.B, kh,
-                              Hk, dh, D.d, w.lz_c, st);
             }
             // x1 = x + projection, and xn = LN2(x1) (bf16, or E4M3 codes for an FFN in FP8 arithmetic), in one pass
             const bool to_y = l == D.nl - 1 && !final_ln;

@@ -76,9 +76,11 @@ void lazy_rows_active(const int32_t *slot, const int32_t *pattern_id, int B, int
 void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const float *stats, const int32_t *head_group,
                       int hg_stride, const int32_t *pattern_id, const int32_t *arow, const int32_t *n_act, int B, int nH,
                       int nG, int L, int dh, int capA, void *Ac, hipStream_t st);
-void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
-                   const void *WoT, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d, float *cvec,
-                   hipStream_t st);
+// the compact rows and the projected context vectors c_b in one launch
+void lazy_att_compact_ctx_proj(const void *att, int64_t ldo, const int32_t *slot, const float *stats,
+                               const int32_t *head_group, int hg_stride, const int32_t *pattern_id, const int32_t *arow,
+                               const int32_t *n_act, int B, int nH, int nG, int L, int dh, int capA, void *Ac,
+                               const void *WoT, int64_t w_pstride, const void *bo, int d, float *cvec, hipStream_t st);
 // FP8 arithmetic: the context vector quantised with 1/inv_sa, weights as E4M3 codes [P][d, ldw], ldw >= nH*dh
 // (8-byte aligned rows)
 void lazy_ctx_proj_q8(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,

@@ -12,62 +12,57 @@ namespace sf {
 
 namespace {
 
-// The rows with an active head, ascending, in two passes over 256-row chunks (one block per sample and chunk).
-// Pass 1 counts, pass 2 places: arow[b, j] = row of compact position j, pos_of[b, i] = compact position of row i
+// The rows with an active head, ascending: one block per sample counts and places them in one go (a row is active
+// when any kept head selected it).  arow[b, j] = row of compact position j, pos_of[b, i] = compact position of row i
 // or -1, n_act[b] = their number (<= capA by construction: a head has at most U active rows and capA >= nH*U), and
 // blk_pattern[b, k] = the sample's pattern for the 128-row blocks of the compact buffer that hold rows, -1 for the
 // empty ones (the GEMM skips those).
-__device__ __forceinline__ bool row_active(const int32_t *__restrict__ slot, int b, int nH, int L, int i)
-{
-    bool act = false;
-    if (i < L)
-        for (int h = 0; h < nH; ++h) act = act || slot[((int64_t)b * nH + h) * L + i] >= 0;
-    return act;
-}
+constexpr int RA_NT = 1024;          // at most 16 rows per thread: L <= 16384 (lazy_cap() admits no longer sequence)
 
-__global__ __launch_bounds__(256) void rows_active_count_kernel(const int32_t *__restrict__ slot, int nH, int L,
-                                                                int32_t *__restrict__ counts)
+__global__ __launch_bounds__(RA_NT) void rows_active_kernel(const int32_t *__restrict__ slot, int nH, int L, int capA,
+                                                            const int32_t *__restrict__ pattern_id,
+                                                            int32_t *__restrict__ arow, int32_t *__restrict__ pos_of,
+                                                            int32_t *__restrict__ n_act, int32_t *__restrict__ blk_pattern)
 {
-    __shared__ int wsum[4];
-    const int c = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint64_t m = __ballot(row_active(slot, b, nH, L, c * 256 + (int)threadIdx.x));
-    if (lane == 0) wsum[wave] = __popcll(m);
-    __syncthreads();
-    if (threadIdx.x == 0) counts[(int64_t)b * gridDim.x + c] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-}
-
-__global__ __launch_bounds__(256) void rows_active_place_kernel(const int32_t *__restrict__ slot, int nH, int L, int capA,
-                                                                const int32_t *__restrict__ counts,
-                                                                const int32_t *__restrict__ pattern_id,
-                                                                int32_t *__restrict__ arow, int32_t *__restrict__ pos_of,
-                                                                int32_t *__restrict__ n_act, int32_t *__restrict__ blk_pattern)
-{
-    __shared__ int wsum[4];
-    __shared__ int base_s, total_s;
-    const int c = blockIdx.x, b = blockIdx.y, nchunk = gridDim.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x < 64) {                                   // nchunk <= 64 (L <= 16384)
-        const int v = (int)threadIdx.x < nchunk ? counts[(int64_t)b * nchunk + threadIdx.x] : 0;
-        int before = (int)threadIdx.x < c ? v : 0, all = v;
+    __shared__ int wsum[RA_NT / 64];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // thread t owns the consecutive rows [t*per, (t+1)*per): positions then follow from one scan over the threads
+    const int per = (L + RA_NT - 1) / RA_NT;
+    const int i0 = tid * per;
+    uint32_t bits = 0;
+    for (int h = 0; h < nH; ++h) {                  // independent loads: no early exit
+        const int32_t *sl = slot + ((int64_t)b * nH + h) * L;
+        for (int k = 0; k < per; ++k)
+            if (i0 + k < L) bits |= (uint32_t)(sl[i0 + k] >= 0) << k;
+    }
+    const int cnt = __popc(bits);
+    int incl = cnt;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) { before += __shfl_xor(before, o); all += __shfl_xor(all, o); }
-        if (threadIdx.x == 0) { base_s = before; total_s = all; }
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
     }
-    const int i = c * 256 + (int)threadIdx.x;
-    const bool act = row_active(slot, b, nH, L, i);
-    const uint64_t m = __ballot(act);
-    if (lane == 0) wsum[wave] = __popcll(m);
+    if (lane == 63) wsum[wave] = incl;
     __syncthreads();
-    int pos = base_s + __popcll(m & ((1ull << lane) - 1ull));
-    for (int w = 0; w < wave; ++w) pos += wsum[w];
-    const bool keep = act && pos < capA;
-    if (i < L) pos_of[(int64_t)b * L + i] = keep ? pos : -1;
-    if (keep) arow[(int64_t)b * capA + pos] = i;
-    if (c == 0) {
-        const int total = min(total_s, capA);
-        if (threadIdx.x == 0) n_act[b] = total;
-        const int p = pattern_id ? pattern_id[b] : 0;
-        for (int k = threadIdx.x; k < capA / 128; k += 256) blk_pattern[(int64_t)b * (capA / 128) + k] = k * 128 < total ? p : -1;
+    int pos = incl - cnt, total = 0;
+#pragma unroll
+    for (int w = 0; w < RA_NT / 64; ++w) {
+        const int c = wsum[w];
+        if (w < wave) pos += c;
+        total += c;
     }
+    for (int k = 0; k < per; ++k) {
+        const int i = i0 + k;
+        if (i >= L) break;
+        const bool keep = ((bits >> k) & 1u) && pos < capA;
+        pos_of[(int64_t)b * L + i] = keep ? pos : -1;
+        if (keep) arow[(int64_t)b * capA + pos] = i;
+        pos += (bits >> k) & 1u;
+    }
+    total = min(total, capA);
+    if (tid == 0) n_act[b] = total;
+    const int p = pattern_id ? pattern_id[b] : 0;
+    for (int k = tid; k < capA / 128; k += RA_NT) blk_pattern[(int64_t)b * (capA / 128) + k] = k * 128 < total ? p : -1;
 }
 
 // 8 consecutive context values of head h (group g of sample b), rounded to bf16 as the attention output stores them
@@ -82,7 +77,7 @@ __device__ __forceinline__ h16x8 ctx8(const float *__restrict__ stats, int b, in
 
 // One wave per compact row: the attention output of an active row - its active heads from `att`, its lazy heads from
 // the context vectors - or a zero row behind n_act[b].  K = nH*dh, a multiple of 8; dh a multiple of 8.
-__global__ __launch_bounds__(256) void att_compact_kernel(const h16 *__restrict__ att, int64_t ldo,
+__device__ __forceinline__ void att_compact_rows(int block, const h16 *__restrict__ att, int64_t ldo,
                                                           const int32_t *__restrict__ slot, const float *__restrict__ stats,
                                                           const int32_t *__restrict__ head_group, int hg_stride,
                                                           const int32_t *__restrict__ pattern_id,
@@ -91,7 +86,7 @@ __global__ __launch_bounds__(256) void att_compact_kernel(const h16 *__restrict_
                                                           h16 *__restrict__ Ac)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t r = (int64_t)block * 4 + (threadIdx.x >> 6);
     if (r >= (int64_t)B * capA) return;
     const int b = (int)(r / capA), j = (int)(r % capA);
     const int K = nH * dh;
@@ -115,14 +110,14 @@ __global__ __launch_bounds__(256) void att_compact_kernel(const h16 *__restrict_
 }
 
 // One wave per (sample, output feature n): c[b, n] = sum_k bf16(ctx_b[k]) WoT[p_b][n, k] + bo[n], fp32.
-__global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__ stats, const int32_t *__restrict__ head_group,
+__device__ __forceinline__ void ctx_proj_rows(int block, const float *__restrict__ stats, const int32_t *__restrict__ head_group,
                                                        int hg_stride, const int32_t *__restrict__ pattern_id,
                                                        const h16 *__restrict__ WoT, int64_t w_pstride,
                                                        const h16 *__restrict__ bo, int B, int nH, int nG, int dh,
                                                        int d, float *__restrict__ cvec)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t r = (int64_t)block * 4 + (threadIdx.x >> 6);
     if (r >= (int64_t)B * d) return;
     const int b = (int)(r / d), n = (int)(r % d);
     const int p = pattern_id ? pattern_id[b] : 0;
@@ -139,6 +134,35 @@ __global__ __launch_bounds__(256) void ctx_proj_kernel(const float *__restrict__
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
     if (lane == 0) cvec[r] = acc + (bo ? (float)bo[n] : 0.f);
+}
+
+__global__ __launch_bounds__(256) void att_compact_kernel(const h16 *__restrict__ att, int64_t ldo,
+                                                          const int32_t *__restrict__ slot, const float *__restrict__ stats,
+                                                          const int32_t *__restrict__ head_group, int hg_stride,
+                                                          const int32_t *__restrict__ pattern_id,
+                                                          const int32_t *__restrict__ arow, const int32_t *__restrict__ n_act,
+                                                          int B, int nH, int nG, int L, int dh, int capA,
+                                                          h16 *__restrict__ Ac)
+{
+    att_compact_rows(blockIdx.x, att, ldo, slot, stats, head_group, hg_stride, pattern_id, arow, n_act, B, nH, nG, L, dh,
+                     capA, Ac);
+}
+
+// Both in one launch (they are independent and small): the first n_compact blocks gather the compact rows, the rest
+// project the context vectors.
+__global__ __launch_bounds__(256) void att_compact_ctx_proj_kernel(
+    int n_compact, const h16 *__restrict__ att, int64_t ldo, const int32_t *__restrict__ slot,
+    const float *__restrict__ stats, const int32_t *__restrict__ head_group, int hg_stride,
+    const int32_t *__restrict__ pattern_id, const int32_t *__restrict__ arow, const int32_t *__restrict__ n_act, int B,
+    int nH, int nG, int L, int dh, int capA, h16 *__restrict__ Ac, const h16 *__restrict__ WoT, int64_t w_pstride,
+    const h16 *__restrict__ bo, int d, float *__restrict__ cvec)
+{
+    if ((int)blockIdx.x < n_compact)
+        att_compact_rows(blockIdx.x, att, ldo, slot, stats, head_group, hg_stride, pattern_id, arow, n_act, B, nH, nG, L,
+                         dh, capA, Ac);
+    else
+        ctx_proj_rows(blockIdx.x - n_compact, stats, head_group, hg_stride, pattern_id, WoT, w_pstride, bo, B, nH, nG, dh,
+                      d, cvec);
 }
 
 // The same in FP8 arithmetic: the context vector is quantised like every other row of the attention output,
@@ -292,10 +316,9 @@ int lazy_cap(int L, int nH, int U, int dh, int d)
 void lazy_rows_active(const int32_t *slot, const int32_t *pattern_id, int B, int nH, int L, int capA, int32_t *counts,
                       int32_t *arow, int32_t *pos_of, int32_t *n_act, int32_t *blk_pattern, hipStream_t st)
 {
-    dim3 grid(ceil_div(L, 256), B);
-    hipLaunchKernelGGL(rows_active_count_kernel, grid, dim3(256), 0, st, slot, nH, L, counts);
-    hipLaunchKernelGGL(rows_active_place_kernel, grid, dim3(256), 0, st, slot, nH, L, capA, counts, pattern_id, arow,
-                       pos_of, n_act, blk_pattern);
+    (void)counts;
+    hipLaunchKernelGGL(rows_active_kernel, dim3(B), dim3(RA_NT), 0, st, slot, nH, L, capA, pattern_id, arow, pos_of, n_act,
+                       blk_pattern);
 }
 
 void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const float *stats, const int32_t *head_group,
@@ -307,13 +330,15 @@ void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const f
                        slot, stats, head_group, hg_stride, pattern_id, arow, n_act, B, nH, nG, L, dh, capA, (h16 *)Ac);
 }
 
-void lazy_ctx_proj(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
-                   const void *WoT, int64_t w_pstride, const void *bo, int B, int nH, int nG, int dh, int d, float *cvec,
-                   hipStream_t st)
+void lazy_att_compact_ctx_proj(const void *att, int64_t ldo, const int32_t *slot, const float *stats,
+                               const int32_t *head_group, int hg_stride, const int32_t *pattern_id, const int32_t *arow,
+                               const int32_t *n_act, int B, int nH, int nG, int L, int dh, int capA, void *Ac,
+                               const void *WoT, int64_t w_pstride, const void *bo, int d, float *cvec, hipStream_t st)
 {
-    const int64_t rows = (int64_t)B * d;
-    hipLaunchKernelGGL(ctx_proj_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, stats, head_group, hg_stride,
-                       pattern_id, (const h16 *)WoT, w_pstride, (const h16 *)bo, B, nH, nG, dh, d, cvec);
+    const int64_t n_compact = ((int64_t)B * capA + 3) / 4, n_proj = ((int64_t)B * d + 3) / 4;
+    hipLaunchKernelGGL(att_compact_ctx_proj_kernel, dim3((unsigned)(n_compact + n_proj)), dim3(256), 0, st, (int)n_compact,
+                       (const h16 *)att, ldo, slot, stats, head_group, hg_stride, pattern_id, arow, n_act, B, nH, nG, L, dh,
+                       capA, (h16 *)Ac, (const h16 *)WoT, w_pstride, (const h16 *)bo, d, cvec);
 }
 
 void lazy_ctx_proj_q8(const float *stats, const int32_t *head_group, int hg_stride, const int32_t *pattern_id,
