@@ -200,7 +200,7 @@ static int32_t enc_ws(const Dims &D, const sf_compact_layer *layers, void *ws, E
         w.lz_arow = c.take<int32_t>(crow);
         w.lz_pos = c.take<int32_t>(rows);
         w.lz_n = c.take<int32_t>(D.B);
-        w.lz_cnt = c.take<int32_t>((size_t)D.B * ceil_div(D.L, 256));
+        w.lz_cnt = c.take<int32_t>((size_t)D.B * ceil_div(D.L, 32));      // one bit per row: selected by some head
         w.lz_blk = c.take<int32_t>((size_t)D.B * (w.lz_cap / 128));
     }
     w.bytes = c.off;
@@ -469,10 +469,11 @@ static int32_t encoder_forward_impl(const sf_desc *desc, const sf_compact_layer 
         const bool lazy = !pk && capA > 0 && capA <= w.lz_cap && (!proj8 || capA >= 256) &&
                           !(((uintptr_t)ly.bo | (uintptr_t)ly.ln2_g | (uintptr_t)ly.ln2_b | (uintptr_t)in) & 15);
         a.skip_fill = lazy && !(proj8 && oq_out);        // a caller who wants the codes of every row gets the rows filled
+        a.act_bits = lazy ? reinterpret_cast<uint32_t *>(w.lz_cnt) : nullptr;
         if (int32_t rc = attention_forward(D.dtype, a, st)) return rc;
         if (lazy) {
             const AttnPlan pl = attn_plan(D.dtype, a, a.ws);
-            lazy_rows_active(pl.slot, pattern_id, D.B, kh, D.L, capA, w.lz_cnt, w.lz_arow, w.lz_pos, w.lz_n, w.lz_blk, st);
+            lazy_rows_active(a.act_bits, pattern_id, D.B, D.L, capA, w.lz_arow, w.lz_pos, w.lz_n, w.lz_blk, st);
             if (proj8) {
                 lazy_att_compact(w.att, a.ldo, pl.slot, pl.stats, ly.head_group, D.Hq, pattern_id, w.lz_arow, w.lz_n, D.B,
                                  kh, Hk, D.L, dh, capA, w.lz_A, st);

@@ -28,6 +28,9 @@ struct AttnArgs {
     // defined).  The per-sample arrays of the workspace, key_valid, sel and score keep their [B, ..., L] shape, L =
     // the longest sequence a sample may have; key_valid marks the sample's own rows.  NULL: samples b*L apart.
     const int32_t *row0, *ext;
+    // [B, ceil(L/32)] or NULL: bit i of sample b is set when some head selected row i (cleared by the statistics
+    // pass, set by the selection; what the active-row output projection starts from)
+    uint32_t *act_bits;
     void *ws; size_t ws_bytes;
 };
 
@@ -71,8 +74,8 @@ int32_t attend_bf16(const AttnArgs &a, const AttnPlan &pl, const void *vt, sf_st
 // Output projection when most rows are lazy (lazy_proj.hip).  lazy_cap: rows per sample of the compact buffers, 0
 // when the shortcut does not apply.  slot [B,nH,L] and stats are the pieces of the attention plan.
 int lazy_cap(int L, int nH, int U, int dh, int d);
-void lazy_rows_active(const int32_t *slot, const int32_t *pattern_id, int B, int nH, int L, int capA, int32_t *counts,
-                      int32_t *arow, int32_t *pos_of, int32_t *n_act, int32_t *blk_pattern, hipStream_t st);
+void lazy_rows_active(const uint32_t *act_bits, const int32_t *pattern_id, int B, int L, int capA, int32_t *arow,
+                      int32_t *pos_of, int32_t *n_act, int32_t *blk_pattern, hipStream_t st);
 void lazy_att_compact(const void *att, int64_t ldo, const int32_t *slot, const float *stats, const int32_t *head_group,
                       int hg_stride, const int32_t *pattern_id, const int32_t *arow, const int32_t *n_act, int B, int nH,
                       int nG, int L, int dh, int capA, void *Ac, hipStream_t st);

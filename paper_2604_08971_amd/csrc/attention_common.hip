@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void kv_stats_partial_bf16_kernel(
 // stats[bg][0][:] = mean allowed key, stats[bg][1][:] = mean allowed value.
 __global__ __launch_bounds__(256) void kv_stats_final_kernel(
     const float *__restrict__ part, int chunks, const uint8_t *__restrict__ key_valid, int nG, int L,
-    int dh, float *__restrict__ stats, int32_t *__restrict__ n_valid)
+    int dh, float *__restrict__ stats, int32_t *__restrict__ n_valid, uint32_t *__restrict__ act_bits)
 {
     __shared__ int red[4];
     const int bg = blockIdx.x, b = bg / nG;
@@ -132,6 +132,8 @@ __global__ __launch_bounds__(256) void kv_stats_final_kernel(
         c = L;
     }
     if (threadIdx.x == 0 && bg % nG == 0) n_valid[b] = c;
+    if (act_bits && bg % nG == 0)                 // the selection that follows sets the bits of the rows it picks
+        for (int w = threadIdx.x; w < (L + 31) / 32; w += 256) act_bits[(int64_t)b * ((L + 31) / 32) + w] = 0u;
     const float inv = c > 0 ? 1.0f / (float)c : 0.f;
     for (int t = threadIdx.x; t < 2 * dh; t += 256) {
         float s = 0.f;
@@ -148,7 +150,8 @@ __global__ __launch_bounds__(256) void kv_stats_final_kernel(
 template <int NT>
 __global__ __launch_bounds__(NT) void select_kernel(
     const float *__restrict__ score, int scoreH, const uint8_t *__restrict__ key_valid, int nH, int L,
-    int U, const int32_t *__restrict__ u_active, int32_t *__restrict__ sel, int selH, int32_t *__restrict__ slot)
+    int U, const int32_t *__restrict__ u_active, int32_t *__restrict__ sel, int selH, int32_t *__restrict__ slot,
+    uint32_t *__restrict__ act_bits)
 {
     extern __shared__ uint32_t keys[];
     __shared__ int scratch[TOPK_SCRATCH];
@@ -173,7 +176,10 @@ __global__ __launch_bounds__(NT) void select_kernel(
     } else {
         block_topk<NT>(keys, L, k, scratch, [&](int i, bool kept, int pos) {
             sl[i] = kept ? pos : -1;
-            if (kept) se[pos] = i;
+            if (kept) {
+                se[pos] = i;
+                if (act_bits) atomicOr(&act_bits[(int64_t)b * ((L + 31) / 32) + (i >> 5)], 1u << (i & 31));
+            }
         });
     }
     for (int r = k + threadIdx.x; r < U; r += NT) se[r] = -1;
@@ -182,7 +188,8 @@ __global__ __launch_bounds__(NT) void select_kernel(
 // Caller-supplied active set: build the row -> slot map and copy the list.
 __global__ __launch_bounds__(256) void forced_slot_kernel(const int32_t *__restrict__ forced, int forcedH,
                                                           int nH, int L, int U, int32_t *__restrict__ sel,
-                                                          int selH, int32_t *__restrict__ slot)
+                                                          int selH, int32_t *__restrict__ slot,
+                                                          uint32_t *__restrict__ act_bits)
 {
     const int bh = blockIdx.x, b = bh / nH, h = bh % nH;
     int32_t *sl = slot + (int64_t)bh * L;
@@ -192,7 +199,10 @@ __global__ __launch_bounds__(256) void forced_slot_kernel(const int32_t *__restr
         int q = forced[((int64_t)b * forcedH + h) * U + r];
         if (q < 0 || q >= L) q = -1;
         sel[((int64_t)b * selH + h) * U + r] = q;
-        if (q >= 0) sl[q] = r;
+        if (q >= 0) {
+            sl[q] = r;
+            if (act_bits) atomicOr(&act_bits[(int64_t)b * ((L + 31) / 32) + (q >> 5)], 1u << (q & 31));
+        }
     }
 }
 
@@ -582,7 +592,7 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
                                a.sk, (const float *)Vuse, svu, v_sj, v_se, a.key_valid, a.nG, a.L, a.dh,
                                DHP, pl.stat_part, a.row0, vT ? nullptr : a.row0);
         hipLaunchKernelGGL(kv_stats_final_kernel, dim3(BG), dim3(256), 0, st, pl.stat_part, pl.stat_chunks,
-                           a.key_valid, a.nG, a.L, a.dh, pl.stats, pl.n_valid);
+                           a.key_valid, a.nG, a.L, a.dh, pl.stats, pl.n_valid, a.act_bits);
     }
 
     // 2. active set
@@ -591,7 +601,7 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
     const int selH = a.sel_out ? userH : a.nH;
     if (a.forced_sel && a.U > 0) {
         hipLaunchKernelGGL(forced_slot_kernel, dim3(BH), dim3(256), 0, st, a.forced_sel, userH, a.nH, a.L, a.U,
-                           sel, selH, pl.slot);
+                           sel, selH, pl.slot, a.act_bits);
     } else {
         const float *M = nullptr;
         int scoreH = a.nH;
@@ -633,10 +643,10 @@ int32_t attention_forward(int dtype, const AttnArgs &a, hipStream_t st)
         // few blocks (one per sample and head): long rows get 1024 threads so that a radix pass is 4 keys per thread
         if (a.L >= 2048)
             hipLaunchKernelGGL(select_kernel<1024>, dim3(BH), dim3(1024), a.L * sizeof(uint32_t), st, M, scoreH,
-                               a.key_valid, a.nH, a.L, a.U, a.u_active, sel, selH, pl.slot);
+                               a.key_valid, a.nH, a.L, a.U, a.u_active, sel, selH, pl.slot, a.act_bits);
         else
             hipLaunchKernelGGL(select_kernel<256>, dim3(BH), dim3(256), a.L * sizeof(uint32_t), st, M, scoreH,
-                               a.key_valid, a.nH, a.L, a.U, a.u_active, sel, selH, pl.slot);
+                               a.key_valid, a.nH, a.L, a.U, a.u_active, sel, selH, pl.slot, a.act_bits);
     }
 
     // 3. active rows

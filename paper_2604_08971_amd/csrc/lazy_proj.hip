@@ -12,29 +12,23 @@ namespace sf {
 
 namespace {
 
-// The rows with an active head, ascending: one block per sample counts and places them in one go (a row is active
-// when any kept head selected it).  arow[b, j] = row of compact position j, pos_of[b, i] = compact position of row i
-// or -1, n_act[b] = their number (<= capA by construction: a head has at most U active rows and capA >= nH*U), and
-// blk_pattern[b, k] = the sample's pattern for the 128-row blocks of the compact buffer that hold rows, -1 for the
-// empty ones (the GEMM skips those).
-constexpr int RA_NT = 1024;          // at most 16 rows per thread: L <= 16384 (lazy_cap() admits no longer sequence)
+// The rows with an active head, ascending, from the bitmap the selection leaves behind (bit i of sample b: some kept
+// head selected row i): one block per sample, a thread per 32-row word.  arow[b, j] = row of compact position j,
+// pos_of[b, i] = compact position of row i or -1, n_act[b] = their number (<= capA by construction: a head has at most
+// U active rows and capA >= nH*U), and blk_pattern[b, k] = the sample's pattern for the 128-row blocks of the compact
+// buffer that hold rows, -1 for the empty ones (the GEMM skips those).
+constexpr int RA_NT = 512;          // one word per thread: L <= 16384 (lazy_cap() admits no longer sequence)
 
-__global__ __launch_bounds__(RA_NT) void rows_active_kernel(const int32_t *__restrict__ slot, int nH, int L, int capA,
+__global__ __launch_bounds__(RA_NT) void rows_active_kernel(const uint32_t *__restrict__ act_bits, int L, int capA,
                                                             const int32_t *__restrict__ pattern_id,
                                                             int32_t *__restrict__ arow, int32_t *__restrict__ pos_of,
                                                             int32_t *__restrict__ n_act, int32_t *__restrict__ blk_pattern)
 {
     __shared__ int wsum[RA_NT / 64];
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // thread t owns the consecutive rows [t*per, (t+1)*per): positions then follow from one scan over the threads
-    const int per = (L + RA_NT - 1) / RA_NT;
-    const int i0 = tid * per;
-    uint32_t bits = 0;
-    for (int h = 0; h < nH; ++h) {                  // independent loads: no early exit
-        const int32_t *sl = slot + ((int64_t)b * nH + h) * L;
-        for (int k = 0; k < per; ++k)
-            if (i0 + k < L) bits |= (uint32_t)(sl[i0 + k] >= 0) << k;
-    }
+    const int nwords = (L + 31) / 32;
+    uint32_t bits = tid < nwords ? act_bits[(int64_t)b * nwords + tid] : 0u;
+    if (tid == nwords - 1 && (L & 31)) bits &= (1u << (L & 31)) - 1u;      // no row behind L
     const int cnt = __popc(bits);
     int incl = cnt;
 #pragma unroll
@@ -51,13 +45,15 @@ __global__ __launch_bounds__(RA_NT) void rows_active_kernel(const int32_t *__res
         if (w < wave) pos += c;
         total += c;
     }
-    for (int k = 0; k < per; ++k) {
-        const int i = i0 + k;
-        if (i >= L) break;
-        const bool keep = ((bits >> k) & 1u) && pos < capA;
-        pos_of[(int64_t)b * L + i] = keep ? pos : -1;
-        if (keep) arow[(int64_t)b * capA + pos] = i;
-        pos += (bits >> k) & 1u;
+    if (tid < nwords) {
+        const int i0 = tid * 32;
+        for (int k = 0; k < 32 && i0 + k < L; ++k) {
+            const bool act = (bits >> k) & 1u;
+            const bool keep = act && pos < capA;
+            pos_of[(int64_t)b * L + i0 + k] = keep ? pos : -1;
+            if (keep) arow[(int64_t)b * capA + pos] = i0 + k;
+            pos += act;
+        }
     }
     total = min(total, capA);
     if (tid == 0) n_act[b] = total;
@@ -313,11 +309,10 @@ int lazy_cap(int L, int nH, int U, int dh, int d)
     return (int)cap;
 }
 
-void lazy_rows_active(const int32_t *slot, const int32_t *pattern_id, int B, int nH, int L, int capA, int32_t *counts,
-                      int32_t *arow, int32_t *pos_of, int32_t *n_act, int32_t *blk_pattern, hipStream_t st)
+void lazy_rows_active(const uint32_t *act_bits, const int32_t *pattern_id, int B, int L, int capA, int32_t *arow,
+                      int32_t *pos_of, int32_t *n_act, int32_t *blk_pattern, hipStream_t st)
 {
-    (void)counts;
-    hipLaunchKernelGGL(rows_active_kernel, dim3(B), dim3(RA_NT), 0, st, slot, nH, L, capA, pattern_id, arow, pos_of, n_act,
+    hipLaunchKernelGGL(rows_active_kernel, dim3(B), dim3(RA_NT), 0, st, act_bits, L, capA, pattern_id, arow, pos_of, n_act,
                        blk_pattern);
 }
 
