@@ -2,6 +2,8 @@
 // concatenated tokens of the sensors that are present), each sample keeps its valid tokens in order at the front of
 // a shorter padded sequence, and its number of active queries follows its own length, U_b = min(c*ceil(ln T_b), T_b)
 // (Sec. 4.4).  Index work only: bit-exact.
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace sf {
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(256) void token_rank_kernel(const uint8_t *__restri
     if (threadIdx.x == 0) len[b] = base_s;
 }
 
-// Pass 2, one block of 1024 threads: the layout.  n_rows[0] = rows in use (runs + slack, a multiple of 256; 0 when
+// Pass 2, one block (as many waves as the batch needs, at most 16: its barriers are the cost): the layout.  n_rows[0] = rows in use (runs + slack, a multiple of 256; 0 when
 // no sample has a token), n_rows[1] = the same before the comparison with Tc.  When the rows do not fit
 // (n_rows[1] > Tc) the plan is the empty one - every sample at row 0 with no rows, every block unused - so that
 // whatever runs on it touches nothing; the caller reads n_rows[1] and comes back with a larger buffer.
@@ -149,15 +151,16 @@ __global__ __launch_bounds__(1024) void pack_layout_kernel(const int32_t *__rest
     __shared__ int wsum[16], wlast[16];
     __shared__ int base_s, last_b_s, tail_b_s, tail_p_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int NT = blockDim.x, NWV = NT >> 6;             // a multiple of 64, at most 1024
     const int nblk = Tc / 256;
     if (tid == 0) { base_s = 0; tail_b_s = -1; tail_p_s = -1; }
-    for (int k = tid; k < nblk; k += 1024) blk_pattern[k] = -1;
+    for (int k = tid; k < nblk; k += NT) blk_pattern[k] = -1;
     __syncthreads();
     for (int p = 0; p < P; ++p) {
         const int seg0 = base_s;
         if (tid == 0) last_b_s = -1;
         __syncthreads();
-        for (int c0 = 0; c0 < B; c0 += 1024) {
+        for (int c0 = 0; c0 < B; c0 += NT) {
             const int b = c0 + tid;
             const bool mine = b < B && (pattern_id ? pattern_id[b] : 0) == p;
             const int v = mine ? len[b] : 0;
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(1024) void pack_layout_kernel(const int32_t *__rest
             __syncthreads();
             if (tid == 0) {
                 int tot = 0, lb = last_b_s;
-                for (int w = 0; w < 16; ++w) { tot += wsum[w]; lb = max(lb, wlast[w]); }
+                for (int w = 0; w < NWV; ++w) { tot += wsum[w]; lb = max(lb, wlast[w]); }
                 base_s += tot;
                 last_b_s = lb;
             }
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(1024) void pack_layout_kernel(const int32_t *__rest
         const int seg1a = (seg1 + 255) & ~255;
         __syncthreads();
         if (seg1 > seg0) {                                    // the run has rows
-            for (int k = seg0 / 256 + tid; k < seg1a / 256; k += 1024)
+            for (int k = seg0 / 256 + tid; k < seg1a / 256; k += NT)
                 if (k < nblk) blk_pattern[k] = p;
             if (tid == 0) {
                 ext[lb] = seg1a - row0[lb];                   // its last sample also answers for the padding
@@ -204,12 +207,12 @@ __global__ __launch_bounds__(1024) void pack_layout_kernel(const int32_t *__rest
     __syncthreads();
     if (need <= Tc) {
         if (used > 0) {
-            for (int k = used / 256 + tid; k < need / 256; k += 1024) blk_pattern[k] = tail_p_s;
+            for (int k = used / 256 + tid; k < need / 256; k += NT) blk_pattern[k] = tail_p_s;
             if (tid == 0) ext[tail_b_s] += slack;
         }
     } else {
-        for (int b = tid; b < B; b += 1024) { row0[b] = 0; ext[b] = 0; }
-        for (int k = tid; k < nblk; k += 1024) blk_pattern[k] = -1;
+        for (int b = tid; b < B; b += NT) { row0[b] = 0; ext[b] = 0; }
+        for (int k = tid; k < nblk; k += NT) blk_pattern[k] = -1;
     }
     if (tid == 0) { n_rows[0] = need <= Tc ? need : 0; n_rows[1] = need; }
 }
@@ -288,7 +291,8 @@ extern "C" int32_t sf_token_pack(const sf_desc *desc, const void *X, const uint8
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int c = desc->c_factor > 0 ? desc->c_factor : 5;
     hipLaunchKernelGGL(token_rank_kernel, dim3(D.B), dim3(256), 0, st, token_valid, D.L, plan->dst_row, plan->len);
-    hipLaunchKernelGGL(pack_layout_kernel, dim3(1), dim3(1024), 0, st, plan->len, pattern_id, D.B, D.P, D.L, plan->Tc,
+    const int lt = (int)std::min<size_t>(1024, align_up((size_t)D.B, 64));
+    hipLaunchKernelGGL(pack_layout_kernel, dim3(1), dim3(lt), 0, st, plan->len, pattern_id, D.B, D.P, D.L, plan->Tc,
                        plan->row0, plan->ext, plan->blk_pattern, plan->n_rows);
     // a sample answers for at most its L tokens, 255 rows of padding and the slack
     dim3 grid((unsigned)ceil_div(2 * D.L + 512, 256), (unsigned)D.B + 1);
