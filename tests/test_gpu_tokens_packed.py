@@ -155,7 +155,7 @@ def test_token_pack_layout_and_rows(dtype, B, L, d, P, c, tight):
         assert not to_host(Xs).any()
 
 
-def _packed_case(wl, samples=None, tight=True):
+def _packed_case(wl, samples=None, tight=True, n_sample=0):
     s = wl.spec
     bf = ORACLE_MODE[s.dtype]
     assert wl.key_valid is not None
@@ -172,8 +172,12 @@ def _packed_case(wl, samples=None, tight=True):
     ref = _layout_reference(wl.key_valid, pattern, P, sf.token_pack_rows_max(dm.desc), s.c)
     Tc = int(ref["n_rows"][1]) if tight else sf.token_pack_rows_max(dm.desc)   # the caller knows the presence counts
     Xp, plan = sf.token_pack(dm.desc, dm.x, dm.key_valid, dm.pattern_id, Tc=Tc)
-    dc = desc_for(wl, U_override=Umax)
-    Yp, sel, _ = sf.encoder_forward_packed(dc, dm.layers, Xp, plan, dm.pattern_id, final_ln=dm.final_ln, want_sel=True)
+    # key sample of the sparsity score: positions of the compacted sample; those at or beyond its length count for nothing
+    idx = np.random.default_rng(s.L + B).integers(0, s.L, (B, n_sample)).astype(np.int32) if n_sample else None
+    idx_dev = to_dev(idx, s.dtype) if n_sample else None
+    dc = desc_for(wl, U_override=Umax, n_sample=n_sample)
+    Yp, sel, _ = sf.encoder_forward_packed(dc, dm.layers, Xp, plan, dm.pattern_id, final_ln=dm.final_ln, want_sel=True,
+                                           sample_idx=idx_dev)
     Y = sf.token_unpack(dm.desc, Yp, plan)
     torch.cuda.synchronize()
     assert np.array_equal(to_host(plan.len), lens) and np.array_equal(to_host(plan.u_active), u_host)
@@ -183,10 +187,10 @@ def _packed_case(wl, samples=None, tight=True):
     # the padded form on the same GPU: the same arithmetic row by row (its V transposition and tile walk differ)
     Lc = min(int(-(-lens.max() // 8) * 8), s.L)
     tc = sf.token_compact(dm.desc, dm.x, dm.key_valid, Lc)
-    dcr = desc_for(wl, U_override=Umax)
+    dcr = desc_for(wl, U_override=Umax, n_sample=n_sample)
     dcr.L = Lc
     Yc_pad, sel_pad, _ = sf.encoder_forward_ragged(dcr, dm.layers, tc["Xc"], dm.pattern_id, tc["valid_c"], tc["u_active"],
-                                                   final_ln=dm.final_ln, want_sel=True)
+                                                   final_ln=dm.final_ln, want_sel=True, sample_idx=idx_dev)
     torch.cuda.synchronize()
     Yp, sel, Y, Yc_pad, sel_pad = to_host(Yp), to_host(sel), to_host(Y), to_host(Yc_pad), to_host(sel_pad)
     worst, worst_pad, picks_diff, picks_tot, sel_same = 0.0, 0.0, 0, 0, True
@@ -210,7 +214,7 @@ def _packed_case(wl, samples=None, tight=True):
         assert (sel[:, b, :, Ub:] == -1).all()
         fs = np.ascontiguousarray(sel[:, [b], :, :Ub])
         y_ref, _, score_f = orc.encoder_forward(xb, packs, Ub, pid, None, act=s.act, forced_sel=fs, final_ln=wl.final_ln,
-                                                bf16=bf, want_score=True)
+                                                bf16=bf, want_score=True, sample_idx=None if idx is None else idx[[b]])
         if 0 < Ub < T:
             for l in range(s.n_layers):
                 for h in range(int(wl.k_head[l])):
@@ -244,6 +248,14 @@ def _packed_case(wl, samples=None, tight=True):
 def test_encoder_packed_parity_small(kw, tight):
     _say(f"packed encoder {kw}")
     _packed_case(make_wl(W.small_spec(**kw)), tight=tight)
+
+
+def test_encoder_packed_parity_with_sampled_score():
+    """The sampled-key sparsity score on packed rows: the key sample is gathered from the sample's own rows."""
+    _say("packed encoder, sampled score")
+    _packed_case(make_wl(W.small_spec(dtype="bf16", d=128, dh=64, Hq=8, Hk=2, F=300, seg=(100, 33, 64, 120), B=7, nl=2,
+                                      dropout="upto:3", act=1)), n_sample=40)
+    _packed_case(make_wl(W.small_spec(dtype="f32", dropout="upto:2", B=5)), n_sample=9)
 
 
 def test_encoder_packed_parity_C3_samples():
