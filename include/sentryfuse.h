@@ -550,7 +550,8 @@ int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compact_layer *l
  *                         n_rows[1] > Tc: the rows did not fit; the plan is
  *                         then the empty one (no sample has rows, Xp is zero,
  *                         the encoder does nothing) and the caller comes back
- *                         with Tc >= n_rows[1].
+ *                         with Tc >= n_rows[1].  n_rows[1] = -1: a pattern
+ *                         number outside [0, P); the empty plan as well.
  * sf_token_pack: X [B,L,d], token_valid [B,L], pattern_id [B] (NULL with P = 1)
  * in; the plan and Xp [Tc,d] (zero rows where src_row < 0) out.
  * sf_encoder_forward_packed is sf_encoder_forward over the packed rows (desc
@@ -563,7 +564,7 @@ int32_t sf_encoder_forward_ragged(const sf_desc *desc, const sf_compact_layer *l
  * sf_token_unpack writes Y[b,i,:] = Yp[dst_row[b,i],:], zero rows for dropped
  * tokens.  All index outputs are bit-exact.
  * Errors: SF_ERR_INVALID_ARG (NULL, Tc not a multiple of 256, aliasing),
- * SF_ERR_SHAPE, SF_ERR_WORKSPACE (sf_encoder_packed_workspace_bytes), as for
+ * SF_ERR_SHAPE (sf_token_pack: more than 4096 presence patterns), SF_ERR_WORKSPACE (sf_encoder_packed_workspace_bytes), as for
  * sf_encoder_forward.
  */
 typedef struct sf_token_pack_plan {

@@ -139,82 +139,102 @@ __global__ __launch_bounds__(256) void token_rank_kernel(const uint8_t *__restri
     if (threadIdx.x == 0) len[b] = base_s;
 }
 
-// Pass 2, one block (as many waves as the batch needs, at most 16: its barriers are the cost): the layout.  n_rows[0] = rows in use (runs + slack, a multiple of 256; 0 when
-// no sample has a token), n_rows[1] = the same before the comparison with Tc.  When the rows do not fit
-// (n_rows[1] > Tc) the plan is the empty one - every sample at row 0 with no rows, every block unused - so that
-// whatever runs on it touches nothing; the caller reads n_rows[1] and comes back with a larger buffer.
-__global__ __launch_bounds__(1024) void pack_layout_kernel(const int32_t *__restrict__ len,
-                                                           const int32_t *__restrict__ pattern_id, int B, int P, int L,
-                                                           int Tc, int32_t *__restrict__ row0, int32_t *__restrict__ ext,
-                                                           int32_t *__restrict__ blk_pattern, int32_t *__restrict__ n_rows)
+// Pass 2, one block: the layout.  n_rows[0] = rows in use (runs + slack, a multiple of 256; 0 when no sample has a
+// token), n_rows[1] = the same before the comparison with Tc.  When the rows do not fit (n_rows[1] > Tc) the plan is
+// the empty one - every sample at row 0 with no rows, every block unused - so that whatever runs on it touches
+// nothing; the caller reads n_rows[1] and comes back with a larger buffer.  A pattern number outside [0, P) gives the
+// empty plan too, with n_rows[1] = -1.
+// Per pattern (LDS, P <= PACK_MAX_P): the rows of its run (integer atomics: order-free), its last sample, then the
+// first row of its run from one scan over the patterns.  Per sample: the samples are walked in order, PACK_NT at a
+// time; a sample's row is its pattern's running position plus the rows of the earlier samples of the same pattern
+// in its chunk.  Three barriers per PACK_NT patterns and per PACK_NT samples.
+constexpr int PACK_MAX_P = 4096, PACK_NT = 256;
+
+__global__ __launch_bounds__(PACK_NT) void pack_layout_kernel(const int32_t *__restrict__ len,
+                                                              const int32_t *__restrict__ pattern_id, int B, int P, int L,
+                                                              int Tc, int32_t *__restrict__ row0, int32_t *__restrict__ ext,
+                                                              int32_t *__restrict__ blk_pattern, int32_t *__restrict__ n_rows)
 {
-    __shared__ int wsum[16], wlast[16];
-    __shared__ int base_s, last_b_s, tail_b_s, tail_p_s;
+    extern __shared__ int32_t psm[];
+    int32_t *seg = psm, *base = psm + P, *lastb = psm + 2 * P, *cur = psm + 3 * P;      // [P] each
+    __shared__ int wsum[PACK_NT / 64];
+    __shared__ __attribute__((aligned(16))) int p_s[PACK_NT], l_s[PACK_NT];
+    __shared__ int carry_s, tail_p_s, bad_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int NT = blockDim.x, NWV = NT >> 6;             // a multiple of 64, at most 1024
     const int nblk = Tc / 256;
-    if (tid == 0) { base_s = 0; tail_b_s = -1; tail_p_s = -1; }
-    for (int k = tid; k < nblk; k += NT) blk_pattern[k] = -1;
+    for (int p = tid; p < P; p += PACK_NT) { seg[p] = 0; lastb[p] = -1; }
+    for (int k = tid; k < nblk; k += PACK_NT) blk_pattern[k] = -1;
+    if (tid == 0) { carry_s = 0; tail_p_s = -1; bad_s = 0; }
     __syncthreads();
-    for (int p = 0; p < P; ++p) {
-        const int seg0 = base_s;
-        if (tid == 0) last_b_s = -1;
-        __syncthreads();
-        for (int c0 = 0; c0 < B; c0 += NT) {
-            const int b = c0 + tid;
-            const bool mine = b < B && (pattern_id ? pattern_id[b] : 0) == p;
-            const int v = mine ? len[b] : 0;
-            int incl = v;                                     // inclusive scan inside the wave
+    for (int b = tid; b < B; b += PACK_NT) {
+        const int p = pattern_id ? pattern_id[b] : 0;
+        if (p < 0 || p >= P) { bad_s = 1; continue; }
+        atomicAdd(&seg[p], len[b]);
+        atomicMax(&lastb[p], b);
+    }
+    __syncthreads();
+    // first row of every run: exclusive scan of the padded run lengths, PACK_NT patterns at a time
+    for (int p0 = 0; p0 < P; p0 += PACK_NT) {
+        const int p = p0 + tid;
+        const int v = p < P ? (seg[p] + 255) & ~255 : 0;
+        int incl = v;
 #pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int t = __shfl_up(incl, o);
-                if (lane >= o) incl += t;
-            }
-            // the last sample of the run: the highest sample number of the pattern
-            const uint64_t mm = __ballot(mine);
-            if (lane == 63) wsum[wave] = incl;
-            if (lane == 0) wlast[wave] = mm ? c0 + wave * 64 + 63 - __builtin_clzll(mm) : -1;
-            __syncthreads();
-            int off = base_s + incl - v;
-            for (int w = 0; w < wave; ++w) off += wsum[w];
-            if (mine) { row0[b] = off; ext[b] = v; }
-            __syncthreads();
-            if (tid == 0) {
-                int tot = 0, lb = last_b_s;
-                for (int w = 0; w < NWV; ++w) { tot += wsum[w]; lb = max(lb, wlast[w]); }
-                base_s += tot;
-                last_b_s = lb;
-            }
-            __syncthreads();
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
         }
-        const int seg1 = base_s, lb = last_b_s;
-        const int seg1a = (seg1 + 255) & ~255;
+        if (lane == 63) wsum[wave] = incl;
         __syncthreads();
-        if (seg1 > seg0) {                                    // the run has rows
-            for (int k = seg0 / 256 + tid; k < seg1a / 256; k += NT)
-                if (k < nblk) blk_pattern[k] = p;
-            if (tid == 0) {
-                ext[lb] = seg1a - row0[lb];                   // its last sample also answers for the padding
-                base_s = seg1a;
-                tail_b_s = lb;
-                tail_p_s = p;
+        int off = carry_s + incl - v;
+        for (int w = 0; w < wave; ++w) off += wsum[w];
+        if (p < P) { base[p] = off; cur[p] = off; }
+        if (p < P && seg[p] > 0) atomicMax(&tail_p_s, p);           // the last run that has rows
+        __syncthreads();
+        if (tid == 0) { int t = 0; for (int w = 0; w < PACK_NT / 64; ++w) t += wsum[w]; carry_s += t; }
+        __syncthreads();
+    }
+    const bool bad = bad_s != 0;
+    const int used = carry_s, slack = (L + 255) & ~255;
+    const int need = bad ? -1 : used > 0 ? used + slack : 0;
+    const bool fits = !bad && need <= Tc;
+    const int tail_p = tail_p_s;
+    for (int c0 = 0; c0 < B; c0 += PACK_NT) {
+        const int b = c0 + tid;
+        int p = b < B ? (pattern_id ? pattern_id[b] : 0) : -1;
+        if (p >= P) p = -1;
+        const int lb = b < B && p >= 0 ? len[b] : 0;
+        p_s[tid] = p;
+        l_s[tid] = lb;
+        __syncthreads();
+        int before = 0;                                 // four entries per LDS read, no branch: the reads pipeline
+#pragma unroll 4
+        for (int t4 = 0; t4 * 4 < tid; ++t4) {
+            const int4 pp = reinterpret_cast<const int4 *>(p_s)[t4], ll = reinterpret_cast<const int4 *>(l_s)[t4];
+            before += (pp.x == p && t4 * 4 + 0 < tid ? ll.x : 0) + (pp.y == p && t4 * 4 + 1 < tid ? ll.y : 0) +
+                      (pp.z == p && t4 * 4 + 2 < tid ? ll.z : 0) + (pp.w == p && t4 * 4 + 3 < tid ? ll.w : 0);
+        }
+        const int row = p >= 0 ? cur[p] + before : 0;
+        __syncthreads();
+        if (p >= 0) atomicAdd(&cur[p], lb);
+        if (b < B) {
+            int e = lb;
+            if (p >= 0 && b == lastb[p] && seg[p] > 0) {            // the last sample of a run answers for its padding
+                e = base[p] + ((seg[p] + 255) & ~255) - row;
+                if (p == tail_p) e += slack;                        // ... and the last run's for the slack
             }
+            row0[b] = fits ? row : 0;
+            ext[b] = fits ? e : 0;
         }
         __syncthreads();
     }
-    const int used = base_s, slack = (L + 255) & ~255;
-    const int need = used > 0 ? used + slack : 0;
-    __syncthreads();
-    if (need <= Tc) {
-        if (used > 0) {
-            for (int k = used / 256 + tid; k < need / 256; k += NT) blk_pattern[k] = tail_p_s;
-            if (tid == 0) ext[tail_b_s] += slack;
+    if (fits) {
+        for (int p = wave; p < P; p += PACK_NT / 64) {        // a wave per run, a lane per block
+            if (seg[p] <= 0) continue;
+            const int k1 = (base[p] + ((seg[p] + 255) & ~255) + (p == tail_p ? slack : 0)) / 256;
+            for (int k = base[p] / 256 + lane; k < k1; k += 64) blk_pattern[k] = p;
         }
-    } else {
-        for (int b = tid; b < B; b += NT) { row0[b] = 0; ext[b] = 0; }
-        for (int k = tid; k < nblk; k += NT) blk_pattern[k] = -1;
     }
-    if (tid == 0) { n_rows[0] = need <= Tc ? need : 0; n_rows[1] = need; }
+    if (tid == 0) { n_rows[0] = fits ? need : 0; n_rows[1] = need; }
 }
 
 // Pass 3, grid (row chunks of 256, B + 1).  Samples: dst_row[b, i] (on entry the rank of token i) becomes the packed
@@ -288,12 +308,12 @@ extern "C" int32_t sf_token_pack(const sf_desc *desc, const void *X, const uint8
     if (!X || !token_valid || !Xp) return fail(SF_ERR_INVALID_ARG, "token_pack: NULL argument");
     if (X == Xp) return fail(SF_ERR_INVALID_ARG, "token_pack: Xp may not alias X");
     if (D.P > 1 && !pattern_id) return fail(SF_ERR_INVALID_ARG, "token_pack: pattern_id required when P > 1");
+    if (D.P > PACK_MAX_P) return fail(SF_ERR_SHAPE, "token_pack: at most %d presence patterns", PACK_MAX_P);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int c = desc->c_factor > 0 ? desc->c_factor : 5;
     hipLaunchKernelGGL(token_rank_kernel, dim3(D.B), dim3(256), 0, st, token_valid, D.L, plan->dst_row, plan->len);
-    const int lt = (int)std::min<size_t>(1024, align_up((size_t)D.B, 64));
-    hipLaunchKernelGGL(pack_layout_kernel, dim3(1), dim3(lt), 0, st, plan->len, pattern_id, D.B, D.P, D.L, plan->Tc,
-                       plan->row0, plan->ext, plan->blk_pattern, plan->n_rows);
+    hipLaunchKernelGGL(pack_layout_kernel, dim3(1), dim3(PACK_NT), (size_t)4 * D.P * sizeof(int32_t), st, plan->len,
+                       pattern_id, D.B, D.P, D.L, plan->Tc, plan->row0, plan->ext, plan->blk_pattern, plan->n_rows);
     // a sample answers for at most its L tokens, 255 rows of padding and the slack
     dim3 grid((unsigned)ceil_div(2 * D.L + 512, 256), (unsigned)D.B + 1);
     hipLaunchKernelGGL(pack_rows_kernel, grid, dim3(256), 0, st, token_valid, plan->len, plan->row0, plan->ext,

@@ -109,7 +109,7 @@ def _check_layout_properties(valid, pattern, plan_host, Tc):
 
 @pytest.mark.parametrize("dtype,B,L,d,P,c,tight", [("f32", 7, 300, 20, 3, 5, False), ("bf16", 40, 480, 64, 11, 5, True),
                                                    ("bf16", 5, 257, 8, 1, 3, False), ("f32", 3, 5000, 8, 4, 5, True),
-                                                   ("bf16", 1100, 96, 16, 6, 5, True)])
+                                                   ("bf16", 1100, 96, 16, 6, 5, True), ("bf16", 700, 40, 16, 300, 5, True)])
 def test_token_pack_layout_and_rows(dtype, B, L, d, P, c, tight):
     _say(f"token pack {dtype} B={B} L={L} P={P} tight={tight}")
     rng = np.random.default_rng(L + B)
@@ -153,6 +153,24 @@ def test_token_pack_layout_and_rows(dtype, B, L, d, P, c, tight):
         for k in refs:
             assert np.array_equal(to_host(getattr(ps, k)), refs[k]), k
         assert not to_host(Xs).any()
+
+
+def test_token_pack_pattern_out_of_range_gives_the_empty_plan():
+    B, L, d, P = 6, 70, 16, 3
+    rng = np.random.default_rng(3)
+    valid = (rng.random((B, L)) < 0.6).astype(np.uint8)
+    pattern = np.array([0, 2, 1, 3, 0, 1], np.int32)                 # 3 is not a pattern
+    x = torch.from_numpy(rng.standard_normal((B, L, d)).astype(np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+    desc = sf.make_desc(B, L, d, 1, 1, 8, 8, dtype=sf.SF_BF16, P=P)
+    Xp, plan = sf.token_pack(desc, to_dev(x, "bf16"), to_dev(valid, "bf16"), to_dev(pattern, "bf16"))
+    torch.cuda.synchronize()
+    assert to_host(plan.n_rows).tolist() == [0, -1]
+    assert not to_host(plan.ext).any() and not to_host(plan.row0).any() and (to_host(plan.blk_pattern) == -1).all()
+    assert (to_host(plan.src_row) == -1).all() and (to_host(plan.dst_row) == -1).all() and not to_host(Xp).any()
+    assert not to_host(plan.valid_c).any() and not to_host(plan.u_active).any()
+    with pytest.raises(sf.SentryFuseError):
+        sf.token_pack(sf.make_desc(B, L, d, 1, 1, 8, 8, dtype=sf.SF_BF16, P=5000), to_dev(x, "bf16"), to_dev(valid, "bf16"),
+                      to_dev(pattern, "bf16"))
 
 
 def _packed_case(wl, samples=None, tight=True, n_sample=0):
