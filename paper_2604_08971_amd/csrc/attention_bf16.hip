@@ -25,14 +25,15 @@ constexpr float RESCALE_LOG2 = 8.0f;    // slack of the softmax reference below 
 // Bit j%32 of word j/32 = key j of sample b is allowed (0 beyond L).
 __device__ __forceinline__ void build_mask_words(const uint8_t *kv, int L, uint32_t *words, int nwords)
 {
-    for (int w = threadIdx.x; w < nwords; w += blockDim.x) {
-        uint32_t m = 0;
-        const int j0 = w * 32;
-        for (int t = 0; t < 32; ++t) {
-            const int j = j0 + t;
-            if (j < L && (!kv || kv[j])) m |= 1u << t;
-        }
-        words[w] = m;
+    // one position per lane, the words from the wave's ballot: a single round of byte loads for the whole block
+    // (a lane that assembled a word by itself paid 32 loads one after the other)
+    const int lane = threadIdx.x & 63;
+    for (int j0 = 0; j0 < nwords * 32; j0 += (int)blockDim.x) {      // the same trip count for every wave
+        const int j = j0 + (int)threadIdx.x;
+        const bool ok = j < L && (!kv || kv[j]);
+        const unsigned long long bal = __ballot(ok);
+        const int w = j >> 5;
+        if ((lane & 31) == 0 && w < nwords) words[w] = (uint32_t)(bal >> (lane & 32));
     }
 }
 
