@@ -734,6 +734,8 @@ def test_sparse_gqa_is_deterministic():
     ("bf16", 0, 4, 384, 256, 1024, 0.6), ("bf16", 1, 3, 203, 128, 520, 0.71), ("bf16", 0, 2, 4096, 768, 3072, 0.7),
     # 37 tile slots per XCD, four column tiles per row: rows of tiles that straddle two rounds of the persistent walk
     ("bf16", 0, 37, 512, 256, 1280, 0.8),
+    # tile counts that do not divide by the XCDs or by the workgroups of an XCD, ragged row tiles
+    ("bf16", 1, 23, 300, 384, 1280, 0.8), ("bf16", 0, 51, 384, 256, 1024, 0.5),
 ])
 def test_pruned_ffn_parity(dtype, act, B, L, d, F, keep):
     _say(f"ffn {dtype} act={act} B={B} L={L} d={d} F={F}")
